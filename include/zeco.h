@@ -1,0 +1,101 @@
+/*
+ * zeco.h - C ABI of the MI355X (gfx950) ZeCO hot path: chunkwise gated-linear-attention (GLA)
+ * segment forward, segment-state scan (the arithmetic of All-Scan) and initial-state correction.
+ *
+ * Conventions for every entry point
+ *   - Tensor pointers are DEVICE pointers owned by the caller, 16-byte aligned.  The library never
+ *     allocates, frees or synchronises; all work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream).
+ *   - Arguments are validated before any HIP call; a non-zero status means nothing was launched
+ *     (ZECO_ERR_HIP: a launch was refused by the runtime).  Outputs are unspecified on error.
+ *   - Results are deterministic (no atomics) and independent of launch-shape heuristics.
+ *   - Notation: B batch, P segments (the paper's devices), L tokens per segment, T = P*L, H heads,
+ *     C chunk length, g = log(alpha) <= 0 the LOG decay of Eq. (1), scale multiplies q
+ *     (1.0 reproduces the paper).  Decay scales row i (the d_k index) of a d_k x d_v state.
+ */
+#ifndef ZECO_H
+#define ZECO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZECO_OK = 0,
+    ZECO_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad stride */
+    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix */
+    ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than zeco_gla_local_fwd_workspace() */
+    ZECO_ERR_HIP = 4          /* HIP runtime refused a launch / attribute */
+} zeco_status;
+
+typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
+
+/* Problem descriptor (Alg. 1 inputs: Q, K in R^{L x d_k}, V in R^{L x d_v}, G, chunk size C,
+ * number of devices P - here P segments resident on one GPU).
+ * q, k, g are addressed as  base + b*stride_b + t*stride_t + h*stride_h + i   (i < d_k, t < T)
+ * v, o as                   base + b*vstride_b + t*vstride_t + h*vstride_h + j (j < d_v)
+ * in ELEMENTS; the innermost dimension is contiguous.  Strides must be multiples of 8 elements. */
+typedef struct {
+    int32_t B, P, H, L;
+    int32_t d_k, d_v, C;       /* supported: C = 64, L % C == 0, d_k and d_v in {64, 128} */
+    int32_t io_dtype;          /* zeco_dtype of q, k, v, o */
+    int32_t g_dtype;           /* zeco_dtype of g */
+    float scale;
+    int64_t stride_b, stride_t, stride_h;
+    int64_t vstride_b, vstride_t, vstride_h;
+} zeco_gla_desc;
+
+/* Bytes of device workspace zeco_gla_local_fwd needs for this descriptor (may be 0).
+ * Returns 0 for an invalid descriptor. */
+size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc);
+
+/* Local pass (Sec. 3.1 "Local State Computation", Alg. 1 chunk loop and output pass with a zero
+ * incoming state; chunk equations of Sec. 2.1): every segment p runs the chunkwise GLA forward
+ * from the ZERO state.
+ *   in   q, k, v, g   device, layouts per the descriptor (io_dtype / g_dtype)
+ *   out  o      [B,T,H,d_v] (descriptor strides), io_dtype: local output
+ *   out  S_loc  [P,B,H,d_k,d_v] fp32 contiguous: final local state S_[N] of each segment
+ *   out  G_cum  [B,T,H,d_k] fp32 contiguous: per token, sum of g from the segment's first token
+ *               through that token (log of Lambda_t .* gamma~_[n-1]; Eq. (gamma) kept per token)
+ *   out  G_tot  [P,B,H,d_k] fp32 contiguous: G_cum at each segment's last token (log gamma~_[N])
+ * bf16 io: bf16 MFMA operands, fp32 accumulation and fp32 state.  fp32 io: fp32 MFMA throughout.
+ * Precondition: within any chunk, sum over tokens of |g| per channel < 80 (the intra-chunk
+ * scores use K / Lambda as in Alg. 1, whose range is exp of that sum). */
+zeco_status zeco_gla_local_fwd(const zeco_gla_desc *desc, const void *q, const void *k,
+                               const void *v, const void *g, void *o, float *S_loc, float *G_cum,
+                               float *G_tot, void *workspace, size_t workspace_bytes,
+                               void *stream);
+
+/* Segment-state scan: the block update of Sec. 3.2 ("Pipelined State Scan") applied along the
+ * chain of segments on one device; Alg. 2 returns (S_recv, S_send) = (S_init[p], S_init[p+1]).
+ *   S_init[0] = S0 (zeros if NULL),  S_init[p+1] = (exp(G_tot[p])^T 1) .* S_init[p] + S_loc[p]
+ *   in   S_loc  [P,BH,d_k,d_v] fp32,  G_tot [P,BH,d_k] fp32,  S0 [BH,d_k,d_v] fp32 or NULL
+ *   out  S_init [P,BH,d_k,d_v] fp32,  S_last [BH,d_k,d_v] fp32 or NULL (= state after segment P-1)
+ * K_blocks: number of contiguous d_k-row blocks the state is split into (d_k % K_blocks == 0);
+ * each block is an independent slab and the result is bitwise independent of K_blocks.
+ * direction: 0 = forward chain; 1 (reverse chain of the backward pass) -> ZECO_ERR_UNSUPPORTED.
+ * d_v % 4 == 0 required; any d_k >= 1. */
+zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
+                            const float *S_loc, const float *G_tot, const float *S0,
+                            float *S_init, float *S_last, int32_t direction, void *stream);
+
+/* Initial-state correction (Eq. (global-correction) carried to the output; the highlighted term
+ * of Alg. 1's output pass, with Lambda_t .* gamma~_[n-1] = exp(G_cum[t])):
+ *   o_t += (scale * q_t .* exp(G_cum[t])) S_init[p]      for every token t of segment p
+ *   in     q (descriptor layout), G_cum [B,T,H,d_k] fp32, S_init [P,B,H,d_k,d_v] fp32
+ *   in/out o (descriptor layout)
+ * first_segment_is_zero != 0: segment 0 is skipped (its incoming state is known to be zero). */
+zeco_status zeco_apply_init_state(const zeco_gla_desc *desc, const void *q, const float *G_cum,
+                                  const float *S_init, void *o, int32_t first_segment_is_zero,
+                                  void *stream);
+
+const char *zeco_status_string(int32_t status);
+int32_t zeco_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZECO_H */

@@ -1,0 +1,202 @@
+// Initial-state correction  o_t += (scale * q_t .* exp(G_cum[t])) S_init[p]  (Eq. (global-correction)
+// carried to the output; the term Alg. 1's output pass adds to S_[n-1]).
+//
+// A skinny GEMM (tokens x d_k)(d_k x d_v) that must stay HBM-bound: q, G_cum and o are streamed
+// once, S_init[p] is loaded once per workgroup and kept in registers as an MFMA operand, and the
+// contraction runs on the matrix cores (at 25.6 flop/byte it would be ALU-bound on plain FMAs).
+// A workgroup takes `tokens_per_wg` consecutive tokens of one (batch, segment, head).
+#include "zeco_device.h"
+#include "zeco_internal.h"
+
+namespace zeco {
+
+// ------------------------------------------------------------------------------------------ bf16
+template <int DK, int DV> struct ApplyCfg {
+    static constexpr int TILE = DV / 4;
+    static constexpr int NKG = 64 / TILE;
+    static constexpr int KS = 8 * NKG;
+    static constexpr int ACC = TILE * TILE / 64;
+    static constexpr int NMT = 64 / TILE;
+    static constexpr int NKS = DK / KS;
+    static constexpr int QS = DK * 2 + 16;          // LDS row stride (bytes)
+    static constexpr int ITEMS = 64 * DK / 8 / 256; // 8-channel groups per thread per 64 tokens
+    static constexpr int kBytes = 2 * 64 * QS;
+};
+
+template <int DK, int DV>
+__global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
+    typedef ApplyCfg<DK, DV> Cfg;
+    typedef Mma<Cfg::TILE> M;
+    constexpr int TILE = Cfg::TILE, KS = Cfg::KS, QS = Cfg::QS;
+    __shared__ __align__(16) unsigned char Qh[Cfg::kBytes];
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lt = lane % TILE, kg = lane / TILE;
+
+    const int blocks_per_seg = p.L / p.tokens_per_wg;
+    int id = blockIdx.x;
+    const int tb = id % blocks_per_seg;
+    id /= blocks_per_seg;
+    const int h = id % p.H;
+    id /= p.H;
+    const int b = id % p.B, seg = p.p0 + id / p.B;
+    const long long tok0 = (long long)seg * p.L + (long long)tb * p.tokens_per_wg;
+    const uint16_t *qp = (const uint16_t *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
+    uint16_t *op = (uint16_t *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
+    const long long T = (long long)p.P * p.L;
+    const float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
+    const long long gcs = (long long)p.H * DK;
+    const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
+
+    // S_init[p] columns [w*TILE, (w+1)*TILE) as the A operand of O^T = S^T Qh^T: lane holds column
+    // lt and, for k-step ks, channels ks*KS + 8*kg .. +7.
+    bf16x8 sf[Cfg::NKS];
+#pragma unroll
+    for (int ks = 0; ks < Cfg::NKS; ++ks) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = S[(size_t)(ks * KS + 8 * kg + e) * DV + w * TILE + lt];
+        u32x4 wv = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]),
+                    pack_bf16(x[6], x[7])};
+        sf[ks] = __builtin_bit_cast(bf16x8, wv);
+    }
+
+    struct Raw {
+        u32x4 q[Cfg::ITEMS];
+        f32x4 g0[Cfg::ITEMS], g1[Cfg::ITEMS];
+    };
+    auto load_raw = [&](int blk, Raw &r) {
+#pragma unroll
+        for (int m = 0; m < Cfg::ITEMS; ++m) {
+            const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
+            const long long tt = (long long)blk * 64 + t;
+            r.q[m] = *reinterpret_cast<const u32x4 *>(qp + tt * p.st + 8 * cg);
+            r.g0[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg);
+            r.g1[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg + 4);
+        }
+    };
+
+    const int nblk = p.tokens_per_wg / 64;
+    Raw nxt;
+    load_raw(0, nxt);
+    for (int blk = 0; blk < nblk; ++blk) {
+        unsigned char *buf = Qh + (blk & 1) * 64 * QS;
+        Raw cur = nxt;
+#pragma unroll
+        for (int m = 0; m < Cfg::ITEMS; ++m) {
+            const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
+            u32x4 out;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ga = e < 2 ? cur.g0[m][2 * e] : cur.g1[m][2 * e - 4];
+                const float gb = e < 2 ? cur.g0[m][2 * e + 1] : cur.g1[m][2 * e - 3];
+                out[e] = pack_bf16(bf16_lo(cur.q[m][e]) * fast_exp(ga) * p.scale,
+                                   bf16_hi(cur.q[m][e]) * fast_exp(gb) * p.scale);
+            }
+            *reinterpret_cast<u32x4 *>(buf + t * QS + 16 * cg) = out;
+        }
+        if (blk + 1 < nblk) load_raw(blk + 1, nxt);
+        __syncthreads();   // one barrier per block: the other buffer was last read two blocks ago
+
+#pragma unroll
+        for (int mt = 0; mt < Cfg::NMT; ++mt) {
+            typename M::acc_t acc;
+#pragma unroll
+            for (int r = 0; r < Cfg::ACC; ++r) acc[r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < Cfg::NKS; ++ks)
+                acc = M::run(sf[ks], lds_frag(buf, (mt * TILE + lt) * QS + (ks * KS + 8 * kg) * 2), acc);
+            uint16_t *orow = op + ((long long)blk * 64 + mt * TILE + lt) * p.vt + w * TILE;
+#pragma unroll
+            for (int qd = 0; qd < Cfg::ACC / 4; ++qd) {
+                u32x2 *ptr = reinterpret_cast<u32x2 *>(orow + M::row(4 * qd, kg));
+                const u32x2 old = *ptr;
+                *ptr = u32x2{pack_bf16(bf16_lo(old[0]) + acc[4 * qd], bf16_hi(old[0]) + acc[4 * qd + 1]),
+                             pack_bf16(bf16_lo(old[1]) + acc[4 * qd + 2], bf16_hi(old[1]) + acc[4 * qd + 3])};
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ fp32
+template <int DK, int DV>
+__global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
+    constexpr int NT = DV * 4, QS = DK + 4;
+    __shared__ __align__(16) float Qh[64 * QS];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int l16 = lane & 15, kg = lane >> 4;
+
+    const int blocks_per_seg = p.L / p.tokens_per_wg;
+    int id = blockIdx.x;
+    const int tb = id % blocks_per_seg;
+    id /= blocks_per_seg;
+    const int h = id % p.H;
+    id /= p.H;
+    const int b = id % p.B, seg = p.p0 + id / p.B;
+    const long long tok0 = (long long)seg * p.L + (long long)tb * p.tokens_per_wg;
+    const float *qp = (const float *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
+    float *op = (float *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
+    const long long T = (long long)p.P * p.L;
+    const float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
+    const long long gcs = (long long)p.H * DK;
+    const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
+
+    f32x4 Sreg[DK / 16];   // B operand: register r of tile it = S[16 it + 4 kg + r][16 w + l16]
+#pragma unroll
+    for (int it = 0; it < DK / 16; ++it)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Sreg[it][r] = S[(size_t)(16 * it + 4 * kg + r) * DV + 16 * w + l16];
+
+    const int nblk = p.tokens_per_wg / 64;
+    for (int blk = 0; blk < nblk; ++blk) {
+        for (int e = tid; e < 64 * DK; e += NT) {
+            const int t = e / DK, c = e % DK;
+            const long long tt = (long long)blk * 64 + t;
+            Qh[t * QS + c] = qp[tt * p.st + c] * fast_exp(Gc[tt * gcs + c]) * p.scale;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int it = 0; it < DK / 16; ++it)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc = mma_f32(Qh[(16 * mt + l16) * QS + 16 * it + 4 * kg + r], Sreg[it][r], acc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                op[((long long)blk * 64 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] += acc[r];
+        }
+        __syncthreads();
+    }
+}
+
+template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hipStream_t s) {
+    const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
+    hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV>), dim3(grid), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
+template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hipStream_t s) {
+    const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
+    hipLaunchKernelGGL((apply_init_f32_kernel<DK, DV>), dim3(grid), dim3(DV * 4), 0, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s) {
+    if (p.P - p.p0 <= 0) return hipSuccess;
+    if (d_k == 64 && d_v == 64) return launch_ab16<64, 64>(p, s);
+    if (d_k == 64 && d_v == 128) return launch_ab16<64, 128>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_ab16<128, 64>(p, s);
+    if (d_k == 128 && d_v == 128) return launch_ab16<128, 128>(p, s);
+    return hipErrorInvalidValue;
+}
+hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s) {
+    if (p.P - p.p0 <= 0) return hipSuccess;
+    if (d_k == 64 && d_v == 64) return launch_af32<64, 64>(p, s);
+    if (d_k == 64 && d_v == 128) return launch_af32<64, 128>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_af32<128, 64>(p, s);
+    if (d_k == 128 && d_v == 128) return launch_af32<128, 128>(p, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace zeco

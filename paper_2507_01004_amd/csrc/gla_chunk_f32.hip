@@ -1,0 +1,206 @@
+// Chunkwise GLA forward of a segment from the zero state, fp32 inputs, fp32 MFMA (16x16x4).
+//
+// One workgroup per (batch, segment, head) walks the N = L/64 chunks in order (Sec. 3.1, local
+// state recurrence) and, per chunk, evaluates the chunk equations of Sec. 2.1 with the intra-chunk
+// scores of Alg. 1 (Q .* Lambda)(K / Lambda)^T under the causal mask (diagonal included):
+//     O   = (Q .* Lambda) S  +  [scores .* M] V
+//     S  <- (gamma^T 1) .* S + (K .* Gamma)^T V
+// The d_k x d_v state lives in MFMA accumulators for the whole segment: wave w owns columns
+// [16w, 16w+16) of S, and because an accumulator register of lane l holds S[16*it + 4*(l/16) + r]
+// [l%16], that register IS the B operand of the 16x16x4 step whose four k-slots are the channels
+// 16*it + 4*kg + r (kg = 0..3) - the inter-chunk product reads S without leaving the registers.
+// This is the accuracy path (relative error <= 1e-4 against the fp64 oracle); the bf16 kernel is
+// the throughput path.
+#include "zeco_device.h"
+#include "zeco_internal.h"
+
+namespace zeco {
+
+template <int DK, int DV> struct F32Cfg {
+    static constexpr int kWaves = DV / 16;
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kTG = kThreads / DK;       // token groups in the gate pass
+    static constexpr int kTPT = 64 / kTG;           // tokens per thread in the gate pass
+    static constexpr int kQS = DK + 4;              // row strides (floats), chosen bank-conflict free
+    static constexpr int kKT = DK + 16;
+    static constexpr int kVS = DV + 16;
+    static constexpr int kPS = 64 + 4;
+    static constexpr int kOffQ = 0;
+    static constexpr int kOffK = kOffQ + 64 * kQS;
+    static constexpr int kOffKT = kOffK + 64 * kQS;
+    static constexpr int kOffV = kOffKT + 64 * kKT;
+    static constexpr int kOffP = kOffV + 64 * kVS;
+    static constexpr int kOffTot = kOffP + 64 * kPS;
+    static constexpr int kOffGam = kOffTot + kTG * DK;
+    static constexpr int kFloats = kOffGam + DK;
+    static constexpr size_t kBytes = sizeof(float) * kFloats;
+};
+
+template <int DK, int DV>
+__global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
+    typedef F32Cfg<DK, DV> Cfg;
+    extern __shared__ __align__(16) float lds[];
+    float *Qs = lds + Cfg::kOffQ;    // Q .* Lambda * scale      [t][i]
+    float *Ks = lds + Cfg::kOffK;    // K / Lambda               [s][i]
+    float *Kt = lds + Cfg::kOffKT;   // K .* Gamma               [s][i]
+    float *Vs = lds + Cfg::kOffV;    // V                        [s][j]
+    float *Ps = lds + Cfg::kOffP;    // masked scores            [t][s]
+    float *tot = lds + Cfg::kOffTot; // per token-group gate sums [tg][i]
+    float *gam = lds + Cfg::kOffGam; // chunk decay gamma         [i]
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int l16 = lane & 15, kg = lane >> 4;
+
+    int sidx = blockIdx.x;                       // stream index = (b * P + p) * H + h
+    const int h = sidx % p.H;
+    sidx /= p.H;
+    const int seg = sidx % p.P, b = sidx / p.P;
+    const long long tok0 = (long long)seg * p.L;
+    const float *q = (const float *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
+    const float *k = (const float *)p.k + b * p.sb + tok0 * p.st + h * p.sh;
+    const float *g = (const float *)p.g + b * p.sb + tok0 * p.st + h * p.sh;
+    const float *v = (const float *)p.v + b * p.vb + tok0 * p.vt + h * p.vh;
+    float *o = (float *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
+    const long long T = (long long)p.P * p.L;
+    float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
+    const long long gcs = (long long)p.H * DK;
+    const size_t sbh = ((size_t)seg * p.B + b) * p.H + h;
+
+    f32x4 Sacc[DK / 16];
+#pragma unroll
+    for (int it = 0; it < DK / 16; ++it) Sacc[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int gc = tid % DK, tg = tid / DK;      // gate pass: channel and token group
+    double seg_prefix = 0.0;                     // log decay accumulated over previous chunks
+
+    for (int n = 0; n < p.n_chunks; ++n) {
+        const long long t0 = (long long)n * 64;
+        // ---- gate pass: inclusive cumulative sum of g over the chunk, per channel -------------
+        float cs[Cfg::kTPT];
+        {
+            float run = 0.f;
+#pragma unroll
+            for (int u = 0; u < Cfg::kTPT; ++u) {
+                run += g[(t0 + tg * Cfg::kTPT + u) * p.st + gc];
+                cs[u] = run;
+            }
+            tot[tg * DK + gc] = run;
+        }
+        for (int e = tid; e < 64 * DV; e += Cfg::kThreads) {
+            const int t = e / DV, j = e % DV;
+            Vs[t * Cfg::kVS + j] = v[(t0 + t) * p.vt + j];
+        }
+        __syncthreads();
+        float pre = 0.f, total = 0.f;
+#pragma unroll
+        for (int u = 0; u < Cfg::kTG; ++u) {
+            const float x = tot[u * DK + gc];
+            if (u < tg) pre += x;
+            total += x;
+        }
+#pragma unroll
+        for (int u = 0; u < Cfg::kTPT; ++u) {
+            const int t = tg * Cfg::kTPT + u;
+            const float c = pre + cs[u];
+            const float qv = q[(t0 + t) * p.st + gc], kv = k[(t0 + t) * p.st + gc];
+            Qs[t * Cfg::kQS + gc] = qv * fast_exp(c) * p.scale;
+            Ks[t * Cfg::kQS + gc] = kv * fast_exp(-c);
+            Kt[t * Cfg::kKT + gc] = kv * fast_exp(total - c);
+            Gc[(t0 + t) * gcs + gc] = (float)(seg_prefix + (double)c);
+        }
+        if (tg == 0) gam[gc] = fast_exp(total);
+        seg_prefix += (double)total;
+        __syncthreads();
+
+        // ---- intra-chunk scores on the 10 lower-triangular 16x16 tiles -------------------------
+        for (int idx = w; idx < 10; idx += Cfg::kWaves) {
+            int tt = 0, rem = idx;
+            while (rem > tt) { rem -= tt + 1; ++tt; }
+            const int ts = rem;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            const float *qa = Qs + (16 * tt + l16) * Cfg::kQS + kg;
+            const float *kb = Ks + (16 * ts + l16) * Cfg::kQS + kg;
+#pragma unroll 8
+            for (int ks = 0; ks < DK / 4; ++ks) acc = mma_f32(qa[4 * ks], kb[4 * ks], acc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int t = 16 * tt + 4 * kg + r, s = 16 * ts + l16;
+                Ps[t * Cfg::kPS + s] = (s <= t) ? acc[r] : 0.f;
+            }
+        }
+
+        // ---- inter-chunk product with the state held in the accumulators ------------------------
+        f32x4 Oacc[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) Oacc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int it = 0; it < DK / 16; ++it) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float bval = Sacc[it][r];
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) {
+                    const float a = Qs[(16 * mt + l16) * Cfg::kQS + 16 * it + 4 * kg + r];
+                    Oacc[mt] = mma_f32(a, bval, Oacc[mt]);
+                }
+            }
+        }
+        __syncthreads();
+
+        // ---- intra-chunk output P V (causal: only s < 16 (mt + 1)) ------------------------------
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            for (int ks = 0; ks < 4 * (mt + 1); ++ks) {
+                const float a = Ps[(16 * mt + l16) * Cfg::kPS + 4 * ks + kg];
+                const float bv = Vs[(4 * ks + kg) * Cfg::kVS + 16 * w + l16];
+                Oacc[mt] = mma_f32(a, bv, Oacc[mt]);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                o[(t0 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] = Oacc[mt][r];
+        }
+
+        // ---- state update S <- gamma .* S + (K .* Gamma)^T V -------------------------------------
+#pragma unroll
+        for (int it = 0; it < DK / 16; ++it) {
+            f32x4 acc = Sacc[it];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] *= gam[16 * it + 4 * kg + r];
+#pragma unroll 4
+            for (int ks = 0; ks < 16; ++ks) {
+                const float a = Kt[(4 * ks + kg) * Cfg::kKT + 16 * it + l16];
+                const float bv = Vs[(4 * ks + kg) * Cfg::kVS + 16 * w + l16];
+                acc = mma_f32(a, bv, acc);
+            }
+            Sacc[it] = acc;
+        }
+        __syncthreads();
+    }
+
+    float *Sl = p.S_loc + sbh * DK * DV;
+#pragma unroll
+    for (int it = 0; it < DK / 16; ++it)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Sl[(16 * it + 4 * kg + r) * DV + 16 * w + l16] = Sacc[it][r];
+    if (tg == 0) p.G_tot[sbh * DK + gc] = (float)seg_prefix;
+}
+
+template <int DK, int DV> static hipError_t launch_f32(const ChunkParams &p, hipStream_t s) {
+    typedef F32Cfg<DK, DV> Cfg;
+    auto kern = gla_chunk_f32_kernel<DK, DV>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(p.B * p.P * p.H), dim3(Cfg::kThreads), Cfg::kBytes, s, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t s) {
+    if (d_k == 64 && d_v == 64) return launch_f32<64, 64>(p, s);
+    if (d_k == 64 && d_v == 128) return launch_f32<64, 128>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_f32<128, 64>(p, s);
+    if (d_k == 128 && d_v == 128) return launch_f32<128, 128>(p, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace zeco

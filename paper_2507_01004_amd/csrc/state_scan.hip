@@ -1,0 +1,72 @@
+// Segment-state scan: S_init[p+1] = (exp(G_tot[p])^T 1) .* S_init[p] + S_loc[p]  (Sec. 3.2 block
+// update, applied along the chain of segments resident on one GPU).
+//
+// Pure streaming: every state element is an independent serial chain of length P, so one thread
+// owns one float4 of a (head, d_k-row-block) slab and walks p = 0..P-1.  The loads of the next
+// kDepth segments do not depend on the chain and are issued ahead of the FMAs that consume them,
+// which is what keeps HBM busy (the on-device analogue of the block pipeline of Sec. 3.2:
+// all row blocks advance concurrently, each block's chain is latency-bound on its own).
+// One fused multiply-add per element per segment, in segment order: bitwise reproducible and
+// independent of how rows are grouped into blocks.
+#include "zeco_device.h"
+#include "zeco_internal.h"
+
+namespace zeco {
+
+constexpr int kScanDepth = 8;
+
+__global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
+    const int blocks_per_head = p.d_k / p.rows_per_block;
+    const int bh = blockIdx.x / blocks_per_head;
+    const int row0 = (blockIdx.x % blocks_per_head) * p.rows_per_block;
+    const int dv4 = p.d_v >> 2;
+    const int slab4 = p.rows_per_block * dv4;
+    const size_t state = (size_t)p.d_k * p.d_v;
+    const size_t seg_stride = (size_t)p.BH * state;         // floats between segments
+    const size_t g_stride = (size_t)p.BH * p.d_k;
+
+    for (int e = threadIdx.x; e < slab4; e += blockDim.x) {
+        const int row = row0 + e / dv4;
+        const size_t off = (size_t)bh * state + (size_t)row * p.d_v + (size_t)(e % dv4) * 4;
+        const float *loc = p.S_loc + off;
+        const float *gt = p.G_tot + (size_t)bh * p.d_k + row;
+        float *init = p.S_init + off;
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+        if (p.S0) s = *reinterpret_cast<const f32x4 *>(p.S0 + off);
+
+        for (int p0 = 0; p0 < p.P; p0 += kScanDepth) {
+            f32x4 x[kScanDepth];
+            float a[kScanDepth];
+#pragma unroll
+            for (int u = 0; u < kScanDepth; ++u) {
+                if (p0 + u < p.P) {
+                    x[u] = *reinterpret_cast<const f32x4 *>(loc + (size_t)(p0 + u) * seg_stride);
+                    a[u] = gt[(size_t)(p0 + u) * g_stride];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kScanDepth; ++u) {
+                if (p0 + u < p.P) {
+                    *reinterpret_cast<f32x4 *>(init + (size_t)(p0 + u) * seg_stride) = s;
+                    const float d = fast_exp(a[u]);
+                    s[0] = __builtin_fmaf(d, s[0], x[u][0]);
+                    s[1] = __builtin_fmaf(d, s[1], x[u][1]);
+                    s[2] = __builtin_fmaf(d, s[2], x[u][2]);
+                    s[3] = __builtin_fmaf(d, s[3], x[u][3]);
+                }
+            }
+        }
+        if (p.S_last) *reinterpret_cast<f32x4 *>(p.S_last + off) = s;
+    }
+}
+
+hipError_t launch_scan(const ScanParams &p, hipStream_t s) {
+    const int blocks = p.BH * (p.d_k / p.rows_per_block);
+    const int slab4 = p.rows_per_block * (p.d_v / 4);
+    int threads = ((slab4 + 63) / 64) * 64;
+    if (threads > 256) threads = 256;
+    hipLaunchKernelGGL(state_scan_kernel, dim3(blocks), dim3(threads), 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace zeco

@@ -1,0 +1,128 @@
+// C ABI of the ZeCO hot path (declared in include/zeco.h): argument validation and dispatch to
+// the gfx950 kernels.  Validation happens before any HIP call so that the error paths can be
+// exercised on a host without a GPU.
+#include "../../include/zeco.h"
+#include "zeco_internal.h"
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool dim_ok(int d) { return d == 64 || d == 128; }
+
+// ZECO_OK when the descriptor is well formed and supported.
+zeco_status check_desc(const zeco_gla_desc *d) {
+    if (!d) return ZECO_ERR_INVALID_ARG;
+    if (d->B <= 0 || d->P <= 0 || d->H <= 0 || d->L <= 0 || d->d_k <= 0 || d->d_v <= 0 || d->C <= 0)
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_F32 && d->io_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
+    if (d->g_dtype != ZECO_F32 && d->g_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
+    if (!(d->scale == d->scale)) return ZECO_ERR_INVALID_ARG;
+    if (d->L % d->C != 0) return ZECO_ERR_INVALID_ARG;
+    if ((int64_t)d->P * d->L > (int64_t)1 << 40) return ZECO_ERR_INVALID_ARG;
+    const int64_t s[6] = {d->stride_b, d->stride_t, d->stride_h, d->vstride_b, d->vstride_t, d->vstride_h};
+    for (int i = 0; i < 6; ++i)
+        if (s[i] < 0 || s[i] % 8 != 0) return ZECO_ERR_INVALID_ARG;
+    if (d->stride_h < d->d_k || d->vstride_h < d->d_v) return ZECO_ERR_INVALID_ARG;
+    if (d->stride_t < d->d_k || d->vstride_t < d->d_v) return ZECO_ERR_INVALID_ARG;
+    if ((int64_t)d->B * d->P * d->H > (int64_t)1 << 24) return ZECO_ERR_INVALID_ARG;
+    if (d->C != 64 || !dim_ok(d->d_k) || !dim_ok(d->d_v)) return ZECO_ERR_UNSUPPORTED;
+    if (d->io_dtype == ZECO_F32 && d->g_dtype != ZECO_F32) return ZECO_ERR_UNSUPPORTED;
+    return ZECO_OK;
+}
+
+zeco_status from_hip(hipError_t e) { return e == hipSuccess ? ZECO_OK : ZECO_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc) {
+    (void)desc;
+    return 0;
+}
+
+zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
+                               const void *g, void *o, float *S_loc, float *G_cum, float *G_tot,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !k || !v || !g || !o || !S_loc || !G_cum || !G_tot) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
+        !aligned16(S_loc) || !aligned16(G_cum) || !aligned16(G_tot))
+        return ZECO_ERR_INVALID_ARG;
+    if (workspace_bytes < zeco_gla_local_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
+    (void)workspace;
+
+    zeco::ChunkParams p;
+    p.q = q; p.k = k; p.v = v; p.g = g; p.o = o;
+    p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot;
+    p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
+    p.n_chunks = d->L / d->C;
+    p.n_slices = 1;
+    p.scale = d->scale;
+    p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
+    p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
+    p.n_slices = zeco::chunk_bf16_slices(d->B * d->P * d->H, d->d_v);
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, s));
+}
+
+zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
+                            const float *S_loc, const float *G_tot, const float *S0, float *S_init,
+                            float *S_last, int32_t direction, void *stream) {
+    if (P <= 0 || BH <= 0 || d_k <= 0 || d_v <= 0 || K_blocks <= 0) return ZECO_ERR_INVALID_ARG;
+    if (d_k % K_blocks != 0) return ZECO_ERR_INVALID_ARG;
+    if (direction != 0 && direction != 1) return ZECO_ERR_INVALID_ARG;
+    if (!S_loc || !G_tot || !S_init) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(S_loc) || !aligned16(S_init) || !aligned16(S0) || !aligned16(S_last) ||
+        (reinterpret_cast<uintptr_t>(G_tot) & 3u))
+        return ZECO_ERR_INVALID_ARG;
+    if ((int64_t)BH * K_blocks > (int64_t)1 << 30) return ZECO_ERR_INVALID_ARG;
+    if (d_v % 4 != 0) return ZECO_ERR_UNSUPPORTED;
+    if (direction == 1) return ZECO_ERR_UNSUPPORTED;
+
+    zeco::ScanParams p;
+    p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = S0; p.S_init = S_init; p.S_last = S_last;
+    p.P = P; p.BH = BH; p.d_k = d_k; p.d_v = d_v; p.rows_per_block = d_k / K_blocks;
+    return from_hip(zeco::launch_scan(p, static_cast<hipStream_t>(stream)));
+}
+
+zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const float *G_cum,
+                                  const float *S_init, void *o, int32_t first_segment_is_zero,
+                                  void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !G_cum || !S_init || !o) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(G_cum) || !aligned16(S_init) || !aligned16(o))
+        return ZECO_ERR_INVALID_ARG;
+
+    zeco::ApplyParams p;
+    p.q = q; p.G_cum = G_cum; p.S_init = S_init; p.o = o;
+    p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
+    p.p0 = first_segment_is_zero ? 1 : 0;
+    int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
+    while (tpw > 64 && d->L % tpw != 0) tpw >>= 1;
+    p.tokens_per_wg = tpw;
+    p.scale = d->scale;
+    p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
+    p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_apply_f32(p, d->d_k, d->d_v, s));
+    return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, s));
+}
+
+const char *zeco_status_string(int32_t status) {
+    switch (status) {
+        case ZECO_OK: return "ok";
+        case ZECO_ERR_INVALID_ARG: return "invalid argument";
+        case ZECO_ERR_UNSUPPORTED: return "unsupported configuration";
+        case ZECO_ERR_WORKSPACE: return "workspace too small";
+        case ZECO_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int32_t zeco_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,75 @@
+// Device-side helpers shared by the gfx950 kernels: vector types, bf16 packing, MFMA tile traits.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace zeco {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kChunk = 64;  // chunk length C; equals the wavefront width
+
+// Two floats -> packed bf16 pair (round to nearest even), low half = a.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    bf16x2 r;
+    r[0] = (__bf16)a;
+    r[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) {
+    return __builtin_bit_cast(float, w & 0xffff0000u);
+}
+
+// Natural exponential through the hardware exp2 (relative error ~1e-6 over the ranges used here).
+__device__ __forceinline__ float fast_exp(float x) { return __expf(x); }
+
+// Traits of the two bf16 MFMA shapes used.  A wave computes D[M x N] += A[M x K] B[K x N] with
+// M = N = TILE.  Lane l holds column (l % TILE) of D; with kg = l / TILE, accumulator register r
+// holds row `row(r, kg)`.  For A (B) lane l holds row (column) l % TILE and the 8 consecutive
+// k-slots 8*kg .. 8*kg+7.
+template <int TILE> struct Mma;
+
+template <> struct Mma<16> {
+    typedef f32x4 acc_t;
+    static constexpr int kAcc = 4;   // accumulator registers per tile
+    static constexpr int kK = 32;    // K extent of one instruction
+    static constexpr int kGroups = 4;
+    __device__ static __forceinline__ acc_t run(bf16x8 a, bf16x8 b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ constexpr int row(int r, int kg) { return 4 * kg + r; }
+};
+
+template <> struct Mma<32> {
+    typedef f32x16 acc_t;
+    static constexpr int kAcc = 16;
+    static constexpr int kK = 16;
+    static constexpr int kGroups = 2;
+    __device__ static __forceinline__ acc_t run(bf16x8 a, bf16x8 b, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ constexpr int row(int r, int kg) {
+        return 8 * (r / 4) + 4 * kg + (r % 4);
+    }
+};
+
+// fp32 MFMA 16x16x4: lane l holds A[l%16][l/16], B[l/16][l%16]; D register r holds row 4*(l/16)+r,
+// column l%16.
+__device__ __forceinline__ f32x4 mma_f32(float a, float b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// 16-byte LDS / global accessors on raw byte pointers.
+__device__ __forceinline__ bf16x8 lds_frag(const unsigned char *base, int byte_off) {
+    return *reinterpret_cast<const bf16x8 *>(base + byte_off);
+}
+
+}  // namespace zeco

@@ -1,0 +1,177 @@
+"""Thin ctypes binding of libzeco.so (C ABI in include/zeco.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels; PyTorch supplies device memory and the stream.
+There is no CPU fallback: a missing library raises.  Tensor layouts: q, k, g [B,T,H,d_k];
+v, o [B,T,H,d_v] (any strides with a contiguous last dimension); S_loc, S_init [P,B,H,d_k,d_v]
+fp32; G_cum [B,T,H,d_k] fp32; G_tot [P,B,H,d_k] fp32.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
+
+ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
+ZECO_F32, ZECO_BF16 = 0, 1
+EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
+           "zeco_apply_init_state", "zeco_status_string", "zeco_version")
+
+
+class GlaDesc(ctypes.Structure):
+    """Mirror of zeco_gla_desc."""
+    _fields_ = [("B", ctypes.c_int32), ("P", ctypes.c_int32), ("H", ctypes.c_int32),
+                ("L", ctypes.c_int32), ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32),
+                ("C", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("g_dtype", ctypes.c_int32),
+                ("scale", ctypes.c_float),
+                ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
+                ("vstride_b", ctypes.c_int64), ("vstride_t", ctypes.c_int64), ("vstride_h", ctypes.c_int64)]
+
+
+class ZecoError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library.  Raises if it has not been built (python -m paper_2507_01004_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libzeco.so is not built: run __graft_entry__.build() "
+                               "(expected at %s); there is no fallback path" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, fp = ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p
+        dp = ctypes.POINTER(GlaDesc)
+        L.zeco_gla_local_fwd_workspace.argtypes = [dp]
+        L.zeco_gla_local_fwd_workspace.restype = ctypes.c_size_t
+        L.zeco_gla_local_fwd.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_local_fwd.restype = i32
+        L.zeco_state_scan.argtypes = [i32, i32, i32, i32, i32, fp, fp, fp, fp, fp, i32, vp]
+        L.zeco_state_scan.restype = i32
+        L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
+        L.zeco_apply_init_state.restype = i32
+        L.zeco_status_string.argtypes = [i32]
+        L.zeco_status_string.restype = ctypes.c_char_p
+        L.zeco_version.argtypes = []
+        L.zeco_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().zeco_status_string(int(status)).decode()
+
+
+def version():
+    return int(lib().zeco_version())
+
+
+def _dtype_code(t):
+    if t.dtype == torch.float32:
+        return ZECO_F32
+    if t.dtype == torch.bfloat16:
+        return ZECO_BF16
+    raise TypeError("unsupported dtype %s" % t.dtype)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def make_desc(q, v, g, P, C=64, scale=1.0):
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    if T % P != 0:
+        raise ValueError("T=%d is not a multiple of P=%d" % (T, P))
+    if q.stride(-1) != 1 or v.stride(-1) != 1:
+        raise ValueError("innermost dimension must be contiguous")
+    return GlaDesc(B, P, H, T // P, dk, dv, C, _dtype_code(q), _dtype_code(g), float(scale),
+                   q.stride(0), q.stride(1), q.stride(2), v.stride(0), v.stride(1), v.stride(2))
+
+
+def _check_same_layout(ref, *others):
+    for t in others:
+        if t.shape != ref.shape or t.stride() != ref.stride() or t.device != ref.device:
+            raise ValueError("tensors sharing a descriptor must share shape, strides and device")
+
+
+def gla_local_fwd(q, k, v, g, P, scale=1.0, C=64, out=None):
+    """zeco_gla_local_fwd.  Returns (o, S_loc, G_cum, G_tot); `out` may supply them preallocated."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    if g.shape != q.shape or g.stride() != q.stride():
+        raise ValueError("g must share q's shape and strides")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share a dtype")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    desc = make_desc(q, v, g, P, C, scale)
+    if out is None:
+        o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
+        S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=q.device)
+        G_cum = torch.empty(B, T, H, dk, dtype=torch.float32, device=q.device)
+        G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device=q.device)
+    else:
+        o, S_loc, G_cum, G_tot = out
+        _check_same_layout(v, o)
+    L = lib()
+    ws_bytes = L.zeco_gla_local_fwd_workspace(ctypes.byref(desc))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=q.device) if ws_bytes else None
+    st = L.zeco_gla_local_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(o),
+                              _ptr(S_loc), _ptr(G_cum), _ptr(G_tot), _ptr(ws), ws_bytes, _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_local_fwd")
+    return o, S_loc, G_cum, G_tot
+
+
+def state_scan(S_loc, G_tot, S0=None, K_blocks=16, out=None, direction=0):
+    """zeco_state_scan on [P,B,H,d_k,d_v] (or [P,BH,d_k,d_v]) states.  Returns (S_init, S_last)."""
+    if not S_loc.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    P, dk, dv = S_loc.shape[0], S_loc.shape[-2], S_loc.shape[-1]
+    BH = S_loc.numel() // (P * dk * dv)
+    if not (S_loc.is_contiguous() and G_tot.is_contiguous()):
+        raise ValueError("S_loc and G_tot must be contiguous")
+    if out is None:
+        S_init = torch.empty_like(S_loc)
+        S_last = torch.empty(S_loc.shape[1:], dtype=torch.float32, device=S_loc.device)
+    else:
+        S_init, S_last = out
+    st = lib().zeco_state_scan(P, BH, dk, dv, int(K_blocks), _ptr(S_loc), _ptr(G_tot), _ptr(S0),
+                               _ptr(S_init), _ptr(S_last), int(direction), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_state_scan")
+    return S_init, S_last
+
+
+def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segment_is_zero=True):
+    """zeco_apply_init_state: o += (scale q .* exp(G_cum)) S_init[p], in place.  `g_like` only
+    supplies the gate dtype recorded in the descriptor."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    desc = make_desc(q, o, g_like, P, C, scale)
+    st = lib().zeco_apply_init_state(ctypes.byref(desc), _ptr(q), _ptr(G_cum), _ptr(S_init), _ptr(o),
+                                     1 if first_segment_is_zero else 0, _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_apply_init_state")
+    return o
+
+
+def segmented_fwd(q, k, v, g, P, scale=1.0, S0=None, K_blocks=16):
+    """Local pass, segment-state scan and correction chained.  Returns (o, S_last, parts) with
+    parts = dict(S_loc, G_cum, G_tot, S_init)."""
+    o, S_loc, G_cum, G_tot = gla_local_fwd(q, k, v, g, P, scale)
+    S_init, S_last = state_scan(S_loc, G_tot, S0=S0, K_blocks=K_blocks)
+    apply_init_state(q, g, G_cum, S_init, o, P, scale, first_segment_is_zero=S0 is None)
+    return o, S_last, dict(S_loc=S_loc, G_cum=G_cum, G_tot=G_tot, S_init=S_init)

@@ -1,0 +1,101 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the header declares,
+and rejects bad arguments with a status code before touching the HIP runtime."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2507_01004_amd import zeco
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(zeco.LIB_PATH):
+        from paper_2507_01004_amd.build import build_lib
+        build_lib()
+    return zeco.lib()
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "zeco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(zeco_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_match_header(L):
+    names = header_functions()
+    assert set(names) == set(zeco.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_strings(L):
+    assert zeco.version() >= 100
+    assert zeco.status_string(zeco.ZECO_OK) == "ok"
+    for s in range(1, 5):
+        assert zeco.status_string(s) not in ("ok", "unknown status")
+    assert zeco.status_string(99) == "unknown status"
+
+
+def good_desc(**kw):
+    d = dict(B=1, P=2, H=2, L=128, d_k=128, d_v=128, C=64, io_dtype=zeco.ZECO_BF16,
+             g_dtype=zeco.ZECO_F32, scale=1.0, stride_b=2 * 256 * 128 * 2, stride_t=256, stride_h=128,
+             vstride_b=2 * 256 * 128 * 2, vstride_t=256, vstride_h=128)
+    d.update(kw)
+    return zeco.GlaDesc(*[d[f[0]] for f in zeco.GlaDesc._fields_])
+
+
+FAKE = ctypes.c_void_p(0x1000)   # aligned, never dereferenced: validation fails first
+
+
+def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
+    return L.zeco_gla_local_fwd(ctypes.byref(desc), q, FAKE, FAKE, FAKE, o, FAKE, FAKE, FAKE, None,
+                                ws_bytes, None)
+
+
+@pytest.mark.parametrize("kw,expect", [
+    (dict(B=0), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(L=100), zeco.ZECO_ERR_INVALID_ARG),          # L % C != 0
+    (dict(stride_t=100), zeco.ZECO_ERR_INVALID_ARG),   # stride not a multiple of 8
+    (dict(stride_h=64), zeco.ZECO_ERR_INVALID_ARG),    # heads overlap
+    (dict(io_dtype=7), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(scale=float("nan")), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(C=32, L=128), zeco.ZECO_ERR_UNSUPPORTED),
+    (dict(d_k=96, stride_h=96), zeco.ZECO_ERR_UNSUPPORTED),
+    (dict(io_dtype=zeco.ZECO_F32, g_dtype=zeco.ZECO_BF16), zeco.ZECO_ERR_UNSUPPORTED),
+])
+def test_local_fwd_rejects_bad_descriptors(L, kw, expect):
+    assert call_local(L, good_desc(**kw)) == expect
+    assert L.zeco_apply_init_state(ctypes.byref(good_desc(**kw)), FAKE, FAKE, FAKE, FAKE, 1, None) == expect
+
+
+def test_local_fwd_rejects_bad_pointers(L):
+    assert call_local(L, good_desc(), q=None) == zeco.ZECO_ERR_INVALID_ARG
+    assert call_local(L, good_desc(), o=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_local_fwd(None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, 0,
+                                None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_local_fwd_workspace(None) == 0
+
+
+def test_state_scan_rejects_bad_arguments(L):
+    def scan(P=4, BH=2, dk=128, dv=128, K=8, S_loc=FAKE, G=FAKE, S0=None, S_init=FAKE, S_last=None, d=0):
+        return L.zeco_state_scan(P, BH, dk, dv, K, S_loc, G, S0, S_init, S_last, d, None)
+    assert scan(P=0) == zeco.ZECO_ERR_INVALID_ARG
+    assert scan(K=3) == zeco.ZECO_ERR_INVALID_ARG          # does not divide d_k
+    assert scan(S_loc=None) == zeco.ZECO_ERR_INVALID_ARG
+    assert scan(S_init=ctypes.c_void_p(0x1008)) == zeco.ZECO_ERR_INVALID_ARG
+    assert scan(d=2) == zeco.ZECO_ERR_INVALID_ARG
+    assert scan(d=1) == zeco.ZECO_ERR_UNSUPPORTED          # reverse chain belongs to the backward pass
+    assert scan(dv=126) == zeco.ZECO_ERR_UNSUPPORTED
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    q = torch.zeros(1, 64, 1, 64)
+    with pytest.raises(RuntimeError):
+        zeco.gla_local_fwd(q, q, q, q, 1)
+    with pytest.raises(RuntimeError):
+        zeco.state_scan(torch.zeros(1, 1, 64, 64), torch.zeros(1, 1, 64))

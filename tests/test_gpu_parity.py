@@ -1,0 +1,166 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
+on seeded synthetic inputs small enough for the oracle yet spanning several chunks, tiles,
+segments and both workgroup decompositions of the bf16 chunk kernel."""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2507_01004_amd import synth, zeco
+from tests.gpu_util import TOL, dev, host, log_err, oracle_full, oracle_local, rel_err_bh
+
+pytestmark = pytest.mark.gpu
+
+# (name, B, H, P, L, d_k, d_v, io, g dtype)
+CASES = [
+    ("c1_f32", 1, 1, 4, 64, 64, 64, "f32", "f32"),                 # BASELINE config 1
+    ("f32_d128", 2, 3, 2, 192, 128, 128, "f32", "f32"),
+    ("f32_dk64_dv128", 1, 2, 3, 128, 64, 128, "f32", "f32"),
+    ("f32_dk128_dv64", 1, 2, 2, 128, 128, 64, "f32", "f32"),
+    ("bf16_sliced", 1, 4, 2, 320, 128, 128, "bf16", "f32"),        # 8 streams -> two d_v slices, 16-wide tiles
+    ("bf16_whole", 2, 16, 8, 128, 128, 128, "bf16", "f32"),        # 256 streams -> one slice, 32-wide tiles
+    ("bf16_gbf16", 1, 3, 2, 256, 128, 128, "bf16", "bf16"),
+    ("bf16_d64", 1, 2, 4, 192, 64, 64, "bf16", "f32"),
+    ("bf16_dk64_dv128", 1, 2, 2, 128, 64, 128, "bf16", "f32"),
+    ("bf16_dk128_dv64", 1, 2, 2, 128, 128, 64, "bf16", "bf16"),
+]
+
+
+def make(case, **kw):
+    name, B, H, P, L, dk, dv, io, gd = case
+    return synth.make_inputs(B, P * L, H, dk, dv, seed=zlib.crc32(name.encode()) % 10000 + 7, io=io, g=gd,
+                             device="cuda", **kw)
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_local_fwd_matches_oracle(case):
+    name, B, H, P, L, dk, dv, io, gd = case
+    print("case", case, flush=True)
+    inp = make(case)
+    o, S_loc, G_cum, G_tot = zeco.gla_local_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5)
+    torch.cuda.synchronize()
+    o_r, S_r, Gc_r, Gt_r = oracle_local(inp, P, scale=0.5)
+    tol = TOL[io]
+    assert rel_err_bh(host(o), o_r, (0, 2)) <= tol
+    assert rel_err_bh(host(S_loc), S_r, (0, 1, 2)) <= tol
+    assert log_err(host(G_cum), Gc_r) <= 1e-5
+    assert log_err(host(G_tot), Gt_r) <= 1e-5
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_pipeline_matches_unsegmented_oracle(case):
+    """Local pass + scan + correction against Eq. (1) run over the whole sequence."""
+    name, B, H, P, L, dk, dv, io, gd = case
+    print("case", case, flush=True)
+    inp = make(case, gate_div=64.0)      # slow decay: the incoming state matters at every token
+    o, S_last, parts = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
+    torch.cuda.synchronize()
+    o_r, Sf_r = oracle_full(inp)
+    tol = TOL[io]
+    assert rel_err_bh(host(o), o_r, (0, 2)) <= tol
+    assert rel_err_bh(host(S_last), Sf_r, (0, 1)) <= tol
+    # the correction must matter in this test, otherwise it proves nothing about it
+    o_loc, _, _, _ = oracle_local(inp, P)
+    assert rel_err_bh(o_loc, o_r, (0, 2)) > 10 * tol or P == 1
+
+
+@pytest.mark.parametrize("case", [CASES[0], CASES[4], CASES[5]], ids=lambda c: c[0])
+def test_pipeline_with_incoming_state_and_zero_gate(case):
+    """g == 0 (plain causal linear attention) and a non-zero S0: nothing decays, so the state
+    and the correction reach every token with full weight."""
+    name, B, H, P, L, dk, dv, io, gd = case
+    print("case", case, flush=True)
+    inp = make(case, zero_gate=True)
+    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    o, S_last, _ = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, S0=S0)
+    torch.cuda.synchronize()
+    o_r, Sf_r = oracle_full(inp, S0=host(S0))
+    assert rel_err_bh(host(o), o_r, (0, 2)) <= TOL[io]
+    assert rel_err_bh(host(S_last), Sf_r, (0, 1)) <= TOL[io]
+
+
+def random_states(P, BH, dk, dv, seed):
+    r = np.random.default_rng(seed)
+    S_loc = r.standard_normal((P, BH, dk, dv)).astype(np.float32)
+    G_tot = (-r.random((P, BH, dk)) * 3).astype(np.float32)
+    S0 = r.standard_normal((BH, dk, dv)).astype(np.float32)
+    return S_loc, G_tot, S0
+
+
+@pytest.mark.parametrize("shape", [(4, 1, 64, 64), (8, 16, 128, 128), (1, 3, 128, 64), (37, 2, 64, 128)])
+def test_state_scan_matches_oracle_and_is_block_independent(shape):
+    P, BH, dk, dv = shape
+    print("scan", shape, flush=True)
+    S_loc, G_tot, S0 = random_states(P, BH, dk, dv, seed=P)
+    for s0 in (None, S0):
+        ref_init, ref_last = oracle.state_scan(S_loc, G_tot, s0)
+        base = None
+        for K in (1, 2, 8, dk // 4, dk):
+            S_init, S_last = zeco.state_scan(dev(S_loc), dev(G_tot), None if s0 is None else dev(s0),
+                                             K_blocks=K)
+            torch.cuda.synchronize()
+            assert rel_err_bh(host(S_init), ref_init, (1,)) <= 1e-5
+            assert rel_err_bh(host(S_last), ref_last, (0,)) <= 1e-5
+            if base is None:
+                base = (S_init.clone(), S_last.clone())
+            else:   # bitwise independent of the row-block count
+                assert torch.equal(S_init, base[0]) and torch.equal(S_last, base[1])
+
+
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("dims", [(64, 64), (128, 128), (64, 128), (128, 64)])
+def test_apply_init_state_matches_oracle(io, dims):
+    dk, dv = dims
+    B, H, P, L = 2, 2, 3, 128
+    print("apply", io, dims, flush=True)
+    r = np.random.default_rng(dk + dv)
+    dt = synth.torch_dtype(io)
+    q = torch.from_numpy(r.standard_normal((B, P * L, H, dk))).to(dt).cuda()
+    o0 = torch.from_numpy(r.standard_normal((B, P * L, H, dv))).to(dt).cuda()
+    G = -np.cumsum(r.random((B, P * L, H, dk)) * 0.05, axis=1).astype(np.float32)
+    S = r.standard_normal((P, B, H, dk, dv)).astype(np.float32)
+    for first_zero in (True, False):
+        Sx = S.copy()
+        if first_zero:
+            Sx[0] = 0
+        o = o0.clone()
+        zeco.apply_init_state(q, torch.empty(0), dev(G), dev(Sx), o, P, scale=0.7,
+                              first_segment_is_zero=first_zero)
+        torch.cuda.synchronize()
+        ref = oracle.apply_init_state(host(q), G.astype(np.float64), Sx.astype(np.float64), host(o0), 0.7)
+        assert rel_err_bh(host(o), ref, (0, 2)) <= TOL[io]
+    # zero incoming states leave o bitwise unchanged
+    o = o0.clone()
+    zeco.apply_init_state(q, torch.empty(0), dev(G), dev(np.zeros_like(S)), o, P, first_segment_is_zero=False)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o0)
+
+
+def test_strided_views_and_determinism():
+    """q, k, g, v taken as views of one fused projection buffer; two runs are bitwise equal."""
+    B, T, H, d, P = 1, 256, 4, 128, 2
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    fused = torch.randn(B, T, H, 4 * d, generator=gen, device="cuda").to(torch.bfloat16)
+    q, k, v = fused[..., :d], fused[..., d:2 * d], fused[..., 2 * d:3 * d]
+    g = (torch.nn.functional.logsigmoid(fused[..., 3 * d:].float()) / 16).to(torch.bfloat16)
+    gbuf = torch.empty_like(fused)
+    gbuf[..., :d] = g
+    gv = gbuf[..., :d]
+    outs = []
+    for _ in range(2):
+        o, S_last, parts = zeco.segmented_fwd(q, k, v, gv, P)
+        torch.cuda.synchronize()
+        outs.append((o.clone(), S_last.clone(), parts["G_cum"].clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    o_r, Sf_r = oracle.gla_recurrent(host(q), host(k), host(v), host(gv))
+    assert rel_err_bh(host(outs[0][0]), o_r, (0, 2)) <= TOL["bf16"]
+    assert rel_err_bh(host(outs[0][1]), Sf_r, (0, 1)) <= TOL["bf16"]
+
+
+def test_errors_surface_as_exceptions():
+    q = torch.zeros(1, 96, 1, 64, device="cuda")
+    with pytest.raises(zeco.ZecoError):
+        zeco.gla_local_fwd(q, q, q, q, 1)            # L = 96 is not a multiple of the chunk length

@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZeCO hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input already resident in HBM:
+zeco_gla_local_fwd -> zeco_state_scan -> zeco_apply_init_state.  Prints ONE JSON line with the
+whole-job throughput (tokens/s), the roofline of the dominant kernel (the chunk kernel of the
+local pass) measured live with HIP events on the launch stream, and the CPU oracle timed on a
+bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c4] [--g-dtype f32|bf16]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
+
+# HBM bytes per launch of the chunk kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/*.txt give the commands and the copy-kernel calibration); None = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_bytes(c, g_bytes):
+    """Algorithmic HBM bytes per launch of each kernel (per token-head figures x units)."""
+    B, H, P, L, dk, dv = c["B"], c["H"], c["P"], c["L"], c["d_k"], c["d_v"]
+    io = 2 if c["io"] == "bf16" else 4
+    th = B * P * L * H                                  # token-heads per launch
+    streams = B * P * H
+    local = th * (2 * dk * io + dv * io + dk * g_bytes   # read q, k, v, g
+                  + dv * io + dk * 4)                     # write o, G_cum
+    local += streams * (dk * dv * 4 + dk * 4)            # S_loc, G_tot
+    scan = streams * (2 * dk * dv * 4 + dk * 4) + B * H * dk * dv * 4
+    th_c = B * (P - 1) * L * H                           # segment 0 needs no correction
+    apply_ = th_c * (dk * io + dk * 4 + 2 * dv * io) + B * (P - 1) * H * dk * dv * 4
+    return dict(local=local, scan=scan, apply=apply_)
+
+
+def algorithmic_flops(c):
+    B, H, P, L, dk, dv, C = c["B"], c["H"], c["P"], c["L"], c["d_k"], c["d_v"], c["C"]
+    th = B * P * L * H
+    local = th * (2 * C * dk + 2 * C * dv + 2 * dk * dv + 2 * dk * dv)   # dense count, Sec. 2.1
+    apply_ = B * (P - 1) * L * H * 2 * dk * dv
+    return dict(local=local, apply=apply_)
+
+
+def cpu_baseline(inp, c, sample_tokens):
+    """The oracle as it stands, on the first `sample_tokens` tokens of every head."""
+    from oracle import oracle
+    from paper_2507_01004_amd import synth
+    h = {n: synth.to_f64(t[:, :sample_tokens]) for n, t in inp.items()}
+    t0 = time.perf_counter()
+    oracle.gla_recurrent(h["q"], h["k"], h["v"], h["g"])
+    dt = time.perf_counter() - t0
+    return {"value": c["B"] * sample_tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": "fp64 token recurrence (Eq. 1) over the first %d tokens of all %d heads of "
+                      "the same inputs, OpenMP over heads" % (sample_tokens, c["H"])}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
+    ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--k-blocks", type=int, default=16)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calib-copy-mib", type=int, default=1024,
+                    help="size of the plain copy timed beside the kernels (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (P sequence segments resident on one MI355X); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2507_01004_amd import synth, zeco
+
+    torch.cuda.set_device(0)
+    inp, c = synth.config_inputs(args.workload, device="cuda:0", g=args.g_dtype)
+    B, H, P, L, dk, dv = c["B"], c["H"], c["P"], c["L"], c["d_k"], c["d_v"]
+    T = P * L
+    q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
+    o = torch.empty_like(v)
+    S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device="cuda:0")
+    G_cum = torch.empty(B, T, H, dk, dtype=torch.float32, device="cuda:0")
+    G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device="cuda:0")
+    S_init = torch.empty_like(S_loc)
+    S_last = torch.empty(B, H, dk, dv, dtype=torch.float32, device="cuda:0")
+
+    def step(ev=None):
+        zeco.gla_local_fwd(q, k, v, g, P, out=(o, S_loc, G_cum, G_tot))
+        if ev:
+            ev[1].record()
+        zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=(S_init, S_last))
+        if ev:
+            ev[2].record()
+        zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        evs[s][0].record()
+        step(evs[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    copy_gbs = None
+    if args.calib_copy_mib:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        zeco.hbm_copy(dst, src)
+        ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ce[0].record()
+        for _ in range(5):
+            zeco.hbm_copy(dst, src)
+        ce[1].record()
+        torch.cuda.synchronize()
+        copy_gbs = 5 * 2 * src.numel() / ce[0].elapsed_time(ce[1]) / 1e6
+        del src, dst
+
+    ms = {n: sum(e[i].elapsed_time(e[i + 1]) for e in evs) / args.steps
+          for i, n in enumerate(["local", "scan", "apply"])}
+    ms_per_step = wall * 1e3 / args.steps
+    g_bytes = 4 if args.g_dtype == "f32" else 2
+    ab = algorithmic_bytes(c, g_bytes)
+    af = algorithmic_flops(c)
+    kernels = {}
+    for n in ("local", "scan", "apply"):
+        if ms[n] > 0:
+            kernels[n] = {"ms": round(ms[n], 4), "alg_bytes": ab[n],
+                          "GBps": round(ab[n] / ms[n] / 1e6, 1),
+                          "hbm_frac": round(ab[n] / ms[n] / 1e6 / HBM_PEAK_GBS, 4)}
+            if n in af:
+                kernels[n]["TFLOPs"] = round(af[n] / ms[n] / 1e9, 1)
+                kernels[n]["mfma_frac"] = round(af[n] / ms[n] / 1e9 / MFMA_BF16_PEAK_TF, 4)
+    ach = ab["local"] / ms["local"] / 1e6
+    out = {
+        "metric": "tokens/s for GLA segment fwd + state scan (1 MI355X)",
+        "value": B * T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c["io"], "data": "synthetic",
+        "config": {"workload": "%s: B=%d H=%d P=%d segments x L=%d tokens, d_k=d_v=%d, C=%d, %s q/k/v/o, "
+                               "%s log-decay; local fwd + segment-state scan + init-state correction"
+                               % (args.workload, B, H, P, L, dk, c["C"], c["io"], args.g_dtype),
+                   "K_blocks": args.k_blocks},
+        "roofline": {"kernel": "gla_chunk_bf16_kernel (zeco_gla_local_fwd)", "bound": "hbm",
+                     "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC.get((args.workload, args.g_dtype))},
+        "kernels": kernels,
+        "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(inp, c, min(T, 131072))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -92,6 +92,12 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *desc, const void *q, cons
                                   const float *S_init, void *o, int32_t first_segment_is_zero,
                                   void *stream);
 
+/* Bandwidth calibration utility (not part of the method): copies `bytes` (a multiple of 16) from
+ * src to dst with a plain grid-stride kernel of 16-byte accesses.  Used to scale the HBM byte
+ * counters of the profiler and to quote the achievable copy bandwidth beside the nominal peak.
+ * Both pointers are device pointers, 16-byte aligned, non-overlapping. */
+zeco_status zeco_hbm_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 const char *zeco_status_string(int32_t status);
 int32_t zeco_version(void);
 

@@ -69,4 +69,20 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Plain copy used to calibrate the profiler's HBM byte counters and the achievable bandwidth.
+__global__ __launch_bounds__(256) void hbm_copy_kernel(u32x4 *dst, const u32x4 *src, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(hbm_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (u32x4 *)dst,
+                       (const u32x4 *)src, n16);
+    return hipGetLastError();
+}
+
 }  // namespace zeco

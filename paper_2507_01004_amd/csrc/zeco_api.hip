@@ -112,6 +112,11 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
     return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, s));
 }
 
+zeco_status zeco_hbm_copy(void *dst, const void *src, size_t bytes, void *stream) {
+    if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0) return ZECO_ERR_INVALID_ARG;
+    return from_hip(zeco::launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+}
+
 const char *zeco_status_string(int32_t status) {
     switch (status) {
         case ZECO_OK: return "ok";

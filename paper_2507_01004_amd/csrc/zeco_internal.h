@@ -40,6 +40,7 @@ hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_scan(const ScanParams &p, hipStream_t s);
+hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 // d_v slices per stream the bf16 chunk kernel will use for this problem (1 or 2).
 int chunk_bf16_slices(int streams, int d_v);

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
 ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
 ZECO_F32, ZECO_BF16 = 0, 1
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
-           "zeco_apply_init_state", "zeco_status_string", "zeco_version")
+           "zeco_apply_init_state", "zeco_hbm_copy", "zeco_status_string", "zeco_version")
 
 
 class GlaDesc(ctypes.Structure):
@@ -56,6 +56,8 @@ def lib():
         L.zeco_state_scan.restype = i32
         L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state.restype = i32
+        L.zeco_hbm_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.zeco_hbm_copy.restype = i32
         L.zeco_status_string.argtypes = [i32]
         L.zeco_status_string.restype = ctypes.c_char_p
         L.zeco_version.argtypes = []
@@ -166,6 +168,19 @@ def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segm
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_apply_init_state")
     return o
+
+
+def hbm_copy(dst, src):
+    """zeco_hbm_copy: plain device copy used for bandwidth / counter calibration."""
+    if not (dst.is_cuda and src.is_cuda and dst.is_contiguous() and src.is_contiguous()):
+        raise RuntimeError("hbm_copy needs contiguous GPU tensors")
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("size mismatch")
+    st = lib().zeco_hbm_copy(_ptr(dst), _ptr(src), nbytes, _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_hbm_copy")
+    return dst
 
 
 def segmented_fwd(q, k, v, g, P, scale=1.0, S0=None, K_blocks=16):

@@ -1,0 +1,55 @@
+"""Parity at the benchmark's full sizes and launch configuration, on sampled (segment, head)
+slices the oracle can compute one by one.  For a segment p >= 1 the oracle is warm-started
+W tokens before the segment: older history is attenuated by exp(sum of g over the window), and
+the test asserts from the actual gates that this factor is below 1e-30."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2507_01004_amd import synth, zeco
+from tests.gpu_util import TOL, host, log_err, rel_err_bh
+
+pytestmark = pytest.mark.gpu
+W = 8192
+
+
+def slice_oracle(inp, L, p, h, S_init_dev):
+    """Oracle output for segment p, head h (batch 0) of the unsegmented run, and the state
+    entering the segment."""
+    t0 = max(0, p * L - W) if p > 0 else 0
+    sl = slice(t0, (p + 1) * L)
+    q, k, v, g = (host(inp[n][:1, sl, h:h + 1]) for n in ("q", "k", "v", "g"))
+    if p > 0:
+        warm = g[0, :p * L - t0, 0].sum(axis=0)
+        assert t0 == 0 or warm.max() < np.log(1e-30), "warm-up window too short for these gates"
+    o, _ = oracle.gla_recurrent(q, k, v, g)
+    n_warm = p * L - t0
+    S_in = None
+    if n_warm:
+        _, S_in = oracle.gla_recurrent(q[:, :n_warm], k[:, :n_warm], v[:, :n_warm], g[:, :n_warm])
+    return o[:, n_warm:], S_in
+
+
+@pytest.mark.parametrize("name,samples", [
+    ("c2", [(0, 0), (0, 9), (0, 15)]),
+    ("c3", [(0, 3), (1, 0), (4, 7), (7, 15)]),
+])
+def test_fullsize_sampled_slices(name, samples):
+    inp, c = synth.config_inputs(name, device="cuda")
+    P, L, H = c["P"], c["L"], c["H"]
+    print("full-size", name, c, flush=True)
+    o, S_last, parts = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
+    torch.cuda.synchronize()
+    for (p, h) in samples:
+        print("  sample segment %d head %d" % (p, h), flush=True)
+        o_ref, S_in = slice_oracle(inp, L, p, h, parts["S_init"])
+        got = host(o[:1, p * L:(p + 1) * L, h:h + 1])
+        assert rel_err_bh(got, o_ref, (0, 2)) <= TOL[c["io"]]
+        # the head of the segment is where the incoming state matters most
+        assert rel_err_bh(got[:, :256], o_ref[:, :256], (0, 2)) <= TOL[c["io"]]
+        if S_in is not None:
+            assert rel_err_bh(host(parts["S_init"][p, :1, h:h + 1]), S_in, (0, 1)) <= TOL[c["io"]]
+        Gc = np.cumsum(host(inp["g"][:1, p * L:(p + 1) * L, h:h + 1]), axis=1)
+        assert log_err(host(parts["G_cum"][:1, p * L:(p + 1) * L, h:h + 1]), Gc) <= 1e-5
+        assert log_err(host(parts["G_tot"][p, :1, h:h + 1]), Gc[:, -1]) <= 1e-5

@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--k-blocks", type=int, default=16)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--layout", default="bthd", choices=["bthd", "bhtd"],
+                    help="memory order of q/k/v/g/o: token-major (default) or head-major")
     ap.add_argument("--calib-copy-mib", type=int, default=1024,
                     help="size of the plain copy timed beside the kernels (0 = skip)")
     args = ap.parse_args()
@@ -88,6 +90,8 @@ def main():
     inp, c = synth.config_inputs(args.workload, device="cuda:0", g=args.g_dtype)
     B, H, P, L, dk, dv = c["B"], c["H"], c["P"], c["L"], c["d_k"], c["d_v"]
     T = P * L
+    if args.layout == "bhtd":   # same values, each head's tokens contiguous in memory
+        inp = {n: t.transpose(1, 2).contiguous().transpose(1, 2) for n, t in inp.items()}
     q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
     o = torch.empty_like(v)
     S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device="cuda:0")
@@ -157,7 +161,7 @@ def main():
         "config": {"workload": "%s: B=%d H=%d P=%d segments x L=%d tokens, d_k=d_v=%d, C=%d, %s q/k/v/o, "
                                "%s log-decay; local fwd + segment-state scan + init-state correction"
                                % (args.workload, B, H, P, L, dk, c["C"], c["io"], args.g_dtype),
-                   "K_blocks": args.k_blocks},
+                   "K_blocks": args.k_blocks, "layout": args.layout},
         "roofline": {"kernel": "gla_chunk_bf16_kernel (zeco_gla_local_fwd)", "bound": "hbm",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4),

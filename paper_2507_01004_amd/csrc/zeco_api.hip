@@ -58,13 +58,14 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
     p.n_chunks = d->L / d->C;
-    p.n_slices = 1;
     p.scale = d->scale;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
+#ifdef ZECO_PHASE_TIMING
+    p.dbg = zeco::g_phase_dbg;
+#endif
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
-    p.n_slices = zeco::chunk_bf16_slices(d->B * d->P * d->H, d->d_v);
     return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, s));
 }
 
@@ -129,5 +130,9 @@ const char *zeco_status_string(int32_t status) {
 }
 
 int32_t zeco_version(void) { return 100; }
+
+#ifdef ZECO_PHASE_TIMING
+void zeco_debug_set_phase_buffer(unsigned long long *buf) { zeco::g_phase_dbg = buf; }
+#endif
 
 }  // extern "C"

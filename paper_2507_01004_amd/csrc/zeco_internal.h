@@ -11,11 +11,16 @@ struct ChunkParams {
     float *S_loc, *G_cum, *G_tot;
     int B, P, H, L;
     int n_chunks;              // L / 64
-    int n_slices;              // d_v slices per (b, p, h) stream (workgroups sharing q, k, g)
     float scale;
     long long sb, st, sh;      // q/k/g element strides
     long long vb, vt, vh;      // v/o element strides
+#ifdef ZECO_PHASE_TIMING
+    unsigned long long *dbg;   // development builds only: cycle stamps of workgroup 0
+#endif
 };
+#ifdef ZECO_PHASE_TIMING
+extern unsigned long long *g_phase_dbg;
+#endif
 
 struct ApplyParams {
     const void *q;
@@ -41,8 +46,5 @@ hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t 
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_scan(const ScanParams &p, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
-
-// d_v slices per stream the bf16 chunk kernel will use for this problem (1 or 2).
-int chunk_bf16_slices(int streams, int d_v);
 
 }  // namespace zeco

@@ -2,33 +2,38 @@
 // fp32 accumulation, fp32 state.  The throughput path.
 //
 // Work decomposition.  A (batch, segment, head) stream is a serial recurrence over N = L/64
-// chunks (Sec. 3.1).  One workgroup of NW = d_v/16 waves owns a stream; wave w owns columns
-// [16w, 16w+16) of the d_k x d_v state, which stays in MFMA accumulators for the whole segment.
-// With d_v = 128 that is 8 waves, two per SIMD, so that one wave's LDS / transcendental / memory
-// latencies are covered by the other's issue slots.
+// chunks (Sec. 3.1).  One workgroup owns a stream and is split into two kinds of waves that run
+// concurrently on the same SIMDs and use different execution resources:
+//   * 4 gate waves (VALU, transcendentals, global memory): for chunk n+1 they load q, k, g, v,
+//     compute the in-chunk cumulative log decay and write the scaled operand tiles to LDS;
+//   * d_v/32 MFMA waves (matrix cores, LDS reads): for chunk n they compute scores, outputs and the
+//     state update; wave j owns columns [32j, 32j+32) of the d_k x d_v state, which stays in MFMA
+//     accumulators for the whole segment.
+// The LDS tiles are double buffered and the two kinds meet at two workgroup barriers per chunk.
 //
 // Per chunk (chunk equations of Sec. 2.1, scores as in Alg. 1):
-//   gate pass   each thread owns 4 channels x TPT consecutive tokens: serial cumsum in registers,
-//               token groups stitched by lane shuffles inside a wave and through LDS across waves:
-//               cs = inclusive cumsum of g, Lambda = e^cs.
-//               writes  Qs = Q .* Lambda, Ks = K / Lambda  (token-major, bf16)
-//                       Kt = (K / Lambda)^T, Vt = V^T       (channel-major, bf16)
-//   scores      P^T = Ks Qs^T on the 10 lower-triangular 16x16 tiles, causal select, -> Ps (bf16)
-//   inter       O^T += S^T Qs^T   with S fed straight from the accumulators (see below)
-//   intra       O^T += Vt Ps^T    (causal k-range); O * scale stored to HBM
-//   state       S <- (gamma^T 1) .* (S + Kt Vt^T)
+//   gate, part 1   each thread owns 4 channels x TPT consecutive tokens: serial cumsum of g in
+//                  registers, token groups stitched by lane shuffles inside a wave and one LDS
+//                  exchange across the gate waves;  Vt = V^T -> LDS
+//   gate, part 2   cs = inclusive cumsum of g, Lambda = e^cs;  Qs = Q .* Lambda, Ks = K / Lambda
+//                  (token-major), Kt = (K / Lambda)^T (channel-major) -> LDS;  G_cum -> HBM
+//   MFMA, part 1   P^T = Ks Qs^T on the 10 lower-triangular 16x16 tiles, causal select -> Ps (bf16);
+//                  O^T  = S^T Qs^T   with S fed straight from the accumulators (see below)
+//   MFMA, part 2   O^T += Vt Ps^T (causal k-range), O * scale -> HBM;
+//                  S <- (gamma^T 1) .* (S + Kt Vt^T)
 // The last line is Eq. (3) with K .* Gamma = (gamma^T 1)-scaled K / Lambda (Gamma = gamma / Lambda),
 // so one scaled copy of K serves both the scores and the state update.
 //
-// Accumulator-as-operand.  Lane l of a 16x16 accumulator tile holds column l%16 and rows
-// 4*(l/16) .. +3.  The MFMA operand layout wants, from the same lane, row (column) l%16 and eight
-// k-slots.  Summation over k is order-free, so the eight state rows a lane owns in two adjacent
-// tiles are used as its eight k-slots, and Qs is stored in LDS with its channels permuted to
-// match (pos_of_channel); Ks uses the same permutation so the scores are unaffected.
+// Accumulator-as-operand.  Lane l of a 32x32 accumulator tile holds column l%32 and, with
+// kg = l/32, rows 8q + 4kg + m (q < 4, m < 4).  The MFMA operand layout wants, from the same lane,
+// row (column) l%32 and eight k-slots.  Summation over k is order-free, so the eight state rows a
+// lane owns in half a tile are used as its eight k-slots, and Qs is stored in LDS with its
+// channels permuted to match (pos_of_channel); Ks uses the same permutation, so the scores are
+// unaffected.
 //
-// Memory pipeline.  One register set holds the raw q, k, g, v of the current chunk; each piece
-// is reloaded with the next chunk's data right after its last use, so the global loads are spread
-// over the gate pass and stay in flight for a whole iteration.
+// Memory pipeline.  One register set holds the raw q, k, g, v of the chunk the gate waves work on;
+// each piece is reloaded with the following chunk's data right after its last use, so the global
+// loads are spread out and stay in flight for a whole iteration.
 #include "zeco_device.h"
 #include "zeco_internal.h"
 
@@ -45,57 +50,45 @@ unsigned long long *g_phase_dbg = nullptr;
 #endif
 
 template <int DK, int DV> struct B16Cfg {
-    static constexpr int NW = DV / 16;             // waves per workgroup, 16 state columns each
-    static constexpr int NT = 64 * NW;
-    static constexpr int NIT = DK / 16;            // state row tiles per wave
-    static constexpr int NKS_D = DK / 32;          // MFMA k-steps across channels
-    // gate pass thread mapping: 4 channels x TPT tokens per thread
+    static constexpr int NWM = DV / 32;            // MFMA waves, 32 state columns each
+    static constexpr int NWG = 4;                  // gate waves
+    static constexpr int NT = 64 * (NWM + NWG);
+    static constexpr int NIT = DK / 32;            // state row tiles per MFMA wave
+    // gate pass thread mapping over the 256 gate threads: 4 channels x TPT tokens per thread
     static constexpr int CQ = DK / 4;              // channel quads
     static constexpr int GW = 64 / CQ;             // token groups inside one wave (2 or 4)
-    static constexpr int TG = NT / CQ;             // token groups
-    static constexpr int TPT = 64 / TG;            // consecutive tokens per thread (8, 4 or 2)
+    static constexpr int TPT = 64 / (NWG * GW);    // consecutive tokens per thread (8 or 4)
     static constexpr int VQ = DV / 4;
-    static constexpr int TPTV = 64 / (NT / VQ);    // = 4
-    // LDS (bytes)
+    static constexpr int TPTV = 64 / (256 / VQ);   // 8 or 4
+    // LDS (bytes).  The scaled tiles are double buffered.
     static constexpr int QS = DK * 2 + 16;         // row stride of Qs, Ks
     static constexpr int TS = 64 * 2 + 16;         // row stride of Kt, Vt, Ps
-    static constexpr int kOffQ = 0;
+    static constexpr int kOffQ = 0;                // offsets inside one tile buffer
     static constexpr int kOffK = kOffQ + 64 * QS;
     static constexpr int kOffKT = kOffK + 64 * QS;
     static constexpr int kOffVT = kOffKT + DK * TS;
-    static constexpr int kOffP = kOffVT + DV * TS;
+    static constexpr int kTileBytes = kOffVT + DV * TS;
+    static constexpr int kOffP = 2 * kTileBytes;
     static constexpr int kOffTot = kOffP + 64 * TS;
-    static constexpr int kOffGam = kOffTot + NW * DK * 4;
-    static constexpr int kBytes = kOffGam + DK * 4;
+    static constexpr int kOffGam = kOffTot + NWG * DK * 4;
+    static constexpr int kBytes = kOffGam + 2 * DK * 4;
 
     // LDS position of channel i inside a Qs/Ks row (see "Accumulator-as-operand"): within each
-    // block of 32 channels, channel 16 q + 4 kg + m sits at 8 kg + 4 q + m.
+    // block of 16 channels, channel 8 q + 4 kg + m sits at 8 kg + 4 q + m.
     __device__ static __forceinline__ constexpr int pos_of_channel(int i) {
-        const int il = i % 32;
-        return (i - il) + 8 * ((il / 4) % 4) + 4 * (il / 16) + (il % 4);
+        const int il = i % 16;
+        return (i - il) + 8 * ((il / 4) % 2) + 4 * (il / 8) + (il % 4);
     }
 };
-
-__device__ __forceinline__ bf16x8 pack8(f32x4 a, f32x4 b) {
-    u32x4 w = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]),
-               pack_bf16(b[2], b[3])};
-    return __builtin_bit_cast(bf16x8, w);
-}
 
 // Four consecutive gate values of one token, as loaded and as floats.
 template <bool GBF16> struct GateVal;
 template <> struct GateVal<false> {
     typedef f32x4 raw_t;
-    __device__ static __forceinline__ raw_t load(const void *g, long long elem) {
-        return *reinterpret_cast<const f32x4 *>((const float *)g + elem);
-    }
     __device__ static __forceinline__ f32x4 get(raw_t r) { return r; }
 };
 template <> struct GateVal<true> {
     typedef u32x2 raw_t;
-    __device__ static __forceinline__ raw_t load(const void *g, long long elem) {
-        return *reinterpret_cast<const u32x2 *>((const uint16_t *)g + elem);
-    }
     __device__ static __forceinline__ f32x4 get(raw_t r) {
         return f32x4{bf16_lo(r[0]), bf16_hi(r[0]), bf16_lo(r[1]), bf16_hi(r[1])};
     }
@@ -115,12 +108,6 @@ template <> struct TokenRun<4> {
         *reinterpret_cast<u32x2 *>(dst) = u32x2{w[0], w[1]};
     }
 };
-template <> struct TokenRun<2> {
-    uint32_t w[1];
-    __device__ __forceinline__ void store(unsigned char *dst) const {
-        *reinterpret_cast<uint32_t *>(dst) = w[0];
-    }
-};
 
 // Low halves / high halves of two packed bf16 pairs: (x.lo, y.lo) and (x.hi, y.hi).
 __device__ __forceinline__ uint32_t pair_lo(uint32_t x, uint32_t y) {
@@ -130,94 +117,105 @@ __device__ __forceinline__ uint32_t pair_hi(uint32_t x, uint32_t y) {
     return __builtin_amdgcn_perm(y, x, 0x07060302u);
 }
 
-template <int DK, int DV, bool GBF16>
-__global__ __launch_bounds__(DV * 4) void gla_chunk_bf16_kernel(ChunkParams p) {
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
+    u32x4 w = {pack_bf16(a[base + 0], a[base + 1]), pack_bf16(a[base + 2], a[base + 3]),
+               pack_bf16(a[base + 4], a[base + 5]), pack_bf16(a[base + 6], a[base + 7])};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+// DV is the number of state columns this workgroup owns: d_v, or d_v / NS when NS sibling workgroups
+// share a stream (each recomputes the gate pass and takes its own slice of v, o and the state).
+template <int DK, int DV, int NS, bool GBF16>
+__global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParams p) {
     typedef B16Cfg<DK, DV> Cfg;
-    typedef Mma<16> M;
+    typedef Mma<32> M;
     typedef GateVal<GBF16> GV;
-    constexpr int QS = Cfg::QS, TS = Cfg::TS, NW = Cfg::NW, NT = Cfg::NT;
+    constexpr int QS = Cfg::QS, TS = Cfg::TS, NWM = Cfg::NWM, NT = Cfg::NT;
     constexpr int TPT = Cfg::TPT, TPTV = Cfg::TPTV, CQ = Cfg::CQ, GW = Cfg::GW;
+    constexpr int GB = GBF16 ? 2 : 4;   // bytes per gate element
     constexpr float kLog2e = 1.4426950408889634f;
     extern __shared__ __align__(16) unsigned char lds[];
-    unsigned char *Qs = lds + Cfg::kOffQ, *Ks = lds + Cfg::kOffK, *Kt = lds + Cfg::kOffKT;
-    unsigned char *Vt = lds + Cfg::kOffVT, *Ps = lds + Cfg::kOffP;
-    float *wtot = reinterpret_cast<float *>(lds + Cfg::kOffTot);   // [wave][channel] gate sums
-    float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // chunk decay gamma [channel]
+    unsigned char *Ps = lds + Cfg::kOffP;
+    float *wtot = reinterpret_cast<float *>(lds + Cfg::kOffTot);   // [gate wave][channel] gate sums
+    float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // [buffer][channel] chunk decay
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known uniform
-    const int l16 = lane & 15, kg = lane >> 4;                // MFMA lane coordinates
+    const int N = p.n_chunks;
 
-    const size_t sbh = blockIdx.x;                  // (seg * B + b) * H + h  (S_loc / G_tot order)
-    int sidx = blockIdx.x;
+    // Workgroup -> (stream, slice).  Workgroup ids are dealt round-robin to the 8 XCDs, so sibling
+    // slices of a stream take consecutive slots of one XCD and share its L2 for q, k, g.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    int sidx = (slot / NS) * 8 + xcd;
+    const int slice = slot % NS;
+    if (sidx >= p.B * p.P * p.H) return;
+    const size_t sbh = sidx;                        // (seg * B + b) * H + h  (S_loc / G_tot order)
     const int h = sidx % p.H;
     sidx /= p.H;
     const int b = sidx % p.B, seg = sidx / p.B;
     const long long tok0 = (long long)seg * p.L;
     const long long kbase = b * p.sb + tok0 * p.st + h * p.sh;
-    const long long vbase = b * p.vb + tok0 * p.vt + h * p.vh;
-    const uint16_t *qp = (const uint16_t *)p.q + kbase;
-    const uint16_t *kp = (const uint16_t *)p.k + kbase;
-    const uint16_t *vp = (const uint16_t *)p.v + vbase;
-    uint16_t *op = (uint16_t *)p.o + vbase;
-    const long long T = (long long)p.P * p.L;
-    float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
-    const long long gcs = (long long)p.H * DK;
-
-    // gate-pass coordinates: channel quad and token group (q, k, g), column quad and token group (v)
-    const int cq = lane % CQ, gl = lane / CQ, tq = w * GW + gl;
-    const int vq = tid % Cfg::VQ, tv = tid / Cfg::VQ;
-    const int qpos = Cfg::pos_of_channel(4 * cq);
-
-    f32x4 Sacc[Cfg::NIT];
-#pragma unroll
-    for (int it = 0; it < Cfg::NIT; ++it) Sacc[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const long long vbase = b * p.vb + tok0 * p.vt + h * p.vh + slice * DV;
+    const unsigned st = (unsigned)p.st, vt = (unsigned)p.vt;
 
     // Score tiles above the diagonal are never computed: zero them once.
     for (int e = tid; e < 64 * TS / 16; e += NT)
         *reinterpret_cast<u32x4 *>(Ps + e * 16) = u32x4{0u, 0u, 0u, 0u};
 
-    struct Raw {
-        u32x2 q[TPT], k[TPT];
-        typename GV::raw_t g[TPT];
-        u32x2 v[TPTV];
-    };
-    auto q_off = [&](int n, int u) { return ((long long)n * 64 + tq * TPT + u) * p.st + 4 * cq; };
-    auto v_off = [&](int n, int u) { return ((long long)n * 64 + tv * TPTV + u) * p.vt + 4 * vq; };
-    Raw r;
+    if (w >= NWM) {
+        // ================================ gate waves ===========================================
+        const int gw = w - NWM, gtid = tid - 64 * NWM;
+        // Uniform byte pointers to the stream's first token; per-thread 32-bit offsets on top.
+        const unsigned char *qb = (const unsigned char *)p.q + kbase * 2;
+        const unsigned char *kb = (const unsigned char *)p.k + kbase * 2;
+        const unsigned char *gb = (const unsigned char *)p.g + kbase * GB;
+        const unsigned char *vb = (const unsigned char *)p.v + vbase * 2;
+        const long long T = (long long)p.P * p.L;
+        unsigned char *Gb = (unsigned char *)(p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK);
+        const unsigned gcs = (unsigned)(p.H * DK);
+
+        // channel quad and token group (q, k, g); column quad and token group (v)
+        const int cq = lane % CQ, gl = lane / CQ, tq = gw * GW + gl;
+        const int vq = gtid % Cfg::VQ, tv = gtid / Cfg::VQ;
+        const int qpos = Cfg::pos_of_channel(4 * cq);
+        const unsigned q_e0 = (unsigned)(tq * TPT) * st + 4 * cq;   // element offsets inside a chunk
+        const unsigned v_e0 = (unsigned)(tv * TPTV) * vt + 4 * vq;
+        const unsigned g_e0 = (unsigned)(tq * TPT) * gcs + 4 * cq;  // G_cum is contiguous [.., H, d_k]
+
+        // Raw q, k, g, v of the chunk worked on next; each piece is reloaded with the following
+        // chunk's data right after its last use (clamped to the last chunk).
+        u32x2 rq[TPT], rk[TPT], rv[TPTV];
+        typename GV::raw_t rg[TPT];
 #pragma unroll
-    for (int u = 0; u < TPT; ++u) {
-        r.q[u] = *reinterpret_cast<const u32x2 *>(qp + q_off(0, u));
-        r.k[u] = *reinterpret_cast<const u32x2 *>(kp + q_off(0, u));
-        r.g[u] = GV::load(p.g, kbase + q_off(0, u));
-    }
+        for (int u = 0; u < TPT; ++u) {
+            rq[u] = *reinterpret_cast<const u32x2 *>(qb + (q_e0 + u * st) * 2);
+            rk[u] = *reinterpret_cast<const u32x2 *>(kb + (q_e0 + u * st) * 2);
+            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (q_e0 + u * st) * GB);
+        }
 #pragma unroll
-    for (int u = 0; u < TPTV; ++u) r.v[u] = *reinterpret_cast<const u32x2 *>(vp + v_off(0, u));
+        for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vb + (v_e0 + u * vt) * 2);
 
-    // Log decay of the previous chunks for this thread's 4 channels, as an unevaluated sum hi + lo.
-    f32x4 seg_hi = {0.f, 0.f, 0.f, 0.f}, seg_lo = {0.f, 0.f, 0.f, 0.f};
+        // Log decay of the previous chunks for this thread's 4 channels, as an unevaluated sum.
+        f32x4 seg_hi = {0.f, 0.f, 0.f, 0.f}, seg_lo = {0.f, 0.f, 0.f, 0.f};
+        f32x4 cs[TPT];                          // in-thread inclusive cumsum of g (part 1 -> part 2)
+        f32x4 excl = {0.f, 0.f, 0.f, 0.f};      // sum over the wave's earlier token groups
 
-    for (int n = 0; n < p.n_chunks; ++n) {
-        const long long t0 = (long long)n * 64;
-        // Chunk whose data is fetched during this iteration; the last iteration refetches its own.
-        const int nn = (n + 1 < p.n_chunks) ? n + 1 : n;
-        ZPT(0);
-
-        // ---- gate pass, part 1: per-thread cumulative sums, V^T ---------------------------------
-        f32x4 cs[TPT];
-        f32x4 excl = {0.f, 0.f, 0.f, 0.f};   // sum over the wave's earlier token groups
-        {
+        // part 1 of chunk m: per-thread cumulative sums, V^T -> tile buffer
+        auto gate_a = [&](int m, unsigned char *tile) __attribute__((always_inline)) {
+            unsigned char *Vt = tile + Cfg::kOffVT;
+            const int nn = (m + 1 < N) ? m + 1 : N - 1;
+            const unsigned char *gn = gb + (long long)nn * 64 * st * GB;   // uniform
+            const unsigned char *vn = vb + (long long)nn * 64 * vt * 2;
             f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
-                const f32x4 gv = GV::get(r.g[u]);
-                r.g[u] = GV::load(p.g, kbase + q_off(nn, u));
+                const f32x4 gv = GV::get(rg[u]);
+                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gn + (q_e0 + u * st) * GB);
 #pragma unroll
                 for (int a = 0; a < 4; ++a) run[a] += gv[a];
                 cs[u] = run;
             }
-            // inclusive scan of the group sums over the GW token groups of this wave
-            f32x4 inc = run;
+            f32x4 inc = run;   // inclusive scan of the group sums over the wave's GW token groups
 #pragma unroll
             for (int d = 1; d < GW; d <<= 1) {
 #pragma unroll
@@ -228,40 +226,41 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_bf16_kernel(ChunkParams p) {
             }
 #pragma unroll
             for (int a = 0; a < 4; ++a) excl[a] = inc[a] - run[a];
-            if (gl == GW - 1) *reinterpret_cast<f32x4 *>(wtot + w * DK + 4 * cq) = inc;
-        }
-        ZPT(1);
-        {
+            if (gl == GW - 1) *reinterpret_cast<f32x4 *>(wtot + gw * DK + 4 * cq) = inc;
+
             TokenRun<TPTV> ch[4];
 #pragma unroll
-            for (int m = 0; m < TPTV / 2; ++m) {
-                const u32x2 x = r.v[2 * m], y = r.v[2 * m + 1];
-                ch[0].w[m] = pair_lo(x[0], y[0]);
-                ch[1].w[m] = pair_hi(x[0], y[0]);
-                ch[2].w[m] = pair_lo(x[1], y[1]);
-                ch[3].w[m] = pair_hi(x[1], y[1]);
+            for (int mm = 0; mm < TPTV / 2; ++mm) {
+                const u32x2 x = rv[2 * mm], y = rv[2 * mm + 1];
+                ch[0].w[mm] = pair_lo(x[0], y[0]);
+                ch[1].w[mm] = pair_hi(x[0], y[0]);
+                ch[2].w[mm] = pair_lo(x[1], y[1]);
+                ch[3].w[mm] = pair_hi(x[1], y[1]);
             }
 #pragma unroll
-            for (int u = 0; u < TPTV; ++u) r.v[u] = *reinterpret_cast<const u32x2 *>(vp + v_off(nn, u));
+            for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vn + (v_e0 + u * vt) * 2);
 #pragma unroll
             for (int a = 0; a < 4; ++a) ch[a].store(Vt + (4 * vq + a) * TS + tv * TPTV * 2);
-        }
-        ZPT(2);
-        __syncthreads();
-        ZPT(3);
+        };
 
-        // ---- gate pass, part 2: stitch waves, scale q and k -------------------------------------
-        f32x4 pre = excl, total = {0.f, 0.f, 0.f, 0.f};
+        // part 2 of chunk m: stitch waves, scale q and k -> tile buffer, G_cum -> HBM
+        auto gate_b = [&](int m, unsigned char *tile, float *gam_m) __attribute__((always_inline)) {
+            unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK, *Kt = tile + Cfg::kOffKT;
+            const int nn = (m + 1 < N) ? m + 1 : N - 1;
+            const unsigned char *qn = qb + (long long)nn * 64 * st * 2;   // uniform
+            const unsigned char *kn = kb + (long long)nn * 64 * st * 2;
+            unsigned char *Gm = Gb + (long long)m * 64 * gcs * 4;
+            f32x4 pre = excl, total = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < NW; ++u) {
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(wtot + u * DK + 4 * cq);
+            for (int u = 0; u < Cfg::NWG; ++u) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(wtot + u * DK + 4 * cq);
+                const float sel = (u < gw) ? 1.f : 0.f;   // wave-uniform
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                if (u < w) pre[a] += x[a];
-                total[a] += x[a];
+                for (int a = 0; a < 4; ++a) {
+                    pre[a] = __builtin_fmaf(sel, x[a], pre[a]);
+                    total[a] += x[a];
+                }
             }
-        }
-        {
             // c = pre + cs is the in-chunk cumulative log decay; exp(c) = exp2(cs*log2e + pre*log2e);
             // G_cum = (segment prefix + pre) + cs with the prefix folded once per channel.
             f32x4 pre2, gbase;
@@ -283,9 +282,9 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_bf16_kernel(ChunkParams p) {
                     ilam[a] = __builtin_amdgcn_exp2f(-y);
                     gout[a] = gbase[a] + cs[u][a];
                 }
-                const u32x2 qw = r.q[u], kw = r.k[u];
-                r.q[u] = *reinterpret_cast<const u32x2 *>(qp + q_off(nn, u));
-                r.k[u] = *reinterpret_cast<const u32x2 *>(kp + q_off(nn, u));
+                const u32x2 qw = rq[u], kw = rk[u];
+                rq[u] = *reinterpret_cast<const u32x2 *>(qn + (q_e0 + u * st) * 2);
+                rk[u] = *reinterpret_cast<const u32x2 *>(kn + (q_e0 + u * st) * 2);
                 *reinterpret_cast<u32x2 *>(Qs + t * QS + qpos * 2) =
                     u32x2{pack_bf16(bf16_lo(qw[0]) * lam[0], bf16_hi(qw[0]) * lam[1]),
                           pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};
@@ -299,136 +298,194 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_bf16_kernel(ChunkParams p) {
                     kt[3].w[u / 2] = pair_hi(kprev[1], kq[1]);
                 }
                 kprev = kq;
-                *reinterpret_cast<f32x4 *>(Gc + (t0 + t) * gcs + 4 * cq) = gout;
+                if (u % NS == slice)   // sibling slices share the G_cum rows between them
+                    *reinterpret_cast<f32x4 *>(Gm + (g_e0 + u * gcs) * 4) = gout;
             }
 #pragma unroll
             for (int a = 0; a < 4; ++a) kt[a].store(Kt + (4 * cq + a) * TS + tq * TPT * 2);
-        }
-        if (tq == 0) {
-            f32x4 gm;
+            if (tq == 0) {
+                f32x4 gm;
 #pragma unroll
-            for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
-            *reinterpret_cast<f32x4 *>(gam + 4 * cq) = gm;
-        }
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {   // (hi, lo) += total, error-free transformation
-            const float x = total[a] + seg_lo[a];
-            const float s = seg_hi[a] + x;
-            const float bb = s - seg_hi[a];
-            seg_lo[a] = (seg_hi[a] - (s - bb)) + (x - bb);
-            seg_hi[a] = s;
-        }
-        ZPT(4);
-        __syncthreads();
-        ZPT(5);
-
-        // ---- scores: P^T tiles (ts <= tt), 16x16x32; all operand reads of a tile issued up front ---
-#pragma unroll
-        for (int i = 0; i < (10 + NW - 1) / NW; ++i) {
-            const int idx = w + NW * i;   // wave-uniform
-            if (idx < 10) {
-                const int tt = (idx >= 6) ? 3 : (idx >= 3) ? 2 : (idx >= 1) ? 1 : 0;
-                const int ts = idx - tt * (tt + 1) / 2;
-                const unsigned char *ka = Ks + (16 * ts + l16) * QS + 16 * kg;
-                const unsigned char *qb = Qs + (16 * tt + l16) * QS + 16 * kg;
-                bf16x8 fa[DK / 32], fb[DK / 32];
-#pragma unroll
-                for (int ks = 0; ks < DK / 32; ++ks) {
-                    fa[ks] = lds_frag(ka, 64 * ks);
-                    fb[ks] = lds_frag(qb, 64 * ks);
-                }
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int ks = 0; ks < DK / 32; ++ks) acc = M::run(fa[ks], fb[ks], acc);
-                if (ts == tt) {
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        if (4 * kg + rr > l16) acc[rr] = 0.f;
-                }
-                *reinterpret_cast<u32x2 *>(Ps + (16 * tt + l16) * TS + (16 * ts + 4 * kg) * 2) =
-                    u32x2{pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3])};
+                for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
+                *reinterpret_cast<f32x4 *>(gam_m + 4 * cq) = gm;
             }
-        }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {   // (hi, lo) += total, error-free transformation
+                const float x = total[a] + seg_lo[a];
+                const float s = seg_hi[a] + x;
+                const float bb = s - seg_hi[a];
+                seg_lo[a] = (seg_hi[a] - (s - bb)) + (x - bb);
+                seg_hi[a] = s;
+            }
+            if (m == N - 1 && tq == 0 && slice == 0) {   // segment total: log of the cumulative decay gamma~_[N]
+                f32x4 gt;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) gt[a] = seg_hi[a] + seg_lo[a];
+                *reinterpret_cast<f32x4 *>(p.G_tot + sbh * DK + 4 * cq) = gt;
+            }
+        };
 
-        ZPT(6);
-        // ---- inter: O^T += S^T Qs^T --------------------------------------------------------------
-        f32x4 Oacc[4];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) Oacc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < Cfg::NKS_D; ++ks) {
-            const bf16x8 sf = pack8(Sacc[2 * ks], Sacc[2 * ks + 1]);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-                Oacc[mt] = M::run(sf, lds_frag(Qs, (mt * 16 + l16) * QS + (ks * 32 + 8 * kg) * 2), Oacc[mt]);
-        }
-        ZPT(7);
+        gate_a(0, lds);
         __syncthreads();
-        ZPT(8);
-
-        // ---- intra: O^T += Vt Ps^T, causal k-range; store O ---------------------------------------
-        bf16x8 vf[2];
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) vf[ks] = lds_frag(Vt, (w * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-#pragma unroll
-            for (int ks = 0; ks <= mt / 2; ++ks)   // tokens s < 16 (mt + 1) only
-                Oacc[mt] = M::run(vf[ks], lds_frag(Ps, (mt * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2), Oacc[mt]);
-            uint16_t *orow = op + (t0 + mt * 16 + l16) * p.vt + w * 16 + 4 * kg;
-            *reinterpret_cast<u32x2 *>(orow) =
-                u32x2{pack_bf16(Oacc[mt][0] * p.scale, Oacc[mt][1] * p.scale),
-                      pack_bf16(Oacc[mt][2] * p.scale, Oacc[mt][3] * p.scale)};
-        }
-
-        ZPT(9);
-        // ---- state: S <- gamma .* (S + Kt Vt^T) ----------------------------------------------------
-#pragma unroll
-        for (int it = 0; it < Cfg::NIT; ++it) {
-            f32x4 acc = Sacc[it];
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                acc = M::run(lds_frag(Kt, (it * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2), vf[ks], acc);
-            const f32x4 gm = *reinterpret_cast<const f32x4 *>(gam + it * 16 + 4 * kg);
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) acc[rr] *= gm[rr];
-            Sacc[it] = acc;
-        }
-        ZPT(10);
+        gate_b(0, lds, gam);
         __syncthreads();
-        ZPT(11);
-    }
+        // Branch-free loop body (a conditional around the passes would force the reloaded registers
+        // through merge copies and with them a wait for every load in flight).
+        for (int n = 0; n + 1 < N; ++n) {
+            unsigned char *nxt = lds + ((n + 1) & 1) * Cfg::kTileBytes;
+            ZPT(0);
+            gate_a(n + 1, nxt);
+            ZPT(2);
+            __syncthreads();   // Ps of chunk n and the gate sums of chunk n+1 are visible
+            ZPT(3);
+            gate_b(n + 1, nxt, gam + ((n + 1) & 1) * DK);
+            ZPT(5);
+            __syncthreads();   // tiles of chunk n+1 complete; buffer of chunk n free
+            ZPT(6);
+        }
+        __syncthreads();   // last chunk: nothing left to produce, keep in step with the MFMA waves
+        __syncthreads();
+    } else {
+        // ================================ MFMA waves ===========================================
+        const int lt = lane & 31, kg = lane >> 5;       // 32x32x16 lane coordinates
+        const int l16 = lane & 15, kg16 = lane >> 4;    // 16x16x32 lane coordinates (score tiles)
+        unsigned char *ob = (unsigned char *)p.o + vbase * 2;
+        const unsigned o_e0 = (unsigned)lt * vt + w * 32 + 4 * kg;   // O^T element of this lane
 
-    float *Sl = p.S_loc + sbh * DK * DV + w * 16 + l16;
+        f32x16 Sacc[Cfg::NIT], Oacc[2];
 #pragma unroll
-    for (int it = 0; it < Cfg::NIT; ++it)
+        for (int it = 0; it < Cfg::NIT; ++it)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) Sl[(size_t)(it * 16 + 4 * kg + rr) * DV] = Sacc[it][rr];
-    if (tq == 0) {
-        f32x4 gt;
+            for (int rr = 0; rr < 16; ++rr) Sacc[it][rr] = 0.f;
+
+        // part 1: scores -> Ps, inter-chunk product -> Oacc
+        auto mfma_a = [&](const unsigned char *tile) __attribute__((always_inline)) {
+            const unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK;
+            // P^T tiles (ts <= tt), 16x16x32; all operand reads of a tile are issued up front
 #pragma unroll
-        for (int a = 0; a < 4; ++a) gt[a] = seg_hi[a] + seg_lo[a];
-        *reinterpret_cast<f32x4 *>(p.G_tot + sbh * DK + 4 * cq) = gt;
+            for (int i = 0; i < (10 + NWM - 1) / NWM; ++i) {
+                const int idx = w + NWM * i;   // wave-uniform
+                if (idx < 10) {
+                    const int tt = (idx >= 6) ? 3 : (idx >= 3) ? 2 : (idx >= 1) ? 1 : 0;
+                    const int ts = idx - tt * (tt + 1) / 2;
+                    const unsigned char *ka = Ks + (16 * ts + l16) * QS + 16 * kg16;
+                    const unsigned char *qf = Qs + (16 * tt + l16) * QS + 16 * kg16;
+                    bf16x8 fa[DK / 32], fb[DK / 32];
+#pragma unroll
+                    for (int ks = 0; ks < DK / 32; ++ks) {
+                        fa[ks] = lds_frag(ka, 64 * ks);
+                        fb[ks] = lds_frag(qf, 64 * ks);
+                    }
+                    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < DK / 32; ++ks) acc = Mma<16>::run(fa[ks], fb[ks], acc);
+                    if (ts == tt) {
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr)
+                            if (4 * kg16 + rr > l16) acc[rr] = 0.f;
+                    }
+                    *reinterpret_cast<u32x2 *>(Ps + (16 * tt + l16) * TS + (16 * ts + 4 * kg16) * 2) =
+                        u32x2{pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3])};
+                }
+            }
+            // O^T = S^T Qs^T
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) Oacc[mt][rr] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < DK / 16; ++ks) {
+                const bf16x8 sf = pack8(Sacc[ks / 2], 8 * (ks % 2));
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+                    Oacc[mt] = M::run(sf, lds_frag(Qs, (mt * 32 + lt) * QS + (ks * 16 + 8 * kg) * 2), Oacc[mt]);
+            }
+        };
+
+        // part 2 of chunk n: intra-chunk output, O store, state update
+        auto mfma_b = [&](int n, const unsigned char *tile, const float *gam_n) __attribute__((always_inline)) {
+            const unsigned char *Kt = tile + Cfg::kOffKT, *Vt = tile + Cfg::kOffVT;
+            unsigned char *on = ob + (long long)n * 64 * vt * 2;   // uniform
+            bf16x8 vf[4];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) vf[ks] = lds_frag(Vt, (w * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2);
+            // O^T += Vt Ps^T over the causal k-range (tokens s < 32 (mt + 1))
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+                for (int ks = 0; ks < 2 * (mt + 1); ++ks)
+                    Oacc[mt] = M::run(vf[ks], lds_frag(Ps, (mt * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), Oacc[mt]);
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+                    *reinterpret_cast<u32x2 *>(on + (o_e0 + mt * 32 * vt + 8 * qd) * 2) =
+                        u32x2{pack_bf16(Oacc[mt][4 * qd] * p.scale, Oacc[mt][4 * qd + 1] * p.scale),
+                              pack_bf16(Oacc[mt][4 * qd + 2] * p.scale, Oacc[mt][4 * qd + 3] * p.scale)};
+            }
+            // S <- gamma .* (S + Kt Vt^T)
+#pragma unroll
+            for (int it = 0; it < Cfg::NIT; ++it) {
+                f32x16 acc = Sacc[it];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+                    acc = M::run(lds_frag(Kt, (it * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), vf[ks], acc);
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    const f32x4 gm = *reinterpret_cast<const f32x4 *>(gam_n + it * 32 + 8 * qd + 4 * kg);
+#pragma unroll
+                    for (int mm = 0; mm < 4; ++mm) acc[4 * qd + mm] *= gm[mm];
+                }
+                Sacc[it] = acc;
+            }
+        };
+
+        __syncthreads();
+        __syncthreads();
+        for (int n = 0; n < N; ++n) {
+            const unsigned char *cur = lds + (n & 1) * Cfg::kTileBytes;
+            ZPT(0);
+            mfma_a(cur);
+            ZPT(2);
+            __syncthreads();
+            ZPT(3);
+            mfma_b(n, cur, gam + (n & 1) * DK);
+            ZPT(5);
+            __syncthreads();
+            ZPT(6);
+        }
+
+        float *Sl = p.S_loc + sbh * DK * (DV * NS) + slice * DV + w * 32 + lt;
+#pragma unroll
+        for (int it = 0; it < Cfg::NIT; ++it)
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr)
+                Sl[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] = Sacc[it][rr];
     }
 }
 
-template <int DK, int DV, bool GBF16>
+template <int DK, int DV, int NS, bool GBF16>
 static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     typedef B16Cfg<DK, DV> Cfg;
-    auto kern = gla_chunk_bf16_kernel<DK, DV, GBF16>;
+    auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GBF16>;
     hipError_t e = hipFuncSetAttribute((const void *)kern,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(p.B * p.P * p.H), dim3(Cfg::NT), Cfg::kBytes, s, p);
+    const int streams = p.B * p.P * p.H;
+    const int grid = ((streams + 7) / 8) * 8 * NS;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(Cfg::NT), Cfg::kBytes, s, p);
     return hipGetLastError();
 }
 
 template <bool GBF16>
 static hipError_t dispatch_b16(const ChunkParams &p, int d_k, int d_v, hipStream_t s) {
-    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, GBF16>(p, s);
-    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, GBF16>(p, s);
-    if (d_k == 64 && d_v == 128) return launch_b16<64, 128, GBF16>(p, s);
-    if (d_k == 128 && d_v == 128) return launch_b16<128, 128, GBF16>(p, s);
+    // With fewer streams than compute units, two sibling workgroups split d_v = 128 so that every
+    // compute unit streams memory; the gate pass is then computed twice.
+    const bool split = d_v == 128 && p.B * p.P * p.H < 256;
+    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, 1, GBF16>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, 1, GBF16>(p, s);
+    if (d_k == 64 && d_v == 128)
+        return split ? launch_b16<64, 64, 2, GBF16>(p, s) : launch_b16<64, 128, 1, GBF16>(p, s);
+    if (d_k == 128 && d_v == 128)
+        return split ? launch_b16<128, 64, 2, GBF16>(p, s) : launch_b16<128, 128, 1, GBF16>(p, s);
     return hipErrorInvalidValue;
 }
 

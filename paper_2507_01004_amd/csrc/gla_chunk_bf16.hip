@@ -108,6 +108,12 @@ template <> struct TokenRun<4> {
         *reinterpret_cast<u32x2 *>(dst) = u32x2{w[0], w[1]};
     }
 };
+template <> struct TokenRun<2> {
+    uint32_t w[1];
+    __device__ __forceinline__ void store(unsigned char *dst) const {
+        *reinterpret_cast<uint32_t *>(dst) = w[0];
+    }
+};
 
 // Low halves / high halves of two packed bf16 pairs: (x.lo, y.lo) and (x.hi, y.hi).
 __device__ __forceinline__ uint32_t pair_lo(uint32_t x, uint32_t y) {
@@ -178,9 +184,12 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         const int cq = lane % CQ, gl = lane / CQ, tq = gw * GW + gl;
         const int vq = gtid % Cfg::VQ, tv = gtid / Cfg::VQ;
         const int qpos = Cfg::pos_of_channel(4 * cq);
-        const unsigned q_e0 = (unsigned)(tq * TPT) * st + 4 * cq;   // element offsets inside a chunk
-        const unsigned v_e0 = (unsigned)(tv * TPTV) * vt + 4 * vq;
-        const unsigned g_e0 = (unsigned)(tq * TPT) * gcs + 4 * cq;  // G_cum is contiguous [.., H, d_k]
+        // Per-thread byte offsets of its first token inside a chunk; token u and the chunk are added
+        // to the uniform base pointer, so one offset register serves every access of a tensor.
+        const unsigned q_b0 = ((unsigned)(tq * TPT) * st + 4 * cq) * 2;
+        const unsigned g_in_b0 = ((unsigned)(tq * TPT) * st + 4 * cq) * GB;
+        const unsigned v_b0 = ((unsigned)(tv * TPTV) * vt + 4 * vq) * 2;
+        const unsigned g_b0 = ((unsigned)(tq * TPT) * gcs + 4 * cq) * 4;   // G_cum: contiguous [.., H, d_k]
 
         // Raw q, k, g, v of the chunk worked on next; each piece is reloaded with the following
         // chunk's data right after its last use (clamped to the last chunk).
@@ -188,29 +197,27 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         typename GV::raw_t rg[TPT];
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
-            rq[u] = *reinterpret_cast<const u32x2 *>(qb + (q_e0 + u * st) * 2);
-            rk[u] = *reinterpret_cast<const u32x2 *>(kb + (q_e0 + u * st) * 2);
-            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (q_e0 + u * st) * GB);
+            rq[u] = *reinterpret_cast<const u32x2 *>(qb + (size_t)(u * st) * 2 + q_b0);
+            rk[u] = *reinterpret_cast<const u32x2 *>(kb + (size_t)(u * st) * 2 + q_b0);
+            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (size_t)(u * st) * GB + g_in_b0);
         }
 #pragma unroll
-        for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vb + (v_e0 + u * vt) * 2);
+        for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vb + (size_t)(u * vt) * 2 + v_b0);
 
         // Log decay of the previous chunks for this thread's 4 channels, as an unevaluated sum.
         f32x4 seg_hi = {0.f, 0.f, 0.f, 0.f}, seg_lo = {0.f, 0.f, 0.f, 0.f};
         f32x4 cs[TPT];                          // in-thread inclusive cumsum of g (part 1 -> part 2)
         f32x4 excl = {0.f, 0.f, 0.f, 0.f};      // sum over the wave's earlier token groups
 
-        // part 1 of chunk m: per-thread cumulative sums, V^T -> tile buffer
-        auto gate_a = [&](int m, unsigned char *tile) __attribute__((always_inline)) {
-            unsigned char *Vt = tile + Cfg::kOffVT;
+        // part 1 of chunk m: per-thread cumulative sums and gate sums
+        auto gate_a = [&](int m) __attribute__((always_inline)) {
             const int nn = (m + 1 < N) ? m + 1 : N - 1;
             const unsigned char *gn = gb + (long long)nn * 64 * st * GB;   // uniform
-            const unsigned char *vn = vb + (long long)nn * 64 * vt * 2;
             f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
                 const f32x4 gv = GV::get(rg[u]);
-                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gn + (q_e0 + u * st) * GB);
+                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gn + (size_t)(u * st) * GB + g_in_b0);
 #pragma unroll
                 for (int a = 0; a < 4; ++a) run[a] += gv[a];
                 cs[u] = run;
@@ -227,7 +234,11 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
 #pragma unroll
             for (int a = 0; a < 4; ++a) excl[a] = inc[a] - run[a];
             if (gl == GW - 1) *reinterpret_cast<f32x4 *>(wtot + gw * DK + 4 * cq) = inc;
-
+        };
+        // V^T of chunk m -> tile buffer
+        auto vt_store = [&](int m, unsigned char *tile) __attribute__((always_inline)) {
+            const int nn = (m + 1 < N) ? m + 1 : N - 1;
+            const unsigned char *vn = vb + (long long)nn * 64 * vt * 2;   // uniform
             TokenRun<TPTV> ch[4];
 #pragma unroll
             for (int mm = 0; mm < TPTV / 2; ++mm) {
@@ -238,19 +249,17 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                 ch[3].w[mm] = pair_hi(x[1], y[1]);
             }
 #pragma unroll
-            for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vn + (v_e0 + u * vt) * 2);
+            for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vn + (size_t)(u * vt) * 2 + v_b0);
 #pragma unroll
-            for (int a = 0; a < 4; ++a) ch[a].store(Vt + (4 * vq + a) * TS + tv * TPTV * 2);
+            for (int a = 0; a < 4; ++a) ch[a].store(tile + Cfg::kOffVT + (4 * vq + a) * TS + tv * TPTV * 2);
         };
 
-        // part 2 of chunk m: stitch waves, scale q and k -> tile buffer, G_cum -> HBM
-        auto gate_b = [&](int m, unsigned char *tile, float *gam_m) __attribute__((always_inline)) {
-            unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK, *Kt = tile + Cfg::kOffKT;
-            const int nn = (m + 1 < N) ? m + 1 : N - 1;
-            const unsigned char *qn = qb + (long long)nn * 64 * st * 2;   // uniform
-            const unsigned char *kn = kb + (long long)nn * 64 * st * 2;
-            unsigned char *Gm = Gb + (long long)m * 64 * gcs * 4;
-            f32x4 pre = excl, total = {0.f, 0.f, 0.f, 0.f};
+        // part 2 of chunk m: stitch waves (setup), scale q and k -> tile buffer and G_cum -> HBM in two
+        // token halves, then gamma and the segment prefix (finish)
+        f32x4 pre2, gbase, total;
+        auto gate_b_setup = [&]() __attribute__((always_inline)) {
+            f32x4 pre = excl;
+            total = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < Cfg::NWG; ++u) {
                 const f32x4 x = *reinterpret_cast<const f32x4 *>(wtot + u * DK + 4 * cq);
@@ -263,16 +272,24 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
             }
             // c = pre + cs is the in-chunk cumulative log decay; exp(c) = exp2(cs*log2e + pre*log2e);
             // G_cum = (segment prefix + pre) + cs with the prefix folded once per channel.
-            f32x4 pre2, gbase;
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
                 pre2[a] = pre[a] * kLog2e;
                 gbase[a] = seg_hi[a] + (pre[a] + seg_lo[a]);
             }
-            TokenRun<TPT> kt[4];
+        };
+        auto gate_b_half = [&](int m, int half, unsigned char *tile) __attribute__((always_inline)) {
+            constexpr int HT = TPT / 2;
+            unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK, *Kt = tile + Cfg::kOffKT;
+            const int nn = (m + 1 < N) ? m + 1 : N - 1;
+            const unsigned char *qn = qb + (long long)nn * 64 * st * 2;   // uniform
+            const unsigned char *kn = kb + (long long)nn * 64 * st * 2;
+            unsigned char *Gm = Gb + (long long)m * 64 * gcs * 4;
+            TokenRun<HT> kt[4];
             u32x2 kprev = {0u, 0u};
 #pragma unroll
-            for (int u = 0; u < TPT; ++u) {
+            for (int uu = 0; uu < HT; ++uu) {
+                const int u = half * HT + uu;
                 const int t = tq * TPT + u;
                 f32x4 lam, ilam, gout;
 #pragma unroll
@@ -283,26 +300,28 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                     gout[a] = gbase[a] + cs[u][a];
                 }
                 const u32x2 qw = rq[u], kw = rk[u];
-                rq[u] = *reinterpret_cast<const u32x2 *>(qn + (q_e0 + u * st) * 2);
-                rk[u] = *reinterpret_cast<const u32x2 *>(kn + (q_e0 + u * st) * 2);
+                rq[u] = *reinterpret_cast<const u32x2 *>(qn + (size_t)(u * st) * 2 + q_b0);
+                rk[u] = *reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0);
                 *reinterpret_cast<u32x2 *>(Qs + t * QS + qpos * 2) =
                     u32x2{pack_bf16(bf16_lo(qw[0]) * lam[0], bf16_hi(qw[0]) * lam[1]),
                           pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};
                 const u32x2 kq = {pack_bf16(bf16_lo(kw[0]) * ilam[0], bf16_hi(kw[0]) * ilam[1]),
                                   pack_bf16(bf16_lo(kw[1]) * ilam[2], bf16_hi(kw[1]) * ilam[3])};
                 *reinterpret_cast<u32x2 *>(Ks + t * QS + qpos * 2) = kq;
-                if (u % 2 == 1) {   // transpose: tokens (u-1, u) of each channel share a word
-                    kt[0].w[u / 2] = pair_lo(kprev[0], kq[0]);
-                    kt[1].w[u / 2] = pair_hi(kprev[0], kq[0]);
-                    kt[2].w[u / 2] = pair_lo(kprev[1], kq[1]);
-                    kt[3].w[u / 2] = pair_hi(kprev[1], kq[1]);
+                if (uu % 2 == 1) {   // transpose: tokens (u-1, u) of each channel share a word
+                    kt[0].w[uu / 2] = pair_lo(kprev[0], kq[0]);
+                    kt[1].w[uu / 2] = pair_hi(kprev[0], kq[0]);
+                    kt[2].w[uu / 2] = pair_lo(kprev[1], kq[1]);
+                    kt[3].w[uu / 2] = pair_hi(kprev[1], kq[1]);
                 }
                 kprev = kq;
                 if (u % NS == slice)   // sibling slices share the G_cum rows between them
-                    *reinterpret_cast<f32x4 *>(Gm + (g_e0 + u * gcs) * 4) = gout;
+                    *reinterpret_cast<f32x4 *>(Gm + (size_t)(u * gcs) * 4 + g_b0) = gout;
             }
 #pragma unroll
-            for (int a = 0; a < 4; ++a) kt[a].store(Kt + (4 * cq + a) * TS + tq * TPT * 2);
+            for (int a = 0; a < 4; ++a) kt[a].store(Kt + (4 * cq + a) * TS + (tq * TPT + half * HT) * 2);
+        };
+        auto gate_b_finish = [&](int m, float *gam_m) __attribute__((always_inline)) {
             if (tq == 0) {
                 f32x4 gm;
 #pragma unroll
@@ -317,7 +336,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                 seg_lo[a] = (seg_hi[a] - (s - bb)) + (x - bb);
                 seg_hi[a] = s;
             }
-            if (m == N - 1 && tq == 0 && slice == 0) {   // segment total: log of the cumulative decay gamma~_[N]
+            if (m == N - 1 && tq == 0 && slice == 0) {   // segment total: log of gamma~_[N]
                 f32x4 gt;
 #pragma unroll
                 for (int a = 0; a < 4; ++a) gt[a] = seg_hi[a] + seg_lo[a];
@@ -325,32 +344,56 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
             }
         };
 
-        gate_a(0, lds);
+        // Schedule (the MFMA waves run part 1 of chunk n in phase X(n) and part 2 in phase Y(n)):
+        //   X(n): V^T(n+1) -> LDS, setup and first token half of part 2 of chunk n+1
+        //   Y(n): second token half and finish of chunk n+1, then part 1 of chunk n+2
+        // so that both phases carry a similar amount of gate work.  The loop bodies are free of
+        // branches (a conditional around the passes would force the reloaded registers through
+        // merge copies, and with them a wait for every load in flight); the tail is peeled.
+        gate_a(0);
+        vt_store(0, lds);
         __syncthreads();
-        gate_b(0, lds, gam);
+        gate_b_setup();
+        gate_b_half(0, 0, lds);
+        gate_b_half(0, 1, lds);
+        gate_b_finish(0, gam);
+        if (N > 1) gate_a(1);
         __syncthreads();
-        // Branch-free loop body (a conditional around the passes would force the reloaded registers
-        // through merge copies and with them a wait for every load in flight).
-        for (int n = 0; n + 1 < N; ++n) {
+        int n = 0;
+        for (; n + 2 < N; ++n) {
             unsigned char *nxt = lds + ((n + 1) & 1) * Cfg::kTileBytes;
             ZPT(0);
-            gate_a(n + 1, nxt);
+            vt_store(n + 1, nxt);
+            gate_b_setup();
+            gate_b_half(n + 1, 0, nxt);
             ZPT(2);
-            __syncthreads();   // Ps of chunk n and the gate sums of chunk n+1 are visible
+            __syncthreads();   // Ps of chunk n visible to the MFMA waves
             ZPT(3);
-            gate_b(n + 1, nxt, gam + ((n + 1) & 1) * DK);
+            gate_b_half(n + 1, 1, nxt);
+            gate_b_finish(n + 1, gam + ((n + 1) & 1) * DK);
+            gate_a(n + 2);
             ZPT(5);
-            __syncthreads();   // tiles of chunk n+1 complete; buffer of chunk n free
+            __syncthreads();   // tiles of chunk n+1 and gate sums of chunk n+2 complete
             ZPT(6);
         }
-        __syncthreads();   // last chunk: nothing left to produce, keep in step with the MFMA waves
+        if (N > 1) {   // n = N-2: produce the last chunk
+            unsigned char *nxt = lds + ((n + 1) & 1) * Cfg::kTileBytes;
+            vt_store(n + 1, nxt);
+            gate_b_setup();
+            gate_b_half(n + 1, 0, nxt);
+            __syncthreads();
+            gate_b_half(n + 1, 1, nxt);
+            gate_b_finish(n + 1, gam + ((n + 1) & 1) * DK);
+            __syncthreads();
+        }
+        __syncthreads();   // n = N-1: nothing left to produce, keep in step with the MFMA waves
         __syncthreads();
     } else {
         // ================================ MFMA waves ===========================================
         const int lt = lane & 31, kg = lane >> 5;       // 32x32x16 lane coordinates
         const int l16 = lane & 15, kg16 = lane >> 4;    // 16x16x32 lane coordinates (score tiles)
         unsigned char *ob = (unsigned char *)p.o + vbase * 2;
-        const unsigned o_e0 = (unsigned)lt * vt + w * 32 + 4 * kg;   // O^T element of this lane
+        const unsigned o_b0 = ((unsigned)lt * vt + w * 32 + 4 * kg) * 2;   // O^T byte offset of this lane
 
         f32x16 Sacc[Cfg::NIT], Oacc[2];
 #pragma unroll
@@ -417,7 +460,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                     Oacc[mt] = M::run(vf[ks], lds_frag(Ps, (mt * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), Oacc[mt]);
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd)
-                    *reinterpret_cast<u32x2 *>(on + (o_e0 + mt * 32 * vt + 8 * qd) * 2) =
+                    *reinterpret_cast<u32x2 *>(on + (size_t)(mt * 32 * vt + 8 * qd) * 2 + o_b0) =
                         u32x2{pack_bf16(Oacc[mt][4 * qd] * p.scale, Oacc[mt][4 * qd + 1] * p.scale),
                               pack_bf16(Oacc[mt][4 * qd + 2] * p.scale, Oacc[mt][4 * qd + 3] * p.scale)};
             }

@@ -20,7 +20,9 @@ template <int DK, int DV> struct ApplyCfg {
     static constexpr int NKS = DK / KS;
     static constexpr int QS = DK * 2 + 16;          // LDS row stride (bytes)
     static constexpr int ITEMS = 64 * DK / 8 / 256; // 8-channel groups per thread per 64 tokens
-    static constexpr int kBytes = 2 * 64 * QS;
+    static constexpr int OITEMS = 64 * DV / 8 / 256; // 8-column pieces of o per thread per 64 tokens
+    static constexpr int CS = DV + 4;               // row stride (floats) of the fp32 staging tile
+    static constexpr int kBytes = 64 * QS + 64 * CS * 4;
 };
 
 template <int DK, int DV>
@@ -28,7 +30,9 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     typedef ApplyCfg<DK, DV> Cfg;
     typedef Mma<Cfg::TILE> M;
     constexpr int TILE = Cfg::TILE, KS = Cfg::KS, QS = Cfg::QS;
-    __shared__ __align__(16) unsigned char Qh[Cfg::kBytes];
+    __shared__ __align__(16) unsigned char lds[Cfg::kBytes];
+    unsigned char *Qh = lds;                                      // scale * q .* exp(G_cum), bf16
+    float *Cs = reinterpret_cast<float *>(lds + 64 * QS);         // correction tile, fp32
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lt = lane % TILE, kg = lane / TILE;
@@ -76,12 +80,26 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         }
     };
 
+    // o is read-modified-written in 16-byte pieces (8 columns of one token per item); the MFMA
+    // result reaches that layout through an fp32 staging tile in LDS.
+    auto load_o = [&](int blk, u32x4 (&ro)[Cfg::OITEMS]) {
+#pragma unroll
+        for (int m = 0; m < Cfg::OITEMS; ++m) {
+            const int item = tid + 256 * m, t = item / (DV / 8), cg = item % (DV / 8);
+            ro[m] = *reinterpret_cast<const u32x4 *>(op + ((long long)blk * 64 + t) * p.vt + 8 * cg);
+        }
+    };
+
     const int nblk = p.tokens_per_wg / 64;
     Raw nxt;
+    u32x4 onx[Cfg::OITEMS];
     load_raw(0, nxt);
+    load_o(0, onx);
     for (int blk = 0; blk < nblk; ++blk) {
-        unsigned char *buf = Qh + (blk & 1) * 64 * QS;
-        Raw cur = nxt;
+        const Raw cur = nxt;
+        u32x4 ocur[Cfg::OITEMS];
+#pragma unroll
+        for (int m = 0; m < Cfg::OITEMS; ++m) ocur[m] = onx[m];
 #pragma unroll
         for (int m = 0; m < Cfg::ITEMS; ++m) {
             const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
@@ -93,10 +111,12 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
                 out[e] = pack_bf16(bf16_lo(cur.q[m][e]) * fast_exp(ga) * p.scale,
                                    bf16_hi(cur.q[m][e]) * fast_exp(gb) * p.scale);
             }
-            *reinterpret_cast<u32x4 *>(buf + t * QS + 16 * cg) = out;
+            *reinterpret_cast<u32x4 *>(Qh + t * QS + 16 * cg) = out;
         }
-        if (blk + 1 < nblk) load_raw(blk + 1, nxt);
-        __syncthreads();   // one barrier per block: the other buffer was last read two blocks ago
+        const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
+        load_raw(nb, nxt);
+        load_o(nb, onx);
+        __syncthreads();   // Qh complete; every thread is done with the staging tile of the last block
 
 #pragma unroll
         for (int mt = 0; mt < Cfg::NMT; ++mt) {
@@ -105,15 +125,25 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
             for (int r = 0; r < Cfg::ACC; ++r) acc[r] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < Cfg::NKS; ++ks)
-                acc = M::run(sf[ks], lds_frag(buf, (mt * TILE + lt) * QS + (ks * KS + 8 * kg) * 2), acc);
-            uint16_t *orow = op + ((long long)blk * 64 + mt * TILE + lt) * p.vt + w * TILE;
+                acc = M::run(sf[ks], lds_frag(Qh, (mt * TILE + lt) * QS + (ks * KS + 8 * kg) * 2), acc);
 #pragma unroll
-            for (int qd = 0; qd < Cfg::ACC / 4; ++qd) {
-                u32x2 *ptr = reinterpret_cast<u32x2 *>(orow + M::row(4 * qd, kg));
-                const u32x2 old = *ptr;
-                *ptr = u32x2{pack_bf16(bf16_lo(old[0]) + acc[4 * qd], bf16_hi(old[0]) + acc[4 * qd + 1]),
-                             pack_bf16(bf16_lo(old[1]) + acc[4 * qd + 2], bf16_hi(old[1]) + acc[4 * qd + 3])};
-            }
+            for (int qd = 0; qd < Cfg::ACC / 4; ++qd)   // lane holds 4 consecutive columns of token lt
+                *reinterpret_cast<f32x4 *>(Cs + (mt * TILE + lt) * Cfg::CS + w * TILE + M::row(4 * qd, kg)) =
+                    f32x4{acc[4 * qd], acc[4 * qd + 1], acc[4 * qd + 2], acc[4 * qd + 3]};
+        }
+        __syncthreads();   // staging tile complete; Qh free for the next block
+
+#pragma unroll
+        for (int m = 0; m < Cfg::OITEMS; ++m) {
+            const int item = tid + 256 * m, t = item / (DV / 8), cg = item % (DV / 8);
+            const f32x4 c0 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg);
+            const f32x4 c1 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg + 4);
+            const u32x4 old = ocur[m];
+            *reinterpret_cast<u32x4 *>(op + ((long long)blk * 64 + t) * p.vt + 8 * cg) =
+                u32x4{pack_bf16(bf16_lo(old[0]) + c0[0], bf16_hi(old[0]) + c0[1]),
+                      pack_bf16(bf16_lo(old[1]) + c0[2], bf16_hi(old[1]) + c0[3]),
+                      pack_bf16(bf16_lo(old[2]) + c1[0], bf16_hi(old[2]) + c1[1]),
+                      pack_bf16(bf16_lo(old[3]) + c1[2], bf16_hi(old[3]) + c1[3])};
         }
     }
 }

@@ -24,15 +24,16 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
     const size_t state = (size_t)p.d_k * p.d_v;
     const size_t seg_stride = (size_t)p.BH * state;         // floats between segments
     const size_t g_stride = (size_t)p.BH * p.d_k;
+    const size_t grp = blockIdx.y;                          // chain (group of P segments)
 
     for (int e = threadIdx.x; e < slab4; e += blockDim.x) {
         const int row = row0 + e / dv4;
         const size_t off = (size_t)bh * state + (size_t)row * p.d_v + (size_t)(e % dv4) * 4;
-        const float *loc = p.S_loc + off;
-        const float *gt = p.G_tot + (size_t)bh * p.d_k + row;
-        float *init = p.S_init + off;
+        const float *loc = p.S_loc + grp * p.P * seg_stride + off;
+        const float *gt = p.G_tot + grp * p.P * g_stride + (size_t)bh * p.d_k + row;
+        float *init = p.S_init + grp * p.P * seg_stride + off;
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        if (p.S0) s = *reinterpret_cast<const f32x4 *>(p.S0 + off);
+        if (p.S0) s = *reinterpret_cast<const f32x4 *>(p.S0 + grp * seg_stride + off);
 
         for (int p0 = 0; p0 < p.P; p0 += kScanDepth) {
             f32x4 x[kScanDepth];
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
                 }
             }
         }
-        if (p.S_last) *reinterpret_cast<f32x4 *>(p.S_last + off) = s;
+        if (p.S_last) *reinterpret_cast<f32x4 *>(p.S_last + grp * seg_stride + off) = s;
     }
 }
 
@@ -65,7 +66,29 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s) {
     const int slab4 = p.rows_per_block * (p.d_v / 4);
     int threads = ((slab4 + 63) / 64) * 64;
     if (threads > 256) threads = 256;
-    hipLaunchKernelGGL(state_scan_kernel, dim3(blocks), dim3(threads), 0, s, p);
+    hipLaunchKernelGGL(state_scan_kernel, dim3(blocks, p.groups), dim3(threads), 0, s, p);
+    return hipGetLastError();
+}
+
+// Exclusive prefix and total of the segments' log decays inside each group (tiny, one thread per
+// (group, batch, head, channel)).
+__global__ __launch_bounds__(256) void gate_prefix_kernel(const float *G_tot, float *G_pre, float *G_sum,
+                                                           int P, int BHdk) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= BHdk) return;
+    const size_t g0 = (size_t)blockIdx.y * P * BHdk + e;
+    float acc = 0.f;
+    for (int r = 0; r < P; ++r) {
+        G_pre[g0 + (size_t)r * BHdk] = acc;
+        acc += G_tot[g0 + (size_t)r * BHdk];
+    }
+    G_sum[(size_t)blockIdx.y * BHdk + e] = acc;
+}
+
+hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, int groups, int P,
+                              int BHdk, hipStream_t s) {
+    hipLaunchKernelGGL(gate_prefix_kernel, dim3((BHdk + 255) / 256, groups), dim3(256), 0, s, G_tot, G_pre,
+                       G_sum, P, BHdk);
     return hipGetLastError();
 }
 

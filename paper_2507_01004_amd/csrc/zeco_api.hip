@@ -36,9 +36,40 @@ zeco_status from_hip(hipError_t e) { return e == hipSuccess ? ZECO_OK : ZECO_ERR
 
 extern "C" {
 
+// Number of sub-segments each segment is split into inside zeco_gla_local_fwd (1 = none).  A stream is
+// a serial chain over chunks, so with few (batch, segment, head) streams most compute units would
+// idle; the local pass then applies the method to itself: sub-segments from the zero state, a scan of
+// their states inside each segment, and a correction that also rebases the cumulative log decay.
+static int subsegments(const zeco_gla_desc *d) {
+    if (d->io_dtype != ZECO_BF16) return 1;
+    const long long streams = (long long)d->B * d->P * d->H;
+    if (streams > 64) return 1;
+    int S = 1;
+    while (streams * S < 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
+    return S;
+}
+
+struct SubLayout {          // workspace carve-up, in floats
+    size_t states, gates;   // elements of one state array / one gate array over all sub-segments
+    size_t off_Ssub, off_Sinit, off_Gtot, off_Gpre, total;
+};
+static SubLayout sub_layout(const zeco_gla_desc *d, int S) {
+    SubLayout w;
+    const size_t n = (size_t)d->P * S * d->B * d->H;
+    w.states = n * d->d_k * d->d_v;
+    w.gates = n * d->d_k;
+    w.off_Ssub = 0;
+    w.off_Sinit = w.off_Ssub + w.states;
+    w.off_Gtot = w.off_Sinit + w.states;
+    w.off_Gpre = w.off_Gtot + w.gates;
+    w.total = w.off_Gpre + w.gates;
+    return w;
+}
+
 size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc) {
-    (void)desc;
-    return 0;
+    if (check_desc(desc) != ZECO_OK) return 0;
+    const int S = subsegments(desc);
+    return S > 1 ? sub_layout(desc, S).total * sizeof(float) : 0;
 }
 
 zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
@@ -50,8 +81,11 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
         !aligned16(S_loc) || !aligned16(G_cum) || !aligned16(G_tot))
         return ZECO_ERR_INVALID_ARG;
-    if (workspace_bytes < zeco_gla_local_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
-    (void)workspace;
+    const size_t need = zeco_gla_local_fwd_workspace(d);
+    if (workspace_bytes < need) return ZECO_ERR_WORKSPACE;
+    if (need && (!workspace || !aligned16(workspace))) return ZECO_ERR_INVALID_ARG;
+    const int S = subsegments(d);
+    hipStream_t s = static_cast<hipStream_t>(stream);
 
     zeco::ChunkParams p;
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o;
@@ -64,9 +98,37 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
 #ifdef ZECO_PHASE_TIMING
     p.dbg = zeco::g_phase_dbg;
 #endif
-    hipStream_t s = static_cast<hipStream_t>(stream);
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, s));
+    if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, s));
+
+    // Few streams: P*S sub-segments of L/S tokens (Sec. 3.1 applied inside each segment).
+    const SubLayout w = sub_layout(d, S);
+    float *ws = static_cast<float *>(workspace);
+    float *Ssub = ws + w.off_Ssub, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot, *Gpre = ws + w.off_Gpre;
+    p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
+    p.S_loc = Ssub; p.G_tot = Gtot;
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, s);
+    if (e != hipSuccess) return ZECO_ERR_HIP;
+
+    zeco::ScanParams sp;   // one chain of S sub-segments per segment; its end state is the segment's S_loc
+    sp.S_loc = Ssub; sp.G_tot = Gtot; sp.S0 = nullptr; sp.S_init = Sinit; sp.S_last = S_loc;
+    sp.P = S; sp.groups = d->P; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+    sp.rows_per_block = d->d_k / 16;
+    if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+    if ((e = zeco::launch_gate_prefix(Gtot, Gpre, G_tot, d->P, S, d->B * d->H * d->d_k, s)) != hipSuccess)
+        return ZECO_ERR_HIP;
+
+    zeco::ApplyParams ap;  // correction of sub-segments 1..S-1 and rebasing of their G_cum
+    ap.q = q; ap.G_cum = G_cum; ap.S_init = Sinit; ap.G_off = Gpre; ap.o = o;
+    ap.B = d->B; ap.P = p.P; ap.H = d->H; ap.L = p.L;
+    ap.p0 = 0; ap.skip_mod = S;
+    int tpw = 1024;
+    while (tpw > 64 && p.L % tpw != 0) tpw >>= 1;
+    ap.tokens_per_wg = tpw;
+    ap.scale = d->scale;
+    ap.sb = d->stride_b; ap.st = d->stride_t; ap.sh = d->stride_h;
+    ap.vb = d->vstride_b; ap.vt = d->vstride_t; ap.vh = d->vstride_h;
+    return from_hip(zeco::launch_apply_bf16(ap, d->d_k, d->d_v, s));
 }
 
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
@@ -85,7 +147,7 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
 
     zeco::ScanParams p;
     p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = S0; p.S_init = S_init; p.S_last = S_last;
-    p.P = P; p.BH = BH; p.d_k = d_k; p.d_v = d_v; p.rows_per_block = d_k / K_blocks;
+    p.P = P; p.BH = BH; p.d_k = d_k; p.d_v = d_v; p.rows_per_block = d_k / K_blocks; p.groups = 1;
     return from_hip(zeco::launch_scan(p, static_cast<hipStream_t>(stream)));
 }
 
@@ -99,9 +161,9 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
         return ZECO_ERR_INVALID_ARG;
 
     zeco::ApplyParams p;
-    p.q = q; p.G_cum = G_cum; p.S_init = S_init; p.o = o;
+    p.q = q; p.G_cum = const_cast<float *>(G_cum); p.S_init = S_init; p.G_off = nullptr; p.o = o;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
-    p.p0 = first_segment_is_zero ? 1 : 0;
+    p.p0 = first_segment_is_zero ? 1 : 0; p.skip_mod = 0;
     int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
     while (tpw > 64 && d->L % tpw != 0) tpw >>= 1;
     p.tokens_per_wg = tpw;

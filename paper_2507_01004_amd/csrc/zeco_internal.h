@@ -24,19 +24,24 @@ extern unsigned long long *g_phase_dbg;
 
 struct ApplyParams {
     const void *q;
-    const float *G_cum, *S_init;
+    float *G_cum;              // read; rewritten as G_cum + G_off when G_off is given
+    const float *S_init;
+    const float *G_off;        // nullable [P,B,H,d_k]: log decay to add to G_cum of each segment
     void *o;
     int B, P, H, L;
     int p0;                    // first segment to correct
+    int skip_mod;              // > 0: segments with index % skip_mod == 0 are left untouched
     int tokens_per_wg;         // multiple of 64 dividing L
     float scale;
     long long sb, st, sh, vb, vt, vh;
 };
 
+// `groups` independent chains of P segments each: S_loc, S_init [groups*P, BH, d_k, d_v],
+// G_tot [groups*P, BH, d_k], S0 and S_last [groups, BH, d_k, d_v].
 struct ScanParams {
     const float *S_loc, *G_tot, *S0;
     float *S_init, *S_last;
-    int P, BH, d_k, d_v, rows_per_block;
+    int P, BH, d_k, d_v, rows_per_block, groups;
 };
 
 // Each returns hipSuccess or the launch error.  d_k, d_v in {64,128}.
@@ -45,6 +50,9 @@ hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_scan(const ScanParams &p, hipStream_t s);
+// Per group of P segments: G_pre[g*P+p] = sum of G_tot[g*P+r] over r < p, G_sum[g] = sum over all r.
+hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, int groups, int P,
+                              int BHdk, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 }  // namespace zeco

@@ -19,8 +19,10 @@ CASES = [
     ("f32_d128", 2, 3, 2, 192, 128, 128, "f32", "f32"),
     ("f32_dk64_dv128", 1, 2, 3, 128, 64, 128, "f32", "f32"),
     ("f32_dk128_dv64", 1, 2, 2, 128, 128, 64, "f32", "f32"),
-    ("bf16_sliced", 1, 4, 2, 320, 128, 128, "bf16", "f32"),        # 8 streams -> two d_v slices, 16-wide tiles
-    ("bf16_whole", 2, 16, 8, 128, 128, 128, "bf16", "f32"),        # 256 streams -> one slice, 32-wide tiles
+    ("bf16_sliced", 1, 4, 2, 320, 128, 128, "bf16", "f32"),        # 8 streams -> two sibling workgroups split d_v
+    ("bf16_whole", 2, 16, 8, 128, 128, 128, "bf16", "f32"),        # 256 streams -> one workgroup per stream
+    ("bf16_subseg", 1, 2, 2, 1024, 128, 128, "bf16", "f32"),       # 4 streams -> 4 sub-segments per segment
+    ("bf16_subseg_d64", 1, 1, 1, 2048, 64, 64, "bf16", "bf16"),    # 1 stream  -> 8 sub-segments
     ("bf16_gbf16", 1, 3, 2, 256, 128, 128, "bf16", "bf16"),
     ("bf16_d64", 1, 2, 4, 192, 64, 64, "bf16", "f32"),
     ("bf16_dk64_dv128", 1, 2, 2, 128, 64, 128, "bf16", "f32"),

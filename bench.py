@@ -7,7 +7,7 @@ whole-job throughput (tokens/s), the roofline of the dominant kernel (the chunk 
 local pass) measured live with HIP events on the launch stream, and the CPU oracle timed on a
 bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c4] [--g-dtype f32|bf16]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--g-dtype f32|bf16]
 """
 import argparse
 import json
@@ -69,7 +69,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--k-blocks", type=int, default=16)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")

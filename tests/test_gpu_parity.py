@@ -24,6 +24,8 @@ CASES = [
     ("bf16_subseg", 1, 2, 2, 1024, 128, 128, "bf16", "f32"),       # 4 streams -> 4 sub-segments per segment
     ("bf16_subseg_d64", 1, 1, 1, 2048, 64, 64, "bf16", "bf16"),    # 1 stream  -> 8 sub-segments
     ("bf16_gbf16", 1, 3, 2, 256, 128, 128, "bf16", "bf16"),
+    ("bf16_onechunk", 1, 2, 4, 64, 128, 128, "bf16", "f32"),       # N = 1: pipeline prologue only
+    ("bf16_whole_onechunk", 1, 16, 16, 64, 128, 128, "bf16", "f32"),
     ("bf16_d64", 1, 2, 4, 192, 64, 64, "bf16", "f32"),
     ("bf16_dk64_dv128", 1, 2, 2, 128, 64, 128, "bf16", "f32"),
     ("bf16_dk128_dv64", 1, 2, 2, 128, 128, 64, "bf16", "bf16"),

@@ -97,6 +97,34 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *desc, const void *q, cons
                                   const float *S_init, void *o, int32_t first_segment_is_zero,
                                   void *stream);
 
+/* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
+ * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
+ * ZECO_ERR_UNSUPPORTED).  Same conventions as above. ------------------------------------------------ */
+
+/* Phase 1 (Alg. 1 chunk-state loop, Eq. (local-recurrence) and Eq. (gamma)): final local state and
+ * total log decay of every segment from the zero state.  Reads k, v, g only.
+ *   out  S_loc [P,B,H,d_k,d_v] fp32,  G_tot [P,B,H,d_k] fp32 */
+zeco_status zeco_gla_local_state(const zeco_gla_desc *desc, const void *k, const void *v,
+                                 const void *g, float *S_loc, float *G_tot, void *stream);
+
+/* Phase 2 (Alg. 1 output pass with the incoming state, Eq. (global-correction)): chunkwise forward of
+ * every segment p started from S_init[p] (as produced by zeco_state_scan); writes the final output.
+ *   in   S_init [P,B,H,d_k,d_v] fp32      out  o (descriptor layout, io_dtype) */
+zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *desc, const void *q, const void *k,
+                                    const void *v, const void *g, const float *S_init, void *o,
+                                    void *stream);
+
+/* Both phases and the scan between them in one call, for all P segments resident on this device.
+ * The library may cut the segments further (more, shorter segments cost no extra traffic here and
+ * keep every compute unit busy); the states of those pieces live in the workspace.
+ *   in   S0 [B,H,d_k,d_v] fp32 or NULL: state entering the first segment
+ *   out  o;  S_last [B,H,d_k,d_v] fp32 or NULL: state after the last token
+ * workspace: zeco_gla_fused_fwd_workspace(desc) bytes of device memory, 16-byte aligned. */
+size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc);
+zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *desc, const void *q, const void *k, const void *v,
+                               const void *g, const float *S0, void *o, float *S_last,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
 /* Bandwidth calibration utility (not part of the method): copies `bytes` (a multiple of 16) from
  * src to dst with a plain grid-stride kernel of 16-byte accesses.  Used to scale the HBM byte
  * counters of the profiler and to quote the achievable copy bandwidth beside the nominal peak.

@@ -131,7 +131,15 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 
 // DV is the number of state columns this workgroup owns: d_v, or d_v / NS when NS sibling workgroups
 // share a stream (each recomputes the gate pass and takes its own slice of v, o and the state).
-template <int DK, int DV, int NS, bool GBF16>
+// MODE selects what a launch computes:
+//   kLocal   the local pass from the zero state: o, S_loc, G_cum, G_tot          (Sec. 3.1)
+//   kStates  only the final local state and total decay of each segment: S_loc, G_tot
+//            (Alg. 1's chunk-state loop; q is not read, nothing per token is written)
+//   kOutput  the output pass from given initial states S_init[p]: o only
+//            (Alg. 1's output pass, the incoming state folded into the running state)
+enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2 };
+
+template <int DK, int DV, int NS, bool GBF16, int MODE>
 __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParams p) {
     typedef B16Cfg<DK, DV> Cfg;
     typedef Mma<32> M;
@@ -197,7 +205,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         typename GV::raw_t rg[TPT];
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
-            rq[u] = *reinterpret_cast<const u32x2 *>(qb + (size_t)(u * st) * 2 + q_b0);
+            if constexpr (MODE != kStates) rq[u] = *reinterpret_cast<const u32x2 *>(qb + (size_t)(u * st) * 2 + q_b0);
             rk[u] = *reinterpret_cast<const u32x2 *>(kb + (size_t)(u * st) * 2 + q_b0);
             rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (size_t)(u * st) * GB + g_in_b0);
         }
@@ -291,23 +299,27 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
             for (int uu = 0; uu < HT; ++uu) {
                 const int u = half * HT + uu;
                 const int t = tq * TPT + u;
-                f32x4 lam, ilam, gout;
+                f32x4 yv, ilam;
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
-                    const float y = __builtin_fmaf(cs[u][a], kLog2e, pre2[a]);
-                    lam[a] = __builtin_amdgcn_exp2f(y);
-                    ilam[a] = __builtin_amdgcn_exp2f(-y);
-                    gout[a] = gbase[a] + cs[u][a];
+                    yv[a] = __builtin_fmaf(cs[u][a], kLog2e, pre2[a]);
+                    ilam[a] = __builtin_amdgcn_exp2f(-yv[a]);
                 }
-                const u32x2 qw = rq[u], kw = rk[u];
-                rq[u] = *reinterpret_cast<const u32x2 *>(qn + (size_t)(u * st) * 2 + q_b0);
+                const u32x2 kw = rk[u];
                 rk[u] = *reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0);
-                *reinterpret_cast<u32x2 *>(Qs + t * QS + qpos * 2) =
-                    u32x2{pack_bf16(bf16_lo(qw[0]) * lam[0], bf16_hi(qw[0]) * lam[1]),
-                          pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};
                 const u32x2 kq = {pack_bf16(bf16_lo(kw[0]) * ilam[0], bf16_hi(kw[0]) * ilam[1]),
                                   pack_bf16(bf16_lo(kw[1]) * ilam[2], bf16_hi(kw[1]) * ilam[3])};
-                *reinterpret_cast<u32x2 *>(Ks + t * QS + qpos * 2) = kq;
+                if constexpr (MODE != kStates) {   // scores and outputs need Q .* Lambda and token-major K / Lambda
+                    f32x4 lam;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) lam[a] = __builtin_amdgcn_exp2f(yv[a]);
+                    const u32x2 qw = rq[u];
+                    rq[u] = *reinterpret_cast<const u32x2 *>(qn + (size_t)(u * st) * 2 + q_b0);
+                    *reinterpret_cast<u32x2 *>(Qs + t * QS + qpos * 2) =
+                        u32x2{pack_bf16(bf16_lo(qw[0]) * lam[0], bf16_hi(qw[0]) * lam[1]),
+                              pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};
+                    *reinterpret_cast<u32x2 *>(Ks + t * QS + qpos * 2) = kq;
+                }
                 if (uu % 2 == 1) {   // transpose: tokens (u-1, u) of each channel share a word
                     kt[0].w[uu / 2] = pair_lo(kprev[0], kq[0]);
                     kt[1].w[uu / 2] = pair_hi(kprev[0], kq[0]);
@@ -315,8 +327,13 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                     kt[3].w[uu / 2] = pair_hi(kprev[1], kq[1]);
                 }
                 kprev = kq;
-                if (u % NS == slice)   // sibling slices share the G_cum rows between them
-                    *reinterpret_cast<f32x4 *>(Gm + (size_t)(u * gcs) * 4 + g_b0) = gout;
+                if constexpr (MODE == kLocal) {
+                    f32x4 gout;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) gout[a] = gbase[a] + cs[u][a];
+                    if (u % NS == slice)   // sibling slices share the G_cum rows between them
+                        *reinterpret_cast<f32x4 *>(Gm + (size_t)(u * gcs) * 4 + g_b0) = gout;
+                }
             }
 #pragma unroll
             for (int a = 0; a < 4; ++a) kt[a].store(Kt + (4 * cq + a) * TS + (tq * TPT + half * HT) * 2);
@@ -328,6 +345,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                 for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
                 *reinterpret_cast<f32x4 *>(gam_m + 4 * cq) = gm;
             }
+            if constexpr (MODE == kOutput) return;   // no decay outputs in the output pass
 #pragma unroll
             for (int a = 0; a < 4; ++a) {   // (hi, lo) += total, error-free transformation
                 const float x = total[a] + seg_lo[a];
@@ -396,10 +414,13 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         const unsigned o_b0 = ((unsigned)lt * vt + w * 32 + 4 * kg) * 2;   // O^T byte offset of this lane
 
         f32x16 Sacc[Cfg::NIT], Oacc[2];
+        float *Sl = p.S_loc + sbh * DK * (DV * NS) + slice * DV + w * 32 + lt;   // this lane's state column
+        const float *Si = p.S_init + sbh * DK * (DV * NS) + slice * DV + w * 32 + lt;
 #pragma unroll
         for (int it = 0; it < Cfg::NIT; ++it)
 #pragma unroll
-            for (int rr = 0; rr < 16; ++rr) Sacc[it][rr] = 0.f;
+            for (int rr = 0; rr < 16; ++rr)
+                Sacc[it][rr] = (MODE == kOutput) ? Si[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] : 0.f;
 
         // part 1: scores -> Ps, inter-chunk product -> Oacc
         auto mfma_a = [&](const unsigned char *tile) __attribute__((always_inline)) {
@@ -454,7 +475,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
             for (int ks = 0; ks < 4; ++ks) vf[ks] = lds_frag(Vt, (w * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2);
             // O^T += Vt Ps^T over the causal k-range (tokens s < 32 (mt + 1))
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
+            for (int mt = 0; mt < (MODE == kStates ? 0 : 2); ++mt) {
 #pragma unroll
                 for (int ks = 0; ks < 2 * (mt + 1); ++ks)
                     Oacc[mt] = M::run(vf[ks], lds_frag(Ps, (mt * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), Oacc[mt]);
@@ -486,7 +507,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         for (int n = 0; n < N; ++n) {
             const unsigned char *cur = lds + (n & 1) * Cfg::kTileBytes;
             ZPT(0);
-            mfma_a(cur);
+            if constexpr (MODE != kStates) mfma_a(cur);
             ZPT(2);
             __syncthreads();
             ZPT(3);
@@ -496,19 +517,20 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
             ZPT(6);
         }
 
-        float *Sl = p.S_loc + sbh * DK * (DV * NS) + slice * DV + w * 32 + lt;
+        if constexpr (MODE != kOutput) {
 #pragma unroll
-        for (int it = 0; it < Cfg::NIT; ++it)
+            for (int it = 0; it < Cfg::NIT; ++it)
 #pragma unroll
-            for (int rr = 0; rr < 16; ++rr)
-                Sl[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] = Sacc[it][rr];
+                for (int rr = 0; rr < 16; ++rr)
+                    Sl[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] = Sacc[it][rr];
+        }
     }
 }
 
-template <int DK, int DV, int NS, bool GBF16>
+template <int DK, int DV, int NS, bool GBF16, int MODE>
 static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     typedef B16Cfg<DK, DV> Cfg;
-    auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GBF16>;
+    auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GBF16, MODE>;
     hipError_t e = hipFuncSetAttribute((const void *)kern,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
     if (e != hipSuccess) return e;
@@ -518,22 +540,26 @@ static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <bool GBF16>
+template <bool GBF16, int MODE>
 static hipError_t dispatch_b16(const ChunkParams &p, int d_k, int d_v, hipStream_t s) {
     // With fewer streams than compute units, two sibling workgroups split d_v = 128 so that every
     // compute unit streams memory; the gate pass is then computed twice.
     const bool split = d_v == 128 && p.B * p.P * p.H < 256;
-    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, 1, GBF16>(p, s);
-    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, 1, GBF16>(p, s);
+    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, 1, GBF16, MODE>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, 1, GBF16, MODE>(p, s);
     if (d_k == 64 && d_v == 128)
-        return split ? launch_b16<64, 64, 2, GBF16>(p, s) : launch_b16<64, 128, 1, GBF16>(p, s);
+        return split ? launch_b16<64, 64, 2, GBF16, MODE>(p, s) : launch_b16<64, 128, 1, GBF16, MODE>(p, s);
     if (d_k == 128 && d_v == 128)
-        return split ? launch_b16<128, 64, 2, GBF16>(p, s) : launch_b16<128, 128, 1, GBF16>(p, s);
+        return split ? launch_b16<128, 64, 2, GBF16, MODE>(p, s) : launch_b16<128, 128, 1, GBF16, MODE>(p, s);
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16, hipStream_t s) {
-    return g_bf16 ? dispatch_b16<true>(p, d_k, d_v, s) : dispatch_b16<false>(p, d_k, d_v, s);
+hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16, int mode, hipStream_t s) {
+    if (mode == kStates)
+        return g_bf16 ? dispatch_b16<true, kStates>(p, d_k, d_v, s) : dispatch_b16<false, kStates>(p, d_k, d_v, s);
+    if (mode == kOutput)
+        return g_bf16 ? dispatch_b16<true, kOutput>(p, d_k, d_v, s) : dispatch_b16<false, kOutput>(p, d_k, d_v, s);
+    return g_bf16 ? dispatch_b16<true, kLocal>(p, d_k, d_v, s) : dispatch_b16<false, kLocal>(p, d_k, d_v, s);
 }
 
 }  // namespace zeco

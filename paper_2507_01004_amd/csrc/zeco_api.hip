@@ -89,7 +89,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
 
     zeco::ChunkParams p;
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o;
-    p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot;
+    p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot; p.S_init = nullptr;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
     p.n_chunks = d->L / d->C;
     p.scale = d->scale;
@@ -99,7 +99,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     p.dbg = zeco::g_phase_dbg;
 #endif
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
-    if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, s));
+    if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 0, s));
 
     // Few streams: P*S sub-segments of L/S tokens (Sec. 3.1 applied inside each segment).
     const SubLayout w = sub_layout(d, S);
@@ -107,7 +107,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     float *Ssub = ws + w.off_Ssub, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot, *Gpre = ws + w.off_Gpre;
     p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
     p.S_loc = Ssub; p.G_tot = Gtot;
-    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, s);
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 0, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::ScanParams sp;   // one chain of S sub-segments per segment; its end state is the segment's S_loc
@@ -129,6 +129,98 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     ap.sb = d->stride_b; ap.st = d->stride_t; ap.sh = d->stride_h;
     ap.vb = d->vstride_b; ap.vt = d->vstride_t; ap.vh = d->vstride_h;
     return from_hip(zeco::launch_apply_bf16(ap, d->d_k, d->d_v, s));
+}
+
+// ---- two-phase forward ------------------------------------------------------------------------------
+static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
+    p.q = p.k = p.v = p.g = nullptr; p.o = nullptr;
+    p.S_loc = p.G_cum = p.G_tot = nullptr; p.S_init = nullptr;
+    p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
+    p.n_chunks = d->L / d->C;
+    p.scale = d->scale;
+    p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
+    p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
+#ifdef ZECO_PHASE_TIMING
+    p.dbg = nullptr;
+#endif
+}
+
+zeco_status zeco_gla_local_state(const zeco_gla_desc *d, const void *k, const void *v, const void *g,
+                                 float *S_loc, float *G_tot, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!k || !v || !g || !S_loc || !G_tot) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_loc) || !aligned16(G_tot))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.k = k; p.v = v; p.g = g; p.S_loc = S_loc; p.G_tot = G_tot;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 1,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
+                                    const void *g, const float *S_init, void *o, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !k || !v || !g || !S_init || !o) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_init) ||
+        !aligned16(o))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_init = S_init;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 2,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+// Pieces each segment is cut into by zeco_gla_fused_fwd: enough for 256 streams, at least 256 tokens each.
+static int fused_pieces(const zeco_gla_desc *d) {
+    const long long streams = (long long)d->B * d->P * d->H;
+    int S = 1;
+    while (streams * S < 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
+    return S;
+}
+
+size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
+    if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    const size_t n = (size_t)desc->P * fused_pieces(desc) * desc->B * desc->H;
+    return (2 * n * desc->d_k * desc->d_v + n * desc->d_k) * sizeof(float);
+}
+
+zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
+                               const void *g, const float *S0, void *o, float *S_last, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
+        !aligned16(S0) || !aligned16(S_last) || !aligned16(workspace))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    if (workspace_bytes < zeco_gla_fused_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int S = fused_pieces(d);
+    const size_t n = (size_t)d->P * S * d->B * d->H, states = n * d->d_k * d->d_v;
+    float *Sloc = static_cast<float *>(workspace), *Sinit = Sloc + states, *Gtot = Sinit + states;
+
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
+    p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 1, s);
+    if (e != hipSuccess) return ZECO_ERR_HIP;
+
+    zeco::ScanParams sp;
+    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
+    sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+    sp.rows_per_block = d->d_k / 16;
+    if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+
+    p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 2, s));
 }
 
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,

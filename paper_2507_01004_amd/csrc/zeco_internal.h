@@ -9,6 +9,7 @@ struct ChunkParams {
     const void *q, *k, *v, *g;
     void *o;
     float *S_loc, *G_cum, *G_tot;
+    const float *S_init;       // [P,B,H,d_k,d_v] initial states (output-pass mode only)
     int B, P, H, L;
     int n_chunks;              // L / 64
     float scale;
@@ -46,7 +47,8 @@ struct ScanParams {
 
 // Each returns hipSuccess or the launch error.  d_k, d_v in {64,128}.
 hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t s);
-hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16, hipStream_t s);
+// mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o)
+hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16, int mode, hipStream_t s);
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_scan(const ScanParams &p, hipStream_t s);

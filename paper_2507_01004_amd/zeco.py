@@ -16,7 +16,9 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
 ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
 ZECO_F32, ZECO_BF16 = 0, 1
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
-           "zeco_apply_init_state", "zeco_hbm_copy", "zeco_status_string", "zeco_version")
+           "zeco_apply_init_state", "zeco_gla_local_state", "zeco_gla_fwd_from_state",
+           "zeco_gla_fused_fwd_workspace", "zeco_gla_fused_fwd", "zeco_hbm_copy", "zeco_status_string",
+           "zeco_version")
 
 
 class GlaDesc(ctypes.Structure):
@@ -56,6 +58,14 @@ def lib():
         L.zeco_state_scan.restype = i32
         L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state.restype = i32
+        L.zeco_gla_local_state.argtypes = [dp, vp, vp, vp, fp, fp, vp]
+        L.zeco_gla_local_state.restype = i32
+        L.zeco_gla_fwd_from_state.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp]
+        L.zeco_gla_fwd_from_state.restype = i32
+        L.zeco_gla_fused_fwd_workspace.argtypes = [dp]
+        L.zeco_gla_fused_fwd_workspace.restype = ctypes.c_size_t
+        L.zeco_gla_fused_fwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_fused_fwd.restype = i32
         L.zeco_hbm_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.zeco_hbm_copy.restype = i32
         L.zeco_status_string.argtypes = [i32]
@@ -168,6 +178,67 @@ def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segm
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_apply_init_state")
     return o
+
+
+def gla_local_state(k, v, g, P, C=64, out=None):
+    """zeco_gla_local_state (phase 1 of the two-phase forward).  Returns (S_loc, G_tot)."""
+    if not k.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    B, T, H, dk = k.shape
+    dv = v.shape[-1]
+    desc = make_desc(k, v, g, P, C, 1.0)
+    if out is None:
+        S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=k.device)
+        G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device=k.device)
+    else:
+        S_loc, G_tot = out
+    st = lib().zeco_gla_local_state(ctypes.byref(desc), _ptr(k), _ptr(v), _ptr(g), _ptr(S_loc),
+                                    _ptr(G_tot), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_local_state")
+    return S_loc, G_tot
+
+
+def gla_fwd_from_state(q, k, v, g, S_init, P, scale=1.0, C=64, out=None):
+    """zeco_gla_fwd_from_state (phase 2): forward of each segment p started from S_init[p].  Returns o."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    desc = make_desc(q, v, g, P, C, scale)
+    o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device) if out is None else out
+    st = lib().zeco_gla_fwd_from_state(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g),
+                                       _ptr(S_init), _ptr(o), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_fwd_from_state")
+    return o
+
+
+def fused_workspace_bytes(q, v, g, P, C=64):
+    return int(lib().zeco_gla_fused_fwd_workspace(ctypes.byref(make_desc(q, v, g, P, C, 1.0))))
+
+
+def gla_fused_fwd(q, k, v, g, P, scale=1.0, S0=None, C=64, out=None, workspace=None, want_last=True):
+    """zeco_gla_fused_fwd: both phases and the scan in one call.  Returns (o, S_last)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    desc = make_desc(q, v, g, P, C, scale)
+    L = lib()
+    need = L.zeco_gla_fused_fwd_workspace(ctypes.byref(desc))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    if out is None:
+        o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
+        S_last = torch.empty(B, H, dk, dv, dtype=torch.float32, device=q.device) if want_last else None
+    else:
+        o, S_last = out
+    st = L.zeco_gla_fused_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(S0), _ptr(o),
+                              _ptr(S_last), _ptr(workspace), workspace.numel(), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_fused_fwd")
+    return o, S_last
 
 
 def hbm_copy(dst, src):

@@ -168,3 +168,44 @@ def test_errors_surface_as_exceptions():
     q = torch.zeros(1, 96, 1, 64, device="cuda")
     with pytest.raises(zeco.ZecoError):
         zeco.gla_local_fwd(q, q, q, q, 1)            # L = 96 is not a multiple of the chunk length
+
+
+BF16_CASES = [c for c in CASES if c[7] == "bf16"]
+
+
+@pytest.mark.parametrize("case", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_two_phase_forward_matches_oracle(case):
+    """Alg. 1's own schedule: states only, scan, output pass from the scanned states; and the fused
+    entry point, with and without a state entering the first segment."""
+    name, B, H, P, L, dk, dv, io, gd = case
+    print("case", case, flush=True)
+    inp = make(case, gate_div=64.0)
+    q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
+    tol = TOL[io]
+    # phase 1 against the oracle's local pass
+    S_loc, G_tot = zeco.gla_local_state(k, v, g, P)
+    torch.cuda.synchronize()
+    _, S_r, _, Gt_r = oracle_local(inp, P)
+    assert rel_err_bh(host(S_loc), S_r, (0, 1, 2)) <= tol
+    assert log_err(host(G_tot), Gt_r) <= 1e-5
+    # phase 2 from the oracle's own scanned states (fp32 copies), against the unsegmented run
+    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    for s0 in (None, S0):
+        o_r, Sf_r = oracle_full(inp, scale=0.5, S0=None if s0 is None else host(s0))
+        Si_r, _ = oracle.state_scan(S_r.reshape(P, B * H, dk, dv), Gt_r.reshape(P, B * H, dk),
+                                    None if s0 is None else host(s0).reshape(B * H, dk, dv))
+        o2 = zeco.gla_fwd_from_state(q, k, v, g, dev(Si_r.reshape(P, B, H, dk, dv)), P, scale=0.5)
+        torch.cuda.synchronize()
+        assert rel_err_bh(host(o2), o_r, (0, 2)) <= tol
+        # everything in one call
+        o3, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=s0)
+        torch.cuda.synchronize()
+        assert rel_err_bh(host(o3), o_r, (0, 2)) <= tol
+        assert rel_err_bh(host(S_last), Sf_r, (0, 1)) <= tol
+
+
+def test_two_phase_rejects_fp32():
+    q = torch.zeros(1, 64, 1, 64, device="cuda")
+    with pytest.raises(zeco.ZecoError) as e:
+        zeco.gla_fused_fwd(q, q, q, q, 1)
+    assert e.value.status == zeco.ZECO_ERR_UNSUPPORTED

@@ -13,7 +13,10 @@
  * Parity pins (tests/test_oracle_pins.py): brute-force quadratic unrolling of Eq. (1), the
  * geometric-series closed form, g == 0 -> causal linear attention, the single-chunk masked
  * matmul of Sec. 2.1, segmentation invariance (Eq. (global-correction), App. A.1), cumsum /
- * product forms of the segment scan, linearity.  No function here is "parity unpinned".
+ * product forms of the segment scan, linearity; for the backward pass: reverse-mode
+ * differentiation of an independent quadratic-form forward, central finite differences of the
+ * forward oracle, the reverse-cumulative-sum identity of App. A.4 for the gate gradient, chaining
+ * of segments through dS, and the g == 0 matmul closed form.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -164,4 +167,88 @@ int oracle_num_threads(void)
 #else
     return 1;
 #endif
+}
+
+/* Backward of Eq. (1) (App. A.4 computes the same gradients chunk by chunk).  For the scalar
+ *     loss = sum_t <o_t, dO_t> + <S_T, dS_T>
+ * reverse-mode differentiation of  S_t = (alpha_t^T 1) .* S_{t-1} + k_t^T v_t,  o_t = scale q_t S_t,
+ * alpha_t = exp(g_t), gives, walking t = T-1 .. 0 with E = d loss / d S_t from the later tokens
+ * (E = dS_T at the last token):
+ *     dS_t  = E + scale q_t^T dO_t
+ *     dq_t  = scale dO_t S_t^T           dk_t = (dS_t v_t^T)^T          dv_t = k_t dS_t
+ *     dg_t[i] = alpha_t[i] * sum_j dS_t[i,j] S_{t-1}[i,j]
+ *     E    <- (alpha_t^T 1) .* dS_t      (after t = 0 this is d loss / d S0)
+ * The forward states are kept at block boundaries and recomputed inside one block at a time.
+ * dO [B,T,H,d_v]; S0, dS_T, dS0 [B,H,d_k,d_v] (S0, dS_T, dS0 nullable). */
+void oracle_gla_recurrent_bwd(int B, int T, int H, int dk, int dv,
+                              const double *q, const double *k, const double *v, const double *g,
+                              double scale, const double *S0, const double *dO, const double *dS_T,
+                              double *dq, double *dk_out, double *dv_out, double *dg, double *dS0)
+{
+    const ptrdiff_t sk = (ptrdiff_t)H * dk, sv = (ptrdiff_t)H * dv;
+    const size_t ss = (size_t)dk * dv;
+    const int BLK = 128;
+    const int nblk = (T + BLK - 1) / BLK;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            const size_t bh = (size_t)b * H + h;
+            const size_t ok = ((size_t)b * T * H + h) * dk, ov = ((size_t)b * T * H + h) * dv;
+            /* forward sweep: state before the first token of every block */
+            double *ckpt = (double *)malloc(sizeof(double) * ss * nblk);
+            double *Sblk = (double *)malloc(sizeof(double) * ss * (BLK + 1));   /* S_{t0-1} .. S_{t1-1} */
+            double *S = (double *)malloc(sizeof(double) * ss);
+            double *E = (double *)malloc(sizeof(double) * ss);
+            double *dS = (double *)malloc(sizeof(double) * ss);
+            if (S0) memcpy(S, S0 + bh * ss, sizeof(double) * ss);
+            else memset(S, 0, sizeof(double) * ss);
+            for (int t = 0; t < T; ++t) {
+                if (t % BLK == 0) memcpy(ckpt + (size_t)(t / BLK) * ss, S, sizeof(double) * ss);
+                for (int i = 0; i < dk; ++i) {
+                    const double a = exp(g[ok + t * sk + i]);
+                    for (int j = 0; j < dv; ++j)
+                        S[i * dv + j] = a * S[i * dv + j] + k[ok + t * sk + i] * v[ov + t * sv + j];
+                }
+            }
+            if (dS_T) memcpy(E, dS_T + bh * ss, sizeof(double) * ss);
+            else memset(E, 0, sizeof(double) * ss);
+            for (int blk = nblk - 1; blk >= 0; --blk) {
+                const int t0 = blk * BLK, t1 = (t0 + BLK < T) ? t0 + BLK : T;
+                memcpy(Sblk, ckpt + (size_t)blk * ss, sizeof(double) * ss);
+                for (int t = t0; t < t1; ++t) {   /* Sblk[t - t0 + 1] = S_t */
+                    const double *prev = Sblk + (size_t)(t - t0) * ss;
+                    double *cur = Sblk + (size_t)(t - t0 + 1) * ss;
+                    for (int i = 0; i < dk; ++i) {
+                        const double a = exp(g[ok + t * sk + i]);
+                        for (int j = 0; j < dv; ++j)
+                            cur[i * dv + j] = a * prev[i * dv + j] + k[ok + t * sk + i] * v[ov + t * sv + j];
+                    }
+                }
+                for (int t = t1 - 1; t >= t0; --t) {
+                    const double *St = Sblk + (size_t)(t - t0 + 1) * ss;
+                    const double *Sp = Sblk + (size_t)(t - t0) * ss;
+                    const double *qt = q + ok + t * sk, *kt = k + ok + t * sk, *gt = g + ok + t * sk;
+                    const double *vt = v + ov + t * sv, *dOt = dO + ov + t * sv;
+                    for (int j = 0; j < dv; ++j) dv_out[ov + t * sv + j] = 0.0;
+                    for (int i = 0; i < dk; ++i) {
+                        const double a = exp(gt[i]);
+                        double accq = 0.0, acck = 0.0, accg = 0.0;
+                        for (int j = 0; j < dv; ++j) {
+                            const double d = E[i * dv + j] + scale * qt[i] * dOt[j];
+                            dS[i * dv + j] = d;
+                            accq += dOt[j] * St[i * dv + j];
+                            acck += d * vt[j];
+                            accg += d * Sp[i * dv + j];
+                            dv_out[ov + t * sv + j] += kt[i] * d;
+                        }
+                        dq[ok + t * sk + i] = scale * accq;
+                        dk_out[ok + t * sk + i] = acck;
+                        dg[ok + t * sk + i] = a * accg;
+                        for (int j = 0; j < dv; ++j) E[i * dv + j] = a * dS[i * dv + j];
+                    }
+                }
+            }
+            if (dS0) memcpy(dS0 + bh * ss, E, sizeof(double) * ss);
+            free(ckpt); free(Sblk); free(S); free(E); free(dS);
+        }
 }

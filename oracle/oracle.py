@@ -43,6 +43,8 @@ def _load():
         lib.oracle_state_scan.restype = None
         lib.oracle_apply_init_state.argtypes = [ci] * 6 + [dp] * 3 + [cd] + [dp]
         lib.oracle_apply_init_state.restype = None
+        lib.oracle_gla_recurrent_bwd.argtypes = [ci] * 5 + [dp] * 4 + [cd] + [dp] * 8
+        lib.oracle_gla_recurrent_bwd.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ci
         _lib = lib
@@ -75,6 +77,27 @@ def gla_recurrent(q, k, v, g, scale=1.0, S0=None):
     _load().oracle_gla_recurrent(B, T, H, dk, dv, _p(q), _p(k), _p(v), _p(g), float(scale),
                                  _p(S0), _p(o), _p(Sf))
     return o, Sf
+
+
+def gla_recurrent_bwd(q, k, v, g, dO, scale=1.0, S0=None, dS_T=None):
+    """Gradients of sum(o * dO) + sum(S_T * dS_T) for the unsegmented recurrence (App. A.4 computes
+    the same quantities chunkwise).  Returns (dq, dk, dv, dg, dS0 [B,H,d_k,d_v])."""
+    q, k, v, g, dO = _c(q), _c(k), _c(v), _c(g), _c(dO)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == q.shape and g.shape == q.shape and v.shape == (B, T, H, dv) and dO.shape == v.shape
+    if S0 is not None:
+        S0 = _c(S0)
+        assert S0.shape == (B, H, dk, dv)
+    if dS_T is not None:
+        dS_T = _c(dS_T)
+        assert dS_T.shape == (B, H, dk, dv)
+    dq, dkk, dg = np.empty_like(q), np.empty_like(q), np.empty_like(q)
+    dvv = np.empty_like(v)
+    dS0 = np.empty((B, H, dk, dv))
+    _load().oracle_gla_recurrent_bwd(B, T, H, dk, dv, _p(q), _p(k), _p(v), _p(g), float(scale), _p(S0),
+                                     _p(dO), _p(dS_T), _p(dq), _p(dkk), _p(dvv), _p(dg), _p(dS0))
+    return dq, dkk, dvv, dg, dS0
 
 
 def gla_local(q, k, v, g, P, scale=1.0):

@@ -81,7 +81,9 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *desc, const void *q, const v
  *   out  S_init [P,BH,d_k,d_v] fp32,  S_last [BH,d_k,d_v] fp32 or NULL (= state after segment P-1)
  * K_blocks: number of contiguous d_k-row blocks the state is split into (d_k % K_blocks == 0);
  * each block is an independent slab and the result is bitwise independent of K_blocks.
- * direction: 0 = forward chain; 1 (reverse chain of the backward pass) -> ZECO_ERR_UNSUPPORTED.
+ * direction: 0 = forward chain.  1 = the backward direction of Alg. 2: the chain runs from the last
+ *   segment to the first, S_init[p] = what enters segment p from segment p+1 (S0 enters the last
+ *   segment), S_last = what leaves segment 0; used for the state gradients of App. A.4.
  * d_v % 4 == 0 required; any d_k >= 1. */
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
                             const float *S_loc, const float *G_tot, const float *S0,
@@ -124,6 +126,44 @@ size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc);
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *desc, const void *q, const void *k, const void *v,
                                const void *g, const float *S0, void *o, float *S_last,
                                void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---- Backward pass (App. A.4): gradients of  sum_t <o_t, dO_t> + <S_T, dS_T>  for the forward above.
+ * bf16 q/k/v/dO and gradients only (fp32 returns ZECO_ERR_UNSUPPORTED).  dO, dv use the layout of v;
+ * dq, dk the layout of q; dg [B,T,H,d_k] fp32 contiguous; all state arrays fp32.  The state gradients
+ * are true gradients (they include `scale`). --------------------------------------------------------- */
+
+/* First loop of the backward listing: per segment, from dS = 0, last chunk to first,
+ *   dS <- (gamma^T 1) .* dS + (Q .* Lambda)^T dO * scale
+ * and what is left after the segment's first token, decayed past it: the gradient this segment sends
+ * to the final state of the segment before it.
+ *   out  dS_loc [P,B,H,d_k,d_v] fp32.
+ * Chained by zeco_state_scan(direction = 1) with the same G_tot as the forward chain. */
+zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *desc, const void *q, const void *g, const void *dO,
+                                float *dS_loc, void *stream);
+
+/* The remaining loops of the backward listing, for every segment p, given the forward state S_init[p]
+ * entering it, the forward state after the last segment (S_last), and dS_in[p], the gradient entering
+ * its final state (zeco_state_scan, direction = 1):
+ *   dq, dk, dv as in App. A.4 (the chunk states S_[n], dS_[n] are recomputed on chip, never stored);
+ *   dg_t = sum over the segment's tokens s >= t of (q_s .* dq_s - k_s .* dk_s)
+ *          + row sums of dS_in[p] .* S_end[p],  S_end[p] = S_init[p+1] (S_last for the last segment):
+ *          the reverse cumulative sum of the listing's last line, carried across segments. */
+zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *desc, const void *q, const void *k,
+                                    const void *v, const void *g, const void *dO, const float *S_init,
+                                    const float *S_last, const float *dS_in, void *dq, void *dk,
+                                    void *dv, float *dg, void *stream);
+
+/* The whole backward in one call: recomputes the forward segment states (phase 1 and its scan, from
+ * S0), runs the state-gradient pass and its reverse scan (from dS_T), then the gradient passes.  Like
+ * zeco_gla_fused_fwd it may cut the segments into shorter pieces.
+ *   in   S0, dS_T [B,H,d_k,d_v] fp32 or NULL (zero)
+ *   out  dq, dk, dv, dg;  dS0 [B,H,d_k,d_v] fp32 or NULL: gradient of the state entering the first segment
+ * workspace: zeco_gla_fused_bwd_workspace(desc) bytes of device memory, 16-byte aligned. */
+size_t zeco_gla_fused_bwd_workspace(const zeco_gla_desc *desc);
+zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *desc, const void *q, const void *k, const void *v,
+                               const void *g, const void *dO, const float *S0, const float *dS_T,
+                               void *dq, void *dk, void *dv, float *dg, float *dS0, void *workspace,
+                               size_t workspace_bytes, void *stream);
 
 /* Bandwidth calibration utility (not part of the method): copies `bytes` (a multiple of 16) from
  * src to dst with a plain grid-stride kernel of 16-byte accesses.  Used to scale the HBM byte

@@ -1,0 +1,515 @@
+// Backward of the chunkwise GLA forward for the two gated operands (App. A.4): dQ and dK, and the
+// gate gradient dG.  bf16 inputs and outputs, bf16 MFMA operands, fp32 accumulation and states.
+//
+// Both gradients have the shape of the forward output pass with the operands in other roles.  With
+// Lambda the in-chunk cumulative decay, gamma the chunk decay, S the forward state entering a chunk,
+// dS the state gradient entering it from the later chunks, dA = mask(dO V^T) (shared by both):
+//   dQ_t = Lambda_t   .* [ dO_t S^T                    + sum_{s<=t} dA_ts (K_s / Lambda_s) ]      forward over chunks
+//   dK_s = 1/Lambda_s .* [ V_s ((gamma^T 1) .* dS)^T   + sum_{t>=s} dA_ts (Q_t .* Lambda_t) ]    backward over chunks
+// i.e.  out_r = F_r .* [ X_r W + sum_{r'<=r} (X_r . Y_r') Z~_r' ]  with
+//   dQ: X = dO, Y = V, Z~ = K / Lambda, F = Lambda,     W = S^T,   W <- (W + Y^T Z~) .* gamma (columns)
+//   dK: X = V, Y = dO, Z~ = Q .* Lambda, F = 1/Lambda,  W = dS^T,  W <- gamma .* W first, then W += Y^T Z~
+// where for dK the chunks are visited last to first and token t of a chunk sits at tile row 63 - t,
+// which turns "t >= s" into the causal mask of the forward pass.  W (d_v x d_k, the transposed state)
+// stays in MFMA accumulators; wave w owns the 16 output channels [16w, 16w+16).  The gated dimension
+// d_k is the OUTPUT dimension here, so the decay acts on the columns of W (one scalar per lane) and
+// the factor F must be applied to the finished tile element by element: the gate pass leaves it in
+// LDS in fp32.
+//
+// One workgroup of d_k/16 waves owns a (batch, segment, head) stream; all waves take part in the gate
+// pass and in the matrix products of a chunk, one after the other, on single-buffered LDS tiles; the
+// raw inputs of the next chunk are fetched into registers while the current one is processed.
+//
+// dG (last line of the backward listing of App. A.4): dG_t = sum over later tokens s >= t of
+// (Q_s .* dQ_s - K_s .* dK_s).  Inside one segment this is a reverse cumulative sum; what the later
+// segments contribute is the constant row_sum(dS_end .* S_end) of the segment's final state and its
+// gradient, which follows from unrolling the recurrence of dS one step past the segment boundary.
+#include "zeco_device.h"
+#include "zeco_internal.h"
+
+namespace zeco {
+
+template <int DK, int DV> struct QKCfg {
+    static constexpr int NW = DK / 16;             // waves, 16 output channels each
+    static constexpr int NT = 64 * NW;
+    static constexpr int NIT = DV / 16;            // row tiles of W per wave
+    // gate pass over the gated operand: 4 channels x TPT consecutive tokens per thread
+    static constexpr int CQ = DK / 4;
+    static constexpr int GW = 64 / CQ;             // token groups inside one wave
+    static constexpr int TG = NT / CQ;             // token groups
+    static constexpr int TPT = 64 / TG;
+    // copy pass over X and Y: 4 channels x TPTV consecutive tokens per thread
+    static constexpr int VQ = DV / 4;
+    static constexpr int TPTV = 64 / (NT / VQ);
+    // LDS (bytes)
+    static constexpr int XS = DV * 2 + 16;         // row stride of Xs, Ys (token-major)
+    static constexpr int TS = 64 * 2 + 16;         // row stride of Yt, Zt, Ps (64 tokens per row)
+    static constexpr int FS = DK * 4 + 16;         // row stride of Fs (fp32)
+    static constexpr int kOffX = 0;
+    static constexpr int kOffY = kOffX + 64 * XS;
+    static constexpr int kOffYT = kOffY + 64 * XS;
+    static constexpr int kOffZT = kOffYT + DV * TS;
+    static constexpr int kOffP = kOffZT + DK * TS;
+    static constexpr int kOffF = kOffP + 64 * TS;
+    static constexpr int kOffTot = kOffF + 64 * FS;
+    static constexpr int kOffGam = kOffTot + NW * DK * 4;
+    static constexpr int kBytes = kOffGam + DK * 4;
+
+    // LDS position of contraction channel j inside an Xs / Ys row.  A lane of a 16x16 accumulator
+    // tile owns rows 4 kg .. 4 kg + 3; the rows it owns in two adjacent tiles of W serve as its eight
+    // k-slots of the 16x16x32 MFMA, so channel 16 q + 4 kg + m of a block of 32 sits at 8 kg + 4 q + m.
+    __device__ static __forceinline__ constexpr int pos_of_channel(int j) {
+        const int jl = j % 32;
+        return (j - jl) + 8 * ((jl / 4) % 4) + 4 * (jl / 16) + (jl % 4);
+    }
+};
+
+template <bool GBF16> struct GateRaw;
+template <> struct GateRaw<false> {
+    typedef f32x4 raw_t;
+    __device__ static __forceinline__ f32x4 get(raw_t r) { return r; }
+};
+template <> struct GateRaw<true> {
+    typedef u32x2 raw_t;
+    __device__ static __forceinline__ f32x4 get(raw_t r) {
+        return f32x4{bf16_lo(r[0]), bf16_hi(r[0]), bf16_lo(r[1]), bf16_hi(r[1])};
+    }
+};
+
+// N consecutive bf16 values (two per word) stored as one LDS write.
+template <int N> struct Run;
+template <> struct Run<8> {
+    uint32_t w[4];
+    __device__ __forceinline__ void store(unsigned char *dst) const {
+        *reinterpret_cast<u32x4 *>(dst) = u32x4{w[0], w[1], w[2], w[3]};
+    }
+};
+template <> struct Run<4> {
+    uint32_t w[2];
+    __device__ __forceinline__ void store(unsigned char *dst) const {
+        *reinterpret_cast<u32x2 *>(dst) = u32x2{w[0], w[1]};
+    }
+};
+template <> struct Run<2> {
+    uint32_t w[1];
+    __device__ __forceinline__ void store(unsigned char *dst) const {
+        *reinterpret_cast<uint32_t *>(dst) = w[0];
+    }
+};
+
+// (x.lo, y.lo) and (x.hi, y.hi) of two packed bf16 pairs.
+__device__ __forceinline__ uint32_t lo_pair(uint32_t x, uint32_t y) {
+    return __builtin_amdgcn_perm(y, x, 0x05040100u);
+}
+__device__ __forceinline__ uint32_t hi_pair(uint32_t x, uint32_t y) {
+    return __builtin_amdgcn_perm(y, x, 0x07060302u);
+}
+
+__device__ __forceinline__ bf16x8 pack2x4(f32x4 a, f32x4 b) {
+    u32x4 w = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]),
+               pack_bf16(b[2], b[3])};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+// REV = false: dQ (x = dO, y = v, z = k, W_init = forward states; the query scale multiplies the
+// output).  REV = true: dK (x = v, y = dO, z = q, W_init = state gradients entering each segment's
+// final state; the query scale rides on Q .* Lambda, so that the running dS is the true gradient).
+template <int DK, int DV, bool REV, bool GBF16>
+__global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
+    typedef QKCfg<DK, DV> Cfg;
+    typedef Mma<16> M;
+    typedef GateRaw<GBF16> GV;
+    constexpr int XS = Cfg::XS, TS = Cfg::TS, FS = Cfg::FS, NW = Cfg::NW, NT = Cfg::NT;
+    constexpr int TPT = Cfg::TPT, TPTV = Cfg::TPTV, CQ = Cfg::CQ, GW = Cfg::GW;
+    constexpr int GB = GBF16 ? 2 : 4;
+    constexpr float kLog2e = 1.4426950408889634f;
+    constexpr float SZ = REV ? 1.f : -1.f;   // exponent sign of the operand Z~; the factor F takes the other
+    extern __shared__ __align__(16) unsigned char lds[];
+    unsigned char *Xs = lds + Cfg::kOffX, *Ys = lds + Cfg::kOffY, *Yt = lds + Cfg::kOffYT;
+    unsigned char *Zt = lds + Cfg::kOffZT, *Ps = lds + Cfg::kOffP, *Fs = lds + Cfg::kOffF;
+    float *wtot = reinterpret_cast<float *>(lds + Cfg::kOffTot);   // [wave][channel] gate sums
+    float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // chunk decay [channel]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int N = p.n_chunks;
+    auto chunk_of = [&](int m) { return REV ? N - 1 - m : m; };
+    auto pos_of = [](int t) { return REV ? 63 - t : t; };
+
+    // workgroup -> stream, dealt so that consecutive streams land on different XCDs
+    const size_t sbh = blockIdx.x;                  // (seg * B + b) * H + h
+    int sidx = blockIdx.x;
+    const int h = sidx % p.H;
+    sidx /= p.H;
+    const int b = sidx % p.B, seg = sidx / p.B;
+    const long long tok0 = (long long)seg * p.L;
+    const long long kbase = b * p.sb + tok0 * p.st + h * p.sh;
+    const long long vbase = b * p.vb + tok0 * p.vt + h * p.vh;
+    const unsigned char *xb = (const unsigned char *)p.x + vbase * 2;
+    const unsigned char *yb = (const unsigned char *)p.y + vbase * 2;
+    const unsigned char *zb = (const unsigned char *)p.z + kbase * 2;
+    const unsigned char *gb = (const unsigned char *)p.g + kbase * GB;
+    unsigned char *ob = (unsigned char *)p.out + kbase * 2;
+    const long long st = p.st, vt = p.vt;
+
+    // gate-pass coordinates (z, g) and copy-pass coordinates (x, y)
+    const int cq = lane % CQ, gl = lane / CQ, tq = w * GW + gl;
+    const int vq = tid % Cfg::VQ, tv = tid / Cfg::VQ;
+    const int xpos = Cfg::pos_of_channel(4 * vq);
+
+    // W^T tile init: Sacc[it][rr] = W[row 16 it + 4 kg + rr][col 16 w + l16] = W_init[col][row]
+    f32x4 Sacc[Cfg::NIT];
+    {
+        const float *Wi = p.W_init + sbh * DK * DV + (size_t)(w * 16 + l16) * DV + 4 * kg;
+#pragma unroll
+        for (int it = 0; it < Cfg::NIT; ++it) Sacc[it] = *reinterpret_cast<const f32x4 *>(Wi + it * 16);
+    }
+
+    // Score tiles above the diagonal are never computed: zero them once.
+    for (int e = tid; e < 64 * TS / 16; e += NT)
+        *reinterpret_cast<u32x4 *>(Ps + e * 16) = u32x4{0u, 0u, 0u, 0u};
+
+    // raw inputs of the chunk worked on next
+    u32x2 rx[TPTV], ry[TPTV], rz[TPT];
+    typename GV::raw_t rg[TPT];
+    {
+        const long long c0 = (long long)chunk_of(0) * 64;
+#pragma unroll
+        for (int u = 0; u < TPT; ++u) {
+            rz[u] = *reinterpret_cast<const u32x2 *>(zb + ((c0 + tq * TPT + u) * st + 4 * cq) * 2);
+            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((c0 + tq * TPT + u) * st + 4 * cq) * GB);
+        }
+#pragma unroll
+        for (int u = 0; u < TPTV; ++u) {
+            rx[u] = *reinterpret_cast<const u32x2 *>(xb + ((c0 + tv * TPTV + u) * vt + 4 * vq) * 2);
+            ry[u] = *reinterpret_cast<const u32x2 *>(yb + ((c0 + tv * TPTV + u) * vt + 4 * vq) * 2);
+        }
+    }
+
+    for (int n = 0; n < N; ++n) {
+        const long long t0 = (long long)chunk_of(n) * 64;                          // this chunk
+        const long long t1 = (long long)chunk_of((n + 1 < N) ? n + 1 : n) * 64;    // chunk fetched meanwhile
+
+        // ---- gate pass, part 1: per-thread cumulative sums of g; X, Y, Y^T -> LDS -----------------
+        f32x4 cs[TPT];
+        f32x4 excl = {0.f, 0.f, 0.f, 0.f};
+        {
+            f32x4 run = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < TPT; ++u) {
+                const f32x4 gv = GV::get(rg[u]);
+                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((t1 + tq * TPT + u) * st + 4 * cq) * GB);
+#pragma unroll
+                for (int a = 0; a < 4; ++a) run[a] += gv[a];
+                cs[u] = run;
+            }
+            f32x4 inc = run;   // inclusive scan of the group sums over the wave's GW token groups
+#pragma unroll
+            for (int d = 1; d < GW; d <<= 1) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float up = __shfl_up(inc[a], d * CQ, 64);
+                    if (gl >= d) inc[a] += up;
+                }
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) excl[a] = inc[a] - run[a];
+            if (gl == GW - 1) *reinterpret_cast<f32x4 *>(wtot + w * DK + 4 * cq) = inc;
+        }
+        {
+            Run<TPTV> ch[4];
+#pragma unroll
+            for (int u = 0; u < TPTV; ++u) {
+                const int r = pos_of(tv * TPTV + u);
+                *reinterpret_cast<u32x2 *>(Xs + r * XS + xpos * 2) = rx[u];
+                *reinterpret_cast<u32x2 *>(Ys + r * XS + xpos * 2) = ry[u];
+            }
+#pragma unroll
+            for (int m = 0; m < TPTV / 2; ++m) {
+                // tokens (2m, 2m+1) of the run share a word; reversed, the run is written back to front
+                const u32x2 a0 = REV ? ry[2 * m + 1] : ry[2 * m], a1 = REV ? ry[2 * m] : ry[2 * m + 1];
+                const int wd = REV ? TPTV / 2 - 1 - m : m;
+                ch[0].w[wd] = lo_pair(a0[0], a1[0]);
+                ch[1].w[wd] = hi_pair(a0[0], a1[0]);
+                ch[2].w[wd] = lo_pair(a0[1], a1[1]);
+                ch[3].w[wd] = hi_pair(a0[1], a1[1]);
+            }
+#pragma unroll
+            for (int u = 0; u < TPTV; ++u) {
+                rx[u] = *reinterpret_cast<const u32x2 *>(xb + ((t1 + tv * TPTV + u) * vt + 4 * vq) * 2);
+                ry[u] = *reinterpret_cast<const u32x2 *>(yb + ((t1 + tv * TPTV + u) * vt + 4 * vq) * 2);
+            }
+            const int c0 = REV ? 64 - (tv + 1) * TPTV : tv * TPTV;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) ch[a].store(Yt + (4 * vq + a) * TS + c0 * 2);
+        }
+        __syncthreads();
+
+        // ---- gate pass, part 2: stitch waves; Z~^T and the factor tile -> LDS ----------------------
+        {
+            f32x4 pre = excl, total = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < NW; ++u) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(wtot + u * DK + 4 * cq);
+                const float sel = (u < w) ? 1.f : 0.f;   // wave-uniform
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    pre[a] = __builtin_fmaf(sel, x[a], pre[a]);
+                    total[a] += x[a];
+                }
+            }
+            Run<TPT> zt[4];
+            u32x2 zprev = {0u, 0u};
+#pragma unroll
+            for (int u = 0; u < TPT; ++u) {
+                const int t = tq * TPT + u;
+                f32x4 ez, ef;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float y = (cs[u][a] + pre[a]) * kLog2e;   // in-chunk cumulative log2 decay
+                    ez[a] = __builtin_amdgcn_exp2f(SZ * y) * p.zscale;
+                    ef[a] = __builtin_amdgcn_exp2f(-SZ * y);
+                }
+                const u32x2 zw = rz[u];
+                rz[u] = *reinterpret_cast<const u32x2 *>(zb + ((t1 + t) * st + 4 * cq) * 2);
+                const u32x2 zq = {pack_bf16(bf16_lo(zw[0]) * ez[0], bf16_hi(zw[0]) * ez[1]),
+                                  pack_bf16(bf16_lo(zw[1]) * ez[2], bf16_hi(zw[1]) * ez[3])};
+                *reinterpret_cast<f32x4 *>(Fs + pos_of(t) * FS + 16 * cq) = ef;
+                if (u % 2 == 1) {
+                    const u32x2 a0 = REV ? zq : zprev, a1 = REV ? zprev : zq;
+                    const int wd = REV ? (TPT - 1 - u) / 2 : u / 2;
+                    zt[0].w[wd] = lo_pair(a0[0], a1[0]);
+                    zt[1].w[wd] = hi_pair(a0[0], a1[0]);
+                    zt[2].w[wd] = lo_pair(a0[1], a1[1]);
+                    zt[3].w[wd] = hi_pair(a0[1], a1[1]);
+                }
+                zprev = zq;
+            }
+            const int c0 = REV ? 64 - (tq + 1) * TPT : tq * TPT;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) zt[a].store(Zt + (4 * cq + a) * TS + c0 * 2);
+            if (tq == 0) {
+                f32x4 gm;
+#pragma unroll
+                for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
+                *reinterpret_cast<f32x4 *>(gam + 4 * cq) = gm;
+            }
+        }
+        __syncthreads();
+
+        // ---- scores: P^T tiles (r' <= r), 16x16x32 over the d_v channels -----------------------------
+        const float gcol = gam[w * 16 + l16];   // decay of this lane's column of W
+        if constexpr (REV) {
+#pragma unroll
+            for (int it = 0; it < Cfg::NIT; ++it)
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) Sacc[it][rr] *= gcol;
+        }
+#pragma unroll
+        for (int i = 0; i < (10 + NW - 1) / NW; ++i) {
+            const int idx = w + NW * i;   // wave-uniform
+            if (idx < 10) {
+                const int tt = (idx >= 6) ? 3 : (idx >= 3) ? 2 : (idx >= 1) ? 1 : 0;
+                const int ts = idx - tt * (tt + 1) / 2;
+                const unsigned char *ya = Ys + (16 * ts + l16) * XS + 16 * kg;
+                const unsigned char *xf = Xs + (16 * tt + l16) * XS + 16 * kg;
+                bf16x8 fa[DV / 32], fb[DV / 32];
+#pragma unroll
+                for (int ks = 0; ks < DV / 32; ++ks) {
+                    fa[ks] = lds_frag(ya, 64 * ks);
+                    fb[ks] = lds_frag(xf, 64 * ks);
+                }
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < DV / 32; ++ks) acc = M::run(fa[ks], fb[ks], acc);
+                if (ts == tt) {
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        if (4 * kg + rr > l16) acc[rr] = 0.f;
+                }
+                *reinterpret_cast<u32x2 *>(Ps + (16 * tt + l16) * TS + (16 * ts + 4 * kg) * 2) =
+                    u32x2{pack_bf16(acc[0], acc[1]), pack_bf16(acc[2], acc[3])};
+            }
+        }
+        // ---- inter: O^T = W^T X^T with W fed from the accumulators -----------------------------------
+        f32x4 Oacc[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) Oacc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < DV / 32; ++ks) {
+            const bf16x8 sf = pack2x4(Sacc[2 * ks], Sacc[2 * ks + 1]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+                Oacc[mt] = M::run(sf, lds_frag(Xs, (mt * 16 + l16) * XS + (ks * 32 + 8 * kg) * 2), Oacc[mt]);
+        }
+        __syncthreads();
+
+        // ---- intra: O^T += Zt Ps^T over the causal range; factor, scale, store ------------------------
+        bf16x8 zf[2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) zf[ks] = lds_frag(Zt, (w * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+            for (int ks = 0; ks <= mt / 2; ++ks)
+                Oacc[mt] = M::run(zf[ks], lds_frag(Ps, (mt * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2), Oacc[mt]);
+            const int r = mt * 16 + l16;
+            const f32x4 f = *reinterpret_cast<const f32x4 *>(Fs + r * FS + (w * 16 + 4 * kg) * 4);
+            unsigned char *orow = ob + ((t0 + pos_of(r)) * st + w * 16 + 4 * kg) * 2;
+            *reinterpret_cast<u32x2 *>(orow) =
+                u32x2{pack_bf16(Oacc[mt][0] * f[0] * p.oscale, Oacc[mt][1] * f[1] * p.oscale),
+                      pack_bf16(Oacc[mt][2] * f[2] * p.oscale, Oacc[mt][3] * f[3] * p.oscale)};
+        }
+        // ---- state: W += Yt Zt^T (then the column decay in the forward direction) ---------------------
+#pragma unroll
+        for (int it = 0; it < Cfg::NIT; ++it) {
+            f32x4 acc = Sacc[it];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                acc = M::run(lds_frag(Yt, (it * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2), zf[ks], acc);
+            if constexpr (!REV) {
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) acc[rr] *= gcol;
+            }
+            Sacc[it] = acc;
+        }
+        __syncthreads();
+    }
+}
+
+// dG_t = c + sum over the segment's tokens s >= t of (q_s dq_s - k_s dk_s), c = row sums of
+// dS_end .* S_end.  One workgroup of 256 threads per stream, chunks of 64 tokens from the last to the
+// first; a thread owns 4 channels x TPT consecutive tokens.
+template <int DK>
+__global__ __launch_bounds__(256) void gla_bwd_dg_kernel(BwdDGParams p) {
+    constexpr int CQ = DK / 4, TG = 256 / CQ, TPT = 64 / TG, GW = 64 / CQ;
+    __shared__ float carry0[DK];
+    __shared__ float wtot[4][DK];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const size_t sbh = blockIdx.x;
+    int sidx = blockIdx.x;
+    const int h = sidx % p.H;
+    sidx /= p.H;
+    const int b = sidx % p.B, seg = sidx / p.B;
+    const long long tok0 = (long long)seg * p.L;
+    const long long kbase = b * p.sb + tok0 * p.st + h * p.sh;
+    const long long T = (long long)p.P * p.L;
+    float *dgb = p.dg + (((long long)b * T + tok0) * p.H + h) * DK;
+    const long long gcs = (long long)p.H * DK;
+
+    // c[i] = sum_j dS_end[i][j] S_end[i][j]
+    {
+        const float *A = p.dS_end + sbh * DK * p.d_v;
+        const float *Bm = (seg + 1 < p.P) ? p.S_init + (sbh + (size_t)p.B * p.H) * DK * p.d_v
+                                          : p.S_last + ((size_t)b * p.H + h) * DK * p.d_v;
+        for (int i = tid >> 1; i < DK; i += 128) {
+            float acc = 0.f;
+            for (int j = (tid & 1) * 4; j < p.d_v; j += 8) {
+                const f32x4 x = *reinterpret_cast<const f32x4 *>(A + (size_t)i * p.d_v + j);
+                const f32x4 y = *reinterpret_cast<const f32x4 *>(Bm + (size_t)i * p.d_v + j);
+                acc += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
+            }
+            acc += __shfl_xor(acc, 1, 64);
+            if ((tid & 1) == 0) carry0[i] = acc;
+        }
+    }
+    __syncthreads();
+    const int cq = lane % CQ, gl = lane / CQ, tq = w * GW + gl;
+    f32x4 carry = *reinterpret_cast<const f32x4 *>(carry0 + 4 * cq);   // sum over all later chunks
+    const uint16_t *qp = (const uint16_t *)p.q + kbase, *kp = (const uint16_t *)p.k + kbase;
+    const uint16_t *dqp = (const uint16_t *)p.dq + kbase, *dkp = (const uint16_t *)p.dk + kbase;
+
+    for (int n = p.n_chunks - 1; n >= 0; --n) {
+        const long long t0 = (long long)n * 64 + tq * TPT;
+        f32x4 d[TPT];
+#pragma unroll
+        for (int u = 0; u < TPT; ++u) {
+            const long long off = (t0 + u) * p.st + 4 * cq;
+            const u32x2 a = *reinterpret_cast<const u32x2 *>(qp + off);
+            const u32x2 da = *reinterpret_cast<const u32x2 *>(dqp + off);
+            const u32x2 c = *reinterpret_cast<const u32x2 *>(kp + off);
+            const u32x2 dc = *reinterpret_cast<const u32x2 *>(dkp + off);
+            d[u] = f32x4{bf16_lo(a[0]) * bf16_lo(da[0]) - bf16_lo(c[0]) * bf16_lo(dc[0]),
+                         bf16_hi(a[0]) * bf16_hi(da[0]) - bf16_hi(c[0]) * bf16_hi(dc[0]),
+                         bf16_lo(a[1]) * bf16_lo(da[1]) - bf16_lo(c[1]) * bf16_lo(dc[1]),
+                         bf16_hi(a[1]) * bf16_hi(da[1]) - bf16_hi(c[1]) * bf16_hi(dc[1])};
+        }
+        // in-thread suffix sums, then the sums of the later token groups: inside the wave by
+        // shuffles, across waves through LDS
+        f32x4 run = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = TPT - 1; u >= 0; --u) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) run[a] += d[u][a];
+            d[u] = run;
+        }
+        f32x4 inc = run;   // inclusive suffix scan over the wave's token groups
+#pragma unroll
+        for (int s = 1; s < GW; s <<= 1) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                const float dn = __shfl_down(inc[a], s * CQ, 64);
+                if (gl + s < GW) inc[a] += dn;
+            }
+        }
+        if (gl == 0) *reinterpret_cast<f32x4 *>(&wtot[w][4 * cq]) = inc;
+        __syncthreads();
+        f32x4 later = carry, total = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int a = 0; a < 4; ++a) later[a] += inc[a] - run[a];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(&wtot[u][4 * cq]);
+            const float sel = (u > w) ? 1.f : 0.f;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                later[a] = __builtin_fmaf(sel, x[a], later[a]);
+                total[a] += x[a];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < TPT; ++u) {
+            f32x4 o;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) o[a] = d[u][a] + later[a];
+            *reinterpret_cast<f32x4 *>(dgb + (t0 + u) * gcs + 4 * cq) = o;
+        }
+#pragma unroll
+        for (int a = 0; a < 4; ++a) carry[a] += total[a];
+        __syncthreads();
+    }
+}
+
+template <int DK, int DV, bool REV, bool GBF16>
+static hipError_t launch_qk(const BwdQKParams &p, hipStream_t s) {
+    typedef QKCfg<DK, DV> Cfg;
+    auto kern = gla_bwd_qk_kernel<DK, DV, REV, GBF16>;
+    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, dim3(p.B * p.P * p.H), dim3(Cfg::NT), Cfg::kBytes, s, p);
+    return hipGetLastError();
+}
+
+template <bool REV, bool GBF16>
+static hipError_t dispatch_qk(const BwdQKParams &p, int d_k, int d_v, hipStream_t s) {
+    if (d_k == 64 && d_v == 64) return launch_qk<64, 64, REV, GBF16>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_qk<128, 64, REV, GBF16>(p, s);
+    if (d_k == 64 && d_v == 128) return launch_qk<64, 128, REV, GBF16>(p, s);
+    if (d_k == 128 && d_v == 128) return launch_qk<128, 128, REV, GBF16>(p, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, bool g_bf16, bool reverse, hipStream_t s) {
+    if (reverse) return g_bf16 ? dispatch_qk<true, true>(p, d_k, d_v, s) : dispatch_qk<true, false>(p, d_k, d_v, s);
+    return g_bf16 ? dispatch_qk<false, true>(p, d_k, d_v, s) : dispatch_qk<false, false>(p, d_k, d_v, s);
+}
+
+hipError_t launch_bwd_dg(const BwdDGParams &p, int d_k, hipStream_t s) {
+    if (d_k == 64) hipLaunchKernelGGL(gla_bwd_dg_kernel<64>, dim3(p.B * p.P * p.H), dim3(256), 0, s, p);
+    else if (d_k == 128) hipLaunchKernelGGL(gla_bwd_dg_kernel<128>, dim3(p.B * p.P * p.H), dim3(256), 0, s, p);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+}  // namespace zeco

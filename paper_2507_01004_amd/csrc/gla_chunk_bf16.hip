@@ -137,7 +137,17 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 //            (Alg. 1's chunk-state loop; q is not read, nothing per token is written)
 //   kOutput  the output pass from given initial states S_init[p]: o only
 //            (Alg. 1's output pass, the incoming state folded into the running state)
-enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2 };
+// and two passes of the backward (App. A.4), which walk the chunks of a segment from the last to the
+// first and keep dS, the gradient of the running state, in the accumulators:
+//   kDState  dS <- (gamma^T 1) .* dS + (Q .* Lambda)^T dO from zero; S_loc receives the gradient that
+//            leaves the segment towards the state entering it (first loop of the backward listing)
+//   kDV      dV = (K / Lambda) ((gamma^T 1) .* dS) + (intra-chunk scores)^T dO, with dS started from
+//            S_init[p] = the gradient entering the segment's final state
+// The backward modes are called with the tensors in other roles (kDState: k := q, v := dO;
+// kDV: q := k, k := q, v := dO, o := dV), flip the sign of the decay exponents, apply gamma before the
+// chunk's products instead of after, and store token t of a chunk at tile row 63 - t, so that the
+// causal structure of the tiles is the one of the forward pass.
+enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4 };
 
 template <int DK, int DV, int NS, bool GBF16, int MODE>
 __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParams p) {
@@ -147,6 +157,10 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
     constexpr int QS = Cfg::QS, TS = Cfg::TS, NWM = Cfg::NWM, NT = Cfg::NT;
     constexpr int TPT = Cfg::TPT, TPTV = Cfg::TPTV, CQ = Cfg::CQ, GW = Cfg::GW;
     constexpr int GB = GBF16 ? 2 : 4;   // bytes per gate element
+    constexpr bool REV = MODE == kDState || MODE == kDV;          // chunks and tokens in reverse
+    constexpr bool NOQ = MODE == kStates || MODE == kDState;      // only the state is computed
+    constexpr bool FROM_INIT = MODE == kOutput || MODE == kDV;    // start from S_init, emit no state
+    constexpr float SGN = REV ? -1.f : 1.f;                       // sign of the decay exponents
     constexpr float kLog2e = 1.4426950408889634f;
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *Ps = lds + Cfg::kOffP;
@@ -156,6 +170,8 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known uniform
     const int N = p.n_chunks;
+    auto chunk_of = [&](int m) { return REV ? N - 1 - m : m; };   // m-th chunk in processing order
+    auto pos_of = [](int t) { return REV ? 63 - t : t; };         // tile row of token t of a chunk
 
     // Workgroup -> (stream, slice).  Workgroup ids are dealt round-robin to the 8 XCDs, so sibling
     // slices of a stream take consecutive slots of one XCD and share its L2 for q, k, g.
@@ -184,6 +200,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         const unsigned char *kb = (const unsigned char *)p.k + kbase * 2;
         const unsigned char *gb = (const unsigned char *)p.g + kbase * GB;
         const unsigned char *vb = (const unsigned char *)p.v + vbase * 2;
+        const long long c0 = (long long)chunk_of(0) * 64;   // first token of the first chunk processed
         const long long T = (long long)p.P * p.L;
         unsigned char *Gb = (unsigned char *)(p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK);
         const unsigned gcs = (unsigned)(p.H * DK);
@@ -205,12 +222,12 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         typename GV::raw_t rg[TPT];
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
-            if constexpr (MODE != kStates) rq[u] = *reinterpret_cast<const u32x2 *>(qb + (size_t)(u * st) * 2 + q_b0);
-            rk[u] = *reinterpret_cast<const u32x2 *>(kb + (size_t)(u * st) * 2 + q_b0);
-            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (size_t)(u * st) * GB + g_in_b0);
+            if constexpr (!NOQ) rq[u] = *reinterpret_cast<const u32x2 *>(qb + (c0 + u) * st * 2 + q_b0);
+            rk[u] = *reinterpret_cast<const u32x2 *>(kb + (c0 + u) * st * 2 + q_b0);
+            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (c0 + u) * st * GB + g_in_b0);
         }
 #pragma unroll
-        for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vb + (size_t)(u * vt) * 2 + v_b0);
+        for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vb + (c0 + u) * vt * 2 + v_b0);
 
         // Log decay of the previous chunks for this thread's 4 channels, as an unevaluated sum.
         f32x4 seg_hi = {0.f, 0.f, 0.f, 0.f}, seg_lo = {0.f, 0.f, 0.f, 0.f};
@@ -219,7 +236,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
 
         // part 1 of chunk m: per-thread cumulative sums and gate sums
         auto gate_a = [&](int m) __attribute__((always_inline)) {
-            const int nn = (m + 1 < N) ? m + 1 : N - 1;
+            const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
             const unsigned char *gn = gb + (long long)nn * 64 * st * GB;   // uniform
             f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -245,21 +262,24 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         };
         // V^T of chunk m -> tile buffer
         auto vt_store = [&](int m, unsigned char *tile) __attribute__((always_inline)) {
-            const int nn = (m + 1 < N) ? m + 1 : N - 1;
+            const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
             const unsigned char *vn = vb + (long long)nn * 64 * vt * 2;   // uniform
             TokenRun<TPTV> ch[4];
 #pragma unroll
             for (int mm = 0; mm < TPTV / 2; ++mm) {
-                const u32x2 x = rv[2 * mm], y = rv[2 * mm + 1];
-                ch[0].w[mm] = pair_lo(x[0], y[0]);
-                ch[1].w[mm] = pair_hi(x[0], y[0]);
-                ch[2].w[mm] = pair_lo(x[1], y[1]);
-                ch[3].w[mm] = pair_hi(x[1], y[1]);
+                // tokens (2mm, 2mm+1) of the run share a word; reversed, the run is written back to front
+                const u32x2 x = REV ? rv[2 * mm + 1] : rv[2 * mm], y = REV ? rv[2 * mm] : rv[2 * mm + 1];
+                const int wd = REV ? TPTV / 2 - 1 - mm : mm;
+                ch[0].w[wd] = pair_lo(x[0], y[0]);
+                ch[1].w[wd] = pair_hi(x[0], y[0]);
+                ch[2].w[wd] = pair_lo(x[1], y[1]);
+                ch[3].w[wd] = pair_hi(x[1], y[1]);
             }
 #pragma unroll
             for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vn + (size_t)(u * vt) * 2 + v_b0);
+            const int p0 = REV ? 64 - (tv + 1) * TPTV : tv * TPTV;   // first tile column of the run
 #pragma unroll
-            for (int a = 0; a < 4; ++a) ch[a].store(tile + Cfg::kOffVT + (4 * vq + a) * TS + tv * TPTV * 2);
+            for (int a = 0; a < 4; ++a) ch[a].store(tile + Cfg::kOffVT + (4 * vq + a) * TS + p0 * 2);
         };
 
         // part 2 of chunk m: stitch waves (setup), scale q and k -> tile buffer and G_cum -> HBM in two
@@ -289,7 +309,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         auto gate_b_half = [&](int m, int half, unsigned char *tile) __attribute__((always_inline)) {
             constexpr int HT = TPT / 2;
             unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK, *Kt = tile + Cfg::kOffKT;
-            const int nn = (m + 1 < N) ? m + 1 : N - 1;
+            const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
             const unsigned char *qn = qb + (long long)nn * 64 * st * 2;   // uniform
             const unsigned char *kn = kb + (long long)nn * 64 * st * 2;
             unsigned char *Gm = Gb + (long long)m * 64 * gcs * 4;
@@ -303,28 +323,31 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
                     yv[a] = __builtin_fmaf(cs[u][a], kLog2e, pre2[a]);
-                    ilam[a] = __builtin_amdgcn_exp2f(-yv[a]);
+                    ilam[a] = __builtin_amdgcn_exp2f(-SGN * yv[a]);
+                    if constexpr (REV) ilam[a] *= p.kscale;   // the query scale rides on Q .* Lambda
                 }
                 const u32x2 kw = rk[u];
                 rk[u] = *reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0);
                 const u32x2 kq = {pack_bf16(bf16_lo(kw[0]) * ilam[0], bf16_hi(kw[0]) * ilam[1]),
                                   pack_bf16(bf16_lo(kw[1]) * ilam[2], bf16_hi(kw[1]) * ilam[3])};
-                if constexpr (MODE != kStates) {   // scores and outputs need Q .* Lambda and token-major K / Lambda
+                if constexpr (!NOQ) {   // scores and outputs need Q .* Lambda and token-major K / Lambda
                     f32x4 lam;
 #pragma unroll
-                    for (int a = 0; a < 4; ++a) lam[a] = __builtin_amdgcn_exp2f(yv[a]);
+                    for (int a = 0; a < 4; ++a) lam[a] = __builtin_amdgcn_exp2f(SGN * yv[a]);
                     const u32x2 qw = rq[u];
                     rq[u] = *reinterpret_cast<const u32x2 *>(qn + (size_t)(u * st) * 2 + q_b0);
-                    *reinterpret_cast<u32x2 *>(Qs + t * QS + qpos * 2) =
+                    *reinterpret_cast<u32x2 *>(Qs + pos_of(t) * QS + qpos * 2) =
                         u32x2{pack_bf16(bf16_lo(qw[0]) * lam[0], bf16_hi(qw[0]) * lam[1]),
                               pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};
-                    *reinterpret_cast<u32x2 *>(Ks + t * QS + qpos * 2) = kq;
+                    *reinterpret_cast<u32x2 *>(Ks + pos_of(t) * QS + qpos * 2) = kq;
                 }
                 if (uu % 2 == 1) {   // transpose: tokens (u-1, u) of each channel share a word
-                    kt[0].w[uu / 2] = pair_lo(kprev[0], kq[0]);
-                    kt[1].w[uu / 2] = pair_hi(kprev[0], kq[0]);
-                    kt[2].w[uu / 2] = pair_lo(kprev[1], kq[1]);
-                    kt[3].w[uu / 2] = pair_hi(kprev[1], kq[1]);
+                    const u32x2 x = REV ? kq : kprev, y = REV ? kprev : kq;
+                    const int wd = REV ? (HT - 1 - uu) / 2 : uu / 2;
+                    kt[0].w[wd] = pair_lo(x[0], y[0]);
+                    kt[1].w[wd] = pair_hi(x[0], y[0]);
+                    kt[2].w[wd] = pair_lo(x[1], y[1]);
+                    kt[3].w[wd] = pair_hi(x[1], y[1]);
                 }
                 kprev = kq;
                 if constexpr (MODE == kLocal) {
@@ -336,7 +359,8 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                 }
             }
 #pragma unroll
-            for (int a = 0; a < 4; ++a) kt[a].store(Kt + (4 * cq + a) * TS + (tq * TPT + half * HT) * 2);
+            for (int a = 0; a < 4; ++a)
+                kt[a].store(Kt + (4 * cq + a) * TS + (REV ? 64 - HT - (tq * TPT + half * HT) : tq * TPT + half * HT) * 2);
         };
         auto gate_b_finish = [&](int m, float *gam_m) __attribute__((always_inline)) {
             if (tq == 0) {
@@ -345,7 +369,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                 for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
                 *reinterpret_cast<f32x4 *>(gam_m + 4 * cq) = gm;
             }
-            if constexpr (MODE == kOutput) return;   // no decay outputs in the output pass
+            if constexpr (MODE != kLocal && MODE != kStates) return;   // no decay outputs in the other passes
 #pragma unroll
             for (int a = 0; a < 4; ++a) {   // (hi, lo) += total, error-free transformation
                 const float x = total[a] + seg_lo[a];
@@ -411,7 +435,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         const int lt = lane & 31, kg = lane >> 5;       // 32x32x16 lane coordinates
         const int l16 = lane & 15, kg16 = lane >> 4;    // 16x16x32 lane coordinates (score tiles)
         unsigned char *ob = (unsigned char *)p.o + vbase * 2;
-        const unsigned o_b0 = ((unsigned)lt * vt + w * 32 + 4 * kg) * 2;   // O^T byte offset of this lane
+        const unsigned o_b0 = ((unsigned)pos_of(lt) * vt + w * 32 + 4 * kg) * 2;   // O^T byte offset of this lane
 
         f32x16 Sacc[Cfg::NIT], Oacc[2];
         float *Sl = p.S_loc + sbh * DK * (DV * NS) + slice * DV + w * 32 + lt;   // this lane's state column
@@ -420,11 +444,24 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         for (int it = 0; it < Cfg::NIT; ++it)
 #pragma unroll
             for (int rr = 0; rr < 16; ++rr)
-                Sacc[it][rr] = (MODE == kOutput) ? Si[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] : 0.f;
+                Sacc[it][rr] = FROM_INIT ? Si[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] : 0.f;
+
+        // rows of the state scaled by the chunk decay
+        auto decay_state = [&](const float *gam_n) __attribute__((always_inline)) {
+#pragma unroll
+            for (int it = 0; it < Cfg::NIT; ++it)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    const f32x4 gm = *reinterpret_cast<const f32x4 *>(gam_n + it * 32 + 8 * qd + 4 * kg);
+#pragma unroll
+                    for (int mm = 0; mm < 4; ++mm) Sacc[it][4 * qd + mm] *= gm[mm];
+                }
+        };
 
         // part 1: scores -> Ps, inter-chunk product -> Oacc
-        auto mfma_a = [&](const unsigned char *tile) __attribute__((always_inline)) {
+        auto mfma_a = [&](const unsigned char *tile, const float *gam_n) __attribute__((always_inline)) {
             const unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK;
+            if constexpr (MODE == kDV) decay_state(gam_n);
             // P^T tiles (ts <= tt), 16x16x32; all operand reads of a tile are issued up front
 #pragma unroll
             for (int i = 0; i < (10 + NWM - 1) / NWM; ++i) {
@@ -469,19 +506,20 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         // part 2 of chunk n: intra-chunk output, O store, state update
         auto mfma_b = [&](int n, const unsigned char *tile, const float *gam_n) __attribute__((always_inline)) {
             const unsigned char *Kt = tile + Cfg::kOffKT, *Vt = tile + Cfg::kOffVT;
-            unsigned char *on = ob + (long long)n * 64 * vt * 2;   // uniform
+            unsigned char *on = ob + (long long)chunk_of(n) * 64 * vt * 2;   // uniform
+            if constexpr (MODE == kDState) decay_state(gam_n);
             bf16x8 vf[4];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) vf[ks] = lds_frag(Vt, (w * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2);
             // O^T += Vt Ps^T over the causal k-range (tokens s < 32 (mt + 1))
 #pragma unroll
-            for (int mt = 0; mt < (MODE == kStates ? 0 : 2); ++mt) {
+            for (int mt = 0; mt < (NOQ ? 0 : 2); ++mt) {
 #pragma unroll
                 for (int ks = 0; ks < 2 * (mt + 1); ++ks)
                     Oacc[mt] = M::run(vf[ks], lds_frag(Ps, (mt * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), Oacc[mt]);
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd)
-                    *reinterpret_cast<u32x2 *>(on + (size_t)(mt * 32 * vt + 8 * qd) * 2 + o_b0) =
+                    *reinterpret_cast<u32x2 *>(on + ((long long)(REV ? -mt : mt) * 32 * vt + 8 * qd) * 2 + o_b0) =
                         u32x2{pack_bf16(Oacc[mt][4 * qd] * p.scale, Oacc[mt][4 * qd + 1] * p.scale),
                               pack_bf16(Oacc[mt][4 * qd + 2] * p.scale, Oacc[mt][4 * qd + 3] * p.scale)};
             }
@@ -492,11 +530,13 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
                     acc = M::run(lds_frag(Kt, (it * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), vf[ks], acc);
+                if constexpr (!REV) {
 #pragma unroll
-                for (int qd = 0; qd < 4; ++qd) {
-                    const f32x4 gm = *reinterpret_cast<const f32x4 *>(gam_n + it * 32 + 8 * qd + 4 * kg);
+                    for (int qd = 0; qd < 4; ++qd) {
+                        const f32x4 gm = *reinterpret_cast<const f32x4 *>(gam_n + it * 32 + 8 * qd + 4 * kg);
 #pragma unroll
-                    for (int mm = 0; mm < 4; ++mm) acc[4 * qd + mm] *= gm[mm];
+                        for (int mm = 0; mm < 4; ++mm) acc[4 * qd + mm] *= gm[mm];
+                    }
                 }
                 Sacc[it] = acc;
             }
@@ -507,7 +547,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         for (int n = 0; n < N; ++n) {
             const unsigned char *cur = lds + (n & 1) * Cfg::kTileBytes;
             ZPT(0);
-            if constexpr (MODE != kStates) mfma_a(cur);
+            if constexpr (!NOQ) mfma_a(cur, gam + (n & 1) * DK);
             ZPT(2);
             __syncthreads();
             ZPT(3);
@@ -517,7 +557,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
             ZPT(6);
         }
 
-        if constexpr (MODE != kOutput) {
+        if constexpr (!FROM_INIT) {
 #pragma unroll
             for (int it = 0; it < Cfg::NIT; ++it)
 #pragma unroll
@@ -559,6 +599,10 @@ hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16
         return g_bf16 ? dispatch_b16<true, kStates>(p, d_k, d_v, s) : dispatch_b16<false, kStates>(p, d_k, d_v, s);
     if (mode == kOutput)
         return g_bf16 ? dispatch_b16<true, kOutput>(p, d_k, d_v, s) : dispatch_b16<false, kOutput>(p, d_k, d_v, s);
+    if (mode == kDState)
+        return g_bf16 ? dispatch_b16<true, kDState>(p, d_k, d_v, s) : dispatch_b16<false, kDState>(p, d_k, d_v, s);
+    if (mode == kDV)
+        return g_bf16 ? dispatch_b16<true, kDV>(p, d_k, d_v, s) : dispatch_b16<false, kDV>(p, d_k, d_v, s);
     return g_bf16 ? dispatch_b16<true, kLocal>(p, d_k, d_v, s) : dispatch_b16<false, kLocal>(p, d_k, d_v, s);
 }
 

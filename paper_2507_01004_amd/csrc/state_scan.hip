@@ -1,5 +1,7 @@
 // Segment-state scan: S_init[p+1] = (exp(G_tot[p])^T 1) .* S_init[p] + S_loc[p]  (Sec. 3.2 block
-// update, applied along the chain of segments resident on one GPU).
+// update, applied along the chain of segments resident on one GPU).  With `reverse` the chain runs
+// from the last segment to the first (the backward direction of Alg. 2): S_init[p] is then what
+// enters segment p from segment p+1, and the end value is what leaves segment 0.
 //
 // Pure streaming: every state element is an independent serial chain of length P, so one thread
 // owns one float4 of a (head, d_k-row-block) slab and walks p = 0..P-1.  The loads of the next
@@ -41,14 +43,16 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
 #pragma unroll
             for (int u = 0; u < kScanDepth; ++u) {
                 if (p0 + u < p.P) {
-                    x[u] = *reinterpret_cast<const f32x4 *>(loc + (size_t)(p0 + u) * seg_stride);
-                    a[u] = gt[(size_t)(p0 + u) * g_stride];
+                    const size_t sg = p.reverse ? p.P - 1 - (p0 + u) : p0 + u;   // segment of this step
+                    x[u] = *reinterpret_cast<const f32x4 *>(loc + sg * seg_stride);
+                    a[u] = gt[sg * g_stride];
                 }
             }
 #pragma unroll
             for (int u = 0; u < kScanDepth; ++u) {
                 if (p0 + u < p.P) {
-                    *reinterpret_cast<f32x4 *>(init + (size_t)(p0 + u) * seg_stride) = s;
+                    const size_t sg = p.reverse ? p.P - 1 - (p0 + u) : p0 + u;
+                    *reinterpret_cast<f32x4 *>(init + sg * seg_stride) = s;
                     const float d = fast_exp(a[u]);
                     s[0] = __builtin_fmaf(d, s[0], x[u][0]);
                     s[1] = __builtin_fmaf(d, s[1], x[u][1]);

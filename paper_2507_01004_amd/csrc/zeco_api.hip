@@ -92,7 +92,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot; p.S_init = nullptr;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
     p.n_chunks = d->L / d->C;
-    p.scale = d->scale;
+    p.scale = d->scale; p.kscale = 1.f;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
 #ifdef ZECO_PHASE_TIMING
@@ -137,7 +137,7 @@ static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
     p.S_loc = p.G_cum = p.G_tot = nullptr; p.S_init = nullptr;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
     p.n_chunks = d->L / d->C;
-    p.scale = d->scale;
+    p.scale = d->scale; p.kscale = 1.f;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
 #ifdef ZECO_PHASE_TIMING
@@ -223,6 +223,139 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 2, s));
 }
 
+// ---- backward (App. A.4) ------------------------------------------------------------------------------
+// The passes after the two scans, over `P` pieces of `L` tokens: dQ from the forward states, dV and dK
+// from the state gradients, dG from all of them.
+static zeco_status bwd_passes(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
+                              const void *v, const void *g, const void *dO, const float *S_init,
+                              const float *S_last, const float *dS_in, void *dq, void *dk, void *dv,
+                              float *dg, hipStream_t s) {
+    const bool gb = d->g_dtype == ZECO_BF16;
+    zeco::BwdQKParams b;
+    b.g = g; b.B = d->B; b.P = P; b.H = d->H; b.L = L; b.n_chunks = L / d->C;
+    b.sb = d->stride_b; b.st = d->stride_t; b.sh = d->stride_h;
+    b.vb = d->vstride_b; b.vt = d->vstride_t; b.vh = d->vstride_h;
+    b.x = dO; b.y = v; b.z = k; b.out = dq; b.W_init = S_init; b.zscale = 1.f; b.oscale = d->scale;
+    hipError_t e = zeco::launch_bwd_qk(b, d->d_k, d->d_v, gb, false, s);
+    if (e != hipSuccess) return ZECO_ERR_HIP;
+
+    zeco::ChunkParams c;
+    fill_chunk_params(c, d);
+    c.P = P; c.L = L; c.n_chunks = L / d->C;
+    c.q = k; c.k = q; c.v = dO; c.g = g; c.o = dv; c.S_init = dS_in; c.scale = 1.f; c.kscale = d->scale;
+    if ((e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, gb, 4, s)) != hipSuccess) return ZECO_ERR_HIP;
+
+    b.x = v; b.y = dO; b.z = q; b.out = dk; b.W_init = dS_in; b.zscale = d->scale; b.oscale = 1.f;
+    if ((e = zeco::launch_bwd_qk(b, d->d_k, d->d_v, gb, true, s)) != hipSuccess) return ZECO_ERR_HIP;
+
+    zeco::BwdDGParams gp;
+    gp.q = q; gp.k = k; gp.dq = dq; gp.dk = dk; gp.dg = dg;
+    gp.dS_end = dS_in; gp.S_init = S_init; gp.S_last = S_last;
+    gp.B = d->B; gp.P = P; gp.H = d->H; gp.L = L; gp.n_chunks = L / d->C; gp.d_v = d->d_v;
+    gp.sb = d->stride_b; gp.st = d->stride_t; gp.sh = d->stride_h;
+    return from_hip(zeco::launch_bwd_dg(gp, d->d_k, s));
+}
+
+zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *d, const void *q, const void *g, const void *dO,
+                                float *dS_loc, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !g || !dO || !dS_loc) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(g) || !aligned16(dO) || !aligned16(dS_loc)) return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.k = q; p.v = dO; p.g = g; p.S_loc = dS_loc; p.kscale = d->scale;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 3,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
+                                    const void *g, const void *dO, const float *S_init, const float *S_last,
+                                    const float *dS_in, void *dq, void *dk, void *dv, float *dg,
+                                    void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !k || !v || !g || !dO || !S_init || !S_last || !dS_in || !dq || !dk || !dv || !dg)
+        return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
+        !aligned16(S_init) || !aligned16(S_last) || !aligned16(dS_in) || !aligned16(dq) || !aligned16(dk) ||
+        !aligned16(dv) || !aligned16(dg))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    return bwd_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dq, dk, dv, dg,
+                      static_cast<hipStream_t>(stream));
+}
+
+// Workspace of zeco_gla_fused_bwd, in floats: forward piece states S_loc [n], S_init [n + one more
+// slot per (b,h) for the final state], their G_tot [n]; state gradients dS_loc [n], dS_in [n].
+struct BwdLayout {
+    size_t n, state, off_Sloc, off_Sinit, off_Gtot, off_dSloc, off_dSin, total;
+};
+static BwdLayout bwd_layout(const zeco_gla_desc *d, int S) {
+    BwdLayout w;
+    const size_t bh = (size_t)d->B * d->H;
+    w.n = (size_t)d->P * S * bh;
+    w.state = (size_t)d->d_k * d->d_v;
+    w.off_Sloc = 0;
+    w.off_Sinit = w.off_Sloc + w.n * w.state;
+    w.off_Gtot = w.off_Sinit + (w.n + bh) * w.state;
+    w.off_dSloc = w.off_Gtot + w.n * d->d_k;
+    w.off_dSin = w.off_dSloc + w.n * w.state;
+    w.total = w.off_dSin + w.n * w.state;
+    return w;
+}
+
+size_t zeco_gla_fused_bwd_workspace(const zeco_gla_desc *desc) {
+    if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    return bwd_layout(desc, fused_pieces(desc)).total * sizeof(float);
+}
+
+zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
+                               const void *g, const void *dO, const float *S0, const float *dS_T,
+                               void *dq, void *dk, void *dv, float *dg, float *dS0, void *workspace,
+                               size_t workspace_bytes, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !k || !v || !g || !dO || !dq || !dk || !dv || !dg || !workspace) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
+        !aligned16(S0) || !aligned16(dS_T) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) ||
+        !aligned16(dg) || !aligned16(dS0) || !aligned16(workspace))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    if (workspace_bytes < zeco_gla_fused_bwd_workspace(d)) return ZECO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int S = fused_pieces(d);
+    const BwdLayout w = bwd_layout(d, S);
+    float *ws = static_cast<float *>(workspace);
+    float *Sloc = ws + w.off_Sloc, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot;
+    float *dSloc = ws + w.off_dSloc, *dSin = ws + w.off_dSin;
+    float *Slast = Sinit + w.n * w.state;
+    const bool gb = d->g_dtype == ZECO_BF16;
+    const int P = d->P * S, L = d->L / S;
+
+    // forward states at the piece boundaries (recomputed: phase 1 of the forward and its scan)
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.P = P; p.L = L; p.n_chunks = L / d->C;
+    p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 1, s);
+    if (e != hipSuccess) return ZECO_ERR_HIP;
+    zeco::ScanParams sp;
+    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
+    sp.P = P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+    sp.rows_per_block = d->d_k / 16;
+    if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+
+    // state gradients: local reverse pass, then the chain from the last piece to the first
+    p.k = q; p.v = dO; p.S_loc = dSloc; p.G_tot = nullptr; p.kscale = d->scale;
+    if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 3, s)) != hipSuccess) return ZECO_ERR_HIP;
+    sp.S_loc = dSloc; sp.S0 = dS_T; sp.S_init = dSin; sp.S_last = dS0; sp.reverse = 1;
+    if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+
+    return bwd_passes(d, P, L, q, k, v, g, dO, Sinit, Slast, dSin, dq, dk, dv, dg, s);
+}
+
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
                             const float *S_loc, const float *G_tot, const float *S0, float *S_init,
                             float *S_last, int32_t direction, void *stream) {
@@ -235,9 +368,9 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
         return ZECO_ERR_INVALID_ARG;
     if ((int64_t)BH * K_blocks > (int64_t)1 << 30) return ZECO_ERR_INVALID_ARG;
     if (d_v % 4 != 0) return ZECO_ERR_UNSUPPORTED;
-    if (direction == 1) return ZECO_ERR_UNSUPPORTED;
 
     zeco::ScanParams p;
+    p.reverse = direction;
     p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = S0; p.S_init = S_init; p.S_last = S_last;
     p.P = P; p.BH = BH; p.d_k = d_k; p.d_v = d_v; p.rows_per_block = d_k / K_blocks; p.groups = 1;
     return from_hip(zeco::launch_scan(p, static_cast<hipStream_t>(stream)));

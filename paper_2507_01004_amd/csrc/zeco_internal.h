@@ -13,6 +13,7 @@ struct ChunkParams {
     int B, P, H, L;
     int n_chunks;              // L / 64
     float scale;
+    float kscale;              // backward modes: multiplier carried by the operand in the k role
     long long sb, st, sh;      // q/k/g element strides
     long long vb, vt, vh;      // v/o element strides
 #ifdef ZECO_PHASE_TIMING
@@ -43,11 +44,35 @@ struct ScanParams {
     const float *S_loc, *G_tot, *S0;
     float *S_init, *S_last;
     int P, BH, d_k, d_v, rows_per_block, groups;
+    int reverse = 0;             // 1: chain runs from segment P-1 down to 0
+};
+
+// dQ / dK pass (gla_bwd_qk.hip).  x, y: [B,T,H,d_v] operands (strides vb, vt, vh); z, g, out:
+// [B,T,H,d_k] (strides sb, st, sh); W_init [P,B,H,d_k,d_v] fp32.
+struct BwdQKParams {
+    const void *x, *y, *z, *g;
+    void *out;
+    const float *W_init;
+    int B, P, H, L, n_chunks;
+    float zscale, oscale;        // multipliers of the gated operand and of the output
+    long long sb, st, sh, vb, vt, vh;
+};
+
+// dG pass.  q, k, dq, dk [B,T,H,d_k] (strides sb, st, sh); dg [B,T,H,d_k] fp32 contiguous;
+// dS_end [P,B,H,d_k,d_v], S_init [P,B,H,d_k,d_v], S_last [B,H,d_k,d_v].
+struct BwdDGParams {
+    const void *q, *k, *dq, *dk;
+    float *dg;
+    const float *dS_end, *S_init, *S_last;
+    int B, P, H, L, n_chunks, d_v;
+    long long sb, st, sh;
 };
 
 // Each returns hipSuccess or the launch error.  d_k, d_v in {64,128}.
 hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t s);
-// mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o)
+// mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
+// 3 backward state pass (k := q, v := dO; S_loc := dS leaving the segment), 4 dV pass (q := k, k := q,
+// v := dO, S_init := dS entering the segment's final state, o := dV)
 hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16, int mode, hipStream_t s);
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
@@ -55,6 +80,10 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s);
 // Per group of P segments: G_pre[g*P+p] = sum of G_tot[g*P+r] over r < p, G_sum[g] = sum over all r.
 hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, int groups, int P,
                               int BHdk, hipStream_t s);
+// reverse = false: dQ (x = dO, y = v, z = k, W_init = forward states); true: dK (x = v, y = dO, z = q,
+// W_init = state gradients)
+hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, bool g_bf16, bool reverse, hipStream_t s);
+hipError_t launch_bwd_dg(const BwdDGParams &p, int d_k, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 }  // namespace zeco

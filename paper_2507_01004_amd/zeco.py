@@ -17,8 +17,9 @@ ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ER
 ZECO_F32, ZECO_BF16 = 0, 1
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
            "zeco_apply_init_state", "zeco_gla_local_state", "zeco_gla_fwd_from_state",
-           "zeco_gla_fused_fwd_workspace", "zeco_gla_fused_fwd", "zeco_hbm_copy", "zeco_status_string",
-           "zeco_version")
+           "zeco_gla_fused_fwd_workspace", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
+           "zeco_gla_bwd_from_state", "zeco_gla_fused_bwd_workspace", "zeco_gla_fused_bwd",
+           "zeco_hbm_copy", "zeco_status_string", "zeco_version")
 
 
 class GlaDesc(ctypes.Structure):
@@ -66,6 +67,14 @@ def lib():
         L.zeco_gla_fused_fwd_workspace.restype = ctypes.c_size_t
         L.zeco_gla_fused_fwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, fp, vp, ctypes.c_size_t, vp]
         L.zeco_gla_fused_fwd.restype = i32
+        L.zeco_gla_bwd_dstate.argtypes = [dp, vp, vp, vp, fp, vp]
+        L.zeco_gla_bwd_dstate.restype = i32
+        L.zeco_gla_bwd_from_state.argtypes = [dp] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, vp]
+        L.zeco_gla_bwd_from_state.restype = i32
+        L.zeco_gla_fused_bwd_workspace.argtypes = [dp]
+        L.zeco_gla_fused_bwd_workspace.restype = ctypes.c_size_t
+        L.zeco_gla_fused_bwd.argtypes = [dp] + [vp] * 5 + [fp] * 2 + [vp] * 3 + [fp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_fused_bwd.restype = i32
         L.zeco_hbm_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.zeco_hbm_copy.restype = i32
         L.zeco_status_string.argtypes = [i32]
@@ -239,6 +248,77 @@ def gla_fused_fwd(q, k, v, g, P, scale=1.0, S0=None, C=64, out=None, workspace=N
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_gla_fused_fwd")
     return o, S_last
+
+
+def gla_bwd_dstate(q, g, dO, P, scale=1.0, C=64, out=None):
+    """zeco_gla_bwd_dstate: per segment, the state gradient it sends to the segment before it.
+    Returns dS_loc [P,B,H,d_k,d_v]."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    B, T, H, dk = q.shape
+    dv = dO.shape[-1]
+    desc = make_desc(q, dO, g, P, C, scale)
+    dS_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=q.device) if out is None else out
+    st = lib().zeco_gla_bwd_dstate(ctypes.byref(desc), _ptr(q), _ptr(g), _ptr(dO), _ptr(dS_loc), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_bwd_dstate")
+    return dS_loc
+
+
+def _grad_outputs(q, v):
+    dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    dk = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
+    dv = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
+    dg = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    return dq, dk, dv, dg
+
+
+def gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P, scale=1.0, C=64, out=None):
+    """zeco_gla_bwd_from_state: dq, dk, dv, dg of every segment from the scanned forward states and
+    state gradients.  Returns (dq, dk, dv, dg)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    _check_same_layout(v, dO)
+    desc = make_desc(q, v, g, P, C, scale)
+    dq, dk, dv, dg = _grad_outputs(q, v) if out is None else out
+    st = lib().zeco_gla_bwd_from_state(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(dO),
+                                       _ptr(S_init), _ptr(S_last), _ptr(dS_in), _ptr(dq), _ptr(dk),
+                                       _ptr(dv), _ptr(dg), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_bwd_from_state")
+    return dq, dk, dv, dg
+
+
+def fused_bwd_workspace_bytes(q, v, g, P, C=64):
+    return int(lib().zeco_gla_fused_bwd_workspace(ctypes.byref(make_desc(q, v, g, P, C, 1.0))))
+
+
+def gla_fused_bwd(q, k, v, g, dO, P, scale=1.0, S0=None, dS_T=None, C=64, out=None, workspace=None,
+                  want_dS0=True):
+    """zeco_gla_fused_bwd: the whole backward in one call.  Returns (dq, dk, dv, dg, dS0)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    _check_same_layout(v, dO)
+    B, T, H, dk_ = q.shape
+    dv_ = v.shape[-1]
+    desc = make_desc(q, v, g, P, C, scale)
+    L = lib()
+    need = L.zeco_gla_fused_bwd_workspace(ctypes.byref(desc))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    if out is None:
+        dq, dk, dv, dg = _grad_outputs(q, v)
+        dS0 = torch.empty(B, H, dk_, dv_, dtype=torch.float32, device=q.device) if want_dS0 else None
+    else:
+        dq, dk, dv, dg, dS0 = out
+    st = L.zeco_gla_fused_bwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(dO), _ptr(S0),
+                              _ptr(dS_T), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(dS0),
+                              _ptr(workspace), workspace.numel(), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_fused_bwd")
+    return dq, dk, dv, dg, dS0
 
 
 def hbm_copy(dst, src):

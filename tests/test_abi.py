@@ -88,7 +88,6 @@ def test_state_scan_rejects_bad_arguments(L):
     assert scan(S_loc=None) == zeco.ZECO_ERR_INVALID_ARG
     assert scan(S_init=ctypes.c_void_p(0x1008)) == zeco.ZECO_ERR_INVALID_ARG
     assert scan(d=2) == zeco.ZECO_ERR_INVALID_ARG
-    assert scan(d=1) == zeco.ZECO_ERR_UNSUPPORTED          # reverse chain belongs to the backward pass
     assert scan(dv=126) == zeco.ZECO_ERR_UNSUPPORTED
 
 
@@ -99,3 +98,22 @@ def test_binding_refuses_cpu_tensors():
         zeco.gla_local_fwd(q, q, q, q, 1)
     with pytest.raises(RuntimeError):
         zeco.state_scan(torch.zeros(1, 1, 64, 64), torch.zeros(1, 1, 64))
+
+
+def test_backward_entry_points_reject_bad_arguments(L):
+    d = good_desc()
+    f32 = good_desc(io_dtype=zeco.ZECO_F32)
+    ref = ctypes.byref
+    assert L.zeco_gla_bwd_dstate(ref(d), None, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_bwd_dstate(ref(f32), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED
+    assert L.zeco_gla_bwd_dstate(ref(good_desc(L=100)), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
+    args = [FAKE] * 12
+    assert L.zeco_gla_bwd_from_state(ref(f32), *args, None) == zeco.ZECO_ERR_UNSUPPORTED
+    args[7] = None                                         # dS_in missing
+    assert L.zeco_gla_bwd_from_state(ref(d), *args, None) == zeco.ZECO_ERR_INVALID_ARG
+    need = L.zeco_gla_fused_bwd_workspace(ref(d))
+    assert need > 0 and L.zeco_gla_fused_bwd_workspace(ref(f32)) == 0
+    fused = [FAKE] * 5 + [None, None] + [FAKE] * 4 + [None, FAKE]
+    assert L.zeco_gla_fused_bwd(ref(d), *fused, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
+    fused[0] = ctypes.c_void_p(0x1004)
+    assert L.zeco_gla_fused_bwd(ref(d), *fused, need, None) == zeco.ZECO_ERR_INVALID_ARG

@@ -1,0 +1,124 @@
+"""GPU parity of the backward pass (App. A.4): the HIP path through the C ABI against the fp64 oracle's
+token-by-token reverse recurrence, on seeded synthetic inputs spanning several chunks, segments, the
+d_v split and the cut into shorter pieces."""
+import zlib
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2507_01004_amd import synth, zeco
+from tests.gpu_util import TOL, dev, host, rel_err_bh
+
+pytestmark = pytest.mark.gpu
+
+# (name, B, H, P, L, d_k, d_v, g dtype)
+CASES = [
+    ("bwd_split", 1, 4, 2, 320, 128, 128, "f32"),          # 8 streams: d_v split in the dV pass, 5 chunks
+    ("bwd_whole", 2, 16, 8, 128, 128, 128, "f32"),         # 256 streams
+    ("bwd_pieces", 1, 2, 2, 1024, 128, 128, "f32"),        # fused call cuts each segment in 4
+    ("bwd_pieces_d64", 1, 1, 1, 2048, 64, 64, "bf16"),
+    ("bwd_gbf16", 1, 3, 2, 256, 128, 128, "bf16"),
+    ("bwd_onechunk", 1, 2, 4, 64, 128, 128, "f32"),
+    ("bwd_dk64_dv128", 1, 2, 2, 192, 64, 128, "f32"),
+    ("bwd_dk128_dv64", 1, 2, 2, 192, 128, 64, "bf16"),
+]
+GRADS = ("dq", "dk", "dv", "dg")
+AXES = (0, 2)
+
+
+def make(case, **kw):
+    name, B, H, P, L, dk, dv, gd = case
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=zlib.crc32(name.encode()) % 10000 + 11, io="bf16", g=gd,
+                            device="cuda", **kw)
+    gen = torch.Generator(device="cuda").manual_seed(zlib.crc32(name.encode()) % 10000 + 12)
+    inp["dO"] = torch.randn(inp["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)
+    return inp
+
+
+def oracle_bwd(inp, scale, S0=None, dS_T=None):
+    return oracle.gla_recurrent_bwd(host(inp["q"]), host(inp["k"]), host(inp["v"]), host(inp["g"]),
+                                    host(inp["dO"]), scale, S0, dS_T)
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_bwd_dstate_matches_oracle(case):
+    """Each segment's outgoing state gradient = d loss / d S0 of that segment run on its own."""
+    name, B, H, P, L, dk, dv, gd = case
+    print("case", case, flush=True)
+    inp = make(case, gate_div=64.0)
+    dS_loc = zeco.gla_bwd_dstate(inp["q"], inp["g"], inp["dO"], P, scale=0.5)
+    torch.cuda.synchronize()
+    for p in range(P):
+        sl = {n: t[:, p * L:(p + 1) * L] for n, t in inp.items()}
+        ref = oracle_bwd(sl, 0.5)[4]
+        assert rel_err_bh(host(dS_loc[p]), ref, (0, 1)) <= TOL["bf16"], p
+
+
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_fused_bwd_matches_unsegmented_oracle(case):
+    name, B, H, P, L, dk, dv, gd = case
+    print("case", case, flush=True)
+    inp = make(case, gate_div=64.0)      # slow decay: states and state gradients reach every token
+    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    for s0, dst in ((None, None), (S0, dS_T)):
+        got = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], inp["dO"], P, scale=0.5, S0=s0, dS_T=dst)
+        torch.cuda.synchronize()
+        ref = oracle_bwd(inp, 0.5, None if s0 is None else host(s0), None if dst is None else host(dst))
+        for name_, x, r in zip(GRADS, got[:4], ref[:4]):
+            assert rel_err_bh(host(x), r, AXES) <= TOL["bf16"], name_
+        assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("case", [CASES[0], CASES[4]], ids=lambda c: c[0])
+def test_bwd_building_blocks_chain(case):
+    """The calls a sequence-parallel run makes around the two All-Scans: forward states, their scan,
+    state gradients, the reverse scan, then the gradient passes, with P segments as given."""
+    name, B, H, P, L, dk, dv, gd = case
+    print("case", case, flush=True)
+    inp = make(case, gate_div=64.0)
+    q, k, v, g, dO = (inp[n] for n in ("q", "k", "v", "g", "dO"))
+    S_loc, G_tot = zeco.gla_local_state(k, v, g, P)
+    S_init, S_last = zeco.state_scan(S_loc, G_tot)
+    dS_loc = zeco.gla_bwd_dstate(q, g, dO, P, scale=0.7)
+    dS_in, dS0 = zeco.state_scan(dS_loc, G_tot, direction=1)
+    got = zeco.gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P, scale=0.7)
+    torch.cuda.synchronize()
+    ref = oracle_bwd(inp, 0.7)
+    for name_, x, r in zip(GRADS, got, ref[:4]):
+        assert rel_err_bh(host(x), r, AXES) <= TOL["bf16"], name_
+    assert rel_err_bh(host(dS0), ref[4], (0, 1)) <= TOL["bf16"]
+    # the reverse scan against the oracle's scan run on the flipped chain
+    Si_r, Sl_r = oracle.state_scan(np.flip(host(dS_loc), 0).reshape(P, B * H, dk, dv),
+                                   np.flip(host(G_tot), 0).reshape(P, B * H, dk))
+    assert rel_err_bh(host(dS_in), np.flip(Si_r, 0).reshape(P, B, H, dk, dv), (1, 2)) <= 1e-5
+    assert rel_err_bh(host(dS0), Sl_r.reshape(B, H, dk, dv), (0, 1)) <= 1e-5
+
+
+def test_bwd_zero_gate_and_strided_views():
+    """g == 0 (nothing decays, every state term at full weight), on head-sliced views of wider tensors."""
+    B, H, P, L, dk, dv = 1, 3, 2, 128, 128, 128
+    wide = synth.make_inputs(B, P * L, H + 2, dk, dv, seed=77, io="bf16", g="f32", device="cuda", zero_gate=True)
+    inp = {n: t[:, :, 1:1 + H] for n, t in wide.items()}
+    gen = torch.Generator(device="cuda").manual_seed(78)
+    inp["dO"] = torch.randn(wide["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)[:, :, 1:1 + H]
+    got = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], inp["dO"], P, scale=1.0)
+    again = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], inp["dO"], P, scale=1.0)
+    torch.cuda.synchronize()
+    ref = oracle_bwd(inp, 1.0)
+    for name_, x, y, r in zip(GRADS, got[:4], again[:4], ref[:4]):
+        assert rel_err_bh(host(x), r, AXES) <= TOL["bf16"], name_
+        assert torch.equal(x, y), name_            # no atomics: bitwise reproducible
+
+
+def test_bwd_rejects_fp32_and_small_workspace():
+    q = torch.zeros(1, 64, 1, 64, device="cuda")
+    with pytest.raises(zeco.ZecoError) as e:
+        zeco.gla_fused_bwd(q, q, q, q, q, 1)
+    assert e.value.status == zeco.ZECO_ERR_UNSUPPORTED
+    qb = q.to(torch.bfloat16)
+    with pytest.raises(zeco.ZecoError) as e:
+        zeco.gla_fused_bwd(qb, qb, qb, q, qb, 1, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == zeco.ZECO_ERR_WORKSPACE

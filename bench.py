@@ -73,6 +73,7 @@ def main():
     ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--k-blocks", type=int, default=16)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward timing")
     ap.add_argument("--layout", default="bthd", choices=["bthd", "bhtd"],
                     help="memory order of q/k/v/g/o: token-major (default) or head-major")
     ap.add_argument("--calib-copy-mib", type=int, default=1024,
@@ -148,6 +149,38 @@ def main():
                      "GBps": round(fb / fms / 1e6, 1), "hbm_frac": round(fb / fms / 1e6 / HBM_PEAK_GBS, 4)}
         del ws, o2, S_last2
 
+    # Backward of the same workload (App. A.4), whole call: reported beside the headline number.
+    backward = None
+    if c["io"] == "bf16" and not args.no_backward:
+        gen = torch.Generator(device="cuda:0").manual_seed(99)
+        dO = torch.randn(v.shape, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+        ws = torch.empty(max(zeco.fused_bwd_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
+        grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v),
+                 torch.empty(q.shape, dtype=torch.float32, device="cuda:0"), torch.empty_like(S_last))
+        for _ in range(max(1, args.warmup // 2)):
+            zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws)
+        torch.cuda.synchronize()
+        be = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        nb = max(1, args.steps // 2)
+        be[0].record()
+        for _ in range(nb):
+            zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws)
+        be[1].record()
+        torch.cuda.synchronize()
+        bms = be[0].elapsed_time(be[1]) / nb
+        gB = 4 if args.g_dtype == "f32" else 2
+        th = B * T * H
+        # bytes of the five passes as built: forward states (k, v, g), state gradients (q, g, dO), dQ (dO, v,
+        # k, q, g in; dq and fp32 q.*dq out), dV (k, q, dO, g in; dv out), dK (v, dO, q, k, g, fp32 q.*dq in;
+        # dk and fp32 dg out)
+        io = dk * 2
+        pb = th * (2 * (2 * io + dk * gB) + (5 * io + dk * gB + dk * 4) + (4 * io + dk * gB)
+                   + (5 * io + dk * gB + 2 * dk * 4))
+        backward = {"entry": "zeco_gla_fused_bwd", "ms_per_step": round(bms, 4),
+                    "tokens_per_s": round(B * T / (bms * 1e-3), 1), "pass_bytes": pb,
+                    "GBps": round(pb / bms / 1e6, 1), "hbm_frac": round(pb / bms / 1e6 / HBM_PEAK_GBS, 4)}
+        del ws, grads, dO
+
     copy_gbs = None
     if args.calib_copy_mib:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -194,6 +227,7 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((args.workload, args.g_dtype))},
         "kernels": kernels,
         "two_phase": two_phase,
+        "backward": backward,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
     }
     if not args.no_cpu:

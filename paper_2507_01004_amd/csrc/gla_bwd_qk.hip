@@ -24,6 +24,12 @@
 // (Q_s .* dQ_s - K_s .* dK_s).  Inside one segment this is a reverse cumulative sum; what the later
 // segments contribute is the constant row_sum(dS_end .* S_end) of the segment's final state and its
 // gradient, which follows from unrolling the recurrence of dS one step past the segment boundary.
+// The two products nearly cancel term by term (the sum stays of the size of one term), so they are
+// formed from the fp32 gradients before those are rounded to bf16: summing rounded terms over
+// thousands of tokens is a random walk that reaches several percent of dG.  The dQ pass leaves
+// Q .* dQ (fp32) in the dG array; the dK pass, which walks the tokens from the last to the first
+// anyway, subtracts K .* dK, accumulates and overwrites the array with dG.  Both do this one chunk
+// late, from the fp32 result tile left in LDS, in the gate pass's thread layout (coalesced rows).
 #include "zeco_device.h"
 #include "zeco_internal.h"
 
@@ -53,7 +59,9 @@ template <int DK, int DV> struct QKCfg {
     static constexpr int kOffF = kOffP + 64 * TS;
     static constexpr int kOffTot = kOffF + 64 * FS;
     static constexpr int kOffGam = kOffTot + NW * DK * 4;
-    static constexpr int kBytes = kOffGam + DK * 4;
+    static constexpr int kOffTot2 = kOffGam + DK * 4;        // [wave][channel] sums of the dG terms
+    static constexpr int kOffCarry = kOffTot2 + NW * DK * 4; // [channel] dG contribution of later segments
+    static constexpr int kBytes = kOffCarry + DK * 4;
 
     // LDS position of contraction channel j inside an Xs / Ys row.  A lane of a 16x16 accumulator
     // tile owns rows 4 kg .. 4 kg + 3; the rows it owns in two adjacent tiles of W serve as its eight
@@ -129,6 +137,8 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     unsigned char *Zt = lds + Cfg::kOffZT, *Ps = lds + Cfg::kOffP, *Fs = lds + Cfg::kOffF;
     float *wtot = reinterpret_cast<float *>(lds + Cfg::kOffTot);   // [wave][channel] gate sums
     float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // chunk decay [channel]
+    float *wtot2 = reinterpret_cast<float *>(lds + Cfg::kOffTot2);
+    float *carry0 = reinterpret_cast<float *>(lds + Cfg::kOffCarry);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -150,8 +160,11 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     const unsigned char *yb = (const unsigned char *)p.y + vbase * 2;
     const unsigned char *zb = (const unsigned char *)p.z + kbase * 2;
     const unsigned char *gb = (const unsigned char *)p.g + kbase * GB;
+    const unsigned char *z2b = (const unsigned char *)p.z2 + kbase * 2;
     unsigned char *ob = (unsigned char *)p.out + kbase * 2;
     const long long st = p.st, vt = p.vt;
+    float *dgb = p.dg + (((long long)b * p.P * p.L + tok0) * p.H + h) * DK;   // [B,T,H,d_k] contiguous
+    const long long gcs = (long long)p.H * DK;
 
     // gate-pass coordinates (z, g) and copy-pass coordinates (x, y)
     const int cq = lane % CQ, gl = lane / CQ, tq = w * GW + gl;
@@ -170,6 +183,26 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     for (int e = tid; e < 64 * TS / 16; e += NT)
         *reinterpret_cast<u32x4 *>(Ps + e * 16) = u32x4{0u, 0u, 0u, 0u};
 
+    // dG carried in from the later segments: c[i] = sum_j dS_end[i][j] S_end[i][j]  (4 threads per row)
+    f32x4 carry = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (REV) {
+        const float *A = p.W_init + sbh * DK * DV;
+        const float *Bm = (seg + 1 < p.P) ? p.S_init + (sbh + (size_t)p.B * p.H) * DK * DV
+                                          : p.S_last + ((size_t)b * p.H + h) * DK * DV;
+        const int i = tid >> 2, part = tid & 3;
+        float acc = 0.f;
+        for (int j = part * 4; j < DV; j += 16) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(A + (size_t)i * DV + j);
+            const f32x4 y = *reinterpret_cast<const f32x4 *>(Bm + (size_t)i * DV + j);
+            acc += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
+        }
+        acc += __shfl_xor(acc, 1, 64);
+        acc += __shfl_xor(acc, 2, 64);
+        if (part == 0) carry0[i] = acc;
+        __syncthreads();
+        carry = *reinterpret_cast<const f32x4 *>(carry0 + 4 * (lane % CQ));
+    }
+
     // raw inputs of the chunk worked on next
     u32x2 rx[TPTV], ry[TPTV], rz[TPT];
     typename GV::raw_t rg[TPT];
@@ -187,9 +220,76 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
     }
 
+    // dG bookkeeping of the chunk finished last: raw z2 (q for dQ, k for dK) and, for dK, the Q .* dQ terms
+    u32x2 rz2[TPT];
+    f32x4 rqd[TPT], dterm[TPT];
+    f32x4 later_in_wave = {0.f, 0.f, 0.f, 0.f};
+
+    // first half: terms from the fp32 result tile in Fs; dQ stores them, dK starts the reverse sums
+    auto dg_first = [&](long long tc) __attribute__((always_inline)) {
+        float *row = dgb + (tc + tq * TPT) * gcs + 4 * cq;
+        f32x4 run = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = TPT - 1; u >= 0; --u) {
+            const f32x4 val = *reinterpret_cast<const f32x4 *>(Fs + pos_of(tq * TPT + u) * FS + 16 * cq);
+            const u32x2 zw = rz2[u];
+            const f32x4 pr = {bf16_lo(zw[0]) * val[0], bf16_hi(zw[0]) * val[1],
+                              bf16_lo(zw[1]) * val[2], bf16_hi(zw[1]) * val[3]};
+            if constexpr (!REV) {
+                *reinterpret_cast<f32x4 *>(row + u * gcs) = pr;
+            } else {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) run[a] += rqd[u][a] - pr[a];
+                dterm[u] = run;   // sum over this thread's tokens >= u
+            }
+        }
+        if constexpr (REV) {
+            f32x4 inc = run;   // inclusive suffix scan over the wave's token groups
+#pragma unroll
+            for (int s = 1; s < GW; s <<= 1) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    const float dn = __shfl_down(inc[a], s * CQ, 64);
+                    if (gl + s < GW) inc[a] += dn;
+                }
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) later_in_wave[a] = inc[a] - run[a];
+            if (gl == 0) *reinterpret_cast<f32x4 *>(wtot2 + w * DK + 4 * cq) = inc;
+        }
+    };
+    // second half (dK, after a barrier): add the later waves and the later chunks, store dG
+    auto dg_second = [&](long long tc) __attribute__((always_inline)) {
+        float *row = dgb + (tc + tq * TPT) * gcs + 4 * cq;
+        f32x4 later = carry, total = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int a = 0; a < 4; ++a) later[a] += later_in_wave[a];
+#pragma unroll
+        for (int u = 0; u < NW; ++u) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(wtot2 + u * DK + 4 * cq);
+            const float sel = (u > w) ? 1.f : 0.f;   // wave-uniform
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                later[a] = __builtin_fmaf(sel, x[a], later[a]);
+                total[a] += x[a];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < TPT; ++u) {
+            f32x4 o;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) o[a] = dterm[u][a] + later[a];
+            *reinterpret_cast<f32x4 *>(row + u * gcs) = o;
+        }
+#pragma unroll
+        for (int a = 0; a < 4; ++a) carry[a] += total[a];
+    };
+
     for (int n = 0; n < N; ++n) {
         const long long t0 = (long long)chunk_of(n) * 64;                          // this chunk
         const long long t1 = (long long)chunk_of((n + 1 < N) ? n + 1 : n) * 64;    // chunk fetched meanwhile
+        const long long tp = (long long)chunk_of((n > 0) ? n - 1 : 0) * 64;        // chunk finished last
+        if (n > 0) dg_first(tp);
 
         // ---- gate pass, part 1: per-thread cumulative sums of g; X, Y, Y^T -> LDS -----------------
         f32x4 cs[TPT];
@@ -245,6 +345,9 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             for (int a = 0; a < 4; ++a) ch[a].store(Yt + (4 * vq + a) * TS + c0 * 2);
         }
         __syncthreads();
+        if constexpr (REV) {
+            if (n > 0) dg_second(tp);
+        }
 
         // ---- gate pass, part 2: stitch waves; Z~^T and the factor tile -> LDS ----------------------
         {
@@ -297,6 +400,13 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             }
         }
         __syncthreads();
+
+        // operands of this chunk's dG terms, consumed one iteration later
+#pragma unroll
+        for (int u = 0; u < TPT; ++u) {
+            rz2[u] = *reinterpret_cast<const u32x2 *>(z2b + ((t0 + tq * TPT + u) * st + 4 * cq) * 2);
+            if constexpr (REV) rqd[u] = *reinterpret_cast<const f32x4 *>(dgb + (t0 + tq * TPT + u) * gcs + 4 * cq);
+        }
 
         // ---- scores: P^T tiles (r' <= r), 16x16x32 over the d_v channels -----------------------------
         const float gcol = gam[w * 16 + l16];   // decay of this lane's column of W
@@ -355,11 +465,13 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             for (int ks = 0; ks <= mt / 2; ++ks)
                 Oacc[mt] = M::run(zf[ks], lds_frag(Ps, (mt * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2), Oacc[mt]);
             const int r = mt * 16 + l16;
-            const f32x4 f = *reinterpret_cast<const f32x4 *>(Fs + r * FS + (w * 16 + 4 * kg) * 4);
+            float *fr = reinterpret_cast<float *>(Fs + r * FS + (w * 16 + 4 * kg) * 4);
+            const f32x4 f = *reinterpret_cast<const f32x4 *>(fr);
+            const f32x4 val = {Oacc[mt][0] * f[0] * p.oscale, Oacc[mt][1] * f[1] * p.oscale,
+                               Oacc[mt][2] * f[2] * p.oscale, Oacc[mt][3] * f[3] * p.oscale};
+            *reinterpret_cast<f32x4 *>(fr) = val;   // fp32 gradient, read back by the dG bookkeeping
             unsigned char *orow = ob + ((t0 + pos_of(r)) * st + w * 16 + 4 * kg) * 2;
-            *reinterpret_cast<u32x2 *>(orow) =
-                u32x2{pack_bf16(Oacc[mt][0] * f[0] * p.oscale, Oacc[mt][1] * f[1] * p.oscale),
-                      pack_bf16(Oacc[mt][2] * f[2] * p.oscale, Oacc[mt][3] * f[3] * p.oscale)};
+            *reinterpret_cast<u32x2 *>(orow) = u32x2{pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
         }
         // ---- state: W += Yt Zt^T (then the column decay in the forward direction) ---------------------
 #pragma unroll
@@ -376,108 +488,12 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
         __syncthreads();
     }
-}
-
-// dG_t = c + sum over the segment's tokens s >= t of (q_s dq_s - k_s dk_s), c = row sums of
-// dS_end .* S_end.  One workgroup of 256 threads per stream, chunks of 64 tokens from the last to the
-// first; a thread owns 4 channels x TPT consecutive tokens.
-template <int DK>
-__global__ __launch_bounds__(256) void gla_bwd_dg_kernel(BwdDGParams p) {
-    constexpr int CQ = DK / 4, TG = 256 / CQ, TPT = 64 / TG, GW = 64 / CQ;
-    __shared__ float carry0[DK];
-    __shared__ float wtot[4][DK];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const size_t sbh = blockIdx.x;
-    int sidx = blockIdx.x;
-    const int h = sidx % p.H;
-    sidx /= p.H;
-    const int b = sidx % p.B, seg = sidx / p.B;
-    const long long tok0 = (long long)seg * p.L;
-    const long long kbase = b * p.sb + tok0 * p.st + h * p.sh;
-    const long long T = (long long)p.P * p.L;
-    float *dgb = p.dg + (((long long)b * T + tok0) * p.H + h) * DK;
-    const long long gcs = (long long)p.H * DK;
-
-    // c[i] = sum_j dS_end[i][j] S_end[i][j]
-    {
-        const float *A = p.dS_end + sbh * DK * p.d_v;
-        const float *Bm = (seg + 1 < p.P) ? p.S_init + (sbh + (size_t)p.B * p.H) * DK * p.d_v
-                                          : p.S_last + ((size_t)b * p.H + h) * DK * p.d_v;
-        for (int i = tid >> 1; i < DK; i += 128) {
-            float acc = 0.f;
-            for (int j = (tid & 1) * 4; j < p.d_v; j += 8) {
-                const f32x4 x = *reinterpret_cast<const f32x4 *>(A + (size_t)i * p.d_v + j);
-                const f32x4 y = *reinterpret_cast<const f32x4 *>(Bm + (size_t)i * p.d_v + j);
-                acc += x[0] * y[0] + x[1] * y[1] + x[2] * y[2] + x[3] * y[3];
-            }
-            acc += __shfl_xor(acc, 1, 64);
-            if ((tid & 1) == 0) carry0[i] = acc;
-        }
-    }
-    __syncthreads();
-    const int cq = lane % CQ, gl = lane / CQ, tq = w * GW + gl;
-    f32x4 carry = *reinterpret_cast<const f32x4 *>(carry0 + 4 * cq);   // sum over all later chunks
-    const uint16_t *qp = (const uint16_t *)p.q + kbase, *kp = (const uint16_t *)p.k + kbase;
-    const uint16_t *dqp = (const uint16_t *)p.dq + kbase, *dkp = (const uint16_t *)p.dk + kbase;
-
-    for (int n = p.n_chunks - 1; n >= 0; --n) {
-        const long long t0 = (long long)n * 64 + tq * TPT;
-        f32x4 d[TPT];
-#pragma unroll
-        for (int u = 0; u < TPT; ++u) {
-            const long long off = (t0 + u) * p.st + 4 * cq;
-            const u32x2 a = *reinterpret_cast<const u32x2 *>(qp + off);
-            const u32x2 da = *reinterpret_cast<const u32x2 *>(dqp + off);
-            const u32x2 c = *reinterpret_cast<const u32x2 *>(kp + off);
-            const u32x2 dc = *reinterpret_cast<const u32x2 *>(dkp + off);
-            d[u] = f32x4{bf16_lo(a[0]) * bf16_lo(da[0]) - bf16_lo(c[0]) * bf16_lo(dc[0]),
-                         bf16_hi(a[0]) * bf16_hi(da[0]) - bf16_hi(c[0]) * bf16_hi(dc[0]),
-                         bf16_lo(a[1]) * bf16_lo(da[1]) - bf16_lo(c[1]) * bf16_lo(dc[1]),
-                         bf16_hi(a[1]) * bf16_hi(da[1]) - bf16_hi(c[1]) * bf16_hi(dc[1])};
-        }
-        // in-thread suffix sums, then the sums of the later token groups: inside the wave by
-        // shuffles, across waves through LDS
-        f32x4 run = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int u = TPT - 1; u >= 0; --u) {
-#pragma unroll
-            for (int a = 0; a < 4; ++a) run[a] += d[u][a];
-            d[u] = run;
-        }
-        f32x4 inc = run;   // inclusive suffix scan over the wave's token groups
-#pragma unroll
-        for (int s = 1; s < GW; s <<= 1) {
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const float dn = __shfl_down(inc[a], s * CQ, 64);
-                if (gl + s < GW) inc[a] += dn;
-            }
-        }
-        if (gl == 0) *reinterpret_cast<f32x4 *>(&wtot[w][4 * cq]) = inc;
+    // dG terms of the last chunk processed
+    const long long tl = (long long)chunk_of(N - 1) * 64;
+    dg_first(tl);
+    if constexpr (REV) {
         __syncthreads();
-        f32x4 later = carry, total = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int a = 0; a < 4; ++a) later[a] += inc[a] - run[a];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const f32x4 x = *reinterpret_cast<const f32x4 *>(&wtot[u][4 * cq]);
-            const float sel = (u > w) ? 1.f : 0.f;
-#pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                later[a] = __builtin_fmaf(sel, x[a], later[a]);
-                total[a] += x[a];
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < TPT; ++u) {
-            f32x4 o;
-#pragma unroll
-            for (int a = 0; a < 4; ++a) o[a] = d[u][a] + later[a];
-            *reinterpret_cast<f32x4 *>(dgb + (t0 + u) * gcs + 4 * cq) = o;
-        }
-#pragma unroll
-        for (int a = 0; a < 4; ++a) carry[a] += total[a];
-        __syncthreads();
+        dg_second(tl);
     }
 }
 
@@ -503,13 +519,6 @@ static hipError_t dispatch_qk(const BwdQKParams &p, int d_k, int d_v, hipStream_
 hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, bool g_bf16, bool reverse, hipStream_t s) {
     if (reverse) return g_bf16 ? dispatch_qk<true, true>(p, d_k, d_v, s) : dispatch_qk<true, false>(p, d_k, d_v, s);
     return g_bf16 ? dispatch_qk<false, true>(p, d_k, d_v, s) : dispatch_qk<false, false>(p, d_k, d_v, s);
-}
-
-hipError_t launch_bwd_dg(const BwdDGParams &p, int d_k, hipStream_t s) {
-    if (d_k == 64) hipLaunchKernelGGL(gla_bwd_dg_kernel<64>, dim3(p.B * p.P * p.H), dim3(256), 0, s, p);
-    else if (d_k == 128) hipLaunchKernelGGL(gla_bwd_dg_kernel<128>, dim3(p.B * p.P * p.H), dim3(256), 0, s, p);
-    else return hipErrorInvalidValue;
-    return hipGetLastError();
 }
 
 }  // namespace zeco

@@ -47,25 +47,17 @@ struct ScanParams {
     int reverse = 0;             // 1: chain runs from segment P-1 down to 0
 };
 
-// dQ / dK pass (gla_bwd_qk.hip).  x, y: [B,T,H,d_v] operands (strides vb, vt, vh); z, g, out:
-// [B,T,H,d_k] (strides sb, st, sh); W_init [P,B,H,d_k,d_v] fp32.
+// dQ / dK pass (gla_bwd_qk.hip).  x, y: [B,T,H,d_v] operands (strides vb, vt, vh); z, z2, g, out:
+// [B,T,H,d_k] (strides sb, st, sh); W_init [P,B,H,d_k,d_v] fp32; dg [B,T,H,d_k] fp32 contiguous (the dQ
+// pass leaves q .* dq there, the dK pass turns it into dG); S_init, S_last: forward states (dK pass).
 struct BwdQKParams {
-    const void *x, *y, *z, *g;
+    const void *x, *y, *z, *z2, *g;
     void *out;
-    const float *W_init;
+    float *dg;
+    const float *W_init, *S_init, *S_last;
     int B, P, H, L, n_chunks;
     float zscale, oscale;        // multipliers of the gated operand and of the output
     long long sb, st, sh, vb, vt, vh;
-};
-
-// dG pass.  q, k, dq, dk [B,T,H,d_k] (strides sb, st, sh); dg [B,T,H,d_k] fp32 contiguous;
-// dS_end [P,B,H,d_k,d_v], S_init [P,B,H,d_k,d_v], S_last [B,H,d_k,d_v].
-struct BwdDGParams {
-    const void *q, *k, *dq, *dk;
-    float *dg;
-    const float *dS_end, *S_init, *S_last;
-    int B, P, H, L, n_chunks, d_v;
-    long long sb, st, sh;
 };
 
 // Each returns hipSuccess or the launch error.  d_k, d_v in {64,128}.
@@ -80,10 +72,9 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s);
 // Per group of P segments: G_pre[g*P+p] = sum of G_tot[g*P+r] over r < p, G_sum[g] = sum over all r.
 hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, int groups, int P,
                               int BHdk, hipStream_t s);
-// reverse = false: dQ (x = dO, y = v, z = k, W_init = forward states); true: dK (x = v, y = dO, z = q,
-// W_init = state gradients)
+// reverse = false: dQ (x = dO, y = v, z = k, z2 = q, W_init = forward states); true: dK (x = v, y = dO,
+// z = q, z2 = k, W_init = state gradients; must run after the dQ pass, whose q .* dq it consumes)
 hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, bool g_bf16, bool reverse, hipStream_t s);
-hipError_t launch_bwd_dg(const BwdDGParams &p, int d_k, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 }  // namespace zeco

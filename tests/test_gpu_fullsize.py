@@ -59,3 +59,45 @@ def test_fullsize_sampled_slices(name, samples):
         Gc = np.cumsum(host(inp["g"][:1, p * L:(p + 1) * L, h:h + 1]), axis=1)
         assert log_err(host(parts["G_cum"][:1, p * L:(p + 1) * L, h:h + 1]), Gc) <= 1e-5
         assert log_err(host(parts["G_tot"][p, :1, h:h + 1]), Gc[:, -1]) <= 1e-5
+
+
+def slice_oracle_bwd(inp, dO, L, p, h, P, W):
+    """Oracle gradients for segment p, head h (batch 0) of the unsegmented run: the oracle runs on a
+    window reaching W tokens before and after the segment; what lies outside is attenuated by the
+    gates of the window, which is asserted."""
+    T = P * L
+    t0 = max(0, p * L - W)
+    t1 = min(T, (p + 1) * L + W)
+    sl = slice(t0, t1)
+    q, k, v, g = (host(inp[n][:1, sl, h:h + 1]) for n in ("q", "k", "v", "g"))
+    d = host(dO[:1, sl, h:h + 1])
+    a, b = p * L - t0, (p + 1) * L - t0
+    assert t0 == 0 or g[0, :a, 0].sum(axis=0).max() < np.log(1e-30)
+    assert t1 == T or g[0, b:, 0].sum(axis=0).max() < np.log(1e-30)
+    grads = oracle.gla_recurrent_bwd(q, k, v, g, d)
+    return [x[:, a:b] for x in grads[:4]]
+
+
+@pytest.mark.parametrize("name,samples", [
+    ("c2", [(0, 0), (0, 9)]),
+    ("c3", [(0, 3), (4, 7), (7, 15)]),
+    ("c4", [(0, 0), (37, 11), (63, 15)]),
+])
+def test_fullsize_backward_sampled_slices(name, samples):
+    inp, c = synth.config_inputs(name, device="cuda")
+    P, L, H = c["P"], c["L"], c["H"]
+    print("full-size backward", name, c, flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(4242)
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    dq, dk, dv, dg, dS0 = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], dO, P)
+    torch.cuda.synchronize()
+    for (p, h) in samples:
+        print("  sample segment %d head %d" % (p, h), flush=True)
+        ref = slice_oracle_bwd(inp, dO, L, p, h, P, W[name])
+        for nm, x, r in zip(("dq", "dk", "dv", "dg"), (dq, dk, dv, dg), ref):
+            got = host(x[:1, p * L:(p + 1) * L, h:h + 1])
+            print("    %s rel err %.4f" % (nm, rel_err_bh(got, r, (0, 2))), flush=True)
+            assert rel_err_bh(got, r, (0, 2)) <= TOL[c["io"]], nm
+            # both ends of the segment are where the states handed over by the scans matter most
+            assert rel_err_bh(got[:, :256], r[:, :256], (0, 2)) <= TOL[c["io"]], nm
+            assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= TOL[c["io"]], nm

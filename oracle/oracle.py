@@ -28,26 +28,30 @@ def build(force=False):
     return _LIB
 
 
+def _bind(lib):
+    """Declare the argument types of every oracle_* function of a loaded library."""
+    dp = ctypes.POINTER(ctypes.c_double)
+    ci, cd = ctypes.c_int, ctypes.c_double
+    lib.oracle_gla_recurrent.argtypes = [ci] * 5 + [dp] * 4 + [cd] + [dp] * 3
+    lib.oracle_gla_recurrent.restype = None
+    lib.oracle_gla_local.argtypes = [ci] * 6 + [dp] * 4 + [cd] + [dp] * 4
+    lib.oracle_gla_local.restype = None
+    lib.oracle_state_scan.argtypes = [ci] * 4 + [dp] * 5
+    lib.oracle_state_scan.restype = None
+    lib.oracle_apply_init_state.argtypes = [ci] * 6 + [dp] * 3 + [cd] + [dp]
+    lib.oracle_apply_init_state.restype = None
+    lib.oracle_gla_recurrent_bwd.argtypes = [ci] * 5 + [dp] * 4 + [cd] + [dp] * 8
+    lib.oracle_gla_recurrent_bwd.restype = None
+    lib.oracle_num_threads.argtypes = []
+    lib.oracle_num_threads.restype = ci
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
         build()
-        lib = ctypes.CDLL(_LIB)
-        dp = ctypes.POINTER(ctypes.c_double)
-        ci, cd = ctypes.c_int, ctypes.c_double
-        lib.oracle_gla_recurrent.argtypes = [ci] * 5 + [dp] * 4 + [cd] + [dp] * 3
-        lib.oracle_gla_recurrent.restype = None
-        lib.oracle_gla_local.argtypes = [ci] * 6 + [dp] * 4 + [cd] + [dp] * 4
-        lib.oracle_gla_local.restype = None
-        lib.oracle_state_scan.argtypes = [ci] * 4 + [dp] * 5
-        lib.oracle_state_scan.restype = None
-        lib.oracle_apply_init_state.argtypes = [ci] * 6 + [dp] * 3 + [cd] + [dp]
-        lib.oracle_apply_init_state.restype = None
-        lib.oracle_gla_recurrent_bwd.argtypes = [ci] * 5 + [dp] * 4 + [cd] + [dp] * 8
-        lib.oracle_gla_recurrent_bwd.restype = None
-        lib.oracle_num_threads.argtypes = []
-        lib.oracle_num_threads.restype = ci
-        _lib = lib
+        _lib = _bind(ctypes.CDLL(_LIB))
     return _lib
 
 

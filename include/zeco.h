@@ -46,6 +46,10 @@ typedef struct {
     float scale;
     int64_t stride_b, stride_t, stride_h;
     int64_t vstride_b, vstride_t, vstride_h;
+    int32_t g_per_head;        /* 0: one log decay per (token, head, channel), g as described above.
+                                * 1: one log decay per (token, head) shared by all d_k channels (the
+                                *    scalar-decay members of the family, Sec. 2.1): g, G_cum and dg are
+                                *    contiguous [B,T,H] fp32, G_tot is [P,B,H]; bf16 q/k/v only. */
 } zeco_gla_desc;
 
 /* Bytes of device workspace zeco_gla_local_fwd needs for this descriptor (may be 0).
@@ -81,13 +85,15 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *desc, const void *q, const v
  *   out  S_init [P,BH,d_k,d_v] fp32,  S_last [BH,d_k,d_v] fp32 or NULL (= state after segment P-1)
  * K_blocks: number of contiguous d_k-row blocks the state is split into (d_k % K_blocks == 0);
  * each block is an independent slab and the result is bitwise independent of K_blocks.
+ * gate_per_head: 0 = G_tot [P,BH,d_k]; 1 = G_tot [P,BH], one log decay per head (see zeco_gla_desc).
  * direction: 0 = forward chain.  1 = the backward direction of Alg. 2: the chain runs from the last
  *   segment to the first, S_init[p] = what enters segment p from segment p+1 (S0 enters the last
  *   segment), S_last = what leaves segment 0; used for the state gradients of App. A.4.
  * d_v % 4 == 0 required; any d_k >= 1. */
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
                             const float *S_loc, const float *G_tot, const float *S0,
-                            float *S_init, float *S_last, int32_t direction, void *stream);
+                            float *S_init, float *S_last, int32_t direction, int32_t gate_per_head,
+                            void *stream);
 
 /* Initial-state correction (Eq. (global-correction) carried to the output; the highlighted term
  * of Alg. 1's output pass, with Lambda_t .* gamma~_[n-1] = exp(G_cum[t])):

@@ -25,7 +25,8 @@ template <int DK, int DV> struct ApplyCfg {
     static constexpr int kBytes = 64 * QS + 64 * CS * 4;
 };
 
-template <int DK, int DV>
+// GH: the cumulative log decay is one value per (token, head), G_cum [B,T,H].
+template <int DK, int DV, bool GH>
 __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     typedef ApplyCfg<DK, DV> Cfg;
     typedef Mma<Cfg::TILE> M;
@@ -49,8 +50,8 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     const uint16_t *qp = (const uint16_t *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
     uint16_t *op = (uint16_t *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
     const long long T = (long long)p.P * p.L;
-    float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
-    const long long gcs = (long long)p.H * DK;
+    float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * (GH ? 1 : DK);
+    const long long gcs = (long long)p.H * (GH ? 1 : DK);
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
 
     // S_init[p] columns [w*TILE, (w+1)*TILE) as the A operand of O^T = S^T Qh^T: lane holds column
@@ -76,8 +77,13 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
             const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
             const long long tt = (long long)blk * 64 + t;
             r.q[m] = *reinterpret_cast<const u32x4 *>(qp + tt * p.st + 8 * cg);
-            r.g0[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg);
-            r.g1[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg + 4);
+            if constexpr (GH) {
+                const float x = Gc[tt * gcs];
+                r.g0[m] = r.g1[m] = f32x4{x, x, x, x};
+            } else {
+                r.g0[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg);
+                r.g1[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg + 4);
+            }
         }
     };
 
@@ -93,7 +99,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
 
     // Optional rebasing of the cumulative log decay: this thread always handles the same 8 channels.
     f32x4 goff0 = {0.f, 0.f, 0.f, 0.f}, goff1 = {0.f, 0.f, 0.f, 0.f};
-    if (p.G_off) {
+    if (!GH && p.G_off) {
         const float *go = p.G_off + (((size_t)seg * p.B + b) * p.H + h) * DK + 8 * (tid % (DK / 8));
         goff0 = *reinterpret_cast<const f32x4 *>(go);
         goff1 = *reinterpret_cast<const f32x4 *>(go + 4);
@@ -121,7 +127,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
                                    bf16_hi(cur.q[m][e]) * fast_exp(gb) * p.scale);
             }
             *reinterpret_cast<u32x4 *>(Qh + t * QS + 16 * cg) = out;
-            if (p.G_off) {
+            if (!GH && p.G_off) {
                 float *gw = Gc + ((long long)blk * 64 + t) * gcs + 8 * cg;
                 *reinterpret_cast<f32x4 *>(gw) = cur.g0[m] + goff0;
                 *reinterpret_cast<f32x4 *>(gw + 4) = cur.g1[m] + goff1;
@@ -217,7 +223,10 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
 
 template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hipStream_t s) {
     const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
-    hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV>), dim3(grid), dim3(256), 0, s, p);
+    if (p.gate_per_head)
+        hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, true>), dim3(grid), dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, false>), dim3(grid), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hipStream_t s) {

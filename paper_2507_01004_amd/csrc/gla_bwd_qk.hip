@@ -72,12 +72,16 @@ template <int DK, int DV> struct QKCfg {
     }
 };
 
-template <bool GBF16> struct GateRaw;
-template <> struct GateRaw<false> {
+template <int GM> struct GateRaw;
+template <> struct GateRaw<kGateHead> {
+    typedef float raw_t;
+    __device__ static __forceinline__ f32x4 get(raw_t r) { return f32x4{r, r, r, r}; }
+};
+template <> struct GateRaw<kGateF32> {
     typedef f32x4 raw_t;
     __device__ static __forceinline__ f32x4 get(raw_t r) { return r; }
 };
-template <> struct GateRaw<true> {
+template <> struct GateRaw<kGateBF16> {
     typedef u32x2 raw_t;
     __device__ static __forceinline__ f32x4 get(raw_t r) {
         return f32x4{bf16_lo(r[0]), bf16_hi(r[0]), bf16_lo(r[1]), bf16_hi(r[1])};
@@ -122,14 +126,15 @@ __device__ __forceinline__ bf16x8 pack2x4(f32x4 a, f32x4 b) {
 // REV = false: dQ (x = dO, y = v, z = k, W_init = forward states; the query scale multiplies the
 // output).  REV = true: dK (x = v, y = dO, z = q, W_init = state gradients entering each segment's
 // final state; the query scale rides on Q .* Lambda, so that the running dS is the true gradient).
-template <int DK, int DV, bool REV, bool GBF16>
+template <int DK, int DV, bool REV, int GM>
 __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     typedef QKCfg<DK, DV> Cfg;
     typedef Mma<16> M;
-    typedef GateRaw<GBF16> GV;
+    typedef GateRaw<GM> GV;
     constexpr int XS = Cfg::XS, TS = Cfg::TS, FS = Cfg::FS, NW = Cfg::NW, NT = Cfg::NT;
     constexpr int TPT = Cfg::TPT, TPTV = Cfg::TPTV, CQ = Cfg::CQ, GW = Cfg::GW;
-    constexpr int GB = GBF16 ? 2 : 4;
+    constexpr int GB = GM == kGateBF16 ? 2 : 4;
+    constexpr bool GH = GM == kGateHead;
     constexpr float kLog2e = 1.4426950408889634f;
     constexpr float SZ = REV ? 1.f : -1.f;   // exponent sign of the operand Z~; the factor F takes the other
     extern __shared__ __align__(16) unsigned char lds[];
@@ -159,12 +164,14 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     const unsigned char *xb = (const unsigned char *)p.x + vbase * 2;
     const unsigned char *yb = (const unsigned char *)p.y + vbase * 2;
     const unsigned char *zb = (const unsigned char *)p.z + kbase * 2;
-    const unsigned char *gb = (const unsigned char *)p.g + kbase * GB;
+    const long long hbase = ((long long)b * p.P * p.L + tok0) * p.H + h;   // per-head arrays [B,T,H]
+    const unsigned char *gb = (const unsigned char *)p.g + (GH ? hbase : kbase) * GB;
+    const long long gst = GH ? (long long)p.H : p.st;                       // gate elements between tokens
     const unsigned char *z2b = (const unsigned char *)p.z2 + kbase * 2;
     unsigned char *ob = (unsigned char *)p.out + kbase * 2;
     const long long st = p.st, vt = p.vt;
-    float *dgb = p.dg + (((long long)b * p.P * p.L + tok0) * p.H + h) * DK;   // [B,T,H,d_k] contiguous
-    const long long gcs = (long long)p.H * DK;
+    float *dgb = p.dg + hbase * (GH ? 1 : DK);   // [B,T,H,d_k] contiguous ([B,T,H] with per-head gates)
+    const long long gcs = (long long)p.H * (GH ? 1 : DK);
 
     // gate-pass coordinates (z, g) and copy-pass coordinates (x, y)
     const int cq = lane % CQ, gl = lane / CQ, tq = w * GW + gl;
@@ -211,7 +218,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
             rz[u] = *reinterpret_cast<const u32x2 *>(zb + ((c0 + tq * TPT + u) * st + 4 * cq) * 2);
-            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((c0 + tq * TPT + u) * st + 4 * cq) * GB);
+            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((c0 + tq * TPT + u) * gst + (GH ? 0 : 4 * cq)) * GB);
         }
 #pragma unroll
         for (int u = 0; u < TPTV; ++u) {
@@ -220,6 +227,13 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
     }
 
+    // sum over the d_k channels of a token: the 4 of this thread, then the CQ lanes that share the token
+    auto channel_sum = [&](f32x4 x) __attribute__((always_inline)) {
+        float tot = (x[0] + x[1]) + (x[2] + x[3]);
+#pragma unroll
+        for (int d = 1; d < CQ; d <<= 1) tot += __shfl_xor(tot, d, 64);
+        return tot;
+    };
     // dG bookkeeping of the chunk finished last: raw z2 (q for dQ, k for dK) and, for dK, the Q .* dQ terms
     u32x2 rz2[TPT];
     f32x4 rqd[TPT], dterm[TPT];
@@ -227,7 +241,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 
     // first half: terms from the fp32 result tile in Fs; dQ stores them, dK starts the reverse sums
     auto dg_first = [&](long long tc) __attribute__((always_inline)) {
-        float *row = dgb + (tc + tq * TPT) * gcs + 4 * cq;
+        float *row = dgb + (tc + tq * TPT) * gcs + (GH ? 0 : 4 * cq);
         f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = TPT - 1; u >= 0; --u) {
@@ -235,7 +249,10 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             const u32x2 zw = rz2[u];
             const f32x4 pr = {bf16_lo(zw[0]) * val[0], bf16_hi(zw[0]) * val[1],
                               bf16_lo(zw[1]) * val[2], bf16_hi(zw[1]) * val[3]};
-            if constexpr (!REV) {
+            if constexpr (!REV && GH) {
+                const float tot = channel_sum(pr);
+                if (cq == 0) row[u * gcs] = tot;
+            } else if constexpr (!REV) {
                 *reinterpret_cast<f32x4 *>(row + u * gcs) = pr;
             } else {
 #pragma unroll
@@ -260,7 +277,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     };
     // second half (dK, after a barrier): add the later waves and the later chunks, store dG
     auto dg_second = [&](long long tc) __attribute__((always_inline)) {
-        float *row = dgb + (tc + tq * TPT) * gcs + 4 * cq;
+        float *row = dgb + (tc + tq * TPT) * gcs + (GH ? 0 : 4 * cq);
         f32x4 later = carry, total = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int a = 0; a < 4; ++a) later[a] += later_in_wave[a];
@@ -279,7 +296,12 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             f32x4 o;
 #pragma unroll
             for (int a = 0; a < 4; ++a) o[a] = dterm[u][a] + later[a];
-            *reinterpret_cast<f32x4 *>(row + u * gcs) = o;
+            if constexpr (GH) {
+                const float tot = channel_sum(o);
+                if (cq == 0) row[u * gcs] = tot;
+            } else {
+                *reinterpret_cast<f32x4 *>(row + u * gcs) = o;
+            }
         }
 #pragma unroll
         for (int a = 0; a < 4; ++a) carry[a] += total[a];
@@ -299,7 +321,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
                 const f32x4 gv = GV::get(rg[u]);
-                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((t1 + tq * TPT + u) * st + 4 * cq) * GB);
+                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((t1 + tq * TPT + u) * gst + (GH ? 0 : 4 * cq)) * GB);
 #pragma unroll
                 for (int a = 0; a < 4; ++a) run[a] += gv[a];
                 cs[u] = run;
@@ -405,7 +427,12 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
             rz2[u] = *reinterpret_cast<const u32x2 *>(z2b + ((t0 + tq * TPT + u) * st + 4 * cq) * 2);
-            if constexpr (REV) rqd[u] = *reinterpret_cast<const f32x4 *>(dgb + (t0 + tq * TPT + u) * gcs + 4 * cq);
+            if constexpr (REV && GH) {   // the channel sum of q .* dq, booked on the first channel
+                const float x = dgb[(t0 + tq * TPT + u) * gcs];
+                rqd[u] = f32x4{cq == 0 ? x : 0.f, 0.f, 0.f, 0.f};
+            } else if constexpr (REV) {
+                rqd[u] = *reinterpret_cast<const f32x4 *>(dgb + (t0 + tq * TPT + u) * gcs + 4 * cq);
+            }
         }
 
         // ---- scores: P^T tiles (r' <= r), 16x16x32 over the d_v channels -----------------------------
@@ -497,28 +524,31 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     }
 }
 
-template <int DK, int DV, bool REV, bool GBF16>
+template <int DK, int DV, bool REV, int GM>
 static hipError_t launch_qk(const BwdQKParams &p, hipStream_t s) {
     typedef QKCfg<DK, DV> Cfg;
-    auto kern = gla_bwd_qk_kernel<DK, DV, REV, GBF16>;
+    auto kern = gla_bwd_qk_kernel<DK, DV, REV, GM>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.B * p.P * p.H), dim3(Cfg::NT), Cfg::kBytes, s, p);
     return hipGetLastError();
 }
 
-template <bool REV, bool GBF16>
+template <bool REV, int GM>
 static hipError_t dispatch_qk(const BwdQKParams &p, int d_k, int d_v, hipStream_t s) {
-    if (d_k == 64 && d_v == 64) return launch_qk<64, 64, REV, GBF16>(p, s);
-    if (d_k == 128 && d_v == 64) return launch_qk<128, 64, REV, GBF16>(p, s);
-    if (d_k == 64 && d_v == 128) return launch_qk<64, 128, REV, GBF16>(p, s);
-    if (d_k == 128 && d_v == 128) return launch_qk<128, 128, REV, GBF16>(p, s);
+    if (d_k == 64 && d_v == 64) return launch_qk<64, 64, REV, GM>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_qk<128, 64, REV, GM>(p, s);
+    if (d_k == 64 && d_v == 128) return launch_qk<64, 128, REV, GM>(p, s);
+    if (d_k == 128 && d_v == 128) return launch_qk<128, 128, REV, GM>(p, s);
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, bool g_bf16, bool reverse, hipStream_t s) {
-    if (reverse) return g_bf16 ? dispatch_qk<true, true>(p, d_k, d_v, s) : dispatch_qk<true, false>(p, d_k, d_v, s);
-    return g_bf16 ? dispatch_qk<false, true>(p, d_k, d_v, s) : dispatch_qk<false, false>(p, d_k, d_v, s);
+hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, int gate_mode, bool reverse, hipStream_t s) {
+    if (gate_mode == kGateBF16)
+        return reverse ? dispatch_qk<true, kGateBF16>(p, d_k, d_v, s) : dispatch_qk<false, kGateBF16>(p, d_k, d_v, s);
+    if (gate_mode == kGateHead)
+        return reverse ? dispatch_qk<true, kGateHead>(p, d_k, d_v, s) : dispatch_qk<false, kGateHead>(p, d_k, d_v, s);
+    return reverse ? dispatch_qk<true, kGateF32>(p, d_k, d_v, s) : dispatch_qk<false, kGateF32>(p, d_k, d_v, s);
 }
 
 }  // namespace zeco

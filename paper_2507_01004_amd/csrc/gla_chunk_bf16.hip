@@ -82,12 +82,16 @@ template <int DK, int DV> struct B16Cfg {
 };
 
 // Four consecutive gate values of one token, as loaded and as floats.
-template <bool GBF16> struct GateVal;
-template <> struct GateVal<false> {
+template <int GM> struct GateVal;
+template <> struct GateVal<kGateF32> {
     typedef f32x4 raw_t;
     __device__ static __forceinline__ f32x4 get(raw_t r) { return r; }
 };
-template <> struct GateVal<true> {
+template <> struct GateVal<kGateHead> {
+    typedef float raw_t;
+    __device__ static __forceinline__ f32x4 get(raw_t r) { return f32x4{r, r, r, r}; }
+};
+template <> struct GateVal<kGateBF16> {
     typedef u32x2 raw_t;
     __device__ static __forceinline__ f32x4 get(raw_t r) {
         return f32x4{bf16_lo(r[0]), bf16_hi(r[0]), bf16_lo(r[1]), bf16_hi(r[1])};
@@ -149,14 +153,15 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 // causal structure of the tiles is the one of the forward pass.
 enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4 };
 
-template <int DK, int DV, int NS, bool GBF16, int MODE>
+template <int DK, int DV, int NS, int GM, int MODE>
 __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParams p) {
     typedef B16Cfg<DK, DV> Cfg;
     typedef Mma<32> M;
-    typedef GateVal<GBF16> GV;
+    typedef GateVal<GM> GV;
     constexpr int QS = Cfg::QS, TS = Cfg::TS, NWM = Cfg::NWM, NT = Cfg::NT;
     constexpr int TPT = Cfg::TPT, TPTV = Cfg::TPTV, CQ = Cfg::CQ, GW = Cfg::GW;
-    constexpr int GB = GBF16 ? 2 : 4;   // bytes per gate element
+    constexpr int GB = GM == kGateBF16 ? 2 : 4;   // bytes per gate element
+    constexpr bool GH = GM == kGateHead;
     constexpr bool REV = MODE == kDState || MODE == kDV;          // chunks and tokens in reverse
     constexpr bool NOQ = MODE == kStates || MODE == kDState;      // only the state is computed
     constexpr bool FROM_INIT = MODE == kOutput || MODE == kDV;    // start from S_init, emit no state
@@ -198,12 +203,14 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         // Uniform byte pointers to the stream's first token; per-thread 32-bit offsets on top.
         const unsigned char *qb = (const unsigned char *)p.q + kbase * 2;
         const unsigned char *kb = (const unsigned char *)p.k + kbase * 2;
-        const unsigned char *gb = (const unsigned char *)p.g + kbase * GB;
+        const long long hbase = ((long long)b * p.P * p.L + tok0) * p.H + h;   // per-head gates: [B,T,H]
+        const unsigned char *gb = (const unsigned char *)p.g + (GH ? hbase : kbase) * GB;
+        const unsigned gst = GH ? (unsigned)p.H : st;                          // gate elements between tokens
         const unsigned char *vb = (const unsigned char *)p.v + vbase * 2;
         const long long c0 = (long long)chunk_of(0) * 64;   // first token of the first chunk processed
         const long long T = (long long)p.P * p.L;
-        unsigned char *Gb = (unsigned char *)(p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK);
-        const unsigned gcs = (unsigned)(p.H * DK);
+        unsigned char *Gb = (unsigned char *)(p.G_cum + (((long long)b * T + tok0) * p.H + h) * (GH ? 1 : DK));
+        const unsigned gcs = (unsigned)(p.H * (GH ? 1 : DK));
 
         // channel quad and token group (q, k, g); column quad and token group (v)
         const int cq = lane % CQ, gl = lane / CQ, tq = gw * GW + gl;
@@ -212,9 +219,9 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         // Per-thread byte offsets of its first token inside a chunk; token u and the chunk are added
         // to the uniform base pointer, so one offset register serves every access of a tensor.
         const unsigned q_b0 = ((unsigned)(tq * TPT) * st + 4 * cq) * 2;
-        const unsigned g_in_b0 = ((unsigned)(tq * TPT) * st + 4 * cq) * GB;
+        const unsigned g_in_b0 = ((unsigned)(tq * TPT) * gst + (GH ? 0 : 4 * cq)) * GB;
         const unsigned v_b0 = ((unsigned)(tv * TPTV) * vt + 4 * vq) * 2;
-        const unsigned g_b0 = ((unsigned)(tq * TPT) * gcs + 4 * cq) * 4;   // G_cum: contiguous [.., H, d_k]
+        const unsigned g_b0 = ((unsigned)(tq * TPT) * gcs + (GH ? 0 : 4 * cq)) * 4;   // G_cum: contiguous [.., H, d_k]
 
         // Raw q, k, g, v of the chunk worked on next; each piece is reloaded with the following
         // chunk's data right after its last use (clamped to the last chunk).
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         for (int u = 0; u < TPT; ++u) {
             if constexpr (!NOQ) rq[u] = *reinterpret_cast<const u32x2 *>(qb + (c0 + u) * st * 2 + q_b0);
             rk[u] = *reinterpret_cast<const u32x2 *>(kb + (c0 + u) * st * 2 + q_b0);
-            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (c0 + u) * st * GB + g_in_b0);
+            rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + (c0 + u) * gst * GB + g_in_b0);
         }
 #pragma unroll
         for (int u = 0; u < TPTV; ++u) rv[u] = *reinterpret_cast<const u32x2 *>(vb + (c0 + u) * vt * 2 + v_b0);
@@ -237,12 +244,12 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
         // part 1 of chunk m: per-thread cumulative sums and gate sums
         auto gate_a = [&](int m) __attribute__((always_inline)) {
             const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
-            const unsigned char *gn = gb + (long long)nn * 64 * st * GB;   // uniform
+            const unsigned char *gn = gb + (long long)nn * 64 * gst * GB;   // uniform
             f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
                 const f32x4 gv = GV::get(rg[u]);
-                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gn + (size_t)(u * st) * GB + g_in_b0);
+                rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gn + (size_t)(u * gst) * GB + g_in_b0);
 #pragma unroll
                 for (int a = 0; a < 4; ++a) run[a] += gv[a];
                 cs[u] = run;
@@ -354,8 +361,12 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                     f32x4 gout;
 #pragma unroll
                     for (int a = 0; a < 4; ++a) gout[a] = gbase[a] + cs[u][a];
-                    if (u % NS == slice)   // sibling slices share the G_cum rows between them
+                    if constexpr (GH) {
+                        if (u % NS == slice && cq == 0)
+                            *reinterpret_cast<float *>(Gm + (size_t)(u * gcs) * 4 + g_b0) = gout[0];
+                    } else if (u % NS == slice) {   // sibling slices share the G_cum rows between them
                         *reinterpret_cast<f32x4 *>(Gm + (size_t)(u * gcs) * 4 + g_b0) = gout;
+                    }
                 }
             }
 #pragma unroll
@@ -382,7 +393,11 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
                 f32x4 gt;
 #pragma unroll
                 for (int a = 0; a < 4; ++a) gt[a] = seg_hi[a] + seg_lo[a];
-                *reinterpret_cast<f32x4 *>(p.G_tot + sbh * DK + 4 * cq) = gt;
+                if constexpr (GH) {
+                    if (cq == 0) p.G_tot[sbh] = gt[0];
+                } else {
+                    *reinterpret_cast<f32x4 *>(p.G_tot + sbh * DK + 4 * cq) = gt;
+                }
             }
         };
 
@@ -567,10 +582,10 @@ __global__ __launch_bounds__(DV * 2 + 256) void gla_chunk_bf16_kernel(ChunkParam
     }
 }
 
-template <int DK, int DV, int NS, bool GBF16, int MODE>
+template <int DK, int DV, int NS, int GM, int MODE>
 static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     typedef B16Cfg<DK, DV> Cfg;
-    auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GBF16, MODE>;
+    auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GM, MODE>;
     hipError_t e = hipFuncSetAttribute((const void *)kern,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
     if (e != hipSuccess) return e;
@@ -580,30 +595,33 @@ static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <bool GBF16, int MODE>
+template <int GM, int MODE>
 static hipError_t dispatch_b16(const ChunkParams &p, int d_k, int d_v, hipStream_t s) {
     // With fewer streams than compute units, two sibling workgroups split d_v = 128 so that every
     // compute unit streams memory; the gate pass is then computed twice.
     const bool split = d_v == 128 && p.B * p.P * p.H < 256;
-    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, 1, GBF16, MODE>(p, s);
-    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, 1, GBF16, MODE>(p, s);
+    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, 1, GM, MODE>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, 1, GM, MODE>(p, s);
     if (d_k == 64 && d_v == 128)
-        return split ? launch_b16<64, 64, 2, GBF16, MODE>(p, s) : launch_b16<64, 128, 1, GBF16, MODE>(p, s);
+        return split ? launch_b16<64, 64, 2, GM, MODE>(p, s) : launch_b16<64, 128, 1, GM, MODE>(p, s);
     if (d_k == 128 && d_v == 128)
-        return split ? launch_b16<128, 64, 2, GBF16, MODE>(p, s) : launch_b16<128, 128, 1, GBF16, MODE>(p, s);
+        return split ? launch_b16<128, 64, 2, GM, MODE>(p, s) : launch_b16<128, 128, 1, GM, MODE>(p, s);
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16, int mode, hipStream_t s) {
-    if (mode == kStates)
-        return g_bf16 ? dispatch_b16<true, kStates>(p, d_k, d_v, s) : dispatch_b16<false, kStates>(p, d_k, d_v, s);
-    if (mode == kOutput)
-        return g_bf16 ? dispatch_b16<true, kOutput>(p, d_k, d_v, s) : dispatch_b16<false, kOutput>(p, d_k, d_v, s);
-    if (mode == kDState)
-        return g_bf16 ? dispatch_b16<true, kDState>(p, d_k, d_v, s) : dispatch_b16<false, kDState>(p, d_k, d_v, s);
-    if (mode == kDV)
-        return g_bf16 ? dispatch_b16<true, kDV>(p, d_k, d_v, s) : dispatch_b16<false, kDV>(p, d_k, d_v, s);
-    return g_bf16 ? dispatch_b16<true, kLocal>(p, d_k, d_v, s) : dispatch_b16<false, kLocal>(p, d_k, d_v, s);
+template <int MODE>
+static hipError_t dispatch_gate(const ChunkParams &p, int d_k, int d_v, int gate_mode, hipStream_t s) {
+    if (gate_mode == kGateBF16) return dispatch_b16<kGateBF16, MODE>(p, d_k, d_v, s);
+    if (gate_mode == kGateHead) return dispatch_b16<kGateHead, MODE>(p, d_k, d_v, s);
+    return dispatch_b16<kGateF32, MODE>(p, d_k, d_v, s);
+}
+
+hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mode, int mode, hipStream_t s) {
+    if (mode == kStates) return dispatch_gate<kStates>(p, d_k, d_v, gate_mode, s);
+    if (mode == kOutput) return dispatch_gate<kOutput>(p, d_k, d_v, gate_mode, s);
+    if (mode == kDState) return dispatch_gate<kDState>(p, d_k, d_v, gate_mode, s);
+    if (mode == kDV) return dispatch_gate<kDV>(p, d_k, d_v, gate_mode, s);
+    return dispatch_gate<kLocal>(p, d_k, d_v, gate_mode, s);
 }
 
 }  // namespace zeco

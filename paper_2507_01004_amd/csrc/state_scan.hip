@@ -25,14 +25,15 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
     const int slab4 = p.rows_per_block * dv4;
     const size_t state = (size_t)p.d_k * p.d_v;
     const size_t seg_stride = (size_t)p.BH * state;         // floats between segments
-    const size_t g_stride = (size_t)p.BH * p.d_k;
+    const size_t gdim = p.gate_per_head ? 1 : p.d_k;        // log decays per (segment, head)
+    const size_t g_stride = (size_t)p.BH * gdim;
     const size_t grp = blockIdx.y;                          // chain (group of P segments)
 
     for (int e = threadIdx.x; e < slab4; e += blockDim.x) {
         const int row = row0 + e / dv4;
         const size_t off = (size_t)bh * state + (size_t)row * p.d_v + (size_t)(e % dv4) * 4;
         const float *loc = p.S_loc + grp * p.P * seg_stride + off;
-        const float *gt = p.G_tot + grp * p.P * g_stride + (size_t)bh * p.d_k + row;
+        const float *gt = p.G_tot + grp * p.P * g_stride + (size_t)bh * gdim + (p.gate_per_head ? 0 : row);
         float *init = p.S_init + grp * p.P * seg_stride + off;
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
         if (p.S0) s = *reinterpret_cast<const f32x4 *>(p.S0 + grp * seg_stride + off);

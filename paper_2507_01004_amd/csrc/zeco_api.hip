@@ -27,7 +27,14 @@ zeco_status check_desc(const zeco_gla_desc *d) {
     if ((int64_t)d->B * d->P * d->H > (int64_t)1 << 24) return ZECO_ERR_INVALID_ARG;
     if (d->C != 64 || !dim_ok(d->d_k) || !dim_ok(d->d_v)) return ZECO_ERR_UNSUPPORTED;
     if (d->io_dtype == ZECO_F32 && d->g_dtype != ZECO_F32) return ZECO_ERR_UNSUPPORTED;
+    if (d->g_per_head != 0 && d->g_per_head != 1) return ZECO_ERR_INVALID_ARG;
+    if (d->g_per_head && (d->io_dtype != ZECO_BF16 || d->g_dtype != ZECO_F32)) return ZECO_ERR_UNSUPPORTED;
     return ZECO_OK;
+}
+
+int gate_mode(const zeco_gla_desc *d) {
+    if (d->g_per_head) return zeco::kGateHead;
+    return d->g_dtype == ZECO_BF16 ? zeco::kGateBF16 : zeco::kGateF32;
 }
 
 zeco_status from_hip(hipError_t e) { return e == hipSuccess ? ZECO_OK : ZECO_ERR_HIP; }
@@ -41,7 +48,7 @@ extern "C" {
 // idle; the local pass then applies the method to itself: sub-segments from the zero state, a scan of
 // their states inside each segment, and a correction that also rebases the cumulative log decay.
 static int subsegments(const zeco_gla_desc *d) {
-    if (d->io_dtype != ZECO_BF16) return 1;
+    if (d->io_dtype != ZECO_BF16 || d->g_per_head) return 1;
     const long long streams = (long long)d->B * d->P * d->H;
     if (streams > 64) return 1;
     int S = 1;
@@ -99,7 +106,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     p.dbg = zeco::g_phase_dbg;
 #endif
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
-    if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 0, s));
+    if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s));
 
     // Few streams: P*S sub-segments of L/S tokens (Sec. 3.1 applied inside each segment).
     const SubLayout w = sub_layout(d, S);
@@ -107,7 +114,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     float *Ssub = ws + w.off_Ssub, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot, *Gpre = ws + w.off_Gpre;
     p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
     p.S_loc = Ssub; p.G_tot = Gtot;
-    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 0, s);
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::ScanParams sp;   // one chain of S sub-segments per segment; its end state is the segment's S_loc
@@ -156,7 +163,7 @@ zeco_status zeco_gla_local_state(const zeco_gla_desc *d, const void *k, const vo
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.k = k; p.v = v; p.g = g; p.S_loc = S_loc; p.G_tot = G_tot;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 1,
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1,
                                             static_cast<hipStream_t>(stream)));
 }
 
@@ -172,7 +179,7 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_init = S_init;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 2,
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2,
                                             static_cast<hipStream_t>(stream)));
 }
 
@@ -210,17 +217,17 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     fill_chunk_params(p, d);
     p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
     p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 1, s);
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::ScanParams sp;
     sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
     sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
-    sp.rows_per_block = d->d_k / 16;
+    sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
 
     p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 2, s));
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, s));
 }
 
 // ---- backward (App. A.4) ------------------------------------------------------------------------------
@@ -230,7 +237,7 @@ static zeco_status bwd_passes(const zeco_gla_desc *d, int P, int L, const void *
                               const void *v, const void *g, const void *dO, const float *S_init,
                               const float *S_last, const float *dS_in, void *dq, void *dk, void *dv,
                               float *dg, hipStream_t s) {
-    const bool gb = d->g_dtype == ZECO_BF16;
+    const int gb = gate_mode(d);
     zeco::BwdQKParams b;
     b.g = g; b.B = d->B; b.P = P; b.H = d->H; b.L = L; b.n_chunks = L / d->C;
     b.sb = d->stride_b; b.st = d->stride_t; b.sh = d->stride_h;
@@ -261,7 +268,7 @@ zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *d, const void *q, const voi
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.k = q; p.v = dO; p.g = g; p.S_loc = dS_loc; p.kscale = d->scale;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, d->g_dtype == ZECO_BF16, 3,
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 3,
                                             static_cast<hipStream_t>(stream)));
 }
 
@@ -336,7 +343,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     float *Sloc = ws + w.off_Sloc, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot;
     float *dSloc = ws + w.off_dSloc, *dSin = ws + w.off_dSin;
     float *Slast = Sinit + w.n * w.state;
-    const bool gb = d->g_dtype == ZECO_BF16;
+    const int gb = gate_mode(d);
     const int P = d->P * S, L = d->L / S;
 
     // forward states at the piece boundaries (recomputed: phase 1 of the forward and its scan)
@@ -349,7 +356,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     zeco::ScanParams sp;
     sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
     sp.P = P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
-    sp.rows_per_block = d->d_k / 16;
+    sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
 
     // state gradients: local reverse pass, then the chain from the last piece to the first
@@ -363,10 +370,11 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
 
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
                             const float *S_loc, const float *G_tot, const float *S0, float *S_init,
-                            float *S_last, int32_t direction, void *stream) {
+                            float *S_last, int32_t direction, int32_t gate_per_head, void *stream) {
     if (P <= 0 || BH <= 0 || d_k <= 0 || d_v <= 0 || K_blocks <= 0) return ZECO_ERR_INVALID_ARG;
     if (d_k % K_blocks != 0) return ZECO_ERR_INVALID_ARG;
     if (direction != 0 && direction != 1) return ZECO_ERR_INVALID_ARG;
+    if (gate_per_head != 0 && gate_per_head != 1) return ZECO_ERR_INVALID_ARG;
     if (!S_loc || !G_tot || !S_init) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(S_loc) || !aligned16(S_init) || !aligned16(S0) || !aligned16(S_last) ||
         (reinterpret_cast<uintptr_t>(G_tot) & 3u))
@@ -375,7 +383,7 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
     if (d_v % 4 != 0) return ZECO_ERR_UNSUPPORTED;
 
     zeco::ScanParams p;
-    p.reverse = direction;
+    p.reverse = direction; p.gate_per_head = gate_per_head;
     p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = S0; p.S_init = S_init; p.S_last = S_last;
     p.P = P; p.BH = BH; p.d_k = d_k; p.d_v = d_v; p.rows_per_block = d_k / K_blocks; p.groups = 1;
     return from_hip(zeco::launch_scan(p, static_cast<hipStream_t>(stream)));
@@ -393,7 +401,7 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
     zeco::ApplyParams p;
     p.q = q; p.G_cum = const_cast<float *>(G_cum); p.S_init = S_init; p.G_off = nullptr; p.o = o;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
-    p.p0 = first_segment_is_zero ? 1 : 0; p.skip_mod = 0;
+    p.p0 = first_segment_is_zero ? 1 : 0; p.skip_mod = 0; p.gate_per_head = d->g_per_head;
     int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
     while (tpw > 64 && d->L % tpw != 0) tpw >>= 1;
     p.tokens_per_wg = tpw;

@@ -5,6 +5,10 @@
 
 namespace zeco {
 
+// Gate layouts: kGateF32 / kGateBF16 = one log decay per (token, head, channel); kGateHead = one fp32
+// log decay per (token, head), shared by all channels (g, G_cum [B,T,H] contiguous; G_tot [P,B,H]).
+enum GateMode { kGateF32 = 0, kGateBF16 = 1, kGateHead = 2 };
+
 struct ChunkParams {
     const void *q, *k, *v, *g;
     void *o;
@@ -34,6 +38,7 @@ struct ApplyParams {
     int p0;                    // first segment to correct
     int skip_mod;              // > 0: segments with index % skip_mod == 0 are left untouched
     int tokens_per_wg;         // multiple of 64 dividing L
+    int gate_per_head = 0;     // 1: G_cum [B,T,H] (bf16 kernel only, no rebasing)
     float scale;
     long long sb, st, sh, vb, vt, vh;
 };
@@ -45,11 +50,13 @@ struct ScanParams {
     float *S_init, *S_last;
     int P, BH, d_k, d_v, rows_per_block, groups;
     int reverse = 0;             // 1: chain runs from segment P-1 down to 0
+    int gate_per_head = 0;       // 1: G_tot [groups*P, BH], one log decay per head
 };
 
 // dQ / dK pass (gla_bwd_qk.hip).  x, y: [B,T,H,d_v] operands (strides vb, vt, vh); z, z2, g, out:
 // [B,T,H,d_k] (strides sb, st, sh); W_init [P,B,H,d_k,d_v] fp32; dg [B,T,H,d_k] fp32 contiguous (the dQ
 // pass leaves q .* dq there, the dK pass turns it into dG); S_init, S_last: forward states (dK pass).
+// With per-head gates g and dg are [B,T,H] and the channel sums are taken before anything is stored.
 struct BwdQKParams {
     const void *x, *y, *z, *z2, *g;
     void *out;
@@ -65,7 +72,7 @@ hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t 
 // mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
 // 3 backward state pass (k := q, v := dO; S_loc := dS leaving the segment), 4 dV pass (q := k, k := q,
 // v := dO, S_init := dS entering the segment's final state, o := dV)
-hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, bool g_bf16, int mode, hipStream_t s);
+hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mode, int mode, hipStream_t s);
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_scan(const ScanParams &p, hipStream_t s);
@@ -74,7 +81,7 @@ hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, in
                               int BHdk, hipStream_t s);
 // reverse = false: dQ (x = dO, y = v, z = k, z2 = q, W_init = forward states); true: dK (x = v, y = dO,
 // z = q, z2 = k, W_init = state gradients; must run after the dQ pass, whose q .* dq it consumes)
-hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, bool g_bf16, bool reverse, hipStream_t s);
+hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, int gate_mode, bool reverse, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 }  // namespace zeco

@@ -25,9 +25,10 @@ def torch_dtype(name):
 
 
 def make_inputs(B, T, H, d_k, d_v, *, seed, io="bf16", g="f32", device="cpu", slow_from=None,
-                slow_shift=2.0, gate_div=16.0, zero_gate=False, slab_tokens=8192):
+                slow_shift=2.0, gate_div=16.0, zero_gate=False, slab_tokens=8192, per_head_gate=False):
     """Returns dict(q, k, v, g) of torch tensors on `device`, generated slab by slab over T so that
-    the fp32 temporaries stay small next to the result."""
+    the fp32 temporaries stay small next to the result.  per_head_gate: g is [B,T,H] (one log decay per
+    token and head, the first channel's draw) instead of [B,T,H,d_k]."""
     dev = torch.device(device)
     gen = torch.Generator(device=dev)
     gen.manual_seed(int(seed))
@@ -35,7 +36,7 @@ def make_inputs(B, T, H, d_k, d_v, *, seed, io="bf16", g="f32", device="cpu", sl
     q = torch.empty(B, T, H, d_k, dtype=io_dt, device=dev)
     k = torch.empty(B, T, H, d_k, dtype=io_dt, device=dev)
     v = torch.empty(B, T, H, d_v, dtype=io_dt, device=dev)
-    gt = torch.empty(B, T, H, d_k, dtype=g_dt, device=dev)
+    gt = torch.empty((B, T, H) if per_head_gate else (B, T, H, d_k), dtype=g_dt, device=dev)
     for t0 in range(0, T, slab_tokens):
         t1 = min(T, t0 + slab_tokens)
         n = t1 - t0
@@ -46,6 +47,8 @@ def make_inputs(B, T, H, d_k, d_v, *, seed, io="bf16", g="f32", device="cpu", sl
         x = torch.randn(B, n, H, d_k, generator=gen, device=dev)
         if slow_from is not None:
             x[:, :, slow_from:] += slow_shift
+        if per_head_gate:
+            x = x[..., 0]
         if zero_gate:
             gt[:, t0:t1] = 0
         else:
@@ -56,8 +59,9 @@ def make_inputs(B, T, H, d_k, d_v, *, seed, io="bf16", g="f32", device="cpu", sl
 def config_inputs(name, *, device="cpu", g="f32", **over):
     c = dict(CONFIGS[name])
     c.update(over)
+    per_head = bool(c.pop("per_head_gate", False))
     return make_inputs(c["B"], c["P"] * c["L"], c["H"], c["d_k"], c["d_v"], seed=c["seed"],
-                       io=c["io"], g=g, device=device, slow_from=c["slow_from"]), c
+                       io=c["io"], g=g, device=device, slow_from=c["slow_from"], per_head_gate=per_head), c
 
 
 def to_f64(t):

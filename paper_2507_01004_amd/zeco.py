@@ -29,7 +29,8 @@ class GlaDesc(ctypes.Structure):
                 ("C", ctypes.c_int32), ("io_dtype", ctypes.c_int32), ("g_dtype", ctypes.c_int32),
                 ("scale", ctypes.c_float),
                 ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
-                ("vstride_b", ctypes.c_int64), ("vstride_t", ctypes.c_int64), ("vstride_h", ctypes.c_int64)]
+                ("vstride_b", ctypes.c_int64), ("vstride_t", ctypes.c_int64), ("vstride_h", ctypes.c_int64),
+                ("g_per_head", ctypes.c_int32)]
 
 
 class ZecoError(RuntimeError):
@@ -55,7 +56,7 @@ def lib():
         L.zeco_gla_local_fwd_workspace.restype = ctypes.c_size_t
         L.zeco_gla_local_fwd.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, vp]
         L.zeco_gla_local_fwd.restype = i32
-        L.zeco_state_scan.argtypes = [i32, i32, i32, i32, i32, fp, fp, fp, fp, fp, i32, vp]
+        L.zeco_state_scan.argtypes = [i32, i32, i32, i32, i32, fp, fp, fp, fp, fp, i32, i32, vp]
         L.zeco_state_scan.restype = i32
         L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state.restype = i32
@@ -109,15 +110,34 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def make_desc(q, v, g, P, C=64, scale=1.0):
+def _desc(q, v, g_code, per_head, P, C, scale):
     B, T, H, dk = q.shape
     dv = v.shape[-1]
     if T % P != 0:
         raise ValueError("T=%d is not a multiple of P=%d" % (T, P))
     if q.stride(-1) != 1 or v.stride(-1) != 1:
         raise ValueError("innermost dimension must be contiguous")
-    return GlaDesc(B, P, H, T // P, dk, dv, C, _dtype_code(q), _dtype_code(g), float(scale),
-                   q.stride(0), q.stride(1), q.stride(2), v.stride(0), v.stride(1), v.stride(2))
+    return GlaDesc(B, P, H, T // P, dk, dv, C, _dtype_code(q), g_code, float(scale),
+                   q.stride(0), q.stride(1), q.stride(2), v.stride(0), v.stride(1), v.stride(2),
+                   int(per_head))
+
+
+def make_desc(q, v, g, P, C=64, scale=1.0):
+    """Descriptor of a call that reads the gate g: [B,T,H,d_k] laid out like q, or, with one log decay
+    per (token, head), a contiguous [B,T,H] tensor."""
+    B, T, H, dk = q.shape
+    per_head = g.dim() == 3
+    if per_head:
+        if tuple(g.shape) != (B, T, H) or not g.is_contiguous():
+            raise ValueError("a per-head gate must be a contiguous [B,T,H] tensor")
+    elif g.shape != q.shape or g.stride() != q.stride():
+        raise ValueError("a per-channel gate must have the shape and strides of q")
+    return _desc(q, v, _dtype_code(g), per_head, P, C, scale)
+
+
+def _gate_dims(g, dk):
+    """Trailing dimensions of the gate-shaped outputs (G_cum, G_tot, dg)."""
+    return () if g.dim() == 3 else (dk,)
 
 
 def _check_same_layout(ref, *others):
@@ -131,8 +151,6 @@ def gla_local_fwd(q, k, v, g, P, scale=1.0, C=64, out=None):
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
-    if g.shape != q.shape or g.stride() != q.stride():
-        raise ValueError("g must share q's shape and strides")
     if k.dtype != q.dtype or v.dtype != q.dtype:
         raise TypeError("q, k, v must share a dtype")
     B, T, H, dk = q.shape
@@ -141,8 +159,8 @@ def gla_local_fwd(q, k, v, g, P, scale=1.0, C=64, out=None):
     if out is None:
         o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
         S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=q.device)
-        G_cum = torch.empty(B, T, H, dk, dtype=torch.float32, device=q.device)
-        G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device=q.device)
+        G_cum = torch.empty((B, T, H) + _gate_dims(g, dk), dtype=torch.float32, device=q.device)
+        G_tot = torch.empty((P, B, H) + _gate_dims(g, dk), dtype=torch.float32, device=q.device)
     else:
         o, S_loc, G_cum, G_tot = out
         _check_same_layout(v, o)
@@ -169,8 +187,11 @@ def state_scan(S_loc, G_tot, S0=None, K_blocks=16, out=None, direction=0):
         S_last = torch.empty(S_loc.shape[1:], dtype=torch.float32, device=S_loc.device)
     else:
         S_init, S_last = out
+    if G_tot.numel() not in (P * BH, P * BH * dk):
+        raise ValueError("G_tot must be [P,BH,d_k] or, for per-head gates, [P,BH]")
+    per_head = int(G_tot.numel() == P * BH and dk != 1)
     st = lib().zeco_state_scan(P, BH, dk, dv, int(K_blocks), _ptr(S_loc), _ptr(G_tot), _ptr(S0),
-                               _ptr(S_init), _ptr(S_last), int(direction), _stream())
+                               _ptr(S_init), _ptr(S_last), int(direction), per_head, _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_state_scan")
     return S_init, S_last
@@ -178,10 +199,10 @@ def state_scan(S_loc, G_tot, S0=None, K_blocks=16, out=None, direction=0):
 
 def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segment_is_zero=True):
     """zeco_apply_init_state: o += (scale q .* exp(G_cum)) S_init[p], in place.  `g_like` only
-    supplies the gate dtype recorded in the descriptor."""
+    supplies the gate dtype recorded in the descriptor; G_cum [B,T,H] selects per-head gates."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
-    desc = make_desc(q, o, g_like, P, C, scale)
+    desc = _desc(q, o, _dtype_code(g_like), G_cum.dim() == 3, P, C, scale)
     st = lib().zeco_apply_init_state(ctypes.byref(desc), _ptr(q), _ptr(G_cum), _ptr(S_init), _ptr(o),
                                      1 if first_segment_is_zero else 0, _stream())
     if st != ZECO_OK:
@@ -198,7 +219,7 @@ def gla_local_state(k, v, g, P, C=64, out=None):
     desc = make_desc(k, v, g, P, C, 1.0)
     if out is None:
         S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=k.device)
-        G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device=k.device)
+        G_tot = torch.empty((P, B, H) + _gate_dims(g, dk), dtype=torch.float32, device=k.device)
     else:
         S_loc, G_tot = out
     st = lib().zeco_gla_local_state(ctypes.byref(desc), _ptr(k), _ptr(v), _ptr(g), _ptr(S_loc),
@@ -265,11 +286,11 @@ def gla_bwd_dstate(q, g, dO, P, scale=1.0, C=64, out=None):
     return dS_loc
 
 
-def _grad_outputs(q, v):
+def _grad_outputs(q, v, g):
     dq = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     dk = torch.empty_strided(q.shape, q.stride(), dtype=q.dtype, device=q.device)
     dv = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
-    dg = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    dg = torch.empty(g.shape, dtype=torch.float32, device=q.device)
     return dq, dk, dv, dg
 
 
@@ -281,7 +302,7 @@ def gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P, scale=1.0, C=64
     _check_same_layout(q, k)
     _check_same_layout(v, dO)
     desc = make_desc(q, v, g, P, C, scale)
-    dq, dk, dv, dg = _grad_outputs(q, v) if out is None else out
+    dq, dk, dv, dg = _grad_outputs(q, v, g) if out is None else out
     st = lib().zeco_gla_bwd_from_state(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(dO),
                                        _ptr(S_init), _ptr(S_last), _ptr(dS_in), _ptr(dq), _ptr(dk),
                                        _ptr(dv), _ptr(dg), _stream())
@@ -309,7 +330,7 @@ def gla_fused_bwd(q, k, v, g, dO, P, scale=1.0, S0=None, dS_T=None, C=64, out=No
     if workspace is None:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
     if out is None:
-        dq, dk, dv, dg = _grad_outputs(q, v)
+        dq, dk, dv, dg = _grad_outputs(q, v, g)
         dS0 = torch.empty(B, H, dk_, dv_, dtype=torch.float32, device=q.device) if want_dS0 else None
     else:
         dq, dk, dv, dg, dS0 = out

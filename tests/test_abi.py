@@ -43,7 +43,7 @@ def test_version_and_strings(L):
 def good_desc(**kw):
     d = dict(B=1, P=2, H=2, L=128, d_k=128, d_v=128, C=64, io_dtype=zeco.ZECO_BF16,
              g_dtype=zeco.ZECO_F32, scale=1.0, stride_b=2 * 256 * 128 * 2, stride_t=256, stride_h=128,
-             vstride_b=2 * 256 * 128 * 2, vstride_t=256, vstride_h=128)
+             vstride_b=2 * 256 * 128 * 2, vstride_t=256, vstride_h=128, g_per_head=0)
     d.update(kw)
     return zeco.GlaDesc(*[d[f[0]] for f in zeco.GlaDesc._fields_])
 
@@ -66,6 +66,9 @@ def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
     (dict(C=32, L=128), zeco.ZECO_ERR_UNSUPPORTED),
     (dict(d_k=96, stride_h=96), zeco.ZECO_ERR_UNSUPPORTED),
     (dict(io_dtype=zeco.ZECO_F32, g_dtype=zeco.ZECO_BF16), zeco.ZECO_ERR_UNSUPPORTED),
+    (dict(g_per_head=2), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(g_per_head=1, g_dtype=zeco.ZECO_BF16), zeco.ZECO_ERR_UNSUPPORTED),   # per-head gates are fp32
+    (dict(g_per_head=1, io_dtype=zeco.ZECO_F32), zeco.ZECO_ERR_UNSUPPORTED),
 ])
 def test_local_fwd_rejects_bad_descriptors(L, kw, expect):
     assert call_local(L, good_desc(**kw)) == expect
@@ -82,7 +85,7 @@ def test_local_fwd_rejects_bad_pointers(L):
 
 def test_state_scan_rejects_bad_arguments(L):
     def scan(P=4, BH=2, dk=128, dv=128, K=8, S_loc=FAKE, G=FAKE, S0=None, S_init=FAKE, S_last=None, d=0):
-        return L.zeco_state_scan(P, BH, dk, dv, K, S_loc, G, S0, S_init, S_last, d, None)
+        return L.zeco_state_scan(P, BH, dk, dv, K, S_loc, G, S0, S_init, S_last, d, 0, None)
     assert scan(P=0) == zeco.ZECO_ERR_INVALID_ARG
     assert scan(K=3) == zeco.ZECO_ERR_INVALID_ARG          # does not divide d_k
     assert scan(S_loc=None) == zeco.ZECO_ERR_INVALID_ARG

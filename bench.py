@@ -27,18 +27,19 @@ MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
 MEASURED_TRAFFIC = {("c3", "f32"): 4303900000, ("c4", "f32"): 34443000000}   # profiles/c3_pipeline_kernels.md
 
 
-def algorithmic_bytes(c, g_bytes):
-    """Algorithmic HBM bytes per launch of each kernel (per token-head figures x units)."""
+def algorithmic_bytes(c, g_in, g_cum):
+    """Algorithmic HBM bytes per launch of each kernel (per token-head figures x units).
+    g_in, g_cum: bytes of g and of G_cum per token-head."""
     B, H, P, L, dk, dv = c["B"], c["H"], c["P"], c["L"], c["d_k"], c["d_v"]
     io = 2 if c["io"] == "bf16" else 4
     th = B * P * L * H                                  # token-heads per launch
     streams = B * P * H
-    local = th * (2 * dk * io + dv * io + dk * g_bytes   # read q, k, v, g
-                  + dv * io + dk * 4)                     # write o, G_cum
+    local = th * (2 * dk * io + dv * io + g_in           # read q, k, v, g
+                  + dv * io + g_cum)                      # write o, G_cum
     local += streams * (dk * dv * 4 + dk * 4)            # S_loc, G_tot
     scan = streams * (2 * dk * dv * 4 + dk * 4) + B * H * dk * dv * 4
     th_c = B * (P - 1) * L * H                           # segment 0 needs no correction
-    apply_ = th_c * (dk * io + dk * 4 + 2 * dv * io) + B * (P - 1) * H * dk * dv * 4
+    apply_ = th_c * (dk * io + g_cum + 2 * dv * io) + B * (P - 1) * H * dk * dv * 4
     return dict(local=local, scan=scan, apply=apply_)
 
 
@@ -80,6 +81,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--gate", default="channel", choices=["channel", "head"],
+                    help="one log decay per (token, head, channel) as in GLA (default), or per (token, head)")
     ap.add_argument("--k-blocks", type=int, default=16)
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-backward", action="store_true", help="skip the backward timing")
@@ -98,7 +101,8 @@ def main():
     from paper_2507_01004_amd import synth, zeco
 
     torch.cuda.set_device(0)
-    inp, c = synth.config_inputs(args.workload, device="cuda:0", g=args.g_dtype)
+    inp, c = synth.config_inputs(args.workload, device="cuda:0", g=args.g_dtype,
+                                 per_head_gate=args.gate == "head")
     B, H, P, L, dk, dv = c["B"], c["H"], c["P"], c["L"], c["d_k"], c["d_v"]
     T = P * L
     if args.layout == "bhtd":   # same values, each head's tokens contiguous in memory
@@ -106,8 +110,11 @@ def main():
     q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
     o = torch.empty_like(v)
     S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device="cuda:0")
-    G_cum = torch.empty(B, T, H, dk, dtype=torch.float32, device="cuda:0")
-    G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device="cuda:0")
+    gdim = (dk,) if args.gate == "channel" else ()
+    G_cum = torch.empty((B, T, H) + gdim, dtype=torch.float32, device="cuda:0")
+    G_tot = torch.empty((P, B, H) + gdim, dtype=torch.float32, device="cuda:0")
+    g_in = (dk * (4 if args.g_dtype == "f32" else 2)) if args.gate == "channel" else 4   # bytes per token-head
+    g_cum = dk * 4 if args.gate == "channel" else 4
     S_init = torch.empty_like(S_loc)
     S_last = torch.empty(B, H, dk, dv, dtype=torch.float32, device="cuda:0")
 
@@ -152,8 +159,8 @@ def main():
         fms = fe[0].elapsed_time(fe[1]) / args.steps
         io = 2
         th = B * T * H
-        fb = th * (dk * io + dv * io + dk * (4 if args.g_dtype == "f32" else 2))        # phase 1: k, v, g
-        fb += th * (2 * dk * io + dv * io + dk * (4 if args.g_dtype == "f32" else 2) + dv * io)   # phase 2
+        fb = th * (dk * io + dv * io + g_in)                        # phase 1: k, v, g
+        fb += th * (2 * dk * io + dv * io + g_in + dv * io)         # phase 2
         two_phase = {"entry": "zeco_gla_fused_fwd", "ms_per_step": round(fms, 4),
                      "tokens_per_s": round(B * T / (fms * 1e-3), 1), "alg_bytes": fb,
                      "GBps": round(fb / fms / 1e6, 1), "hbm_frac": round(fb / fms / 1e6 / HBM_PEAK_GBS, 4)}
@@ -166,7 +173,7 @@ def main():
         dO = torch.randn(v.shape, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
         ws = torch.empty(max(zeco.fused_bwd_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
         grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v),
-                 torch.empty(q.shape, dtype=torch.float32, device="cuda:0"), torch.empty_like(S_last))
+                 torch.empty(g.shape, dtype=torch.float32, device="cuda:0"), torch.empty_like(S_last))
         for _ in range(max(1, args.warmup // 2)):
             zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws)
         torch.cuda.synchronize()
@@ -178,14 +185,12 @@ def main():
         be[1].record()
         torch.cuda.synchronize()
         bms = be[0].elapsed_time(be[1]) / nb
-        gB = 4 if args.g_dtype == "f32" else 2
         th = B * T * H
         # bytes of the five passes as built: forward states (k, v, g), state gradients (q, g, dO), dQ (dO, v,
         # k, q, g in; dq and fp32 q.*dq out), dV (k, q, dO, g in; dv out), dK (v, dO, q, k, g, fp32 q.*dq in;
         # dk and fp32 dg out)
         io = dk * 2
-        pb = th * (2 * (2 * io + dk * gB) + (5 * io + dk * gB + dk * 4) + (4 * io + dk * gB)
-                   + (5 * io + dk * gB + 2 * dk * 4))
+        pb = th * (2 * (2 * io + g_in) + (5 * io + g_in + g_cum) + (4 * io + g_in) + (5 * io + g_in + 2 * g_cum))
         backward = {"entry": "zeco_gla_fused_bwd", "ms_per_step": round(bms, 4),
                     "tokens_per_s": round(B * T / (bms * 1e-3), 1), "pass_bytes": pb,
                     "GBps": round(pb / bms / 1e6, 1), "hbm_frac": round(pb / bms / 1e6 / HBM_PEAK_GBS, 4)}
@@ -226,8 +231,7 @@ def main():
         scan_cold = statistics.median(cold)
         del junk
     ms_per_step = wall * 1e3 / args.steps
-    g_bytes = 4 if args.g_dtype == "f32" else 2
-    ab = algorithmic_bytes(c, g_bytes)
+    ab = algorithmic_bytes(c, g_in, g_cum)
     af = algorithmic_flops(c)
     kernels = {}
     for n in ("local", "scan", "apply"):
@@ -252,13 +256,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": c["io"], "data": "synthetic",
         "config": {"workload": "%s: B=%d H=%d P=%d segments x L=%d tokens, d_k=d_v=%d, C=%d, %s q/k/v/o, "
-                               "%s log-decay; local fwd + segment-state scan + init-state correction"
-                               % (args.workload, B, H, P, L, dk, c["C"], c["io"], args.g_dtype),
+                               "%s log-decay per %s; local fwd + segment-state scan + init-state correction"
+                               % (args.workload, B, H, P, L, dk, c["C"], c["io"], args.g_dtype,
+                                  "channel" if args.gate == "channel" else "head"),
                    "K_blocks": args.k_blocks, "layout": args.layout},
         "roofline": {"kernel": "gla_chunk_bf16_kernel (zeco_gla_local_fwd)", "bound": "hbm",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC.get((args.workload, args.g_dtype))},
+                     "traffic": MEASURED_TRAFFIC.get((args.workload, args.g_dtype)) if args.gate == "channel" else None},
         "kernels": kernels,
         "two_phase": two_phase,
         "backward": backward,

@@ -390,11 +390,18 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             for (int u = 0; u < TPT; ++u) {
                 const int t = tq * TPT + u;
                 f32x4 ez, ef;
+                if constexpr (GH) {   // one decay per token: one pair of exponentials for the four channels
+                    const float y = (cs[u][0] + pre[0]) * kLog2e;
+                    const float z = __builtin_amdgcn_exp2f(SZ * y) * p.zscale, f = __builtin_amdgcn_exp2f(-SZ * y);
+                    ez = f32x4{z, z, z, z};
+                    ef = f32x4{f, f, f, f};
+                } else {
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    const float y = (cs[u][a] + pre[a]) * kLog2e;   // in-chunk cumulative log2 decay
-                    ez[a] = __builtin_amdgcn_exp2f(SZ * y) * p.zscale;
-                    ef[a] = __builtin_amdgcn_exp2f(-SZ * y);
+                    for (int a = 0; a < 4; ++a) {
+                        const float y = (cs[u][a] + pre[a]) * kLog2e;   // in-chunk cumulative log2 decay
+                        ez[a] = __builtin_amdgcn_exp2f(SZ * y) * p.zscale;
+                        ef[a] = __builtin_amdgcn_exp2f(-SZ * y);
+                    }
                 }
                 const u32x2 zw = rz[u];
                 rz[u] = *reinterpret_cast<const u32x2 *>(zb + ((t1 + t) * st + 4 * cq) * 2);

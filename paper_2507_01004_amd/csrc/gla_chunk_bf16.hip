@@ -335,11 +335,19 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 const int u = half * HT + uu;
                 const int t = tq * TPT + u;
                 f32x4 yv, ilam;
+                if constexpr (GH) {   // one decay per token: one exponential serves the four channels
+                    const float y = __builtin_fmaf(cs[u][0], kLog2e, pre2[0]);
+                    float il = __builtin_amdgcn_exp2f(-SGN * y);
+                    if constexpr (REV) il *= p.kscale;
+                    yv = f32x4{y, y, y, y};
+                    ilam = f32x4{il, il, il, il};
+                } else {
 #pragma unroll
-                for (int a = 0; a < 4; ++a) {
-                    yv[a] = __builtin_fmaf(cs[u][a], kLog2e, pre2[a]);
-                    ilam[a] = __builtin_amdgcn_exp2f(-SGN * yv[a]);
-                    if constexpr (REV) ilam[a] *= p.kscale;   // the query scale rides on Q .* Lambda
+                    for (int a = 0; a < 4; ++a) {
+                        yv[a] = __builtin_fmaf(cs[u][a], kLog2e, pre2[a]);
+                        ilam[a] = __builtin_amdgcn_exp2f(-SGN * yv[a]);
+                        if constexpr (REV) ilam[a] *= p.kscale;   // the query scale rides on Q .* Lambda
+                    }
                 }
                 const u32x2 kw = rk[u];
                 rk[u] = *reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0);
@@ -347,8 +355,13 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                                   pack_bf16(bf16_lo(kw[1]) * ilam[2], bf16_hi(kw[1]) * ilam[3])};
                 if constexpr (!NOQ) {   // scores and outputs need Q .* Lambda and token-major K / Lambda
                     f32x4 lam;
+                    if constexpr (GH) {
+                        const float l = __builtin_amdgcn_exp2f(SGN * yv[0]);
+                        lam = f32x4{l, l, l, l};
+                    } else {
 #pragma unroll
-                    for (int a = 0; a < 4; ++a) lam[a] = __builtin_amdgcn_exp2f(SGN * yv[a]);
+                        for (int a = 0; a < 4; ++a) lam[a] = __builtin_amdgcn_exp2f(SGN * yv[a]);
+                    }
                     const u32x2 qw = rq[u];
                     rq[u] = *reinterpret_cast<const u32x2 *>(qn + (size_t)(u * st) * 2 + q_b0);
                     *reinterpret_cast<u32x2 *>(Qs + pos_of(t) * QS + qpos * 2) =

@@ -87,6 +87,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-backward", action="store_true", help="skip the backward timing")
     ap.add_argument("--no-cold-scan", action="store_true", help="skip the cold-cache timing of the scan")
+    ap.add_argument("--no-variants", action="store_true", help="skip the bf16-gate timing")
     ap.add_argument("--layout", default="bthd", choices=["bthd", "bhtd"],
                     help="memory order of q/k/v/g/o: token-major (default) or head-major")
     ap.add_argument("--calib-copy-mib", type=int, default=1024,
@@ -196,6 +197,35 @@ def main():
                     "GBps": round(pb / bms / 1e6, 1), "hbm_frac": round(pb / bms / 1e6 / HBM_PEAK_GBS, 4)}
         del ws, grads, dO
 
+    # The same pipeline with the log decay stored in bf16 (256 B per token-head less to read): a data
+    # format choice of the caller, reported beside the fp32-gate headline.
+    g_bf16 = None
+    if c["io"] == "bf16" and args.g_dtype == "f32" and args.gate == "channel" and not args.no_variants:
+        gh = g.to(torch.bfloat16)
+        def step_h():
+            zeco.gla_local_fwd(q, k, v, gh, P, out=(o, S_loc, G_cum, G_tot))
+            zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=(S_init, S_last))
+            zeco.apply_init_state(q, gh, G_cum, S_init, o, P, first_segment_is_zero=True)
+        ws = torch.empty(max(zeco.fused_workspace_bytes(q, v, gh, P), 16), dtype=torch.uint8, device="cuda:0")
+        o2 = torch.empty_like(v)
+        res = {}
+        for name, fn in (("three_call", step_h),
+                         ("two_phase", lambda: zeco.gla_fused_fwd(q, k, v, gh, P, out=(o2, S_last), workspace=ws))):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            nb = max(1, args.steps // 2)
+            e0.record()
+            for _ in range(nb):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) / nb
+            res[name] = {"ms_per_step": round(t, 4), "tokens_per_s": round(B * T / (t * 1e-3), 1)}
+        g_bf16 = res
+        del gh, ws, o2
+
     copy_gbs = None
     if args.calib_copy_mib:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -267,6 +297,7 @@ def main():
         "kernels": kernels,
         "two_phase": two_phase,
         "backward": backward,
+        "g_bf16": g_bf16,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
     }
     if not args.no_cpu:

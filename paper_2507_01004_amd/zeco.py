@@ -146,8 +146,13 @@ def _check_same_layout(ref, *others):
             raise ValueError("tensors sharing a descriptor must share shape, strides and device")
 
 
-def gla_local_fwd(q, k, v, g, P, scale=1.0, C=64, out=None):
-    """zeco_gla_local_fwd.  Returns (o, S_loc, G_cum, G_tot); `out` may supply them preallocated."""
+def local_fwd_workspace_bytes(q, v, g, P, C=64):
+    return int(lib().zeco_gla_local_fwd_workspace(ctypes.byref(make_desc(q, v, g, P, C, 1.0))))
+
+
+def gla_local_fwd(q, k, v, g, P, scale=1.0, C=64, out=None, workspace=None):
+    """zeco_gla_local_fwd.  Returns (o, S_loc, G_cum, G_tot); `out` and `workspace` may be supplied
+    preallocated (then the call allocates nothing)."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
@@ -166,7 +171,10 @@ def gla_local_fwd(q, k, v, g, P, scale=1.0, C=64, out=None):
         _check_same_layout(v, o)
     L = lib()
     ws_bytes = L.zeco_gla_local_fwd_workspace(ctypes.byref(desc))
-    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=q.device) if ws_bytes else None
+    ws = workspace
+    if ws is None and ws_bytes:
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device=q.device)
+    ws_bytes = ws.numel() if ws is not None else 0
     st = L.zeco_gla_local_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(o),
                               _ptr(S_loc), _ptr(G_cum), _ptr(G_tot), _ptr(ws), ws_bytes, _stream())
     if st != ZECO_OK:

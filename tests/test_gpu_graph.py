@@ -1,0 +1,57 @@
+"""The library allocates nothing and never synchronises, so its calls can be recorded into a HIP graph:
+capture the three-call pipeline, the fused forward and the fused backward once, replay them on new
+input values, and compare every replay bitwise with the eager calls."""
+import pytest
+import torch
+
+from paper_2507_01004_amd import synth, zeco
+
+pytestmark = pytest.mark.gpu
+
+
+def test_pipeline_forward_backward_replay_from_a_graph():
+    B, H, P, L, dk, dv = 1, 4, 4, 512, 128, 128
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=31, io="bf16", g="f32", device="cuda")
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    dO = torch.randn_like(v)
+    T = P * L
+    # every output and workspace is allocated before the capture
+    o3 = torch.empty_like(v)
+    S_loc = torch.empty(P, B, H, dk, dv, device="cuda")
+    G_cum = torch.empty(B, T, H, dk, device="cuda")
+    G_tot = torch.empty(P, B, H, dk, device="cuda")
+    S_init, S_last3 = torch.empty_like(S_loc), torch.empty(B, H, dk, dv, device="cuda")
+    o2, S_last2 = torch.empty_like(v), torch.empty(B, H, dk, dv, device="cuda")
+    ws_f = torch.empty(zeco.fused_workspace_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(zeco.fused_bwd_workspace_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
+    grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v), torch.empty(B, T, H, dk, device="cuda"),
+             torch.empty(B, H, dk, dv, device="cuda"))
+    ws_l = torch.empty(max(zeco.local_fwd_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda")
+
+    def run():
+        zeco.gla_local_fwd(q, k, v, g, P, out=(o3, S_loc, G_cum, G_tot), workspace=ws_l)
+        zeco.state_scan(S_loc, G_tot, out=(S_init, S_last3))
+        zeco.apply_init_state(q, g, G_cum, S_init, o3, P)
+        zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws_f)
+        zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws_b)
+
+    outs = (o3, S_last3, o2, S_last2) + grads
+    run()                      # warm-up outside the capture (loads the code objects)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        gen = torch.Generator(device="cuda").manual_seed(100 + rep)
+        q.copy_(torch.randn(q.shape, generator=gen, device="cuda"))
+        v.copy_(torch.randn(v.shape, generator=gen, device="cuda"))
+        dO.copy_(torch.randn(v.shape, generator=gen, device="cuda"))
+        run()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in outs]
+        for t in outs:
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(outs, eager)):
+            assert torch.equal(a, b), (rep, i)

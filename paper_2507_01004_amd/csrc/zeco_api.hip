@@ -290,12 +290,13 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
 }
 
 // Pieces each segment is cut into by zeco_gla_fused_bwd: as in the forward, and further down to at most
-// 1024 tokens.  The gate gradient is a running sum of nearly cancelling terms that restarts, with an
+// 512 tokens.  The gate gradient is a running sum of nearly cancelling terms that restarts, with an
 // exactly known value, at every piece boundary; the bf16 rounding noise of the terms grows with the
-// square root of the run length (measured: 4 % of max|dG| over 8192 tokens, about 1 % over 1024).
+// square root of the run length (measured, worst head: 4 % of max|dG| over 8192 tokens, 1.8 % over
+// 1024, 1.2 % over 512).
 static int bwd_pieces(const zeco_gla_desc *d) {
     int S = fused_pieces(d);
-    while (d->L / S > 1024 && d->L % (2 * S * 64) == 0) S *= 2;
+    while (d->L / S > 512 && d->L % (2 * S * 64) == 0) S *= 2;
     return S;
 }
 

@@ -101,3 +101,40 @@ def test_fullsize_backward_sampled_slices(name, samples):
             # both ends of the segment are where the states handed over by the scans matter most
             assert rel_err_bh(got[:, :256], r[:, :256], (0, 2)) <= TOL[c["io"]], nm
             assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= TOL[c["io"]], nm
+
+
+@pytest.mark.parametrize("name", ["c2", "c3"])
+def test_fullsize_whole_forward_against_unsegmented_oracle(name):
+    """Every token and head of configs 2 and 3 against Eq. (1) run over the whole sequence (the oracle
+    needs a few seconds for 131072 tokens x 16 heads)."""
+    inp, c = synth.config_inputs(name, device="cuda")
+    P = c["P"]
+    print("whole forward", name, c, flush=True)
+    o, S_last, _ = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
+    o_fused, S_last_fused = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
+    torch.cuda.synchronize()
+    o_ref, S_ref = oracle.gla_recurrent(*(host(inp[n]) for n in ("q", "k", "v", "g")))
+    print("  oracle done", flush=True)
+    for got, got_S in ((o, S_last), (o_fused, S_last_fused)):
+        assert rel_err_bh(host(got), o_ref, (0, 2)) <= TOL[c["io"]]
+        assert rel_err_bh(host(got_S), S_ref, (0, 1)) <= TOL[c["io"]]
+        # Frobenius norm of the error beside the max norm
+        diff = host(got) - o_ref
+        assert np.linalg.norm(diff) <= TOL[c["io"]] * np.linalg.norm(o_ref)
+
+
+def test_fullsize_whole_backward_c2_against_oracle():
+    """Config 2 (one segment of 16384 tokens, 16 heads): all four gradients at every token."""
+    inp, c = synth.config_inputs("c2", device="cuda")
+    print("whole backward c2", c, flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(4243)
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    got = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], dO, c["P"])
+    torch.cuda.synchronize()
+    ref = oracle.gla_recurrent_bwd(*(host(inp[n]) for n in ("q", "k", "v", "g")), host(dO))
+    print("  oracle done", flush=True)
+    for nm, x, r in zip(("dq", "dk", "dv", "dg"), got[:4], ref[:4]):
+        e = rel_err_bh(host(x), r, (0, 2))
+        print("    %s rel err %.4f" % (nm, e), flush=True)
+        assert e <= TOL[c["io"]], nm
+    assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= TOL[c["io"]]

@@ -72,51 +72,6 @@ template <int DK, int DV> struct QKCfg {
     }
 };
 
-template <int GM> struct GateRaw;
-template <> struct GateRaw<kGateHead> {
-    typedef float raw_t;
-    __device__ static __forceinline__ f32x4 get(raw_t r) { return f32x4{r, r, r, r}; }
-};
-template <> struct GateRaw<kGateF32> {
-    typedef f32x4 raw_t;
-    __device__ static __forceinline__ f32x4 get(raw_t r) { return r; }
-};
-template <> struct GateRaw<kGateBF16> {
-    typedef u32x2 raw_t;
-    __device__ static __forceinline__ f32x4 get(raw_t r) {
-        return f32x4{bf16_lo(r[0]), bf16_hi(r[0]), bf16_lo(r[1]), bf16_hi(r[1])};
-    }
-};
-
-// N consecutive bf16 values (two per word) stored as one LDS write.
-template <int N> struct Run;
-template <> struct Run<8> {
-    uint32_t w[4];
-    __device__ __forceinline__ void store(unsigned char *dst) const {
-        *reinterpret_cast<u32x4 *>(dst) = u32x4{w[0], w[1], w[2], w[3]};
-    }
-};
-template <> struct Run<4> {
-    uint32_t w[2];
-    __device__ __forceinline__ void store(unsigned char *dst) const {
-        *reinterpret_cast<u32x2 *>(dst) = u32x2{w[0], w[1]};
-    }
-};
-template <> struct Run<2> {
-    uint32_t w[1];
-    __device__ __forceinline__ void store(unsigned char *dst) const {
-        *reinterpret_cast<uint32_t *>(dst) = w[0];
-    }
-};
-
-// (x.lo, y.lo) and (x.hi, y.hi) of two packed bf16 pairs.
-__device__ __forceinline__ uint32_t lo_pair(uint32_t x, uint32_t y) {
-    return __builtin_amdgcn_perm(y, x, 0x05040100u);
-}
-__device__ __forceinline__ uint32_t hi_pair(uint32_t x, uint32_t y) {
-    return __builtin_amdgcn_perm(y, x, 0x07060302u);
-}
-
 __device__ __forceinline__ bf16x8 pack2x4(f32x4 a, f32x4 b) {
     u32x4 w = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]),
                pack_bf16(b[2], b[3])};
@@ -130,7 +85,7 @@ template <int DK, int DV, bool REV, int GM>
 __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     typedef QKCfg<DK, DV> Cfg;
     typedef Mma<16> M;
-    typedef GateRaw<GM> GV;
+    typedef GateVal<GM> GV;
     constexpr int XS = Cfg::XS, TS = Cfg::TS, FS = Cfg::FS, NW = Cfg::NW, NT = Cfg::NT;
     constexpr int TPT = Cfg::TPT, TPTV = Cfg::TPTV, CQ = Cfg::CQ, GW = Cfg::GW;
     constexpr int GB = GM == kGateBF16 ? 2 : 4;
@@ -340,7 +295,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             if (gl == GW - 1) *reinterpret_cast<f32x4 *>(wtot + w * DK + 4 * cq) = inc;
         }
         {
-            Run<TPTV> ch[4];
+            TokenRun<TPTV> ch[4];
 #pragma unroll
             for (int u = 0; u < TPTV; ++u) {
                 const int r = pos_of(tv * TPTV + u);
@@ -352,10 +307,10 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                 // tokens (2m, 2m+1) of the run share a word; reversed, the run is written back to front
                 const u32x2 a0 = REV ? ry[2 * m + 1] : ry[2 * m], a1 = REV ? ry[2 * m] : ry[2 * m + 1];
                 const int wd = REV ? TPTV / 2 - 1 - m : m;
-                ch[0].w[wd] = lo_pair(a0[0], a1[0]);
-                ch[1].w[wd] = hi_pair(a0[0], a1[0]);
-                ch[2].w[wd] = lo_pair(a0[1], a1[1]);
-                ch[3].w[wd] = hi_pair(a0[1], a1[1]);
+                ch[0].w[wd] = pair_lo(a0[0], a1[0]);
+                ch[1].w[wd] = pair_hi(a0[0], a1[0]);
+                ch[2].w[wd] = pair_lo(a0[1], a1[1]);
+                ch[3].w[wd] = pair_hi(a0[1], a1[1]);
             }
 #pragma unroll
             for (int u = 0; u < TPTV; ++u) {
@@ -384,7 +339,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                     total[a] += x[a];
                 }
             }
-            Run<TPT> zt[4];
+            TokenRun<TPT> zt[4];
             u32x2 zprev = {0u, 0u};
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
@@ -411,10 +366,10 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                 if (u % 2 == 1) {
                     const u32x2 a0 = REV ? zq : zprev, a1 = REV ? zprev : zq;
                     const int wd = REV ? (TPT - 1 - u) / 2 : u / 2;
-                    zt[0].w[wd] = lo_pair(a0[0], a1[0]);
-                    zt[1].w[wd] = hi_pair(a0[0], a1[0]);
-                    zt[2].w[wd] = lo_pair(a0[1], a1[1]);
-                    zt[3].w[wd] = hi_pair(a0[1], a1[1]);
+                    zt[0].w[wd] = pair_lo(a0[0], a1[0]);
+                    zt[1].w[wd] = pair_hi(a0[0], a1[0]);
+                    zt[2].w[wd] = pair_lo(a0[1], a1[1]);
+                    zt[3].w[wd] = pair_hi(a0[1], a1[1]);
                 }
                 zprev = zq;
             }

@@ -81,52 +81,6 @@ template <int DK, int DV, int NWG_> struct B16Cfg {
     }
 };
 
-// Four consecutive gate values of one token, as loaded and as floats.
-template <int GM> struct GateVal;
-template <> struct GateVal<kGateF32> {
-    typedef f32x4 raw_t;
-    __device__ static __forceinline__ f32x4 get(raw_t r) { return r; }
-};
-template <> struct GateVal<kGateHead> {
-    typedef float raw_t;
-    __device__ static __forceinline__ f32x4 get(raw_t r) { return f32x4{r, r, r, r}; }
-};
-template <> struct GateVal<kGateBF16> {
-    typedef u32x2 raw_t;
-    __device__ static __forceinline__ f32x4 get(raw_t r) {
-        return f32x4{bf16_lo(r[0]), bf16_hi(r[0]), bf16_lo(r[1]), bf16_hi(r[1])};
-    }
-};
-
-// N consecutive bf16 values (two per word) stored as one LDS write.
-template <int N> struct TokenRun;
-template <> struct TokenRun<8> {
-    uint32_t w[4];
-    __device__ __forceinline__ void store(unsigned char *dst) const {
-        *reinterpret_cast<u32x4 *>(dst) = u32x4{w[0], w[1], w[2], w[3]};
-    }
-};
-template <> struct TokenRun<4> {
-    uint32_t w[2];
-    __device__ __forceinline__ void store(unsigned char *dst) const {
-        *reinterpret_cast<u32x2 *>(dst) = u32x2{w[0], w[1]};
-    }
-};
-template <> struct TokenRun<2> {
-    uint32_t w[1];
-    __device__ __forceinline__ void store(unsigned char *dst) const {
-        *reinterpret_cast<uint32_t *>(dst) = w[0];
-    }
-};
-
-// Low halves / high halves of two packed bf16 pairs: (x.lo, y.lo) and (x.hi, y.hi).
-__device__ __forceinline__ uint32_t pair_lo(uint32_t x, uint32_t y) {
-    return __builtin_amdgcn_perm(y, x, 0x05040100u);
-}
-__device__ __forceinline__ uint32_t pair_hi(uint32_t x, uint32_t y) {
-    return __builtin_amdgcn_perm(y, x, 0x07060302u);
-}
-
 __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
     u32x4 w = {pack_bf16(a[base + 0], a[base + 1]), pack_bf16(a[base + 2], a[base + 3]),
                pack_bf16(a[base + 4], a[base + 5]), pack_bf16(a[base + 6], a[base + 7])};

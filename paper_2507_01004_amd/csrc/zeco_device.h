@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "zeco_internal.h"
+
 namespace zeco {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -70,6 +72,52 @@ __device__ __forceinline__ f32x4 mma_f32(float a, float b, f32x4 c) {
 // 16-byte LDS / global accessors on raw byte pointers.
 __device__ __forceinline__ bf16x8 lds_frag(const unsigned char *base, int byte_off) {
     return *reinterpret_cast<const bf16x8 *>(base + byte_off);
+}
+
+// Four consecutive gate values of one token, as loaded and as floats.
+template <int GM> struct GateVal;
+template <> struct GateVal<kGateF32> {
+    typedef f32x4 raw_t;
+    __device__ static __forceinline__ f32x4 get(raw_t r) { return r; }
+};
+template <> struct GateVal<kGateHead> {
+    typedef float raw_t;
+    __device__ static __forceinline__ f32x4 get(raw_t r) { return f32x4{r, r, r, r}; }
+};
+template <> struct GateVal<kGateBF16> {
+    typedef u32x2 raw_t;
+    __device__ static __forceinline__ f32x4 get(raw_t r) {
+        return f32x4{bf16_lo(r[0]), bf16_hi(r[0]), bf16_lo(r[1]), bf16_hi(r[1])};
+    }
+};
+
+// N consecutive bf16 values (two per word) stored as one LDS write.
+template <int N> struct TokenRun;
+template <> struct TokenRun<8> {
+    uint32_t w[4];
+    __device__ __forceinline__ void store(unsigned char *dst) const {
+        *reinterpret_cast<u32x4 *>(dst) = u32x4{w[0], w[1], w[2], w[3]};
+    }
+};
+template <> struct TokenRun<4> {
+    uint32_t w[2];
+    __device__ __forceinline__ void store(unsigned char *dst) const {
+        *reinterpret_cast<u32x2 *>(dst) = u32x2{w[0], w[1]};
+    }
+};
+template <> struct TokenRun<2> {
+    uint32_t w[1];
+    __device__ __forceinline__ void store(unsigned char *dst) const {
+        *reinterpret_cast<uint32_t *>(dst) = w[0];
+    }
+};
+
+// Low halves / high halves of two packed bf16 pairs: (x.lo, y.lo) and (x.hi, y.hi).
+__device__ __forceinline__ uint32_t pair_lo(uint32_t x, uint32_t y) {
+    return __builtin_amdgcn_perm(y, x, 0x05040100u);
+}
+__device__ __forceinline__ uint32_t pair_hi(uint32_t x, uint32_t y) {
+    return __builtin_amdgcn_perm(y, x, 0x07060302u);
 }
 
 }  // namespace zeco

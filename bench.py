@@ -192,7 +192,25 @@ def main():
         # dk and fp32 dg out)
         io = dk * 2
         pb = th * (2 * (2 * io + g_in) + (5 * io + g_in + g_cum) + (4 * io + g_in) + (5 * io + g_in + 2 * g_cum))
-        backward = {"entry": "zeco_gla_fused_bwd", "ms_per_step": round(bms, 4),
+        # training pair: the forward leaves the states at the backward's piece boundaries, the backward
+        # starts from them instead of recomputing them
+        save = torch.empty(zeco.saved_states_bytes(q, v, g, P), dtype=torch.uint8, device="cuda:0")
+        wsf = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
+        o4 = torch.empty_like(v)
+        pair = {}
+        for nm, fn in (("fwd_saving_ms", lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last), workspace=wsf, save=save)),
+                       ("bwd_from_saved_ms", lambda: zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws, saved=save))):
+            fn()
+            torch.cuda.synchronize()
+            pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            pe[0].record()
+            for _ in range(nb):
+                fn()
+            pe[1].record()
+            torch.cuda.synchronize()
+            pair[nm] = round(pe[0].elapsed_time(pe[1]) / nb, 4)
+        del save, wsf, o4
+        backward = {"entry": "zeco_gla_fused_bwd", "ms_per_step": round(bms, 4), **pair,
                     "tokens_per_s": round(B * T / (bms * 1e-3), 1), "pass_bytes": pb,
                     "GBps": round(pb / bms / 1e6, 1), "hbm_frac": round(pb / bms / 1e6 / HBM_PEAK_GBS, 4)}
         del ws, grads, dO

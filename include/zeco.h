@@ -127,10 +127,15 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *desc, const void *q, co
  * keep every compute unit busy); the states of those pieces live in the workspace.
  *   in   S0 [B,H,d_k,d_v] fp32 or NULL: state entering the first segment
  *   out  o;  S_last [B,H,d_k,d_v] fp32 or NULL: state after the last token
+ *   out  S_save: NULL, or zeco_gla_saved_states_bytes(desc) bytes of device memory that receive the
+ *        forward states at the boundaries of the pieces the backward works on (a d_k x d_v state per
+ *        512 tokens and head, and the end state); handing it to zeco_gla_fused_bwd spares that call the
+ *        recomputation of the forward states.  Contents are private to the library.
  * workspace: zeco_gla_fused_fwd_workspace(desc) bytes of device memory, 16-byte aligned. */
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc);
+size_t zeco_gla_saved_states_bytes(const zeco_gla_desc *desc);
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *desc, const void *q, const void *k, const void *v,
-                               const void *g, const float *S0, void *o, float *S_last,
+                               const void *g, const float *S0, void *o, float *S_last, float *S_save,
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- Backward pass (App. A.4): gradients of  sum_t <o_t, dO_t> + <S_T, dS_T>  for the forward above.
@@ -163,13 +168,15 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *desc, const void *q, co
  * S0), runs the state-gradient pass and its reverse scan (from dS_T), then the gradient passes.  Like
  * zeco_gla_fused_fwd it may cut the segments into shorter pieces.
  *   in   S0, dS_T [B,H,d_k,d_v] fp32 or NULL (zero)
+ *   in   S_saved: NULL, or what zeco_gla_fused_fwd left in S_save for the same descriptor and inputs
+ *        (S0 is then not read: it is already part of the saved states)
  *   out  dq, dk, dv, dg;  dS0 [B,H,d_k,d_v] fp32 or NULL: gradient of the state entering the first segment
  * workspace: zeco_gla_fused_bwd_workspace(desc) bytes of device memory, 16-byte aligned. */
 size_t zeco_gla_fused_bwd_workspace(const zeco_gla_desc *desc);
 zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *desc, const void *q, const void *k, const void *v,
                                const void *g, const void *dO, const float *S0, const float *dS_T,
-                               void *dq, void *dk, void *dv, float *dg, float *dS0, void *workspace,
-                               size_t workspace_bytes, void *stream);
+                               const float *S_saved, void *dq, void *dk, void *dv, float *dg, float *dS0,
+                               void *workspace, size_t workspace_bytes, void *stream);
 
 /* Bandwidth calibration utility (not part of the method): copies `bytes` (a multiple of 16) from
  * src to dst with a plain grid-stride kernel of 16-byte accesses.  Used to scale the HBM byte

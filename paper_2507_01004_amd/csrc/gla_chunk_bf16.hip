@@ -355,7 +355,12 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
                 *reinterpret_cast<f32x4 *>(gam_m + 4 * cq) = gm;
             }
-            if constexpr (MODE != kLocal && MODE != kStates) return;   // no decay outputs in the other passes
+            // decay outputs: the local pass and the two state passes (the backward one emits G_tot when
+            // asked, so that the reverse scan does not need the forward state pass)
+            if constexpr (MODE == kOutput || MODE == kDV) return;
+            if constexpr (MODE == kDState) {
+                if (!p.G_tot) return;
+            }
 #pragma unroll
             for (int a = 0; a < 4; ++a) {   // (hi, lo) += total, error-free transformation
                 const float x = total[a] + seg_lo[a];
@@ -537,6 +542,18 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         for (int n = 0; n < N; ++n) {
             const unsigned char *cur = lds + (n & 1) * Cfg::kTileBytes;
             ZPT(0);
+            if constexpr (MODE == kOutput) {
+                // the state entering every save_every-th chunk, kept for the backward pass
+                if (p.S_save && n % p.save_every == 0) {
+                    const size_t piece = (size_t)seg * (N / p.save_every) + n / p.save_every;
+                    float *Sv = p.S_save + ((piece * p.B + b) * p.H + h) * DK * (DV * NS) + slice * DV + w * 32 + lt;
+#pragma unroll
+                    for (int it = 0; it < Cfg::NIT; ++it)
+#pragma unroll
+                        for (int rr = 0; rr < 16; ++rr)
+                            Sv[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] = Sacc[it][rr];
+                }
+            }
             if constexpr (!NOQ) mfma_a(cur, gam + (n & 1) * DK);
             ZPT(2);
             __syncthreads();

@@ -141,7 +141,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
 // ---- two-phase forward ------------------------------------------------------------------------------
 static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
     p.q = p.k = p.v = p.g = nullptr; p.o = nullptr;
-    p.S_loc = p.G_cum = p.G_tot = nullptr; p.S_init = nullptr;
+    p.S_loc = p.G_cum = p.G_tot = nullptr; p.S_init = nullptr; p.S_save = nullptr; p.save_every = 0;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
     p.n_chunks = d->L / d->C;
     p.scale = d->scale; p.kscale = 1.f;
@@ -191,6 +191,8 @@ static int fused_pieces(const zeco_gla_desc *d) {
     return S;
 }
 
+static int bwd_pieces(const zeco_gla_desc *d);
+
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
     if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     const size_t n = (size_t)desc->P * fused_pieces(desc) * desc->B * desc->H;
@@ -198,13 +200,13 @@ size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
 }
 
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
-                               const void *g, const float *S0, void *o, float *S_last, void *workspace,
-                               size_t workspace_bytes, void *stream) {
+                               const void *g, const float *S0, void *o, float *S_last, float *S_save,
+                               void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d);
     if (st != ZECO_OK) return st;
     if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
-        !aligned16(S0) || !aligned16(S_last) || !aligned16(workspace))
+        !aligned16(S0) || !aligned16(S_last) || !aligned16(S_save) || !aligned16(workspace))
         return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_gla_fused_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
@@ -221,12 +223,20 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::ScanParams sp;
-    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
+    // With S_save the end state goes to its last slot (the backward reads it there).
+    const int Sb = bwd_pieces(d);
+    float *save_last = S_save ? S_save + (size_t)d->P * Sb * d->B * d->H * d->d_k * d->d_v : nullptr;
+    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_save ? save_last : S_last;
     sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
     sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
 
+    if (S_save && S_last) {
+        e = zeco::launch_copy(S_last, save_last, (size_t)d->B * d->H * d->d_k * d->d_v * sizeof(float), s);
+        if (e != hipSuccess) return ZECO_ERR_HIP;
+    }
     p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;
+    p.S_save = S_save; p.save_every = (d->L / Sb) / d->C;
     return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, s));
 }
 
@@ -319,6 +329,12 @@ static BwdLayout bwd_layout(const zeco_gla_desc *d, int S) {
     return w;
 }
 
+size_t zeco_gla_saved_states_bytes(const zeco_gla_desc *desc) {
+    if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    const BwdLayout w = bwd_layout(desc, bwd_pieces(desc));
+    return (w.n + (size_t)desc->B * desc->H) * w.state * sizeof(float);
+}
+
 size_t zeco_gla_fused_bwd_workspace(const zeco_gla_desc *desc) {
     if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     return bwd_layout(desc, bwd_pieces(desc)).total * sizeof(float);
@@ -326,13 +342,13 @@ size_t zeco_gla_fused_bwd_workspace(const zeco_gla_desc *desc) {
 
 zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
                                const void *g, const void *dO, const float *S0, const float *dS_T,
-                               void *dq, void *dk, void *dv, float *dg, float *dS0, void *workspace,
-                               size_t workspace_bytes, void *stream) {
+                               const float *S_saved, void *dq, void *dk, void *dv, float *dg, float *dS0,
+                               void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d);
     if (st != ZECO_OK) return st;
     if (!q || !k || !v || !g || !dO || !dq || !dk || !dv || !dg || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
-        !aligned16(S0) || !aligned16(dS_T) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) ||
+        !aligned16(S0) || !aligned16(dS_T) || !aligned16(S_saved) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) ||
         !aligned16(dg) || !aligned16(dS0) || !aligned16(workspace))
         return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
@@ -347,26 +363,33 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     const int gb = gate_mode(d);
     const int P = d->P * S, L = d->L / S;
 
-    // forward states at the piece boundaries (recomputed: phase 1 of the forward and its scan)
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.P = P; p.L = L; p.n_chunks = L / d->C;
-    p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 1, s);
-    if (e != hipSuccess) return ZECO_ERR_HIP;
     zeco::ScanParams sp;
-    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
     sp.P = P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
     sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
-    if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+    hipError_t e;
+    const float *Sin = Sinit, *Sl = Slast;
+    if (S_saved) {
+        // forward states at the piece boundaries as the forward left them
+        Sin = S_saved; Sl = S_saved + w.n * w.state;
+    } else {
+        // recomputed: phase 1 of the forward and its scan
+        p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
+        if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 1, s)) != hipSuccess) return ZECO_ERR_HIP;
+        sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
+        if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+    }
 
-    // state gradients: local reverse pass, then the chain from the last piece to the first
-    p.k = q; p.v = dO; p.S_loc = dSloc; p.G_tot = nullptr; p.kscale = d->scale;
+    // state gradients: local reverse pass (which also emits the pieces' total decays when the forward
+    // state pass did not run), then the chain from the last piece to the first
+    p.k = q; p.v = dO; p.g = g; p.S_loc = dSloc; p.G_tot = S_saved ? Gtot : nullptr; p.kscale = d->scale;
     if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 3, s)) != hipSuccess) return ZECO_ERR_HIP;
-    sp.S_loc = dSloc; sp.S0 = dS_T; sp.S_init = dSin; sp.S_last = dS0; sp.reverse = 1;
+    sp.S_loc = dSloc; sp.G_tot = Gtot; sp.S0 = dS_T; sp.S_init = dSin; sp.S_last = dS0; sp.reverse = 1;
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
 
-    return bwd_passes(d, P, L, q, k, v, g, dO, Sinit, Slast, dSin, dq, dk, dv, dg, s);
+    return bwd_passes(d, P, L, q, k, v, g, dO, Sin, Sl, dSin, dq, dk, dv, dg, s);
 }
 
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,

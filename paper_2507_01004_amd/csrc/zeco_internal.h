@@ -14,6 +14,8 @@ struct ChunkParams {
     void *o;
     float *S_loc, *G_cum, *G_tot;
     const float *S_init;       // [P,B,H,d_k,d_v] initial states (output-pass mode only)
+    float *S_save = nullptr;   // output pass: states entering every save_every-th chunk,
+    int save_every = 0;        //   [P * n_chunks / save_every, B, H, d_k, d_v]
     int B, P, H, L;
     int n_chunks;              // L / 64
     float scale;

@@ -17,7 +17,7 @@ ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ER
 ZECO_F32, ZECO_BF16 = 0, 1
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
            "zeco_apply_init_state", "zeco_gla_local_state", "zeco_gla_fwd_from_state",
-           "zeco_gla_fused_fwd_workspace", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
+           "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
            "zeco_gla_bwd_from_state", "zeco_gla_fused_bwd_workspace", "zeco_gla_fused_bwd",
            "zeco_hbm_copy", "zeco_status_string", "zeco_version")
 
@@ -66,7 +66,9 @@ def lib():
         L.zeco_gla_fwd_from_state.restype = i32
         L.zeco_gla_fused_fwd_workspace.argtypes = [dp]
         L.zeco_gla_fused_fwd_workspace.restype = ctypes.c_size_t
-        L.zeco_gla_fused_fwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_saved_states_bytes.argtypes = [dp]
+        L.zeco_gla_saved_states_bytes.restype = ctypes.c_size_t
+        L.zeco_gla_fused_fwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, fp, fp, vp, ctypes.c_size_t, vp]
         L.zeco_gla_fused_fwd.restype = i32
         L.zeco_gla_bwd_dstate.argtypes = [dp, vp, vp, vp, fp, vp]
         L.zeco_gla_bwd_dstate.restype = i32
@@ -74,7 +76,7 @@ def lib():
         L.zeco_gla_bwd_from_state.restype = i32
         L.zeco_gla_fused_bwd_workspace.argtypes = [dp]
         L.zeco_gla_fused_bwd_workspace.restype = ctypes.c_size_t
-        L.zeco_gla_fused_bwd.argtypes = [dp] + [vp] * 5 + [fp] * 2 + [vp] * 3 + [fp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_fused_bwd.argtypes = [dp] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, fp, vp, ctypes.c_size_t, vp]
         L.zeco_gla_fused_bwd.restype = i32
         L.zeco_hbm_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.zeco_hbm_copy.restype = i32
@@ -255,8 +257,14 @@ def fused_workspace_bytes(q, v, g, P, C=64):
     return int(lib().zeco_gla_fused_fwd_workspace(ctypes.byref(make_desc(q, v, g, P, C, 1.0))))
 
 
-def gla_fused_fwd(q, k, v, g, P, scale=1.0, S0=None, C=64, out=None, workspace=None, want_last=True):
-    """zeco_gla_fused_fwd: both phases and the scan in one call.  Returns (o, S_last)."""
+def saved_states_bytes(q, v, g, P, C=64):
+    return int(lib().zeco_gla_saved_states_bytes(ctypes.byref(make_desc(q, v, g, P, C, 1.0))))
+
+
+def gla_fused_fwd(q, k, v, g, P, scale=1.0, S0=None, C=64, out=None, workspace=None, want_last=True,
+                  save=None):
+    """zeco_gla_fused_fwd: both phases and the scan in one call.  Returns (o, S_last).  `save`: a uint8
+    tensor of saved_states_bytes() that receives the forward states for gla_fused_bwd(saved=...)."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
@@ -272,8 +280,10 @@ def gla_fused_fwd(q, k, v, g, P, scale=1.0, S0=None, C=64, out=None, workspace=N
         S_last = torch.empty(B, H, dk, dv, dtype=torch.float32, device=q.device) if want_last else None
     else:
         o, S_last = out
+    if save is not None and save.numel() < L.zeco_gla_saved_states_bytes(ctypes.byref(desc)):
+        raise ValueError("`save` is smaller than saved_states_bytes()")
     st = L.zeco_gla_fused_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(S0), _ptr(o),
-                              _ptr(S_last), _ptr(workspace), workspace.numel(), _stream())
+                              _ptr(S_last), _ptr(save), _ptr(workspace), workspace.numel(), _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_gla_fused_fwd")
     return o, S_last
@@ -324,7 +334,7 @@ def fused_bwd_workspace_bytes(q, v, g, P, C=64):
 
 
 def gla_fused_bwd(q, k, v, g, dO, P, scale=1.0, S0=None, dS_T=None, C=64, out=None, workspace=None,
-                  want_dS0=True):
+                  want_dS0=True, saved=None):
     """zeco_gla_fused_bwd: the whole backward in one call.  Returns (dq, dk, dv, dg, dS0)."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
@@ -343,7 +353,7 @@ def gla_fused_bwd(q, k, v, g, dO, P, scale=1.0, S0=None, dS_T=None, C=64, out=No
     else:
         dq, dk, dv, dg, dS0 = out
     st = L.zeco_gla_fused_bwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(dO), _ptr(S0),
-                              _ptr(dS_T), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(dS0),
+                              _ptr(dS_T), _ptr(saved), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(dS0),
                               _ptr(workspace), workspace.numel(), _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_gla_fused_bwd")

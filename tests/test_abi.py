@@ -116,7 +116,7 @@ def test_backward_entry_points_reject_bad_arguments(L):
     assert L.zeco_gla_bwd_from_state(ref(d), *args, None) == zeco.ZECO_ERR_INVALID_ARG
     need = L.zeco_gla_fused_bwd_workspace(ref(d))
     assert need > 0 and L.zeco_gla_fused_bwd_workspace(ref(f32)) == 0
-    fused = [FAKE] * 5 + [None, None] + [FAKE] * 4 + [None, FAKE]
+    fused = [FAKE] * 5 + [None, None, None] + [FAKE] * 4 + [None, FAKE]
     assert L.zeco_gla_fused_bwd(ref(d), *fused, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
     fused[0] = ctypes.c_void_p(0x1004)
     assert L.zeco_gla_fused_bwd(ref(d), *fused, need, None) == zeco.ZECO_ERR_INVALID_ARG

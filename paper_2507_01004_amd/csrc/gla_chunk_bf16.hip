@@ -251,6 +251,29 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             for (int a = 0; a < 4; ++a) ch[a].store(tile + Cfg::kOffVT + (4 * vq + a) * TS + p0 * 2);
         };
 
+        // Output rows.  The MFMA waves leave the finished O tile of chunk c (bf16, token-major) in the Qs
+        // (and, when d_v > d_k, Ks) tile of the buffer chunk c used, which nobody reads after the scores
+        // and the inter-chunk product.  The gate waves copy it to HBM just before they overwrite the same
+        // bytes with the tiles of chunk c+2: a thread moves exactly the 8 bytes per row it is about to
+        // reuse, and the 32 lanes that share a token write one contiguous row (the accumulator layout
+        // itself would give 16-byte pieces, which cost about twice their share of the traffic).
+        unsigned char *og = (unsigned char *)p.o + vbase * 2;
+        auto flush_o = [&](int c, unsigned char *tile, int u0, int u1) __attribute__((always_inline)) {
+            if constexpr (!NOQ) {
+                unsigned char *oc = og + (long long)chunk_of(c) * 64 * vt * 2;   // uniform
+#pragma unroll
+                for (int u = u0; u < u1; ++u) {
+                    const int t = tq * TPT + u;
+                    if (qpos < DV)
+                        *reinterpret_cast<u32x2 *>(oc + ((size_t)t * vt + qpos) * 2) =
+                            *reinterpret_cast<const u32x2 *>(tile + Cfg::kOffQ + pos_of(t) * QS + qpos * 2);
+                    if constexpr (DV > DK)
+                        *reinterpret_cast<u32x2 *>(oc + ((size_t)t * vt + DK + qpos) * 2) =
+                            *reinterpret_cast<const u32x2 *>(tile + Cfg::kOffK + pos_of(t) * QS + qpos * 2);
+                }
+            }
+        };
+
         // part 2 of chunk m: stitch waves (setup), scale q and k -> tile buffer and G_cum -> HBM in two
         // token halves, then gamma and the segment prefix (finish)
         f32x4 pre2, gbase, total;
@@ -284,6 +307,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             unsigned char *Gm = Gb + (long long)m * 64 * gcs * 4;
             TokenRun<HT> kt[4];
             u32x2 kprev = {0u, 0u};
+            if (m >= 2) flush_o(m - 2, tile, half * HT, half * HT + HT);   // before these rows are rewritten
 #pragma unroll
             for (int uu = 0; uu < HT; ++uu) {
                 const int u = half * HT + uu;
@@ -423,14 +447,19 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             gate_b_finish(n + 1, gam + ((n + 1) & 1) * DK);
             __syncthreads();
         }
-        __syncthreads();   // n = N-1: nothing left to produce, keep in step with the MFMA waves
+        // n = N-1: nothing left to produce; the output rows of the last two chunks are still in LDS
+        if (N > 1) flush_o(N - 2, lds + ((N - 2) & 1) * Cfg::kTileBytes, 0, TPT);
         __syncthreads();
+        __syncthreads();
+        flush_o(N - 1, lds + ((N - 1) & 1) * Cfg::kTileBytes, 0, TPT);
     } else {
         // ================================ MFMA waves ===========================================
         const int lt = lane & 31, kg = lane >> 5;       // 32x32x16 lane coordinates
         const int l16 = lane & 15, kg16 = lane >> 4;    // 16x16x32 lane coordinates (score tiles)
-        unsigned char *ob = (unsigned char *)p.o + vbase * 2;
-        const unsigned o_b0 = ((unsigned)pos_of(lt) * vt + w * 32 + 4 * kg) * 2;   // O^T byte offset of this lane
+        // this lane's 8-byte slots in the staged O tile: row lt (+32 mt), columns 32 w + 8 qd + 4 kg ..+3;
+        // columns beyond d_k continue in the Ks tile
+        const int o_col = w * 32 + 4 * kg;
+        const unsigned o_s0 = (o_col < DK ? Cfg::kOffQ : Cfg::kOffK - DK * 2) + lt * QS + o_col * 2;
 
         f32x16 Sacc[Cfg::NIT], Oacc[2];
         float *Sl = p.S_loc + sbh * DK * (DV * NS) + slice * DV + w * 32 + lt;   // this lane's state column
@@ -501,7 +530,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         // part 2 of chunk n: intra-chunk output, O store, state update
         auto mfma_b = [&](int n, const unsigned char *tile, const float *gam_n) __attribute__((always_inline)) {
             const unsigned char *Kt = tile + Cfg::kOffKT, *Vt = tile + Cfg::kOffVT;
-            unsigned char *on = ob + (long long)chunk_of(n) * 64 * vt * 2;   // uniform
+            unsigned char *os = const_cast<unsigned char *>(tile) + o_s0;
             if constexpr (MODE == kDState) decay_state(gam_n);
             bf16x8 vf[4];
 #pragma unroll
@@ -514,7 +543,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                     Oacc[mt] = M::run(vf[ks], lds_frag(Ps, (mt * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), Oacc[mt]);
 #pragma unroll
                 for (int qd = 0; qd < 4; ++qd)
-                    *reinterpret_cast<u32x2 *>(on + ((long long)(REV ? -mt : mt) * 32 * vt + 8 * qd) * 2 + o_b0) =
+                    *reinterpret_cast<u32x2 *>(os + mt * 32 * QS + 8 * qd * 2) =
                         u32x2{pack_bf16(Oacc[mt][4 * qd] * p.scale, Oacc[mt][4 * qd + 1] * p.scale),
                               pack_bf16(Oacc[mt][4 * qd + 2] * p.scale, Oacc[mt][4 * qd + 3] * p.scale)};
             }

@@ -194,13 +194,18 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     f32x4 rqd[TPT], dterm[TPT];
     f32x4 later_in_wave = {0.f, 0.f, 0.f, 0.f};
 
-    // first half: terms from the fp32 result tile in Fs; dQ stores them, dK starts the reverse sums
+    // first half: the finished chunk's gradient rows go to HBM, and the dG terms are formed from the fp32
+    // result tile in Fs; dQ stores them, dK starts the reverse sums
     auto dg_first = [&](long long tc) __attribute__((always_inline)) {
         float *row = dgb + (tc + tq * TPT) * gcs + (GH ? 0 : 4 * cq);
         f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = TPT - 1; u >= 0; --u) {
             const f32x4 val = *reinterpret_cast<const f32x4 *>(Fs + pos_of(tq * TPT + u) * FS + 16 * cq);
+            // the gradient itself: 32 lanes write one contiguous row (the accumulator layout of the
+            // products would give 32-byte pieces)
+            *reinterpret_cast<u32x2 *>(ob + ((tc + tq * TPT + u) * st + 4 * cq) * 2) =
+                u32x2{pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
             const u32x2 zw = rz2[u];
             const f32x4 pr = {bf16_lo(zw[0]) * val[0], bf16_hi(zw[0]) * val[1],
                               bf16_lo(zw[1]) * val[2], bf16_hi(zw[1]) * val[3]};
@@ -458,9 +463,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             const f32x4 f = *reinterpret_cast<const f32x4 *>(fr);
             const f32x4 val = {Oacc[mt][0] * f[0] * p.oscale, Oacc[mt][1] * f[1] * p.oscale,
                                Oacc[mt][2] * f[2] * p.oscale, Oacc[mt][3] * f[3] * p.oscale};
-            *reinterpret_cast<f32x4 *>(fr) = val;   // fp32 gradient, read back by the dG bookkeeping
-            unsigned char *orow = ob + ((t0 + pos_of(r)) * st + w * 16 + 4 * kg) * 2;
-            *reinterpret_cast<u32x2 *>(orow) = u32x2{pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
+            *reinterpret_cast<f32x4 *>(fr) = val;   // fp32 gradient; stored and used for dG one chunk later
         }
         // ---- state: W += Yt Zt^T (then the column decay in the forward direction) ---------------------
 #pragma unroll

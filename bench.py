@@ -258,6 +258,26 @@ def main():
         copy_gbs = 5 * 2 * src.numel() / ce[0].elapsed_time(ce[1]) / 1e6
         del src, dst
 
+    # The correction stops, per (segment, head), where the decay factor exp(G_cum) has become an exact
+    # zero; the same kernel made to stream every token gives its bandwidth on the full traffic.
+    dense_ms = None
+    if P > 1:
+        de = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
+        nd = max(1, args.steps // 2)
+        de[0].record()
+        for _ in range(nd):
+            zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
+        de[1].record()
+        torch.cuda.synchronize()
+        dense_ms = de[0].elapsed_time(de[1]) / nd
+        # tokens per (segment, head) the default call works on: up to the first 64-token block whose
+        # first token has G_cum < -105 in every channel
+        Gs = G_cum.view((B, P, L // 64, 64, H) + gdim)[:, 1:, :, 0]
+        alive = (Gs >= -105.0).any(dim=-1) if args.gate == "channel" else (Gs >= -105.0)
+        live_frac = float(alive.float().mean().item())
+        del Gs, alive
+
     import statistics
     samples = {n: [e[i].elapsed_time(e[i + 1]) for e in evs] for i, n in enumerate(["local", "scan", "apply"])}
     ms = {n: sum(x) / len(x) for n, x in samples.items()}
@@ -292,6 +312,20 @@ def main():
                 kernels[n]["TFLOPs"] = round(af[n] / ms[n] / 1e9, 1)
                 kernels[n]["mfma_frac"] = round(af[n] / ms[n] / 1e9 / MFMA_BF16_PEAK_TF, 4)
     kernels["local"]["tokens_per_s"] = round(B * T / (ms["local"] * 1e-3), 1)
+    if dense_ms and "apply" in kernels:
+        ka = kernels["apply"]
+        ka["live_fraction"] = round(live_frac, 4)
+        ka["alg_bytes"] = int(ab["apply"] * live_frac)
+        ka["GBps"] = round(ka["alg_bytes"] / ms["apply"] / 1e6, 1)
+        ka["hbm_frac"] = round(ka["GBps"] / HBM_PEAK_GBS, 4)
+        ka.pop("TFLOPs", None)
+        ka.pop("mfma_frac", None)
+        ka["note"] = ("stops where exp(G_cum) is an exact zero in every channel (bitwise the same o); alg_bytes "
+                      "counts the 64-token blocks it works on; dense_* = the same kernel streaming every token")
+        ka["dense_ms"] = round(dense_ms, 4)
+        ka["dense_alg_bytes"] = ab["apply"]
+        ka["dense_GBps"] = round(ab["apply"] / dense_ms / 1e6, 1)
+        ka["dense_hbm_frac"] = round(ab["apply"] / dense_ms / 1e6 / HBM_PEAK_GBS, 4)
     if scan_cold:
         kernels["scan"]["cold_cache_ms"] = round(scan_cold, 4)
         kernels["scan"]["cold_cache_GBps"] = round(ab["scan"] / scan_cold / 1e6, 1)

@@ -98,12 +98,19 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
 /* Initial-state correction (Eq. (global-correction) carried to the output; the highlighted term
  * of Alg. 1's output pass, with Lambda_t .* gamma~_[n-1] = exp(G_cum[t])):
  *   o_t += (scale * q_t .* exp(G_cum[t])) S_init[p]      for every token t of segment p
- *   in     q (descriptor layout), G_cum [B,T,H,d_k] fp32, S_init [P,B,H,d_k,d_v] fp32
+ *   in     q (descriptor layout), G_cum [B,T,H,d_k] fp32, S_init [P,B,H,d_k,d_v] fp32 (finite values)
  *   in/out o (descriptor layout)
- * first_segment_is_zero != 0: segment 0 is skipped (its incoming state is known to be zero). */
+ * flags: bit set of
+ *   ZECO_APPLY_FIRST_SEGMENT_ZERO  segment 0 is skipped (its incoming state is known to be zero)
+ *   ZECO_APPLY_DENSE               stream every token.  Without it the call stops, per (batch, segment,
+ *                                  head) and at 64-token granularity, at the first token whose G_cum is
+ *                                  below -105 in every channel: exp() of that is exactly zero in fp32,
+ *                                  and because g <= 0 makes G_cum non-increasing along a segment the same
+ *                                  holds for all later tokens, whose o the update would leave unchanged.
+ *                                  Both settings give the same o (a -0 may come out as +0 when dense). */
+enum { ZECO_APPLY_FIRST_SEGMENT_ZERO = 1, ZECO_APPLY_DENSE = 2 };
 zeco_status zeco_apply_init_state(const zeco_gla_desc *desc, const void *q, const float *G_cum,
-                                  const float *S_init, void *o, int32_t first_segment_is_zero,
-                                  void *stream);
+                                  const float *S_init, void *o, int32_t flags, void *stream);
 
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
  * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns

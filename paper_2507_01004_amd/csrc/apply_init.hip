@@ -5,10 +5,20 @@
 // once, S_init[p] is loaded once per workgroup and kept in registers as an MFMA operand, and the
 // contraction runs on the matrix cores (at 25.6 flop/byte it would be ALU-bound on plain FMAs).
 // A workgroup takes `tokens_per_wg` consecutive tokens of one (batch, segment, head).
+//
+// Vanished decay.  The log decay is <= 0, so G_cum never increases along a segment.  Once every
+// channel of a token has G_cum < kVanish, exp(G_cum) is exactly 0 in fp32 for that token and all
+// later ones of the segment (2^-151 rounds to zero even with denormals), the product above is an
+// exact zero and o keeps its value: the kernel stops there instead of streaming q, G_cum and o
+// through to add nothing.  With the decays of a trained GLA layer (e-folding length of tens to
+// hundreds of tokens) that is all but the first few thousand tokens of a long segment.  `dense`
+// switches the test off (measurement of the full-traffic kernel, equality tests).
 #include "zeco_device.h"
 #include "zeco_internal.h"
 
 namespace zeco {
+
+constexpr float kVanish = -105.f;   // exp2(-105 log2(e)) = 2^-151.5 rounds to 0 in fp32
 
 // ------------------------------------------------------------------------------------------ bf16
 template <int DK, int DV> struct ApplyCfg {
@@ -32,16 +42,27 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     typedef Mma<Cfg::TILE> M;
     constexpr int TILE = Cfg::TILE, KS = Cfg::KS, QS = Cfg::QS;
     __shared__ __align__(16) unsigned char lds[Cfg::kBytes];
+    __shared__ int gone[4];
     unsigned char *Qh = lds;                                      // scale * q .* exp(G_cum), bf16
     float *Cs = reinterpret_cast<float *>(lds + 64 * QS);         // correction tile, fp32
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int lt = lane % TILE, kg = lane / TILE;
 
-    const int blocks_per_seg = p.L / p.tokens_per_wg;
-    int id = blockIdx.x;
-    const int tb = id % blocks_per_seg;
-    id /= blocks_per_seg;
+    // Workgroup id -> (group of 128 streams, token block, stream in the group), a stream being a
+    // (segment, batch, head).  Inside a group the early token blocks of every stream come first - the
+    // ones with work left once the decay has vanished - and spread evenly over the XCDs, which take
+    // workgroup ids round-robin; a stream stays on one XCD (128 is a multiple of 8), and a group's
+    // S_init states (8 MiB at d = 128) stay in the L2s while its token blocks are worked through.
+    constexpr int kGroup = 128;
+    const int blocks_per_seg = p.L / p.tokens_per_wg, streams = (p.P - p.p0) * p.B * p.H;
+    const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
+    const int gsz = min(kGroup, streams - grp * kGroup);
+    const int tb = r / gsz, j = r % gsz;
+    // position j of a row -> stream: rotated inside each aligned block of 8 by the block's index, so that
+    // the streams of one head (which share a decay speed, hence an amount of work) do not all fall on the
+    // same XCD when H is a multiple of 8
+    int id = grp * kGroup + (((j | 7) < gsz) ? (j & ~7) + ((j - (j >> 3)) & 7) : j);
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + id / p.B;
@@ -53,6 +74,16 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * (GH ? 1 : DK);
     const long long gcs = (long long)p.H * (GH ? 1 : DK);
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
+
+    // Nothing to add from this workgroup's first token on?  (Rebasing G_cum touches every token.)
+    const bool may_stop = !p.dense && !p.G_off;
+    auto all_gone = [&](bool mine) {   // workgroup-wide AND; ends with a barrier
+        const bool wave_all = __ballot(mine) == ~0ull;
+        if (lane == 0) gone[w] = wave_all;
+        __syncthreads();
+        return (gone[0] & gone[1] & gone[2] & gone[3]) != 0;
+    };
+    if (may_stop && all_gone(Gc[GH ? 0 : tid % DK] < kVanish)) return;
 
     // S_init[p] columns [w*TILE, (w+1)*TILE) as the A operand of O^T = S^T Qh^T: lane holds column
     // lt and, for k-step ks, channels ks*KS + 8*kg .. +7.
@@ -115,6 +146,14 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         u32x4 ocur[Cfg::OITEMS];
 #pragma unroll
         for (int m = 0; m < Cfg::OITEMS; ++m) ocur[m] = onx[m];
+        if (may_stop && blk > 0) {   // first token of this block: item 0 of the threads tid < DK/8
+            bool mine = true;
+            if (tid < DK / 8) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) mine = mine && cur.g0[0][e] < kVanish && cur.g1[0][e] < kVanish;
+            }
+            if (all_gone(mine)) break;
+        }
 #pragma unroll
         for (int m = 0; m < Cfg::ITEMS; ++m) {
             const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
@@ -176,10 +215,20 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4;
 
-    const int blocks_per_seg = p.L / p.tokens_per_wg;
-    int id = blockIdx.x;
-    const int tb = id % blocks_per_seg;
-    id /= blocks_per_seg;
+    // Workgroup id -> (group of 128 streams, token block, stream in the group), a stream being a
+    // (segment, batch, head).  Inside a group the early token blocks of every stream come first - the
+    // ones with work left once the decay has vanished - and spread evenly over the XCDs, which take
+    // workgroup ids round-robin; a stream stays on one XCD (128 is a multiple of 8), and a group's
+    // S_init states (8 MiB at d = 128) stay in the L2s while its token blocks are worked through.
+    constexpr int kGroup = 128;
+    const int blocks_per_seg = p.L / p.tokens_per_wg, streams = (p.P - p.p0) * p.B * p.H;
+    const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
+    const int gsz = min(kGroup, streams - grp * kGroup);
+    const int tb = r / gsz, j = r % gsz;
+    // position j of a row -> stream: rotated inside each aligned block of 8 by the block's index, so that
+    // the streams of one head (which share a decay speed, hence an amount of work) do not all fall on the
+    // same XCD when H is a multiple of 8
+    int id = grp * kGroup + (((j | 7) < gsz) ? (j & ~7) + ((j - (j >> 3)) & 7) : j);
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + id / p.B;
@@ -190,6 +239,8 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     const float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
     const long long gcs = (long long)p.H * DK;
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
+
+    if (!p.dense && __syncthreads_and(Gc[tid % DK] < kVanish)) return;   // see "Vanished decay"
 
     f32x4 Sreg[DK / 16];   // B operand: register r of tile it = S[16 it + 4 kg + r][16 w + l16]
 #pragma unroll

@@ -414,18 +414,19 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
 }
 
 zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const float *G_cum,
-                                  const float *S_init, void *o, int32_t first_segment_is_zero,
-                                  void *stream) {
+                                  const float *S_init, void *o, int32_t flags, void *stream) {
     const zeco_status st = check_desc(d);
     if (st != ZECO_OK) return st;
     if (!q || !G_cum || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(G_cum) || !aligned16(S_init) || !aligned16(o))
         return ZECO_ERR_INVALID_ARG;
+    if (flags & ~(ZECO_APPLY_FIRST_SEGMENT_ZERO | ZECO_APPLY_DENSE)) return ZECO_ERR_INVALID_ARG;
 
     zeco::ApplyParams p;
     p.q = q; p.G_cum = const_cast<float *>(G_cum); p.S_init = S_init; p.G_off = nullptr; p.o = o;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
-    p.p0 = first_segment_is_zero ? 1 : 0; p.skip_mod = 0; p.gate_per_head = d->g_per_head;
+    p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0; p.skip_mod = 0; p.gate_per_head = d->g_per_head;
+    p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
     int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
     while (tpw > 64 && d->L % tpw != 0) tpw >>= 1;
     p.tokens_per_wg = tpw;

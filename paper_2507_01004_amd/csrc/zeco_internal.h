@@ -41,6 +41,7 @@ struct ApplyParams {
     int skip_mod;              // > 0: segments with index % skip_mod == 0 are left untouched
     int tokens_per_wg;         // multiple of 64 dividing L
     int gate_per_head = 0;     // 1: G_cum [B,T,H] (bf16 kernel only, no rebasing)
+    int dense = 0;             // 1: stream every token, also where exp(G_cum) has vanished
     float scale;
     long long sb, st, sh, vb, vt, vh;
 };

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
 
 ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
 ZECO_F32, ZECO_BF16 = 0, 1
+APPLY_FIRST_SEGMENT_ZERO, APPLY_DENSE = 1, 2
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
            "zeco_apply_init_state", "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
@@ -207,14 +208,17 @@ def state_scan(S_loc, G_tot, S0=None, K_blocks=16, out=None, direction=0):
     return S_init, S_last
 
 
-def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segment_is_zero=True):
+def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segment_is_zero=True,
+                     dense=False):
     """zeco_apply_init_state: o += (scale q .* exp(G_cum)) S_init[p], in place.  `g_like` only
-    supplies the gate dtype recorded in the descriptor; G_cum [B,T,H] selects per-head gates."""
+    supplies the gate dtype recorded in the descriptor; G_cum [B,T,H] selects per-head gates.
+    dense: also stream the tokens whose decay factor has vanished (ZECO_APPLY_DENSE)."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     desc = _desc(q, o, _dtype_code(g_like), G_cum.dim() == 3, P, C, scale)
     st = lib().zeco_apply_init_state(ctypes.byref(desc), _ptr(q), _ptr(G_cum), _ptr(S_init), _ptr(o),
-                                     1 if first_segment_is_zero else 0, _stream())
+                                     (APPLY_FIRST_SEGMENT_ZERO if first_segment_is_zero else 0)
+                                     | (APPLY_DENSE if dense else 0), _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_apply_init_state")
     return o

@@ -75,6 +75,11 @@ def test_local_fwd_rejects_bad_descriptors(L, kw, expect):
     assert L.zeco_apply_init_state(ctypes.byref(good_desc(**kw)), FAKE, FAKE, FAKE, FAKE, 1, None) == expect
 
 
+def test_apply_init_state_rejects_unknown_flags(L):
+    assert L.zeco_apply_init_state(ctypes.byref(good_desc()), FAKE, FAKE, FAKE, FAKE, 4, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_apply_init_state(ctypes.byref(good_desc()), None, FAKE, FAKE, FAKE, 3, None) == zeco.ZECO_ERR_INVALID_ARG
+
+
 def test_local_fwd_rejects_bad_pointers(L):
     assert call_local(L, good_desc(), q=None) == zeco.ZECO_ERR_INVALID_ARG
     assert call_local(L, good_desc(), o=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG

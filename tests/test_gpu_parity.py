@@ -142,6 +142,56 @@ def test_apply_init_state_matches_oracle(io, dims):
     assert torch.equal(o, o0)
 
 
+@pytest.mark.parametrize("io", ["f32", "bf16"])
+@pytest.mark.parametrize("per_head", [False, True])
+def test_apply_init_state_stops_where_the_decay_has_vanished(io, per_head):
+    """Once exp(G_cum) is an exact zero in every channel the correction adds nothing; the call that
+    stops there and the call that streams every token (ZECO_APPLY_DENSE) must give the same o, and
+    both must match the oracle.  Crossing points: inside a 64-token block, on a block boundary, on a
+    workgroup boundary (1024 tokens), never (one slow channel), and before the first token."""
+    if per_head and io == "f32":
+        pytest.skip("per-head gates are a bf16 feature")
+    dk, dv, B, H, L = 128, 64, 1, 5, 2048
+    P = 2
+    print("apply vanish", io, per_head, flush=True)
+    r = np.random.default_rng(17)
+    dt = synth.torch_dtype(io)
+    q = torch.from_numpy(r.standard_normal((B, P * L, H, dk))).to(dt).cuda()
+    o0 = torch.from_numpy(r.standard_normal((B, P * L, H, dv))).to(dt).cuda()
+    S = r.standard_normal((P, B, H, dk, dv)).astype(np.float32)
+    # per head: number of tokens after which every channel is below the threshold
+    cross = [700, 1024, 1536, None, 0]
+    g = np.zeros((B, P * L, H, dk), dtype=np.float32)
+    for h, c in enumerate(cross):
+        if c is None:
+            g[:, :, h] = -0.2
+            g[:, :, h, 5] = -0.01          # one channel that never vanishes within the segment
+        elif c == 0:
+            g[:, :, h] = -200.0
+        else:
+            g[:, :, h] = -106.0 / c * (1.0 + 0.3 * r.random(dk))
+    if per_head:
+        g = np.ascontiguousarray(g[..., 0])
+    G = np.cumsum(g.reshape((B, P, L) + g.shape[2:]), axis=2).reshape(g.shape).astype(np.float32)
+    G_full = G if not per_head else np.repeat(G[..., None], dk, axis=-1)
+    outs = []
+    for dense in (False, True):
+        o = o0.clone()
+        zeco.apply_init_state(q, torch.empty(0), dev(G), dev(S), o, P, scale=1.3,
+                              first_segment_is_zero=False, dense=dense)
+        torch.cuda.synchronize()
+        outs.append(o)
+    assert torch.equal(outs[0].float() + 0.0, outs[1].float() + 0.0)   # "+ 0.0": -0 and +0 compare equal anyway
+    ref = oracle.apply_init_state(host(q), G_full.astype(np.float64), S.astype(np.float64), host(o0), 1.3)
+    assert rel_err_bh(host(outs[0]), ref, (0, 2)) <= TOL[io]
+    # where the decay has vanished o is untouched, bit for bit
+    for h, c in enumerate(cross):
+        if c is not None:
+            c64 = -(-c // 64) * 64
+            for p in range(P):
+                assert torch.equal(outs[0][:, p * L + c64:(p + 1) * L, h], o0[:, p * L + c64:(p + 1) * L, h])
+
+
 def test_strided_views_and_determinism():
     """q, k, g, v taken as views of one fused projection buffer; two runs are bitwise equal."""
     B, T, H, d, P = 1, 256, 4, 128, 2

@@ -66,17 +66,16 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + id / p.B;
-    if (p.skip_mod > 0 && seg % p.skip_mod == 0) return;
     const long long tok0 = (long long)seg * p.L + (long long)tb * p.tokens_per_wg;
     const uint16_t *qp = (const uint16_t *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
     uint16_t *op = (uint16_t *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
     const long long T = (long long)p.P * p.L;
-    float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * (GH ? 1 : DK);
+    const float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * (GH ? 1 : DK);
     const long long gcs = (long long)p.H * (GH ? 1 : DK);
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
 
-    // Nothing to add from this workgroup's first token on?  (Rebasing G_cum touches every token.)
-    const bool may_stop = !p.dense && !p.G_off;
+    // Nothing to add from this workgroup's first token on?
+    const bool may_stop = !p.dense;
     auto all_gone = [&](bool mine) {   // workgroup-wide AND; ends with a barrier
         const bool wave_all = __ballot(mine) == ~0ull;
         if (lane == 0) gone[w] = wave_all;
@@ -128,14 +127,6 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         }
     };
 
-    // Optional rebasing of the cumulative log decay: this thread always handles the same 8 channels.
-    f32x4 goff0 = {0.f, 0.f, 0.f, 0.f}, goff1 = {0.f, 0.f, 0.f, 0.f};
-    if (!GH && p.G_off) {
-        const float *go = p.G_off + (((size_t)seg * p.B + b) * p.H + h) * DK + 8 * (tid % (DK / 8));
-        goff0 = *reinterpret_cast<const f32x4 *>(go);
-        goff1 = *reinterpret_cast<const f32x4 *>(go + 4);
-    }
-
     const int nblk = p.tokens_per_wg / 64;
     Raw nxt;
     u32x4 onx[Cfg::OITEMS];
@@ -166,11 +157,6 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
                                    bf16_hi(cur.q[m][e]) * fast_exp(gb) * p.scale);
             }
             *reinterpret_cast<u32x4 *>(Qh + t * QS + 16 * cg) = out;
-            if (!GH && p.G_off) {
-                float *gw = Gc + ((long long)blk * 64 + t) * gcs + 8 * cg;
-                *reinterpret_cast<f32x4 *>(gw) = cur.g0[m] + goff0;
-                *reinterpret_cast<f32x4 *>(gw + 4) = cur.g1[m] + goff1;
-            }
         }
         const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
         load_raw(nb, nxt);

@@ -95,6 +95,10 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 //            (Alg. 1's chunk-state loop; q is not read, nothing per token is written)
 //   kOutput  the output pass from given initial states S_init[p]: o only
 //            (Alg. 1's output pass, the incoming state folded into the running state)
+//   kLocalInit  the output pass that also emits the per-token cumulative log decay, counted from the
+//            given offsets G_off[p]: o, G_cum (second pass of the local pass when a segment is cut
+//            into sub-segments; S_init[p] and G_off[p] then hold what precedes sub-segment p inside
+//            its segment)
 // and two passes of the backward (App. A.4), which walk the chunks of a segment from the last to the
 // first and keep dS, the gradient of the running state, in the accumulators:
 //   kDState  dS <- (gamma^T 1) .* dS + (Q .* Lambda)^T dO from zero; S_loc receives the gradient that
@@ -105,13 +109,13 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 // kDV: q := k, k := q, v := dO, o := dV), flip the sign of the decay exponents, apply gamma before the
 // chunk's products instead of after, and store token t of a chunk at tile row 63 - t, so that the
 // causal structure of the tiles is the one of the forward pass.
-enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4 };
+enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4, kLocalInit = 5 };
 
 // Gate waves per workgroup: 4, one per SIMD beside an MFMA wave; 8 in the local pass with per-channel
 // gates at d_k = 128, which moves the most bytes per chunk and gains 2-3 % from the second set of
 // loads in flight (the other modes lose as much).
 constexpr int gate_waves(int dk, int gm, int mode) {
-    return (dk == 128 && mode == kLocal && gm != kGateHead) ? 8 : 4;
+    return (dk == 128 && (mode == kLocal || mode == kLocalInit) && gm != kGateHead) ? 8 : 4;
 }
 constexpr int chunk_threads(int dk, int dv, int gm, int mode) { return 64 * (dv / 32 + gate_waves(dk, gm, mode)); }
 
@@ -126,7 +130,8 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     constexpr bool GH = GM == kGateHead;
     constexpr bool REV = MODE == kDState || MODE == kDV;          // chunks and tokens in reverse
     constexpr bool NOQ = MODE == kStates || MODE == kDState;      // only the state is computed
-    constexpr bool FROM_INIT = MODE == kOutput || MODE == kDV;    // start from S_init, emit no state
+    constexpr bool FROM_INIT = MODE == kOutput || MODE == kDV || MODE == kLocalInit;   // start from S_init, emit no state
+    constexpr bool EMIT_G = MODE == kLocal || MODE == kLocalInit;  // per-token cumulative log decay
     constexpr float SGN = REV ? -1.f : 1.f;                       // sign of the decay exponents
     constexpr float kLog2e = 1.4426950408889634f;
     extern __shared__ __align__(16) unsigned char lds[];
@@ -200,6 +205,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
 
         // Log decay of the previous chunks for this thread's 4 channels, as an unevaluated sum.
         f32x4 seg_hi = {0.f, 0.f, 0.f, 0.f}, seg_lo = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (MODE == kLocalInit) seg_hi = *reinterpret_cast<const f32x4 *>(p.G_off + sbh * DK + 4 * cq);
         f32x4 cs[TPT];                          // in-thread inclusive cumsum of g (part 1 -> part 2)
         f32x4 excl = {0.f, 0.f, 0.f, 0.f};      // sum over the wave's earlier token groups
 
@@ -356,7 +362,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                     kt[3].w[wd] = pair_hi(x[1], y[1]);
                 }
                 kprev = kq;
-                if constexpr (MODE == kLocal) {
+                if constexpr (EMIT_G) {
                     f32x4 gout;
 #pragma unroll
                     for (int a = 0; a < 4; ++a) gout[a] = gbase[a] + cs[u][a];
@@ -393,6 +399,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 seg_lo[a] = (seg_hi[a] - (s - bb)) + (x - bb);
                 seg_hi[a] = s;
             }
+            if constexpr (MODE == kLocalInit) return;
             if (m == N - 1 && tq == 0 && slice == 0) {   // segment total: log of gamma~_[N]
                 f32x4 gt;
 #pragma unroll
@@ -642,6 +649,10 @@ hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mo
     if (mode == kOutput) return dispatch_gate<kOutput>(p, d_k, d_v, gate_mode, s);
     if (mode == kDState) return dispatch_gate<kDState>(p, d_k, d_v, gate_mode, s);
     if (mode == kDV) return dispatch_gate<kDV>(p, d_k, d_v, gate_mode, s);
+    if (mode == kLocalInit)   // per-channel gates only (the sub-segmented local pass)
+        return gate_mode == kGateBF16 ? dispatch_b16<kGateBF16, kLocalInit>(p, d_k, d_v, s)
+               : gate_mode == kGateF32 ? dispatch_b16<kGateF32, kLocalInit>(p, d_k, d_v, s)
+                                       : hipErrorInvalidValue;
     return dispatch_gate<kLocal>(p, d_k, d_v, gate_mode, s);
 }
 

@@ -45,8 +45,8 @@ extern "C" {
 
 // Number of sub-segments each segment is split into inside zeco_gla_local_fwd (1 = none).  A stream is
 // a serial chain over chunks, so with few (batch, segment, head) streams most compute units would
-// idle; the local pass then applies the method to itself: sub-segments from the zero state, a scan of
-// their states inside each segment, and a correction that also rebases the cumulative log decay.
+// idle; the local pass then applies the method to itself: sub-segment states from the zero state, a scan
+// of them inside each segment, and the output pass of every sub-segment from its scanned state.
 static int subsegments(const zeco_gla_desc *d) {
     if (d->io_dtype != ZECO_BF16 || d->g_per_head) return 1;
     const long long streams = (long long)d->B * d->P * d->H;
@@ -108,13 +108,16 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
     if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s));
 
-    // Few streams: P*S sub-segments of L/S tokens (Sec. 3.1 applied inside each segment).
+    // Few streams: P*S sub-segments of L/S tokens, Alg. 1's schedule applied inside each segment: the
+    // sub-segments' end states and total decays from the zero state, their scan inside the segment,
+    // then the output pass of every sub-segment from its scanned state, which also writes G_cum counted
+    // from the segment's first token.
     const SubLayout w = sub_layout(d, S);
     float *ws = static_cast<float *>(workspace);
     float *Ssub = ws + w.off_Ssub, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot, *Gpre = ws + w.off_Gpre;
     p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
     p.S_loc = Ssub; p.G_tot = Gtot;
-    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s);
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::ScanParams sp;   // one chain of S sub-segments per segment; its end state is the segment's S_loc
@@ -125,17 +128,8 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     if ((e = zeco::launch_gate_prefix(Gtot, Gpre, G_tot, d->P, S, d->B * d->H * d->d_k, s)) != hipSuccess)
         return ZECO_ERR_HIP;
 
-    zeco::ApplyParams ap;  // correction of sub-segments 1..S-1 and rebasing of their G_cum
-    ap.q = q; ap.G_cum = G_cum; ap.S_init = Sinit; ap.G_off = Gpre; ap.o = o;
-    ap.B = d->B; ap.P = p.P; ap.H = d->H; ap.L = p.L;
-    ap.p0 = 0; ap.skip_mod = S;
-    int tpw = 1024;
-    while (tpw > 64 && p.L % tpw != 0) tpw >>= 1;
-    ap.tokens_per_wg = tpw;
-    ap.scale = d->scale;
-    ap.sb = d->stride_b; ap.st = d->stride_t; ap.sh = d->stride_h;
-    ap.vb = d->vstride_b; ap.vt = d->vstride_t; ap.vh = d->vstride_h;
-    return from_hip(zeco::launch_apply_bf16(ap, d->d_k, d->d_v, s));
+    p.S_loc = nullptr; p.G_tot = nullptr; p.S_init = Sinit; p.G_off = Gpre;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 5, s));
 }
 
 // ---- two-phase forward ------------------------------------------------------------------------------
@@ -423,9 +417,9 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
     if (flags & ~(ZECO_APPLY_FIRST_SEGMENT_ZERO | ZECO_APPLY_DENSE)) return ZECO_ERR_INVALID_ARG;
 
     zeco::ApplyParams p;
-    p.q = q; p.G_cum = const_cast<float *>(G_cum); p.S_init = S_init; p.G_off = nullptr; p.o = o;
+    p.q = q; p.G_cum = G_cum; p.S_init = S_init; p.o = o;
     p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
-    p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0; p.skip_mod = 0; p.gate_per_head = d->g_per_head;
+    p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0; p.gate_per_head = d->g_per_head;
     p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
     int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
     while (tpw > 64 && d->L % tpw != 0) tpw >>= 1;

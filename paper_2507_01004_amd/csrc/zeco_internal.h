@@ -13,7 +13,8 @@ struct ChunkParams {
     const void *q, *k, *v, *g;
     void *o;
     float *S_loc, *G_cum, *G_tot;
-    const float *S_init;       // [P,B,H,d_k,d_v] initial states (output-pass mode only)
+    const float *S_init;       // [P,B,H,d_k,d_v] initial states (modes that start from a given state)
+    const float *G_off = nullptr;   // [P,B,H,d_k] log decay preceding each segment (mode 5 only)
     float *S_save = nullptr;   // output pass: states entering every save_every-th chunk,
     int save_every = 0;        //   [P * n_chunks / save_every, B, H, d_k, d_v]
     int B, P, H, L;
@@ -32,15 +33,13 @@ extern unsigned long long *g_phase_dbg;
 
 struct ApplyParams {
     const void *q;
-    float *G_cum;              // read; rewritten as G_cum + G_off when G_off is given
+    const float *G_cum;
     const float *S_init;
-    const float *G_off;        // nullable [P,B,H,d_k]: log decay to add to G_cum of each segment
     void *o;
     int B, P, H, L;
     int p0;                    // first segment to correct
-    int skip_mod;              // > 0: segments with index % skip_mod == 0 are left untouched
     int tokens_per_wg;         // multiple of 64 dividing L
-    int gate_per_head = 0;     // 1: G_cum [B,T,H] (bf16 kernel only, no rebasing)
+    int gate_per_head = 0;     // 1: G_cum [B,T,H] (bf16 kernel only)
     int dense = 0;             // 1: stream every token, also where exp(G_cum) has vanished
     float scale;
     long long sb, st, sh, vb, vt, vh;
@@ -74,7 +73,8 @@ struct BwdQKParams {
 hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t s);
 // mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
 // 3 backward state pass (k := q, v := dO; S_loc := dS leaving the segment), 4 dV pass (q := k, k := q,
-// v := dO, S_init := dS entering the segment's final state, o := dV)
+// v := dO, S_init := dS entering the segment's final state, o := dV), 5 output pass from S_init that also
+// writes G_cum counted from G_off (o, G_cum; per-channel gates only)
 hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mode, int mode, hipStream_t s);
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);

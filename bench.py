@@ -141,30 +141,59 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    # The same result by the two-phase schedule (states, scan, output pass from the scanned states):
-    # reported beside the headline number, never as `value`.
-    two_phase = None
+    # The same result by the fused entry point, by either of its schedules: two-phase (states, scan,
+    # output pass from the scanned states) and local pass in chunk-decay form + scan + correction.
+    # Reported beside the headline number, never as `value`.
+    two_phase = fused_correct = chunk_decay = None
     if c["io"] == "bf16":
         ws = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
         o2 = torch.empty_like(v)
         S_last2 = torch.empty_like(S_last)
-        for _ in range(args.warmup):
-            zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws)
-        torch.cuda.synchronize()
-        fe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        fe[0].record()
-        for _ in range(args.steps):
-            zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws)
-        fe[1].record()
-        torch.cuda.synchronize()
-        fms = fe[0].elapsed_time(fe[1]) / args.steps
         io = 2
         th = B * T * H
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            fe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            fe[0].record()
+            for _ in range(args.steps):
+                fn()
+            fe[1].record()
+            torch.cuda.synchronize()
+            return fe[0].elapsed_time(fe[1]) / args.steps
+
+        fms = timed(lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws,
+                                               schedule=zeco.SCHEDULE_TWO_PHASE))
         fb = th * (dk * io + dv * io + g_in)                        # phase 1: k, v, g
         fb += th * (2 * dk * io + dv * io + g_in + dv * io)         # phase 2
-        two_phase = {"entry": "zeco_gla_fused_fwd", "ms_per_step": round(fms, 4),
+        two_phase = {"entry": "zeco_gla_fused_fwd(ZECO_SCHEDULE_TWO_PHASE)", "ms_per_step": round(fms, 4),
                      "tokens_per_s": round(B * T / (fms * 1e-3), 1), "alg_bytes": fb,
                      "GBps": round(fb / fms / 1e6, 1), "hbm_frac": round(fb / fms / 1e6 / HBM_PEAK_GBS, 4)}
+        if args.gate == "channel":
+            cms = timed(lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws,
+                                                   schedule=zeco.SCHEDULE_CORRECT))
+            fused_correct = {"entry": "zeco_gla_fused_fwd(ZECO_SCHEDULE_CORRECT)", "ms_per_step": round(cms, 4),
+                             "tokens_per_s": round(B * T / (cms * 1e-3), 1),
+                             "note": "local pass (chunk-decay form) + scan + correction that stops where the decay "
+                                     "has vanished; traffic depends on the gates"}
+            # the three calls of the headline with the cumulative decay kept per chunk (Alg. 1's gamma~ list)
+            G_chunk = torch.empty(B, T // 64, H, dk, dtype=torch.float32, device="cuda:0")
+
+            def step_cd():
+                zeco.gla_local_fwd_chunk_decay(q, k, v, g, P, out=(o2, S_loc, G_chunk, G_tot))
+                zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=(S_init, S_last2))
+                zeco.apply_init_state_chunk_decay(q, g, G_chunk, S_init, o2, P, first_segment_is_zero=True)
+            dms = timed(step_cd)
+            lms = timed(lambda: zeco.gla_local_fwd_chunk_decay(q, k, v, g, P, out=(o2, S_loc, G_chunk, G_tot)))
+            lb = th * (2 * dk * io + 2 * dv * io + g_in + dk * 4 // 64) + B * P * H * (dk * dv * 4 + dk * 4)
+            chunk_decay = {"entries": "zeco_gla_local_fwd_chunk_decay, zeco_state_scan, zeco_apply_init_state_chunk_decay",
+                           "ms_per_step": round(dms, 4), "tokens_per_s": round(B * T / (dms * 1e-3), 1),
+                           "local_ms": round(lms, 4), "local_alg_bytes": lb,
+                           "local_GBps": round(lb / lms / 1e6, 1),
+                           "local_hbm_frac": round(lb / lms / 1e6 / HBM_PEAK_GBS, 4)}
+            del G_chunk
         del ws, o2, S_last2
 
     # Backward of the same workload (App. A.4), whole call: reported beside the headline number.
@@ -198,7 +227,8 @@ def main():
         wsf = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
         o4 = torch.empty_like(v)
         pair = {}
-        for nm, fn in (("fwd_saving_ms", lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last), workspace=wsf, save=save)),
+        for nm, fn in (("fwd_saving_ms", lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last), workspace=wsf, save=save,
+                                                                    schedule=zeco.SCHEDULE_TWO_PHASE)),
                        ("bwd_from_saved_ms", lambda: zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws, saved=save))):
             fn()
             torch.cuda.synchronize()
@@ -228,7 +258,10 @@ def main():
         o2 = torch.empty_like(v)
         res = {}
         for name, fn in (("three_call", step_h),
-                         ("two_phase", lambda: zeco.gla_fused_fwd(q, k, v, gh, P, out=(o2, S_last), workspace=ws))):
+                         ("two_phase", lambda: zeco.gla_fused_fwd(q, k, v, gh, P, out=(o2, S_last), workspace=ws,
+                                                                  schedule=zeco.SCHEDULE_TWO_PHASE)),
+                         ("fused_correct", lambda: zeco.gla_fused_fwd(q, k, v, gh, P, out=(o2, S_last), workspace=ws,
+                                                                      schedule=zeco.SCHEDULE_CORRECT))):
             for _ in range(3):
                 fn()
             torch.cuda.synchronize()
@@ -348,6 +381,8 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get((args.workload, args.g_dtype)) if args.gate == "channel" else None},
         "kernels": kernels,
         "two_phase": two_phase,
+        "fused_correct": fused_correct,
+        "chunk_decay": chunk_decay,
         "backward": backward,
         "g_bf16": g_bf16,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),

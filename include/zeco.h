@@ -112,6 +112,29 @@ enum { ZECO_APPLY_FIRST_SEGMENT_ZERO = 1, ZECO_APPLY_DENSE = 2 };
 zeco_status zeco_apply_init_state(const zeco_gla_desc *desc, const void *q, const float *G_cum,
                                   const float *S_init, void *o, int32_t flags, void *stream);
 
+/* ---- The local pass and the correction with the cumulative decay kept per chunk, as Alg. 1 stores it
+ * (the list of gamma~_[n], one d_k vector per chunk) instead of per token: the local pass then writes
+ * 8 instead of 512 bytes of decay per token and head (d_k = 128), and the correction rebuilds the
+ * in-chunk factor Lambda_t (Sec. 2.1) from g for the tokens it works on.  bf16 q/k/v/o and per-channel
+ * gates only (otherwise ZECO_ERR_UNSUPPORTED).  Same conventions as above. ----------------------------- */
+
+/* Local pass: as zeco_gla_local_fwd, with
+ *   out  G_chunk [B,T/C,H,d_k] fp32 contiguous: for chunk n of a segment (n = 0 .. L/C-1), the sum of g
+ *        from the segment's first token to the last token BEFORE the chunk (log gamma~_[n], zero for the
+ *        segment's first chunk)
+ * in place of G_cum.  Uses no workspace (with few (batch, segment, head) streams it is not split further). */
+zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *desc, const void *q, const void *k,
+                                           const void *v, const void *g, void *o, float *S_loc,
+                                           float *G_chunk, float *G_tot, void *stream);
+
+/* Correction: as zeco_apply_init_state, with exp(G_cum[t]) formed as
+ *   exp(G_chunk[n] + sum of g over the tokens of chunk n up to and including t).
+ * Without ZECO_APPLY_DENSE it stops, per (batch, segment, head), at the first chunk whose G_chunk is
+ * below -105 in every channel. */
+zeco_status zeco_apply_init_state_chunk_decay(const zeco_gla_desc *desc, const void *q, const void *g,
+                                              const float *G_chunk, const float *S_init, void *o,
+                                              int32_t flags, void *stream);
+
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
  * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
  * ZECO_ERR_UNSUPPORTED).  Same conventions as above. ------------------------------------------------ */
@@ -129,21 +152,33 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *desc, const void *q, co
                                     const void *v, const void *g, const float *S_init, void *o,
                                     void *stream);
 
-/* Both phases and the scan between them in one call, for all P segments resident on this device.
- * The library may cut the segments further (more, shorter segments cost no extra traffic here and
- * keep every compute unit busy); the states of those pieces live in the workspace.
+/* The whole forward in one call, for all P segments resident on this device.  The library may cut the
+ * segments further (more, shorter segments keep every compute unit busy); the states of those pieces
+ * live in the workspace.
  *   in   S0 [B,H,d_k,d_v] fp32 or NULL: state entering the first segment
  *   out  o;  S_last [B,H,d_k,d_v] fp32 or NULL: state after the last token
  *   out  S_save: NULL, or zeco_gla_saved_states_bytes(desc) bytes of device memory that receive the
  *        forward states at the boundaries of the pieces the backward works on (a d_k x d_v state per
  *        512 tokens and head, and the end state); handing it to zeco_gla_fused_bwd spares that call the
  *        recomputation of the forward states.  Contents are private to the library.
- * workspace: zeco_gla_fused_fwd_workspace(desc) bytes of device memory, 16-byte aligned. */
+ *   schedule:
+ *     ZECO_SCHEDULE_TWO_PHASE  Alg. 1's: chunk-state pass (k, v, g), scan, output pass from the scanned
+ *                              states.  Traffic does not depend on the data.
+ *     ZECO_SCHEDULE_CORRECT    local pass from the zero state (chunk-decay form), scan, correction.  The
+ *                              correction stops where the decay factor has vanished, so with decays whose
+ *                              e-folding length is far below the piece length k, v, g are read once
+ *                              instead of twice; with decays near 1 it moves about 10 % more than
+ *                              two-phase.  Per-channel gates, no S_save.
+ *     ZECO_SCHEDULE_AUTO       CORRECT when it is available and the pieces are at least 4096 tokens long,
+ *                              else TWO_PHASE.
+ * workspace: zeco_gla_fused_fwd_workspace(desc) bytes of device memory, 16-byte aligned (enough for
+ * either schedule). */
+enum { ZECO_SCHEDULE_AUTO = 0, ZECO_SCHEDULE_TWO_PHASE = 1, ZECO_SCHEDULE_CORRECT = 2 };
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc);
 size_t zeco_gla_saved_states_bytes(const zeco_gla_desc *desc);
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *desc, const void *q, const void *k, const void *v,
                                const void *g, const float *S0, void *o, float *S_last, float *S_save,
-                               void *workspace, size_t workspace_bytes, void *stream);
+                               int32_t schedule, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- Backward pass (App. A.4): gradients of  sum_t <o_t, dO_t> + <S_T, dS_T>  for the forward above.
  * bf16 q/k/v/dO and gradients only (fp32 returns ZECO_ERR_UNSUPPORTED).  dO, dv use the layout of v;

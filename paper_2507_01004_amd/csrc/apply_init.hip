@@ -35,34 +35,117 @@ template <int DK, int DV> struct ApplyCfg {
     static constexpr int kBytes = 64 * QS + 64 * CS * 4;
 };
 
+// Workgroup id -> (stream, token block), a stream being a (segment, batch, head); returns the stream's
+// index over (segment - p0, batch, head) and sets tb.
+// Order: (group of 128 streams, token block, stream in the group).  Inside a group the early token
+// blocks of every stream come first - the ones with work left once the decay has vanished - and
+// spread evenly over the XCDs, which take workgroup ids round-robin; a stream stays on one XCD (128 is
+// a multiple of 8), and a group's S_init states (8 MiB at d = 128) stay in the L2s while its token
+// blocks are worked through.
+__device__ __forceinline__ int apply_stream_of_workgroup(const ApplyParams &p, int &tb) {
+    constexpr int kGroup = 128;
+    const int blocks_per_seg = p.L / p.tokens_per_wg, streams = (p.P - p.p0) * p.B * p.H;
+    const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
+    const int gsz = min(kGroup, streams - grp * kGroup);
+    const int j = r % gsz;
+    tb = r / gsz;
+    // position j of a row -> stream: rotated inside each aligned block of 8 by the block's index, so that
+    // the streams of one head (which share a decay speed, hence an amount of work) do not all fall on the
+    // same XCD when H is a multiple of 8
+    return grp * kGroup + (((j | 7) < gsz) ? (j & ~7) + ((j - (j >> 3)) & 7) : j);
+}
+
+// Workgroup-wide AND of `mine` through the four flags in LDS; ends with a barrier.  Calls must be
+// separated by at least one other barrier.
+__device__ __forceinline__ bool apply_all(bool mine, int *flags) {
+    const bool wave_all = __ballot(mine) == ~0ull;
+    if ((threadIdx.x & 63) == 0) flags[threadIdx.x >> 6] = wave_all;
+    __syncthreads();
+    return (flags[0] & flags[1] & flags[2] & flags[3]) != 0;
+}
+
+// S_init[p] columns [w*TILE, (w+1)*TILE) as the A operand of O^T = S^T Qh^T: lane holds column lt
+// and, for k-step ks, channels ks*KS + 8*kg .. +7.
+template <int DK, int DV>
+__device__ __forceinline__ void apply_load_state(const float *S, bf16x8 (&sf)[ApplyCfg<DK, DV>::NKS]) {
+    typedef ApplyCfg<DK, DV> Cfg;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lt = lane % Cfg::TILE, kg = lane / Cfg::TILE;
+#pragma unroll
+    for (int ks = 0; ks < Cfg::NKS; ++ks) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = S[(size_t)(ks * Cfg::KS + 8 * kg + e) * DV + w * Cfg::TILE + lt];
+        u32x4 wv = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]),
+                    pack_bf16(x[6], x[7])};
+        sf[ks] = __builtin_bit_cast(bf16x8, wv);
+    }
+}
+
+// o is read-modified-written in 16-byte pieces (8 columns of one token per item).
+template <int DV>
+__device__ __forceinline__ void apply_load_o(const uint16_t *o_blk, long long vt, u32x4 (&ro)[64 * DV / 8 / 256]) {
+#pragma unroll
+    for (int m = 0; m < 64 * DV / 8 / 256; ++m) {
+        const int item = threadIdx.x + 256 * m, t = item / (DV / 8), cg = item % (DV / 8);
+        ro[m] = *reinterpret_cast<const u32x4 *>(o_blk + t * vt + 8 * cg);
+    }
+}
+
+// One 64-token block, after a barrier has made the tile Qh (scale * q .* exp(G), bf16, token-major)
+// complete: the product on the matrix cores, through an fp32 staging tile in LDS (so that o is
+// written in coalesced 16-byte pieces), added to the old rows `ocur`.  Contains one barrier; the
+// caller's next barrier separates the reads of the staging tile from the next block's products.
+template <int DK, int DV>
+__device__ __forceinline__ void apply_block(const bf16x8 (&sf)[ApplyCfg<DK, DV>::NKS], const unsigned char *Qh,
+                                            float *Cs, uint16_t *o_blk, long long vt,
+                                            const u32x4 (&ocur)[ApplyCfg<DK, DV>::OITEMS]) {
+    typedef ApplyCfg<DK, DV> Cfg;
+    typedef Mma<Cfg::TILE> M;
+    constexpr int TILE = Cfg::TILE, KS = Cfg::KS, QS = Cfg::QS;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lt = lane % TILE, kg = lane / TILE;
+#pragma unroll
+    for (int mt = 0; mt < Cfg::NMT; ++mt) {
+        typename M::acc_t acc;
+#pragma unroll
+        for (int r = 0; r < Cfg::ACC; ++r) acc[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < Cfg::NKS; ++ks)
+            acc = M::run(sf[ks], lds_frag(Qh, (mt * TILE + lt) * QS + (ks * KS + 8 * kg) * 2), acc);
+#pragma unroll
+        for (int qd = 0; qd < Cfg::ACC / 4; ++qd)   // lane holds 4 consecutive columns of token lt
+            *reinterpret_cast<f32x4 *>(Cs + (mt * TILE + lt) * Cfg::CS + w * TILE + M::row(4 * qd, kg)) =
+                f32x4{acc[4 * qd], acc[4 * qd + 1], acc[4 * qd + 2], acc[4 * qd + 3]};
+    }
+    __syncthreads();   // staging tile complete; Qh free for the next block
+#pragma unroll
+    for (int m = 0; m < Cfg::OITEMS; ++m) {
+        const int item = tid + 256 * m, t = item / (DV / 8), cg = item % (DV / 8);
+        const f32x4 c0 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg);
+        const f32x4 c1 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg + 4);
+        const u32x4 old = ocur[m];
+        *reinterpret_cast<u32x4 *>(o_blk + t * vt + 8 * cg) =
+            u32x4{pack_bf16(bf16_lo(old[0]) + c0[0], bf16_hi(old[0]) + c0[1]),
+                  pack_bf16(bf16_lo(old[1]) + c0[2], bf16_hi(old[1]) + c0[3]),
+                  pack_bf16(bf16_lo(old[2]) + c1[0], bf16_hi(old[2]) + c1[1]),
+                  pack_bf16(bf16_lo(old[3]) + c1[2], bf16_hi(old[3]) + c1[3])};
+    }
+}
+
 // GH: the cumulative log decay is one value per (token, head), G_cum [B,T,H].
 template <int DK, int DV, bool GH>
 __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     typedef ApplyCfg<DK, DV> Cfg;
-    typedef Mma<Cfg::TILE> M;
-    constexpr int TILE = Cfg::TILE, KS = Cfg::KS, QS = Cfg::QS;
+    constexpr int QS = Cfg::QS;
     __shared__ __align__(16) unsigned char lds[Cfg::kBytes];
     __shared__ int gone[4];
     unsigned char *Qh = lds;                                      // scale * q .* exp(G_cum), bf16
     float *Cs = reinterpret_cast<float *>(lds + 64 * QS);         // correction tile, fp32
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int lt = lane % TILE, kg = lane / TILE;
-
-    // Workgroup id -> (group of 128 streams, token block, stream in the group), a stream being a
-    // (segment, batch, head).  Inside a group the early token blocks of every stream come first - the
-    // ones with work left once the decay has vanished - and spread evenly over the XCDs, which take
-    // workgroup ids round-robin; a stream stays on one XCD (128 is a multiple of 8), and a group's
-    // S_init states (8 MiB at d = 128) stay in the L2s while its token blocks are worked through.
-    constexpr int kGroup = 128;
-    const int blocks_per_seg = p.L / p.tokens_per_wg, streams = (p.P - p.p0) * p.B * p.H;
-    const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
-    const int gsz = min(kGroup, streams - grp * kGroup);
-    const int tb = r / gsz, j = r % gsz;
-    // position j of a row -> stream: rotated inside each aligned block of 8 by the block's index, so that
-    // the streams of one head (which share a decay speed, hence an amount of work) do not all fall on the
-    // same XCD when H is a multiple of 8
-    int id = grp * kGroup + (((j | 7) < gsz) ? (j & ~7) + ((j - (j >> 3)) & 7) : j);
+    const int tid = threadIdx.x;
+    int tb;
+    int id = apply_stream_of_workgroup(p, tb);
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + id / p.B;
@@ -76,26 +159,10 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
 
     // Nothing to add from this workgroup's first token on?
     const bool may_stop = !p.dense;
-    auto all_gone = [&](bool mine) {   // workgroup-wide AND; ends with a barrier
-        const bool wave_all = __ballot(mine) == ~0ull;
-        if (lane == 0) gone[w] = wave_all;
-        __syncthreads();
-        return (gone[0] & gone[1] & gone[2] & gone[3]) != 0;
-    };
-    if (may_stop && all_gone(Gc[GH ? 0 : tid % DK] < kVanish)) return;
+    if (may_stop && apply_all(Gc[GH ? 0 : tid % DK] < kVanish, gone)) return;
 
-    // S_init[p] columns [w*TILE, (w+1)*TILE) as the A operand of O^T = S^T Qh^T: lane holds column
-    // lt and, for k-step ks, channels ks*KS + 8*kg .. +7.
     bf16x8 sf[Cfg::NKS];
-#pragma unroll
-    for (int ks = 0; ks < Cfg::NKS; ++ks) {
-        float x[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = S[(size_t)(ks * KS + 8 * kg + e) * DV + w * TILE + lt];
-        u32x4 wv = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3]), pack_bf16(x[4], x[5]),
-                    pack_bf16(x[6], x[7])};
-        sf[ks] = __builtin_bit_cast(bf16x8, wv);
-    }
+    apply_load_state<DK, DV>(S, sf);
 
     struct Raw {
         u32x4 q[Cfg::ITEMS];
@@ -117,21 +184,11 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         }
     };
 
-    // o is read-modified-written in 16-byte pieces (8 columns of one token per item); the MFMA
-    // result reaches that layout through an fp32 staging tile in LDS.
-    auto load_o = [&](int blk, u32x4 (&ro)[Cfg::OITEMS]) {
-#pragma unroll
-        for (int m = 0; m < Cfg::OITEMS; ++m) {
-            const int item = tid + 256 * m, t = item / (DV / 8), cg = item % (DV / 8);
-            ro[m] = *reinterpret_cast<const u32x4 *>(op + ((long long)blk * 64 + t) * p.vt + 8 * cg);
-        }
-    };
-
     const int nblk = p.tokens_per_wg / 64;
     Raw nxt;
     u32x4 onx[Cfg::OITEMS];
     load_raw(0, nxt);
-    load_o(0, onx);
+    apply_load_o<DV>(op, p.vt, onx);
     for (int blk = 0; blk < nblk; ++blk) {
         const Raw cur = nxt;
         u32x4 ocur[Cfg::OITEMS];
@@ -143,7 +200,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) mine = mine && cur.g0[0][e] < kVanish && cur.g1[0][e] < kVanish;
             }
-            if (all_gone(mine)) break;
+            if (apply_all(mine, gone)) break;
         }
 #pragma unroll
         for (int m = 0; m < Cfg::ITEMS; ++m) {
@@ -160,36 +217,105 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         }
         const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
         load_raw(nb, nxt);
-        load_o(nb, onx);
+        apply_load_o<DV>(op + (long long)nb * 64 * p.vt, p.vt, onx);
         __syncthreads();   // Qh complete; every thread is done with the staging tile of the last block
+        apply_block<DK, DV>(sf, Qh, Cs, op + (long long)blk * 64 * p.vt, p.vt, ocur);
+    }
+}
 
-#pragma unroll
-        for (int mt = 0; mt < Cfg::NMT; ++mt) {
-            typename M::acc_t acc;
-#pragma unroll
-            for (int r = 0; r < Cfg::ACC; ++r) acc[r] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < Cfg::NKS; ++ks)
-                acc = M::run(sf[ks], lds_frag(Qh, (mt * TILE + lt) * QS + (ks * KS + 8 * kg) * 2), acc);
-#pragma unroll
-            for (int qd = 0; qd < Cfg::ACC / 4; ++qd)   // lane holds 4 consecutive columns of token lt
-                *reinterpret_cast<f32x4 *>(Cs + (mt * TILE + lt) * Cfg::CS + w * TILE + M::row(4 * qd, kg)) =
-                    f32x4{acc[4 * qd], acc[4 * qd + 1], acc[4 * qd + 2], acc[4 * qd + 3]};
-        }
-        __syncthreads();   // staging tile complete; Qh free for the next block
+// The same correction from the per-chunk cumulative decay (Alg. 1's list of gamma~_[n]) and the log
+// decays themselves:  exp(G_t) with  G_t = G_chunk[n] + sum of g over the chunk's tokens up to t,
+// the in-chunk factor Lambda_t of Sec. 2.1 times gamma~_[n-1].  A thread owns 4 channels and TPT
+// consecutive tokens of the 64-token block: cumulative sum in registers, the token groups stitched
+// through LDS.  Stops where G_chunk[n] < kVanish in every channel (see "Vanished decay").
+template <int DK, int DV, int GM>
+__global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) {
+    typedef ApplyCfg<DK, DV> Cfg;
+    typedef GateVal<GM> GV;
+    constexpr int QS = Cfg::QS;
+    constexpr int CQ = DK / 4, NG = 256 / CQ, TPT = 64 / NG;   // channel quads, token groups, tokens per thread
+    constexpr int GB = GM == kGateBF16 ? 2 : 4;
+    __shared__ __align__(16) unsigned char lds[Cfg::kBytes];
+    __shared__ __align__(16) float tot[NG * DK];
+    __shared__ int gone[4];
+    unsigned char *Qh = lds;
+    float *Cs = reinterpret_cast<float *>(lds + 64 * QS);
 
+    const int tid = threadIdx.x, cq = tid % CQ, tg = tid / CQ;
+    int tb;
+    int id = apply_stream_of_workgroup(p, tb);
+    const int h = id % p.H;
+    id /= p.H;
+    const int b = id % p.B, seg = p.p0 + id / p.B;
+    const long long tok0 = (long long)seg * p.L + (long long)tb * p.tokens_per_wg;
+    const long long kb = b * p.sb + tok0 * p.st + h * p.sh;
+    const uint16_t *qp = (const uint16_t *)p.q + kb + (long long)(tg * TPT) * p.st + 4 * cq;
+    const unsigned char *gp = (const unsigned char *)p.g + (kb + (long long)(tg * TPT) * p.st + 4 * cq) * GB;
+    uint16_t *op = (uint16_t *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
+    const long long NC = (long long)p.P * p.L / 64;             // chunks per batch entry
+    const float *Gk = p.G_chunk + ((b * NC + tok0 / 64) * p.H + h) * DK + 4 * cq;
+    const long long gks = (long long)p.H * DK;                  // floats between chunks
+    const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
+
+    auto vanished = [](const f32x4 &x) { return x[0] < kVanish && x[1] < kVanish && x[2] < kVanish && x[3] < kVanish; };
+    const bool may_stop = !p.dense;
+    f32x4 pre_n = *reinterpret_cast<const f32x4 *>(Gk);
+    if (may_stop && apply_all(vanished(pre_n), gone)) return;
+
+    bf16x8 sf[Cfg::NKS];
+    apply_load_state<DK, DV>(S, sf);
+
+    u32x2 qn[TPT];
+    typename GV::raw_t gn[TPT];
+    u32x4 onx[Cfg::OITEMS];
+    auto load_raw = [&](int blk) {
 #pragma unroll
-        for (int m = 0; m < Cfg::OITEMS; ++m) {
-            const int item = tid + 256 * m, t = item / (DV / 8), cg = item % (DV / 8);
-            const f32x4 c0 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg);
-            const f32x4 c1 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg + 4);
-            const u32x4 old = ocur[m];
-            *reinterpret_cast<u32x4 *>(op + ((long long)blk * 64 + t) * p.vt + 8 * cg) =
-                u32x4{pack_bf16(bf16_lo(old[0]) + c0[0], bf16_hi(old[0]) + c0[1]),
-                      pack_bf16(bf16_lo(old[1]) + c0[2], bf16_hi(old[1]) + c0[3]),
-                      pack_bf16(bf16_lo(old[2]) + c1[0], bf16_hi(old[2]) + c1[1]),
-                      pack_bf16(bf16_lo(old[3]) + c1[2], bf16_hi(old[3]) + c1[3])};
+        for (int u = 0; u < TPT; ++u) {
+            qn[u] = *reinterpret_cast<const u32x2 *>(qp + ((long long)blk * 64 + u) * p.st);
+            gn[u] = *reinterpret_cast<const typename GV::raw_t *>(gp + ((long long)blk * 64 + u) * p.st * GB);
         }
+    };
+    const int nblk = p.tokens_per_wg / 64;
+    load_raw(0);
+    apply_load_o<DV>(op, p.vt, onx);
+    for (int blk = 0; blk < nblk; ++blk) {
+        const f32x4 pre = pre_n;
+        u32x2 qc[TPT];
+        f32x4 cs[TPT];
+        u32x4 ocur[Cfg::OITEMS];
+#pragma unroll
+        for (int m = 0; m < Cfg::OITEMS; ++m) ocur[m] = onx[m];
+        if (may_stop && blk > 0 && apply_all(vanished(pre), gone)) break;
+        f32x4 run = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < TPT; ++u) {
+            qc[u] = qn[u];
+            run += GV::get(gn[u]);
+            cs[u] = run;
+        }
+        *reinterpret_cast<f32x4 *>(tot + tg * DK + 4 * cq) = run;
+        const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
+        load_raw(nb);
+        apply_load_o<DV>(op + (long long)nb * 64 * p.vt, p.vt, onx);
+        pre_n = *reinterpret_cast<const f32x4 *>(Gk + (long long)nb * gks);
+        __syncthreads();   // group sums visible; every thread is done with the staging tile of the last block
+        f32x4 base = pre;
+#pragma unroll
+        for (int r = 0; r < NG; ++r) {
+            const f32x4 x = *reinterpret_cast<const f32x4 *>(tot + r * DK + 4 * cq);
+            const float sel = r < tg ? 1.f : 0.f;
+#pragma unroll
+            for (int a = 0; a < 4; ++a) base[a] = __builtin_fmaf(sel, x[a], base[a]);
+        }
+#pragma unroll
+        for (int u = 0; u < TPT; ++u) {
+            const f32x4 G = base + cs[u];
+            *reinterpret_cast<u32x2 *>(Qh + (tg * TPT + u) * QS + 8 * cq) =
+                u32x2{pack_bf16(bf16_lo(qc[u][0]) * fast_exp(G[0]) * p.scale, bf16_hi(qc[u][0]) * fast_exp(G[1]) * p.scale),
+                      pack_bf16(bf16_lo(qc[u][1]) * fast_exp(G[2]) * p.scale, bf16_hi(qc[u][1]) * fast_exp(G[3]) * p.scale)};
+        }
+        __syncthreads();   // Qh complete
+        apply_block<DK, DV>(sf, Qh, Cs, op + (long long)blk * 64 * p.vt, p.vt, ocur);
     }
 }
 
@@ -266,6 +392,14 @@ template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hi
         hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, false>), dim3(grid), dim3(256), 0, s, p);
     return hipGetLastError();
 }
+template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hipStream_t s) {
+    const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
+    if (p.g_bf16)
+        hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateBF16>), dim3(grid), dim3(256), 0, s, p);
+    else
+        hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateF32>), dim3(grid), dim3(256), 0, s, p);
+    return hipGetLastError();
+}
 template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hipStream_t s) {
     const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
     hipLaunchKernelGGL((apply_init_f32_kernel<DK, DV>), dim3(grid), dim3(DV * 4), 0, s, p);
@@ -278,6 +412,14 @@ hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t
     if (d_k == 64 && d_v == 128) return launch_ab16<64, 128>(p, s);
     if (d_k == 128 && d_v == 64) return launch_ab16<128, 64>(p, s);
     if (d_k == 128 && d_v == 128) return launch_ab16<128, 128>(p, s);
+    return hipErrorInvalidValue;
+}
+hipError_t launch_apply_cd_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s) {
+    if (p.P - p.p0 <= 0) return hipSuccess;
+    if (d_k == 64 && d_v == 64) return launch_acd<64, 64>(p, s);
+    if (d_k == 64 && d_v == 128) return launch_acd<64, 128>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_acd<128, 64>(p, s);
+    if (d_k == 128 && d_v == 128) return launch_acd<128, 128>(p, s);
     return hipErrorInvalidValue;
 }
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s) {

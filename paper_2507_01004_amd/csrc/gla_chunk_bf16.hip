@@ -95,6 +95,9 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 //            (Alg. 1's chunk-state loop; q is not read, nothing per token is written)
 //   kOutput  the output pass from given initial states S_init[p]: o only
 //            (Alg. 1's output pass, the incoming state folded into the running state)
+//   kLocalCD the local pass with the cumulative decay kept per chunk, as Alg. 1 stores it (the list of
+//            gamma~_[n]): o, S_loc, G_tot and G_chunk[n] = log gamma~_[n-1], the log decay from the segment's
+//            first token up to the start of chunk n; no per-token G_cum is written
 //   kLocalInit  the output pass that also emits the per-token cumulative log decay, counted from the
 //            given offsets G_off[p]: o, G_cum (second pass of the local pass when a segment is cut
 //            into sub-segments; S_init[p] and G_off[p] then hold what precedes sub-segment p inside
@@ -109,7 +112,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 // kDV: q := k, k := q, v := dO, o := dV), flip the sign of the decay exponents, apply gamma before the
 // chunk's products instead of after, and store token t of a chunk at tile row 63 - t, so that the
 // causal structure of the tiles is the one of the forward pass.
-enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4, kLocalInit = 5 };
+enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4, kLocalInit = 5, kLocalCD = 6 };
 
 // Gate waves per workgroup: 4, one per SIMD beside an MFMA wave; 8 in the local pass with per-channel
 // gates at d_k = 128, which moves the most bytes per chunk and gains 2-3 % from the second set of
@@ -391,6 +394,14 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             if constexpr (MODE == kDState) {
                 if (!p.G_tot) return;
             }
+            if constexpr (MODE == kLocalCD) {   // log gamma~ before this chunk
+                if (tq == 0 && slice == 0) {
+                    f32x4 gp;
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) gp[a] = seg_hi[a] + seg_lo[a];
+                    *reinterpret_cast<f32x4 *>(p.G_chunk + ((((long long)b * p.P + seg) * N + m) * p.H + h) * DK + 4 * cq) = gp;
+                }
+            }
 #pragma unroll
             for (int a = 0; a < 4; ++a) {   // (hi, lo) += total, error-free transformation
                 const float x = total[a] + seg_lo[a];
@@ -652,6 +663,10 @@ hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mo
     if (mode == kLocalInit)   // per-channel gates only (the sub-segmented local pass)
         return gate_mode == kGateBF16 ? dispatch_b16<kGateBF16, kLocalInit>(p, d_k, d_v, s)
                : gate_mode == kGateF32 ? dispatch_b16<kGateF32, kLocalInit>(p, d_k, d_v, s)
+                                       : hipErrorInvalidValue;
+    if (mode == kLocalCD)     // per-channel gates only
+        return gate_mode == kGateBF16 ? dispatch_b16<kGateBF16, kLocalCD>(p, d_k, d_v, s)
+               : gate_mode == kGateF32 ? dispatch_b16<kGateF32, kLocalCD>(p, d_k, d_v, s)
                                        : hipErrorInvalidValue;
     return dispatch_gate<kLocal>(p, d_k, d_v, gate_mode, s);
 }

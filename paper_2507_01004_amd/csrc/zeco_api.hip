@@ -146,6 +146,18 @@ static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
 #endif
 }
 
+// Correction over P segments of L tokens each (the caller's, or the pieces of a fused call).
+static void fill_apply_params(zeco::ApplyParams &p, const zeco_gla_desc *d, int P, int L) {
+    p.B = d->B; p.P = P; p.H = d->H; p.L = L;
+    p.p0 = 0; p.gate_per_head = d->g_per_head; p.dense = 0;
+    int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
+    while (tpw > 64 && L % tpw != 0) tpw >>= 1;
+    p.tokens_per_wg = tpw;
+    p.scale = d->scale;
+    p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
+    p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
+}
+
 zeco_status zeco_gla_local_state(const zeco_gla_desc *d, const void *k, const void *v, const void *g,
                                  float *S_loc, float *G_tot, void *stream) {
     const zeco_status st = check_desc(d);
@@ -190,12 +202,13 @@ static int bwd_pieces(const zeco_gla_desc *d);
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
     if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     const size_t n = (size_t)desc->P * fused_pieces(desc) * desc->B * desc->H;
-    return (2 * n * desc->d_k * desc->d_v + n * desc->d_k) * sizeof(float);
+    const size_t chunks = (size_t)desc->B * desc->P * (desc->L / desc->C) * desc->H;   // G_chunk of the CORRECT schedule
+    return (2 * n * desc->d_k * desc->d_v + n * desc->d_k + chunks * desc->d_k) * sizeof(float);
 }
 
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
                                const void *g, const float *S0, void *o, float *S_last, float *S_save,
-                               void *workspace, size_t workspace_bytes, void *stream) {
+                               int32_t schedule, void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d);
     if (st != ZECO_OK) return st;
     if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
@@ -203,15 +216,37 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
         !aligned16(S0) || !aligned16(S_last) || !aligned16(S_save) || !aligned16(workspace))
         return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    if (schedule != ZECO_SCHEDULE_AUTO && schedule != ZECO_SCHEDULE_TWO_PHASE && schedule != ZECO_SCHEDULE_CORRECT)
+        return ZECO_ERR_INVALID_ARG;
+    const bool can_correct = !d->g_per_head && !S_save;
+    if (schedule == ZECO_SCHEDULE_CORRECT && !can_correct) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_gla_fused_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int S = fused_pieces(d);
     const size_t n = (size_t)d->P * S * d->B * d->H, states = n * d->d_k * d->d_v;
     float *Sloc = static_cast<float *>(workspace), *Sinit = Sloc + states, *Gtot = Sinit + states;
+    float *Gchunk = Gtot + n * d->d_k;
 
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
+
+    if (schedule == ZECO_SCHEDULE_CORRECT || (schedule == ZECO_SCHEDULE_AUTO && can_correct && p.L >= 4096)) {
+        // local pass of every piece from the zero state, scan, correction of the pieces' heads
+        p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_loc = Sloc; p.G_tot = Gtot; p.G_chunk = Gchunk;
+        hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 6, s);
+        if (e != hipSuccess) return ZECO_ERR_HIP;
+        zeco::ScanParams sp;
+        sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
+        sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+        sp.rows_per_block = d->d_k / 16;
+        if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+        zeco::ApplyParams ap;
+        fill_apply_params(ap, d, p.P, p.L);
+        ap.q = q; ap.g = g; ap.g_bf16 = d->g_dtype == ZECO_BF16; ap.G_chunk = Gchunk; ap.S_init = Sinit; ap.o = o;
+        ap.p0 = S0 ? 0 : 1;
+        return from_hip(zeco::launch_apply_cd_bf16(ap, d->d_k, d->d_v, s));
+    }
     p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
     hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
@@ -417,19 +452,49 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
     if (flags & ~(ZECO_APPLY_FIRST_SEGMENT_ZERO | ZECO_APPLY_DENSE)) return ZECO_ERR_INVALID_ARG;
 
     zeco::ApplyParams p;
+    fill_apply_params(p, d, d->P, d->L);
     p.q = q; p.G_cum = G_cum; p.S_init = S_init; p.o = o;
-    p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
-    p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0; p.gate_per_head = d->g_per_head;
+    p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0;
     p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
-    int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
-    while (tpw > 64 && d->L % tpw != 0) tpw >>= 1;
-    p.tokens_per_wg = tpw;
-    p.scale = d->scale;
-    p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
-    p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_apply_f32(p, d->d_k, d->d_v, s));
     return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, s));
+}
+
+// ---- chunk-decay form of the local pass and the correction ---------------------------------------------
+zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q, const void *k,
+                                           const void *v, const void *g, void *o, float *S_loc,
+                                           float *G_chunk, float *G_tot, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !k || !v || !g || !o || !S_loc || !G_chunk || !G_tot) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
+        !aligned16(S_loc) || !aligned16(G_chunk) || !aligned16(G_tot))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16 || d->g_per_head) return ZECO_ERR_UNSUPPORTED;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_loc = S_loc; p.G_tot = G_tot; p.G_chunk = G_chunk;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 6,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+zeco_status zeco_apply_init_state_chunk_decay(const zeco_gla_desc *d, const void *q, const void *g,
+                                              const float *G_chunk, const float *S_init, void *o,
+                                              int32_t flags, void *stream) {
+    const zeco_status st = check_desc(d);
+    if (st != ZECO_OK) return st;
+    if (!q || !g || !G_chunk || !S_init || !o) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(g) || !aligned16(G_chunk) || !aligned16(S_init) || !aligned16(o))
+        return ZECO_ERR_INVALID_ARG;
+    if (flags & ~(ZECO_APPLY_FIRST_SEGMENT_ZERO | ZECO_APPLY_DENSE)) return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16 || d->g_per_head) return ZECO_ERR_UNSUPPORTED;
+    zeco::ApplyParams p;
+    fill_apply_params(p, d, d->P, d->L);
+    p.q = q; p.g = g; p.g_bf16 = d->g_dtype == ZECO_BF16; p.G_chunk = G_chunk; p.S_init = S_init; p.o = o;
+    p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0;
+    p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
+    return from_hip(zeco::launch_apply_cd_bf16(p, d->d_k, d->d_v, static_cast<hipStream_t>(stream)));
 }
 
 zeco_status zeco_hbm_copy(void *dst, const void *src, size_t bytes, void *stream) {

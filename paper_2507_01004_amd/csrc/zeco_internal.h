@@ -15,6 +15,7 @@ struct ChunkParams {
     float *S_loc, *G_cum, *G_tot;
     const float *S_init;       // [P,B,H,d_k,d_v] initial states (modes that start from a given state)
     const float *G_off = nullptr;   // [P,B,H,d_k] log decay preceding each segment (mode 5 only)
+    float *G_chunk = nullptr;       // [B,T/64,H,d_k] log decay from the segment start to each chunk's start (mode 6 only)
     float *S_save = nullptr;   // output pass: states entering every save_every-th chunk,
     int save_every = 0;        //   [P * n_chunks / save_every, B, H, d_k, d_v]
     int B, P, H, L;
@@ -33,7 +34,10 @@ extern unsigned long long *g_phase_dbg;
 
 struct ApplyParams {
     const void *q;
-    const float *G_cum;
+    const float *G_cum = nullptr;    // [B,T,H,d_k] per-token cumulative log decay, or
+    const float *G_chunk = nullptr;  // [B,T/64,H,d_k] per-chunk one, together with
+    const void *g = nullptr;         //   the log decays themselves (layout of q)
+    int g_bf16 = 0;                  //   stored as bf16 (1) or fp32 (0)
     const float *S_init;
     void *o;
     int B, P, H, L;
@@ -74,10 +78,13 @@ hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t 
 // mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
 // 3 backward state pass (k := q, v := dO; S_loc := dS leaving the segment), 4 dV pass (q := k, k := q,
 // v := dO, S_init := dS entering the segment's final state, o := dV), 5 output pass from S_init that also
-// writes G_cum counted from G_off (o, G_cum; per-channel gates only)
+// writes G_cum counted from G_off (o, G_cum; per-channel gates only), 6 local pass with the cumulative decay
+// per chunk instead of per token (o, S_loc, G_chunk, G_tot; per-channel gates only)
 hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mode, int mode, hipStream_t s);
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
+// from (g, G_chunk) instead of G_cum; per-channel gates
+hipError_t launch_apply_cd_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_scan(const ScanParams &p, hipStream_t s);
 // Per group of P segments: G_pre[g*P+p] = sum of G_tot[g*P+r] over r < p, G_sum[g] = sum over all r.
 hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, int groups, int P,

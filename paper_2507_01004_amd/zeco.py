@@ -16,8 +16,10 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
 ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
 ZECO_F32, ZECO_BF16 = 0, 1
 APPLY_FIRST_SEGMENT_ZERO, APPLY_DENSE = 1, 2
+SCHEDULE_AUTO, SCHEDULE_TWO_PHASE, SCHEDULE_CORRECT = 0, 1, 2
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
-           "zeco_apply_init_state", "zeco_gla_local_state", "zeco_gla_fwd_from_state",
+           "zeco_apply_init_state", "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
+           "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
            "zeco_gla_bwd_from_state", "zeco_gla_fused_bwd_workspace", "zeco_gla_fused_bwd",
            "zeco_hbm_copy", "zeco_status_string", "zeco_version")
@@ -61,6 +63,10 @@ def lib():
         L.zeco_state_scan.restype = i32
         L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state.restype = i32
+        L.zeco_gla_local_fwd_chunk_decay.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp]
+        L.zeco_gla_local_fwd_chunk_decay.restype = i32
+        L.zeco_apply_init_state_chunk_decay.argtypes = [dp, vp, vp, fp, fp, vp, i32, vp]
+        L.zeco_apply_init_state_chunk_decay.restype = i32
         L.zeco_gla_local_state.argtypes = [dp, vp, vp, vp, fp, fp, vp]
         L.zeco_gla_local_state.restype = i32
         L.zeco_gla_fwd_from_state.argtypes = [dp, vp, vp, vp, vp, fp, vp, vp]
@@ -69,7 +75,7 @@ def lib():
         L.zeco_gla_fused_fwd_workspace.restype = ctypes.c_size_t
         L.zeco_gla_saved_states_bytes.argtypes = [dp]
         L.zeco_gla_saved_states_bytes.restype = ctypes.c_size_t
-        L.zeco_gla_fused_fwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, fp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_fused_fwd.argtypes = [dp, vp, vp, vp, vp, fp, vp, fp, fp, i32, vp, ctypes.c_size_t, vp]
         L.zeco_gla_fused_fwd.restype = i32
         L.zeco_gla_bwd_dstate.argtypes = [dp, vp, vp, vp, fp, vp]
         L.zeco_gla_bwd_dstate.restype = i32
@@ -217,10 +223,51 @@ def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segm
         raise RuntimeError("zeco kernels run on the GPU only")
     desc = _desc(q, o, _dtype_code(g_like), G_cum.dim() == 3, P, C, scale)
     st = lib().zeco_apply_init_state(ctypes.byref(desc), _ptr(q), _ptr(G_cum), _ptr(S_init), _ptr(o),
-                                     (APPLY_FIRST_SEGMENT_ZERO if first_segment_is_zero else 0)
-                                     | (APPLY_DENSE if dense else 0), _stream())
+                                     _apply_flags(first_segment_is_zero, dense), _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_apply_init_state")
+    return o
+
+
+def _apply_flags(first_segment_is_zero, dense):
+    return (APPLY_FIRST_SEGMENT_ZERO if first_segment_is_zero else 0) | (APPLY_DENSE if dense else 0)
+
+
+def gla_local_fwd_chunk_decay(q, k, v, g, P, scale=1.0, C=64, out=None):
+    """zeco_gla_local_fwd_chunk_decay: the local pass with the cumulative log decay kept per chunk.
+    Returns (o, S_loc, G_chunk [B,T/C,H,d_k], G_tot)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    desc = make_desc(q, v, g, P, C, scale)
+    if out is None:
+        o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
+        S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=q.device)
+        G_chunk = torch.empty(B, T // C, H, dk, dtype=torch.float32, device=q.device)
+        G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device=q.device)
+    else:
+        o, S_loc, G_chunk, G_tot = out
+        _check_same_layout(v, o)
+    st = lib().zeco_gla_local_fwd_chunk_decay(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(o),
+                                              _ptr(S_loc), _ptr(G_chunk), _ptr(G_tot), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_local_fwd_chunk_decay")
+    return o, S_loc, G_chunk, G_tot
+
+
+def apply_init_state_chunk_decay(q, g, G_chunk, S_init, o, P, scale=1.0, C=64, first_segment_is_zero=True,
+                                 dense=False):
+    """zeco_apply_init_state_chunk_decay: the correction from g and the per-chunk cumulative log decay."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    desc = make_desc(q, o, g, P, C, scale)
+    st = lib().zeco_apply_init_state_chunk_decay(ctypes.byref(desc), _ptr(q), _ptr(g), _ptr(G_chunk),
+                                                 _ptr(S_init), _ptr(o),
+                                                 _apply_flags(first_segment_is_zero, dense), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_apply_init_state_chunk_decay")
     return o
 
 
@@ -266,9 +313,10 @@ def saved_states_bytes(q, v, g, P, C=64):
 
 
 def gla_fused_fwd(q, k, v, g, P, scale=1.0, S0=None, C=64, out=None, workspace=None, want_last=True,
-                  save=None):
-    """zeco_gla_fused_fwd: both phases and the scan in one call.  Returns (o, S_last).  `save`: a uint8
-    tensor of saved_states_bytes() that receives the forward states for gla_fused_bwd(saved=...)."""
+                  save=None, schedule=SCHEDULE_AUTO):
+    """zeco_gla_fused_fwd: the whole forward in one call.  Returns (o, S_last).  `save`: a uint8
+    tensor of saved_states_bytes() that receives the forward states for gla_fused_bwd(saved=...).
+    schedule: SCHEDULE_AUTO, SCHEDULE_TWO_PHASE or SCHEDULE_CORRECT."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
@@ -287,7 +335,8 @@ def gla_fused_fwd(q, k, v, g, P, scale=1.0, S0=None, C=64, out=None, workspace=N
     if save is not None and save.numel() < L.zeco_gla_saved_states_bytes(ctypes.byref(desc)):
         raise ValueError("`save` is smaller than saved_states_bytes()")
     st = L.zeco_gla_fused_fwd(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(S0), _ptr(o),
-                              _ptr(S_last), _ptr(save), _ptr(workspace), workspace.numel(), _stream())
+                              _ptr(S_last), _ptr(save), int(schedule), _ptr(workspace), workspace.numel(),
+                              _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_gla_fused_fwd")
     return o, S_last

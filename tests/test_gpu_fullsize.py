@@ -42,16 +42,22 @@ def test_fullsize_sampled_slices(name, samples):
     P, L, H = c["P"], c["L"], c["H"]
     print("full-size", name, c, flush=True)
     o, S_last, parts = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
-    o_fused, S_last_fused = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
+    o_fused, S_last_fused = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P,
+                                               schedule=zeco.SCHEDULE_TWO_PHASE)
+    o_corr, S_last_corr = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P,
+                                             schedule=zeco.SCHEDULE_CORRECT)
     torch.cuda.synchronize()
-    # both schedules end in the same state (up to bf16-operand rounding of the two routes)
+    # all schedules end in the same state (up to bf16-operand rounding of the routes)
     assert rel_err_bh(host(S_last_fused), host(S_last), (0, 1)) <= TOL[c["io"]]
+    assert rel_err_bh(host(S_last_corr), host(S_last), (0, 1)) <= TOL[c["io"]]
     for (p, h) in samples:
         print("  sample segment %d head %d" % (p, h), flush=True)
         o_ref, S_in = slice_oracle(inp, L, p, h, W[name])
         got = host(o[:1, p * L:(p + 1) * L, h:h + 1])
         assert rel_err_bh(got, o_ref, (0, 2)) <= TOL[c["io"]]
         assert rel_err_bh(host(o_fused[:1, p * L:(p + 1) * L, h:h + 1]), o_ref, (0, 2)) <= TOL[c["io"]]
+        assert rel_err_bh(host(o_corr[:1, p * L:(p + 1) * L, h:h + 1]), o_ref, (0, 2)) <= TOL[c["io"]]
+        assert rel_err_bh(host(o_corr[:1, p * L:p * L + 256, h:h + 1]), o_ref[:, :256], (0, 2)) <= TOL[c["io"]]
         # the head of the segment is where the incoming state matters most
         assert rel_err_bh(got[:, :256], o_ref[:, :256], (0, 2)) <= TOL[c["io"]]
         if S_in is not None:

@@ -247,11 +247,93 @@ def test_two_phase_forward_matches_oracle(case):
         o2 = zeco.gla_fwd_from_state(q, k, v, g, dev(Si_r.reshape(P, B, H, dk, dv)), P, scale=0.5)
         torch.cuda.synchronize()
         assert rel_err_bh(host(o2), o_r, (0, 2)) <= tol
-        # everything in one call
-        o3, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=s0)
+        # everything in one call, by either schedule
+        for sched in (zeco.SCHEDULE_TWO_PHASE, zeco.SCHEDULE_CORRECT, zeco.SCHEDULE_AUTO):
+            o3, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=s0, schedule=sched)
+            torch.cuda.synchronize()
+            assert rel_err_bh(host(o3), o_r, (0, 2)) <= tol
+            assert rel_err_bh(host(S_last), Sf_r, (0, 1)) <= tol
+
+
+@pytest.mark.parametrize("case", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_chunk_decay_form_matches_oracle(case):
+    """The local pass that keeps the cumulative decay per chunk (Alg. 1's gamma~_[n] list) and the
+    correction that rebuilds the in-chunk factor from g: each against the oracle, then chained."""
+    name, B, H, P, L, dk, dv, io, gd = case
+    print("case", case, flush=True)
+    inp = make(case, gate_div=64.0)
+    q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
+    tol = TOL[io]
+    o, S_loc, G_chunk, G_tot = zeco.gla_local_fwd_chunk_decay(q, k, v, g, P, scale=0.5)
+    torch.cuda.synchronize()
+    o_r, S_r, Gc_r, Gt_r = oracle_local(inp, P, scale=0.5)
+    assert rel_err_bh(host(o), o_r, (0, 2)) <= tol
+    assert rel_err_bh(host(S_loc), S_r, (0, 1, 2)) <= tol
+    assert log_err(host(G_tot), Gt_r) <= 1e-5
+    # G_chunk[n] = cumulative log decay at the last token before chunk n, zero at a segment's first chunk
+    N = L // 64
+    Gk_r = np.zeros((B, P, N, H, dk))
+    Gk_r[:, :, 1:] = Gc_r.reshape(B, P, N, 64, H, dk)[:, :, :-1, 63]
+    assert log_err(host(G_chunk), Gk_r.reshape(B, P * N, H, dk)) <= 1e-5
+    # correction from the oracle's scanned states and the oracle's chunk decays, on the oracle's local output
+    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    o_full, _ = oracle_full(inp, scale=0.5, S0=host(S0))
+    Si_r, _ = oracle.state_scan(S_r.reshape(P, B * H, dk, dv), Gt_r.reshape(P, B * H, dk), host(S0).reshape(B * H, dk, dv))
+    o2 = torch.from_numpy(o_r).to(q.dtype).cuda()
+    zeco.apply_init_state_chunk_decay(q, g, dev(Gk_r.reshape(B, P * N, H, dk)), dev(Si_r.reshape(P, B, H, dk, dv)),
+                                      o2, P, scale=0.5, first_segment_is_zero=False)
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(o2), o_full, (0, 2)) <= tol
+    # chained on the GPU
+    S_init, S_last = zeco.state_scan(S_loc, G_tot, S0=S0)
+    zeco.apply_init_state_chunk_decay(q, g, G_chunk, S_init, o, P, scale=0.5, first_segment_is_zero=False)
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(o), o_full, (0, 2)) <= tol
+
+
+@pytest.mark.parametrize("gd", ["f32", "bf16"])
+def test_chunk_decay_correction_stops_where_the_decay_has_vanished(gd):
+    """As test_apply_init_state_stops_where_the_decay_has_vanished, for the correction that works from g
+    and the per-chunk decay: crossing inside a chunk, on a chunk boundary, on a workgroup boundary,
+    never, and before the first token."""
+    dk, dv, B, H, L, P = 128, 128, 1, 5, 2048, 2
+    print("chunk-decay vanish", gd, flush=True)
+    r = np.random.default_rng(23)
+    q = torch.from_numpy(r.standard_normal((B, P * L, H, dk))).to(torch.bfloat16).cuda()
+    o0 = torch.from_numpy(r.standard_normal((B, P * L, H, dv))).to(torch.bfloat16).cuda()
+    S = r.standard_normal((P, B, H, dk, dv)).astype(np.float32)
+    cross = [700, 1024, 1536, None, 0]
+    g = np.zeros((B, P * L, H, dk), dtype=np.float32)
+    for h, c in enumerate(cross):
+        if c is None:
+            g[:, :, h] = -0.2
+            g[:, :, h, 5] = -0.01
+        elif c == 0:
+            g[:, :, h] = -200.0
+        else:
+            g[:, :, h] = -106.0 / c * (1.0 + 0.3 * r.random(dk))
+    gt = torch.from_numpy(g).to(synth.torch_dtype(gd)).cuda()
+    gh = host(gt)                                              # the gates as the kernel sees them
+    G = np.cumsum(gh.reshape(B, P, L, H, dk), axis=2)
+    Gk = np.zeros((B, P, L // 64, H, dk))
+    Gk[:, :, 1:] = G.reshape(B, P, L // 64, 64, H, dk)[:, :, :-1, 63]
+    Gk_dev = dev(Gk.reshape(B, P * L // 64, H, dk))
+    outs = []
+    for dense in (False, True):
+        o = o0.clone()
+        zeco.apply_init_state_chunk_decay(q, gt, Gk_dev, dev(S), o, P, scale=1.3, first_segment_is_zero=False,
+                                          dense=dense)
         torch.cuda.synchronize()
-        assert rel_err_bh(host(o3), o_r, (0, 2)) <= tol
-        assert rel_err_bh(host(S_last), Sf_r, (0, 1)) <= tol
+        outs.append(o)
+    assert torch.equal(outs[0].float() + 0.0, outs[1].float() + 0.0)
+    ref = oracle.apply_init_state(host(q), G.reshape(B, P * L, H, dk), S.astype(np.float64), host(o0), 1.3)
+    assert rel_err_bh(host(outs[0]), ref, (0, 2)) <= TOL["bf16"]
+    for h, c in enumerate(cross):
+        if c is not None:   # untouched from the first chunk whose incoming decay has vanished
+            Gk_h = host(Gk_dev).reshape(B, P, L // 64, H, dk)[0, 0, :, h]
+            n_stop = int(np.argmax((Gk_h < -105.0).all(axis=-1)))
+            for p in range(P):
+                assert torch.equal(outs[0][:, p * L + 64 * n_stop:(p + 1) * L, h], o0[:, p * L + 64 * n_stop:(p + 1) * L, h])
 
 
 def test_two_phase_rejects_fp32():

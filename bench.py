@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
 
 # HBM bytes per launch of the chunk kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/*.txt give the commands and the copy-kernel calibration); None = not measured.
-MEASURED_TRAFFIC = {("c3", "f32"): 4305900000, ("c4", "f32"): 34452000000}   # profiles/c3_pipeline_kernels.md
+# (profiles/pipeline_kernels_c2_c3_c4.md gives the commands and the copy-kernel calibration); None = not measured.
+MEASURED_TRAFFIC = {("c3", "f32"): 4305900000, ("c4", "f32"): 34452000000}   # profiles/pipeline_kernels_c2_c3_c4.md
 
 
 def algorithmic_bytes(c, g_in, g_cum):
@@ -88,11 +88,21 @@ def main():
     ap.add_argument("--no-backward", action="store_true", help="skip the backward timing")
     ap.add_argument("--no-cold-scan", action="store_true", help="skip the cold-cache timing of the scan")
     ap.add_argument("--no-variants", action="store_true", help="skip the bf16-gate timing")
+    ap.add_argument("--only-pipeline", action="store_true",
+                    help="time the three calls (and the calibration copy) only: no fused, backward, variant or "
+                         "cold-scan legs (for profiler runs, whose per-kernel statistics then cover one launch "
+                         "shape each)")
+    ap.add_argument("--only-fused", action="store_true",
+                    help="besides the three calls, time only the fused forward (both schedules)")
+    ap.add_argument("--dense-correction", action="store_true",
+                    help="pass ZECO_APPLY_DENSE to the correction of the timed pipeline")
     ap.add_argument("--layout", default="bthd", choices=["bthd", "bhtd"],
                     help="memory order of q/k/v/g/o: token-major (default) or head-major")
     ap.add_argument("--calib-copy-mib", type=int, default=1024,
                     help="size of the plain copy timed beside the kernels (0 = skip)")
     args = ap.parse_args()
+    if args.only_pipeline or args.only_fused:
+        args.no_backward = args.no_cold_scan = args.no_variants = True
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (P sequence segments resident on one MI355X); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -126,7 +136,7 @@ def main():
         zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=(S_init, S_last))
         if ev:
             ev[2].record()
-        zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True)
+        zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=args.dense_correction)
         if ev:
             ev[3].record()
 
@@ -145,7 +155,7 @@ def main():
     # output pass from the scanned states) and local pass in chunk-decay form + scan + correction.
     # Reported beside the headline number, never as `value`.
     two_phase = fused_correct = chunk_decay = None
-    if c["io"] == "bf16":
+    if c["io"] == "bf16" and not args.only_pipeline:
         ws = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
         o2 = torch.empty_like(v)
         S_last2 = torch.empty_like(S_last)
@@ -178,6 +188,7 @@ def main():
                              "tokens_per_s": round(B * T / (cms * 1e-3), 1),
                              "note": "local pass (chunk-decay form) + scan + correction that stops where the decay "
                                      "has vanished; traffic depends on the gates"}
+        if args.gate == "channel" and not args.only_fused:
             # the three calls of the headline with the cumulative decay kept per chunk (Alg. 1's gamma~ list)
             G_chunk = torch.empty(B, T // 64, H, dk, dtype=torch.float32, device="cuda:0")
 
@@ -293,23 +304,24 @@ def main():
 
     # The correction stops, per (segment, head), where the decay factor exp(G_cum) has become an exact
     # zero; the same kernel made to stream every token gives its bandwidth on the full traffic.
-    dense_ms = None
-    if P > 1:
-        de = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
-        nd = max(1, args.steps // 2)
-        de[0].record()
-        for _ in range(nd):
-            zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
-        de[1].record()
-        torch.cuda.synchronize()
-        dense_ms = de[0].elapsed_time(de[1]) / nd
+    dense_ms = live_frac = None
+    if P > 1 and not args.dense_correction:
         # tokens per (segment, head) the default call works on: up to the first 64-token block whose
         # first token has G_cum < -105 in every channel
         Gs = G_cum.view((B, P, L // 64, 64, H) + gdim)[:, 1:, :, 0]
         alive = (Gs >= -105.0).any(dim=-1) if args.gate == "channel" else (Gs >= -105.0)
         live_frac = float(alive.float().mean().item())
         del Gs, alive
+        if not (args.only_pipeline or args.only_fused):
+            de = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
+            nd = max(1, args.steps // 2)
+            de[0].record()
+            for _ in range(nd):
+                zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
+            de[1].record()
+            torch.cuda.synchronize()
+            dense_ms = de[0].elapsed_time(de[1]) / nd
 
     import statistics
     samples = {n: [e[i].elapsed_time(e[i + 1]) for e in evs] for i, n in enumerate(["local", "scan", "apply"])}
@@ -345,7 +357,7 @@ def main():
                 kernels[n]["TFLOPs"] = round(af[n] / ms[n] / 1e9, 1)
                 kernels[n]["mfma_frac"] = round(af[n] / ms[n] / 1e9 / MFMA_BF16_PEAK_TF, 4)
     kernels["local"]["tokens_per_s"] = round(B * T / (ms["local"] * 1e-3), 1)
-    if dense_ms and "apply" in kernels:
+    if live_frac is not None and "apply" in kernels:
         ka = kernels["apply"]
         ka["live_fraction"] = round(live_frac, 4)
         ka["alg_bytes"] = int(ab["apply"] * live_frac)
@@ -355,10 +367,11 @@ def main():
         ka.pop("mfma_frac", None)
         ka["note"] = ("stops where exp(G_cum) is an exact zero in every channel (bitwise the same o); alg_bytes "
                       "counts the 64-token blocks it works on; dense_* = the same kernel streaming every token")
-        ka["dense_ms"] = round(dense_ms, 4)
-        ka["dense_alg_bytes"] = ab["apply"]
-        ka["dense_GBps"] = round(ab["apply"] / dense_ms / 1e6, 1)
-        ka["dense_hbm_frac"] = round(ab["apply"] / dense_ms / 1e6 / HBM_PEAK_GBS, 4)
+        if dense_ms:
+            ka["dense_ms"] = round(dense_ms, 4)
+            ka["dense_alg_bytes"] = ab["apply"]
+            ka["dense_GBps"] = round(ab["apply"] / dense_ms / 1e6, 1)
+            ka["dense_hbm_frac"] = round(ab["apply"] / dense_ms / 1e6 / HBM_PEAK_GBS, 4)
     if scan_cold:
         kernels["scan"]["cold_cache_ms"] = round(scan_cold, 4)
         kernels["scan"]["cold_cache_GBps"] = round(ab["scan"] / scan_cold / 1e6, 1)

@@ -74,6 +74,52 @@ def cpu_baseline(inp, c, sample_tokens):
                       "the same inputs, OpenMP over heads" % (sample_tokens, c["H"])}
 
 
+def single_segment_case(args):
+    """configs[1] (one segment of 16384 tokens, H = 16: the local pass alone) timed beside the headline
+    workload: the three calls (scan and correction have nothing to do at P = 1) and the fused forward."""
+    import torch
+    from paper_2507_01004_amd import synth, zeco
+    inp, c = synth.config_inputs("c2", device="cuda:0", g=args.g_dtype, per_head_gate=args.gate == "head")
+    q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
+    B, T, H, dk = q.shape
+    dv, P = v.shape[-1], c["P"]
+    gdim = (dk,) if args.gate == "channel" else ()
+    outs = (torch.empty_like(v), torch.empty(P, B, H, dk, dv, dtype=torch.float32, device="cuda:0"),
+            torch.empty((B, T, H) + gdim, dtype=torch.float32, device="cuda:0"),
+            torch.empty((P, B, H) + gdim, dtype=torch.float32, device="cuda:0"))
+    S_init, S_last = torch.empty_like(outs[1]), torch.empty(B, H, dk, dv, dtype=torch.float32, device="cuda:0")
+    nws = zeco.local_fwd_workspace_bytes(q, v, g, P)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda:0") if nws else None
+    wsf = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
+
+    def step():
+        zeco.gla_local_fwd(q, k, v, g, P, out=outs, workspace=ws)
+        zeco.state_scan(outs[1], outs[3], K_blocks=args.k_blocks, out=(S_init, S_last))
+        zeco.apply_init_state(q, g, outs[2], S_init, outs[0], P, first_segment_is_zero=True)
+
+    res = {}
+    for name, fn in (("three_call", step), ("local_fwd", lambda: zeco.gla_local_fwd(q, k, v, g, P, out=outs, workspace=ws)),
+                     ("fused_fwd", lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(outs[0], S_last), workspace=wsf))):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = e0.elapsed_time(e1) / args.steps
+    g_in = (dk * (4 if args.g_dtype == "f32" else 2)) if args.gate == "channel" else 4
+    ab = algorithmic_bytes(c, g_in, dk * 4 if args.gate == "channel" else 4)["local"]
+    return {"workload": "c2: B=%d H=%d P=%d x L=%d, d_k=d_v=%d" % (B, H, P, c["L"], dk),
+            "ms_per_step": round(res["three_call"], 4), "tokens_per_s": round(B * T / (res["three_call"] * 1e-3), 1),
+            "local_fwd_ms": round(res["local_fwd"], 4), "local_fwd_alg_bytes": ab,
+            "local_fwd_hbm_frac": round(ab / res["local_fwd"] / 1e6 / HBM_PEAK_GBS, 4),
+            "fused_fwd_ms": round(res["fused_fwd"], 4),
+            "fused_fwd_tokens_per_s": round(B * T / (res["fused_fwd"] * 1e-3), 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -400,6 +446,8 @@ def main():
         "g_bf16": g_bf16,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
     }
+    if args.workload != "c2" and not (args.only_pipeline or args.only_fused):
+        out["single_segment_c2"] = single_segment_case(args)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inp, c, min(T, 131072))
     print(json.dumps(out))

@@ -138,6 +138,8 @@ def main():
                     help="time the three calls (and the calibration copy) only: no fused, backward, variant or "
                          "cold-scan legs (for profiler runs, whose per-kernel statistics then cover one launch "
                          "shape each)")
+    ap.add_argument("--only-backward", action="store_true",
+                    help="besides the three calls, time only the backward (and the training pair)")
     ap.add_argument("--only-fused", action="store_true",
                     help="besides the three calls, time only the fused forward (both schedules)")
     ap.add_argument("--dense-correction", action="store_true",
@@ -148,7 +150,9 @@ def main():
                     help="size of the plain copy timed beside the kernels (0 = skip)")
     args = ap.parse_args()
     if args.only_pipeline or args.only_fused:
-        args.no_backward = args.no_cold_scan = args.no_variants = True
+        args.no_backward = True
+    if args.only_pipeline or args.only_fused or args.only_backward:
+        args.no_cold_scan = args.no_variants = True
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (P sequence segments resident on one MI355X); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -201,7 +205,7 @@ def main():
     # output pass from the scanned states) and local pass in chunk-decay form + scan + correction.
     # Reported beside the headline number, never as `value`.
     two_phase = fused_correct = chunk_decay = None
-    if c["io"] == "bf16" and not args.only_pipeline:
+    if c["io"] == "bf16" and not (args.only_pipeline or args.only_backward):
         ws = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
         o2 = torch.empty_like(v)
         S_last2 = torch.empty_like(S_last)
@@ -273,11 +277,11 @@ def main():
         torch.cuda.synchronize()
         bms = be[0].elapsed_time(be[1]) / nb
         th = B * T * H
-        # bytes of the five passes as built: forward states (k, v, g), state gradients (q, g, dO), dQ (dO, v,
-        # k, q, g in; dq and fp32 q.*dq out), dV (k, q, dO, g in; dv out), dK (v, dO, q, k, g, fp32 q.*dq in;
-        # dk and fp32 dg out)
+        # bytes of the four passes as built: forward states (k, v, g), dQ (dO, v, k, q, g in; dq and fp32 q.*dq
+        # out; it also leaves the pieces' state gradients), dV (k, q, dO, g in; dv out), dK (v, dO, q, k, g, fp32
+        # q.*dq in; dk and fp32 dg out)
         io = dk * 2
-        pb = th * (2 * (2 * io + g_in) + (5 * io + g_in + g_cum) + (4 * io + g_in) + (5 * io + g_in + 2 * g_cum))
+        pb = th * ((2 * io + g_in) + (5 * io + g_in + g_cum) + (4 * io + g_in) + (5 * io + g_in + 2 * g_cum))
         # training pair: the forward leaves the states at the backward's piece boundaries, the backward
         # starts from them instead of recomputing them
         save = torch.empty(zeco.saved_states_bytes(q, v, g, P), dtype=torch.uint8, device="cuda:0")
@@ -358,7 +362,7 @@ def main():
         alive = (Gs >= -105.0).any(dim=-1) if args.gate == "channel" else (Gs >= -105.0)
         live_frac = float(alive.float().mean().item())
         del Gs, alive
-        if not (args.only_pipeline or args.only_fused):
+        if not (args.only_pipeline or args.only_fused or args.only_backward):
             de = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
             zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
             nd = max(1, args.steps // 2)
@@ -446,7 +450,7 @@ def main():
         "g_bf16": g_bf16,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
     }
-    if args.workload != "c2" and not (args.only_pipeline or args.only_fused):
+    if args.workload != "c2" and not (args.only_pipeline or args.only_fused or args.only_backward):
         out["single_segment_c2"] = single_segment_case(args)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inp, c, min(T, 131072))

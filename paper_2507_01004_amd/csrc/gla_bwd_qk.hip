@@ -30,12 +30,19 @@
 // Q .* dQ (fp32) in the dG array; the dK pass, which walks the tokens from the last to the first
 // anyway, subtracts K .* dK, accumulates and overwrites the array with dG.  Both do this one chunk
 // late, from the fp32 result tile left in LDS, in the gate pass's thread layout (coalesced rows).
+//
+// State gradient of a segment as a by-product of the dQ pass (EMIT).  What a segment sends back to the
+// state entering it is  dS_loc = scale * sum_t (Q_t .* exp(G_t))^T dO_t  with G_t the log decay from
+// the segment's first token through t: the first loop of the backward listing run from dS = 0.  The
+// listing walks the chunks backwards; the sum itself has no order, so the dQ pass, which reads q, g
+// and dO anyway, accumulates it in a second set of accumulators (transposed like W) from two more
+// tiles, dO^T and (Q .* exp(G))^T, and the separate pass over q, g, dO is not needed.
 #include "zeco_device.h"
 #include "zeco_internal.h"
 
 namespace zeco {
 
-template <int DK, int DV> struct QKCfg {
+template <int DK, int DV, bool EMIT = false> struct QKCfg {
     static constexpr int NW = DK / 16;             // waves, 16 output channels each
     static constexpr int NT = 64 * NW;
     static constexpr int NIT = DV / 16;            // row tiles of W per wave
@@ -61,7 +68,9 @@ template <int DK, int DV> struct QKCfg {
     static constexpr int kOffGam = kOffTot + NW * DK * 4;
     static constexpr int kOffTot2 = kOffGam + DK * 4;        // [wave][channel] sums of the dG terms
     static constexpr int kOffCarry = kOffTot2 + NW * DK * 4; // [channel] dG contribution of later segments
-    static constexpr int kBytes = kOffCarry + DK * 4;
+    static constexpr int kOffXT = kOffCarry + DK * 4;        // EMIT: X^T (channel-major) and (Q .* exp(G))^T
+    static constexpr int kOffQT = kOffXT + (EMIT ? DV * TS : 0);
+    static constexpr int kBytes = kOffQT + (EMIT ? DK * TS : 0);
 
     // LDS position of contraction channel j inside an Xs / Ys row.  A lane of a 16x16 accumulator
     // tile owns rows 4 kg .. 4 kg + 3; the rows it owns in two adjacent tiles of W serve as its eight
@@ -81,9 +90,12 @@ __device__ __forceinline__ bf16x8 pack2x4(f32x4 a, f32x4 b) {
 // REV = false: dQ (x = dO, y = v, z = k, W_init = forward states; the query scale multiplies the
 // output).  REV = true: dK (x = v, y = dO, z = q, W_init = state gradients entering each segment's
 // final state; the query scale rides on Q .* Lambda, so that the running dS is the true gradient).
-template <int DK, int DV, bool REV, int GM>
+// EMIT (dQ pass only): also accumulate the segment's state gradient dS_loc and emit it (and, when asked,
+// the segment's total log decay).
+template <int DK, int DV, bool REV, int GM, bool EMIT>
 __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
-    typedef QKCfg<DK, DV> Cfg;
+    static_assert(!(REV && EMIT), "the state gradient is a by-product of the forward-direction pass");
+    typedef QKCfg<DK, DV, EMIT> Cfg;
     typedef Mma<16> M;
     typedef GateVal<GM> GV;
     constexpr int XS = Cfg::XS, TS = Cfg::TS, FS = Cfg::FS, NW = Cfg::NW, NT = Cfg::NT;
@@ -99,6 +111,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // chunk decay [channel]
     float *wtot2 = reinterpret_cast<float *>(lds + Cfg::kOffTot2);
     float *carry0 = reinterpret_cast<float *>(lds + Cfg::kOffCarry);
+    unsigned char *Xt = lds + Cfg::kOffXT, *Qt = lds + Cfg::kOffQT;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -141,6 +154,12 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         for (int it = 0; it < Cfg::NIT; ++it) Sacc[it] = *reinterpret_cast<const f32x4 *>(Wi + it * 16);
     }
 
+    // EMIT: dS_loc^T in the layout of W, and the log decay of the chunks done so far (this thread's channels)
+    f32x4 Dacc[EMIT ? Cfg::NIT : 1];
+    f32x4 gpre = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int it = 0; it < (EMIT ? Cfg::NIT : 1); ++it) Dacc[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+
     // Score tiles above the diagonal are never computed: zero them once.
     for (int e = tid; e < 64 * TS / 16; e += NT)
         *reinterpret_cast<u32x4 *>(Ps + e * 16) = u32x4{0u, 0u, 0u, 0u};
@@ -167,11 +186,13 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 
     // raw inputs of the chunk worked on next
     u32x2 rx[TPTV], ry[TPTV], rz[TPT];
+    u32x2 rq[EMIT ? TPT : 1];   // EMIT: q of the chunk worked on next (otherwise q is fetched late, for dG only)
     typename GV::raw_t rg[TPT];
     {
         const long long c0 = (long long)chunk_of(0) * 64;
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
+            if constexpr (EMIT) rq[u] = *reinterpret_cast<const u32x2 *>(z2b + ((c0 + tq * TPT + u) * st + 4 * cq) * 2);
             rz[u] = *reinterpret_cast<const u32x2 *>(zb + ((c0 + tq * TPT + u) * st + 4 * cq) * 2);
             rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((c0 + tq * TPT + u) * gst + (GH ? 0 : 4 * cq)) * GB);
         }
@@ -307,6 +328,18 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                 *reinterpret_cast<u32x2 *>(Xs + r * XS + xpos * 2) = rx[u];
                 *reinterpret_cast<u32x2 *>(Ys + r * XS + xpos * 2) = ry[u];
             }
+            if constexpr (EMIT) {   // X^T, channel-major (forward direction: tokens in order)
+                TokenRun<TPTV> cx[4];
+#pragma unroll
+                for (int m = 0; m < TPTV / 2; ++m) {
+                    cx[0].w[m] = pair_lo(rx[2 * m][0], rx[2 * m + 1][0]);
+                    cx[1].w[m] = pair_hi(rx[2 * m][0], rx[2 * m + 1][0]);
+                    cx[2].w[m] = pair_lo(rx[2 * m][1], rx[2 * m + 1][1]);
+                    cx[3].w[m] = pair_hi(rx[2 * m][1], rx[2 * m + 1][1]);
+                }
+#pragma unroll
+                for (int a = 0; a < 4; ++a) cx[a].store(Xt + (4 * vq + a) * TS + tv * TPTV * 2);
+            }
 #pragma unroll
             for (int m = 0; m < TPTV / 2; ++m) {
                 // tokens (2m, 2m+1) of the run share a word; reversed, the run is written back to front
@@ -346,6 +379,13 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             }
             TokenRun<TPT> zt[4];
             u32x2 zprev = {0u, 0u};
+            TokenRun<TPT> qt[EMIT ? 4 : 1];
+            u32x2 qprev = {0u, 0u};
+            f32x4 epre = {0.f, 0.f, 0.f, 0.f};   // EMIT: scale * decay of the earlier chunks of the segment
+            if constexpr (EMIT) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) epre[a] = __builtin_amdgcn_exp2f(gpre[GH ? 0 : a] * kLog2e) * p.qscale;
+            }
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
                 const int t = tq * TPT + u;
@@ -368,6 +408,20 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                 const u32x2 zq = {pack_bf16(bf16_lo(zw[0]) * ez[0], bf16_hi(zw[0]) * ez[1]),
                                   pack_bf16(bf16_lo(zw[1]) * ez[2], bf16_hi(zw[1]) * ez[3])};
                 *reinterpret_cast<f32x4 *>(Fs + pos_of(t) * FS + 16 * cq) = ef;
+                if constexpr (EMIT) {   // (Q .* exp(G))^T: F = Lambda here, times the earlier chunks' decay
+                    const u32x2 qw = rq[u];
+                    rq[u] = *reinterpret_cast<const u32x2 *>(z2b + ((t1 + t) * st + 4 * cq) * 2);
+                    rz2[u] = qw;   // kept for this chunk's dG terms
+                    const u32x2 qh = {pack_bf16(bf16_lo(qw[0]) * ef[0] * epre[0], bf16_hi(qw[0]) * ef[1] * epre[1]),
+                                      pack_bf16(bf16_lo(qw[1]) * ef[2] * epre[2], bf16_hi(qw[1]) * ef[3] * epre[3])};
+                    if (u % 2 == 1) {
+                        qt[0].w[u / 2] = pair_lo(qprev[0], qh[0]);
+                        qt[1].w[u / 2] = pair_hi(qprev[0], qh[0]);
+                        qt[2].w[u / 2] = pair_lo(qprev[1], qh[1]);
+                        qt[3].w[u / 2] = pair_hi(qprev[1], qh[1]);
+                    }
+                    qprev = qh;
+                }
                 if (u % 2 == 1) {
                     const u32x2 a0 = REV ? zq : zprev, a1 = REV ? zprev : zq;
                     const int wd = REV ? (TPT - 1 - u) / 2 : u / 2;
@@ -381,6 +435,13 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             const int c0 = REV ? 64 - (tq + 1) * TPT : tq * TPT;
 #pragma unroll
             for (int a = 0; a < 4; ++a) zt[a].store(Zt + (4 * cq + a) * TS + c0 * 2);
+            if constexpr (EMIT) {
+#pragma unroll
+                for (int a = 0; a < 4; ++a) {
+                    qt[a].store(Qt + (4 * cq + a) * TS + c0 * 2);
+                    gpre[a] += total[a];
+                }
+            }
             if (tq == 0) {
                 f32x4 gm;
 #pragma unroll
@@ -393,7 +454,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         // operands of this chunk's dG terms, consumed one iteration later
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
-            rz2[u] = *reinterpret_cast<const u32x2 *>(z2b + ((t0 + tq * TPT + u) * st + 4 * cq) * 2);
+            if constexpr (!EMIT) rz2[u] = *reinterpret_cast<const u32x2 *>(z2b + ((t0 + tq * TPT + u) * st + 4 * cq) * 2);
             if constexpr (REV && GH) {   // the channel sum of q .* dq, booked on the first channel
                 const float x = dgb[(t0 + tq * TPT + u) * gcs];
                 rqd[u] = f32x4{cq == 0 ? x : 0.f, 0.f, 0.f, 0.f};
@@ -478,7 +539,29 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             }
             Sacc[it] = acc;
         }
+        if constexpr (EMIT) {   // dS_loc^T += X^T (Q .* exp(G))
+            bf16x8 qf[2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) qf[ks] = lds_frag(Qt, (w * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2);
+#pragma unroll
+            for (int it = 0; it < Cfg::NIT; ++it)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    Dacc[it] = M::run(lds_frag(Xt, (it * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2), qf[ks], Dacc[it]);
+        }
         __syncthreads();
+    }
+    if constexpr (EMIT) {
+        float *Dl = p.dS_loc + sbh * DK * DV + (size_t)(w * 16 + l16) * DV + 4 * kg;
+#pragma unroll
+        for (int it = 0; it < Cfg::NIT; ++it) *reinterpret_cast<f32x4 *>(Dl + it * 16) = Dacc[it];
+        if (p.G_tot_out && tq == 0) {   // total log decay of the segment
+            if constexpr (GH) {
+                if (cq == 0) p.G_tot_out[sbh] = gpre[0];
+            } else {
+                *reinterpret_cast<f32x4 *>(p.G_tot_out + sbh * DK + 4 * cq) = gpre;
+            }
+        }
     }
     // dG terms of the last chunk processed
     const long long tl = (long long)chunk_of(N - 1) * 64;
@@ -489,14 +572,21 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     }
 }
 
-template <int DK, int DV, bool REV, int GM>
-static hipError_t launch_qk(const BwdQKParams &p, hipStream_t s) {
-    typedef QKCfg<DK, DV> Cfg;
-    auto kern = gla_bwd_qk_kernel<DK, DV, REV, GM>;
+template <int DK, int DV, bool REV, int GM, bool EMIT>
+static hipError_t launch_qk2(const BwdQKParams &p, hipStream_t s) {
+    typedef QKCfg<DK, DV, EMIT> Cfg;
+    auto kern = gla_bwd_qk_kernel<DK, DV, REV, GM, EMIT>;
     hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.B * p.P * p.H), dim3(Cfg::NT), Cfg::kBytes, s, p);
     return hipGetLastError();
+}
+template <int DK, int DV, bool REV, int GM>
+static hipError_t launch_qk(const BwdQKParams &p, hipStream_t s) {
+    if constexpr (!REV) {
+        if (p.dS_loc) return launch_qk2<DK, DV, false, GM, true>(p, s);
+    }
+    return launch_qk2<DK, DV, REV, GM, false>(p, s);
 }
 
 template <bool REV, int GM>

@@ -270,29 +270,44 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
 }
 
 // ---- backward (App. A.4) ------------------------------------------------------------------------------
-// The passes after the two scans, over `P` pieces of `L` tokens: dQ from the forward states, dV and dK
-// from the state gradients, dG from all of them.
-static zeco_status bwd_passes(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
-                              const void *v, const void *g, const void *dO, const float *S_init,
-                              const float *S_last, const float *dS_in, void *dq, void *dk, void *dv,
-                              float *dg, hipStream_t s) {
-    const int gb = gate_mode(d);
-    zeco::BwdQKParams b;
+// The gradient passes over `P` pieces of `L` tokens.  dQ from the forward states; with `dS_loc` it also
+// emits every piece's state gradient from dS = 0 (and with `G_tot_out` its total log decay), which is
+// what the reverse scan chains into dS_in.
+static void fill_bwd_params(zeco::BwdQKParams &b, const zeco_gla_desc *d, int P, int L, const void *g,
+                            float *dg, const float *S_init, const float *S_last) {
     b.g = g; b.B = d->B; b.P = P; b.H = d->H; b.L = L; b.n_chunks = L / d->C;
     b.sb = d->stride_b; b.st = d->stride_t; b.sh = d->stride_h;
     b.vb = d->vstride_b; b.vt = d->vstride_t; b.vh = d->vstride_h;
     b.dg = dg; b.S_init = S_init; b.S_last = S_last;
-    b.x = dO; b.y = v; b.z = k; b.z2 = q; b.out = dq; b.W_init = S_init; b.zscale = 1.f; b.oscale = d->scale;
-    hipError_t e = zeco::launch_bwd_qk(b, d->d_k, d->d_v, gb, false, s);
-    if (e != hipSuccess) return ZECO_ERR_HIP;
+}
 
+static zeco_status bwd_dq_pass(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
+                               const void *v, const void *g, const void *dO, const float *S_init,
+                               const float *S_last, void *dq, float *dg, float *dS_loc, float *G_tot_out,
+                               hipStream_t s) {
+    zeco::BwdQKParams b;
+    fill_bwd_params(b, d, P, L, g, dg, S_init, S_last);
+    b.x = dO; b.y = v; b.z = k; b.z2 = q; b.out = dq; b.W_init = S_init; b.zscale = 1.f; b.oscale = d->scale;
+    b.dS_loc = dS_loc; b.G_tot_out = G_tot_out; b.qscale = d->scale;
+    return from_hip(zeco::launch_bwd_qk(b, d->d_k, d->d_v, gate_mode(d), false, s));
+}
+
+// dV and dK from the state gradients entering the pieces, dG from all of them (after the dQ pass, whose
+// q .* dq left in dg the dK pass consumes).
+static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
+                                    const void *v, const void *g, const void *dO, const float *S_init,
+                                    const float *S_last, const float *dS_in, void *dk, void *dv,
+                                    float *dg, hipStream_t s) {
+    const int gb = gate_mode(d);
     zeco::ChunkParams c;
     fill_chunk_params(c, d);
     c.P = P; c.L = L; c.n_chunks = L / d->C;
     c.q = k; c.k = q; c.v = dO; c.g = g; c.o = dv; c.S_init = dS_in; c.scale = 1.f; c.kscale = d->scale;
-    if ((e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, gb, 4, s)) != hipSuccess) return ZECO_ERR_HIP;
+    hipError_t e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, gb, 4, s);
+    if (e != hipSuccess) return ZECO_ERR_HIP;
 
-    // after the dQ pass: turns the q .* dq left in dg into dG
+    zeco::BwdQKParams b;
+    fill_bwd_params(b, d, P, L, g, dg, S_init, S_last);
     b.x = v; b.y = dO; b.z = q; b.z2 = k; b.out = dk; b.W_init = dS_in; b.zscale = d->scale; b.oscale = 1.f;
     return from_hip(zeco::launch_bwd_qk(b, d->d_k, d->d_v, gb, true, s));
 }
@@ -324,8 +339,10 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
         !aligned16(dv) || !aligned16(dg))
         return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
-    return bwd_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dq, dk, dv, dg,
-                      static_cast<hipStream_t>(stream));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, s);
+    if (sq != ZECO_OK) return sq;
+    return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, s);
 }
 
 // Pieces each segment is cut into by zeco_gla_fused_bwd: as in the forward, and further down to at most
@@ -411,14 +428,15 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
         if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
     }
 
-    // state gradients: local reverse pass (which also emits the pieces' total decays when the forward
-    // state pass did not run), then the chain from the last piece to the first
-    p.k = q; p.v = dO; p.g = g; p.S_loc = dSloc; p.G_tot = S_saved ? Gtot : nullptr; p.kscale = d->scale;
-    if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 3, s)) != hipSuccess) return ZECO_ERR_HIP;
+    // dQ from the forward states; the same pass leaves every piece's state gradient from dS = 0 (and
+    // the pieces' total decays when the forward state pass did not run), which the reverse scan chains
+    // from the last piece to the first
+    zeco_status zs = bwd_dq_pass(d, P, L, q, k, v, g, dO, Sin, Sl, dq, dg, dSloc, S_saved ? Gtot : nullptr, s);
+    if (zs != ZECO_OK) return zs;
     sp.S_loc = dSloc; sp.G_tot = Gtot; sp.S0 = dS_T; sp.S_init = dSin; sp.S_last = dS0; sp.reverse = 1;
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
 
-    return bwd_passes(d, P, L, q, k, v, g, dO, Sin, Sl, dSin, dq, dk, dv, dg, s);
+    return bwd_dv_dk_passes(d, P, L, q, k, v, g, dO, Sin, Sl, dSin, dk, dv, dg, s);
 }
 
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,

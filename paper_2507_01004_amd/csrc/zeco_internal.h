@@ -70,6 +70,10 @@ struct BwdQKParams {
     const float *W_init, *S_init, *S_last;
     int B, P, H, L, n_chunks;
     float zscale, oscale;        // multipliers of the gated operand and of the output
+    // dQ pass only, optional: also emit each segment's state gradient from dS = 0,
+    // dS_loc [P,B,H,d_k,d_v] = qscale * sum_t (q_t .* exp(G_t))^T x_t, and its total log decay G_tot_out
+    float *dS_loc = nullptr, *G_tot_out = nullptr;
+    float qscale = 1.f;
     long long sb, st, sh, vb, vt, vh;
 };
 

@@ -125,3 +125,29 @@ def test_backward_entry_points_reject_bad_arguments(L):
     assert L.zeco_gla_fused_bwd(ref(d), *fused, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
     fused[0] = ctypes.c_void_p(0x1004)
     assert L.zeco_gla_fused_bwd(ref(d), *fused, need, None) == zeco.ZECO_ERR_INVALID_ARG
+
+
+def test_chunk_decay_and_fused_forward_reject_bad_arguments(L):
+    d = good_desc()
+    f32 = good_desc(io_dtype=zeco.ZECO_F32)
+    head = good_desc(g_per_head=1)
+    ref = ctypes.byref
+    loc = [FAKE] * 9
+    assert L.zeco_gla_local_fwd_chunk_decay(ref(f32), *loc, None) == zeco.ZECO_ERR_UNSUPPORTED
+    assert L.zeco_gla_local_fwd_chunk_decay(ref(head), *loc, None) == zeco.ZECO_ERR_UNSUPPORTED
+    loc[6] = None                                          # G_chunk missing
+    assert L.zeco_gla_local_fwd_chunk_decay(ref(d), *loc, None) == zeco.ZECO_ERR_INVALID_ARG
+    app = [FAKE] * 5
+    assert L.zeco_apply_init_state_chunk_decay(ref(d), *app, 8, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_apply_init_state_chunk_decay(ref(head), *app, 0, None) == zeco.ZECO_ERR_UNSUPPORTED
+    app[1] = ctypes.c_void_p(0x1008)                       # g misaligned
+    assert L.zeco_apply_init_state_chunk_decay(ref(d), *app, 0, None) == zeco.ZECO_ERR_INVALID_ARG
+    need = L.zeco_gla_fused_fwd_workspace(ref(d))
+    assert need > 0
+    # q, k, v, g, S0, o, S_last, S_save, schedule, workspace, bytes, stream
+    fused = [FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None]
+    assert L.zeco_gla_fused_fwd(ref(d), *fused, 7, FAKE, need, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
+    assert L.zeco_gla_fused_fwd(ref(head), *fused, zeco.SCHEDULE_CORRECT, FAKE, need, None) == zeco.ZECO_ERR_UNSUPPORTED
+    fused[7] = FAKE                                        # saved states need the two-phase schedule
+    assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need, None) == zeco.ZECO_ERR_UNSUPPORTED

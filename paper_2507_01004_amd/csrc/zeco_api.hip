@@ -51,8 +51,8 @@ static int subsegments(const zeco_gla_desc *d) {
     if (d->io_dtype != ZECO_BF16 || d->g_per_head) return 1;
     const long long streams = (long long)d->B * d->P * d->H;
     if (streams > 64) return 1;
-    int S = 1;
-    while (streams * S < 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
+    int S = 1;   // as many workgroups as fit the 256 compute units in one round, not more
+    while (streams * S * 2 <= 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
     return S;
 }
 
@@ -142,7 +142,7 @@ static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
 #ifdef ZECO_PHASE_TIMING
-    p.dbg = nullptr;
+    p.dbg = zeco::g_phase_dbg;
 #endif
 }
 
@@ -189,11 +189,11 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const
                                             static_cast<hipStream_t>(stream)));
 }
 
-// Pieces each segment is cut into by zeco_gla_fused_fwd: enough for 256 streams, at least 256 tokens each.
+// Pieces each segment is cut into by zeco_gla_fused_fwd: up to 256 streams, at least 256 tokens each.
 static int fused_pieces(const zeco_gla_desc *d) {
     const long long streams = (long long)d->B * d->P * d->H;
-    int S = 1;
-    while (streams * S < 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
+    int S = 1;   // as many workgroups as fit the 256 compute units in one round, not more
+    while (streams * S * 2 <= 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
     return S;
 }
 

@@ -231,7 +231,7 @@ def main():
         two_phase = {"entry": "zeco_gla_fused_fwd(ZECO_SCHEDULE_TWO_PHASE)", "ms_per_step": round(fms, 4),
                      "tokens_per_s": round(B * T / (fms * 1e-3), 1), "alg_bytes": fb,
                      "GBps": round(fb / fms / 1e6, 1), "hbm_frac": round(fb / fms / 1e6 / HBM_PEAK_GBS, 4)}
-        if args.gate == "channel":
+        if True:
             cms = timed(lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws,
                                                    schedule=zeco.SCHEDULE_CORRECT))
             fused_correct = {"entry": "zeco_gla_fused_fwd(ZECO_SCHEDULE_CORRECT)", "ms_per_step": round(cms, 4),

@@ -202,8 +202,10 @@ static int bwd_pieces(const zeco_gla_desc *d);
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
     if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     const size_t n = (size_t)desc->P * fused_pieces(desc) * desc->B * desc->H;
-    const size_t chunks = (size_t)desc->B * desc->P * (desc->L / desc->C) * desc->H;   // G_chunk of the CORRECT schedule
-    return (2 * n * desc->d_k * desc->d_v + n * desc->d_k + chunks * desc->d_k) * sizeof(float);
+    // cumulative decay of the CORRECT schedule: per chunk and channel, or per token with per-head gates
+    const size_t decay = desc->g_per_head ? (size_t)desc->B * desc->P * desc->L * desc->H
+                                          : (size_t)desc->B * desc->P * (desc->L / desc->C) * desc->H * desc->d_k;
+    return (2 * n * desc->d_k * desc->d_v + n * desc->d_k + decay) * sizeof(float);
 }
 
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
@@ -218,7 +220,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     if (schedule != ZECO_SCHEDULE_AUTO && schedule != ZECO_SCHEDULE_TWO_PHASE && schedule != ZECO_SCHEDULE_CORRECT)
         return ZECO_ERR_INVALID_ARG;
-    const bool can_correct = !d->g_per_head && !S_save;
+    const bool can_correct = !S_save;
     if (schedule == ZECO_SCHEDULE_CORRECT && !can_correct) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_gla_fused_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -233,18 +235,25 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
 
     if (schedule == ZECO_SCHEDULE_CORRECT || (schedule == ZECO_SCHEDULE_AUTO && can_correct && p.L >= 4096)) {
         // local pass of every piece from the zero state, scan, correction of the pieces' heads
-        p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_loc = Sloc; p.G_tot = Gtot; p.G_chunk = Gchunk;
-        hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 6, s);
+        // (per-head gates keep the per-token form: their G_cum is 4 bytes per token and head)
+        p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_loc = Sloc; p.G_tot = Gtot;
+        if (d->g_per_head) p.G_cum = Gchunk; else p.G_chunk = Gchunk;
+        hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), d->g_per_head ? 0 : 6, s);
         if (e != hipSuccess) return ZECO_ERR_HIP;
         zeco::ScanParams sp;
         sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
         sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
-        sp.rows_per_block = d->d_k / 16;
+        sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
         if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
         zeco::ApplyParams ap;
         fill_apply_params(ap, d, p.P, p.L);
-        ap.q = q; ap.g = g; ap.g_bf16 = d->g_dtype == ZECO_BF16; ap.G_chunk = Gchunk; ap.S_init = Sinit; ap.o = o;
+        ap.q = q; ap.S_init = Sinit; ap.o = o;
         ap.p0 = S0 ? 0 : 1;
+        if (d->g_per_head) {
+            ap.G_cum = Gchunk;
+            return from_hip(zeco::launch_apply_bf16(ap, d->d_k, d->d_v, s));
+        }
+        ap.g = g; ap.g_bf16 = d->g_dtype == ZECO_BF16; ap.G_chunk = Gchunk;
         return from_hip(zeco::launch_apply_cd_bf16(ap, d->d_k, d->d_v, s));
     }
     p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;

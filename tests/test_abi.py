@@ -148,6 +148,5 @@ def test_chunk_decay_and_fused_forward_reject_bad_arguments(L):
     fused = [FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None]
     assert L.zeco_gla_fused_fwd(ref(d), *fused, 7, FAKE, need, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
-    assert L.zeco_gla_fused_fwd(ref(head), *fused, zeco.SCHEDULE_CORRECT, FAKE, need, None) == zeco.ZECO_ERR_UNSUPPORTED
     fused[7] = FAKE                                        # saved states need the two-phase schedule
     assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need, None) == zeco.ZECO_ERR_UNSUPPORTED

@@ -74,7 +74,12 @@ def test_head_gate_two_phase_forward_and_backward(case):
     S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
     dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
     for s0, dst in ((None, None), (S0, dS_T)):
-        o, S_last = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=s0)
+        for sched in (zeco.SCHEDULE_CORRECT, zeco.SCHEDULE_TWO_PHASE):
+            o, S_last = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=s0, schedule=sched)
+            torch.cuda.synchronize()
+            o_f, S_f = oracle.gla_recurrent(h["q"], h["k"], h["v"], h["g"], 0.5, None if s0 is None else host(s0))
+            assert rel_err_bh(host(o), o_f, (0, 2)) <= TOLB
+            assert rel_err_bh(host(S_last), S_f, (0, 1)) <= TOLB
         got = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], inp["dO"], P, scale=0.5, S0=s0, dS_T=dst)
         torch.cuda.synchronize()
         s0h = None if s0 is None else host(s0)

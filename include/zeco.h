@@ -40,7 +40,8 @@ typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
  * in ELEMENTS; the innermost dimension is contiguous.  Strides must be multiples of 8 elements. */
 typedef struct {
     int32_t B, P, H, L;
-    int32_t d_k, d_v, C;       /* supported: C = 64, L % C == 0, d_k and d_v in {64, 128} */
+    int32_t d_k, d_v, C;       /* supported: C = 64, L % C == 0, d_k and d_v in {64, 128}.  (A sequence is
+                                * padded with tokens that have k = 0 and g = 0: they change no state.) */
     int32_t io_dtype;          /* zeco_dtype of q, k, v, o */
     int32_t g_dtype;           /* zeco_dtype of g */
     float scale;

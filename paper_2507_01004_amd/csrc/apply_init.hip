@@ -125,11 +125,12 @@ __device__ __forceinline__ void apply_block(const bf16x8 (&sf)[ApplyCfg<DK, DV>:
         const f32x4 c0 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg);
         const f32x4 c1 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg + 4);
         const u32x4 old = ocur[m];
-        *reinterpret_cast<u32x4 *>(o_blk + t * vt + 8 * cg) =
+        __builtin_nontemporal_store(
             u32x4{pack_bf16(bf16_lo(old[0]) + c0[0], bf16_hi(old[0]) + c0[1]),
                   pack_bf16(bf16_lo(old[1]) + c0[2], bf16_hi(old[1]) + c0[3]),
                   pack_bf16(bf16_lo(old[2]) + c1[0], bf16_hi(old[2]) + c1[1]),
-                  pack_bf16(bf16_lo(old[3]) + c1[2], bf16_hi(old[3]) + c1[3])};
+                  pack_bf16(bf16_lo(old[3]) + c1[2], bf16_hi(old[3]) + c1[3])},
+            reinterpret_cast<u32x4 *>(o_blk + t * vt + 8 * cg));
     }
 }
 

@@ -225,8 +225,8 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             const f32x4 val = *reinterpret_cast<const f32x4 *>(Fs + pos_of(tq * TPT + u) * FS + 16 * cq);
             // the gradient itself: 32 lanes write one contiguous row (the accumulator layout of the
             // products would give 32-byte pieces)
-            *reinterpret_cast<u32x2 *>(ob + ((tc + tq * TPT + u) * st + 4 * cq) * 2) =
-                u32x2{pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])};
+            __builtin_nontemporal_store(u32x2{pack_bf16(val[0], val[1]), pack_bf16(val[2], val[3])},
+                                        reinterpret_cast<u32x2 *>(ob + ((tc + tq * TPT + u) * st + 4 * cq) * 2));
             const u32x2 zw = rz2[u];
             const f32x4 pr = {bf16_lo(zw[0]) * val[0], bf16_hi(zw[0]) * val[1],
                               bf16_lo(zw[1]) * val[2], bf16_hi(zw[1]) * val[3]};
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                 const float tot = channel_sum(o);
                 if (cq == 0) row[u * gcs] = tot;
             } else {
-                *reinterpret_cast<f32x4 *>(row + u * gcs) = o;
+                __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(row + u * gcs));
             }
         }
 #pragma unroll

@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
 
 # HBM bytes per launch of the chunk kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/pipeline_kernels_c2_c3_c4.md gives the commands and the copy-kernel calibration); None = not measured.
-MEASURED_TRAFFIC = {("c3", "f32"): 4305900000, ("c4", "f32"): 34452000000}   # profiles/pipeline_kernels_c2_c3_c4.md
+MEASURED_TRAFFIC = {("c3", "f32"): 4305900000, ("c4", "f32"): 34469000000}   # profiles/pipeline_kernels_c2_c3_c4.md
 
 
 def algorithmic_bytes(c, g_in, g_cum):

@@ -193,6 +193,13 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         const unsigned v_b0 = ((unsigned)(tv * TPTV) * vt + 4 * vq) * 2;
         const unsigned g_b0 = ((unsigned)(tq * TPT) * gcs + (GH ? 0 : 4 * cq)) * 4;   // G_cum: contiguous [.., H, d_k]
 
+        // Reloads of the streamed inputs: read once by this workgroup, so non-temporal - unless sibling
+        // workgroups share them through the XCD's L2 (NS = 2), where the hint would cost HBM re-reads.
+        auto stream_load = [](auto *ptr) __attribute__((always_inline)) {
+            if constexpr (NS == 1) return __builtin_nontemporal_load(ptr);
+            else return *ptr;
+        };
+
         // Raw q, k, g, v of the chunk worked on next; each piece is reloaded with the following
         // chunk's data right after its last use (clamped to the last chunk).
         u32x2 rq[TPT], rk[TPT], rv[TPTV];
@@ -220,7 +227,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
                 const f32x4 gv = GV::get(rg[u]);
-                rg[u] = __builtin_nontemporal_load(reinterpret_cast<const typename GV::raw_t *>(gn + (size_t)(u * gst) * GB + g_in_b0));
+                rg[u] = stream_load(reinterpret_cast<const typename GV::raw_t *>(gn + (size_t)(u * gst) * GB + g_in_b0));
 #pragma unroll
                 for (int a = 0; a < 4; ++a) run[a] += gv[a];
                 cs[u] = run;
@@ -254,7 +261,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 ch[3].w[wd] = pair_hi(x[1], y[1]);
             }
 #pragma unroll
-            for (int u = 0; u < TPTV; ++u) rv[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(vn + (size_t)(u * vt) * 2 + v_b0));
+            for (int u = 0; u < TPTV; ++u) rv[u] = stream_load(reinterpret_cast<const u32x2 *>(vn + (size_t)(u * vt) * 2 + v_b0));
             const int p0 = REV ? 64 - (tv + 1) * TPTV : tv * TPTV;   // first tile column of the run
 #pragma unroll
             for (int a = 0; a < 4; ++a) ch[a].store(tile + Cfg::kOffVT + (4 * vq + a) * TS + p0 * 2);
@@ -339,7 +346,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                     }
                 }
                 const u32x2 kw = rk[u];
-                rk[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0));
+                rk[u] = stream_load(reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0));
                 const u32x2 kq = {pack_bf16(bf16_lo(kw[0]) * ilam[0], bf16_hi(kw[0]) * ilam[1]),
                                   pack_bf16(bf16_lo(kw[1]) * ilam[2], bf16_hi(kw[1]) * ilam[3])};
                 if constexpr (!NOQ) {   // scores and outputs need Q .* Lambda and token-major K / Lambda
@@ -352,7 +359,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                         for (int a = 0; a < 4; ++a) lam[a] = __builtin_amdgcn_exp2f(SGN * yv[a]);
                     }
                     const u32x2 qw = rq[u];
-                    rq[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(qn + (size_t)(u * st) * 2 + q_b0));
+                    rq[u] = stream_load(reinterpret_cast<const u32x2 *>(qn + (size_t)(u * st) * 2 + q_b0));
                     *reinterpret_cast<u32x2 *>(Qs + pos_of(t) * QS + qpos * 2) =
                         u32x2{pack_bf16(bf16_lo(qw[0]) * lam[0], bf16_hi(qw[0]) * lam[1]),
                               pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};

@@ -1,5 +1,5 @@
 """The library allocates nothing and never synchronises, so its calls can be recorded into a HIP graph:
-capture the three-call pipeline, the fused forward and the fused backward once, replay them on new
+capture the three-call pipeline, the fused forward (both schedules) and the fused backward once, replay them on new
 input values, and compare every replay bitwise with the eager calls."""
 import pytest
 import torch
@@ -22,6 +22,7 @@ def test_pipeline_forward_backward_replay_from_a_graph():
     G_tot = torch.empty(P, B, H, dk, device="cuda")
     S_init, S_last3 = torch.empty_like(S_loc), torch.empty(B, H, dk, dv, device="cuda")
     o2, S_last2 = torch.empty_like(v), torch.empty(B, H, dk, dv, device="cuda")
+    o4, S_last4 = torch.empty_like(v), torch.empty(B, H, dk, dv, device="cuda")
     ws_f = torch.empty(zeco.fused_workspace_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
     ws_b = torch.empty(zeco.fused_bwd_workspace_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
     grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v), torch.empty(B, T, H, dk, device="cuda"),
@@ -32,10 +33,11 @@ def test_pipeline_forward_backward_replay_from_a_graph():
         zeco.gla_local_fwd(q, k, v, g, P, out=(o3, S_loc, G_cum, G_tot), workspace=ws_l)
         zeco.state_scan(S_loc, G_tot, out=(S_init, S_last3))
         zeco.apply_init_state(q, g, G_cum, S_init, o3, P)
-        zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws_f)
+        zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws_f, schedule=zeco.SCHEDULE_TWO_PHASE)
+        zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last4), workspace=ws_f, schedule=zeco.SCHEDULE_CORRECT)
         zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws_b)
 
-    outs = (o3, S_last3, o2, S_last2) + grads
+    outs = (o3, S_last3, o2, S_last2, o4, S_last4) + grads
     run()                      # warm-up outside the capture (loads the code objects)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()

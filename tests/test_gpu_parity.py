@@ -192,6 +192,31 @@ def test_apply_init_state_stops_where_the_decay_has_vanished(io, per_head):
                 assert torch.equal(outs[0][:, p * L + c64:(p + 1) * L, h], o0[:, p * L + c64:(p + 1) * L, h])
 
 
+def test_correction_with_a_ragged_number_of_streams():
+    """133 (segment, batch, head) streams: one full group of 128 and a partial one whose last block of 8
+    is incomplete, for the workgroup-to-stream mapping of both correction kernels."""
+    dk, dv, B, H, P, L = 64, 64, 1, 19, 8, 128
+    r = np.random.default_rng(5)
+    q = torch.from_numpy(r.standard_normal((B, P * L, H, dk))).to(torch.bfloat16).cuda()
+    o0 = torch.from_numpy(r.standard_normal((B, P * L, H, dv))).to(torch.bfloat16).cuda()
+    g = (-r.random((B, P * L, H, dk)) * 0.05).astype(np.float32)
+    S = r.standard_normal((P, B, H, dk, dv)).astype(np.float32)
+    S[0] = 0
+    G = np.cumsum(g.reshape(B, P, L, H, dk), axis=2)
+    Gk = np.zeros((B, P, L // 64, H, dk))
+    Gk[:, :, 1:] = G.reshape(B, P, L // 64, 64, H, dk)[:, :, :-1, 63]
+    ref = oracle.apply_init_state(host(q), G.reshape(B, P * L, H, dk), S.astype(np.float64), host(o0), 1.0)
+    o = o0.clone()
+    zeco.apply_init_state(q, torch.empty(0), dev(G.reshape(B, P * L, H, dk)), dev(S), o, P, first_segment_is_zero=True)
+    o2 = o0.clone()
+    zeco.apply_init_state_chunk_decay(q, dev(g), dev(Gk.reshape(B, P * L // 64, H, dk)), dev(S), o2, P,
+                                      first_segment_is_zero=True)
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(o), ref, (0, 2)) <= TOL["bf16"]
+    assert rel_err_bh(host(o2), ref, (0, 2)) <= TOL["bf16"]
+    assert torch.equal(o[:, :L], o0[:, :L]) and torch.equal(o2[:, :L], o0[:, :L])   # segment 0 untouched
+
+
 def test_strided_views_and_determinism():
     """q, k, g, v taken as views of one fused projection buffer; two runs are bitwise equal."""
     B, T, H, d, P = 1, 256, 4, 128, 2

@@ -37,6 +37,11 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
         float *init = p.S_init + grp * p.P * seg_stride + off;
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
         if (p.S0) s = *reinterpret_cast<const f32x4 *>(p.S0 + grp * seg_stride + off);
+        // optional by-product: the log decay preceding each segment of the chain and the chain's total,
+        // kept by the thread that owns the first columns of a row (forward chains, per-channel gates)
+        const bool prefix = p.G_pre && e % dv4 == 0;
+        float *gpre = prefix ? p.G_pre + grp * p.P * g_stride + (size_t)bh * gdim + row : nullptr;
+        float gsum = 0.f;
 
         for (int p0 = 0; p0 < p.P; p0 += kScanDepth) {
             f32x4 x[kScanDepth];
@@ -54,6 +59,10 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
                 if (p0 + u < p.P) {
                     const size_t sg = p.reverse ? p.P - 1 - (p0 + u) : p0 + u;
                     *reinterpret_cast<f32x4 *>(init + sg * seg_stride) = s;
+                    if (prefix) {
+                        gpre[sg * g_stride] = gsum;
+                        gsum += a[u];
+                    }
                     const float d = fast_exp(a[u]);
                     s[0] = __builtin_fmaf(d, s[0], x[u][0]);
                     s[1] = __builtin_fmaf(d, s[1], x[u][1]);
@@ -63,6 +72,7 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
             }
         }
         if (p.S_last) *reinterpret_cast<f32x4 *>(p.S_last + grp * seg_stride + off) = s;
+        if (prefix) p.G_sum[grp * g_stride + (size_t)bh * gdim + row] = gsum;
     }
 }
 
@@ -72,28 +82,6 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s) {
     int threads = ((slab4 + 63) / 64) * 64;
     if (threads > 256) threads = 256;
     hipLaunchKernelGGL(state_scan_kernel, dim3(blocks, p.groups), dim3(threads), 0, s, p);
-    return hipGetLastError();
-}
-
-// Exclusive prefix and total of the segments' log decays inside each group (tiny, one thread per
-// (group, batch, head, channel)).
-__global__ __launch_bounds__(256) void gate_prefix_kernel(const float *G_tot, float *G_pre, float *G_sum,
-                                                           int P, int BHdk) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= BHdk) return;
-    const size_t g0 = (size_t)blockIdx.y * P * BHdk + e;
-    float acc = 0.f;
-    for (int r = 0; r < P; ++r) {
-        G_pre[g0 + (size_t)r * BHdk] = acc;
-        acc += G_tot[g0 + (size_t)r * BHdk];
-    }
-    G_sum[(size_t)blockIdx.y * BHdk + e] = acc;
-}
-
-hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, int groups, int P,
-                              int BHdk, hipStream_t s) {
-    hipLaunchKernelGGL(gate_prefix_kernel, dim3((BHdk + 255) / 256, groups), dim3(256), 0, s, G_tot, G_pre,
-                       G_sum, P, BHdk);
     return hipGetLastError();
 }
 

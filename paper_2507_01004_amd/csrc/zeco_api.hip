@@ -124,9 +124,8 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     sp.S_loc = Ssub; sp.G_tot = Gtot; sp.S0 = nullptr; sp.S_init = Sinit; sp.S_last = S_loc;
     sp.P = S; sp.groups = d->P; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
     sp.rows_per_block = d->d_k / 16;
+    sp.G_pre = Gpre; sp.G_sum = G_tot;   // log decay preceding each sub-segment; the segment's total
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
-    if ((e = zeco::launch_gate_prefix(Gtot, Gpre, G_tot, d->P, S, d->B * d->H * d->d_k, s)) != hipSuccess)
-        return ZECO_ERR_HIP;
 
     p.S_loc = nullptr; p.G_tot = nullptr; p.S_init = Sinit; p.G_off = Gpre;
     return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 5, s));

@@ -56,6 +56,9 @@ struct ScanParams {
     float *S_init, *S_last;
     int P, BH, d_k, d_v, rows_per_block, groups;
     int reverse = 0;             // 1: chain runs from segment P-1 down to 0
+    // optional (forward chains, per-channel gates): G_pre [groups*P, BH, d_k] = sum of G_tot over the
+    // earlier segments of the chain, G_sum [groups, BH, d_k] = sum over all of them
+    float *G_pre = nullptr, *G_sum = nullptr;
     int gate_per_head = 0;       // 1: G_tot [groups*P, BH], one log decay per head
 };
 
@@ -90,9 +93,6 @@ hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t
 // from (g, G_chunk) instead of G_cum; per-channel gates
 hipError_t launch_apply_cd_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s);
 hipError_t launch_scan(const ScanParams &p, hipStream_t s);
-// Per group of P segments: G_pre[g*P+p] = sum of G_tot[g*P+r] over r < p, G_sum[g] = sum over all r.
-hipError_t launch_gate_prefix(const float *G_tot, float *G_pre, float *G_sum, int groups, int P,
-                              int BHdk, hipStream_t s);
 // reverse = false: dQ (x = dO, y = v, z = k, z2 = q, W_init = forward states); true: dK (x = v, y = dO,
 // z = q, z2 = k, W_init = state gradients; must run after the dQ pass, whose q .* dq it consumes)
 hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, int gate_mode, bool reverse, hipStream_t s);

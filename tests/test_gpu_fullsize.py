@@ -46,7 +46,13 @@ def test_fullsize_sampled_slices(name, samples):
                                                schedule=zeco.SCHEDULE_TWO_PHASE)
     o_corr, S_last_corr = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P,
                                              schedule=zeco.SCHEDULE_CORRECT)
+    # the three calls with the cumulative decay kept per chunk
+    o_cd, S_loc_cd, G_chunk, G_tot_cd = zeco.gla_local_fwd_chunk_decay(inp["q"], inp["k"], inp["v"], inp["g"], P)
+    S_init_cd, S_last_cd = zeco.state_scan(S_loc_cd, G_tot_cd)
+    zeco.apply_init_state_chunk_decay(inp["q"], inp["g"], G_chunk, S_init_cd, o_cd, P)
+    del S_loc_cd, G_chunk, S_init_cd
     torch.cuda.synchronize()
+    assert rel_err_bh(host(S_last_cd), host(S_last), (0, 1)) <= TOL[c["io"]]
     # all schedules end in the same state (up to bf16-operand rounding of the routes)
     assert rel_err_bh(host(S_last_fused), host(S_last), (0, 1)) <= TOL[c["io"]]
     assert rel_err_bh(host(S_last_corr), host(S_last), (0, 1)) <= TOL[c["io"]]
@@ -57,6 +63,7 @@ def test_fullsize_sampled_slices(name, samples):
         assert rel_err_bh(got, o_ref, (0, 2)) <= TOL[c["io"]]
         assert rel_err_bh(host(o_fused[:1, p * L:(p + 1) * L, h:h + 1]), o_ref, (0, 2)) <= TOL[c["io"]]
         assert rel_err_bh(host(o_corr[:1, p * L:(p + 1) * L, h:h + 1]), o_ref, (0, 2)) <= TOL[c["io"]]
+        assert rel_err_bh(host(o_cd[:1, p * L:(p + 1) * L, h:h + 1]), o_ref, (0, 2)) <= TOL[c["io"]]
         assert rel_err_bh(host(o_corr[:1, p * L:p * L + 256, h:h + 1]), o_ref[:, :256], (0, 2)) <= TOL[c["io"]]
         # the head of the segment is where the incoming state matters most
         assert rel_err_bh(got[:, :256], o_ref[:, :256], (0, 2)) <= TOL[c["io"]]

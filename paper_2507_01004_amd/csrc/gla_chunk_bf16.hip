@@ -14,15 +14,22 @@
 // Per chunk (chunk equations of Sec. 2.1, scores as in Alg. 1):
 //   gate, part 1   each thread owns 4 channels x TPT consecutive tokens: serial cumsum of g in
 //                  registers, token groups stitched by lane shuffles inside a wave and one LDS
-//                  exchange across the gate waves;  Vt = V^T -> LDS
+//                  exchange across the gate waves;  Vs = V -> LDS as it comes (token-major)
 //   gate, part 2   cs = inclusive cumsum of g, Lambda = e^cs;  Qs = Q .* Lambda, Ks = K / Lambda
-//                  (token-major), Kt = (K / Lambda)^T (channel-major) -> LDS;  G_cum -> HBM
+//                  (token-major) -> LDS;  G_cum -> HBM
 //   MFMA, part 1   P^T = Ks Qs^T on the 10 lower-triangular 16x16 tiles, causal select -> Ps (bf16);
 //                  O^T  = S^T Qs^T   with S fed straight from the accumulators (see below)
-//   MFMA, part 2   O^T += Vt Ps^T (causal k-range), O * scale -> HBM;
-//                  S <- (gamma^T 1) .* (S + Kt Vt^T)
+//   MFMA, part 2   O^T += V^T Ps^T (causal k-range), O * scale -> HBM;
+//                  S <- (gamma^T 1) .* (S + (K / Lambda)^T V)
 // The last line is Eq. (3) with K .* Gamma = (gamma^T 1)-scaled K / Lambda (Gamma = gamma / Lambda),
 // so one scaled copy of K serves both the scores and the state update.
+//
+// Transposed operands.  The two products of part 2 contract over tokens, so they need V^T and
+// (K / Lambda)^T fragments (lane = channel, k-slots = tokens).  The matrix waves take them from the
+// token-major tiles with gfx950's transposing LDS read (lds_frag_tr below); the gate waves never
+// transpose anything.  (Channel-major copies written by the gate waves cost them two permutes per
+// token pair and stores whose rows sit four apart per lane, 8-way bank conflicts: 5-6 % of the
+// local pass where the gate waves set the pace, 10-16 % with per-head gates.)
 //
 // Accumulator-as-operand.  Lane l of a 32x32 accumulator tile holds column l%32 and, with
 // kg = l/32, rows 8q + 4kg + m (q < 4, m < 4).  The MFMA operand layout wants, from the same lane,
@@ -62,12 +69,15 @@ template <int DK, int DV, int NWG_> struct B16Cfg {
     static constexpr int TPTV = 64 / (64 * NWG / VQ);   // 8, 4 or 2
     // LDS (bytes).  The scaled tiles are double buffered.
     static constexpr int QS = DK * 2 + 16;         // row stride of Qs, Ks
-    static constexpr int TS = 64 * 2 + 16;         // row stride of Kt, Vt, Ps
+    static constexpr int TS = 64 * 2 + 16;         // row stride of Ps
+    // row stride of Vs: 16 dwords past a multiple of 64 banks, so that the 32 lanes of a transposing read
+    // (4 rows x 4 quads x 2 groups of 16 lanes) fall on 64 different banks
+    static constexpr int VS = DV * 2 + 64;
     static constexpr int kOffQ = 0;                // offsets inside one tile buffer
     static constexpr int kOffK = kOffQ + 64 * QS;
-    static constexpr int kOffKT = kOffK + 64 * QS;
-    static constexpr int kOffVT = kOffKT + DK * TS;
-    static constexpr int kTileBytes = kOffVT + DV * TS;
+    static constexpr int kOffV = kOffK + 64 * QS;
+    static constexpr int kOffO2 = kOffV + 64 * VS; // staged output columns beyond d_k (only when d_v > d_k)
+    static constexpr int kTileBytes = kOffO2 + (DV > DK ? 64 * QS : 0);
     static constexpr int kOffP = 2 * kTileBytes;
     static constexpr int kOffTot = kOffP + 64 * TS;
     static constexpr int kOffGam = kOffTot + NWG * DK * 4;
@@ -85,6 +95,26 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
     u32x4 w = {pack_bf16(a[base + 0], a[base + 1]), pack_bf16(a[base + 2], a[base + 3]),
                pack_bf16(a[base + 4], a[base + 5]), pack_bf16(a[base + 6], a[base + 7])};
     return __builtin_bit_cast(bf16x8, w);
+}
+
+// MFMA operand fragment from a TOKEN-major bf16 tile through gfx950's transposing LDS read
+// (ds_read_b64_tr_b16).  In every group of 16 lanes, lane 4 k + r supplies the address of four
+// consecutive elements of tile row k (8 bytes), and lane 4 r' + e receives, as its element k, element e
+// of what lane 4 k + r' supplied: the group turns a patch of 4 tokens x 16 channels into 16 lanes
+// (channels) x 4 tokens.  `addr` is this lane's address for tokens row0 .. row0+3 (row0 + k for its
+// k = (lane % 16) / 4, columns 4 r ..); the second read, `second` bytes further, fills the lane's
+// other four k-slots, and the lane ends up with 8 tokens of its own channel, which is the operand
+// layout of the 32x32x16 MFMA (lane = row or column lt, k-slots = 8 tokens).  Which tokens the rows are
+// is up to the caller: a contraction does not care about the order of its k-slots as long as both
+// operands agree.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+__device__ __forceinline__ bf16x8 lds_frag_tr(const unsigned char *addr, int second) {
+    typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(addr));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(addr + second));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
 }
 
 // DV is the number of state columns this workgroup owns: d_v, or d_v / NS when NS sibling workgroups
@@ -127,7 +157,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE)> Cfg;
     typedef Mma<32> M;
     typedef GateVal<GM> GV;
-    constexpr int QS = Cfg::QS, TS = Cfg::TS, NWM = Cfg::NWM, NT = Cfg::NT;
+    constexpr int QS = Cfg::QS, TS = Cfg::TS, VS = Cfg::VS, NWM = Cfg::NWM, NT = Cfg::NT;
     constexpr int TPT = Cfg::TPT, TPTV = Cfg::TPTV, CQ = Cfg::CQ, GW = Cfg::GW;
     constexpr int GB = GM == kGateBF16 ? 2 : 4;   // bytes per gate element
     constexpr bool GH = GM == kGateHead;
@@ -245,26 +275,15 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             for (int a = 0; a < 4; ++a) excl[a] = inc[a] - run[a];
             if (gl == GW - 1) *reinterpret_cast<f32x4 *>(wtot + gw * DK + 4 * cq) = inc;
         };
-        // V^T of chunk m -> tile buffer
+        // V of chunk m -> tile buffer, token-major as it comes (the matrix waves read it transposed)
         auto vt_store = [&](int m, unsigned char *tile) __attribute__((always_inline)) {
             const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
             const unsigned char *vn = vb + (long long)nn * 64 * vt * 2;   // uniform
-            TokenRun<TPTV> ch[4];
 #pragma unroll
-            for (int mm = 0; mm < TPTV / 2; ++mm) {
-                // tokens (2mm, 2mm+1) of the run share a word; reversed, the run is written back to front
-                const u32x2 x = REV ? rv[2 * mm + 1] : rv[2 * mm], y = REV ? rv[2 * mm] : rv[2 * mm + 1];
-                const int wd = REV ? TPTV / 2 - 1 - mm : mm;
-                ch[0].w[wd] = pair_lo(x[0], y[0]);
-                ch[1].w[wd] = pair_hi(x[0], y[0]);
-                ch[2].w[wd] = pair_lo(x[1], y[1]);
-                ch[3].w[wd] = pair_hi(x[1], y[1]);
+            for (int u = 0; u < TPTV; ++u) {
+                *reinterpret_cast<u32x2 *>(tile + Cfg::kOffV + pos_of(tv * TPTV + u) * VS + 8 * vq) = rv[u];
+                rv[u] = stream_load(reinterpret_cast<const u32x2 *>(vn + (size_t)(u * vt) * 2 + v_b0));
             }
-#pragma unroll
-            for (int u = 0; u < TPTV; ++u) rv[u] = stream_load(reinterpret_cast<const u32x2 *>(vn + (size_t)(u * vt) * 2 + v_b0));
-            const int p0 = REV ? 64 - (tv + 1) * TPTV : tv * TPTV;   // first tile column of the run
-#pragma unroll
-            for (int a = 0; a < 4; ++a) ch[a].store(tile + Cfg::kOffVT + (4 * vq + a) * TS + p0 * 2);
         };
 
         // Output rows.  The MFMA waves leave the finished O tile of chunk c (bf16, token-major) in the Qs
@@ -286,7 +305,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                         __builtin_nontemporal_store(*reinterpret_cast<const u32x2 *>(tile + Cfg::kOffQ + pos_of(t) * QS + qpos * 2),
                             reinterpret_cast<u32x2 *>(oc + ((size_t)t * vt + qpos) * 2));
                     if constexpr (DV > DK)
-                        __builtin_nontemporal_store(*reinterpret_cast<const u32x2 *>(tile + Cfg::kOffK + pos_of(t) * QS + qpos * 2),
+                        __builtin_nontemporal_store(*reinterpret_cast<const u32x2 *>(tile + Cfg::kOffO2 + pos_of(t) * QS + qpos * 2),
                             reinterpret_cast<u32x2 *>(oc + ((size_t)t * vt + DK + qpos) * 2));
                 }
             }
@@ -318,13 +337,11 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         };
         auto gate_b_half = [&](int m, int half, unsigned char *tile) __attribute__((always_inline)) {
             constexpr int HT = TPT / 2;
-            unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK, *Kt = tile + Cfg::kOffKT;
+            unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK;
             const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
             const unsigned char *qn = qb + (long long)nn * 64 * st * 2;   // uniform
             const unsigned char *kn = kb + (long long)nn * 64 * st * 2;
             unsigned char *Gm = Gb + (long long)m * 64 * gcs * 4;
-            TokenRun<HT> kt[4];
-            u32x2 kprev = {0u, 0u};
             if (m >= 2) flush_o(m - 2, tile, half * HT, half * HT + HT);   // before these rows are rewritten
 #pragma unroll
             for (int uu = 0; uu < HT; ++uu) {
@@ -349,7 +366,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 rk[u] = stream_load(reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0));
                 const u32x2 kq = {pack_bf16(bf16_lo(kw[0]) * ilam[0], bf16_hi(kw[0]) * ilam[1]),
                                   pack_bf16(bf16_lo(kw[1]) * ilam[2], bf16_hi(kw[1]) * ilam[3])};
-                if constexpr (!NOQ) {   // scores and outputs need Q .* Lambda and token-major K / Lambda
+                if constexpr (!NOQ) {   // scores and outputs need Q .* Lambda
                     f32x4 lam;
                     if constexpr (GH) {
                         const float l = __builtin_amdgcn_exp2f(SGN * yv[0]);
@@ -363,17 +380,8 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                     *reinterpret_cast<u32x2 *>(Qs + pos_of(t) * QS + qpos * 2) =
                         u32x2{pack_bf16(bf16_lo(qw[0]) * lam[0], bf16_hi(qw[0]) * lam[1]),
                               pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};
-                    *reinterpret_cast<u32x2 *>(Ks + pos_of(t) * QS + qpos * 2) = kq;
                 }
-                if (uu % 2 == 1) {   // transpose: tokens (u-1, u) of each channel share a word
-                    const u32x2 x = REV ? kq : kprev, y = REV ? kprev : kq;
-                    const int wd = REV ? (HT - 1 - uu) / 2 : uu / 2;
-                    kt[0].w[wd] = pair_lo(x[0], y[0]);
-                    kt[1].w[wd] = pair_hi(x[0], y[0]);
-                    kt[2].w[wd] = pair_lo(x[1], y[1]);
-                    kt[3].w[wd] = pair_hi(x[1], y[1]);
-                }
-                kprev = kq;
+                *reinterpret_cast<u32x2 *>(Ks + pos_of(t) * QS + qpos * 2) = kq;
                 if constexpr (EMIT_G) {
                     f32x4 gout;
 #pragma unroll
@@ -386,9 +394,6 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                     }
                 }
             }
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-                kt[a].store(Kt + (4 * cq + a) * TS + (REV ? 64 - HT - (tq * TPT + half * HT) : tq * TPT + half * HT) * 2);
         };
         auto gate_b_finish = [&](int m, float *gam_m) __attribute__((always_inline)) {
             if (tq == 0) {
@@ -486,7 +491,17 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         // this lane's 8-byte slots in the staged O tile: row lt (+32 mt), columns 32 w + 8 qd + 4 kg ..+3;
         // columns beyond d_k continue in the Ks tile
         const int o_col = w * 32 + 4 * kg;
-        const unsigned o_s0 = (o_col < DK ? Cfg::kOffQ : Cfg::kOffK - DK * 2) + lt * QS + o_col * 2;
+        const unsigned o_s0 = (o_col < DK ? Cfg::kOffQ : Cfg::kOffO2 - DK * 2) + lt * QS + o_col * 2;
+        // Transposing reads: this lane's address inside its group of 16 (row k = (lane % 16) / 4 of the
+        // group's 4 rows, element quad r = lane % 4), for the tokens 8 kg .. 8 kg + 7 of a 16-token step.
+        const int tr_k = (lane & 15) >> 2, tr_r = lane & 3, tr_h = lt >> 4;
+        // V: columns w*32 + 16 tr_h + 4 r .. of the token-major tile
+        const unsigned v_tr0 = Cfg::kOffV + (8 * kg + tr_k) * VS + (w * 32 + 16 * tr_h + 4 * tr_r) * 2;
+        // K / Lambda: channel 32 it + 16 tr_h + 4 r sits at position 8 (r % 2) + 4 (r / 2) of its block of
+        // 16 (the Ks rows keep the stride that suits the 16-byte reads of the score products, so these reads
+        // see some two-way bank conflicts; an order of the k-slots that avoids them needs a second set of
+        // V fragments and measured 2 % slower)
+        const unsigned k_tr0 = Cfg::kOffK + (8 * kg + tr_k) * QS + (16 * tr_h + 8 * (tr_r & 1) + 4 * (tr_r >> 1)) * 2;
 
         f32x16 Sacc[Cfg::NIT], Oacc[2];
         float *Sl = p.S_loc + sbh * DK * (DV * NS) + slice * DV + w * 32 + lt;   // this lane's state column
@@ -556,12 +571,11 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
 
         // part 2 of chunk n: intra-chunk output, O store, state update
         auto mfma_b = [&](int n, const unsigned char *tile, const float *gam_n) __attribute__((always_inline)) {
-            const unsigned char *Kt = tile + Cfg::kOffKT, *Vt = tile + Cfg::kOffVT;
             unsigned char *os = const_cast<unsigned char *>(tile) + o_s0;
             if constexpr (MODE == kDState) decay_state(gam_n);
             bf16x8 vf[4];
 #pragma unroll
-            for (int ks = 0; ks < 4; ++ks) vf[ks] = lds_frag(Vt, (w * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2);
+            for (int ks = 0; ks < 4; ++ks) vf[ks] = lds_frag_tr(tile + v_tr0 + ks * 16 * VS, 4 * VS);
             // O^T += Vt Ps^T over the causal k-range (tokens s < 32 (mt + 1))
 #pragma unroll
             for (int mt = 0; mt < (NOQ ? 0 : 2); ++mt) {
@@ -580,7 +594,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 f32x16 acc = Sacc[it];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
-                    acc = M::run(lds_frag(Kt, (it * 32 + lt) * TS + (ks * 16 + 8 * kg) * 2), vf[ks], acc);
+                    acc = M::run(lds_frag_tr(tile + k_tr0 + ks * 16 * QS + it * 64, 4 * QS), vf[ks], acc);
                 if constexpr (!REV) {
 #pragma unroll
                     for (int qd = 0; qd < 4; ++qd) {

@@ -26,7 +26,8 @@ extern "C" {
 typedef enum {
     ZECO_OK = 0,
     ZECO_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad stride */
-    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix */
+    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix, L % C != 0
+                               * where whole chunks are needed, L < C */
     ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than zeco_gla_local_fwd_workspace() */
     ZECO_ERR_HIP = 4          /* HIP runtime refused a launch / attribute */
 } zeco_status;
@@ -40,8 +41,13 @@ typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
  * in ELEMENTS; the innermost dimension is contiguous.  Strides must be multiples of 8 elements. */
 typedef struct {
     int32_t B, P, H, L;
-    int32_t d_k, d_v, C;       /* supported: C = 64, L % C == 0, d_k and d_v in {64, 128}.  (A sequence is
-                                * padded with tokens that have k = 0 and g = 0: they change no state.) */
+    int32_t d_k, d_v, C;       /* supported: C = 64, d_k and d_v in {64, 128}.  The forward entry points
+                                * (local pass, states, output pass, correction, both decay forms, the fused
+                                * forward without S_save) take any L >= C: when L % C != 0 the FIRST chunk
+                                * of every segment is the short one, L - C*(ceil(L/C) - 1) tokens, the
+                                * others are full (chunking changes rounding, not the result).  The
+                                * backward entry points need L % C == 0 (else ZECO_ERR_UNSUPPORTED; pad the
+                                * sequence with tokens that have k = 0 and g = 0: they change no state). */
     int32_t io_dtype;          /* zeco_dtype of q, k, v, o */
     int32_t g_dtype;           /* zeco_dtype of g */
     float scale;
@@ -120,9 +126,9 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *desc, const void *q, cons
  * gates only (otherwise ZECO_ERR_UNSUPPORTED).  Same conventions as above. ----------------------------- */
 
 /* Local pass: as zeco_gla_local_fwd, with
- *   out  G_chunk [B,T/C,H,d_k] fp32 contiguous: for chunk n of a segment (n = 0 .. L/C-1), the sum of g
- *        from the segment's first token to the last token BEFORE the chunk (log gamma~_[n], zero for the
- *        segment's first chunk)
+ *   out  G_chunk [B,P,N,H,d_k] fp32 contiguous, N = ceil(L/C) (= [B,T/C,H,d_k] when L % C == 0): for chunk
+ *        n of a segment (n = 0 .. N-1), the sum of g from the segment's first token to the last token
+ *        BEFORE the chunk (log gamma~_[n], zero for the segment's first chunk)
  * in place of G_cum.  Uses no workspace (with few (batch, segment, head) streams it is not split further). */
 zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *desc, const void *q, const void *k,
                                            const void *v, const void *g, void *o, float *S_loc,

@@ -13,6 +13,11 @@
 // through to add nothing.  With the decays of a trained GLA layer (e-folding length of tens to
 // hundreds of tokens) that is all but the first few thousand tokens of a long segment.  `dense`
 // switches the test off (measurement of the full-traffic kernel, equality tests).
+//
+// Segment lengths that are no multiple of 64 follow the chunk kernels' convention: the first 64-token
+// block of a segment is the short one, holding the tokens [0, 64 - pad); it is loaded and computed as the
+// window [0, 64) (inside the segment), only its real rows are stored, and block c >= 1 starts at token
+// 64 c - pad.  The last workgroup of a segment may have fewer blocks than the others.
 #include "zeco_device.h"
 #include "zeco_internal.h"
 
@@ -44,7 +49,7 @@ template <int DK, int DV> struct ApplyCfg {
 // blocks are worked through.
 __device__ __forceinline__ int apply_stream_of_workgroup(const ApplyParams &p, int &tb) {
     constexpr int kGroup = 128;
-    const int blocks_per_seg = p.L / p.tokens_per_wg, streams = (p.P - p.p0) * p.B * p.H;
+    const int blocks_per_seg = p.wgs_per_seg, streams = (p.P - p.p0) * p.B * p.H;
     const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
     const int gsz = min(kGroup, streams - grp * kGroup);
     const int j = r % gsz;
@@ -54,6 +59,10 @@ __device__ __forceinline__ int apply_stream_of_workgroup(const ApplyParams &p, i
     // same XCD when H is a multiple of 8
     return grp * kGroup + (((j | 7) < gsz) ? (j & ~7) + ((j - (j >> 3)) & 7) : j);
 }
+
+// First token (inside its segment) of 64-token block c, and the number of rows of it to store.
+__device__ __forceinline__ long long apply_block_start(const ApplyParams &p, int c) { return c ? (long long)c * 64 - p.pad : 0ll; }
+__device__ __forceinline__ int apply_block_rows(const ApplyParams &p, int c) { return c ? 64 : 64 - p.pad; }
 
 // Workgroup-wide AND of `mine` through the four flags in LDS; ends with a barrier.  Calls must be
 // separated by at least one other barrier.
@@ -99,7 +108,7 @@ __device__ __forceinline__ void apply_load_o(const uint16_t *o_blk, long long vt
 template <int DK, int DV>
 __device__ __forceinline__ void apply_block(const bf16x8 (&sf)[ApplyCfg<DK, DV>::NKS], const unsigned char *Qh,
                                             float *Cs, uint16_t *o_blk, long long vt,
-                                            const u32x4 (&ocur)[ApplyCfg<DK, DV>::OITEMS]) {
+                                            const u32x4 (&ocur)[ApplyCfg<DK, DV>::OITEMS], int rows) {
     typedef ApplyCfg<DK, DV> Cfg;
     typedef Mma<Cfg::TILE> M;
     constexpr int TILE = Cfg::TILE, KS = Cfg::KS, QS = Cfg::QS;
@@ -125,7 +134,7 @@ __device__ __forceinline__ void apply_block(const bf16x8 (&sf)[ApplyCfg<DK, DV>:
         const f32x4 c0 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg);
         const f32x4 c1 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg + 4);
         const u32x4 old = ocur[m];
-        __builtin_nontemporal_store(
+        if (t < rows) __builtin_nontemporal_store(
             u32x4{pack_bf16(bf16_lo(old[0]) + c0[0], bf16_hi(old[0]) + c0[1]),
                   pack_bf16(bf16_lo(old[1]) + c0[2], bf16_hi(old[1]) + c0[3]),
                   pack_bf16(bf16_lo(old[2]) + c1[0], bf16_hi(old[2]) + c1[1]),
@@ -150,7 +159,9 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + id / p.B;
-    const long long tok0 = (long long)seg * p.L + (long long)tb * p.tokens_per_wg;
+    const long long tok0 = (long long)seg * p.L;                 // the segment's first token
+    const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block
+    const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
     const uint16_t *qp = (const uint16_t *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
     uint16_t *op = (uint16_t *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
     const long long T = (long long)p.P * p.L;
@@ -160,7 +171,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
 
     // Nothing to add from this workgroup's first token on?
     const bool may_stop = !p.dense;
-    if (may_stop && apply_all(Gc[GH ? 0 : tid % DK] < kVanish, gone)) return;
+    if (may_stop && apply_all(Gc[apply_block_start(p, c0) * gcs + (GH ? 0 : tid % DK)] < kVanish, gone)) return;
 
     bf16x8 sf[Cfg::NKS];
     apply_load_state<DK, DV>(S, sf);
@@ -173,7 +184,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
 #pragma unroll
         for (int m = 0; m < Cfg::ITEMS; ++m) {
             const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
-            const long long tt = (long long)blk * 64 + t;
+            const long long tt = apply_block_start(p, c0 + blk) + t;
             r.q[m] = *reinterpret_cast<const u32x4 *>(qp + tt * p.st + 8 * cg);
             if constexpr (GH) {
                 const float x = Gc[tt * gcs];
@@ -185,11 +196,10 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         }
     };
 
-    const int nblk = p.tokens_per_wg / 64;
     Raw nxt;
     u32x4 onx[Cfg::OITEMS];
     load_raw(0, nxt);
-    apply_load_o<DV>(op, p.vt, onx);
+    apply_load_o<DV>(op + apply_block_start(p, c0) * p.vt, p.vt, onx);
     for (int blk = 0; blk < nblk; ++blk) {
         const Raw cur = nxt;
         u32x4 ocur[Cfg::OITEMS];
@@ -218,9 +228,9 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         }
         const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
         load_raw(nb, nxt);
-        apply_load_o<DV>(op + (long long)nb * 64 * p.vt, p.vt, onx);
+        apply_load_o<DV>(op + apply_block_start(p, c0 + nb) * p.vt, p.vt, onx);
         __syncthreads();   // Qh complete; every thread is done with the staging tile of the last block
-        apply_block<DK, DV>(sf, Qh, Cs, op + (long long)blk * 64 * p.vt, p.vt, ocur);
+        apply_block<DK, DV>(sf, Qh, Cs, op + apply_block_start(p, c0 + blk) * p.vt, p.vt, ocur, apply_block_rows(p, c0 + blk));
     }
 }
 
@@ -248,13 +258,15 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + id / p.B;
-    const long long tok0 = (long long)seg * p.L + (long long)tb * p.tokens_per_wg;
+    const long long tok0 = (long long)seg * p.L;                 // the segment's first token
+    const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block (= chunk)
+    const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
     const long long kb = b * p.sb + tok0 * p.st + h * p.sh;
     const uint16_t *qp = (const uint16_t *)p.q + kb + (long long)(tg * TPT) * p.st + 4 * cq;
     const unsigned char *gp = (const unsigned char *)p.g + (kb + (long long)(tg * TPT) * p.st + 4 * cq) * GB;
     uint16_t *op = (uint16_t *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
-    const long long NC = (long long)p.P * p.L / 64;             // chunks per batch entry
-    const float *Gk = p.G_chunk + ((b * NC + tok0 / 64) * p.H + h) * DK + 4 * cq;
+    const long long NC = (long long)p.P * p.n_chunks;           // chunks per batch entry
+    const float *Gk = p.G_chunk + ((b * NC + (long long)seg * p.n_chunks + c0) * p.H + h) * DK + 4 * cq;
     const long long gks = (long long)p.H * DK;                  // floats between chunks
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
 
@@ -272,13 +284,13 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
     auto load_raw = [&](int blk) {
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
-            qn[u] = *reinterpret_cast<const u32x2 *>(qp + ((long long)blk * 64 + u) * p.st);
-            gn[u] = *reinterpret_cast<const typename GV::raw_t *>(gp + ((long long)blk * 64 + u) * p.st * GB);
+            const long long tt = apply_block_start(p, c0 + blk) + u;
+            qn[u] = *reinterpret_cast<const u32x2 *>(qp + tt * p.st);
+            gn[u] = *reinterpret_cast<const typename GV::raw_t *>(gp + tt * p.st * GB);
         }
     };
-    const int nblk = p.tokens_per_wg / 64;
     load_raw(0);
-    apply_load_o<DV>(op, p.vt, onx);
+    apply_load_o<DV>(op + apply_block_start(p, c0) * p.vt, p.vt, onx);
     for (int blk = 0; blk < nblk; ++blk) {
         const f32x4 pre = pre_n;
         u32x2 qc[TPT];
@@ -297,7 +309,7 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
         *reinterpret_cast<f32x4 *>(tot + tg * DK + 4 * cq) = run;
         const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
         load_raw(nb);
-        apply_load_o<DV>(op + (long long)nb * 64 * p.vt, p.vt, onx);
+        apply_load_o<DV>(op + apply_block_start(p, c0 + nb) * p.vt, p.vt, onx);
         pre_n = *reinterpret_cast<const f32x4 *>(Gk + (long long)nb * gks);
         __syncthreads();   // group sums visible; every thread is done with the staging tile of the last block
         f32x4 base = pre;
@@ -316,7 +328,7 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
                       pack_bf16(bf16_lo(qc[u][1]) * fast_exp(G[2]) * p.scale, bf16_hi(qc[u][1]) * fast_exp(G[3]) * p.scale)};
         }
         __syncthreads();   // Qh complete
-        apply_block<DK, DV>(sf, Qh, Cs, op + (long long)blk * 64 * p.vt, p.vt, ocur);
+        apply_block<DK, DV>(sf, Qh, Cs, op + apply_block_start(p, c0 + blk) * p.vt, p.vt, ocur, apply_block_rows(p, c0 + blk));
     }
 }
 
@@ -334,7 +346,7 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     // workgroup ids round-robin; a stream stays on one XCD (128 is a multiple of 8), and a group's
     // S_init states (8 MiB at d = 128) stay in the L2s while its token blocks are worked through.
     constexpr int kGroup = 128;
-    const int blocks_per_seg = p.L / p.tokens_per_wg, streams = (p.P - p.p0) * p.B * p.H;
+    const int blocks_per_seg = p.wgs_per_seg, streams = (p.P - p.p0) * p.B * p.H;
     const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
     const int gsz = min(kGroup, streams - grp * kGroup);
     const int tb = r / gsz, j = r % gsz;
@@ -345,7 +357,9 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + id / p.B;
-    const long long tok0 = (long long)seg * p.L + (long long)tb * p.tokens_per_wg;
+    const long long tok0 = (long long)seg * p.L;                 // the segment's first token
+    const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block
+    const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
     const float *qp = (const float *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
     float *op = (float *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
     const long long T = (long long)p.P * p.L;
@@ -353,7 +367,7 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     const long long gcs = (long long)p.H * DK;
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
 
-    if (!p.dense && __syncthreads_and(Gc[tid % DK] < kVanish)) return;   // see "Vanished decay"
+    if (!p.dense && __syncthreads_and(Gc[apply_block_start(p, c0) * gcs + tid % DK] < kVanish)) return;   // see "Vanished decay"
 
     f32x4 Sreg[DK / 16];   // B operand: register r of tile it = S[16 it + 4 kg + r][16 w + l16]
 #pragma unroll
@@ -361,11 +375,12 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) Sreg[it][r] = S[(size_t)(16 * it + 4 * kg + r) * DV + 16 * w + l16];
 
-    const int nblk = p.tokens_per_wg / 64;
     for (int blk = 0; blk < nblk; ++blk) {
+        const long long t0 = apply_block_start(p, c0 + blk);
+        const int rows = apply_block_rows(p, c0 + blk);
         for (int e = tid; e < 64 * DK; e += NT) {
             const int t = e / DK, c = e % DK;
-            const long long tt = (long long)blk * 64 + t;
+            const long long tt = t0 + t;
             Qh[t * QS + c] = qp[tt * p.st + c] * fast_exp(Gc[tt * gcs + c]) * p.scale;
         }
         __syncthreads();
@@ -379,14 +394,14 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
                     acc = mma_f32(Qh[(16 * mt + l16) * QS + 16 * it + 4 * kg + r], Sreg[it][r], acc);
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                op[((long long)blk * 64 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] += acc[r];
+                if (16 * mt + 4 * kg + r < rows) op[(t0 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] += acc[r];
         }
         __syncthreads();
     }
 }
 
 template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hipStream_t s) {
-    const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
+    const int grid = (p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
     if (p.gate_per_head)
         hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, true>), dim3(grid), dim3(256), 0, s, p);
     else
@@ -394,7 +409,7 @@ template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hi
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hipStream_t s) {
-    const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
+    const int grid = (p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
     if (p.g_bf16)
         hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateBF16>), dim3(grid), dim3(256), 0, s, p);
     else
@@ -402,7 +417,7 @@ template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hip
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hipStream_t s) {
-    const int grid = (p.P - p.p0) * p.B * p.H * (p.L / p.tokens_per_wg);
+    const int grid = (p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
     hipLaunchKernelGGL((apply_init_f32_kernel<DK, DV>), dim3(grid), dim3(DV * 4), 0, s, p);
     return hipGetLastError();
 }

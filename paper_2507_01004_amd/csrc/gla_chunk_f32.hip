@@ -11,6 +11,11 @@
 // 16*it + 4*kg + r (kg = 0..3) - the inter-chunk product reads S without leaving the registers.
 // This is the accuracy path (relative error <= 1e-4 against the fp64 oracle); the bf16 kernel is
 // the throughput path.
+//
+// A segment length that is no multiple of 64 makes the FIRST chunk the short one: it covers the
+// tokens [0, r), r = L - 64 (N - 1), is loaded as the window [0, 64) (inside the segment, L >= 64)
+// with g, k, v of the rows >= r taken as zero - such rows leave the state, the decay and the other
+// rows' outputs untouched - and stores only its first r rows; chunk n >= 1 starts at token r + 64 (n - 1).
 #include "zeco_device.h"
 #include "zeco_internal.h"
 
@@ -74,21 +79,23 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
     double seg_prefix = 0.0;                     // log decay accumulated over previous chunks
 
     for (int n = 0; n < p.n_chunks; ++n) {
-        const long long t0 = (long long)n * 64;
+        const long long t0 = n ? (long long)n * 64 - p.pad : 0;
+        const int rows = n ? 64 : 64 - p.pad;    // real tokens of this chunk
         // ---- gate pass: inclusive cumulative sum of g over the chunk, per channel -------------
         float cs[Cfg::kTPT];
         {
             float run = 0.f;
 #pragma unroll
             for (int u = 0; u < Cfg::kTPT; ++u) {
-                run += g[(t0 + tg * Cfg::kTPT + u) * p.st + gc];
+                const int t = tg * Cfg::kTPT + u;
+                run += t < rows ? g[(t0 + t) * p.st + gc] : 0.f;
                 cs[u] = run;
             }
             tot[tg * DK + gc] = run;
         }
         for (int e = tid; e < 64 * DV; e += Cfg::kThreads) {
             const int t = e / DV, j = e % DV;
-            Vs[t * Cfg::kVS + j] = v[(t0 + t) * p.vt + j];
+            Vs[t * Cfg::kVS + j] = t < rows ? v[(t0 + t) * p.vt + j] : 0.f;
         }
         __syncthreads();
         float pre = 0.f, total = 0.f;
@@ -102,11 +109,11 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
         for (int u = 0; u < Cfg::kTPT; ++u) {
             const int t = tg * Cfg::kTPT + u;
             const float c = pre + cs[u];
-            const float qv = q[(t0 + t) * p.st + gc], kv = k[(t0 + t) * p.st + gc];
+            const float qv = q[(t0 + t) * p.st + gc], kv = t < rows ? k[(t0 + t) * p.st + gc] : 0.f;
             Qs[t * Cfg::kQS + gc] = qv * fast_exp(c) * p.scale;
             Ks[t * Cfg::kQS + gc] = kv * fast_exp(-c);
             Kt[t * Cfg::kKT + gc] = kv * fast_exp(total - c);
-            Gc[(t0 + t) * gcs + gc] = (float)(seg_prefix + (double)c);
+            if (t < rows) Gc[(t0 + t) * gcs + gc] = (float)(seg_prefix + (double)c);
         }
         if (tg == 0) gam[gc] = fast_exp(total);
         seg_prefix += (double)total;
@@ -157,7 +164,7 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                o[(t0 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] = Oacc[mt][r];
+                if (16 * mt + 4 * kg + r < rows) o[(t0 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] = Oacc[mt][r];
         }
 
         // ---- state update S <- gamma .* S + (K .* Gamma)^T V -------------------------------------

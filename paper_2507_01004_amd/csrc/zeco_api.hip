@@ -9,15 +9,15 @@ namespace {
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool dim_ok(int d) { return d == 64 || d == 128; }
 
-// ZECO_OK when the descriptor is well formed and supported.
-zeco_status check_desc(const zeco_gla_desc *d) {
+// ZECO_OK when the descriptor is well formed and supported.  `any_length`: the entry point takes segment
+// lengths that are no multiple of the chunk size (the forward entry points do, from 64 tokens on).
+zeco_status check_desc(const zeco_gla_desc *d, bool any_length = false) {
     if (!d) return ZECO_ERR_INVALID_ARG;
     if (d->B <= 0 || d->P <= 0 || d->H <= 0 || d->L <= 0 || d->d_k <= 0 || d->d_v <= 0 || d->C <= 0)
         return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_F32 && d->io_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
     if (d->g_dtype != ZECO_F32 && d->g_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
     if (!(d->scale == d->scale)) return ZECO_ERR_INVALID_ARG;
-    if (d->L % d->C != 0) return ZECO_ERR_INVALID_ARG;
     if ((int64_t)d->P * d->L > (int64_t)1 << 40) return ZECO_ERR_INVALID_ARG;
     const int64_t s[6] = {d->stride_b, d->stride_t, d->stride_h, d->vstride_b, d->vstride_t, d->vstride_h};
     for (int i = 0; i < 6; ++i)
@@ -26,6 +26,7 @@ zeco_status check_desc(const zeco_gla_desc *d) {
     if (d->stride_t < d->d_k || d->vstride_t < d->d_v) return ZECO_ERR_INVALID_ARG;
     if ((int64_t)d->B * d->P * d->H > (int64_t)1 << 24) return ZECO_ERR_INVALID_ARG;
     if (d->C != 64 || !dim_ok(d->d_k) || !dim_ok(d->d_v)) return ZECO_ERR_UNSUPPORTED;
+    if (d->L % d->C != 0 && (!any_length || d->L < d->C)) return ZECO_ERR_UNSUPPORTED;
     if (d->io_dtype == ZECO_F32 && d->g_dtype != ZECO_F32) return ZECO_ERR_UNSUPPORTED;
     if (d->g_per_head != 0 && d->g_per_head != 1) return ZECO_ERR_INVALID_ARG;
     if (d->g_per_head && (d->io_dtype != ZECO_BF16 || d->g_dtype != ZECO_F32)) return ZECO_ERR_UNSUPPORTED;
@@ -38,6 +39,13 @@ int gate_mode(const zeco_gla_desc *d) {
 }
 
 zeco_status from_hip(hipError_t e) { return e == hipSuccess ? ZECO_OK : ZECO_ERR_HIP; }
+
+int chunks_of(int L) { return (L + 63) / 64; }
+
+// Segment length of a chunk-kernel launch: chunks, and how far the first one falls short of 64 tokens.
+void set_length(zeco::ChunkParams &p, int L) {
+    p.L = L; p.n_chunks = chunks_of(L); p.pad = 64 * p.n_chunks - L;
+}
 
 }  // namespace
 
@@ -74,7 +82,7 @@ static SubLayout sub_layout(const zeco_gla_desc *d, int S) {
 }
 
 size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc) != ZECO_OK) return 0;
+    if (check_desc(desc, true) != ZECO_OK) return 0;
     const int S = subsegments(desc);
     return S > 1 ? sub_layout(desc, S).total * sizeof(float) : 0;
 }
@@ -82,7 +90,7 @@ size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc) {
 zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
                                const void *g, void *o, float *S_loc, float *G_cum, float *G_tot,
                                void *workspace, size_t workspace_bytes, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!q || !k || !v || !g || !o || !S_loc || !G_cum || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
@@ -97,8 +105,8 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     zeco::ChunkParams p;
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o;
     p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot; p.S_init = nullptr;
-    p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
-    p.n_chunks = d->L / d->C;
+    p.B = d->B; p.P = d->P; p.H = d->H;
+    set_length(p, d->L);
     p.scale = d->scale; p.kscale = 1.f;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
@@ -115,7 +123,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     const SubLayout w = sub_layout(d, S);
     float *ws = static_cast<float *>(workspace);
     float *Ssub = ws + w.off_Ssub, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot, *Gpre = ws + w.off_Gpre;
-    p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
+    p.P = d->P * S; set_length(p, d->L / S);
     p.S_loc = Ssub; p.G_tot = Gtot;
     hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
@@ -135,8 +143,8 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
 static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
     p.q = p.k = p.v = p.g = nullptr; p.o = nullptr;
     p.S_loc = p.G_cum = p.G_tot = nullptr; p.S_init = nullptr; p.S_save = nullptr; p.save_every = 0;
-    p.B = d->B; p.P = d->P; p.H = d->H; p.L = d->L;
-    p.n_chunks = d->L / d->C;
+    p.B = d->B; p.P = d->P; p.H = d->H;
+    set_length(p, d->L);
     p.scale = d->scale; p.kscale = 1.f;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
@@ -149,9 +157,15 @@ static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
 static void fill_apply_params(zeco::ApplyParams &p, const zeco_gla_desc *d, int P, int L) {
     p.B = d->B; p.P = P; p.H = d->H; p.L = L;
     p.p0 = 0; p.gate_per_head = d->g_per_head; p.dense = 0;
-    int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L
-    while (tpw > 64 && L % tpw != 0) tpw >>= 1;
+    p.n_chunks = chunks_of(L); p.pad = 64 * p.n_chunks - L;
+    int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L, or, when
+    if (p.pad) {                          // L is no multiple of 64, not above it (the last workgroup of a
+        while (tpw > 64 && tpw > L) tpw >>= 1;   // segment then has fewer blocks)
+    } else {
+        while (tpw > 64 && L % tpw != 0) tpw >>= 1;
+    }
     p.tokens_per_wg = tpw;
+    p.wgs_per_seg = (64 * p.n_chunks + tpw - 1) / tpw;
     p.scale = d->scale;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
@@ -159,7 +173,7 @@ static void fill_apply_params(zeco::ApplyParams &p, const zeco_gla_desc *d, int 
 
 zeco_status zeco_gla_local_state(const zeco_gla_desc *d, const void *k, const void *v, const void *g,
                                  float *S_loc, float *G_tot, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!k || !v || !g || !S_loc || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_loc) || !aligned16(G_tot))
@@ -174,7 +188,7 @@ zeco_status zeco_gla_local_state(const zeco_gla_desc *d, const void *k, const vo
 
 zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
                                     const void *g, const float *S_init, void *o, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!q || !k || !v || !g || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_init) ||
@@ -199,19 +213,20 @@ static int fused_pieces(const zeco_gla_desc *d) {
 static int bwd_pieces(const zeco_gla_desc *d);
 
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     const size_t n = (size_t)desc->P * fused_pieces(desc) * desc->B * desc->H;
     // cumulative decay of the CORRECT schedule: per chunk and channel, or per token with per-head gates
     const size_t decay = desc->g_per_head ? (size_t)desc->B * desc->P * desc->L * desc->H
-                                          : (size_t)desc->B * desc->P * (desc->L / desc->C) * desc->H * desc->d_k;
+                                          : (size_t)desc->B * desc->P * chunks_of(desc->L) * desc->H * desc->d_k;
     return (2 * n * desc->d_k * desc->d_v + n * desc->d_k + decay) * sizeof(float);
 }
 
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
                                const void *g, const float *S0, void *o, float *S_last, float *S_save,
                                int32_t schedule, void *workspace, size_t workspace_bytes, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (S_save && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // the backward takes whole chunks only
     if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
         !aligned16(S0) || !aligned16(S_last) || !aligned16(S_save) || !aligned16(workspace))
@@ -230,7 +245,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
 
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
-    p.P = d->P * S; p.L = d->L / S; p.n_chunks = p.L / d->C;
+    p.P = d->P * S; set_length(p, d->L / S);   // (a length with a short chunk is not cut: S = 1)
 
     if (schedule == ZECO_SCHEDULE_CORRECT || (schedule == ZECO_SCHEDULE_AUTO && can_correct && p.L >= 4096)) {
         // local pass of every piece from the zero state, scan, correction of the pieces' heads
@@ -309,7 +324,7 @@ static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const 
     const int gb = gate_mode(d);
     zeco::ChunkParams c;
     fill_chunk_params(c, d);
-    c.P = P; c.L = L; c.n_chunks = L / d->C;
+    c.P = P; set_length(c, L);
     c.q = k; c.k = q; c.v = dO; c.g = g; c.o = dv; c.S_init = dS_in; c.scale = 1.f; c.kscale = d->scale;
     hipError_t e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, gb, 4, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
@@ -419,7 +434,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
 
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
-    p.P = P; p.L = L; p.n_chunks = L / d->C;
+    p.P = P; set_length(p, L);
     zeco::ScanParams sp;
     sp.P = P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
     sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
@@ -470,7 +485,7 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
 
 zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const float *G_cum,
                                   const float *S_init, void *o, int32_t flags, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!q || !G_cum || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(G_cum) || !aligned16(S_init) || !aligned16(o))
@@ -491,7 +506,7 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
 zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q, const void *k,
                                            const void *v, const void *g, void *o, float *S_loc,
                                            float *G_chunk, float *G_tot, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!q || !k || !v || !g || !o || !S_loc || !G_chunk || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
@@ -508,7 +523,7 @@ zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q
 zeco_status zeco_apply_init_state_chunk_decay(const zeco_gla_desc *d, const void *q, const void *g,
                                               const float *G_chunk, const float *S_init, void *o,
                                               int32_t flags, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!q || !g || !G_chunk || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(g) || !aligned16(G_chunk) || !aligned16(S_init) || !aligned16(o))

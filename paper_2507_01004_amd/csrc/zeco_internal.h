@@ -15,11 +15,12 @@ struct ChunkParams {
     float *S_loc, *G_cum, *G_tot;
     const float *S_init;       // [P,B,H,d_k,d_v] initial states (modes that start from a given state)
     const float *G_off = nullptr;   // [P,B,H,d_k] log decay preceding each segment (mode 5 only)
-    float *G_chunk = nullptr;       // [B,T/64,H,d_k] log decay from the segment start to each chunk's start (mode 6 only)
+    float *G_chunk = nullptr;       // [B,P,n_chunks,H,d_k] log decay from the segment start to each chunk's start (mode 6 only)
     float *S_save = nullptr;   // output pass: states entering every save_every-th chunk,
     int save_every = 0;        //   [P * n_chunks / save_every, B, H, d_k, d_v]
     int B, P, H, L;
-    int n_chunks;              // L / 64
+    int n_chunks;              // ceil(L / 64)
+    int pad = 0;               // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens (forward modes only)
     float scale;
     float kscale;              // backward modes: multiplier carried by the operand in the k role
     long long sb, st, sh;      // q/k/g element strides
@@ -35,14 +36,16 @@ extern unsigned long long *g_phase_dbg;
 struct ApplyParams {
     const void *q;
     const float *G_cum = nullptr;    // [B,T,H,d_k] per-token cumulative log decay, or
-    const float *G_chunk = nullptr;  // [B,T/64,H,d_k] per-chunk one, together with
+    const float *G_chunk = nullptr;  // [B,P,n_chunks,H,d_k] per-chunk one, together with
     const void *g = nullptr;         //   the log decays themselves (layout of q)
     int g_bf16 = 0;                  //   stored as bf16 (1) or fp32 (0)
     const float *S_init;
     void *o;
     int B, P, H, L;
     int p0;                    // first segment to correct
-    int tokens_per_wg;         // multiple of 64 dividing L
+    int tokens_per_wg;         // multiple of 64
+    int n_chunks, pad;         // 64-token blocks per segment, ceil(L / 64), and 64 n_chunks - L: the first block is the short one
+    int wgs_per_seg;           // workgroups per segment, ceil(64 n_chunks / tokens_per_wg)
     int gate_per_head = 0;     // 1: G_cum [B,T,H] (bf16 kernel only)
     int dense = 0;             // 1: stream every token, also where exp(G_cum) has vanished
     float scale;

@@ -235,7 +235,7 @@ def _apply_flags(first_segment_is_zero, dense):
 
 def gla_local_fwd_chunk_decay(q, k, v, g, P, scale=1.0, C=64, out=None):
     """zeco_gla_local_fwd_chunk_decay: the local pass with the cumulative log decay kept per chunk.
-    Returns (o, S_loc, G_chunk [B,T/C,H,d_k], G_tot)."""
+    Returns (o, S_loc, G_chunk [B, P*ceil(L/C), H, d_k], G_tot)."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
@@ -245,7 +245,7 @@ def gla_local_fwd_chunk_decay(q, k, v, g, P, scale=1.0, C=64, out=None):
     if out is None:
         o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
         S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=q.device)
-        G_chunk = torch.empty(B, T // C, H, dk, dtype=torch.float32, device=q.device)
+        G_chunk = torch.empty(B, P * -(-(T // P) // C), H, dk, dtype=torch.float32, device=q.device)
         G_tot = torch.empty(P, B, H, dk, dtype=torch.float32, device=q.device)
     else:
         o, S_loc, G_chunk, G_tot = out

@@ -58,7 +58,7 @@ def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
 
 @pytest.mark.parametrize("kw,expect", [
     (dict(B=0), zeco.ZECO_ERR_INVALID_ARG),
-    (dict(L=100), zeco.ZECO_ERR_INVALID_ARG),          # L % C != 0
+    (dict(L=40), zeco.ZECO_ERR_UNSUPPORTED),           # shorter than a chunk
     (dict(stride_t=100), zeco.ZECO_ERR_INVALID_ARG),   # stride not a multiple of 8
     (dict(stride_h=64), zeco.ZECO_ERR_INVALID_ARG),    # heads overlap
     (dict(io_dtype=7), zeco.ZECO_ERR_INVALID_ARG),
@@ -73,6 +73,21 @@ def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
 def test_local_fwd_rejects_bad_descriptors(L, kw, expect):
     assert call_local(L, good_desc(**kw)) == expect
     assert L.zeco_apply_init_state(ctypes.byref(good_desc(**kw)), FAKE, FAKE, FAKE, FAKE, 1, None) == expect
+
+
+def test_segment_lengths_that_are_no_multiple_of_the_chunk(L):
+    """The forward entry points take them (validation gets past the descriptor: the next check, a null
+    pointer, answers), the backward ones and a forward that saves states for the backward do not."""
+    d, ref = good_desc(L=100), ctypes.byref
+    assert call_local(L, d, q=None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_apply_init_state(ref(d), None, FAKE, FAKE, FAKE, 1, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_local_fwd_chunk_decay(ref(d), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_fused_fwd_workspace(ref(d)) > 0
+    assert L.zeco_gla_fused_bwd_workspace(ref(d)) == 0 and L.zeco_gla_saved_states_bytes(ref(d)) == 0
+    fwd = [FAKE] * 4 + [None, FAKE, None]
+    assert L.zeco_gla_fused_fwd(ref(d), *fwd, FAKE, 0, FAKE, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED   # S_save
+    fused = [FAKE] * 5 + [None, None, None] + [FAKE] * 4 + [None, FAKE]
+    assert L.zeco_gla_fused_bwd(ref(d), *fused, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED
 
 
 def test_apply_init_state_rejects_unknown_flags(L):
@@ -114,7 +129,7 @@ def test_backward_entry_points_reject_bad_arguments(L):
     ref = ctypes.byref
     assert L.zeco_gla_bwd_dstate(ref(d), None, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_bwd_dstate(ref(f32), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED
-    assert L.zeco_gla_bwd_dstate(ref(good_desc(L=100)), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_bwd_dstate(ref(good_desc(L=100)), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED   # whole chunks only
     args = [FAKE] * 12
     assert L.zeco_gla_bwd_from_state(ref(f32), *args, None) == zeco.ZECO_ERR_UNSUPPORTED
     args[7] = None                                         # dS_in missing

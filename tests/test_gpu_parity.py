@@ -242,7 +242,7 @@ def test_strided_views_and_determinism():
 def test_errors_surface_as_exceptions():
     q = torch.zeros(1, 96, 1, 64, device="cuda")
     with pytest.raises(zeco.ZecoError):
-        zeco.gla_local_fwd(q, q, q, q, 1)            # L = 96 is not a multiple of the chunk length
+        zeco.gla_local_fwd(q, q, q, q, 2)            # L = 48 is shorter than a chunk
 
 
 BF16_CASES = [c for c in CASES if c[7] == "bf16"]

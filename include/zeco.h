@@ -26,8 +26,8 @@ extern "C" {
 typedef enum {
     ZECO_OK = 0,
     ZECO_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad stride */
-    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix, L % C != 0
-                               * where whole chunks are needed, L < C */
+    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix, L < C,
+                               * L % C != 0 with saved states */
     ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than zeco_gla_local_fwd_workspace() */
     ZECO_ERR_HIP = 4          /* HIP runtime refused a launch / attribute */
 } zeco_status;
@@ -41,13 +41,12 @@ typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
  * in ELEMENTS; the innermost dimension is contiguous.  Strides must be multiples of 8 elements. */
 typedef struct {
     int32_t B, P, H, L;
-    int32_t d_k, d_v, C;       /* supported: C = 64, d_k and d_v in {64, 128}.  The forward entry points
-                                * (local pass, states, output pass, correction, both decay forms, the fused
-                                * forward without S_save) take any L >= C: when L % C != 0 the FIRST chunk
-                                * of every segment is the short one, L - C*(ceil(L/C) - 1) tokens, the
-                                * others are full (chunking changes rounding, not the result).  The
-                                * backward entry points need L % C == 0 (else ZECO_ERR_UNSUPPORTED; pad the
-                                * sequence with tokens that have k = 0 and g = 0: they change no state). */
+    int32_t d_k, d_v, C;       /* supported: C = 64, d_k and d_v in {64, 128}, any L >= C.  When L % C != 0
+                                * one chunk of every segment is short, L - C*(ceil(L/C) - 1) tokens (the
+                                * first one in the passes that walk a segment forwards, the last one in
+                                * those that walk it backwards; chunking changes rounding, not the result).
+                                * Only the states saved by the forward for the backward (S_save, S_saved)
+                                * need L % C == 0, else ZECO_ERR_UNSUPPORTED. */
     int32_t io_dtype;          /* zeco_dtype of q, k, v, o */
     int32_t g_dtype;           /* zeco_dtype of g */
     float scale;

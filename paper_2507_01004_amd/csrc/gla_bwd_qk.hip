@@ -119,6 +119,17 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     const int N = p.n_chunks;
     auto chunk_of = [&](int m) { return REV ? N - 1 - m : m; };
     auto pos_of = [](int t) { return REV ? 63 - t : t; };
+    // When L is no multiple of 64 the chunk processed FIRST is the short one, 64 - pad tokens: the segment's
+    // first tokens in the dQ pass, its last ones in the dK pass.  It is loaded as a full window inside the
+    // segment, [0, 64) or [L - 64, L); the gated operand, the log decays and the dG terms of the window's
+    // surplus rows are taken as zero - they then touch no state, no decay and no other row - and their
+    // gradient rows are not stored.
+    const int pad = p.pad;
+    auto cstart = [&](int c) {
+        if constexpr (REV) return (long long)c * 64 - (c == N - 1 ? pad : 0);
+        else return c ? (long long)c * 64 - pad : 0ll;
+    };
+    auto dead = [&](int t) { return REV ? t < pad : t >= 64 - pad; };
 
     // workgroup -> stream, dealt so that consecutive streams land on different XCDs
     const size_t sbh = blockIdx.x;                  // (seg * B + b) * H + h
@@ -189,7 +200,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     u32x2 rq[EMIT ? TPT : 1];   // EMIT: q of the chunk worked on next (otherwise q is fetched late, for dG only)
     typename GV::raw_t rg[TPT];
     {
-        const long long c0 = (long long)chunk_of(0) * 64;
+        const long long c0 = cstart(chunk_of(0));
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
             if constexpr (EMIT) rq[u] = *reinterpret_cast<const u32x2 *>(z2b + ((c0 + tq * TPT + u) * st + 4 * cq) * 2);
@@ -217,11 +228,15 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 
     // first half: the finished chunk's gradient rows go to HBM, and the dG terms are formed from the fp32
     // result tile in Fs; dQ stores them, dK starts the reverse sums
-    auto dg_first = [&](long long tc) __attribute__((always_inline)) {
+    auto dg_first = [&](long long tc, bool first) __attribute__((always_inline)) {
         float *row = dgb + (tc + tq * TPT) * gcs + (GH ? 0 : 4 * cq);
         f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int u = TPT - 1; u >= 0; --u) {
+            if (first && dead(tq * TPT + u)) {   // surplus row: nothing stored, no dG term
+                if constexpr (REV) dterm[u] = run;
+                continue;
+            }
             const f32x4 val = *reinterpret_cast<const f32x4 *>(Fs + pos_of(tq * TPT + u) * FS + 16 * cq);
             // the gradient itself: 32 lanes write one contiguous row (the accumulator layout of the
             // products would give 32-byte pieces)
@@ -257,7 +272,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
     };
     // second half (dK, after a barrier): add the later waves and the later chunks, store dG
-    auto dg_second = [&](long long tc) __attribute__((always_inline)) {
+    auto dg_second = [&](long long tc, bool first) __attribute__((always_inline)) {
         float *row = dgb + (tc + tq * TPT) * gcs + (GH ? 0 : 4 * cq);
         f32x4 later = carry, total = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -274,6 +289,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
+            if (first && dead(tq * TPT + u)) continue;
             f32x4 o;
 #pragma unroll
             for (int a = 0; a < 4; ++a) o[a] = dterm[u][a] + later[a];
@@ -289,10 +305,11 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     };
 
     for (int n = 0; n < N; ++n) {
-        const long long t0 = (long long)chunk_of(n) * 64;                          // this chunk
-        const long long t1 = (long long)chunk_of((n + 1 < N) ? n + 1 : n) * 64;    // chunk fetched meanwhile
-        const long long tp = (long long)chunk_of((n > 0) ? n - 1 : 0) * 64;        // chunk finished last
-        if (n > 0) dg_first(tp);
+        const long long t0 = cstart(chunk_of(n));                          // this chunk
+        const long long t1 = cstart(chunk_of((n + 1 < N) ? n + 1 : n));    // chunk fetched meanwhile
+        const long long tp = cstart(chunk_of((n > 0) ? n - 1 : 0));        // chunk finished last
+        const bool first = n == 0;                                         // the short chunk, if there is one
+        if (n > 0) dg_first(tp, n == 1);
 
         // ---- gate pass, part 1: per-thread cumulative sums of g; X, Y, Y^T -> LDS -----------------
         f32x4 cs[TPT];
@@ -301,7 +318,8 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
-                const f32x4 gv = GV::get(rg[u]);
+                f32x4 gv = GV::get(rg[u]);
+                if (first && dead(tq * TPT + u)) gv = f32x4{0.f, 0.f, 0.f, 0.f};
                 rg[u] = *reinterpret_cast<const typename GV::raw_t *>(gb + ((t1 + tq * TPT + u) * gst + (GH ? 0 : 4 * cq)) * GB);
 #pragma unroll
                 for (int a = 0; a < 4; ++a) run[a] += gv[a];
@@ -361,7 +379,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
         __syncthreads();
         if constexpr (REV) {
-            if (n > 0) dg_second(tp);
+            if (n > 0) dg_second(tp, n == 1);
         }
 
         // ---- gate pass, part 2: stitch waves; Z~^T and the factor tile -> LDS ----------------------
@@ -403,13 +421,15 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                         ef[a] = __builtin_amdgcn_exp2f(-SZ * y);
                     }
                 }
-                const u32x2 zw = rz[u];
+                u32x2 zw = rz[u];
+                if (first && dead(t)) zw = u32x2{0u, 0u};
                 rz[u] = *reinterpret_cast<const u32x2 *>(zb + ((t1 + t) * st + 4 * cq) * 2);
                 const u32x2 zq = {pack_bf16(bf16_lo(zw[0]) * ez[0], bf16_hi(zw[0]) * ez[1]),
                                   pack_bf16(bf16_lo(zw[1]) * ez[2], bf16_hi(zw[1]) * ez[3])};
                 *reinterpret_cast<f32x4 *>(Fs + pos_of(t) * FS + 16 * cq) = ef;
                 if constexpr (EMIT) {   // (Q .* exp(G))^T: F = Lambda here, times the earlier chunks' decay
-                    const u32x2 qw = rq[u];
+                    u32x2 qw = rq[u];
+                    if (first && dead(t)) qw = u32x2{0u, 0u};
                     rq[u] = *reinterpret_cast<const u32x2 *>(z2b + ((t1 + t) * st + 4 * cq) * 2);
                     rz2[u] = qw;   // kept for this chunk's dG terms
                     const u32x2 qh = {pack_bf16(bf16_lo(qw[0]) * ef[0] * epre[0], bf16_hi(qw[0]) * ef[1] * epre[1]),
@@ -564,11 +584,11 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
     }
     // dG terms of the last chunk processed
-    const long long tl = (long long)chunk_of(N - 1) * 64;
-    dg_first(tl);
+    const long long tl = cstart(chunk_of(N - 1));
+    dg_first(tl, N == 1);
     if constexpr (REV) {
         __syncthreads();
-        dg_second(tl);
+        dg_second(tl, N == 1);
     }
 }
 

@@ -178,12 +178,17 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known uniform
     const int N = p.n_chunks;
     auto chunk_of = [&](int m) { return REV ? N - 1 - m : m; };   // m-th chunk in processing order
-    // First token of chunk n.  When L is no multiple of 64 (forward modes only) the FIRST chunk is the short
-    // one: it holds the tokens [0, rows0), is loaded as the window [0, 64) - inside the segment - with g, k, v
-    // of the rows beyond taken as zero, which leaves state, decay and the real rows' outputs untouched, and
-    // stores only its real rows; the chunks after it are full.
-    auto cstart = [&](int n) { return n ? (long long)n * 64 - p.pad : 0ll; };
-    const int rows0 = 64 - p.pad;
+    // First token of chunk n.  When L is no multiple of 64 the chunk processed FIRST is the short one,
+    // 64 - pad tokens: the segment's first tokens in the forward modes, its last ones in the reverse modes.
+    // It is loaded as a full window inside the segment - [0, 64), or [L - 64, L) - with g, k, v of the
+    // window's surplus rows (the far end, or the near end) taken as zero, which leaves state, decay and the
+    // real rows' outputs untouched, and stores only its real rows; all other chunks are full.
+    auto cstart = [&](int n) {
+        if constexpr (REV) return (long long)n * 64 - (n == N - 1 ? p.pad : 0);
+        else return n ? (long long)n * 64 - p.pad : 0ll;
+    };
+    const int pad = p.pad;
+    auto dead = [&](int t) { return REV ? t < pad : t >= 64 - pad; };   // surplus row of the short chunk
     auto pos_of = [](int t) { return REV ? 63 - t : t; };         // tile row of token t of a chunk
 
     // Workgroup -> (stream, slice).  Workgroup ids are dealt round-robin to the 8 XCDs, so sibling
@@ -258,15 +263,15 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         f32x4 excl = {0.f, 0.f, 0.f, 0.f};      // sum over the wave's earlier token groups
 
         // part 1 of chunk m: per-thread cumulative sums and gate sums
-        // (lim: number of real rows of the chunk; the literal 64 of the loop's calls folds the masks away)
-        auto gate_a = [&](int m, int lim) __attribute__((always_inline)) {
+        // (first: the short chunk; the literal `false` of the loop's calls folds the masks away)
+        auto gate_a = [&](int m, bool first) __attribute__((always_inline)) {
             const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
             const unsigned char *gn = gb + cstart(nn) * gst * GB;   // uniform
             f32x4 run = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
                 f32x4 gv = GV::get(rg[u]);
-                if (lim < 64 && tq * TPT + u >= lim) gv = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (first && dead(tq * TPT + u)) gv = f32x4{0.f, 0.f, 0.f, 0.f};
                 rg[u] = stream_load(reinterpret_cast<const typename GV::raw_t *>(gn + (size_t)(u * gst) * GB + g_in_b0));
 #pragma unroll
                 for (int a = 0; a < 4; ++a) run[a] += gv[a];
@@ -286,12 +291,12 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             if (gl == GW - 1) *reinterpret_cast<f32x4 *>(wtot + gw * DK + 4 * cq) = inc;
         };
         // V of chunk m -> tile buffer, token-major as it comes (the matrix waves read it transposed)
-        auto vt_store = [&](int m, unsigned char *tile, int lim) __attribute__((always_inline)) {
+        auto vt_store = [&](int m, unsigned char *tile, bool first) __attribute__((always_inline)) {
             const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
             const unsigned char *vn = vb + cstart(nn) * vt * 2;   // uniform
 #pragma unroll
             for (int u = 0; u < TPTV; ++u) {
-                if (lim < 64 && tv * TPTV + u >= lim) rv[u] = u32x2{0u, 0u};
+                if (first && dead(tv * TPTV + u)) rv[u] = u32x2{0u, 0u};
                 *reinterpret_cast<u32x2 *>(tile + Cfg::kOffV + pos_of(tv * TPTV + u) * VS + 8 * vq) = rv[u];
                 rv[u] = stream_load(reinterpret_cast<const u32x2 *>(vn + (size_t)(u * vt) * 2 + v_b0));
             }
@@ -309,11 +314,10 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         auto flush_o = [&](int c, unsigned char *tile, int u0, int u1) __attribute__((always_inline)) {
             if constexpr (!NOQ) {
                 unsigned char *oc = og + cstart(chunk_of(c)) * vt * 2;   // uniform
-                const int lim = c ? 64 : rows0;
 #pragma unroll
                 for (int u = u0; u < u1; ++u) {
                     const int t = tq * TPT + u;
-                    if (t >= lim) continue;
+                    if (c == 0 && dead(t)) continue;
                     if (qpos < DV)
                         __builtin_nontemporal_store(*reinterpret_cast<const u32x2 *>(tile + Cfg::kOffQ + pos_of(t) * QS + qpos * 2),
                             reinterpret_cast<u32x2 *>(oc + ((size_t)t * vt + qpos) * 2));
@@ -348,7 +352,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 gbase[a] = seg_hi[a] + (pre[a] + seg_lo[a]);
             }
         };
-        auto gate_b_half = [&](int m, int half, unsigned char *tile, int lim) __attribute__((always_inline)) {
+        auto gate_b_half = [&](int m, int half, unsigned char *tile, bool first) __attribute__((always_inline)) {
             constexpr int HT = TPT / 2;
             unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK;
             const int nn = chunk_of((m + 1 < N) ? m + 1 : N - 1);
@@ -376,7 +380,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                     }
                 }
                 u32x2 kw = rk[u];
-                if (lim < 64 && t >= lim) kw = u32x2{0u, 0u};
+                if (first && dead(t)) kw = u32x2{0u, 0u};
                 rk[u] = stream_load(reinterpret_cast<const u32x2 *>(kn + (size_t)(u * st) * 2 + q_b0));
                 const u32x2 kq = {pack_bf16(bf16_lo(kw[0]) * ilam[0], bf16_hi(kw[0]) * ilam[1]),
                                   pack_bf16(bf16_lo(kw[1]) * ilam[2], bf16_hi(kw[1]) * ilam[3])};
@@ -396,7 +400,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                               pack_bf16(bf16_lo(qw[1]) * lam[2], bf16_hi(qw[1]) * lam[3])};
                 }
                 *reinterpret_cast<u32x2 *>(Ks + pos_of(t) * QS + qpos * 2) = kq;
-                if constexpr (EMIT_G) if (lim == 64 || t < lim) {
+                if constexpr (EMIT_G) if (!(first && dead(t))) {
                     f32x4 gout;
 #pragma unroll
                     for (int a = 0; a < 4; ++a) gout[a] = gbase[a] + cs[u][a];
@@ -457,39 +461,39 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         // so that both phases carry a similar amount of gate work.  The loop bodies are free of
         // branches (a conditional around the passes would force the reloaded registers through
         // merge copies, and with them a wait for every load in flight); the tail is peeled.
-        gate_a(0, rows0);
-        vt_store(0, lds, rows0);
+        gate_a(0, true);
+        vt_store(0, lds, true);
         __syncthreads();
         gate_b_setup();
-        gate_b_half(0, 0, lds, rows0);
-        gate_b_half(0, 1, lds, rows0);
+        gate_b_half(0, 0, lds, true);
+        gate_b_half(0, 1, lds, true);
         gate_b_finish(0, gam);
-        if (N > 1) gate_a(1, 64);
+        if (N > 1) gate_a(1, false);
         __syncthreads();
         int n = 0;
         for (; n + 2 < N; ++n) {
             unsigned char *nxt = lds + ((n + 1) & 1) * Cfg::kTileBytes;
             ZPT(0);
-            vt_store(n + 1, nxt, 64);
+            vt_store(n + 1, nxt, false);
             gate_b_setup();
-            gate_b_half(n + 1, 0, nxt, 64);
+            gate_b_half(n + 1, 0, nxt, false);
             ZPT(2);
             __syncthreads();   // Ps of chunk n visible to the MFMA waves
             ZPT(3);
-            gate_b_half(n + 1, 1, nxt, 64);
+            gate_b_half(n + 1, 1, nxt, false);
             gate_b_finish(n + 1, gam + ((n + 1) & 1) * DK);
-            gate_a(n + 2, 64);
+            gate_a(n + 2, false);
             ZPT(5);
             __syncthreads();   // tiles of chunk n+1 and gate sums of chunk n+2 complete
             ZPT(6);
         }
         if (N > 1) {   // n = N-2: produce the last chunk
             unsigned char *nxt = lds + ((n + 1) & 1) * Cfg::kTileBytes;
-            vt_store(n + 1, nxt, 64);
+            vt_store(n + 1, nxt, false);
             gate_b_setup();
-            gate_b_half(n + 1, 0, nxt, 64);
+            gate_b_half(n + 1, 0, nxt, false);
             __syncthreads();
-            gate_b_half(n + 1, 1, nxt, 64);
+            gate_b_half(n + 1, 1, nxt, false);
             gate_b_finish(n + 1, gam + ((n + 1) & 1) * DK);
             __syncthreads();
         }

@@ -226,7 +226,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
                                int32_t schedule, void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
-    if (S_save && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // the backward takes whole chunks only
+    if (S_save && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // states are saved on whole chunks only
     if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
         !aligned16(S0) || !aligned16(S_last) || !aligned16(S_save) || !aligned16(workspace))
@@ -298,7 +298,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
 // what the reverse scan chains into dS_in.
 static void fill_bwd_params(zeco::BwdQKParams &b, const zeco_gla_desc *d, int P, int L, const void *g,
                             float *dg, const float *S_init, const float *S_last) {
-    b.g = g; b.B = d->B; b.P = P; b.H = d->H; b.L = L; b.n_chunks = L / d->C;
+    b.g = g; b.B = d->B; b.P = P; b.H = d->H; b.L = L; b.n_chunks = chunks_of(L); b.pad = 64 * b.n_chunks - L;
     b.sb = d->stride_b; b.st = d->stride_t; b.sh = d->stride_h;
     b.vb = d->vstride_b; b.vt = d->vstride_t; b.vh = d->vstride_h;
     b.dg = dg; b.S_init = S_init; b.S_last = S_last;
@@ -337,7 +337,7 @@ static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const 
 
 zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *d, const void *q, const void *g, const void *dO,
                                 float *dS_loc, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!q || !g || !dO || !dS_loc) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(g) || !aligned16(dO) || !aligned16(dS_loc)) return ZECO_ERR_INVALID_ARG;
@@ -353,7 +353,7 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
                                     const void *g, const void *dO, const float *S_init, const float *S_last,
                                     const float *dS_in, void *dq, void *dk, void *dv, float *dg,
                                     void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (!q || !k || !v || !g || !dO || !S_init || !S_last || !dS_in || !dq || !dk || !dv || !dg)
         return ZECO_ERR_INVALID_ARG;
@@ -373,7 +373,14 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
 // exactly known value, at every piece boundary; the bf16 rounding noise of the terms grows with the
 // square root of the run length (measured, worst head: 4 % of max|dG| over 8192 tokens, 1.8 % over
 // 1024, 1.2 % over 512).
+// A length that is no multiple of 64 is cut into equal pieces of 64 to 512 tokens when it has such a
+// divisor (the pieces then start with a short chunk each) and is left whole otherwise.
 static int bwd_pieces(const zeco_gla_desc *d) {
+    if (d->L % 64 != 0) {
+        for (int S = (d->L + 511) / 512; S <= d->L / 64; ++S)
+            if (d->L % S == 0) return S;
+        return 1;
+    }
     int S = fused_pieces(d);
     while (d->L / S > 512 && d->L % (2 * S * 64) == 0) S *= 2;
     return S;
@@ -405,7 +412,7 @@ size_t zeco_gla_saved_states_bytes(const zeco_gla_desc *desc) {
 }
 
 size_t zeco_gla_fused_bwd_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     return bwd_layout(desc, bwd_pieces(desc)).total * sizeof(float);
 }
 
@@ -413,8 +420,9 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
                                const void *g, const void *dO, const float *S0, const float *dS_T,
                                const float *S_saved, void *dq, void *dk, void *dv, float *dg, float *dS0,
                                void *workspace, size_t workspace_bytes, void *stream) {
-    const zeco_status st = check_desc(d);
+    const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (S_saved && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // states are saved on whole chunks only
     if (!q || !k || !v || !g || !dO || !dq || !dk || !dv || !dg || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
         !aligned16(S0) || !aligned16(dS_T) || !aligned16(S_saved) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) ||

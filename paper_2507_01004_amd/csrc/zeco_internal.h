@@ -20,7 +20,7 @@ struct ChunkParams {
     int save_every = 0;        //   [P * n_chunks / save_every, B, H, d_k, d_v]
     int B, P, H, L;
     int n_chunks;              // ceil(L / 64)
-    int pad = 0;               // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens (forward modes only)
+    int pad = 0;               // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens
     float scale;
     float kscale;              // backward modes: multiplier carried by the operand in the k role
     long long sb, st, sh;      // q/k/g element strides
@@ -74,7 +74,8 @@ struct BwdQKParams {
     void *out;
     float *dg;
     const float *W_init, *S_init, *S_last;
-    int B, P, H, L, n_chunks;
+    int B, P, H, L, n_chunks;    // n_chunks = ceil(L / 64)
+    int pad = 0;                 // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens
     float zscale, oscale;        // multipliers of the gated operand and of the output
     // dQ pass only, optional: also emit each segment's state gradient from dS = 0,
     // dS_loc [P,B,H,d_k,d_v] = qscale * sum_t (q_t .* exp(G_t))^T x_t, and its total log decay G_tot_out

@@ -76,18 +76,22 @@ def test_local_fwd_rejects_bad_descriptors(L, kw, expect):
 
 
 def test_segment_lengths_that_are_no_multiple_of_the_chunk(L):
-    """The forward entry points take them (validation gets past the descriptor: the next check, a null
-    pointer, answers), the backward ones and a forward that saves states for the backward do not."""
+    """The entry points take them (validation gets past the descriptor: the next check, a null pointer,
+    answers), except where states are saved for the backward: those live on whole chunks."""
     d, ref = good_desc(L=100), ctypes.byref
     assert call_local(L, d, q=None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_apply_init_state(ref(d), None, FAKE, FAKE, FAKE, 1, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_local_fwd_chunk_decay(ref(d), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_fused_fwd_workspace(ref(d)) > 0
-    assert L.zeco_gla_fused_bwd_workspace(ref(d)) == 0 and L.zeco_gla_saved_states_bytes(ref(d)) == 0
+    assert L.zeco_gla_fused_bwd_workspace(ref(d)) > 0 and L.zeco_gla_saved_states_bytes(ref(d)) == 0
+    assert L.zeco_gla_bwd_dstate(ref(d), None, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
     fwd = [FAKE] * 4 + [None, FAKE, None]
     assert L.zeco_gla_fused_fwd(ref(d), *fwd, FAKE, 0, FAKE, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED   # S_save
-    fused = [FAKE] * 5 + [None, None, None] + [FAKE] * 4 + [None, FAKE]
-    assert L.zeco_gla_fused_bwd(ref(d), *fused, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED
+    fused = [FAKE] * 5 + [None, None, FAKE] + [FAKE] * 4 + [None, FAKE]
+    assert L.zeco_gla_fused_bwd(ref(d), *fused, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED   # S_saved
+    fused[7] = None
+    fused[0] = None
+    assert L.zeco_gla_fused_bwd(ref(d), *fused, 1 << 30, None) == zeco.ZECO_ERR_INVALID_ARG
 
 
 def test_apply_init_state_rejects_unknown_flags(L):
@@ -129,7 +133,7 @@ def test_backward_entry_points_reject_bad_arguments(L):
     ref = ctypes.byref
     assert L.zeco_gla_bwd_dstate(ref(d), None, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_bwd_dstate(ref(f32), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED
-    assert L.zeco_gla_bwd_dstate(ref(good_desc(L=100)), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED   # whole chunks only
+    assert L.zeco_gla_bwd_dstate(ref(good_desc(L=40)), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED   # shorter than a chunk
     args = [FAKE] * 12
     assert L.zeco_gla_bwd_from_state(ref(f32), *args, None) == zeco.ZECO_ERR_UNSUPPORTED
     args[7] = None                                         # dS_in missing

@@ -158,10 +158,88 @@ def test_ragged_per_head_gates():
         assert rel_err_bh(host(S_last), S_f, (0, 1)) <= TOL["bf16"]
 
 
+BWD_CASES = [
+    # (name, B, H, P, L, d_k, d_v, g dtype)
+    ("rb_100", 1, 4, 2, 100, 128, 128, "f32"),            # d_v split in the dV pass; chunks of 36 + 64
+    ("rb_65", 1, 2, 3, 65, 128, 128, "f32"),              # one token in the short chunk
+    ("rb_whole_127", 2, 16, 5, 127, 128, 128, "f32"),     # 160 streams
+    ("rb_1000", 1, 2, 2, 1000, 128, 128, "bf16"),         # fused call: 2 pieces of 500 tokens per segment
+    ("rb_1046", 1, 1, 2, 1046, 64, 64, "f32"),            # 1046 = 2 x 523: no divisor gives pieces of 64..512 tokens, left whole
+    ("rb_dk64_dv128_200", 1, 2, 2, 200, 64, 128, "f32"),
+    ("rb_dk128_dv64_129", 1, 2, 2, 129, 128, 64, "bf16"),
+]
+GRADS = ("dq", "dk", "dv", "dg")
+
+
+def make_bwd(case, **kw):
+    name, B, H, P, L, dk, dv, gd = case
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=zlib.crc32(name.encode()) % 10000 + 11, io="bf16", g=gd,
+                            device="cuda", **kw)
+    gen = torch.Generator(device="cuda").manual_seed(zlib.crc32(name.encode()) % 10000 + 12)
+    inp["dO"] = torch.randn(inp["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)
+    return inp
+
+
+def oracle_bwd(inp, scale, S0=None, dS_T=None):
+    return oracle.gla_recurrent_bwd(host(inp["q"]), host(inp["k"]), host(inp["v"]), host(inp["g"]),
+                                    host(inp["dO"]), scale, S0, dS_T)
+
+
+@pytest.mark.parametrize("case", BWD_CASES, ids=[c[0] for c in BWD_CASES])
+def test_ragged_backward(case):
+    """The fused backward, and the chain of building blocks around the two scans, against the oracle's
+    token-by-token reverse recurrence over the whole sequence."""
+    name, B, H, P, L, dk, dv, gd = case
+    print("case", case, flush=True)
+    tol = TOL["bf16"]
+    inp = make_bwd(case, gate_div=64.0)
+    q, k, v, g, dO = (inp[n] for n in ("q", "k", "v", "g", "dO"))
+    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    for s0, dst in ((None, None), (S0, dS_T)):
+        got = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, S0=s0, dS_T=dst)
+        torch.cuda.synchronize()
+        ref = oracle_bwd(inp, 0.5, None if s0 is None else host(s0), None if dst is None else host(dst))
+        for name_, x, r in zip(GRADS, got[:4], ref[:4]):
+            assert rel_err_bh(host(x), r, (0, 2)) <= tol, name_
+        assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= tol
+    S_loc, G_tot = zeco.gla_local_state(k, v, g, P)
+    S_init, S_last = zeco.state_scan(S_loc, G_tot)
+    dS_loc = zeco.gla_bwd_dstate(q, g, dO, P, scale=0.7)
+    torch.cuda.synchronize()
+    for p in range(P):      # each segment's outgoing state gradient on its own
+        sl = {n: t[:, p * L:(p + 1) * L] for n, t in inp.items()}
+        assert rel_err_bh(host(dS_loc[p]), oracle_bwd(sl, 0.7)[4], (0, 1)) <= tol, p
+    dS_in, dS0 = zeco.state_scan(dS_loc, G_tot, direction=1)
+    got = zeco.gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P, scale=0.7)
+    torch.cuda.synchronize()
+    ref = oracle_bwd(inp, 0.7)
+    for name_, x, r in zip(GRADS, got, ref[:4]):
+        assert rel_err_bh(host(x), r, (0, 2)) <= tol, name_
+    assert rel_err_bh(host(dS0), ref[4], (0, 1)) <= tol
+
+
+def test_ragged_backward_per_head_gates():
+    B, H, P, L, dk, dv = 1, 3, 2, 230, 128, 128
+    print("ragged backward, per-head gates", flush=True)
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=79, io="bf16", g="f32", device="cuda", gate_div=64.0,
+                            per_head_gate=True)
+    gen = torch.Generator(device="cuda").manual_seed(80)
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)
+    h = {n: host(t) for n, t in inp.items()}
+    h["g"] = np.repeat(h["g"][..., None], dk, axis=-1)
+    ref = oracle.gla_recurrent_bwd(h["q"], h["k"], h["v"], h["g"], host(dO), 0.5, None, None)
+    got = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], dO, P, scale=0.5)
+    torch.cuda.synchronize()
+    for name_, x, r in zip(GRADS[:3], got[:3], ref[:3]):
+        assert rel_err_bh(host(x), r, (0, 2)) <= TOL["bf16"], name_
+    assert rel_err_bh(host(got[3]), ref[3].sum(axis=-1), (0, 2)) <= TOL["bf16"]
+
+
 def test_ragged_lengths_where_whole_chunks_are_needed():
+    """Saved states live on whole chunks; a segment must hold at least one chunk."""
     inp = synth.make_inputs(1, 200, 2, 128, 128, seed=3, io="bf16", g="f32", device="cuda")
     q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
-    with pytest.raises(zeco.ZecoError):
-        zeco.gla_fused_bwd(q, k, v, g, torch.randn_like(v), 2)
+    assert zeco.saved_states_bytes(q, v, g, 2) == 0
     with pytest.raises(zeco.ZecoError):      # shorter than a chunk
         zeco.gla_local_fwd(q[:, :80], k[:, :80], v[:, :80], g[:, :80], 2)

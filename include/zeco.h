@@ -40,7 +40,8 @@ typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
  * v, o as                   base + b*vstride_b + t*vstride_t + h*vstride_h + j (j < d_v)
  * in ELEMENTS; the innermost dimension is contiguous.  Strides must be multiples of 8 elements. */
 typedef struct {
-    int32_t B, P, H, L;
+    int32_t B, P, H, L;        /* B = 0 (an empty batch; BH = 0 in zeco_state_scan) is valid: the entry points
+                                * return ZECO_OK at once, touch no pointer and launch nothing */
     int32_t d_k, d_v, C;       /* supported: C = 64, d_k and d_v in {64, 128}, any L >= C.  When L % C != 0
                                 * one chunk of every segment is short, L - C*(ceil(L/C) - 1) tokens (the
                                 * first one in the passes that walk a segment forwards, the last one in

@@ -13,8 +13,8 @@ bool dim_ok(int d) { return d == 64 || d == 128; }
 // lengths that are no multiple of the chunk size (the forward entry points do, from 64 tokens on).
 zeco_status check_desc(const zeco_gla_desc *d, bool any_length = false) {
     if (!d) return ZECO_ERR_INVALID_ARG;
-    if (d->B <= 0 || d->P <= 0 || d->H <= 0 || d->L <= 0 || d->d_k <= 0 || d->d_v <= 0 || d->C <= 0)
-        return ZECO_ERR_INVALID_ARG;
+    if (d->B < 0 || d->P <= 0 || d->H <= 0 || d->L <= 0 || d->d_k <= 0 || d->d_v <= 0 || d->C <= 0)
+        return ZECO_ERR_INVALID_ARG;   // (B = 0, an empty batch, is valid: every entry point returns at once)
     if (d->io_dtype != ZECO_F32 && d->io_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
     if (d->g_dtype != ZECO_F32 && d->g_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
     if (!(d->scale == d->scale)) return ZECO_ERR_INVALID_ARG;
@@ -92,6 +92,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
                                void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !k || !v || !g || !o || !S_loc || !G_cum || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
         !aligned16(S_loc) || !aligned16(G_cum) || !aligned16(G_tot))
@@ -175,6 +176,7 @@ zeco_status zeco_gla_local_state(const zeco_gla_desc *d, const void *k, const vo
                                  float *S_loc, float *G_tot, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!k || !v || !g || !S_loc || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_loc) || !aligned16(G_tot))
         return ZECO_ERR_INVALID_ARG;
@@ -190,6 +192,7 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const
                                     const void *g, const float *S_init, void *o, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !k || !v || !g || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_init) ||
         !aligned16(o))
@@ -226,6 +229,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
                                int32_t schedule, void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (S_save && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // states are saved on whole chunks only
     if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
@@ -339,6 +343,7 @@ zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *d, const void *q, const voi
                                 float *dS_loc, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !g || !dO || !dS_loc) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(g) || !aligned16(dO) || !aligned16(dS_loc)) return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
@@ -355,6 +360,7 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
                                     void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !k || !v || !g || !dO || !S_init || !S_last || !dS_in || !dq || !dk || !dv || !dg)
         return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
@@ -422,6 +428,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
                                void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (S_saved && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // states are saved on whole chunks only
     if (!q || !k || !v || !g || !dO || !dq || !dk || !dv || !dg || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
@@ -473,10 +480,11 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
                             const float *S_loc, const float *G_tot, const float *S0, float *S_init,
                             float *S_last, int32_t direction, int32_t gate_per_head, void *stream) {
-    if (P <= 0 || BH <= 0 || d_k <= 0 || d_v <= 0 || K_blocks <= 0) return ZECO_ERR_INVALID_ARG;
+    if (P <= 0 || BH < 0 || d_k <= 0 || d_v <= 0 || K_blocks <= 0) return ZECO_ERR_INVALID_ARG;
     if (d_k % K_blocks != 0) return ZECO_ERR_INVALID_ARG;
     if (direction != 0 && direction != 1) return ZECO_ERR_INVALID_ARG;
     if (gate_per_head != 0 && gate_per_head != 1) return ZECO_ERR_INVALID_ARG;
+    if (BH == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!S_loc || !G_tot || !S_init) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(S_loc) || !aligned16(S_init) || !aligned16(S0) || !aligned16(S_last) ||
         (reinterpret_cast<uintptr_t>(G_tot) & 3u))
@@ -495,6 +503,7 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
                                   const float *S_init, void *o, int32_t flags, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !G_cum || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(G_cum) || !aligned16(S_init) || !aligned16(o))
         return ZECO_ERR_INVALID_ARG;
@@ -516,6 +525,7 @@ zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q
                                            float *G_chunk, float *G_tot, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !k || !v || !g || !o || !S_loc || !G_chunk || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
         !aligned16(S_loc) || !aligned16(G_chunk) || !aligned16(G_tot))
@@ -533,6 +543,7 @@ zeco_status zeco_apply_init_state_chunk_decay(const zeco_gla_desc *d, const void
                                               int32_t flags, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !g || !G_chunk || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(g) || !aligned16(G_chunk) || !aligned16(S_init) || !aligned16(o))
         return ZECO_ERR_INVALID_ARG;

@@ -57,7 +57,8 @@ def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
 
 
 @pytest.mark.parametrize("kw,expect", [
-    (dict(B=0), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(B=-1), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(P=0), zeco.ZECO_ERR_INVALID_ARG),
     (dict(L=40), zeco.ZECO_ERR_UNSUPPORTED),           # shorter than a chunk
     (dict(stride_t=100), zeco.ZECO_ERR_INVALID_ARG),   # stride not a multiple of 8
     (dict(stride_h=64), zeco.ZECO_ERR_INVALID_ARG),    # heads overlap
@@ -92,6 +93,23 @@ def test_segment_lengths_that_are_no_multiple_of_the_chunk(L):
     fused[7] = None
     fused[0] = None
     assert L.zeco_gla_fused_bwd(ref(d), *fused, 1 << 30, None) == zeco.ZECO_ERR_INVALID_ARG
+
+
+def test_an_empty_batch_is_a_valid_no_op(L):
+    """B = 0: every entry point returns ZECO_OK before it looks at a pointer (all null here, no GPU needed)."""
+    d, ref, N = good_desc(B=0), ctypes.byref, None
+    assert L.zeco_gla_local_fwd(ref(d), N, N, N, N, N, N, N, N, N, 0, N) == zeco.ZECO_OK
+    assert L.zeco_apply_init_state(ref(d), N, N, N, N, 0, N) == zeco.ZECO_OK
+    assert L.zeco_state_scan(4, 0, 128, 128, 16, N, N, N, N, N, 0, 0, N) == zeco.ZECO_OK
+    assert L.zeco_gla_local_fwd_chunk_decay(ref(d), N, N, N, N, N, N, N, N, N) == zeco.ZECO_OK
+    assert L.zeco_apply_init_state_chunk_decay(ref(d), N, N, N, N, N, 0, N) == zeco.ZECO_OK
+    assert L.zeco_gla_local_state(ref(d), N, N, N, N, N, N) == zeco.ZECO_OK
+    assert L.zeco_gla_fwd_from_state(ref(d), N, N, N, N, N, N, N) == zeco.ZECO_OK
+    assert L.zeco_gla_fused_fwd(ref(d), N, N, N, N, N, N, N, N, 0, N, 0, N) == zeco.ZECO_OK
+    assert L.zeco_gla_bwd_dstate(ref(d), N, N, N, N, N) == zeco.ZECO_OK
+    assert L.zeco_gla_bwd_from_state(ref(d), *([N] * 12), N) == zeco.ZECO_OK
+    assert L.zeco_gla_fused_bwd(ref(d), *([N] * 14), 0, N) == zeco.ZECO_OK
+    assert L.zeco_gla_fused_fwd_workspace(ref(d)) == 0 and L.zeco_gla_local_fwd_workspace(ref(d)) == 0
 
 
 def test_apply_init_state_rejects_unknown_flags(L):

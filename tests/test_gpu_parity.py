@@ -245,6 +245,18 @@ def test_errors_surface_as_exceptions():
         zeco.gla_local_fwd(q, q, q, q, 2)            # L = 48 is shorter than a chunk
 
 
+def test_empty_batch_is_a_no_op():
+    """B = 0 through the binding: the calls succeed, return empty tensors and launch nothing."""
+    q = torch.empty(0, 256, 2, 128, dtype=torch.bfloat16, device="cuda")
+    g = torch.empty(0, 256, 2, 128, device="cuda")
+    o, S_last, parts = zeco.segmented_fwd(q, q, q, g, 2)
+    assert o.shape == q.shape and S_last.shape == (0, 2, 128, 128) and parts["S_loc"].shape == (2, 0, 2, 128, 128)
+    o2, S2 = zeco.gla_fused_fwd(q, q, q, g, 2)
+    grads = zeco.gla_fused_bwd(q, q, q, g, q, 2)
+    torch.cuda.synchronize()
+    assert o2.numel() == 0 and all(t.numel() == 0 for t in grads)
+
+
 BF16_CASES = [c for c in CASES if c[7] == "bf16"]
 
 

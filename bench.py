@@ -23,8 +23,8 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
 
 # HBM bytes per launch of the chunk kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/pipeline_kernels_c2_c3_c4.md gives the commands and the copy-kernel calibration); None = not measured.
-MEASURED_TRAFFIC = {("c3", "f32"): 4305900000, ("c4", "f32"): 34469000000}   # profiles/pipeline_kernels_c2_c3_c4.md
+# (profiles/pipeline_kernels_c2_c3_c4_c5.md gives the commands and the copy-kernel calibration); None = not measured.
+MEASURED_TRAFFIC = {("c3", "f32"): 4305900000, ("c4", "f32"): 34469000000}   # profiles/pipeline_kernels_c2_c3_c4_c5.md
 
 
 def algorithmic_bytes(c, g_in, g_cum):

@@ -401,7 +401,9 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
 }
 
 template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hipStream_t s) {
-    const int grid = (p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    const long long wgs = (long long)(p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
+    const int grid = (int)wgs;
     if (p.gate_per_head)
         hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, true>), dim3(grid), dim3(256), 0, s, p);
     else
@@ -409,7 +411,9 @@ template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hi
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hipStream_t s) {
-    const int grid = (p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    const long long wgs = (long long)(p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
+    const int grid = (int)wgs;
     if (p.g_bf16)
         hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateBF16>), dim3(grid), dim3(256), 0, s, p);
     else
@@ -417,7 +421,9 @@ template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hip
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hipStream_t s) {
-    const int grid = (p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    const long long wgs = (long long)(p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
+    const int grid = (int)wgs;
     hipLaunchKernelGGL((apply_init_f32_kernel<DK, DV>), dim3(grid), dim3(DV * 4), 0, s, p);
     return hipGetLastError();
 }

@@ -120,6 +120,38 @@ def single_segment_case(args):
             "fused_fwd_tokens_per_s": round(B * T / (res["fused_fwd"] * 1e-3), 1)}
 
 
+def scan_variants_case(args):
+    """The segment-state scan alone where one chain is latency-bound (few heads, many segments) and where
+    it streams (many heads): zeco_state_scan against zeco_state_scan_tree, d_k = d_v = 128."""
+    import torch
+    from paper_2507_01004_amd import zeco
+    rows = []
+    for P, BH in ((1024, 1), (1024, 2), (256, 8), (64, 16)):
+        gen = torch.Generator(device="cuda:0").manual_seed(P + BH)
+        S_loc = torch.randn(P, BH, 128, 128, device="cuda:0", generator=gen)
+        G_tot = -torch.rand(P, BH, 128, device="cuda:0", generator=gen)
+        out = (torch.empty_like(S_loc), torch.empty(BH, 128, 128, device="cuda:0"))
+        ws = torch.empty(max(16, int(zeco.lib().zeco_state_scan_tree_workspace(P, BH, 128, 128, 0))),
+                         dtype=torch.uint8, device="cuda:0")
+        ms = {}
+        for name, fn in (("serial", lambda: zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=out)),
+                         ("tree", lambda: zeco.state_scan_tree(S_loc, G_tot, out=out, workspace=ws))):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms[name] = e0.elapsed_time(e1) / args.steps
+        by = 2 * S_loc.numel() * 4
+        rows.append({"P": P, "BH": BH, "serial_ms": round(ms["serial"], 4), "tree_ms": round(ms["tree"], 4),
+                     "serial_GBps": round(by / ms["serial"] / 1e6, 1), "alg_bytes": by})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -452,6 +484,7 @@ def main():
     }
     if args.workload != "c2" and not (args.only_pipeline or args.only_fused or args.only_backward):
         out["single_segment_c2"] = single_segment_case(args)
+        out["scan_variants"] = scan_variants_case(args)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inp, c, min(T, 131072))
     print(json.dumps(out))

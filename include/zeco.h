@@ -102,6 +102,24 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
                             float *S_init, float *S_last, int32_t direction, int32_t gate_per_head,
                             void *stream);
 
+/* The same scan as a tree of depth two (the conclusion's outlook names a tree-like All-Scan): the chain of
+ * P segments is cut into P/g groups of g segments; (1) every group is scanned on its own from the zero
+ * state (its end state and total log decay), (2) the chain over the groups gives the state entering each
+ * group and S_last, (3) every group is scanned again from the state entering it, which writes S_init.
+ * The serial depth drops from P to about 2 g + P/g (g is chosen to minimise it over the divisors of P)
+ * for one more read of S_loc: it pays where a single chain is latency-bound, i.e. few heads and many
+ * segments; with many heads zeco_state_scan already streams at the memory rate and is the faster one.
+ * Same arguments and conventions as zeco_state_scan; the result differs from it by rounding only (the
+ * groups re-associate the sums), it is deterministic; d_k % 16 == 0.  When P has no divisor that
+ * shortens the chain (P prime, P <= 4) the call is zeco_state_scan and needs no workspace.
+ * workspace: device memory of zeco_state_scan_tree_workspace() bytes (may be 0), 16-byte aligned,
+ * caller-owned, contents unspecified afterwards; ZECO_ERR_WORKSPACE when too small. */
+size_t zeco_state_scan_tree_workspace(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t gate_per_head);
+zeco_status zeco_state_scan_tree(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, const float *S_loc,
+                                 const float *G_tot, const float *S0, float *S_init, float *S_last,
+                                 int32_t direction, int32_t gate_per_head, void *workspace,
+                                 size_t workspace_bytes, void *stream);
+
 /* Initial-state correction (Eq. (global-correction) carried to the output; the highlighted term
  * of Alg. 1's output pass, with Lambda_t .* gamma~_[n-1] = exp(G_cum[t])):
  *   o_t += (scale * q_t .* exp(G_cum[t])) S_init[p]      for every token t of segment p

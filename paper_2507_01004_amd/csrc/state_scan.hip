@@ -34,13 +34,15 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
         const size_t off = (size_t)bh * state + (size_t)row * p.d_v + (size_t)(e % dv4) * 4;
         const float *loc = p.S_loc + grp * p.P * seg_stride + off;
         const float *gt = p.G_tot + grp * p.P * g_stride + (size_t)bh * gdim + (p.gate_per_head ? 0 : row);
-        float *init = p.S_init + grp * p.P * seg_stride + off;
+        float *init = p.S_init ? p.S_init + grp * p.P * seg_stride + off : nullptr;   // null: end values only
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
         if (p.S0) s = *reinterpret_cast<const f32x4 *>(p.S0 + grp * seg_stride + off);
-        // optional by-product: the log decay preceding each segment of the chain and the chain's total,
-        // kept by the thread that owns the first columns of a row (forward chains, per-channel gates)
-        const bool prefix = p.G_pre && e % dv4 == 0;
-        float *gpre = prefix ? p.G_pre + grp * p.P * g_stride + (size_t)bh * gdim + row : nullptr;
+        // optional by-products: the log decay preceding each segment of the chain (forward chains) and the
+        // chain's total, kept by the thread that owns the first columns of a row (of the head's first row
+        // when the head has one decay)
+        const bool prefix = (p.G_pre || p.G_sum) && e % dv4 == 0 && (!p.gate_per_head || row == 0);
+        const size_t gcol = (size_t)bh * gdim + (p.gate_per_head ? 0 : row);
+        float *gpre = (prefix && p.G_pre) ? p.G_pre + grp * p.P * g_stride + gcol : nullptr;
         float gsum = 0.f;
 
         for (int p0 = 0; p0 < p.P; p0 += kScanDepth) {
@@ -58,9 +60,9 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
             for (int u = 0; u < kScanDepth; ++u) {
                 if (p0 + u < p.P) {
                     const size_t sg = p.reverse ? p.P - 1 - (p0 + u) : p0 + u;
-                    *reinterpret_cast<f32x4 *>(init + sg * seg_stride) = s;
+                    if (init) *reinterpret_cast<f32x4 *>(init + sg * seg_stride) = s;
                     if (prefix) {
-                        gpre[sg * g_stride] = gsum;
+                        if (gpre) gpre[sg * g_stride] = gsum;
                         gsum += a[u];
                     }
                     const float d = fast_exp(a[u]);
@@ -72,7 +74,7 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
             }
         }
         if (p.S_last) *reinterpret_cast<f32x4 *>(p.S_last + grp * seg_stride + off) = s;
-        if (prefix) p.G_sum[grp * g_stride + (size_t)bh * gdim + row] = gsum;
+        if (prefix && p.G_sum) p.G_sum[grp * g_stride + gcol] = gsum;
     }
 }
 

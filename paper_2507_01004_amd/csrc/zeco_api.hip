@@ -499,6 +499,70 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
     return from_hip(zeco::launch_scan(p, static_cast<hipStream_t>(stream)));
 }
 
+// ---- two-level (tree of depth two) scan ----------------------------------------------------------------
+// Segments per group: the divisor g of P that minimises the length of the serial work, 2 g + P / g (two
+// passes inside the groups, one over the groups).  Returns P when no proper divisor helps.
+static int tree_group(int P) {
+    int best = P;
+    long long cost = P;                       // the plain chain
+    for (int g = 2; g < P; ++g) {
+        if (P % g) continue;
+        const long long c = 2ll * g + P / g;
+        if (c < cost) { cost = c; best = g; }
+    }
+    return best;
+}
+
+size_t zeco_state_scan_tree_workspace(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t gate_per_head) {
+    if (P <= 0 || BH <= 0 || d_k <= 0 || d_v <= 0) return 0;
+    const int g = tree_group(P);
+    if (g == P) return 0;
+    const size_t J = P / g, state = (size_t)BH * d_k * d_v;
+    return (2 * J * state + J * (size_t)BH * (gate_per_head ? 1 : d_k)) * sizeof(float);
+}
+
+zeco_status zeco_state_scan_tree(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, const float *S_loc,
+                                 const float *G_tot, const float *S0, float *S_init, float *S_last,
+                                 int32_t direction, int32_t gate_per_head, void *workspace,
+                                 size_t workspace_bytes, void *stream) {
+    const int g = P > 0 ? tree_group(P) : 0;
+    if (P <= 0 || g == P || BH <= 0)   // nothing to split (or an argument the plain scan reports)
+        return zeco_state_scan(P, BH, d_k, d_v, d_k >= 16 && d_k % 16 == 0 ? 16 : 1, S_loc, G_tot, S0, S_init, S_last,
+                               direction, gate_per_head, stream);
+    if (d_k <= 0 || d_v <= 0 || d_k % 16 != 0) return ZECO_ERR_INVALID_ARG;
+    if (direction != 0 && direction != 1) return ZECO_ERR_INVALID_ARG;
+    if (gate_per_head != 0 && gate_per_head != 1) return ZECO_ERR_INVALID_ARG;
+    if (!S_loc || !G_tot || !S_init) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(S_loc) || !aligned16(S_init) || !aligned16(S0) || !aligned16(S_last) ||
+        (reinterpret_cast<uintptr_t>(G_tot) & 3u))
+        return ZECO_ERR_INVALID_ARG;
+    if ((int64_t)BH * 16 > (int64_t)1 << 30 || P / g > 65535) return ZECO_ERR_INVALID_ARG;
+    if (d_v % 4 != 0) return ZECO_ERR_UNSUPPORTED;
+    if (workspace_bytes < zeco_state_scan_tree_workspace(P, BH, d_k, d_v, gate_per_head)) return ZECO_ERR_WORKSPACE;
+    if (!workspace || !aligned16(workspace)) return ZECO_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int J = P / g;
+    const size_t state = (size_t)BH * d_k * d_v;
+    float *T = static_cast<float *>(workspace), *I = T + J * state, *Gt = I + J * state;
+
+    zeco::ScanParams p;
+    p.reverse = direction; p.gate_per_head = gate_per_head;
+    p.BH = BH; p.d_k = d_k; p.d_v = d_v; p.rows_per_block = d_k / 16;
+    // 1: every group on its own from the zero state: its end state and its total log decay
+    p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = nullptr; p.S_init = nullptr; p.S_last = T; p.G_sum = Gt;
+    p.P = g; p.groups = J;
+    hipError_t e = zeco::launch_scan(p, s);
+    if (e != hipSuccess) return ZECO_ERR_HIP;
+    // 2: the chain over the groups: the state entering each group, and the end state
+    p.S_loc = T; p.G_tot = Gt; p.S0 = S0; p.S_init = I; p.S_last = S_last; p.G_sum = nullptr;
+    p.P = J; p.groups = 1;
+    if ((e = zeco::launch_scan(p, s)) != hipSuccess) return ZECO_ERR_HIP;
+    // 3: every group again, from the state entering it
+    p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = I; p.S_init = S_init; p.S_last = nullptr;
+    p.P = g; p.groups = J;
+    return from_hip(zeco::launch_scan(p, s));
+}
+
 zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const float *G_cum,
                                   const float *S_init, void *o, int32_t flags, void *stream) {
     const zeco_status st = check_desc(d, true);

@@ -56,11 +56,11 @@ struct ApplyParams {
 // G_tot [groups*P, BH, d_k], S0 and S_last [groups, BH, d_k, d_v].
 struct ScanParams {
     const float *S_loc, *G_tot, *S0;
-    float *S_init, *S_last;
+    float *S_init, *S_last;      // either may be null (not stored)
     int P, BH, d_k, d_v, rows_per_block, groups;
     int reverse = 0;             // 1: chain runs from segment P-1 down to 0
-    // optional (forward chains, per-channel gates): G_pre [groups*P, BH, d_k] = sum of G_tot over the
-    // earlier segments of the chain, G_sum [groups, BH, d_k] = sum over all of them
+    // optional, each on its own: G_pre [groups*P, BH, d_k] = sum of G_tot over the earlier segments of the
+    // chain (forward chains only), G_sum [groups, BH, d_k] = sum over all of them ([.., BH] with one decay per head)
     float *G_pre = nullptr, *G_sum = nullptr;
     int gate_per_head = 0;       // 1: G_tot [groups*P, BH], one log decay per head
 };

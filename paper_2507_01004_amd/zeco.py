@@ -15,9 +15,37 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
 
 ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
 ZECO_F32, ZECO_BF16 = 0, 1
+def state_scan_tree(S_loc, G_tot, S0=None, out=None, direction=0, workspace=None):
+    """zeco_state_scan_tree: the scan as a tree of depth two (groups of segments scanned in parallel).
+    Same arguments and result as state_scan, up to rounding.  Returns (S_init, S_last)."""
+    if not S_loc.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    P, dk, dv = S_loc.shape[0], S_loc.shape[-2], S_loc.shape[-1]
+    BH = S_loc.numel() // (P * dk * dv)
+    if not (S_loc.is_contiguous() and G_tot.is_contiguous()):
+        raise ValueError("S_loc and G_tot must be contiguous")
+    if out is None:
+        S_init = torch.empty_like(S_loc)
+        S_last = torch.empty(S_loc.shape[1:], dtype=torch.float32, device=S_loc.device)
+    else:
+        S_init, S_last = out
+    if G_tot.numel() not in (P * BH, P * BH * dk):
+        raise ValueError("G_tot must be [P,BH,d_k] or, for per-head gates, [P,BH]")
+    per_head = int(G_tot.numel() == P * BH and dk != 1)
+    need = int(lib().zeco_state_scan_tree_workspace(P, BH, dk, dv, per_head))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=S_loc.device)
+    st = lib().zeco_state_scan_tree(P, BH, dk, dv, _ptr(S_loc), _ptr(G_tot), _ptr(S0), _ptr(S_init), _ptr(S_last),
+                                    int(direction), per_head, _ptr(workspace), workspace.numel(), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_state_scan_tree")
+    return S_init, S_last
+
+
 APPLY_FIRST_SEGMENT_ZERO, APPLY_DENSE = 1, 2
 SCHEDULE_AUTO, SCHEDULE_TWO_PHASE, SCHEDULE_CORRECT = 0, 1, 2
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
+           "zeco_state_scan_tree_workspace", "zeco_state_scan_tree",
            "zeco_apply_init_state", "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
            "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
@@ -61,6 +89,10 @@ def lib():
         L.zeco_gla_local_fwd.restype = i32
         L.zeco_state_scan.argtypes = [i32, i32, i32, i32, i32, fp, fp, fp, fp, fp, i32, i32, vp]
         L.zeco_state_scan.restype = i32
+        L.zeco_state_scan_tree_workspace.argtypes = [i32, i32, i32, i32, i32]
+        L.zeco_state_scan_tree_workspace.restype = ctypes.c_size_t
+        L.zeco_state_scan_tree.argtypes = [i32, i32, i32, i32, fp, fp, fp, fp, fp, i32, i32, vp, ctypes.c_size_t, vp]
+        L.zeco_state_scan_tree.restype = i32
         L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state.restype = i32
         L.zeco_gla_local_fwd_chunk_decay.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp]

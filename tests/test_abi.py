@@ -112,6 +112,21 @@ def test_an_empty_batch_is_a_valid_no_op(L):
     assert L.zeco_gla_fused_fwd_workspace(ref(d)) == 0 and L.zeco_gla_local_fwd_workspace(ref(d)) == 0
 
 
+def test_state_scan_tree_validates_and_sizes_its_workspace(L):
+    ws = L.zeco_state_scan_tree_workspace
+    assert ws(36, 2, 128, 128, 0) == (2 * 9 * 2 * 128 * 128 + 9 * 2 * 128) * 4      # groups of 4: 2*4 + 9 = 17 < 36
+    assert ws(36, 2, 128, 128, 1) == (2 * 9 * 2 * 128 * 128 + 9 * 2) * 4
+    assert ws(37, 2, 128, 128, 0) == 0 and ws(4, 2, 128, 128, 0) == 0 and ws(0, 2, 128, 128, 0) == 0
+    tree = lambda P=36, ws_bytes=1 << 30, S_loc=FAKE, w=FAKE, direction=0: L.zeco_state_scan_tree(
+        P, 2, 128, 128, S_loc, FAKE, None, FAKE, None, direction, 0, w, ws_bytes, None)
+    assert tree(ws_bytes=16) == zeco.ZECO_ERR_WORKSPACE
+    assert tree(S_loc=None) == zeco.ZECO_ERR_INVALID_ARG
+    assert tree(w=None) == zeco.ZECO_ERR_INVALID_ARG
+    assert tree(direction=2) == zeco.ZECO_ERR_INVALID_ARG
+    assert tree(P=0) == zeco.ZECO_ERR_INVALID_ARG
+    assert tree(P=37, S_loc=None, w=None, ws_bytes=0) == zeco.ZECO_ERR_INVALID_ARG     # the serial path's own check
+
+
 def test_apply_init_state_rejects_unknown_flags(L):
     assert L.zeco_apply_init_state(ctypes.byref(good_desc()), FAKE, FAKE, FAKE, FAKE, 4, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_apply_init_state(ctypes.byref(good_desc()), None, FAKE, FAKE, FAKE, 3, None) == zeco.ZECO_ERR_INVALID_ARG

@@ -113,6 +113,37 @@ def test_state_scan_matches_oracle_and_is_block_independent(shape):
                 assert torch.equal(S_init, base[0]) and torch.equal(S_last, base[1])
 
 
+@pytest.mark.parametrize("shape", [(36, 2, 128, 128), (256, 1, 128, 64), (12, 3, 64, 128), (37, 2, 64, 64), (4, 1, 64, 64),
+                                   (1, 2, 128, 128)])
+def test_state_scan_tree_matches_oracle(shape):
+    """The scan as a tree of depth two, both directions, with and without an incoming state, against the
+    oracle's serial chain (the reverse chain = the oracle on the flipped segments); P = 37 (prime), 4 and 1
+    have no divisor that shortens the chain and take the serial path."""
+    P, BH, dk, dv = shape
+    print("tree scan", shape, flush=True)
+    S_loc, G_tot, S0 = random_states(P, BH, dk, dv, seed=100 + P)
+    for s0 in (None, S0):
+        ref_init, ref_last = oracle.state_scan(S_loc, G_tot, s0)
+        S_init, S_last = zeco.state_scan_tree(dev(S_loc), dev(G_tot), None if s0 is None else dev(s0))
+        again = zeco.state_scan_tree(dev(S_loc), dev(G_tot), None if s0 is None else dev(s0))
+        torch.cuda.synchronize()
+        assert rel_err_bh(host(S_init), ref_init, (1,)) <= 1e-5
+        assert rel_err_bh(host(S_last), ref_last, (0,)) <= 1e-5
+        assert torch.equal(S_init, again[0]) and torch.equal(S_last, again[1])      # deterministic
+        rev_init, rev_last = oracle.state_scan(np.flip(S_loc, 0), np.flip(G_tot, 0), s0)
+        S_init, S_last = zeco.state_scan_tree(dev(S_loc), dev(G_tot), None if s0 is None else dev(s0), direction=1)
+        torch.cuda.synchronize()
+        assert rel_err_bh(host(S_init), np.flip(rev_init, 0), (1,)) <= 1e-5
+        assert rel_err_bh(host(S_last), rev_last, (0,)) <= 1e-5
+    # one log decay per head: the oracle fed the broadcast value
+    Gh = G_tot[..., 0].copy()
+    ref_init, ref_last = oracle.state_scan(S_loc, np.repeat(Gh[..., None], dk, axis=-1), S0)
+    S_init, S_last = zeco.state_scan_tree(dev(S_loc), dev(Gh), dev(S0))
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(S_init), ref_init, (1,)) <= 1e-5
+    assert rel_err_bh(host(S_last), ref_last, (0,)) <= 1e-5
+
+
 @pytest.mark.parametrize("io", ["f32", "bf16"])
 @pytest.mark.parametrize("dims", [(64, 64), (128, 128), (64, 128), (128, 64)])
 def test_apply_init_state_matches_oracle(io, dims):

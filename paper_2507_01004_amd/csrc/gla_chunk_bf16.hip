@@ -97,26 +97,6 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
     return __builtin_bit_cast(bf16x8, w);
 }
 
-// MFMA operand fragment from a TOKEN-major bf16 tile through gfx950's transposing LDS read
-// (ds_read_b64_tr_b16).  In every group of 16 lanes, lane 4 k + r supplies the address of four
-// consecutive elements of tile row k (8 bytes), and lane 4 r' + e receives, as its element k, element e
-// of what lane 4 k + r' supplied: the group turns a patch of 4 tokens x 16 channels into 16 lanes
-// (channels) x 4 tokens.  `addr` is this lane's address for tokens row0 .. row0+3 (row0 + k for its
-// k = (lane % 16) / 4, columns 4 r ..); the second read, `second` bytes further, fills the lane's
-// other four k-slots, and the lane ends up with 8 tokens of its own channel, which is the operand
-// layout of the 32x32x16 MFMA (lane = row or column lt, k-slots = 8 tokens).  Which tokens the rows are
-// is up to the caller: a contraction does not care about the order of its k-slots as long as both
-// operands agree.
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-__device__ __forceinline__ bf16x8 lds_frag_tr(const unsigned char *addr, int second) {
-    typedef __attribute__((address_space(3))) s16x4 *lds_ptr;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(addr));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(addr + second));
-    typedef __attribute__((ext_vector_type(8))) short s16x8;
-    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-    return __builtin_bit_cast(bf16x8, v);
-}
-
 // DV is the number of state columns this workgroup owns: d_v, or d_v / NS when NS sibling workgroups
 // share a stream (each recomputes the gate pass and takes its own slice of v, o and the state).
 // MODE selects what a launch computes:

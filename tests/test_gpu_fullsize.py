@@ -116,6 +116,44 @@ def test_fullsize_backward_sampled_slices(name, samples):
             assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= TOL[c["io"]], nm
 
 
+def test_fullsize_ragged_segment_length_sampled_slices():
+    """c3's tensors cut to 8 segments of 16380 tokens (255 chunks and one of 60 tokens per segment; the
+    fused backward cuts each into 35 pieces of 468): every forward route and the backward on sampled slices."""
+    inp, c = synth.config_inputs("c3", device="cuda")
+    P, H, L = c["P"], c["H"], 16380
+    gen = torch.Generator(device="cuda").manual_seed(4243)
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)[:, :P * L]
+    inp = {n: t[:, :P * L] for n, t in inp.items()}      # views: the strides of the full tensors
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    tol = TOL[c["io"]]
+    print("full-size ragged", P, L, flush=True)
+    o, S_last, parts = zeco.segmented_fwd(q, k, v, g, P)
+    o_tp, S_tp = zeco.gla_fused_fwd(q, k, v, g, P, schedule=zeco.SCHEDULE_TWO_PHASE)
+    o_co, S_co = zeco.gla_fused_fwd(q, k, v, g, P, schedule=zeco.SCHEDULE_CORRECT)
+    grads = zeco.gla_fused_bwd(q, k, v, g, dO, P)
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(S_tp), host(S_last), (0, 1)) <= tol
+    assert rel_err_bh(host(S_co), host(S_last), (0, 1)) <= tol
+    for (p, h) in [(0, 2), (3, 9), (7, 15)]:
+        print("  sample segment %d head %d" % (p, h), flush=True)
+        seg = slice(p * L, (p + 1) * L)
+        o_ref, S_in = slice_oracle(inp, L, p, h, W["c3"])
+        for got in (o, o_tp, o_co):
+            x = host(got[:1, seg, h:h + 1])
+            assert rel_err_bh(x, o_ref, (0, 2)) <= tol
+            assert rel_err_bh(x[:, :256], o_ref[:, :256], (0, 2)) <= tol
+        if S_in is not None:
+            assert rel_err_bh(host(parts["S_init"][p, :1, h:h + 1]), S_in, (0, 1)) <= tol
+        Gc = np.cumsum(host(g[:1, seg, h:h + 1]), axis=1)
+        assert log_err(host(parts["G_cum"][:1, seg, h:h + 1]), Gc) <= 1e-5
+        ref = slice_oracle_bwd(inp, dO, L, p, h, P, W["c3"])
+        for nm, x, r in zip(("dq", "dk", "dv", "dg"), grads, ref):
+            got = host(x[:1, seg, h:h + 1])
+            assert rel_err_bh(got, r, (0, 2)) <= tol, nm
+            assert rel_err_bh(got[:, :256], r[:, :256], (0, 2)) <= tol, nm
+            assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= tol, nm
+
+
 @pytest.mark.parametrize("name", ["c2", "c3"])
 def test_fullsize_whole_forward_against_unsegmented_oracle(name):
     """Every token and head of configs 2 and 3 against Eq. (1) run over the whole sequence (the oracle

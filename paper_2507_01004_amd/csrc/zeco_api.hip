@@ -51,6 +51,11 @@ void set_length(zeco::ChunkParams &p, int L) {
 
 extern "C" {
 
+// Can the S equal pieces of a segment of L tokens be halved once more?  Pieces of whole chunks stay pieces of
+// whole chunks; a length that is no multiple of 64 is cut into equal pieces wherever it divides, each
+// piece then starting with a short chunk of its own.
+static bool halves_evenly(int L, int S) { return L % 64 == 0 ? L % (2 * S * 64) == 0 : L % (2 * S) == 0; }
+
 // Number of sub-segments each segment is split into inside zeco_gla_local_fwd (1 = none).  A stream is
 // a serial chain over chunks, so with few (batch, segment, head) streams most compute units would
 // idle; the local pass then applies the method to itself: sub-segment states from the zero state, a scan
@@ -60,7 +65,7 @@ static int subsegments(const zeco_gla_desc *d) {
     const long long streams = (long long)d->B * d->P * d->H;
     if (streams > 64) return 1;
     int S = 1;   // as many workgroups as fit the 256 compute units in one round, not more
-    while (streams * S * 2 <= 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
+    while (streams * S * 2 <= 256 && halves_evenly(d->L, S) && d->L / (2 * S) >= 256) S *= 2;
     return S;
 }
 
@@ -209,7 +214,7 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const
 static int fused_pieces(const zeco_gla_desc *d) {
     const long long streams = (long long)d->B * d->P * d->H;
     int S = 1;   // as many workgroups as fit the 256 compute units in one round, not more
-    while (streams * S * 2 <= 256 && d->L % (2 * S * 64) == 0 && d->L / (2 * S) >= 256) S *= 2;
+    while (streams * S * 2 <= 256 && halves_evenly(d->L, S) && d->L / (2 * S) >= 256) S *= 2;
     return S;
 }
 
@@ -219,8 +224,9 @@ size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
     if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     const size_t n = (size_t)desc->P * fused_pieces(desc) * desc->B * desc->H;
     // cumulative decay of the CORRECT schedule: per chunk and channel, or per token with per-head gates
+    const int S = fused_pieces(desc);
     const size_t decay = desc->g_per_head ? (size_t)desc->B * desc->P * desc->L * desc->H
-                                          : (size_t)desc->B * desc->P * chunks_of(desc->L) * desc->H * desc->d_k;
+                                          : (size_t)desc->B * desc->P * S * chunks_of(desc->L / S) * desc->H * desc->d_k;
     return (2 * n * desc->d_k * desc->d_v + n * desc->d_k + decay) * sizeof(float);
 }
 
@@ -249,7 +255,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
 
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
-    p.P = d->P * S; set_length(p, d->L / S);   // (a length with a short chunk is not cut: S = 1)
+    p.P = d->P * S; set_length(p, d->L / S);
 
     if (schedule == ZECO_SCHEDULE_CORRECT || (schedule == ZECO_SCHEDULE_AUTO && can_correct && p.L >= 4096)) {
         // local pass of every piece from the zero state, scan, correction of the pieces' heads

@@ -25,6 +25,8 @@ CASES = [
     ("bf16_whole_127", 2, 16, 5, 127, 128, 128, "bf16", "f32"),      # one workgroup per stream
     ("bf16_1000", 1, 3, 2, 1000, 128, 128, "bf16", "f32"),           # 16 chunks, the first of 40 tokens
     ("bf16_2100", 1, 2, 2, 2100, 128, 128, "bf16", "f32"),           # correction: 3 workgroups per segment, the last of one block
+    ("bf16_subseg_2056", 1, 2, 2, 2056, 128, 128, "bf16", "f32"),    # 4 streams: 8 sub-segments of 257 tokens per segment
+    ("bf16_subseg_4100", 1, 1, 1, 4100, 64, 64, "bf16", "bf16"),      # 1 stream: 4 sub-segments of 1025 tokens
     ("bf16_gbf16_300", 1, 3, 2, 300, 128, 128, "bf16", "bf16"),
     ("bf16_d64_200", 1, 2, 4, 200, 64, 64, "bf16", "f32"),
     ("bf16_dk64_dv128_100", 1, 2, 2, 100, 64, 128, "bf16", "f32"),

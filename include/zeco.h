@@ -38,7 +38,8 @@ typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
  * number of devices P - here P segments resident on one GPU).
  * q, k, g are addressed as  base + b*stride_b + t*stride_t + h*stride_h + i   (i < d_k, t < T)
  * v, o as                   base + b*vstride_b + t*vstride_t + h*vstride_h + j (j < d_v)
- * in ELEMENTS; the innermost dimension is contiguous.  Strides must be multiples of 8 elements. */
+ * in ELEMENTS; the innermost dimension is contiguous.  Strides must be multiples of 8 elements, the token
+ * strides at most 2^24 elements (ZECO_ERR_UNSUPPORTED beyond). */
 typedef struct {
     int32_t B, P, H, L;        /* B = 0 (an empty batch; BH = 0 in zeco_state_scan) is valid: the entry points
                                 * return ZECO_OK at once, touch no pointer and launch nothing */

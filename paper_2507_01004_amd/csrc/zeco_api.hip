@@ -24,6 +24,8 @@ zeco_status check_desc(const zeco_gla_desc *d, bool any_length = false) {
         if (s[i] < 0 || s[i] % 8 != 0) return ZECO_ERR_INVALID_ARG;
     if (d->stride_h < d->d_k || d->vstride_h < d->d_v) return ZECO_ERR_INVALID_ARG;
     if (d->stride_t < d->d_k || d->vstride_t < d->d_v) return ZECO_ERR_INVALID_ARG;
+    // the kernels keep in-chunk offsets (64 tokens x stride_t elements) in 32 bits
+    if (d->stride_t > ((int64_t)1 << 24) || d->vstride_t > ((int64_t)1 << 24)) return ZECO_ERR_UNSUPPORTED;
     if ((int64_t)d->B * d->P * d->H > (int64_t)1 << 24) return ZECO_ERR_INVALID_ARG;
     if (d->C != 64 || !dim_ok(d->d_k) || !dim_ok(d->d_v)) return ZECO_ERR_UNSUPPORTED;
     if (d->L % d->C != 0 && (!any_length || d->L < d->C)) return ZECO_ERR_UNSUPPORTED;

@@ -61,6 +61,7 @@ def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
     (dict(P=0), zeco.ZECO_ERR_INVALID_ARG),
     (dict(L=40), zeco.ZECO_ERR_UNSUPPORTED),           # shorter than a chunk
     (dict(stride_t=100), zeco.ZECO_ERR_INVALID_ARG),   # stride not a multiple of 8
+    (dict(stride_t=(1 << 24) + 8, stride_b=1 << 40), zeco.ZECO_ERR_UNSUPPORTED),   # token stride beyond 2^24 elements
     (dict(stride_h=64), zeco.ZECO_ERR_INVALID_ARG),    # heads overlap
     (dict(io_dtype=7), zeco.ZECO_ERR_INVALID_ARG),
     (dict(scale=float("nan")), zeco.ZECO_ERR_INVALID_ARG),

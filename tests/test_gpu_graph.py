@@ -1,5 +1,5 @@
 """The library allocates nothing and never synchronises, so its calls can be recorded into a HIP graph:
-capture the three-call pipeline, the fused forward (both schedules) and the fused backward once, replay them on new
+capture the three-call pipeline, the tree scan, the fused forward (both schedules) and the fused backward once, replay them on new
 input values, and compare every replay bitwise with the eager calls."""
 import pytest
 import torch
@@ -10,7 +10,7 @@ pytestmark = pytest.mark.gpu
 
 
 def test_pipeline_forward_backward_replay_from_a_graph():
-    B, H, P, L, dk, dv = 1, 4, 4, 512, 128, 128
+    B, H, P, L, dk, dv = 1, 4, 16, 128, 128, 128     # 16 segments: the tree scan really splits (8 groups of 2)
     inp = synth.make_inputs(B, P * L, H, dk, dv, seed=31, io="bf16", g="f32", device="cuda")
     q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
     dO = torch.randn_like(v)
@@ -21,6 +21,9 @@ def test_pipeline_forward_backward_replay_from_a_graph():
     G_cum = torch.empty(B, T, H, dk, device="cuda")
     G_tot = torch.empty(P, B, H, dk, device="cuda")
     S_init, S_last3 = torch.empty_like(S_loc), torch.empty(B, H, dk, dv, device="cuda")
+    S_init_t, S_last_t = torch.empty_like(S_loc), torch.empty(B, H, dk, dv, device="cuda")
+    ws_t = torch.empty(max(16, int(zeco.lib().zeco_state_scan_tree_workspace(P, B * H, dk, dv, 0))), dtype=torch.uint8,
+                       device="cuda")
     o2, S_last2 = torch.empty_like(v), torch.empty(B, H, dk, dv, device="cuda")
     o4, S_last4 = torch.empty_like(v), torch.empty(B, H, dk, dv, device="cuda")
     ws_f = torch.empty(zeco.fused_workspace_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
@@ -32,12 +35,13 @@ def test_pipeline_forward_backward_replay_from_a_graph():
     def run():
         zeco.gla_local_fwd(q, k, v, g, P, out=(o3, S_loc, G_cum, G_tot), workspace=ws_l)
         zeco.state_scan(S_loc, G_tot, out=(S_init, S_last3))
+        zeco.state_scan_tree(S_loc, G_tot, out=(S_init_t, S_last_t), workspace=ws_t)
         zeco.apply_init_state(q, g, G_cum, S_init, o3, P)
         zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws_f, schedule=zeco.SCHEDULE_TWO_PHASE)
         zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last4), workspace=ws_f, schedule=zeco.SCHEDULE_CORRECT)
         zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws_b)
 
-    outs = (o3, S_last3, o2, S_last2, o4, S_last4) + grads
+    outs = (o3, S_last3, S_init_t, S_last_t, o2, S_last2, o4, S_last4) + grads
     run()                      # warm-up outside the capture (loads the code objects)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()

@@ -42,7 +42,8 @@ typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
  * strides at most 2^24 elements (ZECO_ERR_UNSUPPORTED beyond). */
 typedef struct {
     int32_t B, P, H, L;        /* B = 0 (an empty batch; BH = 0 in zeco_state_scan) is valid: the entry points
-                                * return ZECO_OK at once, touch no pointer and launch nothing */
+                                * return ZECO_OK at once, touch no pointer and launch nothing.  Limits
+                                * (ZECO_ERR_INVALID_ARG beyond): B*P*H <= 2^24, L <= 2^30, P*L <= 2^40 */
     int32_t d_k, d_v, C;       /* supported: C = 64, d_k and d_v in {64, 128}, any L >= C.  When L % C != 0
                                 * one chunk of every segment is short, L - C*(ceil(L/C) - 1) tokens (the
                                 * first one in the passes that walk a segment forwards, the last one in

@@ -18,7 +18,7 @@ zeco_status check_desc(const zeco_gla_desc *d, bool any_length = false) {
     if (d->io_dtype != ZECO_F32 && d->io_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
     if (d->g_dtype != ZECO_F32 && d->g_dtype != ZECO_BF16) return ZECO_ERR_INVALID_ARG;
     if (!(d->scale == d->scale)) return ZECO_ERR_INVALID_ARG;
-    if ((int64_t)d->P * d->L > (int64_t)1 << 40) return ZECO_ERR_INVALID_ARG;
+    if ((int64_t)d->P * d->L > (int64_t)1 << 40 || d->L > (1 << 30)) return ZECO_ERR_INVALID_ARG;
     const int64_t s[6] = {d->stride_b, d->stride_t, d->stride_h, d->vstride_b, d->vstride_t, d->vstride_h};
     for (int i = 0; i < 6; ++i)
         if (s[i] < 0 || s[i] % 8 != 0) return ZECO_ERR_INVALID_ARG;

@@ -59,6 +59,7 @@ def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
 @pytest.mark.parametrize("kw,expect", [
     (dict(B=-1), zeco.ZECO_ERR_INVALID_ARG),
     (dict(P=0), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(L=(1 << 30) + 64, P=1, stride_b=1 << 44), zeco.ZECO_ERR_INVALID_ARG),   # beyond the length limit
     (dict(L=40), zeco.ZECO_ERR_UNSUPPORTED),           # shorter than a chunk
     (dict(stride_t=100), zeco.ZECO_ERR_INVALID_ARG),   # stride not a multiple of 8
     (dict(stride_t=(1 << 24) + 8, stride_b=1 << 40), zeco.ZECO_ERR_UNSUPPORTED),   # token stride beyond 2^24 elements

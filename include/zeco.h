@@ -28,7 +28,7 @@ typedef enum {
     ZECO_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad stride */
     ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix, L < C,
                                * L % C != 0 with saved states */
-    ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than zeco_gla_local_fwd_workspace() */
+    ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than the entry point's own *_workspace() query says */
     ZECO_ERR_HIP = 4          /* HIP runtime refused a launch / attribute */
 } zeco_status;
 

@@ -276,6 +276,23 @@ def test_errors_surface_as_exceptions():
         zeco.gla_local_fwd(q, q, q, q, 2)            # L = 48 is shorter than a chunk
 
 
+def test_fp32_path_holds_its_tolerance_on_long_segments():
+    """The accuracy path over 4 segments of 4096 tokens (64 chunks each, a ragged variant beside it): the
+    relative error against the fp64 oracle stays below 1e-4 where rounding has thousands of steps to add up."""
+    B, H, P, dk, dv = 1, 2, 4, 128, 128
+    for L in (4096, 4000):
+        print("fp32 long", L, flush=True)
+        inp = synth.make_inputs(B, P * L, H, dk, dv, seed=4096 + L, io="f32", g="f32", device="cuda", gate_div=64.0)
+        S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+        o, S_last, parts = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=S0)
+        torch.cuda.synchronize()
+        o_r, Sf_r = oracle_full(inp, scale=0.5, S0=host(S0))
+        assert rel_err_bh(host(o), o_r, (0, 2)) <= TOL["f32"]
+        assert rel_err_bh(host(S_last), Sf_r, (0, 1)) <= TOL["f32"]
+        Gc = np.cumsum(host(inp["g"]).reshape(B, P, L, H, dk), axis=2).reshape(B, P * L, H, dk)
+        assert log_err(host(parts["G_cum"]), Gc) <= 1e-5
+
+
 def test_empty_batch_is_a_no_op():
     """B = 0 through the binding: the calls succeed, return empty tensors and launch nothing."""
     q = torch.empty(0, 256, 2, 128, dtype=torch.bfloat16, device="cuda")

@@ -293,6 +293,42 @@ def test_fp32_path_holds_its_tolerance_on_long_segments():
         assert log_err(host(parts["G_cum"]), Gc) <= 1e-5
 
 
+@pytest.mark.parametrize("per_head", [False, True])
+def test_strong_gates_up_to_the_documented_range(per_head):
+    """Log decays between -1.2 and -0.4 per token: up to 77 per chunk and channel, just inside the documented
+    range (below 80) of the direct form K / Lambda, whose largest factor is then e^77.  Forward by every route
+    and backward against the oracle; the correction dies out within the first chunk of a segment."""
+    B, H, P, L, dk, dv = 1, 3, 2, 256, 128, 128
+    print("strong gates", per_head, flush=True)
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=91, io="bf16", g="f32", device="cuda", per_head_gate=per_head)
+    gen = torch.Generator(device="cuda").manual_seed(92)
+    inp["g"] = -(0.4 + 0.8 * torch.rand(inp["g"].shape, generator=gen, device="cuda"))
+    inp["g"][:, 64:128] = -1.2                          # one chunk at the strongest decay in every channel
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    h = {n: host(t) for n, t in inp.items()}
+    if per_head:
+        h["g"] = np.repeat(h["g"][..., None], dk, axis=-1)
+    o_r, S_r = oracle.gla_recurrent(h["q"], h["k"], h["v"], h["g"], 0.5)
+    ref = oracle.gla_recurrent_bwd(h["q"], h["k"], h["v"], h["g"], host(dO), 0.5, None, None)
+    o, S_last, _ = zeco.segmented_fwd(q, k, v, g, P, scale=0.5)
+    outs = [o] + [zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, schedule=sc)[0]
+                  for sc in (zeco.SCHEDULE_TWO_PHASE, zeco.SCHEDULE_CORRECT)]
+    grads = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5)
+    torch.cuda.synchronize()
+    for x in outs:
+        assert torch.isfinite(x.float()).all()
+        assert rel_err_bh(host(x), o_r, (0, 2)) <= TOL["bf16"]
+    assert rel_err_bh(host(S_last), S_r, (0, 1)) <= TOL["bf16"]
+    for name_, x, r in zip(("dq", "dk", "dv"), grads[:3], ref[:3]):
+        assert rel_err_bh(host(x), r, (0, 2)) <= TOL["bf16"], name_
+    # dG is a sum of nearly cancelling terms (exactly zero at a segment's first token): with decays this strong
+    # the sum itself is small while the bf16 rounding noise of its terms is not, and the per-head layout adds up
+    # 128 channels of it - the bound here is 5e-2 instead of the 2e-2 that holds on the workloads' gates
+    dg_r = ref[3].sum(axis=-1) if per_head else ref[3]
+    assert rel_err_bh(host(grads[3]), dg_r, (0, 2)) <= (5e-2 if per_head else TOL["bf16"])
+
+
 def test_empty_batch_is_a_no_op():
     """B = 0 through the binding: the calls succeed, return empty tensors and launch nothing."""
     q = torch.empty(0, 256, 2, 128, dtype=torch.bfloat16, device="cuda")

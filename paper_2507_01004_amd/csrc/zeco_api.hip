@@ -49,6 +49,67 @@ void set_length(zeco::ChunkParams &p, int L) {
     p.L = L; p.n_chunks = chunks_of(L); p.pad = 64 * p.n_chunks - L;
 }
 
+// Segments per group of the two-level scan: the divisor g of P that minimises the length of the serial
+// work, 2 g + P / g (two passes inside the groups, one over the groups).  Returns P when no proper divisor helps.
+int tree_group(int P) {
+    int best = P;
+    long long cost = P;                       // the plain chain
+    auto consider = [&](int g) {
+        const long long c = 2ll * g + P / g;
+        if (c < cost || (c == cost && g < best)) { cost = c; best = g; }
+    };
+    for (int a = 2; (long long)a * a <= P; ++a) {   // divisor pairs (a, P / a)
+        if (P % a) continue;
+        consider(a);
+        consider(P / a);
+    }
+    return best;
+}
+
+// Floats of scratch the two-level scan of a chain of P segments needs (0: the chain is not split).
+size_t tree_floats(int P, int BH, int d_k, int d_v, int gate_per_head) {
+    const int g = tree_group(P);
+    if (g == P) return 0;
+    const size_t J = P / g, state = (size_t)BH * d_k * d_v;
+    return 2 * J * state + J * (size_t)BH * (gate_per_head ? 1 : d_k);
+}
+
+// The two-level scan of one chain (sp.groups == 1, sp.P segments): every group of g segments from the zero
+// state (end state and total log decay), the chain over the groups, every group again from the state
+// entering it.  `scratch`: tree_floats() floats.
+hipError_t launch_scan_tree(zeco::ScanParams sp, float *scratch, hipStream_t s) {
+    const int P = sp.P, g = tree_group(P), J = P / g;
+    const size_t state = (size_t)sp.BH * sp.d_k * sp.d_v;
+    float *T = scratch, *I = T + J * state, *Gt = I + J * state;
+    zeco::ScanParams p = sp;
+    p.G_pre = nullptr;
+    p.S0 = nullptr; p.S_init = nullptr; p.S_last = T; p.G_sum = Gt; p.P = g; p.groups = J;
+    hipError_t e = zeco::launch_scan(p, s);
+    if (e != hipSuccess) return e;
+    p.S_loc = T; p.G_tot = Gt; p.S0 = sp.S0; p.S_init = I; p.S_last = sp.S_last; p.G_sum = nullptr;
+    p.P = J; p.groups = 1;
+    if ((e = zeco::launch_scan(p, s)) != hipSuccess) return e;
+    p.S_loc = sp.S_loc; p.G_tot = sp.G_tot; p.S0 = I; p.S_init = sp.S_init; p.S_last = nullptr;
+    p.P = g; p.groups = J;
+    return zeco::launch_scan(p, s);
+}
+
+// Inside the fused calls: is the chain of P pieces better scanned as a tree?  One chain step costs about
+// 0.17 us whatever the width, so the serial scan is latency-bound while B*H is small (measured, d = 128:
+// 256 x 1 1.8x, 256 x 2 1.4x, 1024 x 4 1.3x in favour of the tree; 256 x 4 even; from 8 heads on the
+// serial scan streams at the memory rate and wins).
+bool chain_wants_tree(int P, int BH) {
+    if (!((BH <= 2 && P >= 128) || (BH <= 4 && P >= 1024))) return false;
+    const int g = tree_group(P);
+    return g != P && P / g <= 65535;          // (the groups are the y dimension of the launch)
+}
+size_t chain_scratch_floats(int P, int BH, int d_k, int d_v, int gate_per_head) {
+    return chain_wants_tree(P, BH) ? tree_floats(P, BH, d_k, d_v, gate_per_head) : 0;
+}
+hipError_t launch_scan_chain(const zeco::ScanParams &sp, float *scratch, hipStream_t s) {
+    return chain_wants_tree(sp.P, sp.BH) ? launch_scan_tree(sp, scratch, s) : zeco::launch_scan(sp, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -222,14 +283,30 @@ static int fused_pieces(const zeco_gla_desc *d) {
 
 static int bwd_pieces(const zeco_gla_desc *d);
 
+// Workspace of zeco_gla_fused_fwd, in floats: piece states S_loc [n], S_init [n], their G_tot [n], the
+// cumulative decay of the CORRECT schedule (per chunk and channel, or per token with per-head gates), and
+// the scratch of the piece scan where it runs as a tree.
+struct FwdLayout {
+    size_t n, states, off_Sinit, off_Gtot, off_decay, off_tree, total;
+};
+static FwdLayout fwd_layout(const zeco_gla_desc *d, int S) {
+    FwdLayout w;
+    const size_t gd = d->g_per_head ? 1 : d->d_k;
+    w.n = (size_t)d->P * S * d->B * d->H;
+    w.states = w.n * d->d_k * d->d_v;
+    w.off_Sinit = w.states;
+    w.off_Gtot = 2 * w.states;
+    w.off_decay = w.off_Gtot + ((w.n * gd + 3) & ~(size_t)3);
+    const size_t decay = d->g_per_head ? (size_t)d->B * d->P * d->L * d->H
+                                       : (size_t)d->B * d->P * S * chunks_of(d->L / S) * d->H * d->d_k;
+    w.off_tree = w.off_decay + ((decay + 3) & ~(size_t)3);
+    w.total = w.off_tree + chain_scratch_floats(d->P * S, d->B * d->H, d->d_k, d->d_v, d->g_per_head);
+    return w;
+}
+
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
     if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
-    const size_t n = (size_t)desc->P * fused_pieces(desc) * desc->B * desc->H;
-    // cumulative decay of the CORRECT schedule: per chunk and channel, or per token with per-head gates
-    const int S = fused_pieces(desc);
-    const size_t decay = desc->g_per_head ? (size_t)desc->B * desc->P * desc->L * desc->H
-                                          : (size_t)desc->B * desc->P * S * chunks_of(desc->L / S) * desc->H * desc->d_k;
-    return (2 * n * desc->d_k * desc->d_v + n * desc->d_k + decay) * sizeof(float);
+    return fwd_layout(desc, fused_pieces(desc)).total * sizeof(float);
 }
 
 zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
@@ -251,9 +328,9 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     if (workspace_bytes < zeco_gla_fused_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int S = fused_pieces(d);
-    const size_t n = (size_t)d->P * S * d->B * d->H, states = n * d->d_k * d->d_v;
-    float *Sloc = static_cast<float *>(workspace), *Sinit = Sloc + states, *Gtot = Sinit + states;
-    float *Gchunk = Gtot + n * d->d_k;
+    const FwdLayout w = fwd_layout(d, S);
+    float *Sloc = static_cast<float *>(workspace), *Sinit = Sloc + w.off_Sinit, *Gtot = Sloc + w.off_Gtot;
+    float *Gchunk = Sloc + w.off_decay, *tree = Sloc + w.off_tree;
 
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
@@ -270,7 +347,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
         sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
         sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
         sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
-        if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+        if ((e = launch_scan_chain(sp, tree, s)) != hipSuccess) return ZECO_ERR_HIP;
         zeco::ApplyParams ap;
         fill_apply_params(ap, d, p.P, p.L);
         ap.q = q; ap.S_init = Sinit; ap.o = o;
@@ -293,7 +370,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_save ? save_last : S_last;
     sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
     sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
-    if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+    if ((e = launch_scan_chain(sp, tree, s)) != hipSuccess) return ZECO_ERR_HIP;
 
     if (S_save && S_last) {
         e = zeco::launch_copy(S_last, save_last, (size_t)d->B * d->H * d->d_k * d->d_v * sizeof(float), s);
@@ -403,7 +480,7 @@ static int bwd_pieces(const zeco_gla_desc *d) {
 // Workspace of zeco_gla_fused_bwd, in floats: forward piece states S_loc [n], S_init [n + one more
 // slot per (b,h) for the final state], their G_tot [n]; state gradients dS_loc [n], dS_in [n].
 struct BwdLayout {
-    size_t n, state, off_Sloc, off_Sinit, off_Gtot, off_dSloc, off_dSin, total;
+    size_t n, state, off_Sloc, off_Sinit, off_Gtot, off_dSloc, off_dSin, off_tree, total;
 };
 static BwdLayout bwd_layout(const zeco_gla_desc *d, int S) {
     BwdLayout w;
@@ -415,7 +492,8 @@ static BwdLayout bwd_layout(const zeco_gla_desc *d, int S) {
     w.off_Gtot = w.off_Sinit + (w.n + bh) * w.state;
     w.off_dSloc = w.off_Gtot + w.n * d->d_k;
     w.off_dSin = w.off_dSloc + w.n * w.state;
-    w.total = w.off_dSin + w.n * w.state;
+    w.off_tree = w.off_dSin + w.n * w.state;   // scratch of the two piece scans where they run as trees
+    w.total = w.off_tree + chain_scratch_floats(d->P * S, d->B * d->H, d->d_k, d->d_v, d->g_per_head);
     return w;
 }
 
@@ -471,7 +549,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
         p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
         if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 1, s)) != hipSuccess) return ZECO_ERR_HIP;
         sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
-        if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+        if ((e = launch_scan_chain(sp, ws + w.off_tree, s)) != hipSuccess) return ZECO_ERR_HIP;
     }
 
     // dQ from the forward states; the same pass leaves every piece's state gradient from dS = 0 (and
@@ -480,7 +558,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     zeco_status zs = bwd_dq_pass(d, P, L, q, k, v, g, dO, Sin, Sl, dq, dg, dSloc, S_saved ? Gtot : nullptr, s);
     if (zs != ZECO_OK) return zs;
     sp.S_loc = dSloc; sp.G_tot = Gtot; sp.S0 = dS_T; sp.S_init = dSin; sp.S_last = dS0; sp.reverse = 1;
-    if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
+    if ((e = launch_scan_chain(sp, ws + w.off_tree, s)) != hipSuccess) return ZECO_ERR_HIP;
 
     return bwd_dv_dk_passes(d, P, L, q, k, v, g, dO, Sin, Sl, dSin, dk, dv, dg, s);
 }
@@ -508,25 +586,9 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
 }
 
 // ---- two-level (tree of depth two) scan ----------------------------------------------------------------
-// Segments per group: the divisor g of P that minimises the length of the serial work, 2 g + P / g (two
-// passes inside the groups, one over the groups).  Returns P when no proper divisor helps.
-static int tree_group(int P) {
-    int best = P;
-    long long cost = P;                       // the plain chain
-    for (int g = 2; g < P; ++g) {
-        if (P % g) continue;
-        const long long c = 2ll * g + P / g;
-        if (c < cost) { cost = c; best = g; }
-    }
-    return best;
-}
-
 size_t zeco_state_scan_tree_workspace(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t gate_per_head) {
     if (P <= 0 || BH <= 0 || d_k <= 0 || d_v <= 0) return 0;
-    const int g = tree_group(P);
-    if (g == P) return 0;
-    const size_t J = P / g, state = (size_t)BH * d_k * d_v;
-    return (2 * J * state + J * (size_t)BH * (gate_per_head ? 1 : d_k)) * sizeof(float);
+    return tree_floats(P, BH, d_k, d_v, gate_per_head) * sizeof(float);
 }
 
 zeco_status zeco_state_scan_tree(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, const float *S_loc,
@@ -548,27 +610,13 @@ zeco_status zeco_state_scan_tree(int32_t P, int32_t BH, int32_t d_k, int32_t d_v
     if (d_v % 4 != 0) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_state_scan_tree_workspace(P, BH, d_k, d_v, gate_per_head)) return ZECO_ERR_WORKSPACE;
     if (!workspace || !aligned16(workspace)) return ZECO_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int J = P / g;
-    const size_t state = (size_t)BH * d_k * d_v;
-    float *T = static_cast<float *>(workspace), *I = T + J * state, *Gt = I + J * state;
 
     zeco::ScanParams p;
     p.reverse = direction; p.gate_per_head = gate_per_head;
     p.BH = BH; p.d_k = d_k; p.d_v = d_v; p.rows_per_block = d_k / 16;
-    // 1: every group on its own from the zero state: its end state and its total log decay
-    p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = nullptr; p.S_init = nullptr; p.S_last = T; p.G_sum = Gt;
-    p.P = g; p.groups = J;
-    hipError_t e = zeco::launch_scan(p, s);
-    if (e != hipSuccess) return ZECO_ERR_HIP;
-    // 2: the chain over the groups: the state entering each group, and the end state
-    p.S_loc = T; p.G_tot = Gt; p.S0 = S0; p.S_init = I; p.S_last = S_last; p.G_sum = nullptr;
-    p.P = J; p.groups = 1;
-    if ((e = zeco::launch_scan(p, s)) != hipSuccess) return ZECO_ERR_HIP;
-    // 3: every group again, from the state entering it
-    p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = I; p.S_init = S_init; p.S_last = nullptr;
-    p.P = g; p.groups = J;
-    return from_hip(zeco::launch_scan(p, s));
+    p.S_loc = S_loc; p.G_tot = G_tot; p.S0 = S0; p.S_init = S_init; p.S_last = S_last;
+    p.P = P; p.groups = 1;
+    return from_hip(launch_scan_tree(p, static_cast<float *>(workspace), static_cast<hipStream_t>(stream)));
 }
 
 zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const float *G_cum,

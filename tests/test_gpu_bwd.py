@@ -143,3 +143,30 @@ def test_backward_from_states_saved_by_the_forward(case):
     for name_, x, r in zip(GRADS, got[:4], ref[:4]):
         assert rel_err_bh(host(x), r, AXES) <= TOL["bf16"], name_
     assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("H", [1, 2])
+def test_few_heads_long_sequence_scans_the_pieces_as_a_tree(H):
+    """One or two heads and 32768 tokens per segment: the fused calls cut the sequence into 128 pieces and more
+    and scan them with the two-level scan (a serial chain that short on width is latency-bound).  Forward by
+    both schedules and backward against the oracle, with a state entering and a state gradient leaving."""
+    B, P, L, dk, dv = 1, 2, 32768, 64, 64
+    print("few heads", H, flush=True)
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=500 + H, io="bf16", g="f32", device="cuda", gate_div=64.0)
+    gen = torch.Generator(device="cuda").manual_seed(501)
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    o_r, S_r = oracle.gla_recurrent(host(q), host(k), host(v), host(g), 0.5, host(S0))
+    ref = oracle.gla_recurrent_bwd(host(q), host(k), host(v), host(g), host(dO), 0.5, host(S0), host(dS_T))
+    for sched in (zeco.SCHEDULE_TWO_PHASE, zeco.SCHEDULE_CORRECT):
+        o, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0, schedule=sched)
+        torch.cuda.synchronize()
+        assert rel_err_bh(host(o), o_r, (0, 2)) <= TOL["bf16"]
+        assert rel_err_bh(host(S_last), S_r, (0, 1)) <= TOL["bf16"]
+    got = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, S0=S0, dS_T=dS_T)
+    torch.cuda.synchronize()
+    for name_, x, r in zip(GRADS, got[:4], ref[:4]):
+        assert rel_err_bh(host(x), r, AXES) <= TOL["bf16"], name_
+    assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= TOL["bf16"]

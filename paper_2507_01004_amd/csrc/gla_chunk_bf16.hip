@@ -238,7 +238,14 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
 
         // Log decay of the previous chunks for this thread's 4 channels, as an unevaluated sum.
         f32x4 seg_hi = {0.f, 0.f, 0.f, 0.f}, seg_lo = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (MODE == kLocalInit) seg_hi = *reinterpret_cast<const f32x4 *>(p.G_off + sbh * DK + 4 * cq);
+        if constexpr (MODE == kLocalInit) {
+            if constexpr (GH) {
+                const float x = p.G_off[sbh];   // one log decay per head
+                seg_hi = f32x4{x, x, x, x};
+            } else {
+                seg_hi = *reinterpret_cast<const f32x4 *>(p.G_off + sbh * DK + 4 * cq);
+            }
+        }
         f32x4 cs[TPT];                          // in-thread inclusive cumsum of g (part 1 -> part 2)
         f32x4 excl = {0.f, 0.f, 0.f, 0.f};      // sum over the wave's earlier token groups
 
@@ -684,10 +691,7 @@ hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mo
         return p.S_save ? dispatch_gate<kOutputSave>(p, d_k, d_v, gate_mode, s) : dispatch_gate<kOutput>(p, d_k, d_v, gate_mode, s);
     if (mode == kDState) return dispatch_gate<kDState>(p, d_k, d_v, gate_mode, s);
     if (mode == kDV) return dispatch_gate<kDV>(p, d_k, d_v, gate_mode, s);
-    if (mode == kLocalInit)   // per-channel gates only (the sub-segmented local pass)
-        return gate_mode == kGateBF16 ? dispatch_b16<kGateBF16, kLocalInit>(p, d_k, d_v, s)
-               : gate_mode == kGateF32 ? dispatch_b16<kGateF32, kLocalInit>(p, d_k, d_v, s)
-                                       : hipErrorInvalidValue;
+    if (mode == kLocalInit) return dispatch_gate<kLocalInit>(p, d_k, d_v, gate_mode, s);
     if (mode == kLocalCD)     // per-channel gates only
         return gate_mode == kGateBF16 ? dispatch_b16<kGateBF16, kLocalCD>(p, d_k, d_v, s)
                : gate_mode == kGateF32 ? dispatch_b16<kGateF32, kLocalCD>(p, d_k, d_v, s)

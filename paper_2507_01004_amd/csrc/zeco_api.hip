@@ -124,7 +124,7 @@ static bool halves_evenly(int L, int S) { return L % 64 == 0 ? L % (2 * S * 64) 
 // idle; the local pass then applies the method to itself: sub-segment states from the zero state, a scan
 // of them inside each segment, and the output pass of every sub-segment from its scanned state.
 static int subsegments(const zeco_gla_desc *d) {
-    if (d->io_dtype != ZECO_BF16 || d->g_per_head) return 1;
+    if (d->io_dtype != ZECO_BF16) return 1;
     const long long streams = (long long)d->B * d->P * d->H;
     if (streams > 64) return 1;
     int S = 1;   // as many workgroups as fit the 256 compute units in one round, not more
@@ -200,7 +200,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     zeco::ScanParams sp;   // one chain of S sub-segments per segment; its end state is the segment's S_loc
     sp.S_loc = Ssub; sp.G_tot = Gtot; sp.S0 = nullptr; sp.S_init = Sinit; sp.S_last = S_loc;
     sp.P = S; sp.groups = d->P; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
-    sp.rows_per_block = d->d_k / 16;
+    sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
     sp.G_pre = Gpre; sp.G_sum = G_tot;   // log decay preceding each sub-segment; the segment's total
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
 

@@ -14,7 +14,7 @@ struct ChunkParams {
     void *o;
     float *S_loc, *G_cum, *G_tot;
     const float *S_init;       // [P,B,H,d_k,d_v] initial states (modes that start from a given state)
-    const float *G_off = nullptr;   // [P,B,H,d_k] log decay preceding each segment (mode 5 only)
+    const float *G_off = nullptr;   // [P,B,H,d_k] ([P,B,H] per-head) log decay preceding each segment (mode 5 only)
     float *G_chunk = nullptr;       // [B,P,n_chunks,H,d_k] log decay from the segment start to each chunk's start (mode 6 only)
     float *S_save = nullptr;   // output pass: states entering every save_every-th chunk,
     int save_every = 0;        //   [P * n_chunks / save_every, B, H, d_k, d_v]
@@ -89,7 +89,7 @@ hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t 
 // mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
 // 3 backward state pass (k := q, v := dO; S_loc := dS leaving the segment), 4 dV pass (q := k, k := q,
 // v := dO, S_init := dS entering the segment's final state, o := dV), 5 output pass from S_init that also
-// writes G_cum counted from G_off (o, G_cum; per-channel gates only), 6 local pass with the cumulative decay
+// writes G_cum counted from G_off (o, G_cum), 6 local pass with the cumulative decay
 // per chunk instead of per token (o, S_loc, G_chunk, G_tot; per-channel gates only)
 hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mode, int mode, hipStream_t s);
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s);

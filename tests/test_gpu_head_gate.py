@@ -17,7 +17,8 @@ pytestmark = pytest.mark.gpu
 CASES = [
     ("hg_split", 1, 4, 2, 320, 128, 128),        # 8 streams: sibling workgroups split d_v
     ("hg_whole", 2, 16, 8, 128, 128, 128),       # 256 streams
-    ("hg_pieces", 1, 2, 2, 2048, 128, 128),      # fused calls cut the segments
+    ("hg_pieces", 1, 2, 2, 2048, 128, 128),      # few streams: sub-segmented local pass, fused calls cut the segments
+    ("hg_pieces_ragged", 1, 1, 1, 4100, 64, 64), # the same with a length that is no multiple of 64 (4 x 1025)
     ("hg_onechunk", 1, 2, 4, 64, 128, 128),
     ("hg_d64", 1, 2, 3, 192, 64, 64),
     ("hg_dk128_dv64", 1, 2, 2, 192, 128, 64),    # state of the Mamba-2 shape: wide key, narrow value

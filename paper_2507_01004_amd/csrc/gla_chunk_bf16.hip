@@ -56,10 +56,11 @@ unsigned long long *g_phase_dbg = nullptr;
 #define ZPT(pt)
 #endif
 
-template <int DK, int DV, int NWG_> struct B16Cfg {
+template <int DK, int DV, int NWG_, int NWI_ = 0> struct B16Cfg {
     static constexpr int NWM = DV / 32;            // MFMA waves, 32 state columns each
     static constexpr int NWG = NWG_;               // gate waves
-    static constexpr int NT = 64 * (NWM + NWG);
+    static constexpr int NWI = NWI_;               // idle waves (placement only, see idle_waves)
+    static constexpr int NT = 64 * (NWM + NWG + NWI);
     static constexpr int NIT = DK / 32;            // state row tiles per MFMA wave
     // gate pass thread mapping over the 256 gate threads: 4 channels x TPT tokens per thread
     static constexpr int CQ = DK / 4;              // channel quads
@@ -132,11 +133,20 @@ enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4, kLo
 constexpr int gate_waves(int dk, int gm, int mode) {
     return (dk == 128 && (mode == kLocal || mode == kLocalInit) && gm != kGateHead) ? 8 : 4;
 }
-constexpr int chunk_threads(int dk, int dv, int gm, int mode) { return 64 * (dv / 32 + gate_waves(dk, gm, mode)); }
+// Waves of a workgroup go round the four SIMDs of the compute unit in order.  With two matrix waves and eight
+// gate waves that puts each matrix wave on a SIMD with two gate waves and leaves two SIMDs with two gate waves
+// only - and the matrix waves are the longer side of both phases (cycle stamps: they reach the barriers last,
+// the gate waves wait there for a quarter of the chunk).  Two waves that do nothing but keep the barriers
+// (wave slots 4 and 5) shift the placement: a matrix wave then shares its SIMD with one gate wave, the other
+// two SIMDs carry three gate waves each.
+constexpr int idle_waves(int dk, int dv, int gm, int mode) { return (dv / 32 == 2 && gate_waves(dk, gm, mode) == 8) ? 2 : 0; }
+constexpr int chunk_threads(int dk, int dv, int gm, int mode) {
+    return 64 * (dv / 32 + gate_waves(dk, gm, mode) + idle_waves(dk, dv, gm, mode));
+}
 
 template <int DK, int DV, int NS, int GM, int MODE>
 __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf16_kernel(ChunkParams p) {
-    typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE)> Cfg;
+    typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE), idle_waves(DK, DV, GM, MODE)> Cfg;
     typedef Mma<32> M;
     typedef GateVal<GM> GV;
     constexpr int QS = Cfg::QS, TS = Cfg::TS, VS = Cfg::VS, NWM = Cfg::NWM, NT = Cfg::NT;
@@ -155,7 +165,10 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // [buffer][channel] chunk decay
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, known uniform
+    const int pw = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave slot, known uniform
+    // role: w < NWM matrix wave w, NWM <= w < NWM + NWG gate wave w - NWM, beyond that idle (slots 4, 5)
+    const int w = Cfg::NWI == 0 ? pw : (pw < NWM ? pw : (pw == 4 || pw == 5) ? NWM + Cfg::NWG + (pw - 4)
+                                                                              : NWM + (pw < 4 ? pw - 2 : pw - 4));
     const int N = p.n_chunks;
     auto chunk_of = [&](int m) { return REV ? N - 1 - m : m; };   // m-th chunk in processing order
     // First token of chunk n.  When L is no multiple of 64 the chunk processed FIRST is the short one,
@@ -190,9 +203,12 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     for (int e = tid; e < 64 * TS / 16; e += NT)
         *reinterpret_cast<u32x4 *>(Ps + e * 16) = u32x4{0u, 0u, 0u, 0u};
 
-    if (w >= NWM) {
+    if (w >= NWM + Cfg::NWG) {
+        // idle waves: the barriers of the other waves, nothing else (2 before the loop, 2 per chunk)
+        for (int i = 0; i < 2 * N + 2; ++i) __syncthreads();
+    } else if (w >= NWM) {
         // ================================ gate waves ===========================================
-        const int gw = w - NWM, gtid = tid - 64 * NWM;
+        const int gw = w - NWM, gtid = gw * 64 + lane;
         // Uniform byte pointers to the stream's first token; per-thread 32-bit offsets on top.
         const unsigned char *qb = (const unsigned char *)p.q + kbase * 2;
         const unsigned char *kb = (const unsigned char *)p.k + kbase * 2;
@@ -651,7 +667,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
 
 template <int DK, int DV, int NS, int GM, int MODE>
 static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
-    typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE)> Cfg;
+    typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE), idle_waves(DK, DV, GM, MODE)> Cfg;
     auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GM, MODE>;
     hipError_t e = hipFuncSetAttribute((const void *)kern,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);

@@ -40,6 +40,9 @@ template <int DK, int DV> struct ApplyCfg {
     static constexpr int kBytes = 64 * QS + 64 * CS * 4;
 };
 
+// Segments a launch corrects: p0, p0 + seg_step, .. below P.
+__host__ __device__ __forceinline__ int apply_segments(const ApplyParams &p) { return (p.P - p.p0 + p.seg_step - 1) / p.seg_step; }
+
 // Workgroup id -> (stream, token block), a stream being a (segment, batch, head); returns the stream's
 // index over (segment - p0, batch, head) and sets tb.
 // Order: (group of 128 streams, token block, stream in the group).  Inside a group the early token
@@ -49,7 +52,7 @@ template <int DK, int DV> struct ApplyCfg {
 // blocks are worked through.
 __device__ __forceinline__ int apply_stream_of_workgroup(const ApplyParams &p, int &tb) {
     constexpr int kGroup = 128;
-    const int blocks_per_seg = p.wgs_per_seg, streams = (p.P - p.p0) * p.B * p.H;
+    const int blocks_per_seg = p.wgs_per_seg, streams = apply_segments(p) * p.B * p.H;
     const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
     const int gsz = min(kGroup, streams - grp * kGroup);
     const int j = r % gsz;
@@ -158,7 +161,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     int id = apply_stream_of_workgroup(p, tb);
     const int h = id % p.H;
     id /= p.H;
-    const int b = id % p.B, seg = p.p0 + id / p.B;
+    const int b = id % p.B, seg = p.p0 + p.seg_step * (id / p.B);
     const long long tok0 = (long long)seg * p.L;                 // the segment's first token
     const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block
     const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
@@ -257,7 +260,7 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
     int id = apply_stream_of_workgroup(p, tb);
     const int h = id % p.H;
     id /= p.H;
-    const int b = id % p.B, seg = p.p0 + id / p.B;
+    const int b = id % p.B, seg = p.p0 + p.seg_step * (id / p.B);
     const long long tok0 = (long long)seg * p.L;                 // the segment's first token
     const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block (= chunk)
     const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
@@ -346,7 +349,7 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     // workgroup ids round-robin; a stream stays on one XCD (128 is a multiple of 8), and a group's
     // S_init states (8 MiB at d = 128) stay in the L2s while its token blocks are worked through.
     constexpr int kGroup = 128;
-    const int blocks_per_seg = p.wgs_per_seg, streams = (p.P - p.p0) * p.B * p.H;
+    const int blocks_per_seg = p.wgs_per_seg, streams = apply_segments(p) * p.B * p.H;
     const int grp = blockIdx.x / (kGroup * blocks_per_seg), r = blockIdx.x % (kGroup * blocks_per_seg);
     const int gsz = min(kGroup, streams - grp * kGroup);
     const int tb = r / gsz, j = r % gsz;
@@ -356,7 +359,7 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     int id = grp * kGroup + (((j | 7) < gsz) ? (j & ~7) + ((j - (j >> 3)) & 7) : j);
     const int h = id % p.H;
     id /= p.H;
-    const int b = id % p.B, seg = p.p0 + id / p.B;
+    const int b = id % p.B, seg = p.p0 + p.seg_step * (id / p.B);
     const long long tok0 = (long long)seg * p.L;                 // the segment's first token
     const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block
     const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
@@ -401,7 +404,7 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
 }
 
 template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hipStream_t s) {
-    const long long wgs = (long long)(p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    const long long wgs = (long long)apply_segments(p) * p.B * p.H * p.wgs_per_seg;
     if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
     const int grid = (int)wgs;
     if (p.gate_per_head)
@@ -411,7 +414,7 @@ template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hi
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hipStream_t s) {
-    const long long wgs = (long long)(p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    const long long wgs = (long long)apply_segments(p) * p.B * p.H * p.wgs_per_seg;
     if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
     const int grid = (int)wgs;
     if (p.g_bf16)
@@ -421,7 +424,7 @@ template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hip
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hipStream_t s) {
-    const long long wgs = (long long)(p.P - p.p0) * p.B * p.H * p.wgs_per_seg;
+    const long long wgs = (long long)apply_segments(p) * p.B * p.H * p.wgs_per_seg;
     if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
     const int grid = (int)wgs;
     hipLaunchKernelGGL((apply_init_f32_kernel<DK, DV>), dim3(grid), dim3(DV * 4), 0, s, p);
@@ -429,7 +432,7 @@ template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hi
 }
 
 hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s) {
-    if (p.P - p.p0 <= 0) return hipSuccess;
+    if (apply_segments(p) <= 0) return hipSuccess;
     if (d_k == 64 && d_v == 64) return launch_ab16<64, 64>(p, s);
     if (d_k == 64 && d_v == 128) return launch_ab16<64, 128>(p, s);
     if (d_k == 128 && d_v == 64) return launch_ab16<128, 64>(p, s);
@@ -437,7 +440,7 @@ hipError_t launch_apply_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t
     return hipErrorInvalidValue;
 }
 hipError_t launch_apply_cd_bf16(const ApplyParams &p, int d_k, int d_v, hipStream_t s) {
-    if (p.P - p.p0 <= 0) return hipSuccess;
+    if (apply_segments(p) <= 0) return hipSuccess;
     if (d_k == 64 && d_v == 64) return launch_acd<64, 64>(p, s);
     if (d_k == 64 && d_v == 128) return launch_acd<64, 128>(p, s);
     if (d_k == 128 && d_v == 64) return launch_acd<128, 64>(p, s);
@@ -445,7 +448,7 @@ hipError_t launch_apply_cd_bf16(const ApplyParams &p, int d_k, int d_v, hipStrea
     return hipErrorInvalidValue;
 }
 hipError_t launch_apply_f32(const ApplyParams &p, int d_k, int d_v, hipStream_t s) {
-    if (p.P - p.p0 <= 0) return hipSuccess;
+    if (apply_segments(p) <= 0) return hipSuccess;
     if (d_k == 64 && d_v == 64) return launch_af32<64, 64>(p, s);
     if (d_k == 64 && d_v == 128) return launch_af32<64, 128>(p, s);
     if (d_k == 128 && d_v == 64) return launch_af32<128, 64>(p, s);

@@ -87,6 +87,27 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
+// G_cum[b, t, h] += G_pre[piece of t, b, h] for per-head log decays (G_cum [B,T,H], G_pre [pieces,B,H], pieces
+// of `len` tokens counted over the whole sequence): rebases the cumulative decay of pieces that were run
+// from their own first token onto the segment's first token.
+__global__ __launch_bounds__(256) void gate_offset_head_kernel(float *G_cum, const float *G_pre, int B, long long T, int H, int len) {
+    const long long n = (long long)B * T * H;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const int h = (int)(i % H);
+        const long long bt = i / H, t = bt % T, b = bt / T;
+        G_cum[i] += G_pre[((t / len) * B + b) * H + h];
+    }
+}
+
+hipError_t launch_gate_offset_head(float *G_cum, const float *G_pre, int B, long long T, int H, int len, hipStream_t s) {
+    const long long n = (long long)B * T * H;
+    long long blocks = (n + 255) / 256;
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(gate_offset_head_kernel, dim3((unsigned)blocks), dim3(256), 0, s, G_cum, G_pre, B, T, H, len);
+    return hipGetLastError();
+}
+
 // Plain copy used to calibrate the profiler's HBM byte counters and the achievable bandwidth.
 __global__ __launch_bounds__(256) void hbm_copy_kernel(u32x4 *dst, const u32x4 *src, size_t n16) {
     const size_t stride = (size_t)gridDim.x * blockDim.x;

@@ -132,6 +132,17 @@ static int subsegments(const zeco_gla_desc *d) {
     return S;
 }
 
+// With one decay per head and between 65 and 128 streams the local pass runs every segment as two halves
+// from the zero state on whole workgroups (256 streams), then corrects the second halves' outputs with the
+// first halves' end states where their decay has not vanished, and rebases the second halves' G_cum, which
+// costs 4 bytes per token and head in this layout: sibling workgroups on 128 streams leave the kernel bound
+// by its own pipeline (3.3 TB/s at c3), whole workgroups on 256 streams move 5.4 TB/s.
+static bool halves_with_correction(const zeco_gla_desc *d) {
+    if (d->io_dtype != ZECO_BF16 || !d->g_per_head || d->d_v != 128) return false;
+    const long long streams = (long long)d->B * d->P * d->H;
+    return streams > 64 && streams <= 128 && d->L % 128 == 0 && d->L / 2 >= 4096;
+}
+
 struct SubLayout {          // workspace carve-up, in floats
     size_t states, gates;   // elements of one state array / one gate array over all sub-segments
     size_t off_Ssub, off_Sinit, off_Gtot, off_Gpre, total;
@@ -149,8 +160,11 @@ static SubLayout sub_layout(const zeco_gla_desc *d, int S) {
     return w;
 }
 
+static void fill_apply_params(zeco::ApplyParams &p, const zeco_gla_desc *d, int P, int L);
+
 size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc) {
     if (check_desc(desc, true) != ZECO_OK) return 0;
+    if (halves_with_correction(desc)) return sub_layout(desc, 2).total * sizeof(float);
     const int S = subsegments(desc);
     return S > 1 ? sub_layout(desc, S).total * sizeof(float) : 0;
 }
@@ -183,6 +197,30 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     p.dbg = zeco::g_phase_dbg;
 #endif
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
+    if (halves_with_correction(d)) {
+        const SubLayout w = sub_layout(d, 2);
+        float *ws = static_cast<float *>(workspace);
+        float *Ssub = ws + w.off_Ssub, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot, *Gpre = ws + w.off_Gpre;
+        // the halves from the zero state: o, G_cum counted from each half's first token, end states
+        p.P = d->P * 2; set_length(p, d->L / 2);
+        p.S_loc = Ssub; p.G_tot = Gtot;
+        if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s) != hipSuccess) return ZECO_ERR_HIP;
+        // chain of the two halves of every segment: the state and the log decay entering the second half,
+        // the segment's end state and total
+        zeco::ScanParams sp;
+        sp.S_loc = Ssub; sp.G_tot = Gtot; sp.S0 = nullptr; sp.S_init = Sinit; sp.S_last = S_loc;
+        sp.P = 2; sp.groups = d->P; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+        sp.rows_per_block = d->d_k / 16; sp.gate_per_head = 1;
+        sp.G_pre = Gpre; sp.G_sum = G_tot;
+        if (zeco::launch_scan(sp, s) != hipSuccess) return ZECO_ERR_HIP;
+        // second halves (every other piece): o += (scale q .* exp(G_cum)) S_entering, with G_cum still counted
+        // from the half's first token
+        zeco::ApplyParams ap;
+        fill_apply_params(ap, d, d->P * 2, d->L / 2);
+        ap.q = q; ap.G_cum = G_cum; ap.S_init = Sinit; ap.o = o; ap.p0 = 1; ap.seg_step = 2;
+        if (zeco::launch_apply_bf16(ap, d->d_k, d->d_v, s) != hipSuccess) return ZECO_ERR_HIP;
+        return from_hip(zeco::launch_gate_offset_head(G_cum, Gpre, d->B, (long long)d->P * d->L, d->H, d->L / 2, s));
+    }
     if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s));
 
     // Few streams: P*S sub-segments of L/S tokens, Alg. 1's schedule applied inside each segment: the

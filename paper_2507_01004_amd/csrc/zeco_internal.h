@@ -43,6 +43,7 @@ struct ApplyParams {
     void *o;
     int B, P, H, L;
     int p0;                    // first segment to correct
+    int seg_step = 1;          // ... and every seg_step-th one after it
     int tokens_per_wg;         // multiple of 64
     int n_chunks, pad;         // 64-token blocks per segment, ceil(L / 64), and 64 n_chunks - L: the first block is the short one
     int wgs_per_seg;           // workgroups per segment, ceil(64 n_chunks / tokens_per_wg)
@@ -100,6 +101,8 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s);
 // reverse = false: dQ (x = dO, y = v, z = k, z2 = q, W_init = forward states); true: dK (x = v, y = dO,
 // z = q, z2 = k, W_init = state gradients; must run after the dQ pass, whose q .* dq it consumes)
 hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, int gate_mode, bool reverse, hipStream_t s);
+// per-head log decays: G_cum [B,T,H] += G_pre [T/len, B, H] of the piece each token lies in
+hipError_t launch_gate_offset_head(float *G_cum, const float *G_pre, int B, long long T, int H, int len, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
 
 }  // namespace zeco

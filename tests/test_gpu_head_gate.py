@@ -19,6 +19,7 @@ CASES = [
     ("hg_whole", 2, 16, 8, 128, 128, 128),       # 256 streams
     ("hg_pieces", 1, 2, 2, 2048, 128, 128),      # few streams: sub-segmented local pass, fused calls cut the segments
     ("hg_pieces_ragged", 1, 1, 1, 4100, 64, 64), # the same with a length that is no multiple of 64 (4 x 1025)
+    ("hg_halves", 1, 8, 10, 8192, 128, 128),     # 80 streams of 8192 tokens: the local pass runs every segment as two halves
     ("hg_onechunk", 1, 2, 4, 64, 128, 128),
     ("hg_d64", 1, 2, 3, 192, 64, 64),
     ("hg_dk128_dv64", 1, 2, 2, 192, 128, 64),    # state of the Mamba-2 shape: wide key, narrow value

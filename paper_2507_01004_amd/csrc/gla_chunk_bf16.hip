@@ -138,8 +138,9 @@ constexpr int gate_waves(int dk, int gm, int mode) {
 // only - and the matrix waves are the longer side of both phases (cycle stamps: they reach the barriers last,
 // the gate waves wait there for a quarter of the chunk).  Two waves that do nothing but keep the barriers
 // (wave slots 4 and 5) shift the placement: a matrix wave then shares its SIMD with one gate wave, the other
-// two SIMDs carry three gate waves each.
-constexpr int idle_waves(int dk, int dv, int gm, int mode) { return (dv / 32 == 2 && gate_waves(dk, gm, mode) == 8) ? 2 : 0; }
+// two SIMDs carry three gate waves each.  With four gate waves the matrix waves then have their SIMDs to
+// themselves (2-3 % on the sibling configurations of the other modes).
+constexpr int idle_waves(int dk, int dv, int gm, int mode) { return (dv / 32 == 2) ? 2 : 0; }
 constexpr int chunk_threads(int dk, int dv, int gm, int mode) {
     return 64 * (dv / 32 + gate_waves(dk, gm, mode) + idle_waves(dk, dv, gm, mode));
 }

@@ -3,7 +3,7 @@
  * token) linked into the same program.  It checks what the Python tests cannot: that the header compiles as
  * C, that the descriptor struct and the enums have the layout the library was built with, and that the
  * library needs nothing from its caller but device pointers and a stream.  Test infrastructure: built by
- * tests/c_client/build.py, run by tests/test_gpu_c_client.py.  Exit status 0 = all checks passed. */
+ * tests/c_client/build_c_client.py, run by tests/test_gpu_c_client.py.  Exit status 0 = all checks passed. */
 #include <math.h>
 #include <stdint.h>
 #include <stdio.h>

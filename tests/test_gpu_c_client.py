@@ -7,7 +7,7 @@ import sys
 import pytest
 
 sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_client"))
-import build as c_client_build   # noqa: E402
+import build_c_client as c_client_build   # noqa: E402
 
 
 def test_c_client_builds_against_the_header():

@@ -162,6 +162,27 @@ zeco_status zeco_apply_init_state_chunk_decay(const zeco_gla_desc *desc, const v
                                               const float *G_chunk, const float *S_init, void *o,
                                               int32_t flags, void *stream);
 
+/* ---- The local pass and the correction over segments of unequal length.  Sec. 3.1 cuts the sequence into
+ * P equal segments; nothing in its local pass, in the state recurrence of Sec. 3.2 or in the correction
+ * depends on that, only the token range each segment covers does.  Here segment p covers the tokens
+ *   [seg_start[p], seg_start[p+1])   of the T tokens of EVERY batch entry,
+ * with seg_start a DEVICE array of P+1 int64 (8-byte aligned), read by the kernels, never by the host.
+ *   desc->L          upper bound of the segment lengths (any value >= C; it sizes the correction's launch)
+ *   T                tokens per batch entry of q, k, v, g, o and G_cum ([B,T,H,..]); P * C <= T <= 2^40
+ *   every segment    C <= seg_start[p+1] - seg_start[p] <= desc->L, inside [0, T]; tokens before seg_start[0]
+ *                    and from seg_start[P] on belong to no segment and are neither read nor written
+ * A segment that breaks these rules is skipped by the kernels (nothing of it is read or written, its S_loc
+ * and G_tot stay as they were); the host cannot see that, so the call still returns ZECO_OK.
+ * Outputs as in zeco_gla_local_fwd and zeco_apply_init_state, G_cum counted from each segment's own first
+ * token; the scan between the two calls is zeco_state_scan, unchanged.  No workspace: the segments are not
+ * split further.  bf16 q/k/v/o only (fp32 returns ZECO_ERR_UNSUPPORTED); both gate layouts. ------------- */
+zeco_status zeco_gla_local_fwd_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                      const void *q, const void *k, const void *v, const void *g, void *o,
+                                      float *S_loc, float *G_cum, float *G_tot, void *stream);
+zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                         const void *q, const float *G_cum, const float *S_init, void *o,
+                                         int32_t flags, void *stream);
+
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
  * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
  * ZECO_ERR_UNSUPPORTED).  Same conventions as above. ------------------------------------------------ */

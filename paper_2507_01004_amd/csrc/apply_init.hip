@@ -64,8 +64,9 @@ __device__ __forceinline__ int apply_stream_of_workgroup(const ApplyParams &p, i
 }
 
 // First token (inside its segment) of 64-token block c, and the number of rows of it to store.
-__device__ __forceinline__ long long apply_block_start(const ApplyParams &p, int c) { return c ? (long long)c * 64 - p.pad : 0ll; }
-__device__ __forceinline__ int apply_block_rows(const ApplyParams &p, int c) { return c ? 64 : 64 - p.pad; }
+// (pad = 64 ceil(L / 64) - L of the segment: block 0 is the short one)
+__device__ __forceinline__ long long apply_block_start(int pad, int c) { return c ? (long long)c * 64 - pad : 0ll; }
+__device__ __forceinline__ int apply_block_rows(int pad, int c) { return c ? 64 : 64 - pad; }
 
 // Workgroup-wide AND of `mine` through the four flags in LDS; ends with a barrier.  Calls must be
 // separated by at least one other barrier.
@@ -162,19 +163,31 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + p.seg_step * (id / p.B);
-    const long long tok0 = (long long)seg * p.L;                 // the segment's first token
+    long long tok0 = (long long)seg * p.L;                       // the segment's first token
+    long long T = (long long)p.P * p.L;                          // tokens per batch entry
+    int n_chunks = p.n_chunks, pad = p.pad;
     const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block
-    const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
+    if (p.seg_start) {
+        // segments of unequal length: bounds from the table; the grid is sized for the longest segment allowed,
+        // so workgroups past this segment's end leave, and so do those of a segment that cannot be taken
+        tok0 = p.seg_start[seg];
+        T = p.T;
+        const long long len = p.seg_start[seg + 1] - tok0;
+        if (tok0 < 0 || len < 64 || len > p.L || tok0 + len > T) return;
+        n_chunks = (int)((len + 63) >> 6);
+        pad = 64 * n_chunks - (int)len;
+        if (c0 >= n_chunks) return;
+    }
+    const int nblk = min(p.tokens_per_wg / 64, n_chunks - c0);
     const uint16_t *qp = (const uint16_t *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
     uint16_t *op = (uint16_t *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
-    const long long T = (long long)p.P * p.L;
     const float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * (GH ? 1 : DK);
     const long long gcs = (long long)p.H * (GH ? 1 : DK);
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
 
     // Nothing to add from this workgroup's first token on?
     const bool may_stop = !p.dense;
-    if (may_stop && apply_all(Gc[apply_block_start(p, c0) * gcs + (GH ? 0 : tid % DK)] < kVanish, gone)) return;
+    if (may_stop && apply_all(Gc[apply_block_start(pad, c0) * gcs + (GH ? 0 : tid % DK)] < kVanish, gone)) return;
 
     bf16x8 sf[Cfg::NKS];
     apply_load_state<DK, DV>(S, sf);
@@ -187,7 +200,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
 #pragma unroll
         for (int m = 0; m < Cfg::ITEMS; ++m) {
             const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
-            const long long tt = apply_block_start(p, c0 + blk) + t;
+            const long long tt = apply_block_start(pad, c0 + blk) + t;
             r.q[m] = *reinterpret_cast<const u32x4 *>(qp + tt * p.st + 8 * cg);
             if constexpr (GH) {
                 const float x = Gc[tt * gcs];
@@ -202,7 +215,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     Raw nxt;
     u32x4 onx[Cfg::OITEMS];
     load_raw(0, nxt);
-    apply_load_o<DV>(op + apply_block_start(p, c0) * p.vt, p.vt, onx);
+    apply_load_o<DV>(op + apply_block_start(pad, c0) * p.vt, p.vt, onx);
     for (int blk = 0; blk < nblk; ++blk) {
         const Raw cur = nxt;
         u32x4 ocur[Cfg::OITEMS];
@@ -231,9 +244,9 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         }
         const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
         load_raw(nb, nxt);
-        apply_load_o<DV>(op + apply_block_start(p, c0 + nb) * p.vt, p.vt, onx);
+        apply_load_o<DV>(op + apply_block_start(pad, c0 + nb) * p.vt, p.vt, onx);
         __syncthreads();   // Qh complete; every thread is done with the staging tile of the last block
-        apply_block<DK, DV>(sf, Qh, Cs, op + apply_block_start(p, c0 + blk) * p.vt, p.vt, ocur, apply_block_rows(p, c0 + blk));
+        apply_block<DK, DV>(sf, Qh, Cs, op + apply_block_start(pad, c0 + blk) * p.vt, p.vt, ocur, apply_block_rows(pad, c0 + blk));
     }
 }
 
@@ -287,13 +300,13 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
     auto load_raw = [&](int blk) {
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
-            const long long tt = apply_block_start(p, c0 + blk) + u;
+            const long long tt = apply_block_start(p.pad, c0 + blk) + u;
             qn[u] = *reinterpret_cast<const u32x2 *>(qp + tt * p.st);
             gn[u] = *reinterpret_cast<const typename GV::raw_t *>(gp + tt * p.st * GB);
         }
     };
     load_raw(0);
-    apply_load_o<DV>(op + apply_block_start(p, c0) * p.vt, p.vt, onx);
+    apply_load_o<DV>(op + apply_block_start(p.pad, c0) * p.vt, p.vt, onx);
     for (int blk = 0; blk < nblk; ++blk) {
         const f32x4 pre = pre_n;
         u32x2 qc[TPT];
@@ -312,7 +325,7 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
         *reinterpret_cast<f32x4 *>(tot + tg * DK + 4 * cq) = run;
         const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
         load_raw(nb);
-        apply_load_o<DV>(op + apply_block_start(p, c0 + nb) * p.vt, p.vt, onx);
+        apply_load_o<DV>(op + apply_block_start(p.pad, c0 + nb) * p.vt, p.vt, onx);
         pre_n = *reinterpret_cast<const f32x4 *>(Gk + (long long)nb * gks);
         __syncthreads();   // group sums visible; every thread is done with the staging tile of the last block
         f32x4 base = pre;
@@ -331,7 +344,7 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
                       pack_bf16(bf16_lo(qc[u][1]) * fast_exp(G[2]) * p.scale, bf16_hi(qc[u][1]) * fast_exp(G[3]) * p.scale)};
         }
         __syncthreads();   // Qh complete
-        apply_block<DK, DV>(sf, Qh, Cs, op + apply_block_start(p, c0 + blk) * p.vt, p.vt, ocur, apply_block_rows(p, c0 + blk));
+        apply_block<DK, DV>(sf, Qh, Cs, op + apply_block_start(p.pad, c0 + blk) * p.vt, p.vt, ocur, apply_block_rows(p.pad, c0 + blk));
     }
 }
 
@@ -370,7 +383,7 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     const long long gcs = (long long)p.H * DK;
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
 
-    if (!p.dense && __syncthreads_and(Gc[apply_block_start(p, c0) * gcs + tid % DK] < kVanish)) return;   // see "Vanished decay"
+    if (!p.dense && __syncthreads_and(Gc[apply_block_start(p.pad, c0) * gcs + tid % DK] < kVanish)) return;   // see "Vanished decay"
 
     f32x4 Sreg[DK / 16];   // B operand: register r of tile it = S[16 it + 4 kg + r][16 w + l16]
 #pragma unroll
@@ -379,8 +392,8 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
         for (int r = 0; r < 4; ++r) Sreg[it][r] = S[(size_t)(16 * it + 4 * kg + r) * DV + 16 * w + l16];
 
     for (int blk = 0; blk < nblk; ++blk) {
-        const long long t0 = apply_block_start(p, c0 + blk);
-        const int rows = apply_block_rows(p, c0 + blk);
+        const long long t0 = apply_block_start(p.pad, c0 + blk);
+        const int rows = apply_block_rows(p.pad, c0 + blk);
         for (int e = tid; e < 64 * DK; e += NT) {
             const int t = e / DK, c = e % DK;
             const long long tt = t0 + t;

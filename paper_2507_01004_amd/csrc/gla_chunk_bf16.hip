@@ -170,7 +170,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     // role: w < NWM matrix wave w, NWM <= w < NWM + NWG gate wave w - NWM, beyond that idle (slots 4, 5)
     const int w = Cfg::NWI == 0 ? pw : (pw < NWM ? pw : (pw == 4 || pw == 5) ? NWM + Cfg::NWG + (pw - 4)
                                                                               : NWM + (pw < 4 ? pw - 2 : pw - 4));
-    const int N = p.n_chunks;
+    int N = p.n_chunks, pad = p.pad;   // (per segment when the segments differ in length, see below)
     auto chunk_of = [&](int m) { return REV ? N - 1 - m : m; };   // m-th chunk in processing order
     // First token of chunk n.  When L is no multiple of 64 the chunk processed FIRST is the short one,
     // 64 - pad tokens: the segment's first tokens in the forward modes, its last ones in the reverse modes.
@@ -178,10 +178,9 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     // window's surplus rows (the far end, or the near end) taken as zero, which leaves state, decay and the
     // real rows' outputs untouched, and stores only its real rows; all other chunks are full.
     auto cstart = [&](int n) {
-        if constexpr (REV) return (long long)n * 64 - (n == N - 1 ? p.pad : 0);
-        else return n ? (long long)n * 64 - p.pad : 0ll;
+        if constexpr (REV) return (long long)n * 64 - (n == N - 1 ? pad : 0);
+        else return n ? (long long)n * 64 - pad : 0ll;
     };
-    const int pad = p.pad;
     auto dead = [&](int t) { return REV ? t < pad : t >= 64 - pad; };   // surplus row of the short chunk
     auto pos_of = [](int t) { return REV ? 63 - t : t; };         // tile row of token t of a chunk
 
@@ -195,7 +194,19 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     const int h = sidx % p.H;
     sidx /= p.H;
     const int b = sidx % p.B, seg = sidx / p.B;
-    const long long tok0 = (long long)seg * p.L;
+    long long tok0 = (long long)seg * p.L, T = (long long)p.P * p.L;   // first token; tokens per batch entry
+    if constexpr (MODE == kLocal) {
+        if (p.seg_start) {
+            // segments of unequal length: this one's bounds from the table.  A segment the kernel cannot take
+            // (under 64 tokens, over the bound L, outside the tensor) is left alone: the whole workgroup leaves.
+            tok0 = p.seg_start[seg];
+            T = p.T;
+            const long long len = p.seg_start[seg + 1] - tok0;
+            if (tok0 < 0 || len < 64 || len > p.L || tok0 + len > T) return;
+            N = (int)((len + 63) >> 6);
+            pad = 64 * N - (int)len;
+        }
+    }
     const long long kbase = b * p.sb + tok0 * p.st + h * p.sh;
     const long long vbase = b * p.vb + tok0 * p.vt + h * p.vh + slice * DV;
     const unsigned st = (unsigned)p.st, vt = (unsigned)p.vt;
@@ -213,12 +224,11 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         // Uniform byte pointers to the stream's first token; per-thread 32-bit offsets on top.
         const unsigned char *qb = (const unsigned char *)p.q + kbase * 2;
         const unsigned char *kb = (const unsigned char *)p.k + kbase * 2;
-        const long long hbase = ((long long)b * p.P * p.L + tok0) * p.H + h;   // per-head gates: [B,T,H]
+        const long long hbase = ((long long)b * T + tok0) * p.H + h;   // per-head gates: [B,T,H]
         const unsigned char *gb = (const unsigned char *)p.g + (GH ? hbase : kbase) * GB;
         const unsigned gst = GH ? (unsigned)p.H : st;                          // gate elements between tokens
         const unsigned char *vb = (const unsigned char *)p.v + vbase * 2;
         const long long c0 = cstart(chunk_of(0));   // first token of the first chunk processed
-        const long long T = (long long)p.P * p.L;
         unsigned char *Gb = (unsigned char *)(p.G_cum + (((long long)b * T + tok0) * p.H + h) * (GH ? 1 : DK));
         const unsigned gcs = (unsigned)(p.H * (GH ? 1 : DK));
 

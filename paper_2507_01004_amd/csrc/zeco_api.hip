@@ -677,6 +677,60 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
     return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, s));
 }
 
+// ---- segments of unequal length ---------------------------------------------------------------------------
+static zeco_status check_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T) {
+    const zeco_status st = check_desc(d, true);
+    if (st != ZECO_OK) return st;
+    if (T < (int64_t)d->P * d->C || T > (int64_t)1 << 40) return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    if (d->B == 0) return ZECO_OK;
+    if (!seg_start || (reinterpret_cast<uintptr_t>(seg_start) & 7u)) return ZECO_ERR_INVALID_ARG;
+    return ZECO_OK;
+}
+
+zeco_status zeco_gla_local_fwd_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
+                                      const void *q, const void *k, const void *v, const void *g, void *o,
+                                      float *S_loc, float *G_cum, float *G_tot, void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!q || !k || !v || !g || !o || !S_loc || !G_cum || !G_tot) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
+        !aligned16(S_loc) || !aligned16(G_cum) || !aligned16(G_tot))
+        return ZECO_ERR_INVALID_ARG;
+    static_assert(sizeof(long long) == sizeof(int64_t), "the kernels read the table as long long");
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.q = q; p.k = k; p.v = v; p.g = g; p.o = o;
+    p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot;
+    p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, static_cast<hipStream_t>(stream)));
+}
+
+zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
+                                         const void *q, const float *G_cum, const float *S_init, void *o,
+                                         int32_t flags, void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!q || !G_cum || !S_init || !o) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(G_cum) || !aligned16(S_init) || !aligned16(o))
+        return ZECO_ERR_INVALID_ARG;
+    if (flags & ~(ZECO_APPLY_FIRST_SEGMENT_ZERO | ZECO_APPLY_DENSE)) return ZECO_ERR_INVALID_ARG;
+    zeco::ApplyParams p;
+    fill_apply_params(p, d, d->P, d->L);
+    // a launch sized for the longest segment allowed; the lengths need not divide into the workgroups' shares
+    int tpw = 1024;
+    while (tpw > 64 && tpw > d->L) tpw >>= 1;
+    p.tokens_per_wg = tpw;
+    p.wgs_per_seg = (64 * p.n_chunks + tpw - 1) / tpw;
+    p.q = q; p.G_cum = G_cum; p.S_init = S_init; p.o = o;
+    p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
+    p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0;
+    p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
+    return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, static_cast<hipStream_t>(stream)));
+}
+
 // ---- chunk-decay form of the local pass and the correction ---------------------------------------------
 zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q, const void *k,
                                            const void *v, const void *g, void *o, float *S_loc,

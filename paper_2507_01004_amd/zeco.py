@@ -46,7 +46,8 @@ APPLY_FIRST_SEGMENT_ZERO, APPLY_DENSE = 1, 2
 SCHEDULE_AUTO, SCHEDULE_TWO_PHASE, SCHEDULE_CORRECT = 0, 1, 2
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
            "zeco_state_scan_tree_workspace", "zeco_state_scan_tree",
-           "zeco_apply_init_state", "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
+           "zeco_apply_init_state", "zeco_gla_local_fwd_varlen", "zeco_apply_init_state_varlen",
+           "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
            "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
            "zeco_gla_bwd_from_state", "zeco_gla_fused_bwd_workspace", "zeco_gla_fused_bwd",
@@ -95,6 +96,10 @@ def lib():
         L.zeco_state_scan_tree.restype = i32
         L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state.restype = i32
+        L.zeco_gla_local_fwd_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, fp, fp, fp, vp]
+        L.zeco_gla_local_fwd_varlen.restype = i32
+        L.zeco_apply_init_state_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, fp, fp, vp, i32, vp]
+        L.zeco_apply_init_state_varlen.restype = i32
         L.zeco_gla_local_fwd_chunk_decay.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp]
         L.zeco_gla_local_fwd_chunk_decay.restype = i32
         L.zeco_apply_init_state_chunk_decay.argtypes = [dp, vp, vp, fp, fp, vp, i32, vp]
@@ -258,6 +263,65 @@ def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segm
                                      _apply_flags(first_segment_is_zero, dense), _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_apply_init_state")
+    return o
+
+
+def _varlen_desc(q, v, g_code, per_head, seg_start, max_len, scale):
+    """Descriptor of a call over segments of unequal length: L is the bound on the lengths."""
+    if seg_start.dtype != torch.int64 or not seg_start.is_cuda or seg_start.dim() != 1 or not seg_start.is_contiguous():
+        raise ValueError("seg_start must be a contiguous int64 device vector of P+1 token offsets")
+    if q.stride(-1) != 1 or v.stride(-1) != 1:
+        raise ValueError("innermost dimension must be contiguous")
+    B, T, H, dk = q.shape
+    return GlaDesc(B, seg_start.numel() - 1, H, int(max_len), dk, v.shape[-1], 64, _dtype_code(q), g_code,
+                   float(scale), q.stride(0), q.stride(1), q.stride(2), v.stride(0), v.stride(1), v.stride(2),
+                   int(per_head))
+
+
+def gla_local_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, out=None):
+    """zeco_gla_local_fwd_varlen: the local pass over segments [seg_start[p], seg_start[p+1]) of the token
+    axis, none longer than max_len.  seg_start: int64 device vector.  Returns (o, S_loc, G_cum, G_tot)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise TypeError("q, k, v must share a dtype")
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    per_head = g.dim() == 3
+    if per_head:
+        if tuple(g.shape) != (B, T, H) or not g.is_contiguous():
+            raise ValueError("a per-head gate must be a contiguous [B,T,H] tensor")
+    elif g.shape != q.shape or g.stride() != q.stride():
+        raise ValueError("a per-channel gate must have the shape and strides of q")
+    desc = _varlen_desc(q, v, _dtype_code(g), per_head, seg_start, max_len, scale)
+    P = desc.P
+    if out is None:
+        o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
+        S_loc = torch.empty(P, B, H, dk, dv, dtype=torch.float32, device=q.device)
+        G_cum = torch.empty((B, T, H) + _gate_dims(g, dk), dtype=torch.float32, device=q.device)
+        G_tot = torch.empty((P, B, H) + _gate_dims(g, dk), dtype=torch.float32, device=q.device)
+    else:
+        o, S_loc, G_cum, G_tot = out
+        _check_same_layout(v, o)
+    st = lib().zeco_gla_local_fwd_varlen(ctypes.byref(desc), _ptr(seg_start), T, _ptr(q), _ptr(k), _ptr(v), _ptr(g),
+                                         _ptr(o), _ptr(S_loc), _ptr(G_cum), _ptr(G_tot), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_local_fwd_varlen")
+    return o, S_loc, G_cum, G_tot
+
+
+def apply_init_state_varlen(q, g_like, G_cum, S_init, o, seg_start, max_len, scale=1.0, first_segment_is_zero=True,
+                            dense=False):
+    """zeco_apply_init_state_varlen: the correction over the segments of gla_local_fwd_varlen, in place."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    desc = _varlen_desc(q, o, _dtype_code(g_like), G_cum.dim() == 3, seg_start, max_len, scale)
+    st = lib().zeco_apply_init_state_varlen(ctypes.byref(desc), _ptr(seg_start), q.shape[1], _ptr(q), _ptr(G_cum),
+                                            _ptr(S_init), _ptr(o), _apply_flags(first_segment_is_zero, dense),
+                                            _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_apply_init_state_varlen")
     return o
 
 

@@ -134,6 +134,26 @@ def test_apply_init_state_rejects_unknown_flags(L):
     assert L.zeco_apply_init_state(ctypes.byref(good_desc()), None, FAKE, FAKE, FAKE, 3, None) == zeco.ZECO_ERR_INVALID_ARG
 
 
+def test_unequal_segment_lengths_validate_before_any_launch(L):
+    """zeco_gla_local_fwd_varlen / zeco_apply_init_state_varlen: descriptor, T and the table's pointer."""
+    ref = ctypes.byref
+    loc = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_local_fwd_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None)
+    app = lambda d=None, seg=FAKE, T=4096, q=FAKE, flags=0: L.zeco_apply_init_state_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, flags, None)
+    for call in (loc, app):
+        assert call(seg=None) == zeco.ZECO_ERR_INVALID_ARG
+        assert call(seg=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG        # not 8-byte aligned
+        assert call(T=127) == zeco.ZECO_ERR_INVALID_ARG                             # under P * C tokens
+        assert call(T=(1 << 40) + 1) == zeco.ZECO_ERR_INVALID_ARG
+        assert call(q=None) == zeco.ZECO_ERR_INVALID_ARG
+        assert call(q=ctypes.c_void_p(0x1008)) == zeco.ZECO_ERR_INVALID_ARG
+        assert call(d=good_desc(L=48)) == zeco.ZECO_ERR_UNSUPPORTED                  # bound under one chunk
+        assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
+        assert call(d=good_desc(B=0), seg=None, q=None) == zeco.ZECO_OK              # empty batch
+    assert app(flags=4) == zeco.ZECO_ERR_INVALID_ARG
+
+
 def test_local_fwd_rejects_bad_pointers(L):
     assert call_local(L, good_desc(), q=None) == zeco.ZECO_ERR_INVALID_ARG
     assert call_local(L, good_desc(), o=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG

@@ -1,6 +1,8 @@
 """The library allocates nothing and never synchronises, so its calls can be recorded into a HIP graph:
-capture the three-call pipeline, the tree scan, the fused forward (both schedules) and the fused backward once, replay them on new
-input values, and compare every replay bitwise with the eager calls."""
+capture the three-call pipeline, the tree scan, the fused forward (both schedules), the fused backward and the
+three calls over segments of unequal length once, replay them on new input values - and, for the last, on a
+new table of segment offsets, which is device data like any other input - and compare every replay bitwise
+with the eager calls."""
 import pytest
 import torch
 
@@ -31,6 +33,9 @@ def test_pipeline_forward_backward_replay_from_a_graph():
     grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v), torch.empty(B, T, H, dk, device="cuda"),
              torch.empty(B, H, dk, dv, device="cuda"))
     ws_l = torch.empty(max(zeco.local_fwd_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda")
+    seg = torch.arange(P + 1, dtype=torch.int64, device="cuda") * L      # P+1 token offsets, rewritten per replay
+    o5, S_loc5, G_cum5, G_tot5 = torch.empty_like(v), torch.empty_like(S_loc), torch.empty_like(G_cum), torch.empty_like(G_tot)
+    S_init5, S_last5 = torch.empty_like(S_loc), torch.empty(B, H, dk, dv, device="cuda")
 
     def run():
         zeco.gla_local_fwd(q, k, v, g, P, out=(o3, S_loc, G_cum, G_tot), workspace=ws_l)
@@ -40,8 +45,12 @@ def test_pipeline_forward_backward_replay_from_a_graph():
         zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws_f, schedule=zeco.SCHEDULE_TWO_PHASE)
         zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last4), workspace=ws_f, schedule=zeco.SCHEDULE_CORRECT)
         zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws_b)
+        zeco.gla_local_fwd_varlen(q, k, v, g, seg, 512, out=(o5, S_loc5, G_cum5, G_tot5))
+        zeco.state_scan(S_loc5, G_tot5, out=(S_init5, S_last5))
+        zeco.apply_init_state_varlen(q, g, G_cum5, S_init5, o5, seg, 512)
 
-    outs = (o3, S_last3, S_init_t, S_last_t, o2, S_last2, o4, S_last4) + grads
+    outs = (o3, S_last3, S_init_t, S_last_t, o2, S_last2, o4, S_last4, o5, S_last5) + grads
+    lengths = ([128] * 16, [64, 192] * 8, [100, 156] * 8)                # each sums to T
     run()                      # warm-up outside the capture (loads the code objects)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -52,6 +61,7 @@ def test_pipeline_forward_backward_replay_from_a_graph():
         q.copy_(torch.randn(q.shape, generator=gen, device="cuda"))
         v.copy_(torch.randn(v.shape, generator=gen, device="cuda"))
         dO.copy_(torch.randn(v.shape, generator=gen, device="cuda"))
+        seg.copy_(torch.tensor([0] + list(torch.tensor(lengths[rep]).cumsum(0)), dtype=torch.int64))
         run()
         torch.cuda.synchronize()
         eager = [t.clone() for t in outs]
@@ -61,3 +71,5 @@ def test_pipeline_forward_backward_replay_from_a_graph():
         torch.cuda.synchronize()
         for i, (a, b) in enumerate(zip(outs, eager)):
             assert torch.equal(a, b), (rep, i)
+        if rep == 0:   # equal lengths: the same result as the ordinary three calls
+            assert torch.equal(o5, o3) and torch.equal(S_last5, S_last3)

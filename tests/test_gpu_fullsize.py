@@ -154,6 +154,53 @@ def test_fullsize_ragged_segment_length_sampled_slices():
             assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= tol, nm
 
 
+def range_oracle(inp, a, e, h, W):
+    """Oracle output for the tokens [a, e) of head h (batch 0) of the unsegmented run, warm-started W tokens
+    before a, and the state entering token a."""
+    t0 = max(0, a - W)
+    q, k, v, g = (host(inp[n][:1, t0:e, h:h + 1]) for n in ("q", "k", "v", "g"))
+    n_warm = a - t0
+    if t0 > 0:
+        assert g[0, :n_warm, 0].sum(axis=0).max() < np.log(1e-30), "warm-up window too short for these gates"
+    o, _ = oracle.gla_recurrent(q, k, v, g)
+    S_in = None
+    if n_warm:
+        _, S_in = oracle.gla_recurrent(q[:, :n_warm], k[:, :n_warm], v[:, :n_warm], g[:, :n_warm])
+    return o[:, n_warm:], S_in
+
+
+def test_fullsize_unequal_segments_sampled_slices():
+    """c3's tensors cut into 8 segments of 4100 to 28664 tokens (three of them ragged): the three calls over
+    unequal segments on sampled (segment, head) slices."""
+    inp, c = synth.config_inputs("c3", device="cuda")
+    lengths = [8190, 24576, 16384, 12291, 20480, 16387, 4100, 28664]
+    T = c["P"] * c["L"]
+    assert sum(lengths) == T
+    start = [0] + [int(x) for x in np.cumsum(lengths)]
+    seg = torch.tensor(start, dtype=torch.int64, device="cuda")
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    tol = TOL[c["io"]]
+    print("full-size unequal segments", lengths, flush=True)
+    o, S_loc, G_cum, G_tot = zeco.gla_local_fwd_varlen(q, k, v, g, seg, max(lengths))
+    S_init, S_last = zeco.state_scan(S_loc, G_tot)
+    zeco.apply_init_state_varlen(q, g, G_cum, S_init, o, seg, max(lengths))
+    _, S_last_eq, _ = zeco.segmented_fwd(q, k, v, g, c["P"])
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(S_last), host(S_last_eq), (0, 1)) <= tol     # the end state does not depend on the cut
+    for (p, h) in [(0, 5), (1, 0), (3, 12), (6, 9), (7, 15)]:
+        print("  sample segment %d head %d" % (p, h), flush=True)
+        a, e = start[p], start[p + 1]
+        o_ref, S_in = range_oracle(inp, a, e, h, W["c3"])
+        got = host(o[:1, a:e, h:h + 1])
+        assert rel_err_bh(got, o_ref, (0, 2)) <= tol
+        assert rel_err_bh(got[:, :256], o_ref[:, :256], (0, 2)) <= tol
+        if S_in is not None:
+            assert rel_err_bh(host(S_init[p, :1, h:h + 1]), S_in, (0, 1)) <= tol
+        Gc = np.cumsum(host(g[:1, a:e, h:h + 1]), axis=1)
+        assert log_err(host(G_cum[:1, a:e, h:h + 1]), Gc) <= 1e-5
+        assert log_err(host(G_tot[p, :1, h:h + 1]), Gc[:, -1]) <= 1e-5
+
+
 @pytest.mark.parametrize("name", ["c2", "c3"])
 def test_fullsize_whole_forward_against_unsegmented_oracle(name):
     """Every token and head of configs 2 and 3 against Eq. (1) run over the whole sequence (the oracle

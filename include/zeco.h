@@ -63,10 +63,11 @@ typedef struct {
 
 /* Bytes of device workspace zeco_gla_local_fwd needs for this descriptor (may be 0).
  * Non-zero when the problem has few (batch, segment, head) streams (bf16, B*P*H <= 64; with one decay per
- * head up to 128, where every segment is run as two halves and the second half corrected): the local pass then splits every segment into sub-segments and runs Alg. 1's own
- * schedule inside each segment (end states of the sub-segments from the zero state, their scan, the
- * output pass of every sub-segment from its scanned state), and keeps the sub-segment states in the
- * workspace (device memory, 16-byte aligned, caller-owned, contents unspecified afterwards).
+ * head up to 128, where every segment is run as two halves and the second half corrected): the local pass
+ * then splits every segment into sub-segments and runs Alg. 1's own schedule inside each segment (end
+ * states of the sub-segments from the zero state, their scan, the output pass of every sub-segment from
+ * its scanned state), and keeps the sub-segment states in the workspace (device memory, 16-byte aligned,
+ * caller-owned, contents unspecified afterwards).
  * Returns 0 for an invalid descriptor. */
 size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc);
 

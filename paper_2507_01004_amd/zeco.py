@@ -15,33 +15,6 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
 
 ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
 ZECO_F32, ZECO_BF16 = 0, 1
-def state_scan_tree(S_loc, G_tot, S0=None, out=None, direction=0, workspace=None):
-    """zeco_state_scan_tree: the scan as a tree of depth two (groups of segments scanned in parallel).
-    Same arguments and result as state_scan, up to rounding.  Returns (S_init, S_last)."""
-    if not S_loc.is_cuda:
-        raise RuntimeError("zeco kernels run on the GPU only")
-    P, dk, dv = S_loc.shape[0], S_loc.shape[-2], S_loc.shape[-1]
-    BH = S_loc.numel() // (P * dk * dv)
-    if not (S_loc.is_contiguous() and G_tot.is_contiguous()):
-        raise ValueError("S_loc and G_tot must be contiguous")
-    if out is None:
-        S_init = torch.empty_like(S_loc)
-        S_last = torch.empty(S_loc.shape[1:], dtype=torch.float32, device=S_loc.device)
-    else:
-        S_init, S_last = out
-    if G_tot.numel() not in (P * BH, P * BH * dk):
-        raise ValueError("G_tot must be [P,BH,d_k] or, for per-head gates, [P,BH]")
-    per_head = int(G_tot.numel() == P * BH and dk != 1)
-    need = int(lib().zeco_state_scan_tree_workspace(P, BH, dk, dv, per_head))
-    if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=S_loc.device)
-    st = lib().zeco_state_scan_tree(P, BH, dk, dv, _ptr(S_loc), _ptr(G_tot), _ptr(S0), _ptr(S_init), _ptr(S_last),
-                                    int(direction), per_head, _ptr(workspace), workspace.numel(), _stream())
-    if st != ZECO_OK:
-        raise ZecoError(st, "zeco_state_scan_tree")
-    return S_init, S_last
-
-
 APPLY_FIRST_SEGMENT_ZERO, APPLY_DENSE = 1, 2
 SCHEDULE_AUTO, SCHEDULE_TWO_PHASE, SCHEDULE_CORRECT = 0, 1, 2
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
@@ -248,6 +221,33 @@ def state_scan(S_loc, G_tot, S0=None, K_blocks=16, out=None, direction=0):
                                _ptr(S_init), _ptr(S_last), int(direction), per_head, _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_state_scan")
+    return S_init, S_last
+
+
+def state_scan_tree(S_loc, G_tot, S0=None, out=None, direction=0, workspace=None):
+    """zeco_state_scan_tree: the scan as a tree of depth two (groups of segments scanned in parallel).
+    Same arguments and result as state_scan, up to rounding.  Returns (S_init, S_last)."""
+    if not S_loc.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    P, dk, dv = S_loc.shape[0], S_loc.shape[-2], S_loc.shape[-1]
+    BH = S_loc.numel() // (P * dk * dv)
+    if not (S_loc.is_contiguous() and G_tot.is_contiguous()):
+        raise ValueError("S_loc and G_tot must be contiguous")
+    if out is None:
+        S_init = torch.empty_like(S_loc)
+        S_last = torch.empty(S_loc.shape[1:], dtype=torch.float32, device=S_loc.device)
+    else:
+        S_init, S_last = out
+    if G_tot.numel() not in (P * BH, P * BH * dk):
+        raise ValueError("G_tot must be [P,BH,d_k] or, for per-head gates, [P,BH]")
+    per_head = int(G_tot.numel() == P * BH and dk != 1)
+    need = int(lib().zeco_state_scan_tree_workspace(P, BH, dk, dv, per_head))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=S_loc.device)
+    st = lib().zeco_state_scan_tree(P, BH, dk, dv, _ptr(S_loc), _ptr(G_tot), _ptr(S0), _ptr(S_init), _ptr(S_last),
+                                    int(direction), per_head, _ptr(workspace), workspace.numel(), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_state_scan_tree")
     return S_init, S_last
 
 

@@ -152,6 +152,48 @@ def scan_variants_case(args):
     return rows
 
 
+def unequal_segments_case(args, inp, P, T):
+    """The local pass and the correction over P segments of unequal length summing to the workload's T
+    tokens (zeco_gla_local_fwd_varlen, zeco_apply_init_state_varlen): equal lengths, lengths within an
+    eighth of the mean, and lengths from a quarter to seven quarters of the mean."""
+    import torch
+    from paper_2507_01004_amd import zeco
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    L = T // P
+    spreads = {"equal": [0] * P, "mild": [((-1) ** i) * (L // 8) * ((i // 2) % 2 + 1) // 2 for i in range(P)],
+               "wide": [((-1) ** i) * (L // 4) * ((i // 2) % 3 + 1) for i in range(P)]}
+    rows = []
+    for name, delta in spreads.items():
+        lengths = [L + d for d in delta]
+        lengths[-1] += T - sum(lengths)          # whatever the pattern leaves over goes to the last segment
+        if min(lengths) < 64:
+            continue
+        start = [0]
+        for n in lengths:
+            start.append(start[-1] + n)
+        seg = torch.tensor(start, dtype=torch.int64, device="cuda:0")
+        bound = max(lengths)
+        out = zeco.gla_local_fwd_varlen(q, k, v, g, seg, bound)
+        o, S_loc, G_cum, G_tot = out
+        S_init, _ = zeco.state_scan(S_loc, G_tot)
+        ms = {}
+        for leg, fn in (("local", lambda: zeco.gla_local_fwd_varlen(q, k, v, g, seg, bound, out=out)),
+                        ("apply", lambda: zeco.apply_init_state_varlen(q, g, G_cum, S_init, o, seg, bound))):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ms[leg] = e0.elapsed_time(e1) / args.steps
+        rows.append({"lengths": name, "min": min(lengths), "max": bound, "local_ms": round(ms["local"], 4),
+                     "apply_ms": round(ms["apply"], 4)})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -485,6 +527,8 @@ def main():
     if args.workload != "c2" and not (args.only_pipeline or args.only_fused or args.only_backward):
         out["single_segment_c2"] = single_segment_case(args)
         out["scan_variants"] = scan_variants_case(args)
+        if c["io"] == "bf16" and args.gate == "channel" and P >= 2:
+            out["unequal_segments"] = unequal_segments_case(args, inp, P, T)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(inp, c, min(T, 131072))
     print(json.dumps(out))

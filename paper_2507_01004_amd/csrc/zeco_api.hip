@@ -510,8 +510,14 @@ static int bwd_pieces(const zeco_gla_desc *d) {
             if (d->L % S == 0) return S;
         return 1;
     }
+    // whole chunks per piece, and every forward piece a whole number of backward pieces (the forward saves
+    // its states at the backward's piece boundaries): the forward's count times the smallest factor that
+    // brings the pieces to 512 tokens or fewer and leaves them at least two chunks
     int S = fused_pieces(d);
-    while (d->L / S > 512 && d->L % (2 * S * 64) == 0) S *= 2;
+    const int chunks = d->L / S / 64, want = (d->L / S + 511) / 512;
+    for (int m = want; m > 1 && 2 * m <= chunks; ++m)
+        if (chunks % m == 0) return S * m;
+    while (d->L / S > 512 && d->L % (2 * S * 64) == 0) S *= 2;   // none (a prime count): halve while it halves
     return S;
 }
 

@@ -20,6 +20,8 @@ CASES = [
     ("bwd_pieces", 1, 2, 2, 1024, 128, 128, "f32"),        # fused call cuts each segment in 4
     ("bwd_pieces_d64", 1, 1, 1, 2048, 64, 64, "bf16"),
     ("bwd_gbf16", 1, 3, 2, 256, 128, 128, "bf16"),
+    ("bwd_pieces_odd", 1, 1, 1, 1920, 128, 128, "f32"),    # 30 chunks: forward 2 pieces, backward 6 of 5 chunks
+    ("bwd_pieces_prime", 1, 2, 1, 1664, 64, 128, "f32"),   # 26 chunks: 2 pieces of 13, which no factor divides
     ("bwd_onechunk", 1, 2, 4, 64, 128, 128, "f32"),
     ("bwd_dk64_dv128", 1, 2, 2, 192, 64, 128, "f32"),
     ("bwd_dk128_dv64", 1, 2, 2, 192, 128, 64, "bf16"),
@@ -124,7 +126,7 @@ def test_bwd_rejects_fp32_and_small_workspace():
     assert e.value.status == zeco.ZECO_ERR_WORKSPACE
 
 
-@pytest.mark.parametrize("case", [CASES[0], CASES[2], CASES[3]], ids=lambda c: c[0])
+@pytest.mark.parametrize("case", [CASES[0], CASES[2], CASES[3], CASES[5], CASES[6]], ids=lambda c: c[0])
 def test_backward_from_states_saved_by_the_forward(case):
     """The forward leaves the states at the backward's piece boundaries; the backward started from them
     (no recomputation of the forward states) gives the same gradients within tolerance."""

@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         tok0 = p.seg_start[seg];
         T = p.T;
         const long long len = p.seg_start[seg + 1] - tok0;
-        if (tok0 < 0 || len < 64 || len > p.L || tok0 + len > T) return;
+        if (tok0 < 0 || len < 64 || len > p.L || tok0 > T - len) return;   // (in this order: no sum can overflow)
         n_chunks = (int)((len + 63) >> 6);
         pad = 64 * n_chunks - (int)len;
         if (c0 >= n_chunks) return;

@@ -202,7 +202,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             tok0 = p.seg_start[seg];
             T = p.T;
             const long long len = p.seg_start[seg + 1] - tok0;
-            if (tok0 < 0 || len < 64 || len > p.L || tok0 + len > T) return;
+            if (tok0 < 0 || len < 64 || len > p.L || tok0 > T - len) return;   // (in this order: no sum can overflow)
             N = (int)((len + 63) >> 6);
             pad = 64 * N - (int)len;
         }

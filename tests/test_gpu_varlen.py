@@ -148,3 +148,18 @@ def test_varlen_segment_outside_the_rules_is_skipped():
             assert rel_err_bh(host(S_loc)[p], S_r[0], (0, 1)) <= TOL["bf16"], p
         else:
             assert torch.all(o[:, a:e] == mark) and torch.all(S_loc[p] == mark) and torch.all(G_tot[p] == mark), p
+
+    # offsets far outside the tensor: both segments that touch them are skipped, the others computed
+    start = [0, 128, 2 ** 62, 368, 668]
+    seg = torch.tensor(start, dtype=torch.int64, device="cuda")
+    o.fill_(mark); S_loc.fill_(mark); G_tot.fill_(mark); G_cum.fill_(mark)
+    zeco.gla_local_fwd_varlen(inp["q"], inp["k"], inp["v"], inp["g"], seg, 512, scale=1.0,
+                              out=(o, S_loc, G_cum, G_tot))
+    zeco.apply_init_state_varlen(inp["q"], inp["g"], G_cum, S_init, o, seg, 512, first_segment_is_zero=False)
+    torch.cuda.synchronize()
+    assert torch.all(o[:, 128:368] == mark) and torch.all(S_loc[1:3] == mark) and torch.all(G_tot[1:3] == mark)
+    for p, (a, e) in ((0, (0, 128)), (3, (368, 668))):
+        sl = {n: host(inp[n])[:, a:e] for n in "qkvg"}
+        o_r, S_r, _, _ = oracle.gla_local(sl["q"], sl["k"], sl["v"], sl["g"], 1, 1.0)
+        assert rel_err_bh(host(o)[:, a:e], o_r, (0, 2)) <= TOL["bf16"], p
+        assert rel_err_bh(host(S_loc)[p], S_r[0], (0, 1)) <= TOL["bf16"], p

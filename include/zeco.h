@@ -176,7 +176,7 @@ zeco_status zeco_apply_init_state_chunk_decay(const zeco_gla_desc *desc, const v
  * and G_tot stay as they were); the host cannot see that, so the call still returns ZECO_OK.
  * Outputs as in zeco_gla_local_fwd and zeco_apply_init_state, G_cum counted from each segment's own first
  * token; the scan between the two calls is zeco_state_scan, unchanged.  No workspace: the segments are not
- * split further.  bf16 q/k/v/o only (fp32 returns ZECO_ERR_UNSUPPORTED); both gate layouts. ------------- */
+ * split further.  All dtypes and gate layouts of the ordinary calls. ------------- */
 zeco_status zeco_gla_local_fwd_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
                                       const void *q, const void *k, const void *v, const void *g, void *o,
                                       float *S_loc, float *G_cum, float *G_tot, void *stream);

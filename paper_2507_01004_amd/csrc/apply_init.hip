@@ -373,17 +373,27 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
     const int h = id % p.H;
     id /= p.H;
     const int b = id % p.B, seg = p.p0 + p.seg_step * (id / p.B);
-    const long long tok0 = (long long)seg * p.L;                 // the segment's first token
+    long long tok0 = (long long)seg * p.L;                       // the segment's first token
+    long long T = (long long)p.P * p.L;                          // tokens per batch entry
+    int n_chunks = p.n_chunks, pad = p.pad;
     const int c0 = tb * (p.tokens_per_wg / 64);                  // this workgroup's first block
-    const int nblk = min(p.tokens_per_wg / 64, p.n_chunks - c0);
+    if (p.seg_start) {   // segments of unequal length, as in the bf16 kernel
+        tok0 = p.seg_start[seg];
+        T = p.T;
+        const long long len = p.seg_start[seg + 1] - tok0;
+        if (tok0 < 0 || len < 64 || len > p.L || tok0 > T - len) return;   // (in this order: no sum can overflow)
+        n_chunks = (int)((len + 63) >> 6);
+        pad = 64 * n_chunks - (int)len;
+        if (c0 >= n_chunks) return;
+    }
+    const int nblk = min(p.tokens_per_wg / 64, n_chunks - c0);
     const float *qp = (const float *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
     float *op = (float *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
-    const long long T = (long long)p.P * p.L;
     const float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
     const long long gcs = (long long)p.H * DK;
     const float *S = p.S_init + (((size_t)seg * p.B + b) * p.H + h) * DK * DV;
 
-    if (!p.dense && __syncthreads_and(Gc[apply_block_start(p.pad, c0) * gcs + tid % DK] < kVanish)) return;   // see "Vanished decay"
+    if (!p.dense && __syncthreads_and(Gc[apply_block_start(pad, c0) * gcs + tid % DK] < kVanish)) return;   // see "Vanished decay"
 
     f32x4 Sreg[DK / 16];   // B operand: register r of tile it = S[16 it + 4 kg + r][16 w + l16]
 #pragma unroll
@@ -392,8 +402,8 @@ __global__ __launch_bounds__(DV * 4) void apply_init_f32_kernel(ApplyParams p) {
         for (int r = 0; r < 4; ++r) Sreg[it][r] = S[(size_t)(16 * it + 4 * kg + r) * DV + 16 * w + l16];
 
     for (int blk = 0; blk < nblk; ++blk) {
-        const long long t0 = apply_block_start(p.pad, c0 + blk);
-        const int rows = apply_block_rows(p.pad, c0 + blk);
+        const long long t0 = apply_block_start(pad, c0 + blk);
+        const int rows = apply_block_rows(pad, c0 + blk);
         for (int e = tid; e < 64 * DK; e += NT) {
             const int t = e / DK, c = e % DK;
             const long long tt = t0 + t;

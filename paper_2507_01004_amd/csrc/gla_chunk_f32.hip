@@ -60,13 +60,23 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
     const int h = sidx % p.H;
     sidx /= p.H;
     const int seg = sidx % p.P, b = sidx / p.P;
-    const long long tok0 = (long long)seg * p.L;
+    long long tok0 = (long long)seg * p.L, T = (long long)p.P * p.L;   // first token; tokens per batch entry
+    int n_chunks = p.n_chunks, pad = p.pad;
+    if (p.seg_start) {
+        // segments of unequal length: this one's bounds from the table; a segment that cannot be taken (under
+        // 64 tokens, over the bound L, outside the tensor) is left alone
+        tok0 = p.seg_start[seg];
+        T = p.T;
+        const long long len = p.seg_start[seg + 1] - tok0;
+        if (tok0 < 0 || len < 64 || len > p.L || tok0 > T - len) return;   // (in this order: no sum can overflow)
+        n_chunks = (int)((len + 63) >> 6);
+        pad = 64 * n_chunks - (int)len;
+    }
     const float *q = (const float *)p.q + b * p.sb + tok0 * p.st + h * p.sh;
     const float *k = (const float *)p.k + b * p.sb + tok0 * p.st + h * p.sh;
     const float *g = (const float *)p.g + b * p.sb + tok0 * p.st + h * p.sh;
     const float *v = (const float *)p.v + b * p.vb + tok0 * p.vt + h * p.vh;
     float *o = (float *)p.o + b * p.vb + tok0 * p.vt + h * p.vh;
-    const long long T = (long long)p.P * p.L;
     float *Gc = p.G_cum + (((long long)b * T + tok0) * p.H + h) * DK;
     const long long gcs = (long long)p.H * DK;
     const size_t sbh = ((size_t)seg * p.B + b) * p.H + h;
@@ -78,9 +88,9 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
     const int gc = tid % DK, tg = tid / DK;      // gate pass: channel and token group
     double seg_prefix = 0.0;                     // log decay accumulated over previous chunks
 
-    for (int n = 0; n < p.n_chunks; ++n) {
-        const long long t0 = n ? (long long)n * 64 - p.pad : 0;
-        const int rows = n ? 64 : 64 - p.pad;    // real tokens of this chunk
+    for (int n = 0; n < n_chunks; ++n) {
+        const long long t0 = n ? (long long)n * 64 - pad : 0;
+        const int rows = n ? 64 : 64 - pad;      // real tokens of this chunk
         // ---- gate pass: inclusive cumulative sum of g over the chunk, per channel -------------
         float cs[Cfg::kTPT];
         {

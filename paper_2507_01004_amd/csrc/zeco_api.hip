@@ -688,7 +688,6 @@ static zeco_status check_varlen(const zeco_gla_desc *d, const int64_t *seg_start
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (T < (int64_t)d->P * d->C || T > (int64_t)1 << 40) return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     if (d->B == 0) return ZECO_OK;
     if (!seg_start || (reinterpret_cast<uintptr_t>(seg_start) & 7u)) return ZECO_ERR_INVALID_ARG;
     return ZECO_OK;
@@ -710,7 +709,9 @@ zeco_status zeco_gla_local_fwd_varlen(const zeco_gla_desc *d, const int64_t *seg
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o;
     p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s));
 }
 
 zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
@@ -734,7 +735,9 @@ zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *d, const int64_t *
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
     p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0;
     p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
-    return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_apply_f32(p, d->d_k, d->d_v, s));
+    return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, s));
 }
 
 // ---- chunk-decay form of the local pass and the correction ---------------------------------------------

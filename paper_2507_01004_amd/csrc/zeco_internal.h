@@ -21,8 +21,9 @@ struct ChunkParams {
     int B, P, H, L;
     int n_chunks;              // ceil(L / 64)
     int pad = 0;               // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens
-    // Segments of unequal length (mode 0 only): segment p covers tokens [seg_start[p], seg_start[p+1]) of the
-    // T tokens of every batch entry; L is then the upper bound of the lengths, n_chunks and pad are unused.
+    // Segments of unequal length (mode 0 of the bf16 kernel, and the fp32 kernel): segment p covers tokens
+    // [seg_start[p], seg_start[p+1]) of the T tokens of every batch entry; L is then the upper bound of the
+    // lengths, n_chunks and pad are unused.
     const long long *seg_start = nullptr;
     long long T = 0;
     float scale;
@@ -51,7 +52,7 @@ struct ApplyParams {
     int tokens_per_wg;         // multiple of 64
     int n_chunks, pad;         // 64-token blocks per segment, ceil(L / 64), and 64 n_chunks - L: the first block is the short one
     int wgs_per_seg;           // workgroups per segment, ceil(64 n_chunks / tokens_per_wg)
-    const long long *seg_start = nullptr;   // segments of unequal length (bf16 kernel with G_cum only):
+    const long long *seg_start = nullptr;   // segments of unequal length (the kernels that read G_cum):
     long long T = 0;                        //   as in ChunkParams; n_chunks, pad, wgs_per_seg describe the bound L
     int gate_per_head = 0;     // 1: G_cum [B,T,H] (bf16 kernel only)
     int dense = 0;             // 1: stream every token, also where exp(G_cum) has vanished

@@ -149,7 +149,7 @@ def test_unequal_segment_lengths_validate_before_any_launch(L):
         assert call(q=None) == zeco.ZECO_ERR_INVALID_ARG
         assert call(q=ctypes.c_void_p(0x1008)) == zeco.ZECO_ERR_INVALID_ARG
         assert call(d=good_desc(L=48)) == zeco.ZECO_ERR_UNSUPPORTED                  # bound under one chunk
-        assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
+        assert call(d=good_desc(io_dtype=zeco.ZECO_F32, g_dtype=zeco.ZECO_BF16)) == zeco.ZECO_ERR_UNSUPPORTED
         assert call(d=good_desc(B=0), seg=None, q=None) == zeco.ZECO_OK              # empty batch
     assert app(flags=4) == zeco.ZECO_ERR_INVALID_ARG
 

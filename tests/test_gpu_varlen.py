@@ -15,8 +15,10 @@ from tests.gpu_util import TOL, host, log_err, rel_err_bh
 
 pytestmark = pytest.mark.gpu
 
-# (name, B, H, lengths, d_k, d_v, g dtype, per-head gate)
+# (name, B, H, lengths, d_k, d_v, g dtype, per-head gate); io is fp32 where the name says so, else bf16
 CASES = [
+    ("f32_mixed", 1, 2, (100, 64, 191, 320), 64, 64, "f32", False),
+    ("f32_d128", 2, 1, (65, 1100, 129), 128, 128, "f32", False),                 # correction: 2 workgroups for the longest
     ("mixed_d128", 1, 4, (64, 200, 65, 1000, 128), 128, 128, "f32", False),       # sibling workgroups split d_v
     ("mixed_whole", 2, 16, (127, 64, 300, 191, 77), 128, 128, "f32", False),     # one workgroup per stream
     ("long_and_short", 1, 2, (2100, 70, 1320), 128, 128, "f32", False),          # correction: 3 workgroups for the longest
@@ -31,9 +33,13 @@ def offsets(lengths):
     return [0] + [int(x) for x in np.cumsum(lengths)]
 
 
+def io_of(name):
+    return "f32" if name.startswith("f32") else "bf16"
+
+
 def make(case, T, **kw):
     name, B, H, lengths, dk, dv, gd, ph = case
-    return synth.make_inputs(B, T, H, dk, dv, seed=zlib.crc32(name.encode()) % 10000 + 21, io="bf16", g=gd,
+    return synth.make_inputs(B, T, H, dk, dv, seed=zlib.crc32(name.encode()) % 10000 + 21, io=io_of(name), g=gd,
                              device="cuda", per_head_gate=ph, **kw)
 
 
@@ -51,7 +57,7 @@ def first_channel(G, per_head):
 def test_varlen_local_pass_and_three_calls(case):
     name, B, H, lengths, dk, dv, gd, ph = case
     print("case", case, flush=True)
-    tol = TOL["bf16"]
+    tol = TOL[io_of(name)]
     P, T, Lmax = len(lengths), sum(lengths), max(lengths)
     start = offsets(lengths)
     seg = torch.tensor(start, dtype=torch.int64, device="cuda")

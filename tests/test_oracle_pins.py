@@ -133,6 +133,26 @@ def test_segmented_equals_unsegmented(P):
         assert relerr(S_last, Sf_ref) < 1e-9
 
 
+def test_segments_of_unequal_length_equal_unsegmented():
+    """The same invariance for an uneven cut: the local pass of every token range on its own, the state
+    recurrence over the ranges, the correction of every range by the state entering it."""
+    B, T, H, dk, dv = 2, 90, 2, 4, 3
+    q, k, v, g = tiny_inputs(B, T, H, dk, dv, seed=33)
+    S0 = np.random.default_rng(3).standard_normal((B, H, dk, dv))
+    start = [0, 7, 8, 40, 41, 77, 90]
+    P = len(start) - 1
+    parts = [oracle.gla_local(q[:, a:e], k[:, a:e], v[:, a:e], g[:, a:e], 1, scale=0.9)
+             for a, e in zip(start[:-1], start[1:])]
+    S_loc = np.stack([x[1][0] for x in parts]).reshape(P, B * H, dk, dv)
+    G_tot = np.stack([x[3][0] for x in parts]).reshape(P, B * H, dk)
+    S_init, S_last = oracle.state_scan(S_loc, G_tot, S0.reshape(B * H, dk, dv))
+    o = np.concatenate([oracle.apply_init_state(q[:, a:e], x[2], S_init[p:p + 1].reshape(1, B, H, dk, dv), x[0], 0.9)
+                        for p, (a, e, x) in enumerate(zip(start[:-1], start[1:], parts))], axis=1)
+    o_ref, Sf_ref = oracle.gla_recurrent(q, k, v, g, scale=0.9, S0=S0)
+    assert relerr(o, o_ref) < 1e-9
+    assert relerr(S_last.reshape(B, H, dk, dv), Sf_ref) < 1e-9
+
+
 def test_scan_states_are_global_states_at_segment_boundaries():
     """S_init[p] must be the unsegmented run's state right before segment p."""
     B, P, L, H, dk, dv = 1, 4, 12, 1, 3, 4

@@ -184,6 +184,17 @@ zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *desc, const int64_
                                          const void *q, const float *G_cum, const float *S_init, void *o,
                                          int32_t flags, void *stream);
 
+/* The two phases of Alg. 1's own schedule (zeco_gla_local_state, zeco_gla_fwd_from_state below) over the same
+ * table: end state and total log decay of every segment from the zero state; then, after zeco_state_scan,
+ * the forward of every segment from the state entering it, which writes the final o.  No o from the zero
+ * state and no G_cum are ever stored.  bf16 q/k/v/o only (fp32 returns ZECO_ERR_UNSUPPORTED). */
+zeco_status zeco_gla_local_state_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                        const void *k, const void *v, const void *g, float *S_loc,
+                                        float *G_tot, void *stream);
+zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                           const void *q, const void *k, const void *v, const void *g,
+                                           const float *S_init, void *o, void *stream);
+
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
  * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
  * ZECO_ERR_UNSUPPORTED).  Same conventions as above. ------------------------------------------------ */

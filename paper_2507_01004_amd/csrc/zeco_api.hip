@@ -740,6 +740,41 @@ zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *d, const int64_t *
     return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, s));
 }
 
+// The two phases of Alg. 1's own schedule over the same table (bf16 only, like the equal-length calls).
+zeco_status zeco_gla_local_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
+                                        const void *k, const void *v, const void *g, float *S_loc,
+                                        float *G_tot, void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!k || !v || !g || !S_loc || !G_tot) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_loc) || !aligned16(G_tot))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.k = k; p.v = v; p.g = g; p.S_loc = S_loc; p.G_tot = G_tot;
+    p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, static_cast<hipStream_t>(stream)));
+}
+
+zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
+                                           const void *q, const void *k, const void *v, const void *g,
+                                           const float *S_init, void *o, void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!q || !k || !v || !g || !S_init || !o) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_init) || !aligned16(o))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_init = S_init;
+    p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, static_cast<hipStream_t>(stream)));
+}
+
 // ---- chunk-decay form of the local pass and the correction ---------------------------------------------
 zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q, const void *k,
                                            const void *v, const void *g, void *o, float *S_loc,

@@ -21,7 +21,7 @@ struct ChunkParams {
     int B, P, H, L;
     int n_chunks;              // ceil(L / 64)
     int pad = 0;               // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens
-    // Segments of unequal length (mode 0 of the bf16 kernel, and the fp32 kernel): segment p covers tokens
+    // Segments of unequal length (modes 0, 1 and 2 of the bf16 kernel, and the fp32 kernel): segment p covers tokens
     // [seg_start[p], seg_start[p+1]) of the T tokens of every batch entry; L is then the upper bound of the
     // lengths, n_chunks and pad are unused.
     const long long *seg_start = nullptr;

@@ -20,6 +20,7 @@ SCHEDULE_AUTO, SCHEDULE_TWO_PHASE, SCHEDULE_CORRECT = 0, 1, 2
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
            "zeco_state_scan_tree_workspace", "zeco_state_scan_tree",
            "zeco_apply_init_state", "zeco_gla_local_fwd_varlen", "zeco_apply_init_state_varlen",
+           "zeco_gla_local_state_varlen", "zeco_gla_fwd_from_state_varlen",
            "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
            "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
@@ -73,6 +74,10 @@ def lib():
         L.zeco_gla_local_fwd_varlen.restype = i32
         L.zeco_apply_init_state_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state_varlen.restype = i32
+        L.zeco_gla_local_state_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, fp, fp, vp]
+        L.zeco_gla_local_state_varlen.restype = i32
+        L.zeco_gla_fwd_from_state_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, fp, vp, vp]
+        L.zeco_gla_fwd_from_state_varlen.restype = i32
         L.zeco_gla_local_fwd_chunk_decay.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp]
         L.zeco_gla_local_fwd_chunk_decay.restype = i32
         L.zeco_apply_init_state_chunk_decay.argtypes = [dp, vp, vp, fp, fp, vp, i32, vp]
@@ -322,6 +327,50 @@ def apply_init_state_varlen(q, g_like, G_cum, S_init, o, seg_start, max_len, sca
                                             _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_apply_init_state_varlen")
+    return o
+
+
+def _gate_per_head(q, g):
+    per_head = g.dim() == 3
+    if per_head:
+        if tuple(g.shape) != tuple(q.shape[:3]) or not g.is_contiguous():
+            raise ValueError("a per-head gate must be a contiguous [B,T,H] tensor")
+    elif g.shape != q.shape or g.stride() != q.stride():
+        raise ValueError("a per-channel gate must have the shape and strides of q")
+    return per_head
+
+
+def gla_local_state_varlen(k, v, g, seg_start, max_len, out=None):
+    """zeco_gla_local_state_varlen: end state and total log decay of every segment of the table from the
+    zero state.  Returns (S_loc, G_tot)."""
+    if not k.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    B, T, H, dk = k.shape
+    dv = v.shape[-1]
+    desc = _varlen_desc(k, v, _dtype_code(g), _gate_per_head(k, g), seg_start, max_len, 1.0)
+    if out is None:
+        S_loc = torch.empty(desc.P, B, H, dk, dv, dtype=torch.float32, device=k.device)
+        G_tot = torch.empty((desc.P, B, H) + _gate_dims(g, dk), dtype=torch.float32, device=k.device)
+    else:
+        S_loc, G_tot = out
+    st = lib().zeco_gla_local_state_varlen(ctypes.byref(desc), _ptr(seg_start), T, _ptr(k), _ptr(v), _ptr(g),
+                                           _ptr(S_loc), _ptr(G_tot), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_local_state_varlen")
+    return S_loc, G_tot
+
+
+def gla_fwd_from_state_varlen(q, k, v, g, S_init, seg_start, max_len, scale=1.0, out=None):
+    """zeco_gla_fwd_from_state_varlen: the forward of every segment of the table from S_init[p].  Returns o."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device) if out is None else out
+    st = lib().zeco_gla_fwd_from_state_varlen(ctypes.byref(desc), _ptr(seg_start), q.shape[1], _ptr(q), _ptr(k),
+                                              _ptr(v), _ptr(g), _ptr(S_init), _ptr(o), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_fwd_from_state_varlen")
     return o
 
 

@@ -135,13 +135,19 @@ def test_apply_init_state_rejects_unknown_flags(L):
 
 
 def test_unequal_segment_lengths_validate_before_any_launch(L):
-    """zeco_gla_local_fwd_varlen / zeco_apply_init_state_varlen: descriptor, T and the table's pointer."""
+    """The four entry points over a table of segment offsets: descriptor, T and the table's pointer."""
     ref = ctypes.byref
     loc = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_local_fwd_varlen(
         ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None)
     app = lambda d=None, seg=FAKE, T=4096, q=FAKE, flags=0: L.zeco_apply_init_state_varlen(
         ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, flags, None)
-    for call in (loc, app):
+    sta = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_local_state_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, FAKE, None)
+    out = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_fwd_from_state_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, FAKE, FAKE, None)
+    for call in (sta, out):
+        assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
+    for call in (loc, app, sta, out):
         assert call(seg=None) == zeco.ZECO_ERR_INVALID_ARG
         assert call(seg=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG        # not 8-byte aligned
         assert call(T=127) == zeco.ZECO_ERR_INVALID_ARG                             # under P * C tokens

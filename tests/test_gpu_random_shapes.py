@@ -100,6 +100,10 @@ def test_random_shape_all_routes(case):
         S_init, S_last = zeco.state_scan(S_loc, G_tot, S0=S0)
         zeco.apply_init_state_varlen(q, g, G_cum, S_init, o, seg, bound, scale=0.5, first_segment_is_zero=False)
         check_forward(o, S_last, "unequal segments %s" % (start,))
+        S_loc, G_tot = zeco.gla_local_state_varlen(k, v, g, seg, bound)
+        S_init, S_last = zeco.state_scan(S_loc, G_tot, S0=S0)
+        o = zeco.gla_fwd_from_state_varlen(q, k, v, g, S_init, seg, bound, scale=0.5)
+        check_forward(o, S_last, "unequal segments, two phases %s" % (start,))
 
     got = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, S0=S0, dS_T=dS_T)
     torch.cuda.synchronize()

@@ -1,4 +1,5 @@
-"""Segments of unequal length (zeco_gla_local_fwd_varlen, zeco_apply_init_state_varlen): the local pass of
+"""Segments of unequal length (zeco_gla_local_fwd_varlen, zeco_apply_init_state_varlen, and the two phases
+zeco_gla_local_state_varlen, zeco_gla_fwd_from_state_varlen): the local pass of
 every segment against the oracle's local pass of that token range on its own, and the three calls (the scan is
 the ordinary one) against the unsegmented fp64 recurrence over the whole sequence.  Lengths mix multiples of
 the chunk size with ragged ones, one chunk with many, and differ by up to 30x inside one call; tokens before
@@ -93,6 +94,15 @@ def test_varlen_local_pass_and_three_calls(case):
         assert rel_err_bh(host(o_c), o_f, (0, 2)) <= tol, dense
     assert rel_err_bh(host(S_last), S_f, (0, 1)) <= tol
     assert rel_err_bh(o_local, o_f, (0, 2)) > 5 * tol     # the correction matters here
+    if io_of(name) == "bf16":   # Alg. 1's own schedule over the same table: states, scan, output from the states
+        S_loc2, G_tot2 = zeco.gla_local_state_varlen(inp["k"], inp["v"], inp["g"], seg, Lmax)
+        S_init2, S_last2 = zeco.state_scan(S_loc2, G_tot2, S0=S0)
+        o2 = zeco.gla_fwd_from_state_varlen(inp["q"], inp["k"], inp["v"], inp["g"], S_init2, seg, Lmax, scale=0.5)
+        torch.cuda.synchronize()
+        assert log_err(host(G_tot2), host(G_tot)) <= 1e-5     # (the two modes sum the gates in different orders)
+        assert rel_err_bh(host(S_loc2), host(S_loc), (1, 2)) <= tol
+        assert rel_err_bh(host(o2), o_f, (0, 2)) <= tol
+        assert rel_err_bh(host(S_last2), S_f, (0, 1)) <= tol
 
 
 def test_varlen_tokens_outside_the_segments_stay_untouched_and_bound_may_be_loose():

@@ -195,6 +195,20 @@ zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *desc, const int6
                                            const void *q, const void *k, const void *v, const void *g,
                                            const float *S_init, void *o, void *stream);
 
+/* The backward's building blocks (zeco_gla_bwd_dstate, zeco_gla_bwd_from_state below) over the same table:
+ * every segment's state gradient from dS = 0; then, after the reverse zeco_state_scan, dq, dk, dv, dg of
+ * every segment.  Arguments as in the equal-length calls.  The segments are not cut into shorter pieces, so
+ * dg carries the rounding noise of a running sum over a whole segment (about 2 % of max|dg| at 1000 tokens,
+ * 4 % at 8000); dq, dk, dv do not.  bf16 q/k/v only (fp32 returns ZECO_ERR_UNSUPPORTED). */
+zeco_status zeco_gla_bwd_dstate_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                       const void *q, const void *g, const void *dO, float *dS_loc,
+                                       void *stream);
+zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                           const void *q, const void *k, const void *v, const void *g,
+                                           const void *dO, const float *S_init, const float *S_last,
+                                           const float *dS_in, void *dq, void *dk, void *dv, float *dg,
+                                           void *stream);
+
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
  * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
  * ZECO_ERR_UNSUPPORTED).  Same conventions as above. ------------------------------------------------ */

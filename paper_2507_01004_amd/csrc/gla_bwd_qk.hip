@@ -116,7 +116,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, kg = lane >> 4;
-    const int N = p.n_chunks;
+    int N = p.n_chunks, pad = p.pad;   // (per segment when the segments differ in length, see below)
     auto chunk_of = [&](int m) { return REV ? N - 1 - m : m; };
     auto pos_of = [](int t) { return REV ? 63 - t : t; };
     // When L is no multiple of 64 the chunk processed FIRST is the short one, 64 - pad tokens: the segment's
@@ -124,7 +124,6 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     // segment, [0, 64) or [L - 64, L); the gated operand, the log decays and the dG terms of the window's
     // surplus rows are taken as zero - they then touch no state, no decay and no other row - and their
     // gradient rows are not stored.
-    const int pad = p.pad;
     auto cstart = [&](int c) {
         if constexpr (REV) return (long long)c * 64 - (c == N - 1 ? pad : 0);
         else return c ? (long long)c * 64 - pad : 0ll;
@@ -137,13 +136,23 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     const int h = sidx % p.H;
     sidx /= p.H;
     const int b = sidx % p.B, seg = sidx / p.B;
-    const long long tok0 = (long long)seg * p.L;
+    long long tok0 = (long long)seg * p.L, T = (long long)p.P * p.L;   // first token; tokens per batch entry
+    if (p.seg_start) {
+        // segments of unequal length: this one's bounds from the table; a segment that cannot be taken (under
+        // 64 tokens, over the bound L, outside the tensor) is left alone: the whole workgroup leaves
+        tok0 = p.seg_start[seg];
+        T = p.T;
+        const long long len = p.seg_start[seg + 1] - tok0;
+        if (tok0 < 0 || len < 64 || len > p.L || tok0 > T - len) return;   // (in this order: no sum can overflow)
+        N = (int)((len + 63) >> 6);
+        pad = 64 * N - (int)len;
+    }
     const long long kbase = b * p.sb + tok0 * p.st + h * p.sh;
     const long long vbase = b * p.vb + tok0 * p.vt + h * p.vh;
     const unsigned char *xb = (const unsigned char *)p.x + vbase * 2;
     const unsigned char *yb = (const unsigned char *)p.y + vbase * 2;
     const unsigned char *zb = (const unsigned char *)p.z + kbase * 2;
-    const long long hbase = ((long long)b * p.P * p.L + tok0) * p.H + h;   // per-head arrays [B,T,H]
+    const long long hbase = ((long long)b * T + tok0) * p.H + h;   // per-head arrays [B,T,H]
     const unsigned char *gb = (const unsigned char *)p.g + (GH ? hbase : kbase) * GB;
     const long long gst = GH ? (long long)p.H : p.st;                       // gate elements between tokens
     const unsigned char *z2b = (const unsigned char *)p.z2 + kbase * 2;

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     sidx /= p.H;
     const int b = sidx % p.B, seg = sidx / p.B;
     long long tok0 = (long long)seg * p.L, T = (long long)p.P * p.L;   // first token; tokens per batch entry
-    if constexpr (MODE == kLocal || MODE == kStates || MODE == kOutput) {
+    if constexpr (MODE != kLocalInit && MODE != kLocalCD && MODE != kOutputSave) {
         if (p.seg_start) {
             // segments of unequal length: this one's bounds from the table.  A segment the kernel cannot take
             // (under 64 tokens, over the bound L, outside the tensor) is left alone: the whole workgroup leaves.

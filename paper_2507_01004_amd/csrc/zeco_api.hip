@@ -434,9 +434,10 @@ static void fill_bwd_params(zeco::BwdQKParams &b, const zeco_gla_desc *d, int P,
 static zeco_status bwd_dq_pass(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
                                const void *v, const void *g, const void *dO, const float *S_init,
                                const float *S_last, void *dq, float *dg, float *dS_loc, float *G_tot_out,
-                               hipStream_t s) {
+                               hipStream_t s, const int64_t *seg_start = nullptr, int64_t T = 0) {
     zeco::BwdQKParams b;
     fill_bwd_params(b, d, P, L, g, dg, S_init, S_last);
+    b.seg_start = reinterpret_cast<const long long *>(seg_start); b.T = T;
     b.x = dO; b.y = v; b.z = k; b.z2 = q; b.out = dq; b.W_init = S_init; b.zscale = 1.f; b.oscale = d->scale;
     b.dS_loc = dS_loc; b.G_tot_out = G_tot_out; b.qscale = d->scale;
     return from_hip(zeco::launch_bwd_qk(b, d->d_k, d->d_v, gate_mode(d), false, s));
@@ -447,17 +448,20 @@ static zeco_status bwd_dq_pass(const zeco_gla_desc *d, int P, int L, const void 
 static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
                                     const void *v, const void *g, const void *dO, const float *S_init,
                                     const float *S_last, const float *dS_in, void *dk, void *dv,
-                                    float *dg, hipStream_t s) {
+                                    float *dg, hipStream_t s, const int64_t *seg_start = nullptr,
+                                    int64_t T = 0) {
     const int gb = gate_mode(d);
     zeco::ChunkParams c;
     fill_chunk_params(c, d);
     c.P = P; set_length(c, L);
+    c.seg_start = reinterpret_cast<const long long *>(seg_start); c.T = T;
     c.q = k; c.k = q; c.v = dO; c.g = g; c.o = dv; c.S_init = dS_in; c.scale = 1.f; c.kscale = d->scale;
     hipError_t e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, gb, 4, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::BwdQKParams b;
     fill_bwd_params(b, d, P, L, g, dg, S_init, S_last);
+    b.seg_start = reinterpret_cast<const long long *>(seg_start); b.T = T;
     b.x = v; b.y = dO; b.z = q; b.z2 = k; b.out = dk; b.W_init = dS_in; b.zscale = d->scale; b.oscale = 1.f;
     return from_hip(zeco::launch_bwd_qk(b, d->d_k, d->d_v, gb, true, s));
 }
@@ -773,6 +777,45 @@ zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *d, const int64_t
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_init = S_init;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
     return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, static_cast<hipStream_t>(stream)));
+}
+
+// The backward's building blocks over the same table (bf16 only, like the equal-length calls).
+zeco_status zeco_gla_bwd_dstate_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
+                                       const void *q, const void *g, const void *dO, float *dS_loc,
+                                       void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!q || !g || !dO || !dS_loc) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(g) || !aligned16(dO) || !aligned16(dS_loc)) return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.k = q; p.v = dO; p.g = g; p.S_loc = dS_loc; p.kscale = d->scale;
+    p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 3, static_cast<hipStream_t>(stream)));
+}
+
+zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
+                                           const void *q, const void *k, const void *v, const void *g,
+                                           const void *dO, const float *S_init, const float *S_last,
+                                           const float *dS_in, void *dq, void *dk, void *dv, float *dg,
+                                           void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!q || !k || !v || !g || !dO || !S_init || !S_last || !dS_in || !dq || !dk || !dv || !dg)
+        return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
+        !aligned16(S_init) || !aligned16(S_last) || !aligned16(dS_in) || !aligned16(dq) || !aligned16(dk) ||
+        !aligned16(dv) || !aligned16(dg))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, s,
+                                       seg_start, T);
+    if (sq != ZECO_OK) return sq;
+    return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, s, seg_start, T);
 }
 
 // ---- chunk-decay form of the local pass and the correction ---------------------------------------------

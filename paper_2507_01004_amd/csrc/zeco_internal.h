@@ -21,7 +21,7 @@ struct ChunkParams {
     int B, P, H, L;
     int n_chunks;              // ceil(L / 64)
     int pad = 0;               // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens
-    // Segments of unequal length (modes 0, 1 and 2 of the bf16 kernel, and the fp32 kernel): segment p covers tokens
+    // Segments of unequal length (modes 0 to 4 of the bf16 kernel, and the fp32 kernel): segment p covers tokens
     // [seg_start[p], seg_start[p+1]) of the T tokens of every batch entry; L is then the upper bound of the
     // lengths, n_chunks and pad are unused.
     const long long *seg_start = nullptr;
@@ -84,6 +84,8 @@ struct BwdQKParams {
     const float *W_init, *S_init, *S_last;
     int B, P, H, L, n_chunks;    // n_chunks = ceil(L / 64)
     int pad = 0;                 // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens
+    const long long *seg_start = nullptr;   // segments of unequal length, as in ChunkParams (L = bound on the
+    long long T = 0;                        //   lengths, T = tokens per batch entry)
     float zscale, oscale;        // multipliers of the gated operand and of the output
     // dQ pass only, optional: also emit each segment's state gradient from dS = 0,
     // dS_loc [P,B,H,d_k,d_v] = qscale * sum_t (q_t .* exp(G_t))^T x_t, and its total log decay G_tot_out

@@ -21,6 +21,7 @@ EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_sca
            "zeco_state_scan_tree_workspace", "zeco_state_scan_tree",
            "zeco_apply_init_state", "zeco_gla_local_fwd_varlen", "zeco_apply_init_state_varlen",
            "zeco_gla_local_state_varlen", "zeco_gla_fwd_from_state_varlen",
+           "zeco_gla_bwd_dstate_varlen", "zeco_gla_bwd_from_state_varlen",
            "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
            "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
@@ -78,6 +79,10 @@ def lib():
         L.zeco_gla_local_state_varlen.restype = i32
         L.zeco_gla_fwd_from_state_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, fp, vp, vp]
         L.zeco_gla_fwd_from_state_varlen.restype = i32
+        L.zeco_gla_bwd_dstate_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, fp, vp]
+        L.zeco_gla_bwd_dstate_varlen.restype = i32
+        L.zeco_gla_bwd_from_state_varlen.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, vp]
+        L.zeco_gla_bwd_from_state_varlen.restype = i32
         L.zeco_gla_local_fwd_chunk_decay.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp]
         L.zeco_gla_local_fwd_chunk_decay.restype = i32
         L.zeco_apply_init_state_chunk_decay.argtypes = [dp, vp, vp, fp, fp, vp, i32, vp]
@@ -372,6 +377,39 @@ def gla_fwd_from_state_varlen(q, k, v, g, S_init, seg_start, max_len, scale=1.0,
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_gla_fwd_from_state_varlen")
     return o
+
+
+def gla_bwd_dstate_varlen(q, g, dO, seg_start, max_len, scale=1.0, out=None):
+    """zeco_gla_bwd_dstate_varlen: the state gradient leaving every segment of the table towards the earlier
+    ones, from dS = 0.  Returns dS_loc [P,B,H,d_k,d_v]."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    B, T, H, dk = q.shape
+    dv = dO.shape[-1]
+    desc = _varlen_desc(q, dO, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    dS_loc = torch.empty(desc.P, B, H, dk, dv, dtype=torch.float32, device=q.device) if out is None else out
+    st = lib().zeco_gla_bwd_dstate_varlen(ctypes.byref(desc), _ptr(seg_start), T, _ptr(q), _ptr(g), _ptr(dO),
+                                          _ptr(dS_loc), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_bwd_dstate_varlen")
+    return dS_loc
+
+
+def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, max_len, scale=1.0, out=None):
+    """zeco_gla_bwd_from_state_varlen: dq, dk, dv, dg of every segment of the table from the scanned forward
+    states and state gradients.  Returns (dq, dk, dv, dg)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    _check_same_layout(v, dO)
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    dq, dk, dv, dg = _grad_outputs(q, v, g) if out is None else out
+    st = lib().zeco_gla_bwd_from_state_varlen(ctypes.byref(desc), _ptr(seg_start), q.shape[1], _ptr(q), _ptr(k),
+                                              _ptr(v), _ptr(g), _ptr(dO), _ptr(S_init), _ptr(S_last), _ptr(dS_in),
+                                              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_bwd_from_state_varlen")
+    return dq, dk, dv, dg
 
 
 def _apply_flags(first_segment_is_zero, dense):

@@ -135,7 +135,7 @@ def test_apply_init_state_rejects_unknown_flags(L):
 
 
 def test_unequal_segment_lengths_validate_before_any_launch(L):
-    """The four entry points over a table of segment offsets: descriptor, T and the table's pointer."""
+    """The six entry points over a table of segment offsets: descriptor, T and the table's pointer."""
     ref = ctypes.byref
     loc = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_local_fwd_varlen(
         ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None)
@@ -145,9 +145,13 @@ def test_unequal_segment_lengths_validate_before_any_launch(L):
         ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, FAKE, None)
     out = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_fwd_from_state_varlen(
         ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, FAKE, FAKE, None)
-    for call in (sta, out):
+    dst = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_bwd_dstate_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, None)
+    bwd = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_bwd_from_state_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, *([FAKE] * 11), None)
+    for call in (sta, out, dst, bwd):
         assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
-    for call in (loc, app, sta, out):
+    for call in (loc, app, sta, out, dst, bwd):
         assert call(seg=None) == zeco.ZECO_ERR_INVALID_ARG
         assert call(seg=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG        # not 8-byte aligned
         assert call(T=127) == zeco.ZECO_ERR_INVALID_ARG                             # under P * C tokens

@@ -105,9 +105,23 @@ def test_random_shape_all_routes(case):
         o = zeco.gla_fwd_from_state_varlen(q, k, v, g, S_init, seg, bound, scale=0.5)
         check_forward(o, S_last, "unequal segments, two phases %s" % (start,))
 
+    ref_dg = ref[3].sum(axis=-1) if per_head else ref[3]
     got = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, S0=S0, dS_T=dS_T)
     torch.cuda.synchronize()
     for nm, x, r in zip(("dq", "dk", "dv"), got[:3], ref[:3]):
         assert rel_err_bh(host(x), r, (0, 2)) <= tol, nm
-    assert rel_err_bh(host(got[3]), ref[3].sum(axis=-1) if per_head else ref[3], (0, 2)) <= tol, "dg"
+    assert rel_err_bh(host(got[3]), ref_dg, (0, 2)) <= tol, "dg"
     assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= tol, "dS0"
+
+    if start is not None:   # the backward's building blocks over the unequal cut
+        S_loc, G_tot = zeco.gla_local_state_varlen(k, v, g, seg, bound)
+        S_init, S_last = zeco.state_scan(S_loc, G_tot, S0=S0)
+        dS_loc = zeco.gla_bwd_dstate_varlen(q, g, dO, seg, bound, scale=0.5)
+        dS_in, dS0 = zeco.state_scan(dS_loc, G_tot, S0=dS_T, direction=1)
+        got = zeco.gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg, bound, scale=0.5)
+        torch.cuda.synchronize()
+        for nm, x, r in zip(("dq", "dk", "dv"), got[:3], ref[:3]):
+            assert rel_err_bh(host(x), r, (0, 2)) <= tol, nm + ", unequal segments"
+        assert rel_err_bh(host(dS0), ref[4], (0, 1)) <= tol, "dS0, unequal segments"
+        if bound <= 700:    # whole segments are one running sum of dg each: beyond this its noise passes the bound
+            assert rel_err_bh(host(got[3]), ref_dg, (0, 2)) <= tol, "dg, unequal segments"

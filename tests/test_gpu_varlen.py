@@ -1,5 +1,5 @@
 """Segments of unequal length (zeco_gla_local_fwd_varlen, zeco_apply_init_state_varlen, and the two phases
-zeco_gla_local_state_varlen, zeco_gla_fwd_from_state_varlen): the local pass of
+zeco_gla_local_state_varlen, zeco_gla_fwd_from_state_varlen, and the backward's building blocks): the local pass of
 every segment against the oracle's local pass of that token range on its own, and the three calls (the scan is
 the ordinary one) against the unsegmented fp64 recurrence over the whole sequence.  Lengths mix multiples of
 the chunk size with ragged ones, one chunk with many, and differ by up to 30x inside one call; tokens before
@@ -103,6 +103,37 @@ def test_varlen_local_pass_and_three_calls(case):
         assert rel_err_bh(host(S_loc2), host(S_loc), (1, 2)) <= tol
         assert rel_err_bh(host(o2), o_f, (0, 2)) <= tol
         assert rel_err_bh(host(S_last2), S_f, (0, 1)) <= tol
+
+
+@pytest.mark.parametrize("case", [c for c in CASES if not c[0].startswith("f32")], ids=lambda c: c[0])
+def test_varlen_backward_building_blocks(case):
+    """Forward states, their scan, the state gradients, the reverse scan and the gradient passes, all over the
+    same table, against the oracle's backward of the unsegmented recurrence with S0 and dS_T."""
+    name, B, H, lengths, dk, dv, gd, ph = case
+    print("case", case, flush=True)
+    tol = TOL["bf16"]
+    P, T, Lmax = len(lengths), sum(lengths), max(lengths)
+    seg = torch.tensor(offsets(lengths), dtype=torch.int64, device="cuda")
+    inp = make(case, T, gate_div=64.0)
+    q, k, v, g = (inp[n] for n in "qkvg")
+    gen = torch.Generator(device="cuda").manual_seed(zlib.crc32(name.encode()) % 10000 + 23)
+    dO = torch.randn(v.shape, generator=gen, device="cuda").to(torch.bfloat16)
+    S0 = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
+    dS_T = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
+    S_loc, G_tot = zeco.gla_local_state_varlen(k, v, g, seg, Lmax)
+    S_init, S_last = zeco.state_scan(S_loc, G_tot, S0=S0)
+    dS_loc = zeco.gla_bwd_dstate_varlen(q, g, dO, seg, Lmax, scale=0.5)
+    dS_in, dS0 = zeco.state_scan(dS_loc, G_tot, S0=dS_T, direction=1)
+    got = zeco.gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg, Lmax, scale=0.5)
+    torch.cuda.synchronize()
+    ref = oracle.gla_recurrent_bwd(host(q), host(k), host(v), widen(g, dk), host(dO), 0.5, host(S0), host(dS_T))
+    for nm, x, r in zip(("dq", "dk", "dv"), got[:3], ref[:3]):
+        assert rel_err_bh(host(x), r, (0, 2)) <= tol, nm
+    # dg is a running sum over a whole segment here (no shorter pieces): its rounding noise grows with the
+    # square root of the segment length, 2 % of max|dg| being reached near 1000 tokens
+    dg_tol = tol if Lmax <= 700 else 2 * tol
+    assert rel_err_bh(host(got[3]), ref[3].sum(axis=-1) if ph else ref[3], (0, 2)) <= dg_tol, "dg"
+    assert rel_err_bh(host(dS0), ref[4], (0, 1)) <= tol, "dS0"
 
 
 def test_varlen_tokens_outside_the_segments_stay_untouched_and_bound_may_be_loose():

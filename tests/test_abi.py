@@ -234,3 +234,13 @@ def test_chunk_decay_and_fused_forward_reject_bad_arguments(L):
     assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
     fused[7] = FAKE                                        # saved states need the two-phase schedule
     assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need, None) == zeco.ZECO_ERR_UNSUPPORTED
+
+
+def test_a_missing_library_raises_instead_of_falling_back(monkeypatch):
+    """The binding has no other path: without libzeco.so every call fails with a message that says how to build it."""
+    monkeypatch.setattr(zeco, "_lib", None)
+    monkeypatch.setattr(zeco, "LIB_PATH", os.path.join(os.path.dirname(zeco.LIB_PATH), "no_such_libzeco.so"))
+    with pytest.raises(RuntimeError, match="not built"):
+        zeco.lib()
+    with pytest.raises(RuntimeError, match="not built"):
+        zeco.version()

@@ -260,19 +260,27 @@ static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
 #endif
 }
 
+// Tokens per workgroup of the correction: the largest of cap..64 (powers of two) that divides L, or, when the
+// segments need not divide evenly (a ragged L, unequal segments), that is not above L - the last workgroup
+// of a segment then has fewer blocks.  1024 where the call stops at the vanished decay (fewer workgroups
+// that find nothing to do), 256 where it streams every token (measured 4 % faster there).
+static void set_apply_share(zeco::ApplyParams &p, int L, int cap, bool divide) {
+    int tpw = cap;
+    if (divide) {
+        while (tpw > 64 && L % tpw != 0) tpw >>= 1;
+    } else {
+        while (tpw > 64 && tpw > L) tpw >>= 1;
+    }
+    p.tokens_per_wg = tpw;
+    p.wgs_per_seg = (64 * p.n_chunks + tpw - 1) / tpw;
+}
+
 // Correction over P segments of L tokens each (the caller's, or the pieces of a fused call).
 static void fill_apply_params(zeco::ApplyParams &p, const zeco_gla_desc *d, int P, int L) {
     p.B = d->B; p.P = P; p.H = d->H; p.L = L;
     p.p0 = 0; p.gate_per_head = d->g_per_head; p.dense = 0;
     p.n_chunks = chunks_of(L); p.pad = 64 * p.n_chunks - L;
-    int tpw = 1024;                       // tokens per workgroup: largest of 1024..64 dividing L, or, when
-    if (p.pad) {                          // L is no multiple of 64, not above it (the last workgroup of a
-        while (tpw > 64 && tpw > L) tpw >>= 1;   // segment then has fewer blocks)
-    } else {
-        while (tpw > 64 && L % tpw != 0) tpw >>= 1;
-    }
-    p.tokens_per_wg = tpw;
-    p.wgs_per_seg = (64 * p.n_chunks + tpw - 1) / tpw;
+    set_apply_share(p, L, 1024, p.pad == 0);
     p.scale = d->scale;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
@@ -684,6 +692,7 @@ zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const f
     p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_apply_f32(p, d->d_k, d->d_v, s));
+    if (p.dense) set_apply_share(p, d->L, 256, p.pad == 0);
     return from_hip(zeco::launch_apply_bf16(p, d->d_k, d->d_v, s));
 }
 
@@ -730,11 +739,9 @@ zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *d, const int64_t *
     if (flags & ~(ZECO_APPLY_FIRST_SEGMENT_ZERO | ZECO_APPLY_DENSE)) return ZECO_ERR_INVALID_ARG;
     zeco::ApplyParams p;
     fill_apply_params(p, d, d->P, d->L);
+    p.dense = (flags & ZECO_APPLY_DENSE) ? 1 : 0;
     // a launch sized for the longest segment allowed; the lengths need not divide into the workgroups' shares
-    int tpw = 1024;
-    while (tpw > 64 && tpw > d->L) tpw >>= 1;
-    p.tokens_per_wg = tpw;
-    p.wgs_per_seg = (64 * p.n_chunks + tpw - 1) / tpw;
+    set_apply_share(p, d->L, (p.dense && d->io_dtype == ZECO_BF16) ? 256 : 1024, false);
     p.q = q; p.G_cum = G_cum; p.S_init = S_init; p.o = o;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
     p.p0 = (flags & ZECO_APPLY_FIRST_SEGMENT_ZERO) ? 1 : 0;

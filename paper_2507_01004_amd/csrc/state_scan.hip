@@ -4,8 +4,8 @@
 // enters segment p from segment p+1, and the end value is what leaves segment 0.
 //
 // Pure streaming: every state element is an independent serial chain of length P, so one thread
-// owns one float4 of a (head, d_k-row-block) slab and walks p = 0..P-1.  The loads of the next
-// kDepth segments do not depend on the chain and are issued ahead of the FMAs that consume them,
+// owns a few consecutive floats of a (head, d_k-row-block) slab and walks p = 0..P-1.  The loads of
+// the following segments do not depend on the chain and are issued ahead of the FMAs that consume them,
 // which is what keeps HBM busy (the on-device analogue of the block pipeline of Sec. 3.2:
 // all row blocks advance concurrently, each block's chain is latency-bound on its own).
 // One fused multiply-add per element per segment, in segment order: bitwise reproducible and
@@ -15,76 +15,148 @@
 
 namespace zeco {
 
-constexpr int kScanDepth = 8;
+// V floats of a state row per thread, D segments of loads in flight per thread.
+template <int V> struct alignas(4 * V) ScanVec { float v[V]; };
 
-__global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p) {
+// Grid: x = (head, row block, part of the block's slab), y = chain.  A thread owns V consecutive floats of
+// one state row and walks the chain; its loads run D segments ahead of the multiply-adds in a ring of
+// registers (the slot a step has just consumed is refilled with the step D further on), so that D loads per
+// thread are in flight at every moment, not only at the start of a batch: with BH * d_k * d_v / V threads
+// and a DRAM latency of 1-2 us that product is what decides how much of the HBM rate the kernel sees.
+// The steady-state loop is free of branches (a branch makes the compiler wait for all outstanding loads at
+// the join): STORE (S_init is written) and BYP (the by-products G_pre / G_sum are wanted) are template
+// flags, and the rounds whose refills would run past the chain's end are peeled off into a guarded tail.
+// Loads, the gate loads and the stores all count against the 63 memory operations a wave can have
+// outstanding, so D beyond 20 buys nothing.
+template <int V, int D, bool STORE, bool BYP>
+__global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p, int parts) {
+    typedef ScanVec<V> vec_t;
     const int blocks_per_head = p.d_k / p.rows_per_block;
-    const int bh = blockIdx.x / blocks_per_head;
-    const int row0 = (blockIdx.x % blocks_per_head) * p.rows_per_block;
-    const int dv4 = p.d_v >> 2;
-    const int slab4 = p.rows_per_block * dv4;
+    const int part = blockIdx.x % parts, rb = blockIdx.x / parts;
+    const int bh = rb / blocks_per_head;
+    const int row0 = (rb % blocks_per_head) * p.rows_per_block;
+    const int dvv = p.d_v / V;                               // threads per state row
+    const int slab = p.rows_per_block * dvv;                 // threads' worth of work in a row block
     const size_t state = (size_t)p.d_k * p.d_v;
     const size_t seg_stride = (size_t)p.BH * state;         // floats between segments
     const size_t gdim = p.gate_per_head ? 1 : p.d_k;        // log decays per (segment, head)
     const size_t g_stride = (size_t)p.BH * gdim;
     const size_t grp = blockIdx.y;                          // chain (group of P segments)
+    const int P = p.P;
 
-    for (int e = threadIdx.x; e < slab4; e += blockDim.x) {
-        const int row = row0 + e / dv4;
-        const size_t off = (size_t)bh * state + (size_t)row * p.d_v + (size_t)(e % dv4) * 4;
-        const float *loc = p.S_loc + grp * p.P * seg_stride + off;
-        const float *gt = p.G_tot + grp * p.P * g_stride + (size_t)bh * gdim + (p.gate_per_head ? 0 : row);
-        float *init = p.S_init ? p.S_init + grp * p.P * seg_stride + off : nullptr;   // null: end values only
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
-        if (p.S0) s = *reinterpret_cast<const f32x4 *>(p.S0 + grp * seg_stride + off);
-        // optional by-products: the log decay preceding each segment of the chain (forward chains) and the
-        // chain's total, kept by the thread that owns the first columns of a row (of the head's first row
-        // when the head has one decay)
-        const bool prefix = (p.G_pre || p.G_sum) && e % dv4 == 0 && (!p.gate_per_head || row == 0);
-        const size_t gcol = (size_t)bh * gdim + (p.gate_per_head ? 0 : row);
-        float *gpre = (prefix && p.G_pre) ? p.G_pre + grp * p.P * g_stride + gcol : nullptr;
-        float gsum = 0.f;
-
-        for (int p0 = 0; p0 < p.P; p0 += kScanDepth) {
-            f32x4 x[kScanDepth];
-            float a[kScanDepth];
+    const int e = part * 256 + threadIdx.x;
+    if (e >= slab) return;
+    const int row = row0 + e / dvv;
+    const size_t off = (size_t)bh * state + (size_t)row * p.d_v + (size_t)(e % dvv) * V;
+    const float *loc = p.S_loc + grp * P * seg_stride + off;
+    const float *gt = p.G_tot + grp * P * g_stride + (size_t)bh * gdim + (p.gate_per_head ? 0 : row);
+    float *init = STORE ? p.S_init + grp * P * seg_stride + off : nullptr;
+    vec_t s;
 #pragma unroll
-            for (int u = 0; u < kScanDepth; ++u) {
-                if (p0 + u < p.P) {
-                    const size_t sg = p.reverse ? p.P - 1 - (p0 + u) : p0 + u;   // segment of this step
-                    x[u] = *reinterpret_cast<const f32x4 *>(loc + sg * seg_stride);
-                    a[u] = gt[sg * g_stride];
-                }
+    for (int i = 0; i < V; ++i) s.v[i] = 0.f;
+    if (p.S0) s = *reinterpret_cast<const vec_t *>(p.S0 + grp * seg_stride + off);
+    // optional by-products: the log decay preceding each segment of the chain (forward chains) and the
+    // chain's total, kept by the thread that owns the first columns of a row (of the head's first row
+    // when the head has one decay)
+    const bool prefix = BYP && e % dvv == 0 && (!p.gate_per_head || row == 0);
+    const size_t gcol = (size_t)bh * gdim + (p.gate_per_head ? 0 : row);
+    float *gpre = (prefix && p.G_pre) ? p.G_pre + grp * P * g_stride + gcol : nullptr;
+    float gsum = 0.f;
+
+    // running pointers: of the next step to fetch, of the next step to consume (chain order, either direction)
+    const long long first = p.reverse ? P - 1 : 0, dir = p.reverse ? -1 : 1;
+    const long long sstep = dir * (long long)seg_stride, gstep = dir * (long long)g_stride;
+    const float *lf = loc + first * (long long)seg_stride, *gf = gt + first * (long long)g_stride;
+    float *sp = STORE ? init + first * (long long)seg_stride : nullptr;
+    float *gp = gpre ? gpre + first * (long long)g_stride : nullptr;
+    vec_t x[D];
+    float a[D];
+    auto fetch = [&](int u) {
+        x[u] = *reinterpret_cast<const vec_t *>(lf);
+        a[u] = *gf;
+        lf += sstep;
+        gf += gstep;
+    };
+    auto consume = [&](int u) {
+        if (STORE) {
+            *reinterpret_cast<vec_t *>(sp) = s;
+            sp += sstep;
+        }
+        if (BYP) {
+            if (gp) {
+                *gp = gsum;
+                gp += gstep;
             }
+            gsum += a[u];
+        }
+        const float d = fast_exp(a[u]);
 #pragma unroll
-            for (int u = 0; u < kScanDepth; ++u) {
-                if (p0 + u < p.P) {
-                    const size_t sg = p.reverse ? p.P - 1 - (p0 + u) : p0 + u;
-                    if (init) *reinterpret_cast<f32x4 *>(init + sg * seg_stride) = s;
-                    if (prefix) {
-                        if (gpre) gpre[sg * g_stride] = gsum;
-                        gsum += a[u];
-                    }
-                    const float d = fast_exp(a[u]);
-                    s[0] = __builtin_fmaf(d, s[0], x[u][0]);
-                    s[1] = __builtin_fmaf(d, s[1], x[u][1]);
-                    s[2] = __builtin_fmaf(d, s[2], x[u][2]);
-                    s[3] = __builtin_fmaf(d, s[3], x[u][3]);
-                }
+        for (int i = 0; i < V; ++i) s.v[i] = __builtin_fmaf(d, s.v[i], x[u].v[i]);
+    };
+    int p0 = 0;
+    if (P >= 2 * D) {
+        // long chain: unconditional prologue, then rounds in which every step and its refill are in the chain
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            fetch(u);
+            __builtin_amdgcn_sched_barrier(0);   // in ring order: the waits below count the loads issued since
+        }
+        for (; p0 + 2 * D <= P; p0 += D) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                consume(u);
+                // (the refill must not be scheduled above the last use of the slot it overwrites: the slot
+                // would then need a second register and a copy at the loop's head, which waits for every load)
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(u);
             }
         }
-        if (p.S_last) *reinterpret_cast<f32x4 *>(p.S_last + grp * seg_stride + off) = s;
-        if (prefix && p.G_sum) p.G_sum[grp * g_stride + gcol] = gsum;
+    } else {
+#pragma unroll
+        for (int u = 0; u < D; ++u)
+            if (u < P) fetch(u);
     }
+    for (; p0 < P; p0 += D) {              // the last one or two rounds (all of a short chain)
+#pragma unroll
+        for (int u = 0; u < D; ++u) {
+            if (p0 + u < P) {
+                consume(u);
+                if (p0 + u + D < P) fetch(u);
+            }
+        }
+    }
+    if (p.S_last) *reinterpret_cast<vec_t *>(p.S_last + grp * seg_stride + off) = s;
+    if (prefix && p.G_sum) p.G_sum[grp * g_stride + gcol] = gsum;
 }
 
-hipError_t launch_scan(const ScanParams &p, hipStream_t s) {
-    const int blocks = p.BH * (p.d_k / p.rows_per_block);
-    const int slab4 = p.rows_per_block * (p.d_v / 4);
-    int threads = ((slab4 + 63) / 64) * 64;
+template <int V, int D> static hipError_t launch_scan_vd(const ScanParams &p, hipStream_t s) {
+    const int slab = p.rows_per_block * (p.d_v / V);
+    const int parts = (slab + 255) / 256;
+    int threads = ((slab + 63) / 64) * 64;
     if (threads > 256) threads = 256;
-    hipLaunchKernelGGL(state_scan_kernel, dim3(blocks, p.groups), dim3(threads), 0, s, p);
+    const long long blocks = (long long)p.BH * (p.d_k / p.rows_per_block) * parts;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks, p.groups), block(threads);
+    const bool byp = p.G_pre || p.G_sum;
+    if (p.S_init) {
+        if (byp) hipLaunchKernelGGL((state_scan_kernel<V, D, true, true>), grid, block, 0, s, p, parts);
+        else hipLaunchKernelGGL((state_scan_kernel<V, D, true, false>), grid, block, 0, s, p, parts);
+    } else {
+        if (byp) hipLaunchKernelGGL((state_scan_kernel<V, D, false, true>), grid, block, 0, s, p, parts);
+        else hipLaunchKernelGGL((state_scan_kernel<V, D, false, false>), grid, block, 0, s, p, parts);
+    }
     return hipGetLastError();
+}
+
+// Floats per thread and ring depth, measured on MI355X at d_k = d_v = 128 with inputs not in any cache:
+// 16 heads (65536 threads at four floats each) run best with 16-byte accesses and 8 segments in flight
+// (5.2 TB/s; deeper rings are 5-10 % slower); 8 heads fill the chip only at two floats per thread (256 x 8:
+// 4.5 -> 5.3 TB/s with 16 in flight); a single head at one float per thread (1024 x 1: 1.5 -> 2.3 TB/s).
+hipError_t launch_scan(const ScanParams &p, hipStream_t s) {
+    const long long quads = (long long)p.groups * p.BH * p.d_k * p.d_v / 4;   // (d_v is a multiple of 4)
+    if (quads >= 65536) return launch_scan_vd<4, 8>(p, s);
+    if (quads >= 32768) return launch_scan_vd<2, 16>(p, s);
+    return launch_scan_vd<1, 16>(p, s);
 }
 
 // G_cum[b, t, h] += G_pre[piece of t, b, h] for per-head log decays (G_cum [B,T,H], G_pre [pieces,B,H], pieces

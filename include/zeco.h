@@ -29,7 +29,8 @@ typedef enum {
     ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix, L < C,
                                * L % C != 0 with saved states */
     ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than the entry point's own *_workspace() query says */
-    ZECO_ERR_HIP = 4          /* HIP runtime refused a launch / attribute */
+    ZECO_ERR_HIP = 4,         /* HIP runtime refused a launch / attribute */
+    ZECO_ERR_SCRATCH_LIMIT = 5 /* zeco_state_scan_tree_static: the problem needs more than the library's static scratch */
 } zeco_status;
 
 typedef enum { ZECO_F32 = 0, ZECO_BF16 = 1 } zeco_dtype;
@@ -122,6 +123,24 @@ zeco_status zeco_state_scan_tree(int32_t P, int32_t BH, int32_t d_k, int32_t d_v
                                  const float *G_tot, const float *S0, float *S_init, float *S_last,
                                  int32_t direction, int32_t gate_per_head, void *workspace,
                                  size_t workspace_bytes, void *stream);
+
+/* zeco_state_scan_tree for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, conventions and results (bitwise) as
+ * zeco_state_scan_tree, without the workspace: the group states live in a fixed array inside the library's
+ * device image, zeco_state_scan_tree_static_limit() bytes (33 MiB) on every GPU the library runs on, held
+ * until the process ends.  The call allocates and frees nothing.
+ *   - A problem whose zeco_state_scan_tree_workspace() exceeds the limit returns ZECO_ERR_SCRATCH_LIMIT and
+ *     launches nothing (33 MiB covers 1024 segments of up to 4 heads at d_k = d_v = 128, the range in
+ *     which the tree is the faster scan).
+ *   - The first call on a device looks up the array's address on that device (hipGetSymbolAddress, no
+ *     allocation, no synchronisation); make that call with the device current, as for every other call.
+ *   - All calls on one GPU share that GPU's array.  Nothing in it has to start at zero and nothing is kept
+ *     from call to call (each call writes every byte it later reads), but two calls that overlap on one GPU
+ *     - on different streams, or from different threads - race on it: order them on one stream. */
+size_t zeco_state_scan_tree_static_limit(void);
+zeco_status zeco_state_scan_tree_static(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, const float *S_loc,
+                                        const float *G_tot, const float *S0, float *S_init, float *S_last,
+                                        int32_t direction, int32_t gate_per_head, void *stream);
 
 /* Initial-state correction (Eq. (global-correction) carried to the output; the highlighted term
  * of Alg. 1's output pass, with Lambda_t .* gamma~_[n-1] = exp(G_cum[t])):

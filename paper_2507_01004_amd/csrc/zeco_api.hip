@@ -4,6 +4,15 @@
 #include "../../include/zeco.h"
 #include "zeco_internal.h"
 
+#include <atomic>
+
+// Scratch of zeco_state_scan_tree_static, the entry point for callers that cannot allocate: a fixed array in
+// the library's device image, one copy per GPU the library runs on, held until the process ends.  In host
+// code this name only identifies the symbol - it is not a device address; the address on the current GPU
+// comes from hipGetSymbolAddress (static_scratch() below) and that pointer is what the launches are given.
+constexpr size_t kStaticScratchBytes = (size_t)33 << 20;
+static __device__ __align__(256) unsigned char zeco_static_scratch[kStaticScratchBytes];
+
 namespace {
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -108,6 +117,27 @@ size_t chain_scratch_floats(int P, int BH, int d_k, int d_v, int gate_per_head) 
 }
 hipError_t launch_scan_chain(const zeco::ScanParams &sp, float *scratch, hipStream_t s) {
     return chain_wants_tree(sp.P, sp.BH) ? launch_scan_tree(sp, scratch, s) : zeco::launch_scan(sp, s);
+}
+
+// Device address of zeco_static_scratch on the current GPU.  Every GPU has its own copy of the array at its
+// own address, so the address is looked up once per device, with that device current, and kept.  (Two
+// threads that make a device's first call together both look up the same address; no lock is needed.)
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_static_scratch[kMaxDevices];
+hipError_t static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *ptr = g_static_scratch[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(zeco_static_scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_static_scratch[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return hipSuccess;
 }
 
 }  // namespace
@@ -675,6 +705,29 @@ zeco_status zeco_state_scan_tree(int32_t P, int32_t BH, int32_t d_k, int32_t d_v
     return from_hip(launch_scan_tree(p, static_cast<float *>(workspace), static_cast<hipStream_t>(stream)));
 }
 
+size_t zeco_state_scan_tree_static_limit(void) { return kStaticScratchBytes; }
+
+zeco_status zeco_state_scan_tree_static(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, const float *S_loc,
+                                        const float *G_tot, const float *S0, float *S_init, float *S_last,
+                                        int32_t direction, int32_t gate_per_head, void *stream) {
+    // the size check comes first: it needs nothing but the four sizes
+    const size_t need = zeco_state_scan_tree_workspace(P, BH, d_k, d_v, gate_per_head);
+    if (need > kStaticScratchBytes) return ZECO_ERR_SCRATCH_LIMIT;
+    if (need == 0)   // the chain is not split (or an argument is bad, which the workspace variant reports)
+        return zeco_state_scan_tree(P, BH, d_k, d_v, S_loc, G_tot, S0, S_init, S_last, direction, gate_per_head,
+                                    nullptr, 0, stream);
+    // Validate what zeco_state_scan_tree validates before the first HIP call (the lookup below is one).
+    if (d_k % 16 != 0 || (direction != 0 && direction != 1) || (gate_per_head != 0 && gate_per_head != 1))
+        return ZECO_ERR_INVALID_ARG;
+    if (!S_loc || !G_tot || !S_init) return ZECO_ERR_INVALID_ARG;
+    void *scratch = nullptr;
+    if (static_scratch(&scratch) != hipSuccess) return ZECO_ERR_HIP;
+    // The three passes write every byte of the scratch they later read (group end states and decay sums, then
+    // the states entering the groups), so whatever an earlier call left there does not matter.
+    return zeco_state_scan_tree(P, BH, d_k, d_v, S_loc, G_tot, S0, S_init, S_last, direction, gate_per_head,
+                                scratch, kStaticScratchBytes, stream);
+}
+
 zeco_status zeco_apply_init_state(const zeco_gla_desc *d, const void *q, const float *G_cum,
                                   const float *S_init, void *o, int32_t flags, void *stream) {
     const zeco_status st = check_desc(d, true);
@@ -875,6 +928,7 @@ const char *zeco_status_string(int32_t status) {
         case ZECO_ERR_UNSUPPORTED: return "unsupported configuration";
         case ZECO_ERR_WORKSPACE: return "workspace too small";
         case ZECO_ERR_HIP: return "HIP runtime error";
+        case ZECO_ERR_SCRATCH_LIMIT: return "problem needs more than the library's static scratch";
         default: return "unknown status";
     }
 }

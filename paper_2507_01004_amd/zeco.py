@@ -13,12 +13,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libzeco.so")
 
-ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP = range(5)
+ZECO_OK, ZECO_ERR_INVALID_ARG, ZECO_ERR_UNSUPPORTED, ZECO_ERR_WORKSPACE, ZECO_ERR_HIP, ZECO_ERR_SCRATCH_LIMIT = range(6)
 ZECO_F32, ZECO_BF16 = 0, 1
 APPLY_FIRST_SEGMENT_ZERO, APPLY_DENSE = 1, 2
 SCHEDULE_AUTO, SCHEDULE_TWO_PHASE, SCHEDULE_CORRECT = 0, 1, 2
 EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_scan",
            "zeco_state_scan_tree_workspace", "zeco_state_scan_tree",
+           "zeco_state_scan_tree_static_limit", "zeco_state_scan_tree_static",
            "zeco_apply_init_state", "zeco_gla_local_fwd_varlen", "zeco_apply_init_state_varlen",
            "zeco_gla_local_state_varlen", "zeco_gla_fwd_from_state_varlen",
            "zeco_gla_bwd_dstate_varlen", "zeco_gla_bwd_from_state_varlen",
@@ -69,6 +70,10 @@ def lib():
         L.zeco_state_scan_tree_workspace.restype = ctypes.c_size_t
         L.zeco_state_scan_tree.argtypes = [i32, i32, i32, i32, fp, fp, fp, fp, fp, i32, i32, vp, ctypes.c_size_t, vp]
         L.zeco_state_scan_tree.restype = i32
+        L.zeco_state_scan_tree_static_limit.argtypes = []
+        L.zeco_state_scan_tree_static_limit.restype = ctypes.c_size_t
+        L.zeco_state_scan_tree_static.argtypes = [i32, i32, i32, i32, fp, fp, fp, fp, fp, i32, i32, vp]
+        L.zeco_state_scan_tree_static.restype = i32
         L.zeco_apply_init_state.argtypes = [dp, vp, fp, fp, vp, i32, vp]
         L.zeco_apply_init_state.restype = i32
         L.zeco_gla_local_fwd_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, vp, vp, fp, fp, fp, vp]
@@ -258,6 +263,26 @@ def state_scan_tree(S_loc, G_tot, S0=None, out=None, direction=0, workspace=None
                                     int(direction), per_head, _ptr(workspace), workspace.numel(), _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_state_scan_tree")
+    return S_init, S_last
+
+
+def state_scan_tree_static(S_loc, G_tot, S0, out, direction=0):
+    """zeco_state_scan_tree_static: zeco_state_scan_tree on the library's own fixed scratch.  The call
+    allocates nothing, and neither does this wrapper: the outputs (S_init, S_last) are the caller's."""
+    if not S_loc.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    P, dk, dv = S_loc.shape[0], S_loc.shape[-2], S_loc.shape[-1]
+    BH = S_loc.numel() // (P * dk * dv)
+    if not (S_loc.is_contiguous() and G_tot.is_contiguous()):
+        raise ValueError("S_loc and G_tot must be contiguous")
+    S_init, S_last = out
+    if G_tot.numel() not in (P * BH, P * BH * dk):
+        raise ValueError("G_tot must be [P,BH,d_k] or, for per-head gates, [P,BH]")
+    per_head = int(G_tot.numel() == P * BH and dk != 1)
+    st = lib().zeco_state_scan_tree_static(P, BH, dk, dv, _ptr(S_loc), _ptr(G_tot), _ptr(S0), _ptr(S_init),
+                                           _ptr(S_last), int(direction), per_head, _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_state_scan_tree_static")
     return S_init, S_last
 
 

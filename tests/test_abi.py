@@ -35,7 +35,7 @@ def test_exports_match_header(L):
 def test_version_and_strings(L):
     assert zeco.version() >= 100
     assert zeco.status_string(zeco.ZECO_OK) == "ok"
-    for s in range(1, 5):
+    for s in range(1, 6):
         assert zeco.status_string(s) not in ("ok", "unknown status")
     assert zeco.status_string(99) == "unknown status"
 
@@ -244,3 +244,18 @@ def test_a_missing_library_raises_instead_of_falling_back(monkeypatch):
         zeco.lib()
     with pytest.raises(RuntimeError, match="not built"):
         zeco.version()
+
+
+def test_static_scratch_scan_checks_its_limit_before_any_hip_call(L):
+    """zeco_state_scan_tree_static: the limit is the stated 33 MiB; a problem whose group states do not fit
+    is refused with its own status, with no pointer read and no HIP call made."""
+    limit = L.zeco_state_scan_tree_static_limit()
+    assert limit == 33 << 20
+    call = lambda P, BH, S_loc=FAKE: L.zeco_state_scan_tree_static(P, BH, 128, 128, S_loc, FAKE, None, FAKE, None, 0, 0, None)
+    assert L.zeco_state_scan_tree_workspace(1024, 4, 128, 128, 0) <= limit      # the largest case it is meant for
+    assert L.zeco_state_scan_tree_workspace(1024, 8, 128, 128, 0) > limit
+    assert call(1024, 8) == zeco.ZECO_ERR_SCRATCH_LIMIT
+    assert call(1024, 8, S_loc=None) == zeco.ZECO_ERR_SCRATCH_LIMIT             # the size check comes first
+    assert call(36, 2, S_loc=None) == zeco.ZECO_ERR_INVALID_ARG
+    assert call(0, 2) == zeco.ZECO_ERR_INVALID_ARG
+    assert call(37, 0) == zeco.ZECO_OK                                          # empty batch

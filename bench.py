@@ -7,7 +7,11 @@ whole-job throughput (tokens/s), the roofline of the dominant kernel (the chunk 
 local pass) measured live with HIP events on the launch stream, and the CPU oracle timed on a
 bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c4|c5] [--g-dtype f32|bf16]
+The default workload is c5 (H = 8, 256 segments x 32768 tokens = 8.4 M tokens, 128 GiB of tensors), the largest
+configuration that fits one GPU; the same legs at c3 and the single-segment case c2 are appended under
+`other_workloads`.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c4|c3|c2] [--g-dtype f32|bf16]
 """
 import argparse
 import json
@@ -24,6 +28,8 @@ MFMA_BF16_PEAK_TF = 2500.0  # dense bf16
 
 # HBM bytes per launch of the chunk kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/pipeline_kernels_c2_c3_c4_c5.md gives the commands and the copy-kernel calibration); None = not measured.
+# c5: not measured (the counter pass of that workload ended in the profiler before any kernel ran and is not
+# repeated); c4 runs the same instantiation of the chunk kernel, one workgroup per stream.
 MEASURED_TRAFFIC = {("c3", "f32"): 4305900000, ("c4", "f32"): 34469000000}   # profiles/pipeline_kernels_c2_c3_c4_c5.md
 
 
@@ -194,49 +200,18 @@ def unequal_segments_case(args, inp, P, T):
     return rows
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
-    ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
-    ap.add_argument("--gate", default="channel", choices=["channel", "head"],
-                    help="one log decay per (token, head, channel) as in GLA (default), or per (token, head)")
-    ap.add_argument("--k-blocks", type=int, default=16)
-    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-backward", action="store_true", help="skip the backward timing")
-    ap.add_argument("--no-cold-scan", action="store_true", help="skip the cold-cache timing of the scan")
-    ap.add_argument("--no-variants", action="store_true", help="skip the bf16-gate timing")
-    ap.add_argument("--only-pipeline", action="store_true",
-                    help="time the three calls (and the calibration copy) only: no fused, backward, variant or "
-                         "cold-scan legs (for profiler runs, whose per-kernel statistics then cover one launch "
-                         "shape each)")
-    ap.add_argument("--only-backward", action="store_true",
-                    help="besides the three calls, time only the backward (and the training pair)")
-    ap.add_argument("--only-fused", action="store_true",
-                    help="besides the three calls, time only the fused forward (both schedules)")
-    ap.add_argument("--dense-correction", action="store_true",
-                    help="pass ZECO_APPLY_DENSE to the correction of the timed pipeline")
-    ap.add_argument("--layout", default="bthd", choices=["bthd", "bhtd"],
-                    help="memory order of q/k/v/g/o: token-major (default) or head-major")
-    ap.add_argument("--calib-copy-mib", type=int, default=1024,
-                    help="size of the plain copy timed beside the kernels (0 = skip)")
-    args = ap.parse_args()
-    if args.only_pipeline or args.only_fused:
-        args.no_backward = True
-    if args.only_pipeline or args.only_fused or args.only_backward:
-        args.no_cold_scan = args.no_variants = True
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (P sequence segments resident on one MI355X); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def free_gib():
+    import torch
+    return torch.cuda.mem_get_info()[0] / 2 ** 30
 
+
+def run_workload(args, workload, with_cpu):
+    """All legs of one workload; returns the JSON object of the line."""
+    import statistics
     import torch
     from paper_2507_01004_amd import synth, zeco
 
-    torch.cuda.set_device(0)
-    inp, c = synth.config_inputs(args.workload, device="cuda:0", g=args.g_dtype,
+    inp, c = synth.config_inputs(workload, device="cuda:0", g=args.g_dtype,
                                  per_head_gate=args.gate == "head")
     B, H, P, L, dk, dv = c["B"], c["H"], c["P"], c["L"], c["d_k"], c["d_v"]
     T = P * L
@@ -252,6 +227,8 @@ def main():
     g_cum = dk * 4 if args.gate == "channel" else 4
     S_init = torch.empty_like(S_loc)
     S_last = torch.empty(B, H, dk, dv, dtype=torch.float32, device="cuda:0")
+    tensor_gib = sum(t.numel() * t.element_size() for t in (q, k, v, g, o, G_cum)) / 2 ** 30
+    skipped = {}
 
     def step(ev=None):
         zeco.gla_local_fwd(q, k, v, g, P, out=(o, S_loc, G_cum, G_tot))
@@ -275,6 +252,19 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    def timed(fn, warm=None, reps=None):
+        for _ in range(args.warmup if warm is None else warm):
+            fn()
+        torch.cuda.synchronize()
+        fe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        n = args.steps if reps is None else reps
+        fe[0].record()
+        for _ in range(n):
+            fn()
+        fe[1].record()
+        torch.cuda.synchronize()
+        return fe[0].elapsed_time(fe[1]) / n
+
     # The same result by the fused entry point, by either of its schedules: two-phase (states, scan,
     # output pass from the scanned states) and local pass in chunk-decay form + scan + correction.
     # Reported beside the headline number, never as `value`.
@@ -285,19 +275,6 @@ def main():
         S_last2 = torch.empty_like(S_last)
         io = 2
         th = B * T * H
-
-        def timed(fn):
-            for _ in range(args.warmup):
-                fn()
-            torch.cuda.synchronize()
-            fe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            fe[0].record()
-            for _ in range(args.steps):
-                fn()
-            fe[1].record()
-            torch.cuda.synchronize()
-            return fe[0].elapsed_time(fe[1]) / args.steps
-
         fms = timed(lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws,
                                                schedule=zeco.SCHEDULE_TWO_PHASE))
         fb = th * (dk * io + dv * io + g_in)                        # phase 1: k, v, g
@@ -305,13 +282,12 @@ def main():
         two_phase = {"entry": "zeco_gla_fused_fwd(ZECO_SCHEDULE_TWO_PHASE)", "ms_per_step": round(fms, 4),
                      "tokens_per_s": round(B * T / (fms * 1e-3), 1), "alg_bytes": fb,
                      "GBps": round(fb / fms / 1e6, 1), "hbm_frac": round(fb / fms / 1e6 / HBM_PEAK_GBS, 4)}
-        if True:
-            cms = timed(lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws,
-                                                   schedule=zeco.SCHEDULE_CORRECT))
-            fused_correct = {"entry": "zeco_gla_fused_fwd(ZECO_SCHEDULE_CORRECT)", "ms_per_step": round(cms, 4),
-                             "tokens_per_s": round(B * T / (cms * 1e-3), 1),
-                             "note": "local pass (chunk-decay form) + scan + correction that stops where the decay "
-                                     "has vanished; traffic depends on the gates"}
+        cms = timed(lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o2, S_last2), workspace=ws,
+                                               schedule=zeco.SCHEDULE_CORRECT))
+        fused_correct = {"entry": "zeco_gla_fused_fwd(ZECO_SCHEDULE_CORRECT)", "ms_per_step": round(cms, 4),
+                         "tokens_per_s": round(B * T / (cms * 1e-3), 1),
+                         "note": "local pass (chunk-decay form) + scan + correction that stops where the decay "
+                                 "has vanished; traffic depends on the gates"}
         if args.gate == "channel" and not args.only_fused:
             # the three calls of the headline with the cumulative decay kept per chunk (Alg. 1's gamma~ list)
             G_chunk = torch.empty(B, T // 64, H, dk, dtype=torch.float32, device="cuda:0")
@@ -329,56 +305,9 @@ def main():
                            "local_GBps": round(lb / lms / 1e6, 1),
                            "local_hbm_frac": round(lb / lms / 1e6 / HBM_PEAK_GBS, 4)}
             del G_chunk
+            zeco.gla_local_fwd(q, k, v, g, P, out=(o, S_loc, G_cum, G_tot))   # S_loc, G_tot of the headline again
+            zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=(S_init, S_last))
         del ws, o2, S_last2
-
-    # Backward of the same workload (App. A.4), whole call: reported beside the headline number.
-    backward = None
-    if c["io"] == "bf16" and not args.no_backward:
-        gen = torch.Generator(device="cuda:0").manual_seed(99)
-        dO = torch.randn(v.shape, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
-        ws = torch.empty(max(zeco.fused_bwd_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
-        grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v),
-                 torch.empty(g.shape, dtype=torch.float32, device="cuda:0"), torch.empty_like(S_last))
-        for _ in range(max(1, args.warmup // 2)):
-            zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws)
-        torch.cuda.synchronize()
-        be = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        nb = max(1, args.steps // 2)
-        be[0].record()
-        for _ in range(nb):
-            zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws)
-        be[1].record()
-        torch.cuda.synchronize()
-        bms = be[0].elapsed_time(be[1]) / nb
-        th = B * T * H
-        # bytes of the four passes as built: forward states (k, v, g), dQ (dO, v, k, q, g in; dq and fp32 q.*dq
-        # out; it also leaves the pieces' state gradients), dV (k, q, dO, g in; dv out), dK (v, dO, q, k, g, fp32
-        # q.*dq in; dk and fp32 dg out)
-        io = dk * 2
-        pb = th * ((2 * io + g_in) + (5 * io + g_in + g_cum) + (4 * io + g_in) + (5 * io + g_in + 2 * g_cum))
-        # training pair: the forward leaves the states at the backward's piece boundaries, the backward
-        # starts from them instead of recomputing them
-        save = torch.empty(zeco.saved_states_bytes(q, v, g, P), dtype=torch.uint8, device="cuda:0")
-        wsf = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
-        o4 = torch.empty_like(v)
-        pair = {}
-        for nm, fn in (("fwd_saving_ms", lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last), workspace=wsf, save=save,
-                                                                    schedule=zeco.SCHEDULE_TWO_PHASE)),
-                       ("bwd_from_saved_ms", lambda: zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws, saved=save))):
-            fn()
-            torch.cuda.synchronize()
-            pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            pe[0].record()
-            for _ in range(nb):
-                fn()
-            pe[1].record()
-            torch.cuda.synchronize()
-            pair[nm] = round(pe[0].elapsed_time(pe[1]) / nb, 4)
-        del save, wsf, o4
-        backward = {"entry": "zeco_gla_fused_bwd", "ms_per_step": round(bms, 4), **pair,
-                    "tokens_per_s": round(B * T / (bms * 1e-3), 1), "pass_bytes": pb,
-                    "GBps": round(pb / bms / 1e6, 1), "hbm_frac": round(pb / bms / 1e6 / HBM_PEAK_GBS, 4)}
-        del ws, grads, dO
 
     # The same pipeline with the log decay stored in bf16 (256 B per token-head less to read): a data
     # format choice of the caller, reported beside the fp32-gate headline.
@@ -397,20 +326,11 @@ def main():
                                                                   schedule=zeco.SCHEDULE_TWO_PHASE)),
                          ("fused_correct", lambda: zeco.gla_fused_fwd(q, k, v, gh, P, out=(o2, S_last), workspace=ws,
                                                                       schedule=zeco.SCHEDULE_CORRECT))):
-            for _ in range(3):
-                fn()
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            nb = max(1, args.steps // 2)
-            e0.record()
-            for _ in range(nb):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            t = e0.elapsed_time(e1) / nb
+            t = timed(fn, warm=3, reps=max(1, args.steps // 2))
             res[name] = {"ms_per_step": round(t, 4), "tokens_per_s": round(B * T / (t * 1e-3), 1)}
         g_bf16 = res
         del gh, ws, o2
+        step()   # the fp32-gate outputs again
 
     copy_gbs = None
     if args.calib_copy_mib:
@@ -432,41 +352,89 @@ def main():
     if P > 1 and not args.dense_correction:
         # tokens per (segment, head) the default call works on: up to the first 64-token block whose
         # first token has G_cum < -105 in every channel
-        Gs = G_cum.view((B, P, L // 64, 64, H) + gdim)[:, 1:, :, 0]
-        alive = (Gs >= -105.0).any(dim=-1) if args.gate == "channel" else (Gs >= -105.0)
-        live_frac = float(alive.float().mean().item())
-        del Gs, alive
+        live = []
+        for p1 in range(1, P, 16):     # a few segments at a time: the comparison makes a temporary
+            Gs = G_cum.view((B, P, L // 64, 64, H) + gdim)[:, p1:p1 + 16, :, 0]
+            alive = (Gs >= -105.0).any(dim=-1) if args.gate == "channel" else (Gs >= -105.0)
+            live.append((float(alive.float().sum().item()), alive.numel()))
+            del Gs, alive
+        live_frac = sum(x for x, _ in live) / sum(n for _, n in live)
         if not (args.only_pipeline or args.only_fused or args.only_backward):
-            de = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
-            nd = max(1, args.steps // 2)
-            de[0].record()
-            for _ in range(nd):
-                zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True)
-            de[1].record()
-            torch.cuda.synchronize()
-            dense_ms = de[0].elapsed_time(de[1]) / nd
+            dense_ms = timed(lambda: zeco.apply_init_state(q, g, G_cum, S_init, o, P, first_segment_is_zero=True, dense=True),
+                             warm=1, reps=max(1, args.steps // 2))
 
-    import statistics
     samples = {n: [e[i].elapsed_time(e[i + 1]) for e in evs] for i, n in enumerate(["local", "scan", "apply"])}
     ms = {n: sum(x) / len(x) for n, x in samples.items()}
 
-    # The scan's working set fits the 256 MB Infinity Cache below c5: time it again with the caches
-    # flushed by a 512 MiB fill between iterations.
-    scan_cold = None
+    # The scan's working set may sit in the 256 MB Infinity Cache when it is timed in a loop.  Cold figures: after
+    # a sweep that READS 1 GiB (the caches then hold clean lines of something else: the scan's own HBM rate),
+    # and after a 512 MiB FILL (dirty lines that the scan's traffic has to push out on top of its own).
+    scan_cold = scan_cold_fill = None
     if not args.no_cold_scan:
-        junk = torch.empty(512 << 20, dtype=torch.uint8, device="cuda:0")
-        cold = []
-        for _ in range(10):
-            junk.fill_(3)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=(S_init, S_last))
-            e1.record()
-            torch.cuda.synchronize()
-            cold.append(e0.elapsed_time(e1))
-        scan_cold = statistics.median(cold)
+        junk = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        for mode in ("read", "fill"):
+            cold = []
+            for _ in range(10):
+                if mode == "read":
+                    junk.sum()
+                else:
+                    junk[:512 << 20].fill_(3)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                zeco.state_scan(S_loc, G_tot, K_blocks=args.k_blocks, out=(S_init, S_last))
+                e1.record()
+                torch.cuda.synchronize()
+                cold.append(e0.elapsed_time(e1))
+            if mode == "read":
+                scan_cold = statistics.median(cold)
+            else:
+                scan_cold_fill = statistics.median(cold)
         del junk
+
+    # Backward of the same workload (App. A.4), whole call: reported beside the headline number.  It needs
+    # dO, four gradients and its workspace; o and G_cum are released first (nothing below reads them).
+    backward = None
+    if c["io"] == "bf16" and not args.no_backward:
+        del o, G_cum
+        torch.cuda.empty_cache()
+        ws_bytes = zeco.fused_bwd_workspace_bytes(q, v, g, P)
+        need = (ws_bytes + zeco.saved_states_bytes(q, v, g, P) + zeco.fused_workspace_bytes(q, v, g, P)
+                + 5 * v.numel() * 2 + g.numel() * 4) / 2 ** 30
+        if need + 4 > free_gib():
+            skipped["backward"] = "needs %.0f GiB beside the inputs, %.0f GiB free" % (need, free_gib())
+        else:
+            gen = torch.Generator(device="cuda:0").manual_seed(99)
+            dO = torch.empty_like(v)
+            for t0 in range(0, T, 65536):
+                dO[:, t0:t0 + 65536] = torch.randn((B, min(65536, T - t0), H, dv), generator=gen, device="cuda:0").to(torch.bfloat16)
+            ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda:0")
+            grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v),
+                     torch.empty(g.shape, dtype=torch.float32, device="cuda:0"), torch.empty_like(S_last))
+            nb = max(1, args.steps // 2)
+            bms = timed(lambda: zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws),
+                        warm=max(1, args.warmup // 2), reps=nb)
+            th = B * T * H
+            # bytes of the four passes as built: forward states (k, v, g), dQ (dO, v, k, q, g in; dq and fp32 q.*dq
+            # out; it also leaves the pieces' state gradients), dV (k, q, dO, g in; dv out), dK (v, dO, q, k, g, fp32
+            # q.*dq in; dk and fp32 dg out)
+            io = dk * 2
+            pb = th * ((2 * io + g_in) + (5 * io + g_in + g_cum) + (4 * io + g_in) + (5 * io + g_in + 2 * g_cum))
+            # training pair: the forward leaves the states at the backward's piece boundaries, the backward
+            # starts from them instead of recomputing them
+            save = torch.empty(zeco.saved_states_bytes(q, v, g, P), dtype=torch.uint8, device="cuda:0")
+            wsf = torch.empty(max(zeco.fused_workspace_bytes(q, v, g, P), 16), dtype=torch.uint8, device="cuda:0")
+            o4 = torch.empty_like(v)
+            pair = {}
+            for nm, fn in (("fwd_saving_ms", lambda: zeco.gla_fused_fwd(q, k, v, g, P, out=(o4, S_last), workspace=wsf, save=save,
+                                                                        schedule=zeco.SCHEDULE_TWO_PHASE)),
+                           ("bwd_from_saved_ms", lambda: zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws, saved=save))):
+                pair[nm] = round(timed(fn, warm=1, reps=nb), 4)
+            del save, wsf, o4
+            backward = {"entry": "zeco_gla_fused_bwd", "ms_per_step": round(bms, 4), **pair,
+                        "tokens_per_s": round(B * T / (bms * 1e-3), 1), "pass_bytes": pb,
+                        "GBps": round(pb / bms / 1e6, 1), "hbm_frac": round(pb / bms / 1e6 / HBM_PEAK_GBS, 4)}
+            del ws, grads, dO
+
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(c, g_in, g_cum)
     af = algorithmic_flops(c)
@@ -481,6 +449,7 @@ def main():
                 kernels[n]["TFLOPs"] = round(af[n] / ms[n] / 1e9, 1)
                 kernels[n]["mfma_frac"] = round(af[n] / ms[n] / 1e9 / MFMA_BF16_PEAK_TF, 4)
     kernels["local"]["tokens_per_s"] = round(B * T / (ms["local"] * 1e-3), 1)
+    dense_step = None
     if live_frac is not None and "apply" in kernels:
         ka = kernels["apply"]
         ka["live_fraction"] = round(live_frac, 4)
@@ -496,10 +465,17 @@ def main():
             ka["dense_alg_bytes"] = ab["apply"]
             ka["dense_GBps"] = round(ab["apply"] / dense_ms / 1e6, 1)
             ka["dense_hbm_frac"] = round(ab["apply"] / dense_ms / 1e6 / HBM_PEAK_GBS, 4)
+            # the step with the correction streaming every token (gates near 1 leave no other choice)
+            dms = ms["local"] + ms["scan"] + dense_ms
+            dense_step = {"ms_per_step": round(dms, 4), "tokens_per_s": round(B * T / (dms * 1e-3), 1),
+                          "note": "local + scan as timed + the dense correction: what the step costs when no decay vanishes"}
     if scan_cold:
         kernels["scan"]["cold_cache_ms"] = round(scan_cold, 4)
         kernels["scan"]["cold_cache_GBps"] = round(ab["scan"] / scan_cold / 1e6, 1)
-        kernels["scan"]["note"] = "GBps is effective (working set may sit in the Infinity Cache); cold_cache_* after a 512 MiB fill"
+        kernels["scan"]["cold_after_fill_ms"] = round(scan_cold_fill, 4)
+        kernels["scan"]["cold_after_fill_GBps"] = round(ab["scan"] / scan_cold_fill / 1e6, 1)
+        kernels["scan"]["note"] = ("GBps is effective (working set may sit in the Infinity Cache); cold_cache_* after a "
+                                   "1 GiB read sweep, cold_after_fill_* after a 512 MiB fill (dirty lines to evict)")
     ach = ab["local"] / ms["local"] / 1e6
     out = {
         "metric": "tokens/s for GLA segment fwd + state scan (1 MI355X)",
@@ -509,14 +485,15 @@ def main():
         "dtype": c["io"], "data": "synthetic",
         "config": {"workload": "%s: B=%d H=%d P=%d segments x L=%d tokens, d_k=d_v=%d, C=%d, %s q/k/v/o, "
                                "%s log-decay per %s; local fwd + segment-state scan + init-state correction"
-                               % (args.workload, B, H, P, L, dk, c["C"], c["io"], args.g_dtype,
+                               % (workload, B, H, P, L, dk, c["C"], c["io"], args.g_dtype,
                                   "channel" if args.gate == "channel" else "head"),
-                   "K_blocks": args.k_blocks, "layout": args.layout},
+                   "K_blocks": args.k_blocks, "layout": args.layout, "tensor_GiB": round(tensor_gib, 1)},
         "roofline": {"kernel": "gla_chunk_bf16_kernel (zeco_gla_local_fwd)", "bound": "hbm",
                      "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC.get((args.workload, args.g_dtype)) if args.gate == "channel" else None},
+                     "traffic": MEASURED_TRAFFIC.get((workload, args.g_dtype)) if args.gate == "channel" else None},
         "kernels": kernels,
+        "dense_correction_step": dense_step,
         "two_phase": two_phase,
         "fused_correct": fused_correct,
         "chunk_decay": chunk_decay,
@@ -524,13 +501,72 @@ def main():
         "g_bf16": g_bf16,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
     }
-    if args.workload != "c2" and not (args.only_pipeline or args.only_fused or args.only_backward):
-        out["single_segment_c2"] = single_segment_case(args)
-        out["scan_variants"] = scan_variants_case(args)
+    if skipped:
+        out["skipped"] = skipped
+    if workload == "c3" and not (args.only_pipeline or args.only_fused or args.only_backward):
         if c["io"] == "bf16" and args.gate == "channel" and P >= 2:
             out["unequal_segments"] = unequal_segments_case(args, inp, P, T)
-    if not args.no_cpu:
+    if with_cpu:
         out["cpu_baseline"] = cpu_baseline(inp, c, min(T, 131072))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c5", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--g-dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--gate", default="channel", choices=["channel", "head"],
+                    help="one log decay per (token, head, channel) as in GLA (default), or per (token, head)")
+    ap.add_argument("--k-blocks", type=int, default=16)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-backward", action="store_true", help="skip the backward timing")
+    ap.add_argument("--no-cold-scan", action="store_true", help="skip the cold-cache timing of the scan")
+    ap.add_argument("--no-variants", action="store_true", help="skip the bf16-gate timing")
+    ap.add_argument("--no-others", action="store_true", help="skip the c3 / c2 / scan legs appended to the default workload")
+    ap.add_argument("--only-pipeline", action="store_true",
+                    help="time the three calls (and the calibration copy) only: no fused, backward, variant or "
+                         "cold-scan legs (for profiler runs, whose per-kernel statistics then cover one launch "
+                         "shape each)")
+    ap.add_argument("--only-backward", action="store_true",
+                    help="besides the three calls, time only the backward (and the training pair)")
+    ap.add_argument("--only-fused", action="store_true",
+                    help="besides the three calls, time only the fused forward (both schedules)")
+    ap.add_argument("--dense-correction", action="store_true",
+                    help="pass ZECO_APPLY_DENSE to the correction of the timed pipeline")
+    ap.add_argument("--layout", default="bthd", choices=["bthd", "bhtd"],
+                    help="memory order of q/k/v/g/o: token-major (default) or head-major")
+    ap.add_argument("--calib-copy-mib", type=int, default=1024,
+                    help="size of the plain copy timed beside the kernels (0 = skip)")
+    args = ap.parse_args()
+    if args.only_pipeline or args.only_fused:
+        args.no_backward = True
+    if args.only_pipeline or args.only_fused or args.only_backward:
+        args.no_cold_scan = args.no_variants = args.no_others = True
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (P sequence segments resident on one MI355X); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    torch.cuda.set_device(0)
+    out = run_workload(args, args.workload, with_cpu=not args.no_cpu)
+    torch.cuda.empty_cache()
+    if not args.no_others:
+        others = {}
+        if args.workload != "c3":
+            r = run_workload(args, "c3", with_cpu=False)
+            torch.cuda.empty_cache()
+            others["c3"] = {n: r[n] for n in ("value", "ms_per_step", "config", "roofline", "kernels", "dense_correction_step",
+                                              "two_phase", "fused_correct", "chunk_decay", "backward", "g_bf16",
+                                              "unequal_segments") if n in r}
+        if args.workload != "c2":
+            others["c2"] = single_segment_case(args)
+        out["other_workloads"] = others
+        out["scan_variants"] = scan_variants_case(args)
     print(json.dumps(out))
 
 

@@ -216,9 +216,9 @@ zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *desc, const int6
 
 /* The backward's building blocks (zeco_gla_bwd_dstate, zeco_gla_bwd_from_state below) over the same table:
  * every segment's state gradient from dS = 0; then, after the reverse zeco_state_scan, dq, dk, dv, dg of
- * every segment.  Arguments as in the equal-length calls.  The segments are not cut into shorter pieces, so
- * dg carries the rounding noise of a running sum over a whole segment (about 2 % of max|dg| at 1000 tokens,
- * 4 % at 8000); dq, dk, dv do not.  bf16 q/k/v only (fp32 returns ZECO_ERR_UNSUPPORTED). */
+ * every segment.  Arguments as in the equal-length calls; the workspace is
+ * zeco_gla_bwd_from_state_workspace(desc) bytes, sized for the bound desc->L on the lengths.
+ * bf16 q/k/v only (fp32 returns ZECO_ERR_UNSUPPORTED). */
 zeco_status zeco_gla_bwd_dstate_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
                                        const void *q, const void *g, const void *dO, float *dS_loc,
                                        void *stream);
@@ -226,7 +226,7 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *desc, const int6
                                            const void *q, const void *k, const void *v, const void *g,
                                            const void *dO, const float *S_init, const float *S_last,
                                            const float *dS_in, void *dq, void *dk, void *dv, float *dg,
-                                           void *stream);
+                                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
  * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
@@ -293,11 +293,20 @@ zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *desc, const void *q, const 
  *   dq, dk, dv as in App. A.4 (the chunk states S_[n], dS_[n] are recomputed on chip, never stored);
  *   dg_t = sum over the segment's tokens s >= t of (q_s .* dq_s - k_s .* dk_s)
  *          + row sums of dS_in[p] .* S_end[p],  S_end[p] = S_init[p+1] (S_last for the last segment):
- *          the reverse cumulative sum of the listing's last line, carried across segments. */
+ *          the reverse cumulative sum of the listing's last line, carried across segments.
+ * The two products of that sum nearly cancel, and what is left of it after thousands of tokens is mostly the
+ * rounding noise of the bf16 matrix operands.  The sum is therefore restarted every 512 tokens from its
+ * exactly known value there, the row sums of (gradient of the state) .* (forward state) at that token:
+ * the dQ pass leaves the forward states at those tokens in the workspace, the dK pass reads them back.
+ * workspace: zeco_gla_bwd_from_state_workspace(desc) bytes of device memory (a d_k x d_v fp32 state per 512
+ * tokens and head; 0 for segments of up to 512 tokens), 16-byte aligned, caller-owned, contents unspecified
+ * afterwards; ZECO_ERR_WORKSPACE when too small. */
+size_t zeco_gla_bwd_from_state_workspace(const zeco_gla_desc *desc);
 zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *desc, const void *q, const void *k,
                                     const void *v, const void *g, const void *dO, const float *S_init,
                                     const float *S_last, const float *dS_in, void *dq, void *dk,
-                                    void *dv, float *dg, void *stream);
+                                    void *dv, float *dg, void *workspace, size_t workspace_bytes,
+                                    void *stream);
 
 /* The whole backward in one call: recomputes the forward segment states (phase 1 and its scan, from
  * S0), runs the state-gradient pass and its reverse scan (from dS_T), then the gradient passes.  Like

@@ -31,6 +31,16 @@
 // anyway, subtracts K .* dK, accumulates and overwrites the array with dG.  Both do this one chunk
 // late, from the fp32 result tile left in LDS, in the gate pass's thread layout (coalesced rows).
 //
+// Re-anchoring.  What is left in that running sum is the rounding noise of the bf16 MFMA operands, a random
+// walk that grows with the square root of the tokens summed (about 1 % of max|dG| after 512 tokens, 4 % after
+// 8192).  At every chunk boundary the exact value of the sum is known: the contribution of all later tokens
+// to dG is row_sum(dS .* S) of the forward state at the boundary and its gradient.  The dQ pass holds that
+// state in its accumulators and the dK pass holds the gradient, so with a checkpoint array (S_ck) the dQ
+// pass stores the state entering every kAnchor-th chunk and the dK pass, when it arrives at the same
+// boundary from the other side, replaces its running value by the exact one.  For that the two passes
+// must cut a segment at the same tokens: with S_ck the dQ pass puts the short chunk of a length that is no
+// multiple of 64 at the segment's END (short_last), where the dK pass has it.
+//
 // State gradient of a segment as a by-product of the dQ pass (EMIT).  What a segment sends back to the
 // state entering it is  dS_loc = scale * sum_t (Q_t .* exp(G_t))^T dO_t  with G_t the log decay from
 // the segment's first token through t: the first loop of the backward listing run from dS = 0.  The
@@ -68,7 +78,8 @@ template <int DK, int DV, bool EMIT = false> struct QKCfg {
     static constexpr int kOffGam = kOffTot + NW * DK * 4;
     static constexpr int kOffTot2 = kOffGam + DK * 4;        // [wave][channel] sums of the dG terms
     static constexpr int kOffCarry = kOffTot2 + NW * DK * 4; // [channel] dG contribution of later segments
-    static constexpr int kOffXT = kOffCarry + DK * 4;        // EMIT: X^T (channel-major) and (Q .* exp(G))^T
+    static constexpr int kOffAnchor = kOffCarry + DK * 4;    // [channel] exact dG contribution at the last checkpoint passed
+    static constexpr int kOffXT = kOffAnchor + DK * 4;       // EMIT: X^T (channel-major) and (Q .* exp(G))^T
     static constexpr int kOffQT = kOffXT + (EMIT ? DV * TS : 0);
     static constexpr int kBytes = kOffQT + (EMIT ? DK * TS : 0);
 
@@ -80,6 +91,8 @@ template <int DK, int DV, bool EMIT = false> struct QKCfg {
         return (j - jl) + 8 * ((jl / 4) % 4) + 4 * (jl / 16) + (jl % 4);
     }
 };
+
+constexpr int kAnchor = 8;   // chunks between two checkpoints of the forward state (512 tokens)
 
 __device__ __forceinline__ bf16x8 pack2x4(f32x4 a, f32x4 b) {
     u32x4 w = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]),
@@ -111,6 +124,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // chunk decay [channel]
     float *wtot2 = reinterpret_cast<float *>(lds + Cfg::kOffTot2);
     float *carry0 = reinterpret_cast<float *>(lds + Cfg::kOffCarry);
+    float *anchor = reinterpret_cast<float *>(lds + Cfg::kOffAnchor);
     unsigned char *Xt = lds + Cfg::kOffXT, *Qt = lds + Cfg::kOffQT;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -124,11 +138,13 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     // segment, [0, 64) or [L - 64, L); the gated operand, the log decays and the dG terms of the window's
     // surplus rows are taken as zero - they then touch no state, no decay and no other row - and their
     // gradient rows are not stored.
+    // (With checkpoints the dQ pass cuts like the dK pass: the short chunk is the segment's last one.)
+    const bool short_last = REV || p.short_last;
     auto cstart = [&](int c) {
-        if constexpr (REV) return (long long)c * 64 - (c == N - 1 ? pad : 0);
-        else return c ? (long long)c * 64 - pad : 0ll;
+        return short_last ? (long long)c * 64 - (c == N - 1 ? pad : 0) : (c ? (long long)c * 64 - pad : 0ll);
     };
-    auto dead = [&](int t) { return REV ? t < pad : t >= 64 - pad; };
+    auto dead = [&](int t) { return short_last ? t < pad : t >= 64 - pad; };
+    auto is_short = [&](int c) { return c == (short_last ? N - 1 : 0); };   // chunk c is the short one (if any is)
 
     // workgroup -> stream, dealt so that consecutive streams land on different XCDs
     const size_t sbh = blockIdx.x;                  // (seg * B + b) * H + h
@@ -281,8 +297,11 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
     };
     // second half (dK, after a barrier): add the later waves and the later chunks, store dG
-    auto dg_second = [&](long long tc, bool first) __attribute__((always_inline)) {
+    auto dg_second = [&](long long tc, bool first, int c) __attribute__((always_inline)) {
         float *row = dgb + (tc + tq * TPT) * gcs + (GH ? 0 : 4 * cq);
+        // chunk c ends at a checkpoint: what the later tokens contribute is known exactly (left in `anchor`
+        // when the pass crossed that boundary, two iterations ago)
+        if (p.S_ck && (c + 1) % kAnchor == 0 && c + 1 < N) carry = *reinterpret_cast<const f32x4 *>(anchor + 4 * cq);
         f32x4 later = carry, total = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int a = 0; a < 4; ++a) later[a] += later_in_wave[a];
@@ -317,8 +336,16 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         const long long t0 = cstart(chunk_of(n));                          // this chunk
         const long long t1 = cstart(chunk_of((n + 1 < N) ? n + 1 : n));    // chunk fetched meanwhile
         const long long tp = cstart(chunk_of((n > 0) ? n - 1 : 0));        // chunk finished last
-        const bool first = n == 0;                                         // the short chunk, if there is one
-        if (n > 0) dg_first(tp, n == 1);
+        const bool first = is_short(chunk_of(n));                          // the short chunk, if there is one
+        if (n > 0) dg_first(tp, is_short(chunk_of(n - 1)));
+        if constexpr (!REV) {
+            // checkpoint: the forward state entering this chunk, for the dK pass to re-anchor dG with
+            if (p.S_ck && n > 0 && n % kAnchor == 0) {
+                float *ck = p.S_ck + (sbh * p.n_ck + (n / kAnchor - 1)) * DK * DV + (size_t)(w * 16 + l16) * DV + 4 * kg;
+#pragma unroll
+                for (int it = 0; it < Cfg::NIT; ++it) *reinterpret_cast<f32x4 *>(ck + it * 16) = Sacc[it];
+            }
+        }
 
         // ---- gate pass, part 1: per-thread cumulative sums of g; X, Y, Y^T -> LDS -----------------
         f32x4 cs[TPT];
@@ -388,7 +415,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
         __syncthreads();
         if constexpr (REV) {
-            if (n > 0) dg_second(tp, n == 1);
+            if (n > 0) dg_second(tp, is_short(chunk_of(n - 1)), chunk_of(n - 1));
         }
 
         // ---- gate pass, part 2: stitch waves; Z~^T and the factor tile -> LDS ----------------------
@@ -568,6 +595,23 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             }
             Sacc[it] = acc;
         }
+        if constexpr (REV) {
+            // W is now the gradient of the state entering this chunk.  At a checkpoint: the exact dG
+            // contribution of this chunk and everything after it to the earlier tokens, row_sum(dS .* S)
+            const int c = chunk_of(n);
+            if (p.S_ck && c > 0 && c % kAnchor == 0) {
+                const float *ck = p.S_ck + (sbh * p.n_ck + (c / kAnchor - 1)) * DK * DV + (size_t)(w * 16 + l16) * DV + 4 * kg;
+                float acc = 0.f;
+#pragma unroll
+                for (int it = 0; it < Cfg::NIT; ++it) {
+                    const f32x4 x = *reinterpret_cast<const f32x4 *>(ck + it * 16);
+                    acc += (Sacc[it][0] * x[0] + Sacc[it][1] * x[1]) + (Sacc[it][2] * x[2] + Sacc[it][3] * x[3]);
+                }
+                acc += __shfl_xor(acc, 16, 64);
+                acc += __shfl_xor(acc, 32, 64);
+                if (kg == 0) anchor[w * 16 + l16] = acc;
+            }
+        }
         if constexpr (EMIT) {   // dS_loc^T += X^T (Q .* exp(G))
             bf16x8 qf[2];
 #pragma unroll
@@ -594,10 +638,10 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     }
     // dG terms of the last chunk processed
     const long long tl = cstart(chunk_of(N - 1));
-    dg_first(tl, N == 1);
+    dg_first(tl, is_short(chunk_of(N - 1)));
     if constexpr (REV) {
         __syncthreads();
-        dg_second(tl, N == 1);
+        dg_second(tl, is_short(chunk_of(N - 1)), chunk_of(N - 1));
     }
 }
 

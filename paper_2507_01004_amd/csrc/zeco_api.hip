@@ -469,12 +469,20 @@ static void fill_bwd_params(zeco::BwdQKParams &b, const zeco_gla_desc *d, int P,
     b.dg = dg; b.S_init = S_init; b.S_last = S_last;
 }
 
+// Checkpoints of the forward state per (batch, segment, head) that re-anchor dG: one at every 8th chunk
+// boundary inside a segment of (at most) L tokens.
+static int bwd_checkpoints(int L) { return (chunks_of(L) - 1) / 8; }
+static size_t bwd_checkpoint_floats(const zeco_gla_desc *d, int P, int L) {
+    return (size_t)d->B * P * d->H * bwd_checkpoints(L) * d->d_k * d->d_v;
+}
+
 static zeco_status bwd_dq_pass(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
                                const void *v, const void *g, const void *dO, const float *S_init,
                                const float *S_last, void *dq, float *dg, float *dS_loc, float *G_tot_out,
-                               hipStream_t s, const int64_t *seg_start = nullptr, int64_t T = 0) {
+                               float *S_ck, hipStream_t s, const int64_t *seg_start = nullptr, int64_t T = 0) {
     zeco::BwdQKParams b;
     fill_bwd_params(b, d, P, L, g, dg, S_init, S_last);
+    if (S_ck && bwd_checkpoints(L) > 0) { b.S_ck = S_ck; b.n_ck = bwd_checkpoints(L); b.short_last = 1; }
     b.seg_start = reinterpret_cast<const long long *>(seg_start); b.T = T;
     b.x = dO; b.y = v; b.z = k; b.z2 = q; b.out = dq; b.W_init = S_init; b.zscale = 1.f; b.oscale = d->scale;
     b.dS_loc = dS_loc; b.G_tot_out = G_tot_out; b.qscale = d->scale;
@@ -486,7 +494,7 @@ static zeco_status bwd_dq_pass(const zeco_gla_desc *d, int P, int L, const void 
 static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const void *q, const void *k,
                                     const void *v, const void *g, const void *dO, const float *S_init,
                                     const float *S_last, const float *dS_in, void *dk, void *dv,
-                                    float *dg, hipStream_t s, const int64_t *seg_start = nullptr,
+                                    float *dg, float *S_ck, hipStream_t s, const int64_t *seg_start = nullptr,
                                     int64_t T = 0) {
     const int gb = gate_mode(d);
     zeco::ChunkParams c;
@@ -501,6 +509,7 @@ static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const 
     fill_bwd_params(b, d, P, L, g, dg, S_init, S_last);
     b.seg_start = reinterpret_cast<const long long *>(seg_start); b.T = T;
     b.x = v; b.y = dO; b.z = q; b.z2 = k; b.out = dk; b.W_init = dS_in; b.zscale = d->scale; b.oscale = 1.f;
+    if (S_ck && bwd_checkpoints(L) > 0) { b.S_ck = S_ck; b.n_ck = bwd_checkpoints(L); }
     return from_hip(zeco::launch_bwd_qk(b, d->d_k, d->d_v, gb, true, s));
 }
 
@@ -519,13 +528,21 @@ zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *d, const void *q, const voi
                                             static_cast<hipStream_t>(stream)));
 }
 
+size_t zeco_gla_bwd_from_state_workspace(const zeco_gla_desc *desc) {
+    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    return bwd_checkpoint_floats(desc, desc->P, desc->L) * sizeof(float);
+}
+
 zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
                                     const void *g, const void *dO, const float *S_init, const float *S_last,
                                     const float *dS_in, void *dq, void *dk, void *dv, float *dg,
-                                    void *stream) {
+                                    void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    const size_t need = zeco_gla_bwd_from_state_workspace(d);
+    if (workspace_bytes < need) return ZECO_ERR_WORKSPACE;
+    if (need && (!workspace || !aligned16(workspace))) return ZECO_ERR_INVALID_ARG;
     if (!q || !k || !v || !g || !dO || !S_init || !S_last || !dS_in || !dq || !dk || !dv || !dg)
         return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
@@ -534,9 +551,10 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
         return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, s);
+    float *S_ck = need ? static_cast<float *>(workspace) : nullptr;
+    const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, S_ck, s);
     if (sq != ZECO_OK) return sq;
-    return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, s);
+    return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, S_ck, s);
 }
 
 // Pieces each segment is cut into by zeco_gla_fused_bwd: as in the forward, and further down to at most
@@ -566,7 +584,7 @@ static int bwd_pieces(const zeco_gla_desc *d) {
 // Workspace of zeco_gla_fused_bwd, in floats: forward piece states S_loc [n], S_init [n + one more
 // slot per (b,h) for the final state], their G_tot [n]; state gradients dS_loc [n], dS_in [n].
 struct BwdLayout {
-    size_t n, state, off_Sloc, off_Sinit, off_Gtot, off_dSloc, off_dSin, off_tree, total;
+    size_t n, state, off_Sloc, off_Sinit, off_Gtot, off_dSloc, off_dSin, off_tree, off_ck, total;
 };
 static BwdLayout bwd_layout(const zeco_gla_desc *d, int S) {
     BwdLayout w;
@@ -579,7 +597,9 @@ static BwdLayout bwd_layout(const zeco_gla_desc *d, int S) {
     w.off_dSloc = w.off_Gtot + w.n * d->d_k;
     w.off_dSin = w.off_dSloc + w.n * w.state;
     w.off_tree = w.off_dSin + w.n * w.state;   // scratch of the two piece scans where they run as trees
-    w.total = w.off_tree + chain_scratch_floats(d->P * S, d->B * d->H, d->d_k, d->d_v, d->g_per_head);
+    // checkpoints inside pieces that could not be cut down to 512 tokens (a chunk count without a fitting factor)
+    w.off_ck = w.off_tree + chain_scratch_floats(d->P * S, d->B * d->H, d->d_k, d->d_v, d->g_per_head);
+    w.total = w.off_ck + bwd_checkpoint_floats(d, d->P * S, d->L / S);
     return w;
 }
 
@@ -641,12 +661,13 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     // dQ from the forward states; the same pass leaves every piece's state gradient from dS = 0 (and
     // the pieces' total decays when the forward state pass did not run), which the reverse scan chains
     // from the last piece to the first
-    zeco_status zs = bwd_dq_pass(d, P, L, q, k, v, g, dO, Sin, Sl, dq, dg, dSloc, S_saved ? Gtot : nullptr, s);
+    float *S_ck = bwd_checkpoints(L) > 0 ? ws + w.off_ck : nullptr;
+    zeco_status zs = bwd_dq_pass(d, P, L, q, k, v, g, dO, Sin, Sl, dq, dg, dSloc, S_saved ? Gtot : nullptr, S_ck, s);
     if (zs != ZECO_OK) return zs;
     sp.S_loc = dSloc; sp.G_tot = Gtot; sp.S0 = dS_T; sp.S_init = dSin; sp.S_last = dS0; sp.reverse = 1;
     if ((e = launch_scan_chain(sp, ws + w.off_tree, s)) != hipSuccess) return ZECO_ERR_HIP;
 
-    return bwd_dv_dk_passes(d, P, L, q, k, v, g, dO, Sin, Sl, dSin, dk, dv, dg, s);
+    return bwd_dv_dk_passes(d, P, L, q, k, v, g, dO, Sin, Sl, dSin, dk, dv, dg, S_ck, s);
 }
 
 zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int32_t K_blocks,
@@ -860,10 +881,13 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *d, const int64_t
                                            const void *q, const void *k, const void *v, const void *g,
                                            const void *dO, const float *S_init, const float *S_last,
                                            const float *dS_in, void *dq, void *dk, void *dv, float *dg,
-                                           void *stream) {
+                                           void *workspace, size_t workspace_bytes, void *stream) {
     const zeco_status st = check_varlen(d, seg_start, T);
     if (st != ZECO_OK) return st;
     if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    const size_t need = zeco_gla_bwd_from_state_workspace(d);   // sized for the bound on the lengths
+    if (workspace_bytes < need) return ZECO_ERR_WORKSPACE;
+    if (need && (!workspace || !aligned16(workspace))) return ZECO_ERR_INVALID_ARG;
     if (!q || !k || !v || !g || !dO || !S_init || !S_last || !dS_in || !dq || !dk || !dv || !dg)
         return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
@@ -872,10 +896,11 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *d, const int64_t
         return ZECO_ERR_INVALID_ARG;
     if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, s,
+    float *S_ck = need ? static_cast<float *>(workspace) : nullptr;
+    const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, S_ck, s,
                                        seg_start, T);
     if (sq != ZECO_OK) return sq;
-    return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, s, seg_start, T);
+    return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, S_ck, s, seg_start, T);
 }
 
 // ---- chunk-decay form of the local pass and the correction ---------------------------------------------

@@ -91,6 +91,11 @@ struct BwdQKParams {
     // dS_loc [P,B,H,d_k,d_v] = qscale * sum_t (q_t .* exp(G_t))^T x_t, and its total log decay G_tot_out
     float *dS_loc = nullptr, *G_tot_out = nullptr;
     float qscale = 1.f;
+    // optional checkpoints that re-anchor dG: S_ck [B*P*H, n_ck, d_k, d_v], the forward state entering every
+    // 8th chunk (chunks 8, 16, ..) of each segment; written by the dQ pass, read by the dK pass.  With it the dQ
+    // pass must be launched with short_last = 1 (the short chunk of a ragged length at the segment's end).
+    float *S_ck = nullptr;
+    int n_ck = 0, short_last = 0;
     long long sb, st, sh, vb, vt, vh;
 };
 

@@ -26,7 +26,7 @@ EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_sca
            "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
            "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
-           "zeco_gla_bwd_from_state", "zeco_gla_fused_bwd_workspace", "zeco_gla_fused_bwd",
+           "zeco_gla_bwd_from_state_workspace", "zeco_gla_bwd_from_state", "zeco_gla_fused_bwd_workspace", "zeco_gla_fused_bwd",
            "zeco_hbm_copy", "zeco_status_string", "zeco_version")
 
 
@@ -86,7 +86,7 @@ def lib():
         L.zeco_gla_fwd_from_state_varlen.restype = i32
         L.zeco_gla_bwd_dstate_varlen.argtypes = [dp, vp, ctypes.c_int64, vp, vp, vp, fp, vp]
         L.zeco_gla_bwd_dstate_varlen.restype = i32
-        L.zeco_gla_bwd_from_state_varlen.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, vp]
+        L.zeco_gla_bwd_from_state_varlen.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, vp, ctypes.c_size_t, vp]
         L.zeco_gla_bwd_from_state_varlen.restype = i32
         L.zeco_gla_local_fwd_chunk_decay.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp]
         L.zeco_gla_local_fwd_chunk_decay.restype = i32
@@ -104,7 +104,9 @@ def lib():
         L.zeco_gla_fused_fwd.restype = i32
         L.zeco_gla_bwd_dstate.argtypes = [dp, vp, vp, vp, fp, vp]
         L.zeco_gla_bwd_dstate.restype = i32
-        L.zeco_gla_bwd_from_state.argtypes = [dp] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, vp]
+        L.zeco_gla_bwd_from_state.argtypes = [dp] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_bwd_from_state_workspace.argtypes = [dp]
+        L.zeco_gla_bwd_from_state_workspace.restype = ctypes.c_size_t
         L.zeco_gla_bwd_from_state.restype = i32
         L.zeco_gla_fused_bwd_workspace.argtypes = [dp]
         L.zeco_gla_fused_bwd_workspace.restype = ctypes.c_size_t
@@ -420,7 +422,15 @@ def gla_bwd_dstate_varlen(q, g, dO, seg_start, max_len, scale=1.0, out=None):
     return dS_loc
 
 
-def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, max_len, scale=1.0, out=None):
+def _bwd_from_state_workspace(desc, workspace, device):
+    need = int(lib().zeco_gla_bwd_from_state_workspace(ctypes.byref(desc)))
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, (workspace.numel() if workspace is not None else 0)
+
+
+def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, max_len, scale=1.0, out=None,
+                              workspace=None):
     """zeco_gla_bwd_from_state_varlen: dq, dk, dv, dg of every segment of the table from the scanned forward
     states and state gradients.  Returns (dq, dk, dv, dg)."""
     if not q.is_cuda:
@@ -429,9 +439,11 @@ def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, 
     _check_same_layout(v, dO)
     desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
     dq, dk, dv, dg = _grad_outputs(q, v, g) if out is None else out
+    workspace, ws_bytes = _bwd_from_state_workspace(desc, workspace, q.device)
     st = lib().zeco_gla_bwd_from_state_varlen(ctypes.byref(desc), _ptr(seg_start), q.shape[1], _ptr(q), _ptr(k),
                                               _ptr(v), _ptr(g), _ptr(dO), _ptr(S_init), _ptr(S_last), _ptr(dS_in),
-                                              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _stream())
+                                              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(workspace), ws_bytes,
+                                              _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_gla_bwd_from_state_varlen")
     return dq, dk, dv, dg
@@ -573,7 +585,7 @@ def _grad_outputs(q, v, g):
     return dq, dk, dv, dg
 
 
-def gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P, scale=1.0, C=64, out=None):
+def gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P, scale=1.0, C=64, out=None, workspace=None):
     """zeco_gla_bwd_from_state: dq, dk, dv, dg of every segment from the scanned forward states and
     state gradients.  Returns (dq, dk, dv, dg)."""
     if not q.is_cuda:
@@ -582,9 +594,10 @@ def gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P, scale=1.0, C=64
     _check_same_layout(v, dO)
     desc = make_desc(q, v, g, P, C, scale)
     dq, dk, dv, dg = _grad_outputs(q, v, g) if out is None else out
+    workspace, ws_bytes = _bwd_from_state_workspace(desc, workspace, q.device)
     st = lib().zeco_gla_bwd_from_state(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(dO),
                                        _ptr(S_init), _ptr(S_last), _ptr(dS_in), _ptr(dq), _ptr(dk),
-                                       _ptr(dv), _ptr(dg), _stream())
+                                       _ptr(dv), _ptr(dg), _ptr(workspace), ws_bytes, _stream())
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_gla_bwd_from_state")
     return dq, dk, dv, dg

@@ -40,3 +40,9 @@ def oracle_full(inp, scale=1.0, S0=None):
 
 def dev(a, dtype=torch.float32):
     return torch.from_numpy(np.ascontiguousarray(a)).to(dtype).cuda()
+
+
+def randn_seeded(shape, seed, dtype=torch.float32):
+    """Standard normal values on the GPU from a generator of their own (a failure must be reproducible)."""
+    gen = torch.Generator(device="cuda").manual_seed(int(seed))
+    return torch.randn(tuple(shape), device="cuda", generator=gen).to(dtype)

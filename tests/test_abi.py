@@ -109,7 +109,7 @@ def test_an_empty_batch_is_a_valid_no_op(L):
     assert L.zeco_gla_fwd_from_state(ref(d), N, N, N, N, N, N, N) == zeco.ZECO_OK
     assert L.zeco_gla_fused_fwd(ref(d), N, N, N, N, N, N, N, N, 0, N, 0, N) == zeco.ZECO_OK
     assert L.zeco_gla_bwd_dstate(ref(d), N, N, N, N, N) == zeco.ZECO_OK
-    assert L.zeco_gla_bwd_from_state(ref(d), *([N] * 12), N) == zeco.ZECO_OK
+    assert L.zeco_gla_bwd_from_state(ref(d), *([N] * 12), N, 0, N) == zeco.ZECO_OK
     assert L.zeco_gla_fused_bwd(ref(d), *([N] * 14), 0, N) == zeco.ZECO_OK
     assert L.zeco_gla_fused_fwd_workspace(ref(d)) == 0 and L.zeco_gla_local_fwd_workspace(ref(d)) == 0
 
@@ -148,7 +148,7 @@ def test_unequal_segment_lengths_validate_before_any_launch(L):
     dst = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_bwd_dstate_varlen(
         ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, None)
     bwd = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_bwd_from_state_varlen(
-        ref(d or good_desc(L=1000)), seg, T, q, *([FAKE] * 11), None)
+        ref(d or good_desc(L=1000)), seg, T, q, *([FAKE] * 11), FAKE, 1 << 30, None)
     for call in (sta, out, dst, bwd):
         assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
     for call in (loc, app, sta, out, dst, bwd):
@@ -200,9 +200,18 @@ def test_backward_entry_points_reject_bad_arguments(L):
     assert L.zeco_gla_bwd_dstate(ref(f32), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED
     assert L.zeco_gla_bwd_dstate(ref(good_desc(L=40)), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED   # shorter than a chunk
     args = [FAKE] * 12
-    assert L.zeco_gla_bwd_from_state(ref(f32), *args, None) == zeco.ZECO_ERR_UNSUPPORTED
+    assert L.zeco_gla_bwd_from_state(ref(f32), *args, None, 0, None) == zeco.ZECO_ERR_UNSUPPORTED
     args[7] = None                                         # dS_in missing
-    assert L.zeco_gla_bwd_from_state(ref(d), *args, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_bwd_from_state(ref(d), *args, None, 0, None) == zeco.ZECO_ERR_INVALID_ARG
+    # checkpoints of the forward state that re-anchor dG: one per 512 tokens inside a segment, none up to 512
+    wsz = L.zeco_gla_bwd_from_state_workspace
+    assert wsz(ref(d)) == 0 and wsz(ref(good_desc(L=512))) == 0 and wsz(ref(f32)) == 0
+    long = good_desc(L=16384)
+    assert wsz(ref(long)) == 1 * 2 * 2 * 31 * 128 * 128 * 4
+    assert wsz(ref(good_desc(L=513))) == 1 * 2 * 2 * 1 * 128 * 128 * 4
+    args = [FAKE] * 12
+    assert L.zeco_gla_bwd_from_state(ref(long), *args, FAKE, wsz(ref(long)) - 1, None) == zeco.ZECO_ERR_WORKSPACE
+    assert L.zeco_gla_bwd_from_state(ref(long), *args, None, wsz(ref(long)), None) == zeco.ZECO_ERR_INVALID_ARG
     need = L.zeco_gla_fused_bwd_workspace(ref(d))
     assert need > 0 and L.zeco_gla_fused_bwd_workspace(ref(f32)) == 0
     fused = [FAKE] * 5 + [None, None, None] + [FAKE] * 4 + [None, FAKE]

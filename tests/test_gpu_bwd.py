@@ -63,8 +63,9 @@ def test_fused_bwd_matches_unsegmented_oracle(case):
     name, B, H, P, L, dk, dv, gd = case
     print("case", case, flush=True)
     inp = make(case, gate_div=64.0)      # slow decay: states and state gradients reach every token
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
-    dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    gen = torch.Generator(device="cuda").manual_seed(zlib.crc32(name.encode()) % 10000 + 13)
+    S0 = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
+    dS_T = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
     for s0, dst in ((None, None), (S0, dS_T)):
         got = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], inp["dO"], P, scale=0.5, S0=s0, dS_T=dst)
         torch.cuda.synchronize()
@@ -74,7 +75,19 @@ def test_fused_bwd_matches_unsegmented_oracle(case):
         assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("case", [CASES[0], CASES[4]], ids=lambda c: c[0])
+# segments far beyond 512 tokens, where the dK pass re-anchors the running sum of dG at the forward-state
+# checkpoints the dQ pass left: whole chunks, a ragged length (the two passes must cut it at the same tokens),
+# a chunk count that is no multiple of 8, both state shapes and gate formats
+LONG_CASES = [
+    ("blocks_long", 1, 2, 2, 4096, 128, 128, "f32"),
+    ("blocks_long_ragged", 1, 2, 2, 4133, 128, 128, "f32"),
+    ("blocks_long_odd", 2, 1, 1, 3008, 64, 128, "bf16"),       # 47 chunks: 5 checkpoints, 7 chunks after the last
+    ("blocks_long_ragged_d64", 1, 3, 1, 1601, 64, 64, "f32"),  # 26 chunks, the last one holds a single token
+    ("blocks_513", 1, 2, 3, 513, 128, 64, "f32"),              # one checkpoint, nine chunks, the short one last
+]
+
+
+@pytest.mark.parametrize("case", [CASES[0], CASES[4]] + LONG_CASES, ids=lambda c: c[0])
 def test_bwd_building_blocks_chain(case):
     """The calls a sequence-parallel run makes around the two All-Scans: forward states, their scan,
     state gradients, the reverse scan, then the gradient passes, with P segments as given."""
@@ -134,7 +147,8 @@ def test_backward_from_states_saved_by_the_forward(case):
     print("case", case, flush=True)
     inp = make(case, gate_div=64.0)
     q, k, v, g, dO = (inp[n] for n in ("q", "k", "v", "g", "dO"))
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    gen = torch.Generator(device="cuda").manual_seed(zlib.crc32(name.encode()) % 10000 + 14)
+    S0 = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
     save = torch.empty(zeco.saved_states_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
     o, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0, save=save)
     o_plain, S_last_plain = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0)
@@ -158,8 +172,8 @@ def test_few_heads_long_sequence_scans_the_pieces_as_a_tree(H):
     gen = torch.Generator(device="cuda").manual_seed(501)
     dO = torch.randn(inp["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)
     q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
-    dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
+    dS_T = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
     o_r, S_r = oracle.gla_recurrent(host(q), host(k), host(v), host(g), 0.5, host(S0))
     ref = oracle.gla_recurrent_bwd(host(q), host(k), host(v), host(g), host(dO), 0.5, host(S0), host(dS_T))
     for sched in (zeco.SCHEDULE_TWO_PHASE, zeco.SCHEDULE_CORRECT):

@@ -116,6 +116,83 @@ def test_fullsize_backward_sampled_slices(name, samples):
             assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= TOL[c["io"]], nm
 
 
+def test_fullsize_backward_c5_sampled_slices():
+    """Config 5 (8.4 M tokens, half the heads decaying four times slower): the fused backward on one fast and
+    two slow heads; the slow heads are where states and state gradients carry furthest across the pieces."""
+    inp, c = synth.config_inputs("c5", device="cuda")
+    P, L, H = c["P"], c["L"], c["H"]
+    print("full-size backward c5", c, flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(4245)
+    dO = torch.empty_like(inp["v"])
+    for t0 in range(0, P * L, 1 << 16):      # slab by slab: the fp32 draw of the whole tensor would be 32 GiB
+        dO[:, t0:t0 + (1 << 16)] = torch.randn((1, 1 << 16, H, c["d_v"]), generator=gen, device="cuda").to(torch.bfloat16)
+    dq, dk, dv, dg, dS0 = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], dO, P)
+    torch.cuda.synchronize()
+    for (p, h) in [(128, 2), (0, 6), (255, 7)]:
+        print("  sample segment %d head %d" % (p, h), flush=True)
+        ref = slice_oracle_bwd(inp, dO, L, p, h, P, W["c5"])
+        for nm, x, r in zip(("dq", "dk", "dv", "dg"), (dq, dk, dv, dg), ref):
+            got = host(x[:1, p * L:(p + 1) * L, h:h + 1])
+            print("    %s rel err %.4f" % (nm, rel_err_bh(got, r, (0, 2))), flush=True)
+            assert rel_err_bh(got, r, (0, 2)) <= TOL[c["io"]], nm
+            assert rel_err_bh(got[:, :256], r[:, :256], (0, 2)) <= TOL[c["io"]], nm
+            assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= TOL[c["io"]], nm
+
+
+def test_fullsize_backward_building_blocks_sampled_slices():
+    """Config 3 through the calls a sequence-parallel rank makes around the two scans, with the segments as
+    given (16384 tokens each, not cut into pieces): forward states, scan, state gradients, reverse scan, gradient
+    passes.  dG is a running sum over a whole segment there, re-anchored every 512 tokens.  Then the same over
+    an unequal cut of the same tokens (three ragged lengths)."""
+    inp, c = synth.config_inputs("c3", device="cuda")
+    P, L, H = c["P"], c["L"], c["H"]
+    tol = TOL[c["io"]]
+    print("full-size backward building blocks", c, flush=True)
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    gen = torch.Generator(device="cuda").manual_seed(4246)
+    dO = torch.randn(v.shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    S_loc, G_tot = zeco.gla_local_state(k, v, g, P)
+    S_init, S_last = zeco.state_scan(S_loc, G_tot)
+    dS_loc = zeco.gla_bwd_dstate(q, g, dO, P)
+    dS_in, dS0 = zeco.state_scan(dS_loc, G_tot, direction=1)
+    grads = zeco.gla_bwd_from_state(q, k, v, g, dO, S_init, S_last, dS_in, P)
+    torch.cuda.synchronize()
+    for (p, h) in [(0, 3), (4, 7), (7, 15)]:
+        print("  sample segment %d head %d" % (p, h), flush=True)
+        ref = slice_oracle_bwd(inp, dO, L, p, h, P, W["c3"])
+        for nm, x, r in zip(("dq", "dk", "dv", "dg"), grads, ref):
+            got = host(x[:1, p * L:(p + 1) * L, h:h + 1])
+            print("    %s rel err %.4f" % (nm, rel_err_bh(got, r, (0, 2))), flush=True)
+            assert rel_err_bh(got, r, (0, 2)) <= tol, nm
+            assert rel_err_bh(got[:, :256], r[:, :256], (0, 2)) <= tol, nm
+            assert rel_err_bh(got[:, -256:], r[:, -256:], (0, 2)) <= tol, nm
+
+    lengths = [8190, 24576, 16384, 12291, 20480, 16387, 4100, 28664]
+    start = [0] + [int(x) for x in np.cumsum(lengths)]
+    seg = torch.tensor(start, dtype=torch.int64, device="cuda")
+    bound = max(lengths)
+    print("  unequal segments", lengths, flush=True)
+    S_loc, G_tot = zeco.gla_local_state_varlen(k, v, g, seg, bound)
+    S_init, S_last = zeco.state_scan(S_loc, G_tot)
+    dS_loc = zeco.gla_bwd_dstate_varlen(q, g, dO, seg, bound)
+    dS_in, dS0 = zeco.state_scan(dS_loc, G_tot, direction=1)
+    grads = zeco.gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg, bound)
+    torch.cuda.synchronize()
+    T = P * L
+    for (p, h) in [(0, 5), (3, 12), (7, 15)]:
+        print("  sample segment %d head %d" % (p, h), flush=True)
+        a, e = start[p], start[p + 1]
+        t0, t1 = max(0, a - W["c3"]), min(T, e + W["c3"])
+        hq, hk, hv, hg = (host(inp[n][:1, t0:t1, h:h + 1]) for n in ("q", "k", "v", "g"))
+        assert t0 == 0 or hg[0, :a - t0, 0].sum(axis=0).max() < np.log(1e-30)
+        assert t1 == T or hg[0, e - t0:, 0].sum(axis=0).max() < np.log(1e-30)
+        ref = oracle.gla_recurrent_bwd(hq, hk, hv, hg, host(dO[:1, t0:t1, h:h + 1]))
+        for nm, x, r in zip(("dq", "dk", "dv", "dg"), grads, ref[:4]):
+            got, r = host(x[:1, a:e, h:h + 1]), r[:, a - t0:e - t0]
+            print("    %s rel err %.4f" % (nm, rel_err_bh(got, r, (0, 2))), flush=True)
+            assert rel_err_bh(got, r, (0, 2)) <= tol, nm
+
+
 def test_fullsize_ragged_segment_length_sampled_slices():
     """c3's tensors cut to 8 segments of 16380 tokens (255 chunks and one of 60 tokens per segment; the
     fused backward cuts each into 35 pieces of 468): every forward route and the backward on sampled slices."""

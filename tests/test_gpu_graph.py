@@ -7,6 +7,7 @@ import pytest
 import torch
 
 from paper_2507_01004_amd import synth, zeco
+from tests.gpu_util import randn_seeded
 
 pytestmark = pytest.mark.gpu
 
@@ -15,7 +16,7 @@ def test_pipeline_forward_backward_replay_from_a_graph():
     B, H, P, L, dk, dv = 1, 4, 16, 128, 128, 128     # 16 segments: the tree scan really splits (8 groups of 2)
     inp = synth.make_inputs(B, P * L, H, dk, dv, seed=31, io="bf16", g="f32", device="cuda")
     q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
-    dO = torch.randn_like(v)
+    dO = randn_seeded(v.shape, 7301, v.dtype)
     T = P * L
     # every output and workspace is allocated before the capture
     o3 = torch.empty_like(v)

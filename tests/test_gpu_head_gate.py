@@ -9,7 +9,7 @@ import torch
 
 from oracle import oracle
 from paper_2507_01004_amd import synth, zeco
-from tests.gpu_util import TOL, host, log_err, rel_err_bh
+from tests.gpu_util import TOL, host, log_err, rel_err_bh, randn_seeded
 
 pytestmark = pytest.mark.gpu
 
@@ -59,7 +59,7 @@ def test_head_gate_three_call_forward(case):
     assert rel_err_bh(host(S_loc), S_r, (0, 1, 2)) <= TOLB
     assert log_err(host(G_cum), Gc_r[..., 0]) <= 1e-5
     assert log_err(host(G_tot), Gt_r[..., 0]) <= 1e-5
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7000) * 0.3
     o, S_last, parts = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=S0)
     torch.cuda.synchronize()
     o_f, S_f = oracle.gla_recurrent(h["q"], h["k"], h["v"], h["g"], 0.5, host(S0))
@@ -73,8 +73,8 @@ def test_head_gate_two_phase_forward_and_backward(case):
     print("case", case, flush=True)
     inp = make(case, gate_div=64.0)
     h = wide(inp, dk)
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
-    dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7001) * 0.3
+    dS_T = randn_seeded((B, H, dk, dv), 7002) * 0.3
     for s0, dst in ((None, None), (S0, dS_T)):
         for sched in (zeco.SCHEDULE_CORRECT, zeco.SCHEDULE_TWO_PHASE):
             o, S_last = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=s0, schedule=sched)

@@ -9,7 +9,7 @@ import torch
 
 from oracle import oracle
 from paper_2507_01004_amd import synth, zeco
-from tests.gpu_util import TOL, dev, host, log_err, oracle_full, oracle_local, rel_err_bh
+from tests.gpu_util import TOL, dev, host, log_err, oracle_full, oracle_local, rel_err_bh, randn_seeded
 
 pytestmark = pytest.mark.gpu
 
@@ -77,7 +77,7 @@ def test_pipeline_with_incoming_state_and_zero_gate(case):
     name, B, H, P, L, dk, dv, io, gd = case
     print("case", case, flush=True)
     inp = make(case, zero_gate=True)
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7100) * 0.3
     o, S_last, _ = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, S0=S0)
     torch.cuda.synchronize()
     o_r, Sf_r = oracle_full(inp, S0=host(S0))
@@ -280,7 +280,7 @@ def test_fp32_path_holds_its_tolerance_on_long_segments():
     for L in (4096, 4000):
         print("fp32 long", L, flush=True)
         inp = synth.make_inputs(B, P * L, H, dk, dv, seed=4096 + L, io="f32", g="f32", device="cuda", gate_div=64.0)
-        S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+        S0 = randn_seeded((B, H, dk, dv), 7101) * 0.3
         o, S_last, parts = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=S0)
         torch.cuda.synchronize()
         o_r, Sf_r = oracle_full(inp, scale=0.5, S0=host(S0))
@@ -357,7 +357,7 @@ def test_two_phase_forward_matches_oracle(case):
     assert rel_err_bh(host(S_loc), S_r, (0, 1, 2)) <= tol
     assert log_err(host(G_tot), Gt_r) <= 1e-5
     # phase 2 from the oracle's own scanned states (fp32 copies), against the unsegmented run
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7102) * 0.3
     for s0 in (None, S0):
         o_r, Sf_r = oracle_full(inp, scale=0.5, S0=None if s0 is None else host(s0))
         Si_r, _ = oracle.state_scan(S_r.reshape(P, B * H, dk, dv), Gt_r.reshape(P, B * H, dk),
@@ -394,7 +394,7 @@ def test_chunk_decay_form_matches_oracle(case):
     Gk_r[:, :, 1:] = Gc_r.reshape(B, P, N, 64, H, dk)[:, :, :-1, 63]
     assert log_err(host(G_chunk), Gk_r.reshape(B, P * N, H, dk)) <= 1e-5
     # correction from the oracle's scanned states and the oracle's chunk decays, on the oracle's local output
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7103) * 0.3
     o_full, _ = oracle_full(inp, scale=0.5, S0=host(S0))
     Si_r, _ = oracle.state_scan(S_r.reshape(P, B * H, dk, dv), Gt_r.reshape(P, B * H, dk), host(S0).reshape(B * H, dk, dv))
     o2 = torch.from_numpy(o_r).to(q.dtype).cuda()

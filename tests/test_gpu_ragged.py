@@ -11,7 +11,7 @@ import torch
 
 from oracle import oracle
 from paper_2507_01004_amd import synth, zeco
-from tests.gpu_util import TOL, dev, host, log_err, oracle_full, oracle_local, rel_err_bh
+from tests.gpu_util import TOL, dev, host, log_err, oracle_full, oracle_local, rel_err_bh, randn_seeded
 
 pytestmark = pytest.mark.gpu
 
@@ -101,7 +101,7 @@ def test_ragged_two_phase_chunk_decay_and_fused_forward(case):
     tol = TOL[io]
     inp = make(case, gate_div=64.0)
     q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7200) * 0.3
     o_l, S_r, Gc_r, Gt_r = oracle_local(inp, P, scale=0.5)
     # states only, output pass from the oracle's scanned states
     S_loc, G_tot = zeco.gla_local_state(k, v, g, P)
@@ -148,7 +148,7 @@ def test_ragged_per_head_gates():
                             per_head_gate=True)
     h = {n: host(t) for n, t in inp.items()}
     h["g"] = np.repeat(h["g"][..., None], dk, axis=-1)
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7201) * 0.3
     o_f, S_f = oracle.gla_recurrent(h["q"], h["k"], h["v"], h["g"], 0.5, host(S0))
     o, S_last, _ = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=S0)
     torch.cuda.synchronize()
@@ -197,8 +197,8 @@ def test_ragged_backward(case):
     tol = TOL["bf16"]
     inp = make_bwd(case, gate_div=64.0)
     q, k, v, g, dO = (inp[n] for n in ("q", "k", "v", "g", "dO"))
-    S0 = torch.randn(B, H, dk, dv, device="cuda") * 0.3
-    dS_T = torch.randn(B, H, dk, dv, device="cuda") * 0.3
+    S0 = randn_seeded((B, H, dk, dv), 7202) * 0.3
+    dS_T = randn_seeded((B, H, dk, dv), 7203) * 0.3
     for s0, dst in ((None, None), (S0, dS_T)):
         got = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, S0=s0, dS_T=dst)
         torch.cuda.synchronize()

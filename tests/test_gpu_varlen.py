@@ -129,10 +129,8 @@ def test_varlen_backward_building_blocks(case):
     ref = oracle.gla_recurrent_bwd(host(q), host(k), host(v), widen(g, dk), host(dO), 0.5, host(S0), host(dS_T))
     for nm, x, r in zip(("dq", "dk", "dv"), got[:3], ref[:3]):
         assert rel_err_bh(host(x), r, (0, 2)) <= tol, nm
-    # dg is a running sum over a whole segment here (no shorter pieces): its rounding noise grows with the
-    # square root of the segment length, 2 % of max|dg| being reached near 1000 tokens
-    dg_tol = tol if Lmax <= 700 else 2 * tol
-    assert rel_err_bh(host(got[3]), ref[3].sum(axis=-1) if ph else ref[3], (0, 2)) <= dg_tol, "dg"
+    # (dg: the running sum over a segment is re-anchored every 512 tokens, so long segments hold the bound too)
+    assert rel_err_bh(host(got[3]), ref[3].sum(axis=-1) if ph else ref[3], (0, 2)) <= tol, "dg"
     assert rel_err_bh(host(dS0), ref[4], (0, 1)) <= tol, "dS0"
 
 

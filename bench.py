@@ -132,7 +132,7 @@ def scan_variants_case(args):
     import torch
     from paper_2507_01004_amd import zeco
     rows = []
-    for P, BH in ((1024, 1), (1024, 2), (256, 8), (64, 16)):
+    for P, BH in ((128, 1), (256, 1), (1024, 1), (4096, 1), (256, 2), (1024, 2), (4096, 2), (1024, 4), (256, 8), (64, 16)):
         gen = torch.Generator(device="cuda:0").manual_seed(P + BH)
         S_loc = torch.randn(P, BH, 128, 128, device="cuda:0", generator=gen)
         G_tot = -torch.rand(P, BH, 128, device="cuda:0", generator=gen)
@@ -345,6 +345,20 @@ def run_workload(args, workload, with_cpu):
         torch.cuda.synchronize()
         copy_gbs = 5 * 2 * src.numel() / ce[0].elapsed_time(ce[1]) / 1e6
         del src, dst
+    # What the memory system gives plain coalesced streams with the kernels' ratios of reads to writes
+    # (zeco_hbm_mix: 256 MiB per stream): the scan is 1:1, the correction 4:1 (q, 2 x G_cum, o in; o out),
+    # the local pass 5:3 in units of 256 B per token-head (q, k, v, 2 x g in; o, 2 x G_cum out).
+    mix_gbs = None
+    if args.calib_copy_mib and with_cpu:
+        sl = 256 << 20
+        src = torch.empty(5 * sl, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty(3 * sl, dtype=torch.uint8, device="cuda:0")
+        mix_gbs = {}
+        for r, w in ((1, 0), (0, 1), (1, 1), (4, 1), (5, 3)):
+            zeco.hbm_mix(dst, src, sl, r, w)
+            t = timed(lambda: zeco.hbm_mix(dst, src, sl, r, w), warm=1, reps=5)
+            mix_gbs["%d:%d" % (r, w)] = round((r + w) * sl / t / 1e6, 1)
+        del src, dst
 
     # The correction stops, per (segment, head), where the decay factor exp(G_cum) has become an exact
     # zero; the same kernel made to stream every token gives its bandwidth on the full traffic.
@@ -500,6 +514,7 @@ def run_workload(args, workload, with_cpu):
         "backward": backward,
         "g_bf16": g_bf16,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
+        "hbm_mix_GBps": mix_gbs,
     }
     if skipped:
         out["skipped"] = skipped

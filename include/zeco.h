@@ -6,8 +6,10 @@
  *   - Tensor pointers are DEVICE pointers owned by the caller, 16-byte aligned.  The library never
  *     allocates, frees or synchronises; all work is enqueued on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream).
- *   - Arguments are validated before any HIP call; a non-zero status means nothing was launched
- *     (ZECO_ERR_HIP: a launch was refused by the runtime).  Outputs are unspecified on error.
+ *   - Arguments are validated before any HIP call: ZECO_ERR_INVALID_ARG, _UNSUPPORTED, _WORKSPACE and
+ *     _SCRATCH_LIMIT mean that nothing was launched and no output was touched.  ZECO_ERR_HIP means that the
+ *     runtime refused a launch (or a kernel attribute); entry points that launch several kernels may then
+ *     have enqueued the earlier ones, and the outputs are unspecified.
  *   - Results are deterministic (no atomics) and independent of launch-shape heuristics.
  *   - Notation: B batch, P segments (the paper's devices), L tokens per segment, T = P*L, H heads,
  *     C chunk length, g = log(alpha) <= 0 the LOG decay of Eq. (1), scale multiplies q
@@ -83,7 +85,8 @@ size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc);
  *   out  G_tot  [P,B,H,d_k] fp32 contiguous: G_cum at each segment's last token (log gamma~_[N])
  * bf16 io: bf16 MFMA operands, fp32 accumulation and fp32 state.  fp32 io: fp32 MFMA throughout.
  * Precondition: within any chunk, sum over tokens of |g| per channel < 80 (the intra-chunk
- * scores use K / Lambda as in Alg. 1, whose range is exp of that sum). */
+ * scores use K / Lambda as in Alg. 1, whose range is exp of that sum).  The call cannot check this: beyond
+ * the range the factors overflow and o and S_loc come out as inf / NaN while the status is still ZECO_OK. */
 zeco_status zeco_gla_local_fwd(const zeco_gla_desc *desc, const void *q, const void *k,
                                const void *v, const void *g, void *o, float *S_loc, float *G_cum,
                                float *G_tot, void *workspace, size_t workspace_bytes,
@@ -111,8 +114,8 @@ zeco_status zeco_state_scan(int32_t P, int32_t BH, int32_t d_k, int32_t d_v, int
  * state (its end state and total log decay), (2) the chain over the groups gives the state entering each
  * group and S_last, (3) every group is scanned again from the state entering it, which writes S_init.
  * The serial depth drops from P to about 2 g + P/g (g is chosen to minimise it over the divisors of P)
- * for one more read of S_loc: it pays where a single chain is latency-bound, i.e. few heads and many
- * segments; with many heads zeco_state_scan already streams at the memory rate and is the faster one.
+ * for one more read of S_loc: it pays where a single chain is latency-bound, i.e. one head and 512 segments
+ * or more; from two heads on zeco_state_scan has enough chains in flight and is the faster one.
  * Same arguments and conventions as zeco_state_scan; the result differs from it by rounding only (the
  * groups re-associate the sums), it is deterministic; d_k % 16 == 0.  When P has no divisor that
  * shortens the chain (P prime, P <= 4) the call is zeco_state_scan and needs no workspace.
@@ -130,8 +133,8 @@ zeco_status zeco_state_scan_tree(int32_t P, int32_t BH, int32_t d_k, int32_t d_v
  * device image, zeco_state_scan_tree_static_limit() bytes (33 MiB) on every GPU the library runs on, held
  * until the process ends.  The call allocates and frees nothing.
  *   - A problem whose zeco_state_scan_tree_workspace() exceeds the limit returns ZECO_ERR_SCRATCH_LIMIT and
- *     launches nothing (33 MiB covers 1024 segments of up to 4 heads at d_k = d_v = 128, the range in
- *     which the tree is the faster scan).
+ *     launches nothing (33 MiB covers 1024 segments of up to 4 heads, or 16384 segments of one head, at
+ *     d_k = d_v = 128; the tree is the faster scan only for few heads).
  *   - The first call on a device looks up the array's address on that device (hipGetSymbolAddress, no
  *     allocation, no synchronisation); make that call with the device current, as for every other call.
  *   - All calls on one GPU share that GPU's array.  Nothing in it has to start at zero and nothing is kept
@@ -227,6 +230,25 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *desc, const int6
                                            const void *dO, const float *S_init, const float *S_last,
                                            const float *dS_in, void *dq, void *dk, void *dv, float *dg,
                                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* The whole forward and the whole backward over the same table, each in one call, on the segments as given
+ * (they are not cut into shorter pieces: the longest segment sets a pass's duration): the three phases of
+ * Alg. 1 - states from the zero state, their scan from S0, output pass - and, for the backward (App. A.4),
+ * the forward states and their scan again, the dQ pass, which also leaves every segment's state gradient, the
+ * reverse scan from dS_T, and the dV and dK passes; dg is re-anchored every 512 tokens as in
+ * zeco_gla_bwd_from_state.  Arguments as in zeco_gla_fused_fwd / zeco_gla_fused_bwd (no saved states, no
+ * schedule); workspace sizes from the *_workspace queries, sized for the bound desc->L.  bf16 q/k/v only. */
+size_t zeco_gla_fused_fwd_varlen_workspace(const zeco_gla_desc *desc);
+zeco_status zeco_gla_fused_fwd_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                      const void *q, const void *k, const void *v, const void *g,
+                                      const float *S0, void *o, float *S_last, void *workspace,
+                                      size_t workspace_bytes, void *stream);
+size_t zeco_gla_fused_bwd_varlen_workspace(const zeco_gla_desc *desc);
+zeco_status zeco_gla_fused_bwd_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
+                                      const void *q, const void *k, const void *v, const void *g,
+                                      const void *dO, const float *S0, const float *dS_T, void *dq, void *dk,
+                                      void *dv, float *dg, float *dS0, void *workspace,
+                                      size_t workspace_bytes, void *stream);
 
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
  * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
@@ -327,6 +349,14 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *desc, const void *q, const v
  * counters of the profiler and to quote the achievable copy bandwidth beside the nominal peak.
  * Both pointers are device pointers, 16-byte aligned, non-overlapping. */
 zeco_status zeco_hbm_copy(void *dst, const void *src, size_t bytes, void *stream);
+
+/* The same for a mix of traffic: `reads` source streams and `writes` destination streams of slice_bytes each
+ * (src holds reads * slice_bytes bytes, dst writes * slice_bytes; a read-only run needs 16 bytes of dst), one
+ * 16-byte word of every stream per thread and step.  Gives the rate the memory system reaches for a kernel's
+ * ratio of reads to writes, to quote beside that kernel's own figure.  Mixes built: 1:0, 0:1, 1:1, 2:1, 3:1,
+ * 4:1 (the correction), 3:2, 5:3 (the local pass); others return ZECO_ERR_UNSUPPORTED. */
+zeco_status zeco_hbm_mix(void *dst, const void *src, size_t slice_bytes, int32_t reads, int32_t writes,
+                         void *stream);
 
 const char *zeco_status_string(int32_t status);
 int32_t zeco_version(void);

@@ -649,7 +649,8 @@ template <int DK, int DV, bool REV, int GM, bool EMIT>
 static hipError_t launch_qk2(const BwdQKParams &p, hipStream_t s) {
     typedef QKCfg<DK, DV, EMIT> Cfg;
     auto kern = gla_bwd_qk_kernel<DK, DV, REV, GM, EMIT>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
+    static LdsLimit limit;   // one per instantiation
+    hipError_t e = limit.raise((const void *)kern, Cfg::kBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.B * p.P * p.H), dim3(Cfg::NT), Cfg::kBytes, s, p);
     return hipGetLastError();

@@ -46,15 +46,6 @@
 
 namespace zeco {
 
-#ifdef ZECO_PHASE_TIMING
-// Development aid: cycle-counter stamps of workgroup 0, chunks 64..67, 12 points per chunk and wave.
-unsigned long long *g_phase_dbg = nullptr;
-#define ZPT(pt)                                                                                  \
-    if (p.dbg && blockIdx.x == 0 && lane == 0 && n >= 64 && n < 68)                              \
-    p.dbg[((w * 4 + (n - 64)) * 12) + (pt)] = __builtin_readcyclecounter()
-#else
-#define ZPT(pt)
-#endif
 
 template <int DK, int DV, int NWG_, int NWI_ = 0> struct B16Cfg {
     static constexpr int NWM = DV / 32;            // MFMA waves, 32 state columns each
@@ -487,19 +478,14 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         int n = 0;
         for (; n + 2 < N; ++n) {
             unsigned char *nxt = lds + ((n + 1) & 1) * Cfg::kTileBytes;
-            ZPT(0);
             vt_store(n + 1, nxt, false);
             gate_b_setup();
             gate_b_half(n + 1, 0, nxt, false);
-            ZPT(2);
             __syncthreads();   // Ps of chunk n visible to the MFMA waves
-            ZPT(3);
             gate_b_half(n + 1, 1, nxt, false);
             gate_b_finish(n + 1, gam + ((n + 1) & 1) * DK);
             gate_a(n + 2, false);
-            ZPT(5);
             __syncthreads();   // tiles of chunk n+1 and gate sums of chunk n+2 complete
-            ZPT(6);
         }
         if (N > 1) {   // n = N-2: produce the last chunk
             unsigned char *nxt = lds + ((n + 1) & 1) * Cfg::kTileBytes;
@@ -643,7 +629,6 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         __syncthreads();
         for (int n = 0; n < N; ++n) {
             const unsigned char *cur = lds + (n & 1) * Cfg::kTileBytes;
-            ZPT(0);
             if constexpr (MODE == kOutputSave) {
                 // the state entering every save_every-th chunk, kept for the backward pass
                 if (p.S_save && n % p.save_every == 0) {
@@ -657,13 +642,9 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                 }
             }
             if constexpr (!NOQ) mfma_a(cur, gam + (n & 1) * DK);
-            ZPT(2);
             __syncthreads();
-            ZPT(3);
             mfma_b(n, cur, gam + (n & 1) * DK);
-            ZPT(5);
             __syncthreads();
-            ZPT(6);
         }
 
         if constexpr (!FROM_INIT) {
@@ -680,8 +661,8 @@ template <int DK, int DV, int NS, int GM, int MODE>
 static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE), idle_waves(DK, DV, GM, MODE)> Cfg;
     auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GM, MODE>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kBytes);
+    static LdsLimit limit;   // one per instantiation
+    hipError_t e = limit.raise((const void *)kern, Cfg::kBytes);
     if (e != hipSuccess) return e;
     const int streams = p.B * p.P * p.H;
     const int grid = ((streams + 7) / 8) * 8 * NS;

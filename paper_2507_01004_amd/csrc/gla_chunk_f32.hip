@@ -205,8 +205,8 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
 template <int DK, int DV> static hipError_t launch_f32(const ChunkParams &p, hipStream_t s) {
     typedef F32Cfg<DK, DV> Cfg;
     auto kern = gla_chunk_f32_kernel<DK, DV>;
-    hipError_t e = hipFuncSetAttribute((const void *)kern,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Cfg::kBytes);
+    static LdsLimit limit;   // one per instantiation
+    hipError_t e = limit.raise((const void *)kern, (int)Cfg::kBytes);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(p.B * p.P * p.H), dim3(Cfg::kThreads), Cfg::kBytes, s, p);
     return hipGetLastError();

@@ -196,4 +196,46 @@ hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) 
     return hipGetLastError();
 }
 
+// Calibration of the achievable HBM rate for a given mix of traffic: every thread reads one 16-byte word from
+// each of R source arrays and writes one to each of W destination arrays per step (the arrays are consecutive
+// slices of n16 words of src and dst), with the access width and coalescing of the plain copy above.
+template <int R, int W>
+__global__ __launch_bounds__(256) void hbm_mix_kernel(u32x4 *dst, const u32x4 *src, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    u32x4 keep = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        u32x4 x = {(uint32_t)i, 1u, 2u, 3u};
+#pragma unroll
+        for (int r = 0; r < R; ++r) x ^= __builtin_nontemporal_load(src + r * n16 + i);
+#pragma unroll
+        for (int w = 0; w < W; ++w) __builtin_nontemporal_store(x, dst + w * n16 + i);
+        if (W == 0) keep ^= x;
+    }
+    // (a read-only run must still use what it read: one word per thread, written only if it is the rare value)
+    if (W == 0 && (keep[0] ^ keep[1] ^ keep[2] ^ keep[3]) == 0x9e3779b9u) dst[0] = keep;
+}
+
+template <int R, int W> static hipError_t launch_mix_rw(void *dst, const void *src, size_t n16, hipStream_t s) {
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL((hbm_mix_kernel<R, W>), dim3((unsigned)blocks), dim3(256), 0, s, (u32x4 *)dst, (const u32x4 *)src, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_mix(void *dst, const void *src, size_t slice_bytes, int reads, int writes, hipStream_t s) {
+    const size_t n16 = slice_bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    switch (reads * 4 + writes) {
+        case 1 * 4 + 0: return launch_mix_rw<1, 0>(dst, src, n16, s);
+        case 0 * 4 + 1: return launch_mix_rw<0, 1>(dst, src, n16, s);
+        case 1 * 4 + 1: return launch_mix_rw<1, 1>(dst, src, n16, s);
+        case 2 * 4 + 1: return launch_mix_rw<2, 1>(dst, src, n16, s);
+        case 3 * 4 + 1: return launch_mix_rw<3, 1>(dst, src, n16, s);
+        case 4 * 4 + 1: return launch_mix_rw<4, 1>(dst, src, n16, s);
+        case 5 * 4 + 3: return launch_mix_rw<5, 3>(dst, src, n16, s);
+        case 3 * 4 + 2: return launch_mix_rw<3, 2>(dst, src, n16, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace zeco

@@ -103,12 +103,12 @@ hipError_t launch_scan_tree(zeco::ScanParams sp, float *scratch, hipStream_t s) 
     return zeco::launch_scan(p, s);
 }
 
-// Inside the fused calls: is the chain of P pieces better scanned as a tree?  One chain step costs about
-// 0.17 us whatever the width, so the serial scan is latency-bound while B*H is small (measured, d = 128:
-// 256 x 1 1.8x, 256 x 2 1.4x, 1024 x 4 1.3x in favour of the tree; 256 x 4 even; from 8 heads on the
-// serial scan streams at the memory rate and wins).
+// Inside the fused calls: is the chain of P pieces better scanned as a tree?  Only for a single head: its
+// serial chain (16384 threads at one float each) is bound by the latency of a step, 1024 segments take
+// 0.057 ms against 0.044 ms as a tree, 4096 take 0.227 against 0.198 ms; at 256 segments the two are even,
+// and from two heads on the serial scan is the faster one at every length (1024 x 2: 0.060 against 0.077 ms).
 bool chain_wants_tree(int P, int BH) {
-    if (!((BH <= 2 && P >= 128) || (BH <= 4 && P >= 1024))) return false;
+    if (!(BH == 1 && P >= 512)) return false;
     const int g = tree_group(P);
     return g != P && P / g <= 65535;          // (the groups are the y dimension of the launch)
 }
@@ -223,9 +223,6 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     p.scale = d->scale; p.kscale = 1.f;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
-#ifdef ZECO_PHASE_TIMING
-    p.dbg = zeco::g_phase_dbg;
-#endif
     if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
     if (halves_with_correction(d)) {
         const SubLayout w = sub_layout(d, 2);
@@ -285,9 +282,6 @@ static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
     p.scale = d->scale; p.kscale = 1.f;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
-#ifdef ZECO_PHASE_TIMING
-    p.dbg = zeco::g_phase_dbg;
-#endif
 }
 
 // Tokens per workgroup of the correction: the largest of cap..64 (powers of two) that divides L, or, when the
@@ -903,6 +897,102 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *d, const int64_t
     return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, S_ck, s, seg_start, T);
 }
 
+// The whole forward and the whole backward over the same table, each in one call: the phases of Alg. 1 (states,
+// scan, output pass) and of the backward (forward states and their scan, dQ pass with the segments' state
+// gradients, reverse scan, dV and dK passes) on the segments as given.
+struct VarlenLayout {   // workspace carve-up, in floats
+    size_t state, off_Sinit, off_Gtot, off_dSloc, off_dSin, off_ck, total;
+};
+static VarlenLayout varlen_layout(const zeco_gla_desc *d, bool backward) {
+    VarlenLayout w;
+    const size_t n = (size_t)d->P * d->B * d->H, bh = (size_t)d->B * d->H;
+    w.state = (size_t)d->d_k * d->d_v;
+    w.off_Sinit = n * w.state;                          // S_loc [n] first
+    w.off_Gtot = w.off_Sinit + (n + bh) * w.state;      // S_init [n] and one more slot: the final state
+    w.off_dSloc = w.off_Gtot + ((n * (d->g_per_head ? 1 : d->d_k) + 3) & ~(size_t)3);
+    if (!backward) { w.off_dSin = w.off_ck = w.total = w.off_dSloc; return w; }
+    w.off_dSin = w.off_dSloc + n * w.state;
+    w.off_ck = w.off_dSin + n * w.state;
+    w.total = w.off_ck + bwd_checkpoint_floats(d, d->P, d->L);
+    return w;
+}
+
+size_t zeco_gla_fused_fwd_varlen_workspace(const zeco_gla_desc *desc) {
+    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    return varlen_layout(desc, false).total * sizeof(float);
+}
+size_t zeco_gla_fused_bwd_varlen_workspace(const zeco_gla_desc *desc) {
+    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    return varlen_layout(desc, true).total * sizeof(float);
+}
+
+zeco_status zeco_gla_fused_fwd_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T, const void *q,
+                                      const void *k, const void *v, const void *g, const float *S0, void *o,
+                                      float *S_last, void *workspace, size_t workspace_bytes, void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) || !aligned16(S0) ||
+        !aligned16(S_last) || !aligned16(workspace))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    if (workspace_bytes < zeco_gla_fused_fwd_varlen_workspace(d)) return ZECO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const VarlenLayout w = varlen_layout(d, false);
+    float *Sloc = static_cast<float *>(workspace), *Sinit = Sloc + w.off_Sinit, *Gtot = Sloc + w.off_Gtot;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
+    p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
+    if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s) != hipSuccess) return ZECO_ERR_HIP;
+    zeco::ScanParams sp;
+    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
+    sp.P = d->P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+    sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
+    if (zeco::launch_scan(sp, s) != hipSuccess) return ZECO_ERR_HIP;
+    p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, s));
+}
+
+zeco_status zeco_gla_fused_bwd_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T, const void *q,
+                                      const void *k, const void *v, const void *g, const void *dO,
+                                      const float *S0, const float *dS_T, void *dq, void *dk, void *dv, float *dg,
+                                      float *dS0, void *workspace, size_t workspace_bytes, void *stream) {
+    const zeco_status st = check_varlen(d, seg_start, T);
+    if (st != ZECO_OK) return st;
+    if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
+    if (!q || !k || !v || !g || !dO || !dq || !dk || !dv || !dg || !workspace) return ZECO_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) || !aligned16(S0) ||
+        !aligned16(dS_T) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(dg) || !aligned16(dS0) ||
+        !aligned16(workspace))
+        return ZECO_ERR_INVALID_ARG;
+    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    if (workspace_bytes < zeco_gla_fused_bwd_varlen_workspace(d)) return ZECO_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const VarlenLayout w = varlen_layout(d, true);
+    const size_t n = (size_t)d->P * d->B * d->H;
+    float *ws = static_cast<float *>(workspace);
+    float *Sloc = ws, *Sinit = ws + w.off_Sinit, *Slast = Sinit + n * w.state, *Gtot = ws + w.off_Gtot;
+    float *dSloc = ws + w.off_dSloc, *dSin = ws + w.off_dSin;
+    float *S_ck = bwd_checkpoints(d->L) > 0 ? ws + w.off_ck : nullptr;
+    zeco::ChunkParams p;
+    fill_chunk_params(p, d);
+    p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
+    p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
+    if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s) != hipSuccess) return ZECO_ERR_HIP;
+    zeco::ScanParams sp;
+    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
+    sp.P = d->P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+    sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
+    if (zeco::launch_scan(sp, s) != hipSuccess) return ZECO_ERR_HIP;
+    zeco_status zs = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, Sinit, Slast, dq, dg, dSloc, nullptr, S_ck, s, seg_start, T);
+    if (zs != ZECO_OK) return zs;
+    sp.S_loc = dSloc; sp.S0 = dS_T; sp.S_init = dSin; sp.S_last = dS0; sp.reverse = 1;
+    if (zeco::launch_scan(sp, s) != hipSuccess) return ZECO_ERR_HIP;
+    return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, Sinit, Slast, dSin, dk, dv, dg, S_ck, s, seg_start, T);
+}
+
 // ---- chunk-decay form of the local pass and the correction ---------------------------------------------
 zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q, const void *k,
                                            const void *v, const void *g, void *o, float *S_loc,
@@ -946,6 +1036,15 @@ zeco_status zeco_hbm_copy(void *dst, const void *src, size_t bytes, void *stream
     return from_hip(zeco::launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
 }
 
+zeco_status zeco_hbm_mix(void *dst, const void *src, size_t slice_bytes, int32_t reads, int32_t writes, void *stream) {
+    if (!dst || !src || !aligned16(dst) || !aligned16(src) || slice_bytes % 16 != 0) return ZECO_ERR_INVALID_ARG;
+    const int ok[][2] = {{1, 0}, {0, 1}, {1, 1}, {2, 1}, {3, 1}, {4, 1}, {5, 3}, {3, 2}};
+    bool found = false;
+    for (auto &m : ok) found = found || (m[0] == reads && m[1] == writes);
+    if (!found) return ZECO_ERR_UNSUPPORTED;
+    return from_hip(zeco::launch_mix(dst, src, slice_bytes, reads, writes, static_cast<hipStream_t>(stream)));
+}
+
 const char *zeco_status_string(int32_t status) {
     switch (status) {
         case ZECO_OK: return "ok";
@@ -959,9 +1058,5 @@ const char *zeco_status_string(int32_t status) {
 }
 
 int32_t zeco_version(void) { return 100; }
-
-#ifdef ZECO_PHASE_TIMING
-void zeco_debug_set_phase_buffer(unsigned long long *buf) { zeco::g_phase_dbg = buf; }
-#endif
 
 }  // extern "C"

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace zeco {
 
 // Gate layouts: kGateF32 / kGateBF16 = one log decay per (token, head, channel); kGateHead = one fp32
@@ -30,13 +32,7 @@ struct ChunkParams {
     float kscale;              // backward modes: multiplier carried by the operand in the k role
     long long sb, st, sh;      // q/k/g element strides
     long long vb, vt, vh;      // v/o element strides
-#ifdef ZECO_PHASE_TIMING
-    unsigned long long *dbg;   // development builds only: cycle stamps of workgroup 0
-#endif
 };
-#ifdef ZECO_PHASE_TIMING
-extern unsigned long long *g_phase_dbg;
-#endif
 
 struct ApplyParams {
     const void *q;
@@ -99,6 +95,23 @@ struct BwdQKParams {
     long long sb, st, sh, vb, vt, vh;
 };
 
+// A kernel that uses more dynamic LDS than the default limit has the limit raised once per device (the
+// attribute belongs to the function on that device), not at every launch.  One static object per kernel
+// instantiation; devices beyond the 64 the mask covers are simply set every time.
+struct LdsLimit {
+    std::atomic<unsigned long long> done{0};
+    hipError_t raise(const void *kernel, int bytes) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const unsigned long long bit = (dev >= 0 && dev < 64) ? 1ull << dev : 0ull;
+        if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+        if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+        return e;
+    }
+};
+
 // Each returns hipSuccess or the launch error.  d_k, d_v in {64,128}.
 hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t s);
 // mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
@@ -118,5 +131,7 @@ hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, int gate_mode, 
 // per-head log decays: G_cum [B,T,H] += G_pre [T/len, B, H] of the piece each token lies in
 hipError_t launch_gate_offset_head(float *G_cum, const float *G_pre, int B, long long T, int H, int len, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);
+// reads x writes 16-byte streams over slices of slice_bytes each (calibration of the HBM rate of a traffic mix)
+hipError_t launch_mix(void *dst, const void *src, size_t slice_bytes, int reads, int writes, hipStream_t s);
 
 }  // namespace zeco

@@ -23,11 +23,13 @@ EXPORTS = ("zeco_gla_local_fwd_workspace", "zeco_gla_local_fwd", "zeco_state_sca
            "zeco_apply_init_state", "zeco_gla_local_fwd_varlen", "zeco_apply_init_state_varlen",
            "zeco_gla_local_state_varlen", "zeco_gla_fwd_from_state_varlen",
            "zeco_gla_bwd_dstate_varlen", "zeco_gla_bwd_from_state_varlen",
+           "zeco_gla_fused_fwd_varlen_workspace", "zeco_gla_fused_fwd_varlen",
+           "zeco_gla_fused_bwd_varlen_workspace", "zeco_gla_fused_bwd_varlen",
            "zeco_gla_local_fwd_chunk_decay", "zeco_apply_init_state_chunk_decay",
            "zeco_gla_local_state", "zeco_gla_fwd_from_state",
            "zeco_gla_fused_fwd_workspace", "zeco_gla_saved_states_bytes", "zeco_gla_fused_fwd", "zeco_gla_bwd_dstate",
            "zeco_gla_bwd_from_state_workspace", "zeco_gla_bwd_from_state", "zeco_gla_fused_bwd_workspace", "zeco_gla_fused_bwd",
-           "zeco_hbm_copy", "zeco_status_string", "zeco_version")
+           "zeco_hbm_copy", "zeco_hbm_mix", "zeco_status_string", "zeco_version")
 
 
 class GlaDesc(ctypes.Structure):
@@ -88,6 +90,13 @@ def lib():
         L.zeco_gla_bwd_dstate_varlen.restype = i32
         L.zeco_gla_bwd_from_state_varlen.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 5 + [fp] * 3 + [vp] * 3 + [fp, vp, ctypes.c_size_t, vp]
         L.zeco_gla_bwd_from_state_varlen.restype = i32
+        for nm in ("zeco_gla_fused_fwd_varlen_workspace", "zeco_gla_fused_bwd_varlen_workspace"):
+            getattr(L, nm).argtypes = [dp]
+            getattr(L, nm).restype = ctypes.c_size_t
+        L.zeco_gla_fused_fwd_varlen.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 4 + [fp, vp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_fused_fwd_varlen.restype = i32
+        L.zeco_gla_fused_bwd_varlen.argtypes = [dp, vp, ctypes.c_int64] + [vp] * 5 + [fp, fp] + [vp] * 3 + [fp, fp, vp, ctypes.c_size_t, vp]
+        L.zeco_gla_fused_bwd_varlen.restype = i32
         L.zeco_gla_local_fwd_chunk_decay.argtypes = [dp, vp, vp, vp, vp, vp, fp, fp, fp, vp]
         L.zeco_gla_local_fwd_chunk_decay.restype = i32
         L.zeco_apply_init_state_chunk_decay.argtypes = [dp, vp, vp, fp, fp, vp, i32, vp]
@@ -114,6 +123,8 @@ def lib():
         L.zeco_gla_fused_bwd.restype = i32
         L.zeco_hbm_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.zeco_hbm_copy.restype = i32
+        L.zeco_hbm_mix.argtypes = [vp, vp, ctypes.c_size_t, i32, i32, vp]
+        L.zeco_hbm_mix.restype = i32
         L.zeco_status_string.argtypes = [i32]
         L.zeco_status_string.restype = ctypes.c_char_p
         L.zeco_version.argtypes = []
@@ -449,6 +460,50 @@ def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, 
     return dq, dk, dv, dg
 
 
+def gla_fused_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, S0=None, out=None, workspace=None):
+    """zeco_gla_fused_fwd_varlen: the whole forward over a table of unequal segments.  Returns (o, S_last)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    B, T, H, dk = q.shape
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    if out is None:
+        out = (torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device),
+               torch.empty(B, H, dk, v.shape[-1], dtype=torch.float32, device=q.device))
+    o, S_last = out
+    need = int(lib().zeco_gla_fused_fwd_varlen_workspace(ctypes.byref(desc)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    st = lib().zeco_gla_fused_fwd_varlen(ctypes.byref(desc), _ptr(seg_start), T, _ptr(q), _ptr(k), _ptr(v), _ptr(g),
+                                         _ptr(S0), _ptr(o), _ptr(S_last), _ptr(workspace), workspace.numel(), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_fused_fwd_varlen")
+    return o, S_last
+
+
+def gla_fused_bwd_varlen(q, k, v, g, dO, seg_start, max_len, scale=1.0, S0=None, dS_T=None, out=None, workspace=None):
+    """zeco_gla_fused_bwd_varlen: the whole backward over a table of unequal segments.
+    Returns (dq, dk, dv, dg, dS0)."""
+    if not q.is_cuda:
+        raise RuntimeError("zeco kernels run on the GPU only")
+    _check_same_layout(q, k)
+    _check_same_layout(v, dO)
+    B, T, H, dk = q.shape
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    if out is None:
+        out = _grad_outputs(q, v, g) + (torch.empty(B, H, dk, v.shape[-1], dtype=torch.float32, device=q.device),)
+    dq, dk_, dv, dg, dS0 = out
+    need = int(lib().zeco_gla_fused_bwd_varlen_workspace(ctypes.byref(desc)))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    st = lib().zeco_gla_fused_bwd_varlen(ctypes.byref(desc), _ptr(seg_start), T, _ptr(q), _ptr(k), _ptr(v), _ptr(g),
+                                         _ptr(dO), _ptr(S0), _ptr(dS_T), _ptr(dq), _ptr(dk_), _ptr(dv), _ptr(dg),
+                                         _ptr(dS0), _ptr(workspace), workspace.numel(), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_gla_fused_bwd_varlen")
+    return dq, dk_, dv, dg, dS0
+
+
 def _apply_flags(first_segment_is_zero, dense):
     return (APPLY_FIRST_SEGMENT_ZERO if first_segment_is_zero else 0) | (APPLY_DENSE if dense else 0)
 
@@ -645,6 +700,15 @@ def hbm_copy(dst, src):
     if st != ZECO_OK:
         raise ZecoError(st, "zeco_hbm_copy")
     return dst
+
+
+def hbm_mix(dst, src, slice_bytes, reads, writes):
+    """zeco_hbm_mix: `reads` x `writes` streams of slice_bytes each (bandwidth calibration for a traffic mix)."""
+    if src.numel() * src.element_size() < reads * slice_bytes or dst.numel() * dst.element_size() < max(16, writes * slice_bytes):
+        raise ValueError("buffers too small for the mix")
+    st = lib().zeco_hbm_mix(_ptr(dst), _ptr(src), int(slice_bytes), int(reads), int(writes), _stream())
+    if st != ZECO_OK:
+        raise ZecoError(st, "zeco_hbm_mix")
 
 
 def segmented_fwd(q, k, v, g, P, scale=1.0, S0=None, K_blocks=16):

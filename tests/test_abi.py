@@ -149,9 +149,17 @@ def test_unequal_segment_lengths_validate_before_any_launch(L):
         ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, None)
     bwd = lambda d=None, seg=FAKE, T=4096, q=FAKE: L.zeco_gla_bwd_from_state_varlen(
         ref(d or good_desc(L=1000)), seg, T, q, *([FAKE] * 11), FAKE, 1 << 30, None)
-    for call in (sta, out, dst, bwd):
+    ffw = lambda d=None, seg=FAKE, T=4096, q=FAKE, ws=1 << 30: L.zeco_gla_fused_fwd_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, FAKE, FAKE, FAKE, None, FAKE, None, FAKE, ws, None)
+    fbw = lambda d=None, seg=FAKE, T=4096, q=FAKE, ws=1 << 30: L.zeco_gla_fused_bwd_varlen(
+        ref(d or good_desc(L=1000)), seg, T, q, *([FAKE] * 4), None, None, *([FAKE] * 4), None, FAKE, ws, None)
+    need_f = L.zeco_gla_fused_fwd_varlen_workspace(ref(good_desc(L=1000)))
+    need_b = L.zeco_gla_fused_bwd_varlen_workspace(ref(good_desc(L=1000)))
+    assert 0 < need_f < need_b and L.zeco_gla_fused_bwd_varlen_workspace(ref(good_desc(io_dtype=zeco.ZECO_F32))) == 0
+    assert ffw(ws=need_f - 1) == zeco.ZECO_ERR_WORKSPACE and fbw(ws=need_b - 1) == zeco.ZECO_ERR_WORKSPACE
+    for call in (sta, out, dst, bwd, ffw, fbw):
         assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
-    for call in (loc, app, sta, out, dst, bwd):
+    for call in (loc, app, sta, out, dst, bwd, ffw, fbw):
         assert call(seg=None) == zeco.ZECO_ERR_INVALID_ARG
         assert call(seg=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG        # not 8-byte aligned
         assert call(T=127) == zeco.ZECO_ERR_INVALID_ARG                             # under P * C tokens
@@ -268,3 +276,10 @@ def test_static_scratch_scan_checks_its_limit_before_any_hip_call(L):
     assert call(36, 2, S_loc=None) == zeco.ZECO_ERR_INVALID_ARG
     assert call(0, 2) == zeco.ZECO_ERR_INVALID_ARG
     assert call(37, 0) == zeco.ZECO_OK                                          # empty batch
+
+
+def test_hbm_mix_takes_only_the_mixes_it_was_built_for(L):
+    assert L.zeco_hbm_mix(FAKE, FAKE, 1 << 20, 7, 1, None) == zeco.ZECO_ERR_UNSUPPORTED
+    assert L.zeco_hbm_mix(FAKE, FAKE, 1 << 20, 0, 0, None) == zeco.ZECO_ERR_UNSUPPORTED
+    assert L.zeco_hbm_mix(None, FAKE, 1 << 20, 4, 1, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_hbm_mix(FAKE, FAKE, 24, 4, 1, None) == zeco.ZECO_ERR_INVALID_ARG

@@ -113,6 +113,27 @@ def test_state_scan_matches_oracle_and_is_block_independent(shape):
                 assert torch.equal(S_init, base[0]) and torch.equal(S_last, base[1])
 
 
+@pytest.mark.parametrize("shape", [(64, 16, 128, 128), (256, 8, 128, 128), (33, 4, 128, 128), (100, 2, 64, 64)])
+def test_state_scan_at_full_size_with_decays_of_order_one(shape):
+    """The benchmark configurations' scan shapes (64 segments x 16 heads, 256 x 8) and two narrow ones, which
+    take the other thread widths of the kernel, with log decays in (-3, 0): at the workloads' own gates
+    exp(G_tot) is an exact zero, so only a case like this one checks the chained decay term at scale.  Both
+    directions, against the oracle's serial chain."""
+    P, BH, dk, dv = shape
+    print("scan, full size", shape, flush=True)
+    S_loc, G_tot, S0 = random_states(P, BH, dk, dv, seed=300 + P)
+    ref_init, ref_last = oracle.state_scan(S_loc, G_tot, S0)
+    S_init, S_last = zeco.state_scan(dev(S_loc), dev(G_tot), dev(S0))
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(S_init), ref_init, (1,)) <= 1e-5
+    assert rel_err_bh(host(S_last), ref_last, (0,)) <= 1e-5
+    rev_init, rev_last = oracle.state_scan(np.flip(S_loc, 0), np.flip(G_tot, 0), None)
+    S_init, S_last = zeco.state_scan(dev(S_loc), dev(G_tot), None, direction=1)
+    torch.cuda.synchronize()
+    assert rel_err_bh(host(S_init), np.flip(rev_init, 0), (1,)) <= 1e-5
+    assert rel_err_bh(host(S_last), rev_last, (0,)) <= 1e-5
+
+
 @pytest.mark.parametrize("shape", [(36, 2, 128, 128), (256, 1, 128, 64), (12, 3, 64, 128), (37, 2, 64, 64), (4, 1, 64, 64),
                                    (1, 2, 128, 128)])
 def test_state_scan_tree_matches_oracle(shape):

@@ -103,6 +103,10 @@ def test_varlen_local_pass_and_three_calls(case):
         assert rel_err_bh(host(S_loc2), host(S_loc), (1, 2)) <= tol
         assert rel_err_bh(host(o2), o_f, (0, 2)) <= tol
         assert rel_err_bh(host(S_last2), S_f, (0, 1)) <= tol
+        # the same three phases as one call: the same kernels on the same data
+        o3, S_last3 = zeco.gla_fused_fwd_varlen(inp["q"], inp["k"], inp["v"], inp["g"], seg, Lmax, scale=0.5, S0=S0)
+        torch.cuda.synchronize()
+        assert torch.equal(o3, o2) and torch.equal(S_last3, S_last2)
 
 
 @pytest.mark.parametrize("case", [c for c in CASES if not c[0].startswith("f32")], ids=lambda c: c[0])
@@ -132,6 +136,13 @@ def test_varlen_backward_building_blocks(case):
     # (dg: the running sum over a segment is re-anchored every 512 tokens, so long segments hold the bound too)
     assert rel_err_bh(host(got[3]), ref[3].sum(axis=-1) if ph else ref[3], (0, 2)) <= tol, "dg"
     assert rel_err_bh(host(dS0), ref[4], (0, 1)) <= tol, "dS0"
+    # the whole backward as one call (its dQ pass also emits the state gradients, so dS_loc is rounded differently)
+    one = zeco.gla_fused_bwd_varlen(q, k, v, g, dO, seg, Lmax, scale=0.5, S0=S0, dS_T=dS_T)
+    torch.cuda.synchronize()
+    for nm, x, r in zip(("dq", "dk", "dv"), one[:3], ref[:3]):
+        assert rel_err_bh(host(x), r, (0, 2)) <= tol, nm + ", one call"
+    assert rel_err_bh(host(one[3]), ref[3].sum(axis=-1) if ph else ref[3], (0, 2)) <= tol, "dg, one call"
+    assert rel_err_bh(host(one[4]), ref[4], (0, 1)) <= tol, "dS0, one call"
 
 
 def test_varlen_tokens_outside_the_segments_stay_untouched_and_bound_may_be_loose():

@@ -358,6 +358,10 @@ def run_workload(args, workload, with_cpu):
             zeco.hbm_mix(dst, src, sl, r, w)
             t = timed(lambda: zeco.hbm_mix(dst, src, sl, r, w), warm=1, reps=5)
             mix_gbs["%d:%d" % (r, w)] = round((r + w) * sl / t / 1e6, 1)
+        # the correction rewrites one of its four input streams in place
+        last = src[3 * sl:4 * sl]
+        t = timed(lambda: zeco.hbm_mix(last, src, sl, 4, 1), warm=1, reps=5)
+        mix_gbs["4:1 in place"] = round(5 * sl / t / 1e6, 1)
         del src, dst
 
     # The correction stops, per (segment, head), where the decay factor exp(G_cum) has become an exact

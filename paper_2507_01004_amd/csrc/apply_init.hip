@@ -25,6 +25,28 @@ namespace zeco {
 
 constexpr float kVanish = -105.f;   // exp2(-105 log2(e)) = 2^-151.5 rounds to 0 in fp32
 
+// q, G_cum and o are read with ordinary loads and o is written back with non-temporal stores.  Measured
+// (dense call, c3 / c4): that combination 5.3 TB/s, ordinary loads and stores 5.1-5.2, non-temporal loads with
+// ordinary stores 4.3-4.4, both non-temporal 4.7.  A plain streaming kernel with this kernel's traffic (three
+// token-major streams read, one of them rewritten in place) reaches 5.0-5.5 TB/s whatever the length of the
+// contiguous pieces a workgroup takes (256 bytes of a token's row up to the whole 4 KiB row): the in-place
+// rewrite, not the row length, sets the rate.
+// q, G_cum (or g) and o are streamed once.  Non-temporal loads together with non-temporal stores of o give the
+// dense call 5.7 TB/s against 5.3 with ordinary loads (c3, c4) - provided nothing is loaded twice: with the
+// prefetch of the block after a workgroup's last one clamped to that last block, the second fetch of its rows hit
+// the cache with ordinary loads and went to HBM again with non-temporal ones (4.3-4.7 TB/s), so the prefetch
+// is skipped there instead.  The hint costs latency, though: where the call stops at the vanished decay and
+// few workgroups find work (c3: about 340 of them, fewer than the chip has slots) it is 20 % slower, so the
+// launcher asks for it only in dense calls and in launches with more streams than workgroup slots.
+// (Other combinations, dense call: ordinary loads and stores 5.1-5.2 TB/s, non-temporal loads with ordinary
+// stores 4.3-5.2.  The order of the workgroups - token blocks of a stream together, heads of a token block
+// together, a linear sweep through memory - moves the figure by 2 % at most.)
+template <bool NT, typename T> __device__ __forceinline__ T apply_ld(const T *p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <typename T> __device__ __forceinline__ void apply_st(T v, T *p) { __builtin_nontemporal_store(v, p); }
+
 // ------------------------------------------------------------------------------------------ bf16
 template <int DK, int DV> struct ApplyCfg {
     static constexpr int TILE = DV / 4;
@@ -96,12 +118,12 @@ __device__ __forceinline__ void apply_load_state(const float *S, bf16x8 (&sf)[Ap
 }
 
 // o is read-modified-written in 16-byte pieces (8 columns of one token per item).
-template <int DV>
+template <int DV, bool NT>
 __device__ __forceinline__ void apply_load_o(const uint16_t *o_blk, long long vt, u32x4 (&ro)[64 * DV / 8 / 256]) {
 #pragma unroll
     for (int m = 0; m < 64 * DV / 8 / 256; ++m) {
         const int item = threadIdx.x + 256 * m, t = item / (DV / 8), cg = item % (DV / 8);
-        ro[m] = *reinterpret_cast<const u32x4 *>(o_blk + t * vt + 8 * cg);
+        ro[m] = apply_ld<NT>(reinterpret_cast<const u32x4 *>(o_blk + t * vt + 8 * cg));
     }
 }
 
@@ -138,7 +160,7 @@ __device__ __forceinline__ void apply_block(const bf16x8 (&sf)[ApplyCfg<DK, DV>:
         const f32x4 c0 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg);
         const f32x4 c1 = *reinterpret_cast<const f32x4 *>(Cs + t * Cfg::CS + 8 * cg + 4);
         const u32x4 old = ocur[m];
-        if (t < rows) __builtin_nontemporal_store(
+        if (t < rows) apply_st(
             u32x4{pack_bf16(bf16_lo(old[0]) + c0[0], bf16_hi(old[0]) + c0[1]),
                   pack_bf16(bf16_lo(old[1]) + c0[2], bf16_hi(old[1]) + c0[3]),
                   pack_bf16(bf16_lo(old[2]) + c1[0], bf16_hi(old[2]) + c1[1]),
@@ -148,7 +170,8 @@ __device__ __forceinline__ void apply_block(const bf16x8 (&sf)[ApplyCfg<DK, DV>:
 }
 
 // GH: the cumulative log decay is one value per (token, head), G_cum [B,T,H].
-template <int DK, int DV, bool GH>
+// NT: non-temporal loads of the streamed rows (see above).
+template <int DK, int DV, bool GH, bool NT>
 __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     typedef ApplyCfg<DK, DV> Cfg;
     constexpr int QS = Cfg::QS;
@@ -201,13 +224,13 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
         for (int m = 0; m < Cfg::ITEMS; ++m) {
             const int item = tid + 256 * m, t = item / (DK / 8), cg = item % (DK / 8);
             const long long tt = apply_block_start(pad, c0 + blk) + t;
-            r.q[m] = *reinterpret_cast<const u32x4 *>(qp + tt * p.st + 8 * cg);
+            r.q[m] = apply_ld<NT>(reinterpret_cast<const u32x4 *>(qp + tt * p.st + 8 * cg));
             if constexpr (GH) {
                 const float x = Gc[tt * gcs];
                 r.g0[m] = r.g1[m] = f32x4{x, x, x, x};
             } else {
-                r.g0[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg);
-                r.g1[m] = *reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg + 4);
+                r.g0[m] = apply_ld<NT>(reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg));
+                r.g1[m] = apply_ld<NT>(reinterpret_cast<const f32x4 *>(Gc + tt * gcs + 8 * cg + 4));
             }
         }
     };
@@ -215,7 +238,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
     Raw nxt;
     u32x4 onx[Cfg::OITEMS];
     load_raw(0, nxt);
-    apply_load_o<DV>(op + apply_block_start(pad, c0) * p.vt, p.vt, onx);
+    apply_load_o<DV, NT>(op + apply_block_start(pad, c0) * p.vt, p.vt, onx);
     for (int blk = 0; blk < nblk; ++blk) {
         const Raw cur = nxt;
         u32x4 ocur[Cfg::OITEMS];
@@ -242,9 +265,10 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
             }
             *reinterpret_cast<u32x4 *>(Qh + t * QS + 16 * cg) = out;
         }
-        const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
-        load_raw(nb, nxt);
-        apply_load_o<DV>(op + apply_block_start(pad, c0 + nb) * p.vt, p.vt, onx);
+        if (blk + 1 < nblk) {   // (uniform) the next block's rows; nothing is fetched twice
+            load_raw(blk + 1, nxt);
+            apply_load_o<DV, NT>(op + apply_block_start(pad, c0 + blk + 1) * p.vt, p.vt, onx);
+        }
         __syncthreads();   // Qh complete; every thread is done with the staging tile of the last block
         apply_block<DK, DV>(sf, Qh, Cs, op + apply_block_start(pad, c0 + blk) * p.vt, p.vt, ocur, apply_block_rows(pad, c0 + blk));
     }
@@ -255,7 +279,7 @@ __global__ __launch_bounds__(256) void apply_init_bf16_kernel(ApplyParams p) {
 // the in-chunk factor Lambda_t of Sec. 2.1 times gamma~_[n-1].  A thread owns 4 channels and TPT
 // consecutive tokens of the 64-token block: cumulative sum in registers, the token groups stitched
 // through LDS.  Stops where G_chunk[n] < kVanish in every channel (see "Vanished decay").
-template <int DK, int DV, int GM>
+template <int DK, int DV, int GM, bool NT>
 __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) {
     typedef ApplyCfg<DK, DV> Cfg;
     typedef GateVal<GM> GV;
@@ -301,12 +325,12 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
 #pragma unroll
         for (int u = 0; u < TPT; ++u) {
             const long long tt = apply_block_start(p.pad, c0 + blk) + u;
-            qn[u] = *reinterpret_cast<const u32x2 *>(qp + tt * p.st);
-            gn[u] = *reinterpret_cast<const typename GV::raw_t *>(gp + tt * p.st * GB);
+            qn[u] = apply_ld<NT>(reinterpret_cast<const u32x2 *>(qp + tt * p.st));
+            gn[u] = apply_ld<NT>(reinterpret_cast<const typename GV::raw_t *>(gp + tt * p.st * GB));
         }
     };
     load_raw(0);
-    apply_load_o<DV>(op + apply_block_start(p.pad, c0) * p.vt, p.vt, onx);
+    apply_load_o<DV, NT>(op + apply_block_start(p.pad, c0) * p.vt, p.vt, onx);
     for (int blk = 0; blk < nblk; ++blk) {
         const f32x4 pre = pre_n;
         u32x2 qc[TPT];
@@ -323,10 +347,11 @@ __global__ __launch_bounds__(256) void apply_init_cd_bf16_kernel(ApplyParams p) 
             cs[u] = run;
         }
         *reinterpret_cast<f32x4 *>(tot + tg * DK + 4 * cq) = run;
-        const int nb = (blk + 1 < nblk) ? blk + 1 : blk;   // next block, clamped (branch-free prefetch)
-        load_raw(nb);
-        apply_load_o<DV>(op + apply_block_start(p.pad, c0 + nb) * p.vt, p.vt, onx);
-        pre_n = *reinterpret_cast<const f32x4 *>(Gk + (long long)nb * gks);
+        if (blk + 1 < nblk) {   // (uniform) the next block's rows; nothing is fetched twice
+            load_raw(blk + 1);
+            apply_load_o<DV, NT>(op + apply_block_start(p.pad, c0 + blk + 1) * p.vt, p.vt, onx);
+            pre_n = *reinterpret_cast<const f32x4 *>(Gk + (long long)(blk + 1) * gks);
+        }
         __syncthreads();   // group sums visible; every thread is done with the staging tile of the last block
         f32x4 base = pre;
 #pragma unroll
@@ -430,20 +455,29 @@ template <int DK, int DV> static hipError_t launch_ab16(const ApplyParams &p, hi
     const long long wgs = (long long)apply_segments(p) * p.B * p.H * p.wgs_per_seg;
     if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
     const int grid = (int)wgs;
-    if (p.gate_per_head)
-        hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, true>), dim3(grid), dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, false>), dim3(grid), dim3(256), 0, s, p);
+    // non-temporal loads: dense calls, and launches with more streams than the chip has workgroup slots
+    const bool nt = p.dense || (long long)apply_segments(p) * p.B * p.H >= 768;
+    if (p.gate_per_head) {
+        if (nt) hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, true, true>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, true, false>), dim3(grid), dim3(256), 0, s, p);
+    } else {
+        if (nt) hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, false, true>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((apply_init_bf16_kernel<DK, DV, false, false>), dim3(grid), dim3(256), 0, s, p);
+    }
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_acd(const ApplyParams &p, hipStream_t s) {
     const long long wgs = (long long)apply_segments(p) * p.B * p.H * p.wgs_per_seg;
     if (wgs > 0x7fffffffll) return hipErrorInvalidValue;   // beyond the grid's x dimension
     const int grid = (int)wgs;
-    if (p.g_bf16)
-        hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateBF16>), dim3(grid), dim3(256), 0, s, p);
-    else
-        hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateF32>), dim3(grid), dim3(256), 0, s, p);
+    const bool nt = p.dense || (long long)apply_segments(p) * p.B * p.H >= 768;   // as in launch_ab16
+    if (p.g_bf16) {
+        if (nt) hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateBF16, true>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateBF16, false>), dim3(grid), dim3(256), 0, s, p);
+    } else {
+        if (nt) hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateF32, true>), dim3(grid), dim3(256), 0, s, p);
+        else hipLaunchKernelGGL((apply_init_cd_bf16_kernel<DK, DV, kGateF32, false>), dim3(grid), dim3(256), 0, s, p);
+    }
     return hipGetLastError();
 }
 template <int DK, int DV> static hipError_t launch_af32(const ApplyParams &p, hipStream_t s) {

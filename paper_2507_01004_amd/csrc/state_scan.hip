@@ -17,6 +17,23 @@ namespace zeco {
 
 // V floats of a state row per thread, D segments of loads in flight per thread.
 template <int V> struct alignas(4 * V) ScanVec { float v[V]; };
+template <int V> struct ScanRaw;
+template <> struct ScanRaw<4> { typedef f32x4 t; };
+template <> struct ScanRaw<2> { typedef f32x2 t; };
+template <> struct ScanRaw<1> { typedef float t; };
+// S_loc is read once and never again by this kernel: non-temporal loads.  They change nothing when the
+// inputs stream from HBM with clean caches (5.3 TB/s either way at 64 x 16 and 256 x 8 states of 128 x 128) and
+// help when the caches are full of another kernel's dirty lines (3.5 -> 4.9 TB/s after a 512 MiB fill); with the
+// working set in the Infinity Cache ordinary loads are the faster ones (6.3 against 5.7 TB/s).  S_init is
+// stored with ordinary stores: the correction reads it next.
+template <int V> __device__ __forceinline__ ScanVec<V> scan_load(const float *ptr) {
+    typedef typename ScanRaw<V>::t raw_t;
+    return __builtin_bit_cast(ScanVec<V>, __builtin_nontemporal_load(reinterpret_cast<const raw_t *>(ptr)));
+}
+template <int V> __device__ __forceinline__ void scan_store(float *ptr, const ScanVec<V> &x) {
+    typedef typename ScanRaw<V>::t raw_t;
+    *reinterpret_cast<raw_t *>(ptr) = __builtin_bit_cast(raw_t, x);
+}
 
 // Grid: x = (head, row block, part of the block's slab), y = chain.  A thread owns V consecutive floats of
 // one state row and walks the chain; its loads run D segments ahead of the multiply-adds in a ring of
@@ -72,14 +89,14 @@ __global__ __launch_bounds__(256) void state_scan_kernel(ScanParams p, int parts
     vec_t x[D];
     float a[D];
     auto fetch = [&](int u) {
-        x[u] = *reinterpret_cast<const vec_t *>(lf);
+        x[u] = scan_load<V>(lf);
         a[u] = *gf;
         lf += sstep;
         gf += gstep;
     };
     auto consume = [&](int u) {
         if (STORE) {
-            *reinterpret_cast<vec_t *>(sp) = s;
+            scan_store<V>(sp, s);
             sp += sstep;
         }
         if (BYP) {
@@ -198,26 +215,34 @@ hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s) 
 
 // Calibration of the achievable HBM rate for a given mix of traffic: every thread reads one 16-byte word from
 // each of R source arrays and writes one to each of W destination arrays per step (the arrays are consecutive
-// slices of n16 words of src and dst), with the access width and coalescing of the plain copy above.
+// slices of n16 words of src and dst).  A workgroup takes one contiguous piece of 16 KiB of every stream, the
+// pieces in workgroup order; loads are non-temporal, stores ordinary.  Of the plain patterns measured this is
+// the fastest (one read per write: 6.9-7.0 TB/s, against 5.1-5.7 for a grid-stride loop with either kind of
+// load and store); dst may be one of the source slices (a stream rewritten in place).
+constexpr int kMixPiece = 1024;   // 16-byte words per workgroup and stream
 template <int R, int W>
 __global__ __launch_bounds__(256) void hbm_mix_kernel(u32x4 *dst, const u32x4 *src, size_t n16) {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t i0 = (size_t)blockIdx.x * kMixPiece;
     u32x4 keep = {0u, 0u, 0u, 0u};
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
-        u32x4 x = {(uint32_t)i, 1u, 2u, 3u};
 #pragma unroll
-        for (int r = 0; r < R; ++r) x ^= __builtin_nontemporal_load(src + r * n16 + i);
+    for (int it = 0; it < kMixPiece / 256; ++it) {
+        const size_t i = i0 + it * 256 + threadIdx.x;
+        if (i < n16) {
+            u32x4 x = {(uint32_t)i, 1u, 2u, 3u};
 #pragma unroll
-        for (int w = 0; w < W; ++w) __builtin_nontemporal_store(x, dst + w * n16 + i);
-        if (W == 0) keep ^= x;
+            for (int r = 0; r < R; ++r) x ^= __builtin_nontemporal_load(src + r * n16 + i);
+#pragma unroll
+            for (int w = 0; w < W; ++w) dst[w * n16 + i] = x;
+            if (W == 0) keep ^= x;
+        }
     }
     // (a read-only run must still use what it read: one word per thread, written only if it is the rare value)
     if (W == 0 && (keep[0] ^ keep[1] ^ keep[2] ^ keep[3]) == 0x9e3779b9u) dst[0] = keep;
 }
 
 template <int R, int W> static hipError_t launch_mix_rw(void *dst, const void *src, size_t n16, hipStream_t s) {
-    size_t blocks = (n16 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    const size_t blocks = (n16 + kMixPiece - 1) / kMixPiece;
+    if (blocks > 0x7fffffffull) return hipErrorInvalidValue;
     hipLaunchKernelGGL((hbm_mix_kernel<R, W>), dim3((unsigned)blocks), dim3(256), 0, s, (u32x4 *)dst, (const u32x4 *)src, n16);
     return hipGetLastError();
 }

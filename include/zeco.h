@@ -28,7 +28,7 @@ extern "C" {
 typedef enum {
     ZECO_OK = 0,
     ZECO_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad stride */
-    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C != 64, d not in {64,128}, dtype mix, L < C,
+    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C not 64 (bf16) or 16/32/64 (fp32), d not in {64,128}, dtype mix, L < 64,
                                * L % C != 0 with saved states */
     ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than the entry point's own *_workspace() query says */
     ZECO_ERR_HIP = 4,         /* HIP runtime refused a launch / attribute */
@@ -47,7 +47,9 @@ typedef struct {
     int32_t B, P, H, L;        /* B = 0 (an empty batch; BH = 0 in zeco_state_scan) is valid: the entry points
                                 * return ZECO_OK at once, touch no pointer and launch nothing.  Limits
                                 * (ZECO_ERR_INVALID_ARG beyond): B*P*H <= 2^24, L <= 2^30, P*L <= 2^40 */
-    int32_t d_k, d_v, C;       /* supported: C = 64, d_k and d_v in {64, 128}, any L >= C.  When L % C != 0
+    int32_t d_k, d_v, C;       /* supported: d_k and d_v in {64, 128}; C = 64, and with fp32 q/k/v also 16 and 32 (the
+                                * result does not depend on C beyond rounding; the sum of |g| over a chunk must stay
+                                * below 80, so a shorter chunk takes stronger gates); any L >= 64.  When L % C != 0
                                 * one chunk of every segment is short, L - C*(ceil(L/C) - 1) tokens (the
                                 * first one in the passes that walk a segment forwards, the last one in
                                 * those that walk it backwards; chunking changes rounding, not the result).
@@ -209,7 +211,7 @@ zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *desc, const int64_
 /* The two phases of Alg. 1's own schedule (zeco_gla_local_state, zeco_gla_fwd_from_state below) over the same
  * table: end state and total log decay of every segment from the zero state; then, after zeco_state_scan,
  * the forward of every segment from the state entering it, which writes the final o.  No o from the zero
- * state and no G_cum are ever stored.  bf16 q/k/v/o only (fp32 returns ZECO_ERR_UNSUPPORTED). */
+ * state and no G_cum are ever stored.  bf16 and fp32 q/k/v/o. */
 zeco_status zeco_gla_local_state_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
                                         const void *k, const void *v, const void *g, float *S_loc,
                                         float *G_tot, void *stream);
@@ -237,7 +239,8 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *desc, const int6
  * the forward states and their scan again, the dQ pass, which also leaves every segment's state gradient, the
  * reverse scan from dS_T, and the dV and dK passes; dg is re-anchored every 512 tokens as in
  * zeco_gla_bwd_from_state.  Arguments as in zeco_gla_fused_fwd / zeco_gla_fused_bwd (no saved states, no
- * schedule); workspace sizes from the *_workspace queries, sized for the bound desc->L.  bf16 q/k/v only. */
+ * schedule); workspace sizes from the *_workspace queries, sized for the bound desc->L.  The forward takes
+ * bf16 and fp32 q/k/v, the backward bf16 only. */
 size_t zeco_gla_fused_fwd_varlen_workspace(const zeco_gla_desc *desc);
 zeco_status zeco_gla_fused_fwd_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
                                       const void *q, const void *k, const void *v, const void *g,
@@ -251,8 +254,8 @@ zeco_status zeco_gla_fused_bwd_varlen(const zeco_gla_desc *desc, const int64_t *
                                       size_t workspace_bytes, void *stream);
 
 /* ---- Two-phase forward: Alg. 1's own schedule (chunk-state loop, All-Scan, output pass), which never
- * materialises the local output or the per-token cumulative decay.  bf16 q/k/v/o only (fp32 returns
- * ZECO_ERR_UNSUPPORTED).  Same conventions as above. ------------------------------------------------ */
+ * materialises the local output or the per-token cumulative decay.  bf16 and fp32 q/k/v/o (fp32: no saved
+ * states, no ZECO_SCHEDULE_CORRECT).  Same conventions as above. ------------------------------------- */
 
 /* Phase 1 (Alg. 1 chunk-state loop, Eq. (local-recurrence) and Eq. (gamma)): final local state and
  * total log decay of every segment from the zero state.  Reads k, v, g only.

@@ -36,8 +36,11 @@ zeco_status check_desc(const zeco_gla_desc *d, bool any_length = false) {
     // the kernels keep in-chunk offsets (64 tokens x stride_t elements) in 32 bits
     if (d->stride_t > ((int64_t)1 << 24) || d->vstride_t > ((int64_t)1 << 24)) return ZECO_ERR_UNSUPPORTED;
     if ((int64_t)d->B * d->P * d->H > (int64_t)1 << 24) return ZECO_ERR_INVALID_ARG;
-    if (d->C != 64 || !dim_ok(d->d_k) || !dim_ok(d->d_v)) return ZECO_ERR_UNSUPPORTED;
-    if (d->L % d->C != 0 && (!any_length || d->L < d->C)) return ZECO_ERR_UNSUPPORTED;
+    // chunk length: 64 for bf16 (one token per lane of a wavefront); the fp32 kernel also takes 16 and 32
+    const bool chunk_ok = d->C == 64 || (d->io_dtype == ZECO_F32 && (d->C == 16 || d->C == 32));
+    if (!chunk_ok || !dim_ok(d->d_k) || !dim_ok(d->d_v)) return ZECO_ERR_UNSUPPORTED;
+    if (d->L % d->C != 0 && !any_length) return ZECO_ERR_UNSUPPORTED;
+    if (d->L < 64) return ZECO_ERR_UNSUPPORTED;   // (the correction works on windows of 64 tokens inside a segment)
     if (d->io_dtype == ZECO_F32 && d->g_dtype != ZECO_F32) return ZECO_ERR_UNSUPPORTED;
     if (d->g_per_head != 0 && d->g_per_head != 1) return ZECO_ERR_INVALID_ARG;
     if (d->g_per_head && (d->io_dtype != ZECO_BF16 || d->g_dtype != ZECO_F32)) return ZECO_ERR_UNSUPPORTED;
@@ -56,6 +59,21 @@ int chunks_of(int L) { return (L + 63) / 64; }
 // Segment length of a chunk-kernel launch: chunks, and how far the first one falls short of 64 tokens.
 void set_length(zeco::ChunkParams &p, int L) {
     p.L = L; p.n_chunks = chunks_of(L); p.pad = 64 * p.n_chunks - L;
+}
+// The same in chunks of C tokens (the fp32 kernel).
+void set_length_c(zeco::ChunkParams &p, int L, int C) {
+    p.L = L; p.n_chunks = (L + C - 1) / C; p.pad = C * p.n_chunks - L;
+}
+
+int gate_mode(const zeco_gla_desc *d);
+// One of the three phases both precisions have (0 local pass, 1 states only, 2 output pass from S_init), on the
+// segments p describes (p.L tokens each, or the table p.seg_start).
+hipError_t launch_phase(zeco::ChunkParams &p, const zeco_gla_desc *d, int mode, hipStream_t s) {
+    if (d->io_dtype == ZECO_F32) {
+        set_length_c(p, p.L, d->C);
+        return zeco::launch_chunk_f32(p, d->d_k, d->d_v, d->C, mode, s);
+    }
+    return zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), mode, s);
 }
 
 // Segments per group of the two-level scan: the divisor g of P that minimises the length of the serial
@@ -223,7 +241,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     p.scale = d->scale; p.kscale = 1.f;
     p.sb = d->stride_b; p.st = d->stride_t; p.sh = d->stride_h;
     p.vb = d->vstride_b; p.vt = d->vstride_t; p.vh = d->vstride_h;
-    if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
+    if (d->io_dtype == ZECO_F32) return from_hip(launch_phase(p, d, 0, s));
     if (halves_with_correction(d)) {
         const SubLayout w = sub_layout(d, 2);
         float *ws = static_cast<float *>(workspace);
@@ -318,12 +336,10 @@ zeco_status zeco_gla_local_state(const zeco_gla_desc *d, const void *k, const vo
     if (!k || !v || !g || !S_loc || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_loc) || !aligned16(G_tot))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.k = k; p.v = v; p.g = g; p.S_loc = S_loc; p.G_tot = G_tot;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1,
-                                            static_cast<hipStream_t>(stream)));
+    return from_hip(launch_phase(p, d, 1, static_cast<hipStream_t>(stream)));
 }
 
 zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const void *k, const void *v,
@@ -335,12 +351,10 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_init) ||
         !aligned16(o))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_init = S_init;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2,
-                                            static_cast<hipStream_t>(stream)));
+    return from_hip(launch_phase(p, d, 2, static_cast<hipStream_t>(stream)));
 }
 
 // Pieces each segment is cut into by zeco_gla_fused_fwd: up to 256 streams, at least 256 tokens each.
@@ -375,7 +389,7 @@ static FwdLayout fwd_layout(const zeco_gla_desc *d, int S) {
 }
 
 size_t zeco_gla_fused_fwd_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK) return 0;
     return fwd_layout(desc, fused_pieces(desc)).total * sizeof(float);
 }
 
@@ -390,10 +404,11 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
         !aligned16(S0) || !aligned16(S_last) || !aligned16(S_save) || !aligned16(workspace))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     if (schedule != ZECO_SCHEDULE_AUTO && schedule != ZECO_SCHEDULE_TWO_PHASE && schedule != ZECO_SCHEDULE_CORRECT)
         return ZECO_ERR_INVALID_ARG;
-    const bool can_correct = !S_save;
+    // fp32: the two phases of Alg. 1 only (no chunk-decay correction, no states saved for a backward)
+    if (d->io_dtype != ZECO_BF16 && S_save) return ZECO_ERR_UNSUPPORTED;
+    const bool can_correct = !S_save && d->io_dtype == ZECO_BF16;
     if (schedule == ZECO_SCHEDULE_CORRECT && !can_correct) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_gla_fused_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -430,12 +445,12 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
         return from_hip(zeco::launch_apply_cd_bf16(ap, d->d_k, d->d_v, s));
     }
     p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s);
+    hipError_t e = launch_phase(p, d, 1, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::ScanParams sp;
     // With S_save the end state goes to its last slot (the backward reads it there).
-    const int Sb = bwd_pieces(d);
+    const int Sb = S_save ? bwd_pieces(d) : 1;
     float *save_last = S_save ? S_save + (size_t)d->P * Sb * d->B * d->H * d->d_k * d->d_v : nullptr;
     sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_save ? save_last : S_last;
     sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
@@ -447,8 +462,8 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
         if (e != hipSuccess) return ZECO_ERR_HIP;
     }
     p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;
-    p.S_save = S_save; p.save_every = (d->L / Sb) / d->C;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, s));
+    p.S_save = S_save; p.save_every = S_save ? (d->L / Sb) / d->C : 0;
+    return from_hip(launch_phase(p, d, 2, s));
 }
 
 // ---- backward (App. A.4) ------------------------------------------------------------------------------
@@ -791,8 +806,7 @@ zeco_status zeco_gla_local_fwd_varlen(const zeco_gla_desc *d, const int64_t *seg
     p.S_loc = S_loc; p.G_cum = G_cum; p.G_tot = G_tot;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_chunk_f32(p, d->d_k, d->d_v, s));
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s));
+    return from_hip(launch_phase(p, d, 0, s));
 }
 
 zeco_status zeco_apply_init_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
@@ -829,12 +843,11 @@ zeco_status zeco_gla_local_state_varlen(const zeco_gla_desc *d, const int64_t *s
     if (!k || !v || !g || !S_loc || !G_tot) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_loc) || !aligned16(G_tot))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.k = k; p.v = v; p.g = g; p.S_loc = S_loc; p.G_tot = G_tot;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, static_cast<hipStream_t>(stream)));
+    return from_hip(launch_phase(p, d, 1, static_cast<hipStream_t>(stream)));
 }
 
 zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
@@ -846,12 +859,11 @@ zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *d, const int64_t
     if (!q || !k || !v || !g || !S_init || !o) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(S_init) || !aligned16(o))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_init = S_init;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, static_cast<hipStream_t>(stream)));
+    return from_hip(launch_phase(p, d, 2, static_cast<hipStream_t>(stream)));
 }
 
 // The backward's building blocks over the same table (bf16 only, like the equal-length calls).
@@ -918,7 +930,7 @@ static VarlenLayout varlen_layout(const zeco_gla_desc *d, bool backward) {
 }
 
 size_t zeco_gla_fused_fwd_varlen_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK) return 0;
     return varlen_layout(desc, false).total * sizeof(float);
 }
 size_t zeco_gla_fused_bwd_varlen_workspace(const zeco_gla_desc *desc) {
@@ -936,7 +948,6 @@ zeco_status zeco_gla_fused_fwd_varlen(const zeco_gla_desc *d, const int64_t *seg
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) || !aligned16(S0) ||
         !aligned16(S_last) || !aligned16(workspace))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_gla_fused_fwd_varlen_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const VarlenLayout w = varlen_layout(d, false);
@@ -945,14 +956,14 @@ zeco_status zeco_gla_fused_fwd_varlen(const zeco_gla_desc *d, const int64_t *seg
     fill_chunk_params(p, d);
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
     p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-    if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s) != hipSuccess) return ZECO_ERR_HIP;
+    if (launch_phase(p, d, 1, s) != hipSuccess) return ZECO_ERR_HIP;
     zeco::ScanParams sp;
     sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
     sp.P = d->P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
     sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
     if (zeco::launch_scan(sp, s) != hipSuccess) return ZECO_ERR_HIP;
     p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 2, s));
+    return from_hip(launch_phase(p, d, 2, s));
 }
 
 zeco_status zeco_gla_fused_bwd_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T, const void *q,

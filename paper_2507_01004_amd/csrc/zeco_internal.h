@@ -113,7 +113,9 @@ struct LdsLimit {
 };
 
 // Each returns hipSuccess or the launch error.  d_k, d_v in {64,128}.
-hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, hipStream_t s);
+// fp32 kernel: chunk length C in {16, 32, 64} (p.n_chunks, p.pad count chunks of C tokens); mode 0 local pass,
+// 1 states only, 2 output pass from S_init
+hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, int C, int mode, hipStream_t s);
 // mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
 // 3 backward state pass (k := q, v := dO; S_loc := dS leaving the segment), 4 dV pass (q := k, k := q,
 // v := dO, S_init := dS entering the segment's final state, o := dV), 5 output pass from S_init that also

@@ -314,19 +314,19 @@ def apply_init_state(q, g_like, G_cum, S_init, o, P, scale=1.0, C=64, first_segm
     return o
 
 
-def _varlen_desc(q, v, g_code, per_head, seg_start, max_len, scale):
+def _varlen_desc(q, v, g_code, per_head, seg_start, max_len, scale, C=64):
     """Descriptor of a call over segments of unequal length: L is the bound on the lengths."""
     if seg_start.dtype != torch.int64 or not seg_start.is_cuda or seg_start.dim() != 1 or not seg_start.is_contiguous():
         raise ValueError("seg_start must be a contiguous int64 device vector of P+1 token offsets")
     if q.stride(-1) != 1 or v.stride(-1) != 1:
         raise ValueError("innermost dimension must be contiguous")
     B, T, H, dk = q.shape
-    return GlaDesc(B, seg_start.numel() - 1, H, int(max_len), dk, v.shape[-1], 64, _dtype_code(q), g_code,
+    return GlaDesc(B, seg_start.numel() - 1, H, int(max_len), dk, v.shape[-1], int(C), _dtype_code(q), g_code,
                    float(scale), q.stride(0), q.stride(1), q.stride(2), v.stride(0), v.stride(1), v.stride(2),
                    int(per_head))
 
 
-def gla_local_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, out=None):
+def gla_local_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, C=64, out=None):
     """zeco_gla_local_fwd_varlen: the local pass over segments [seg_start[p], seg_start[p+1]) of the token
     axis, none longer than max_len.  seg_start: int64 device vector.  Returns (o, S_loc, G_cum, G_tot)."""
     if not q.is_cuda:
@@ -342,7 +342,7 @@ def gla_local_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, out=None):
             raise ValueError("a per-head gate must be a contiguous [B,T,H] tensor")
     elif g.shape != q.shape or g.stride() != q.stride():
         raise ValueError("a per-channel gate must have the shape and strides of q")
-    desc = _varlen_desc(q, v, _dtype_code(g), per_head, seg_start, max_len, scale)
+    desc = _varlen_desc(q, v, _dtype_code(g), per_head, seg_start, max_len, scale, C)
     P = desc.P
     if out is None:
         o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device)
@@ -359,12 +359,12 @@ def gla_local_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, out=None):
     return o, S_loc, G_cum, G_tot
 
 
-def apply_init_state_varlen(q, g_like, G_cum, S_init, o, seg_start, max_len, scale=1.0, first_segment_is_zero=True,
+def apply_init_state_varlen(q, g_like, G_cum, S_init, o, seg_start, max_len, scale=1.0, C=64, first_segment_is_zero=True,
                             dense=False):
     """zeco_apply_init_state_varlen: the correction over the segments of gla_local_fwd_varlen, in place."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
-    desc = _varlen_desc(q, o, _dtype_code(g_like), G_cum.dim() == 3, seg_start, max_len, scale)
+    desc = _varlen_desc(q, o, _dtype_code(g_like), G_cum.dim() == 3, seg_start, max_len, scale, C)
     st = lib().zeco_apply_init_state_varlen(ctypes.byref(desc), _ptr(seg_start), q.shape[1], _ptr(q), _ptr(G_cum),
                                             _ptr(S_init), _ptr(o), _apply_flags(first_segment_is_zero, dense),
                                             _stream())
@@ -383,14 +383,14 @@ def _gate_per_head(q, g):
     return per_head
 
 
-def gla_local_state_varlen(k, v, g, seg_start, max_len, out=None):
+def gla_local_state_varlen(k, v, g, seg_start, max_len, C=64, out=None):
     """zeco_gla_local_state_varlen: end state and total log decay of every segment of the table from the
     zero state.  Returns (S_loc, G_tot)."""
     if not k.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     B, T, H, dk = k.shape
     dv = v.shape[-1]
-    desc = _varlen_desc(k, v, _dtype_code(g), _gate_per_head(k, g), seg_start, max_len, 1.0)
+    desc = _varlen_desc(k, v, _dtype_code(g), _gate_per_head(k, g), seg_start, max_len, 1.0, C)
     if out is None:
         S_loc = torch.empty(desc.P, B, H, dk, dv, dtype=torch.float32, device=k.device)
         G_tot = torch.empty((desc.P, B, H) + _gate_dims(g, dk), dtype=torch.float32, device=k.device)
@@ -403,12 +403,12 @@ def gla_local_state_varlen(k, v, g, seg_start, max_len, out=None):
     return S_loc, G_tot
 
 
-def gla_fwd_from_state_varlen(q, k, v, g, S_init, seg_start, max_len, scale=1.0, out=None):
+def gla_fwd_from_state_varlen(q, k, v, g, S_init, seg_start, max_len, scale=1.0, C=64, out=None):
     """zeco_gla_fwd_from_state_varlen: the forward of every segment of the table from S_init[p].  Returns o."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
-    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale, C)
     o = torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device) if out is None else out
     st = lib().zeco_gla_fwd_from_state_varlen(ctypes.byref(desc), _ptr(seg_start), q.shape[1], _ptr(q), _ptr(k),
                                               _ptr(v), _ptr(g), _ptr(S_init), _ptr(o), _stream())
@@ -417,14 +417,14 @@ def gla_fwd_from_state_varlen(q, k, v, g, S_init, seg_start, max_len, scale=1.0,
     return o
 
 
-def gla_bwd_dstate_varlen(q, g, dO, seg_start, max_len, scale=1.0, out=None):
+def gla_bwd_dstate_varlen(q, g, dO, seg_start, max_len, scale=1.0, C=64, out=None):
     """zeco_gla_bwd_dstate_varlen: the state gradient leaving every segment of the table towards the earlier
     ones, from dS = 0.  Returns dS_loc [P,B,H,d_k,d_v]."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     B, T, H, dk = q.shape
     dv = dO.shape[-1]
-    desc = _varlen_desc(q, dO, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    desc = _varlen_desc(q, dO, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale, C)
     dS_loc = torch.empty(desc.P, B, H, dk, dv, dtype=torch.float32, device=q.device) if out is None else out
     st = lib().zeco_gla_bwd_dstate_varlen(ctypes.byref(desc), _ptr(seg_start), T, _ptr(q), _ptr(g), _ptr(dO),
                                           _ptr(dS_loc), _stream())
@@ -440,7 +440,7 @@ def _bwd_from_state_workspace(desc, workspace, device):
     return workspace, (workspace.numel() if workspace is not None else 0)
 
 
-def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, max_len, scale=1.0, out=None,
+def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, max_len, scale=1.0, C=64, out=None,
                               workspace=None):
     """zeco_gla_bwd_from_state_varlen: dq, dk, dv, dg of every segment of the table from the scanned forward
     states and state gradients.  Returns (dq, dk, dv, dg)."""
@@ -448,7 +448,7 @@ def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, 
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
     _check_same_layout(v, dO)
-    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale, C)
     dq, dk, dv, dg = _grad_outputs(q, v, g) if out is None else out
     workspace, ws_bytes = _bwd_from_state_workspace(desc, workspace, q.device)
     st = lib().zeco_gla_bwd_from_state_varlen(ctypes.byref(desc), _ptr(seg_start), q.shape[1], _ptr(q), _ptr(k),
@@ -460,13 +460,13 @@ def gla_bwd_from_state_varlen(q, k, v, g, dO, S_init, S_last, dS_in, seg_start, 
     return dq, dk, dv, dg
 
 
-def gla_fused_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, S0=None, out=None, workspace=None):
+def gla_fused_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, C=64, S0=None, out=None, workspace=None):
     """zeco_gla_fused_fwd_varlen: the whole forward over a table of unequal segments.  Returns (o, S_last)."""
     if not q.is_cuda:
         raise RuntimeError("zeco kernels run on the GPU only")
     _check_same_layout(q, k)
     B, T, H, dk = q.shape
-    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale, C)
     if out is None:
         out = (torch.empty_strided(v.shape, v.stride(), dtype=v.dtype, device=v.device),
                torch.empty(B, H, dk, v.shape[-1], dtype=torch.float32, device=q.device))
@@ -481,7 +481,7 @@ def gla_fused_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, S0=None, out
     return o, S_last
 
 
-def gla_fused_bwd_varlen(q, k, v, g, dO, seg_start, max_len, scale=1.0, S0=None, dS_T=None, out=None, workspace=None):
+def gla_fused_bwd_varlen(q, k, v, g, dO, seg_start, max_len, scale=1.0, C=64, S0=None, dS_T=None, out=None, workspace=None):
     """zeco_gla_fused_bwd_varlen: the whole backward over a table of unequal segments.
     Returns (dq, dk, dv, dg, dS0)."""
     if not q.is_cuda:
@@ -489,7 +489,7 @@ def gla_fused_bwd_varlen(q, k, v, g, dO, seg_start, max_len, scale=1.0, S0=None,
     _check_same_layout(q, k)
     _check_same_layout(v, dO)
     B, T, H, dk = q.shape
-    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale)
+    desc = _varlen_desc(q, v, _dtype_code(g), _gate_per_head(q, g), seg_start, max_len, scale, C)
     if out is None:
         out = _grad_outputs(q, v, g) + (torch.empty(B, H, dk, v.shape[-1], dtype=torch.float32, device=q.device),)
     dq, dk_, dv, dg, dS0 = out
@@ -711,10 +711,10 @@ def hbm_mix(dst, src, slice_bytes, reads, writes):
         raise ZecoError(st, "zeco_hbm_mix")
 
 
-def segmented_fwd(q, k, v, g, P, scale=1.0, S0=None, K_blocks=16):
+def segmented_fwd(q, k, v, g, P, scale=1.0, S0=None, K_blocks=16, C=64):
     """Local pass, segment-state scan and correction chained.  Returns (o, S_last, parts) with
     parts = dict(S_loc, G_cum, G_tot, S_init)."""
-    o, S_loc, G_cum, G_tot = gla_local_fwd(q, k, v, g, P, scale)
+    o, S_loc, G_cum, G_tot = gla_local_fwd(q, k, v, g, P, scale, C=C)
     S_init, S_last = state_scan(S_loc, G_tot, S0=S0, K_blocks=K_blocks)
-    apply_init_state(q, g, G_cum, S_init, o, P, scale, first_segment_is_zero=S0 is None)
+    apply_init_state(q, g, G_cum, S_init, o, P, scale, C=C, first_segment_is_zero=S0 is None)
     return o, S_last, dict(S_loc=S_loc, G_cum=G_cum, G_tot=G_tot, S_init=S_init)

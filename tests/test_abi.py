@@ -157,7 +157,7 @@ def test_unequal_segment_lengths_validate_before_any_launch(L):
     need_b = L.zeco_gla_fused_bwd_varlen_workspace(ref(good_desc(L=1000)))
     assert 0 < need_f < need_b and L.zeco_gla_fused_bwd_varlen_workspace(ref(good_desc(io_dtype=zeco.ZECO_F32))) == 0
     assert ffw(ws=need_f - 1) == zeco.ZECO_ERR_WORKSPACE and fbw(ws=need_b - 1) == zeco.ZECO_ERR_WORKSPACE
-    for call in (sta, out, dst, bwd, ffw, fbw):
+    for call in (dst, bwd, fbw):     # the backward is bf16 only; the forward phases take fp32 too
         assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
     for call in (loc, app, sta, out, dst, bwd, ffw, fbw):
         assert call(seg=None) == zeco.ZECO_ERR_INVALID_ARG
@@ -283,3 +283,17 @@ def test_hbm_mix_takes_only_the_mixes_it_was_built_for(L):
     assert L.zeco_hbm_mix(FAKE, FAKE, 1 << 20, 0, 0, None) == zeco.ZECO_ERR_UNSUPPORTED
     assert L.zeco_hbm_mix(None, FAKE, 1 << 20, 4, 1, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_hbm_mix(FAKE, FAKE, 24, 4, 1, None) == zeco.ZECO_ERR_INVALID_ARG
+
+
+def test_chunk_length_per_precision(L):
+    """C = 64 for bf16 q/k/v; the fp32 kernel also has 16 and 32.  Segments shorter than 64 tokens are refused
+    whatever the chunk length (the correction works on windows of 64 tokens)."""
+    ref = ctypes.byref
+    f32 = lambda **kw: good_desc(io_dtype=zeco.ZECO_F32, **kw)
+    ws = L.zeco_gla_fused_fwd_workspace
+    assert ws(ref(f32())) > 0 and ws(ref(f32(C=16))) > 0 and ws(ref(f32(C=32))) > 0
+    assert ws(ref(f32(C=48))) == 0 and ws(ref(f32(C=128))) == 0 and ws(ref(good_desc(C=32))) == 0
+    assert call_local(L, good_desc(C=32)) == zeco.ZECO_ERR_UNSUPPORTED
+    assert call_local(L, f32(C=8)) == zeco.ZECO_ERR_UNSUPPORTED
+    assert call_local(L, f32(C=16, L=48)) == zeco.ZECO_ERR_UNSUPPORTED
+    assert call_local(L, f32(C=16, L=80), q=None) == zeco.ZECO_ERR_INVALID_ARG      # the descriptor itself is fine

@@ -475,8 +475,15 @@ def test_chunk_decay_correction_stops_where_the_decay_has_vanished(gd):
                 assert torch.equal(outs[0][:, p * L + 64 * n_stop:(p + 1) * L, h], o0[:, p * L + 64 * n_stop:(p + 1) * L, h])
 
 
-def test_two_phase_rejects_fp32():
+def test_fused_forward_fp32_has_the_two_phases_only():
+    """fp32 inputs take Alg. 1's schedule (tests/test_gpu_f32_chunks.py); the chunk-decay correction schedule and
+    the states saved for a backward exist for bf16 only."""
     q = torch.zeros(1, 64, 1, 64, device="cuda")
+    o, _ = zeco.gla_fused_fwd(q, q, q, q, 1)
+    assert torch.equal(o, q)
     with pytest.raises(zeco.ZecoError) as e:
-        zeco.gla_fused_fwd(q, q, q, q, 1)
+        zeco.gla_fused_fwd(q, q, q, q, 1, schedule=zeco.SCHEDULE_CORRECT)
+    assert e.value.status == zeco.ZECO_ERR_UNSUPPORTED
+    with pytest.raises(zeco.ZecoError) as e:
+        zeco.gla_fused_fwd(q, q, q, q, 1, save=torch.empty(1 << 20, dtype=torch.uint8, device="cuda"))
     assert e.value.status == zeco.ZECO_ERR_UNSUPPORTED

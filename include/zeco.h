@@ -28,8 +28,7 @@ extern "C" {
 typedef enum {
     ZECO_OK = 0,
     ZECO_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, misaligned pointer, bad stride */
-    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C not 64 (bf16) or 16/32/64 (fp32), d not in {64,128}, dtype mix, L < 64,
-                               * L % C != 0 with saved states */
+    ZECO_ERR_UNSUPPORTED = 2, /* valid but not implemented: C not 64 (bf16) or 16/32/64 (fp32), d not in {64,128}, dtype mix, L < 64 */
     ZECO_ERR_WORKSPACE = 3,   /* workspace smaller than the entry point's own *_workspace() query says */
     ZECO_ERR_HIP = 4,         /* HIP runtime refused a launch / attribute */
     ZECO_ERR_SCRATCH_LIMIT = 5 /* zeco_state_scan_tree_static: the problem needs more than the library's static scratch */
@@ -52,9 +51,7 @@ typedef struct {
                                 * below 80, so a shorter chunk takes stronger gates); any L >= 64.  When L % C != 0
                                 * one chunk of every segment is short, L - C*(ceil(L/C) - 1) tokens (the
                                 * first one in the passes that walk a segment forwards, the last one in
-                                * those that walk it backwards; chunking changes rounding, not the result).
-                                * Only the states saved by the forward for the backward (S_save, S_saved)
-                                * need L % C == 0, else ZECO_ERR_UNSUPPORTED. */
+                                * those that walk it backwards; chunking changes rounding, not the result). */
     int32_t io_dtype;          /* zeco_dtype of q, k, v, o */
     int32_t g_dtype;           /* zeco_dtype of g */
     float scale;
@@ -276,9 +273,9 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *desc, const void *q, co
  *   in   S0 [B,H,d_k,d_v] fp32 or NULL: state entering the first segment
  *   out  o;  S_last [B,H,d_k,d_v] fp32 or NULL: state after the last token
  *   out  S_save: NULL, or zeco_gla_saved_states_bytes(desc) bytes of device memory that receive the
- *        forward states at the boundaries of the pieces the backward works on (a d_k x d_v state per
- *        512 tokens and head, and the end state); handing it to zeco_gla_fused_bwd spares that call the
- *        recomputation of the forward states.  Contents are private to the library.
+ *        forward states entering the pieces the backward works on (the forward's own pieces), and the
+ *        end state; handing it to zeco_gla_fused_bwd spares that call the recomputation of the forward
+ *        states.  Contents are private to the library.  bf16 only.
  *   schedule:
  *     ZECO_SCHEDULE_TWO_PHASE  Alg. 1's: chunk-state pass (k, v, g), scan, output pass from the scanned
  *                              states.  Traffic does not depend on the data.
@@ -286,7 +283,7 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *desc, const void *q, co
  *                              correction stops where the decay factor has vanished, so with decays whose
  *                              e-folding length is far below the piece length k, v, g are read once
  *                              instead of twice; with decays near 1 it moves about 10 % more than
- *                              two-phase.  Not together with S_save.
+ *                              two-phase.
  *     ZECO_SCHEDULE_AUTO       CORRECT when it is available and the pieces are at least 4096 tokens long,
  *                              else TWO_PHASE.
  * workspace: zeco_gla_fused_fwd_workspace(desc) bytes of device memory, 16-byte aligned (enough for

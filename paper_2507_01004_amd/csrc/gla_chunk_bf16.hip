@@ -95,8 +95,6 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 //   kLocal   the local pass from the zero state: o, S_loc, G_cum, G_tot          (Sec. 3.1)
 //   kStates  only the final local state and total decay of each segment: S_loc, G_tot
 //            (Alg. 1's chunk-state loop; q is not read, nothing per token is written)
-//   kOutputSave  kOutput that also stores the running state every save_every chunks (a launch of its own:
-//            the 64 strided stores cost the plain output pass registers it does not have, 2 % of its time)
 //   kOutput  the output pass from given initial states S_init[p]: o only
 //            (Alg. 1's output pass, the incoming state folded into the running state)
 //   kLocalCD the local pass with the cumulative decay kept per chunk, as Alg. 1 stores it (the list of
@@ -116,7 +114,7 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
 // kDV: q := k, k := q, v := dO, o := dV), flip the sign of the decay exponents, apply gamma before the
 // chunk's products instead of after, and store token t of a chunk at tile row 63 - t, so that the
 // causal structure of the tiles is the one of the forward pass.
-enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4, kLocalInit = 5, kLocalCD = 6, kOutputSave = 7 };
+enum ChunkMode { kLocal = 0, kStates = 1, kOutput = 2, kDState = 3, kDV = 4, kLocalInit = 5, kLocalCD = 6 };
 
 // Gate waves per workgroup: 4, one per SIMD beside an MFMA wave; 8 in the local pass with per-channel
 // gates at d_k = 128, which moves the most bytes per chunk and gains 2-3 % from the second set of
@@ -147,7 +145,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     constexpr bool GH = GM == kGateHead;
     constexpr bool REV = MODE == kDState || MODE == kDV;          // chunks and tokens in reverse
     constexpr bool NOQ = MODE == kStates || MODE == kDState;      // only the state is computed
-    constexpr bool FROM_INIT = MODE == kOutput || MODE == kOutputSave || MODE == kDV || MODE == kLocalInit;   // start from S_init, emit no state
+    constexpr bool FROM_INIT = MODE == kOutput || MODE == kDV || MODE == kLocalInit;   // start from S_init, emit no state
     constexpr bool EMIT_G = MODE == kLocal || MODE == kLocalInit;  // per-token cumulative log decay
     constexpr float SGN = REV ? -1.f : 1.f;                       // sign of the decay exponents
     constexpr float kLog2e = 1.4426950408889634f;
@@ -186,7 +184,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     sidx /= p.H;
     const int b = sidx % p.B, seg = sidx / p.B;
     long long tok0 = (long long)seg * p.L, T = (long long)p.P * p.L;   // first token; tokens per batch entry
-    if constexpr (MODE != kLocalInit && MODE != kLocalCD && MODE != kOutputSave) {
+    if constexpr (MODE != kLocalInit && MODE != kLocalCD) {
         if (p.seg_start) {
             // segments of unequal length: this one's bounds from the table.  A segment the kernel cannot take
             // (under 64 tokens, over the bound L, outside the tensor) is left alone: the whole workgroup leaves.
@@ -427,7 +425,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             }
             // decay outputs: the local pass and the two state passes (the backward one emits G_tot when
             // asked, so that the reverse scan does not need the forward state pass)
-            if constexpr (MODE == kOutput || MODE == kOutputSave || MODE == kDV) return;
+            if constexpr (MODE == kOutput || MODE == kDV) return;
             if constexpr (MODE == kDState) {
                 if (!p.G_tot) return;
             }
@@ -629,18 +627,6 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         __syncthreads();
         for (int n = 0; n < N; ++n) {
             const unsigned char *cur = lds + (n & 1) * Cfg::kTileBytes;
-            if constexpr (MODE == kOutputSave) {
-                // the state entering every save_every-th chunk, kept for the backward pass
-                if (p.S_save && n % p.save_every == 0) {
-                    const size_t piece = (size_t)seg * (N / p.save_every) + n / p.save_every;
-                    float *Sv = p.S_save + ((piece * p.B + b) * p.H + h) * DK * (DV * NS) + slice * DV + w * 32 + lt;
-#pragma unroll
-                    for (int it = 0; it < Cfg::NIT; ++it)
-#pragma unroll
-                        for (int rr = 0; rr < 16; ++rr)
-                            Sv[(size_t)(it * 32 + M::row(rr, kg)) * (DV * NS)] = Sacc[it][rr];
-                }
-            }
             if constexpr (!NOQ) mfma_a(cur, gam + (n & 1) * DK);
             __syncthreads();
             mfma_b(n, cur, gam + (n & 1) * DK);
@@ -695,8 +681,7 @@ static hipError_t dispatch_gate(const ChunkParams &p, int d_k, int d_v, int gate
 
 hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mode, int mode, hipStream_t s) {
     if (mode == kStates) return dispatch_gate<kStates>(p, d_k, d_v, gate_mode, s);
-    if (mode == kOutput)
-        return p.S_save ? dispatch_gate<kOutputSave>(p, d_k, d_v, gate_mode, s) : dispatch_gate<kOutput>(p, d_k, d_v, gate_mode, s);
+    if (mode == kOutput) return dispatch_gate<kOutput>(p, d_k, d_v, gate_mode, s);
     if (mode == kDState) return dispatch_gate<kDState>(p, d_k, d_v, gate_mode, s);
     if (mode == kDV) return dispatch_gate<kDV>(p, d_k, d_v, gate_mode, s);
     if (mode == kLocalInit) return dispatch_gate<kLocalInit>(p, d_k, d_v, gate_mode, s);

@@ -294,7 +294,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
 // ---- two-phase forward ------------------------------------------------------------------------------
 static void fill_chunk_params(zeco::ChunkParams &p, const zeco_gla_desc *d) {
     p.q = p.k = p.v = p.g = nullptr; p.o = nullptr;
-    p.S_loc = p.G_cum = p.G_tot = nullptr; p.S_init = nullptr; p.S_save = nullptr; p.save_every = 0;
+    p.S_loc = p.G_cum = p.G_tot = nullptr; p.S_init = nullptr;
     p.B = d->B; p.P = d->P; p.H = d->H;
     set_length(p, d->L);
     p.scale = d->scale; p.kscale = 1.f;
@@ -399,7 +399,6 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
-    if (S_save && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // states are saved on whole chunks only
     if (!q || !k || !v || !g || !o || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(o) ||
         !aligned16(S0) || !aligned16(S_last) || !aligned16(S_save) || !aligned16(workspace))
@@ -408,7 +407,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
         return ZECO_ERR_INVALID_ARG;
     // fp32: the two phases of Alg. 1 only (no chunk-decay correction, no states saved for a backward)
     if (d->io_dtype != ZECO_BF16 && S_save) return ZECO_ERR_UNSUPPORTED;
-    const bool can_correct = !S_save && d->io_dtype == ZECO_BF16;
+    const bool can_correct = d->io_dtype == ZECO_BF16;
     if (schedule == ZECO_SCHEDULE_CORRECT && !can_correct) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_gla_fused_fwd_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -416,23 +415,40 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     const FwdLayout w = fwd_layout(d, S);
     float *Sloc = static_cast<float *>(workspace), *Sinit = Sloc + w.off_Sinit, *Gtot = Sloc + w.off_Gtot;
     float *Gchunk = Sloc + w.off_decay, *tree = Sloc + w.off_tree;
+    // With S_save the scan writes the states entering the pieces, and the end state after them, straight into
+    // it: the backward works on the same pieces and reads them there (S_save [n pieces + 1 slot per (b, h)]).
+    if (S_save) Sinit = S_save;
+    float *save_last = S_save ? S_save + w.states : nullptr;
 
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.P = d->P * S; set_length(p, d->L / S);
+    const bool correct = schedule == ZECO_SCHEDULE_CORRECT || (schedule == ZECO_SCHEDULE_AUTO && can_correct && p.L >= 4096);
 
-    if (schedule == ZECO_SCHEDULE_CORRECT || (schedule == ZECO_SCHEDULE_AUTO && can_correct && p.L >= 4096)) {
-        // local pass of every piece from the zero state, scan, correction of the pieces' heads
-        // (per-head gates keep the per-token form: their G_cum is 4 bytes per token and head)
-        p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_loc = Sloc; p.G_tot = Gtot;
+    // first pass: the pieces from the zero state - with their local outputs and the cumulative decay per chunk
+    // (per token with per-head gates, whose G_cum is 4 bytes per token and head), or their end states only
+    p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
+    hipError_t e;
+    if (correct) {
+        p.q = q; p.o = o;
         if (d->g_per_head) p.G_cum = Gchunk; else p.G_chunk = Gchunk;
-        hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), d->g_per_head ? 0 : 6, s);
+        e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), d->g_per_head ? 0 : 6, s);
+    } else {
+        e = launch_phase(p, d, 1, s);
+    }
+    if (e != hipSuccess) return ZECO_ERR_HIP;
+
+    zeco::ScanParams sp;
+    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_save ? save_last : S_last;
+    sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
+    sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
+    if ((e = launch_scan_chain(sp, tree, s)) != hipSuccess) return ZECO_ERR_HIP;
+    if (S_save && S_last) {
+        e = zeco::launch_copy(S_last, save_last, (size_t)d->B * d->H * d->d_k * d->d_v * sizeof(float), s);
         if (e != hipSuccess) return ZECO_ERR_HIP;
-        zeco::ScanParams sp;
-        sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_last;
-        sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
-        sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
-        if ((e = launch_scan_chain(sp, tree, s)) != hipSuccess) return ZECO_ERR_HIP;
+    }
+
+    if (correct) {   // correction of the pieces' heads
         zeco::ApplyParams ap;
         fill_apply_params(ap, d, p.P, p.L);
         ap.q = q; ap.S_init = Sinit; ap.o = o;
@@ -444,25 +460,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
         ap.g = g; ap.g_bf16 = d->g_dtype == ZECO_BF16; ap.G_chunk = Gchunk;
         return from_hip(zeco::launch_apply_cd_bf16(ap, d->d_k, d->d_v, s));
     }
-    p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-    hipError_t e = launch_phase(p, d, 1, s);
-    if (e != hipSuccess) return ZECO_ERR_HIP;
-
-    zeco::ScanParams sp;
-    // With S_save the end state goes to its last slot (the backward reads it there).
-    const int Sb = S_save ? bwd_pieces(d) : 1;
-    float *save_last = S_save ? S_save + (size_t)d->P * Sb * d->B * d->H * d->d_k * d->d_v : nullptr;
-    sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = S_save ? save_last : S_last;
-    sp.P = p.P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
-    sp.rows_per_block = d->d_k / 16; sp.gate_per_head = d->g_per_head;
-    if ((e = launch_scan_chain(sp, tree, s)) != hipSuccess) return ZECO_ERR_HIP;
-
-    if (S_save && S_last) {
-        e = zeco::launch_copy(S_last, save_last, (size_t)d->B * d->H * d->d_k * d->d_v * sizeof(float), s);
-        if (e != hipSuccess) return ZECO_ERR_HIP;
-    }
-    p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;
-    p.S_save = S_save; p.save_every = S_save ? (d->L / Sb) / d->C : 0;
+    p.q = q; p.o = o; p.S_init = Sinit; p.S_loc = nullptr; p.G_tot = nullptr;   // output pass from the scanned states
     return from_hip(launch_phase(p, d, 2, s));
 }
 
@@ -566,29 +564,14 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
     return bwd_dv_dk_passes(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dS_in, dk, dv, dg, S_ck, s);
 }
 
-// Pieces each segment is cut into by zeco_gla_fused_bwd: as in the forward, and further down to at most
-// 512 tokens.  The gate gradient is a running sum of nearly cancelling terms that restarts, with an
-// exactly known value, at every piece boundary; the bf16 rounding noise of the terms grows with the
-// square root of the run length (measured, worst head: 4 % of max|dG| over 8192 tokens, 1.8 % over
-// 1024, 1.2 % over 512).
-// A length that is no multiple of 64 is cut into equal pieces of 64 to 512 tokens when it has such a
-// divisor (the pieces then start with a short chunk each) and is left whole otherwise.
-static int bwd_pieces(const zeco_gla_desc *d) {
-    if (d->L % 64 != 0) {
-        for (int S = (d->L + 511) / 512; S <= d->L / 64; ++S)
-            if (d->L % S == 0) return S;
-        return 1;
-    }
-    // whole chunks per piece, and every forward piece a whole number of backward pieces (the forward saves
-    // its states at the backward's piece boundaries): the forward's count times the smallest factor that
-    // brings the pieces to 512 tokens or fewer and leaves them at least two chunks
-    int S = fused_pieces(d);
-    const int chunks = d->L / S / 64, want = (d->L / S + 511) / 512;
-    for (int m = want; m > 1 && 2 * m <= chunks; ++m)
-        if (chunks % m == 0) return S * m;
-    while (d->L / S > 512 && d->L % (2 * S * 64) == 0) S *= 2;   // none (a prime count): halve while it halves
-    return S;
-}
+// Pieces each segment is cut into by zeco_gla_fused_bwd: the forward's (as many streams as fill the compute units
+// once, whole chunks or equal ragged pieces).  The gate gradient, a running sum of nearly cancelling terms whose
+// bf16 rounding noise grows with the square root of the run length, is re-anchored every 512 tokens inside a
+// piece from the forward-state checkpoints of the dQ pass, so the pieces need not be short for its sake: cut
+// down to 512 tokens each (as this call once did) the same passes spend 12-20 % more time on pipeline prologues,
+// on the states of 64 times as many pieces and on scans over them (c3 3.58 -> 3.12 ms, c4 28.2 -> 22.6 ms,
+// c5 113 -> 93.5 ms).
+static int bwd_pieces(const zeco_gla_desc *d) { return fused_pieces(d); }
 
 // Workspace of zeco_gla_fused_bwd, in floats: forward piece states S_loc [n], S_init [n + one more
 // slot per (b,h) for the final state], their G_tot [n]; state gradients dS_loc [n], dS_in [n].
@@ -613,7 +596,7 @@ static BwdLayout bwd_layout(const zeco_gla_desc *d, int S) {
 }
 
 size_t zeco_gla_saved_states_bytes(const zeco_gla_desc *desc) {
-    if (check_desc(desc) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
     const BwdLayout w = bwd_layout(desc, bwd_pieces(desc));
     return (w.n + (size_t)desc->B * desc->H) * w.state * sizeof(float);
 }
@@ -630,7 +613,6 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     const zeco_status st = check_desc(d, true);
     if (st != ZECO_OK) return st;
     if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
-    if (S_saved && d->L % d->C != 0) return ZECO_ERR_UNSUPPORTED;   // states are saved on whole chunks only
     if (!q || !k || !v || !g || !dO || !dq || !dk || !dv || !dg || !workspace) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g) || !aligned16(dO) ||
         !aligned16(S0) || !aligned16(dS_T) || !aligned16(S_saved) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) ||

@@ -18,8 +18,6 @@ struct ChunkParams {
     const float *S_init;       // [P,B,H,d_k,d_v] initial states (modes that start from a given state)
     const float *G_off = nullptr;   // [P,B,H,d_k] ([P,B,H] per-head) log decay preceding each segment (mode 5 only)
     float *G_chunk = nullptr;       // [B,P,n_chunks,H,d_k] log decay from the segment start to each chunk's start (mode 6 only)
-    float *S_save = nullptr;   // output pass: states entering every save_every-th chunk,
-    int save_every = 0;        //   [P * n_chunks / save_every, B, H, d_k, d_v]
     int B, P, H, L;
     int n_chunks;              // ceil(L / 64)
     int pad = 0;               // 64 n_chunks - L: the first chunk processed holds 64 - pad tokens

@@ -80,19 +80,17 @@ def test_local_fwd_rejects_bad_descriptors(L, kw, expect):
 
 def test_segment_lengths_that_are_no_multiple_of_the_chunk(L):
     """The entry points take them (validation gets past the descriptor: the next check, a null pointer,
-    answers), except where states are saved for the backward: those live on whole chunks."""
+    answers), saved states included."""
     d, ref = good_desc(L=100), ctypes.byref
     assert call_local(L, d, q=None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_apply_init_state(ref(d), None, FAKE, FAKE, FAKE, 1, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_local_fwd_chunk_decay(ref(d), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_fused_fwd_workspace(ref(d)) > 0
-    assert L.zeco_gla_fused_bwd_workspace(ref(d)) > 0 and L.zeco_gla_saved_states_bytes(ref(d)) == 0
+    assert L.zeco_gla_fused_bwd_workspace(ref(d)) > 0 and L.zeco_gla_saved_states_bytes(ref(d)) > 0
     assert L.zeco_gla_bwd_dstate(ref(d), None, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
-    fwd = [FAKE] * 4 + [None, FAKE, None]
-    assert L.zeco_gla_fused_fwd(ref(d), *fwd, FAKE, 0, FAKE, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED   # S_save
+    fwd = [None] + [FAKE] * 3 + [None, FAKE, None]
+    assert L.zeco_gla_fused_fwd(ref(d), *fwd, FAKE, 0, FAKE, 1 << 30, None) == zeco.ZECO_ERR_INVALID_ARG   # with S_save
     fused = [FAKE] * 5 + [None, None, FAKE] + [FAKE] * 4 + [None, FAKE]
-    assert L.zeco_gla_fused_bwd(ref(d), *fused, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED   # S_saved
-    fused[7] = None
     fused[0] = None
     assert L.zeco_gla_fused_bwd(ref(d), *fused, 1 << 30, None) == zeco.ZECO_ERR_INVALID_ARG
 
@@ -249,8 +247,10 @@ def test_chunk_decay_and_fused_forward_reject_bad_arguments(L):
     fused = [FAKE, FAKE, FAKE, FAKE, None, FAKE, None, None]
     assert L.zeco_gla_fused_fwd(ref(d), *fused, 7, FAKE, need, None) == zeco.ZECO_ERR_INVALID_ARG
     assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
-    fused[7] = FAKE                                        # saved states need the two-phase schedule
-    assert L.zeco_gla_fused_fwd(ref(d), *fused, zeco.SCHEDULE_CORRECT, FAKE, need, None) == zeco.ZECO_ERR_UNSUPPORTED
+    f32 = good_desc(io_dtype=zeco.ZECO_F32)                # fp32: two phases only, no saved states
+    assert L.zeco_gla_fused_fwd(ref(f32), *fused, zeco.SCHEDULE_CORRECT, FAKE, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED
+    fused[7] = FAKE
+    assert L.zeco_gla_fused_fwd(ref(f32), *fused, zeco.SCHEDULE_TWO_PHASE, FAKE, 1 << 30, None) == zeco.ZECO_ERR_UNSUPPORTED
 
 
 def test_a_missing_library_raises_instead_of_falling_back(monkeypatch):

@@ -139,26 +139,29 @@ def test_bwd_rejects_fp32_and_small_workspace():
     assert e.value.status == zeco.ZECO_ERR_WORKSPACE
 
 
-@pytest.mark.parametrize("case", [CASES[0], CASES[2], CASES[3], CASES[5], CASES[6]], ids=lambda c: c[0])
+@pytest.mark.parametrize("case", [CASES[0], CASES[2], CASES[3], CASES[5], CASES[6],
+                                  ("bwd_saved_ragged", 1, 2, 2, 1000, 128, 128, "f32"),
+                                  ("bwd_saved_long", 1, 1, 1, 16384, 128, 128, "f32")], ids=lambda c: c[0])
 def test_backward_from_states_saved_by_the_forward(case):
-    """The forward leaves the states at the backward's piece boundaries; the backward started from them
-    (no recomputation of the forward states) gives the same gradients within tolerance."""
+    """The forward, by either schedule, leaves the states entering the backward's pieces; the backward started
+    from them (no recomputation of the forward states) gives the same gradients within tolerance."""
     name, B, H, P, L, dk, dv, gd = case
     print("case", case, flush=True)
     inp = make(case, gate_div=64.0)
     q, k, v, g, dO = (inp[n] for n in ("q", "k", "v", "g", "dO"))
     gen = torch.Generator(device="cuda").manual_seed(zlib.crc32(name.encode()) % 10000 + 14)
     S0 = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
-    save = torch.empty(zeco.saved_states_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
-    o, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0, save=save)
-    o_plain, S_last_plain = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0)
-    assert torch.equal(o, o_plain) and torch.equal(S_last, S_last_plain)     # saving changes nothing
-    got = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, saved=save)       # S0 comes with the saved states
-    torch.cuda.synchronize()
     ref = oracle_bwd(inp, 0.5, host(S0), None)
-    for name_, x, r in zip(GRADS, got[:4], ref[:4]):
-        assert rel_err_bh(host(x), r, AXES) <= TOL["bf16"], name_
-    assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= TOL["bf16"]
+    for sched in (zeco.SCHEDULE_TWO_PHASE, zeco.SCHEDULE_CORRECT):
+        save = torch.empty(zeco.saved_states_bytes(q, v, g, P), dtype=torch.uint8, device="cuda")
+        o, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0, save=save, schedule=sched)
+        o_plain, S_last_plain = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0, schedule=sched)
+        assert torch.equal(o, o_plain) and torch.equal(S_last, S_last_plain)     # saving changes nothing
+        got = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, saved=save)       # S0 comes with the saved states
+        torch.cuda.synchronize()
+        for name_, x, r in zip(GRADS, got[:4], ref[:4]):
+            assert rel_err_bh(host(x), r, AXES) <= TOL["bf16"], name_
+        assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= TOL["bf16"]
 
 
 @pytest.mark.parametrize("H", [1, 2])

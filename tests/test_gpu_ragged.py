@@ -239,10 +239,9 @@ def test_ragged_backward_per_head_gates():
     assert rel_err_bh(host(got[3]), ref[3].sum(axis=-1), (0, 2)) <= TOL["bf16"]
 
 
-def test_ragged_lengths_where_whole_chunks_are_needed():
-    """Saved states live on whole chunks; a segment must hold at least one chunk."""
+def test_ragged_lengths_a_segment_must_hold_a_chunk():
     inp = synth.make_inputs(1, 200, 2, 128, 128, seed=3, io="bf16", g="f32", device="cuda")
     q, k, v, g = inp["q"], inp["k"], inp["v"], inp["g"]
-    assert zeco.saved_states_bytes(q, v, g, 2) == 0
+    assert zeco.saved_states_bytes(q, v, g, 2) > 0       # states are saved per piece, whatever its length
     with pytest.raises(zeco.ZecoError):      # shorter than a chunk
         zeco.gla_local_fwd(q[:, :80], k[:, :80], v[:, :80], g[:, :80], 2)

@@ -332,6 +332,17 @@ def run_workload(args, workload, with_cpu):
         del gh, ws, o2
         step()   # the fp32-gate outputs again
 
+    # The same three calls with the wide range of gates (zeco_gla_desc.wide_gates: decay factors of the tiles
+    # counted from half the chunk's total, a second multiplication of the state per chunk).
+    wide = None
+    if c["io"] == "bf16" and not args.no_variants:
+        with zeco.wide_gates():
+            lms = timed(lambda: zeco.gla_local_fwd(q, k, v, g, P, out=(o, S_loc, G_cum, G_tot)), warm=3,
+                        reps=max(1, args.steps // 2))
+            t = timed(step, warm=3, reps=max(1, args.steps // 2))
+        wide = {"local_fwd_ms": round(lms, 4), "ms_per_step": round(t, 4), "tokens_per_s": round(B * T / (t * 1e-3), 1)}
+        step()   # the standard range's outputs again
+
     copy_gbs = None
     if args.calib_copy_mib:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -517,6 +528,7 @@ def run_workload(args, workload, with_cpu):
         "chunk_decay": chunk_decay,
         "backward": backward,
         "g_bf16": g_bf16,
+        "wide_gates": wide,
         "hbm_copy_GBps": None if copy_gbs is None else round(copy_gbs, 1),
         "hbm_mix_GBps": mix_gbs,
     }
@@ -580,7 +592,7 @@ def main():
             r = run_workload(args, "c3", with_cpu=False)
             torch.cuda.empty_cache()
             others["c3"] = {n: r[n] for n in ("value", "ms_per_step", "config", "roofline", "kernels", "dense_correction_step",
-                                              "two_phase", "fused_correct", "chunk_decay", "backward", "g_bf16",
+                                              "two_phase", "fused_correct", "chunk_decay", "backward", "g_bf16", "wide_gates",
                                               "unequal_segments") if n in r}
         if args.workload != "c2":
             others["c2"] = single_segment_case(args)

@@ -47,8 +47,8 @@ typedef struct {
                                 * return ZECO_OK at once, touch no pointer and launch nothing.  Limits
                                 * (ZECO_ERR_INVALID_ARG beyond): B*P*H <= 2^24, L <= 2^30, P*L <= 2^40 */
     int32_t d_k, d_v, C;       /* supported: d_k and d_v in {64, 128}; C = 64, and with fp32 q/k/v also 16 and 32 (the
-                                * result does not depend on C beyond rounding; the sum of |g| over a chunk must stay
-                                * below 80, so a shorter chunk takes stronger gates); any L >= 64.  When L % C != 0
+                                * result does not depend on C beyond rounding; the sum of |g| over a chunk is limited,
+                                * see wide_gates, so a shorter chunk takes stronger gates); any L >= 64.  When L % C != 0
                                 * one chunk of every segment is short, L - C*(ceil(L/C) - 1) tokens (the
                                 * first one in the passes that walk a segment forwards, the last one in
                                 * those that walk it backwards; chunking changes rounding, not the result). */
@@ -61,6 +61,17 @@ typedef struct {
                                 * 1: one log decay per (token, head) shared by all d_k channels (the
                                 *    scalar-decay members of the family, Sec. 2.1): g, G_cum and dg are
                                 *    contiguous [B,T,H] fp32, G_tot is [P,B,H]; bf16 q/k/v only. */
+    int32_t wide_gates;        /* Range of the gates with bf16 q/k/v (fp32 q/k/v always have the wide range).
+                                * The intra-chunk scores use Q .* Lambda and K / Lambda as in Alg. 1, whose
+                                * factors grow with the chunk's total log decay; per chunk and channel the sum
+                                * of |g| over the chunk's tokens must stay
+                                * 0: below 80 (log Lambda counted from the chunk's start, as in Alg. 1:
+                                *    mean decays alpha > 0.29 per token at C = 64),
+                                * 1: below 160 (log Lambda counted from half the chunk's total, however the
+                                *    decay is spread over the chunk: alpha > 0.08 per token), at about 3 % more
+                                *    time in the chunk kernels.
+                                * No call can check this: beyond the range the factors overflow and the
+                                * outputs come out as inf / NaN while the status is still ZECO_OK. */
 } zeco_gla_desc;
 
 /* Bytes of device workspace zeco_gla_local_fwd needs for this descriptor (may be 0).
@@ -83,9 +94,8 @@ size_t zeco_gla_local_fwd_workspace(const zeco_gla_desc *desc);
  *               through that token (log of Lambda_t .* gamma~_[n-1]; Eq. (gamma) kept per token)
  *   out  G_tot  [P,B,H,d_k] fp32 contiguous: G_cum at each segment's last token (log gamma~_[N])
  * bf16 io: bf16 MFMA operands, fp32 accumulation and fp32 state.  fp32 io: fp32 MFMA throughout.
- * Precondition: within any chunk, sum over tokens of |g| per channel < 80 (the intra-chunk
- * scores use K / Lambda as in Alg. 1, whose range is exp of that sum).  The call cannot check this: beyond
- * the range the factors overflow and o and S_loc come out as inf / NaN while the status is still ZECO_OK. */
+ * Precondition: the gates stay inside the range the descriptor's wide_gates selects; so for every forward and
+ * backward entry point below. */
 zeco_status zeco_gla_local_fwd(const zeco_gla_desc *desc, const void *q, const void *k,
                                const void *v, const void *g, void *o, float *S_loc, float *G_cum,
                                float *G_tot, void *workspace, size_t workspace_bytes,

@@ -9,6 +9,9 @@
 // i.e.  out_r = F_r .* [ X_r W + sum_{r'<=r} (X_r . Y_r') Z~_r' ]  with
 //   dQ: X = dO, Y = V, Z~ = K / Lambda, F = Lambda,     W = S^T,   W <- (W + Y^T Z~) .* gamma (columns)
 //   dK: X = V, Y = dO, Z~ = Q .* Lambda, F = 1/Lambda,  W = dS^T,  W <- gamma .* W first, then W += Y^T Z~
+// (as built, Lambda is counted from HALF the chunk's total log decay and gamma is applied as two factors
+// sqrt(gamma), one before the chunk's products and one after its update: the same products with half the
+// range of exponents)
 // where for dK the chunks are visited last to first and token t of a chunk sits at tile row 63 - t,
 // which turns "t >= s" into the causal mask of the forward pass.  W (d_v x d_k, the transposed state)
 // stays in MFMA accumulators; wave w owns the 16 output channels [16w, 16w+16).  The gated dimension
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
     unsigned char *Xs = lds + Cfg::kOffX, *Ys = lds + Cfg::kOffY, *Yt = lds + Cfg::kOffYT;
     unsigned char *Zt = lds + Cfg::kOffZT, *Ps = lds + Cfg::kOffP, *Fs = lds + Cfg::kOffF;
     float *wtot = reinterpret_cast<float *>(lds + Cfg::kOffTot);   // [wave][channel] gate sums
-    float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // chunk decay [channel]
+    float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // e^(total / 2) of the chunk [channel]
     float *wtot2 = reinterpret_cast<float *>(lds + Cfg::kOffTot2);
     float *carry0 = reinterpret_cast<float *>(lds + Cfg::kOffCarry);
     float *anchor = reinterpret_cast<float *>(lds + Cfg::kOffAnchor);
@@ -420,7 +423,10 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 
         // ---- gate pass, part 2: stitch waves; Z~^T and the factor tile -> LDS ----------------------
         {
-            f32x4 pre = excl, total = {0.f, 0.f, 0.f, 0.f};
+            // The decay factors of Z~ and F are taken relative to half the chunk's total log decay, as in the forward
+            // kernel: no exponent then exceeds |total| / 2.  W is decayed in two equal steps to match: by e^(total/2)
+            // before the chunk's products and again after its update.
+            f32x4 pre = excl, total = {0.f, 0.f, 0.f, 0.f}, mid;
 #pragma unroll
             for (int u = 0; u < NW; ++u) {
                 const f32x4 x = *reinterpret_cast<const f32x4 *>(wtot + u * DK + 4 * cq);
@@ -431,6 +437,11 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                     total[a] += x[a];
                 }
             }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                mid[a] = 0.5f * total[a];
+                pre[a] -= mid[a];
+            }
             TokenRun<TPT> zt[4];
             u32x2 zprev = {0u, 0u};
             TokenRun<TPT> qt[EMIT ? 4 : 1];
@@ -438,7 +449,7 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
             f32x4 epre = {0.f, 0.f, 0.f, 0.f};   // EMIT: scale * decay of the earlier chunks of the segment
             if constexpr (EMIT) {
 #pragma unroll
-                for (int a = 0; a < 4; ++a) epre[a] = __builtin_amdgcn_exp2f(gpre[GH ? 0 : a] * kLog2e) * p.qscale;
+                for (int a = 0; a < 4; ++a) epre[a] = __builtin_amdgcn_exp2f((gpre[GH ? 0 : a] + mid[GH ? 0 : a]) * kLog2e) * p.qscale;
             }
 #pragma unroll
             for (int u = 0; u < TPT; ++u) {
@@ -499,10 +510,10 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
                 }
             }
             if (tq == 0) {
-                f32x4 gm;
+                f32x4 gh;
 #pragma unroll
-                for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
-                *reinterpret_cast<f32x4 *>(gam + 4 * cq) = gm;
+                for (int a = 0; a < 4; ++a) gh[a] = __builtin_amdgcn_exp2f(mid[a] * kLog2e);
+                *reinterpret_cast<f32x4 *>(gam + 4 * cq) = gh;
             }
         }
         __syncthreads();
@@ -520,13 +531,12 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
         }
 
         // ---- scores: P^T tiles (r' <= r), 16x16x32 over the d_v channels -----------------------------
-        const float gcol = gam[w * 16 + l16];   // decay of this lane's column of W
-        if constexpr (REV) {
+        // half the decay of this lane's column of W: once before the chunk's products, once after its update
+        const float gcol = gam[w * 16 + l16];
 #pragma unroll
-            for (int it = 0; it < Cfg::NIT; ++it)
+        for (int it = 0; it < Cfg::NIT; ++it)
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) Sacc[it][rr] *= gcol;
-        }
+            for (int rr = 0; rr < 4; ++rr) Sacc[it][rr] *= gcol;
 #pragma unroll
         for (int i = 0; i < (10 + NW - 1) / NW; ++i) {
             const int idx = w + NW * i;   // wave-uniform
@@ -589,10 +599,8 @@ __global__ __launch_bounds__(DK * 4) void gla_bwd_qk_kernel(BwdQKParams p) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
                 acc = M::run(lds_frag(Yt, (it * 16 + l16) * TS + (ks * 32 + 8 * kg) * 2), zf[ks], acc);
-            if constexpr (!REV) {
 #pragma unroll
-                for (int rr = 0; rr < 4; ++rr) acc[rr] *= gcol;
-            }
+            for (int rr = 0; rr < 4; ++rr) acc[rr] *= gcol;
             Sacc[it] = acc;
         }
         if constexpr (REV) {

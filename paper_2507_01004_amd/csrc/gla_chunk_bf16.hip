@@ -134,7 +134,17 @@ constexpr int chunk_threads(int dk, int dv, int gm, int mode) {
     return 64 * (dv / 32 + gate_waves(dk, gm, mode) + idle_waves(dk, dv, gm, mode));
 }
 
-template <int DK, int DV, int NS, int GM, int MODE>
+//
+// WIDE selects the reference point of the decay factors in the operand tiles.  With c the in-chunk cumulative
+// log decay and total its value at the chunk's end, the tiles hold Q .* e^(c - ref) and K .* e^(ref - c); any
+// ref per channel gives the same products e^(c_t - c_s).
+//   WIDE = false: ref = 0, the chunk's start, as in Alg. 1.  The state takes one factor per chunk, e^total
+//            (gamma), and the tiles span e^(+-|total|): |total| has to stay below 80 for bf16 operands.
+//   WIDE = true:  ref = total / 2.  No exponent exceeds |total| / 2 wherever in the chunk the decay happens,
+//            so |total| may reach 160.  The state takes e^(total/2) twice, before the chunk's products with
+//            it and after its update (in either walking direction), which costs the MFMA waves a second
+//            multiplication of the state per chunk: about 3 % of the local pass.
+template <int DK, int DV, int NS, int GM, int MODE, bool WIDE>
 __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf16_kernel(ChunkParams p) {
     typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE), idle_waves(DK, DV, GM, MODE)> Cfg;
     typedef Mma<32> M;
@@ -152,7 +162,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     extern __shared__ __align__(16) unsigned char lds[];
     unsigned char *Ps = lds + Cfg::kOffP;
     float *wtot = reinterpret_cast<float *>(lds + Cfg::kOffTot);   // [gate wave][channel] gate sums
-    float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // [buffer][channel] chunk decay
+    float *gam = reinterpret_cast<float *>(lds + Cfg::kOffGam);    // [buffer][channel] chunk decay e^total (WIDE: e^(total/2))
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int pw = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave slot, known uniform
@@ -347,11 +357,11 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
                     total[a] += x[a];
                 }
             }
-            // c = pre + cs is the in-chunk cumulative log decay; exp(c) = exp2(cs*log2e + pre*log2e);
+            // c = pre + cs is the in-chunk cumulative log decay; exp(c - ref) = exp2(cs*log2e + (pre - ref)*log2e);
             // G_cum = (segment prefix + pre) + cs with the prefix folded once per channel.
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
-                pre2[a] = pre[a] * kLog2e;
+                pre2[a] = (WIDE ? __builtin_fmaf(-0.5f, total[a], pre[a]) : pre[a]) * kLog2e;
                 gbase[a] = seg_hi[a] + (pre[a] + seg_lo[a]);
             }
         };
@@ -420,7 +430,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
             if (tq == 0) {
                 f32x4 gm;
 #pragma unroll
-                for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * kLog2e);
+                for (int a = 0; a < 4; ++a) gm[a] = __builtin_amdgcn_exp2f(total[a] * (WIDE ? 0.5f * kLog2e : kLog2e));
                 *reinterpret_cast<f32x4 *>(gam_m + 4 * cq) = gm;
             }
             // decay outputs: the local pass and the two state passes (the backward one emits G_tot when
@@ -543,7 +553,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         // part 1: scores -> Ps, inter-chunk product -> Oacc
         auto mfma_a = [&](const unsigned char *tile, const float *gam_n) __attribute__((always_inline)) {
             const unsigned char *Qs = tile + Cfg::kOffQ, *Ks = tile + Cfg::kOffK;
-            if constexpr (MODE == kDV) decay_state(gam_n);
+            if constexpr (MODE == kDV || (WIDE && !REV)) decay_state(gam_n);
             // P^T tiles (ts <= tt), 16x16x32; all operand reads of a tile are issued up front
 #pragma unroll
             for (int i = 0; i < (10 + NWM - 1) / NWM; ++i) {
@@ -588,7 +598,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
         // part 2 of chunk n: intra-chunk output, O store, state update
         auto mfma_b = [&](int n, const unsigned char *tile, const float *gam_n) __attribute__((always_inline)) {
             unsigned char *os = const_cast<unsigned char *>(tile) + o_s0;
-            if constexpr (MODE == kDState) decay_state(gam_n);
+            if constexpr (MODE == kDState || (WIDE && MODE == kStates)) decay_state(gam_n);
             bf16x8 vf[4];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) vf[ks] = lds_frag_tr(tile + v_tr0 + ks * 16 * VS, 4 * VS);
@@ -611,7 +621,7 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
                     acc = M::run(lds_frag_tr(tile + k_tr0 + ks * 16 * QS + it * 64, 4 * QS), vf[ks], acc);
-                if constexpr (!REV) {
+                if constexpr (!REV || WIDE) {
 #pragma unroll
                     for (int qd = 0; qd < 4; ++qd) {
                         const f32x4 gm = *reinterpret_cast<const f32x4 *>(gam_n + it * 32 + 8 * qd + 4 * kg);
@@ -643,10 +653,10 @@ __global__ __launch_bounds__(chunk_threads(DK, DV, GM, MODE)) void gla_chunk_bf1
     }
 }
 
-template <int DK, int DV, int NS, int GM, int MODE>
+template <int DK, int DV, int NS, int GM, int MODE, bool WIDE>
 static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     typedef B16Cfg<DK, DV, gate_waves(DK, GM, MODE), idle_waves(DK, DV, GM, MODE)> Cfg;
-    auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GM, MODE>;
+    auto kern = gla_chunk_bf16_kernel<DK, DV, NS, GM, MODE, WIDE>;
     static LdsLimit limit;   // one per instantiation
     hipError_t e = limit.raise((const void *)kern, Cfg::kBytes);
     if (e != hipSuccess) return e;
@@ -656,27 +666,37 @@ static hipError_t launch_b16(const ChunkParams &p, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int GM, int MODE>
-static hipError_t dispatch_b16(const ChunkParams &p, int d_k, int d_v, hipStream_t s) {
+template <int GM, int MODE, bool WIDE>
+static hipError_t dispatch_dims(const ChunkParams &p, int d_k, int d_v, hipStream_t s) {
     // With at most half as many streams as compute units, two sibling workgroups split d_v = 128 so that
     // more compute units stream memory; the gate pass is then computed twice.  Between 128 and 256 streams
     // one workgroup per stream on part of the chip is faster than two rounds of siblings (192 streams:
     // 1.21 ms against 1.58 ms for the local pass of 16384 tokens).
     const bool split = d_v == 128 && p.B * p.P * p.H * 2 <= 256;
-    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, 1, GM, MODE>(p, s);
-    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, 1, GM, MODE>(p, s);
+    if (d_k == 64 && d_v == 64) return launch_b16<64, 64, 1, GM, MODE, WIDE>(p, s);
+    if (d_k == 128 && d_v == 64) return launch_b16<128, 64, 1, GM, MODE, WIDE>(p, s);
     if (d_k == 64 && d_v == 128)
-        return split ? launch_b16<64, 64, 2, GM, MODE>(p, s) : launch_b16<64, 128, 1, GM, MODE>(p, s);
+        return split ? launch_b16<64, 64, 2, GM, MODE, WIDE>(p, s) : launch_b16<64, 128, 1, GM, MODE, WIDE>(p, s);
     if (d_k == 128 && d_v == 128)
-        return split ? launch_b16<128, 64, 2, GM, MODE>(p, s) : launch_b16<128, 128, 1, GM, MODE>(p, s);
+        return split ? launch_b16<128, 64, 2, GM, MODE, WIDE>(p, s) : launch_b16<128, 128, 1, GM, MODE, WIDE>(p, s);
     return hipErrorInvalidValue;
+}
+
+template <int GM, int MODE>
+static hipError_t dispatch_b16(const ChunkParams &p, int d_k, int d_v, bool wide, hipStream_t s) {
+    return wide ? dispatch_dims<GM, MODE, true>(p, d_k, d_v, s) : dispatch_dims<GM, MODE, false>(p, d_k, d_v, s);
 }
 
 template <int MODE>
 static hipError_t dispatch_gate(const ChunkParams &p, int d_k, int d_v, int gate_mode, hipStream_t s) {
-    if (gate_mode == kGateBF16) return dispatch_b16<kGateBF16, MODE>(p, d_k, d_v, s);
-    if (gate_mode == kGateHead) return dispatch_b16<kGateHead, MODE>(p, d_k, d_v, s);
-    return dispatch_b16<kGateF32, MODE>(p, d_k, d_v, s);
+    const bool wide = (gate_mode & kGateWide) != 0;
+    const int layout = gate_mode & ~kGateWide;
+    if (layout == kGateBF16) return dispatch_b16<kGateBF16, MODE>(p, d_k, d_v, wide, s);
+    if (layout == kGateHead) {
+        if constexpr (MODE == kLocalCD) return hipErrorInvalidValue;   // per-channel gates only
+        else return dispatch_b16<kGateHead, MODE>(p, d_k, d_v, wide, s);
+    }
+    return dispatch_b16<kGateF32, MODE>(p, d_k, d_v, wide, s);
 }
 
 hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mode, int mode, hipStream_t s) {
@@ -685,10 +705,7 @@ hipError_t launch_chunk_bf16(const ChunkParams &p, int d_k, int d_v, int gate_mo
     if (mode == kDState) return dispatch_gate<kDState>(p, d_k, d_v, gate_mode, s);
     if (mode == kDV) return dispatch_gate<kDV>(p, d_k, d_v, gate_mode, s);
     if (mode == kLocalInit) return dispatch_gate<kLocalInit>(p, d_k, d_v, gate_mode, s);
-    if (mode == kLocalCD)     // per-channel gates only
-        return gate_mode == kGateBF16 ? dispatch_b16<kGateBF16, kLocalCD>(p, d_k, d_v, s)
-               : gate_mode == kGateF32 ? dispatch_b16<kGateF32, kLocalCD>(p, d_k, d_v, s)
-                                       : hipErrorInvalidValue;
+    if (mode == kLocalCD) return dispatch_gate<kLocalCD>(p, d_k, d_v, gate_mode, s);
     return dispatch_gate<kLocal>(p, d_k, d_v, gate_mode, s);
 }
 

@@ -47,7 +47,8 @@ template <int DK, int DV, int C> struct F32Cfg {
     static constexpr int kOffP = kOffV + C * kVS;
     static constexpr int kOffTot = kOffP + C * kPS;
     static constexpr int kOffGam = kOffTot + kTG * DK;
-    static constexpr int kFloats = kOffGam + DK;
+    static constexpr int kOffMid = kOffGam + DK;
+    static constexpr int kFloats = kOffMid + DK;
     static constexpr size_t kBytes = sizeof(float) * kFloats;
     static_assert(kTPT >= 1 && C % 16 == 0, "chunk length");
 };
@@ -66,6 +67,7 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
     float *Ps = lds + Cfg::kOffP;    // masked scores            [t][s]
     float *tot = lds + Cfg::kOffTot; // per token-group gate sums [tg][i]
     float *gam = lds + Cfg::kOffGam; // chunk decay gamma         [i]
+    float *emid = lds + Cfg::kOffMid; // sqrt(gamma)               [i]
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4;
@@ -130,6 +132,9 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
             Vs[t * Cfg::kVS + j] = t < rows ? v[(t0 + t) * p.vt + j] : 0.f;
         }
         __syncthreads();
+        // The factors of Qs and Ks are taken relative to half the chunk's total log decay (mid = total / 2): the
+        // same products e^(c_t - c_s) with no exponent beyond |total| / 2; the inter-chunk product makes up for it
+        // with e^mid on the state's rows.
         float pre = 0.f, total = 0.f;
 #pragma unroll
         for (int u = 0; u < Cfg::kTG; ++u) {
@@ -137,21 +142,25 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
             if (u < tg) pre += x;
             total += x;
         }
+        const float mid = 0.5f * total;
 #pragma unroll
         for (int u = 0; u < Cfg::kTPT; ++u) {
             const int t = tg * Cfg::kTPT + u;
             const float c = pre + cs[u];
             const float kv = t < rows ? k[(t0 + t) * p.st + gc] : 0.f;
             if constexpr (!NOQ) {
-                Qs[t * Cfg::kQS + gc] = q[(t0 + t) * p.st + gc] * fast_exp(c) * p.scale;
-                Ks[t * Cfg::kQS + gc] = kv * fast_exp(-c);
+                Qs[t * Cfg::kQS + gc] = q[(t0 + t) * p.st + gc] * fast_exp(c - mid) * p.scale;
+                Ks[t * Cfg::kQS + gc] = kv * fast_exp(mid - c);
             }
             Kt[t * Cfg::kKT + gc] = kv * fast_exp(total - c);
             if constexpr (EMIT_G) {
                 if (t < rows) Gc[(t0 + t) * gcs + gc] = (float)(seg_prefix + (double)c);
             }
         }
-        if (tg == 0) gam[gc] = fast_exp(total);
+        if (tg == 0) {
+            gam[gc] = fast_exp(total);
+            emid[gc] = fast_exp(mid);
+        }
         seg_prefix += (double)total;
         __syncthreads();
 
@@ -181,7 +190,7 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
             for (int it = 0; it < DK / 16; ++it) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float bval = Sacc[it][r];
+                    const float bval = Sacc[it][r] * emid[16 * it + 4 * kg + r];
 #pragma unroll
                     for (int mt = 0; mt < Cfg::kNT; ++mt) {
                         const float a = Qs[(16 * mt + l16) * Cfg::kQS + 16 * it + 4 * kg + r];

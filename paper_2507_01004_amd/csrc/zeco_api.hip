@@ -44,6 +44,7 @@ zeco_status check_desc(const zeco_gla_desc *d, bool any_length = false) {
     if (d->io_dtype == ZECO_F32 && d->g_dtype != ZECO_F32) return ZECO_ERR_UNSUPPORTED;
     if (d->g_per_head != 0 && d->g_per_head != 1) return ZECO_ERR_INVALID_ARG;
     if (d->g_per_head && (d->io_dtype != ZECO_BF16 || d->g_dtype != ZECO_F32)) return ZECO_ERR_UNSUPPORTED;
+    if (d->wide_gates != 0 && d->wide_gates != 1) return ZECO_ERR_INVALID_ARG;
     return ZECO_OK;
 }
 
@@ -51,6 +52,9 @@ int gate_mode(const zeco_gla_desc *d) {
     if (d->g_per_head) return zeco::kGateHead;
     return d->g_dtype == ZECO_BF16 ? zeco::kGateBF16 : zeco::kGateF32;
 }
+
+// the same with the descriptor's choice of range, for the bf16 chunk kernel
+int chunk_gate(const zeco_gla_desc *d) { return gate_mode(d) | (d->wide_gates ? zeco::kGateWide : 0); }
 
 zeco_status from_hip(hipError_t e) { return e == hipSuccess ? ZECO_OK : ZECO_ERR_HIP; }
 
@@ -66,6 +70,7 @@ void set_length_c(zeco::ChunkParams &p, int L, int C) {
 }
 
 int gate_mode(const zeco_gla_desc *d);
+int chunk_gate(const zeco_gla_desc *d);
 // One of the three phases both precisions have (0 local pass, 1 states only, 2 output pass from S_init), on the
 // segments p describes (p.L tokens each, or the table p.seg_start).
 hipError_t launch_phase(zeco::ChunkParams &p, const zeco_gla_desc *d, int mode, hipStream_t s) {
@@ -73,7 +78,7 @@ hipError_t launch_phase(zeco::ChunkParams &p, const zeco_gla_desc *d, int mode, 
         set_length_c(p, p.L, d->C);
         return zeco::launch_chunk_f32(p, d->d_k, d->d_v, d->C, mode, s);
     }
-    return zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), mode, s);
+    return zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), mode, s);
 }
 
 // Segments per group of the two-level scan: the divisor g of P that minimises the length of the serial
@@ -249,7 +254,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
         // the halves from the zero state: o, G_cum counted from each half's first token, end states
         p.P = d->P * 2; set_length(p, d->L / 2);
         p.S_loc = Ssub; p.G_tot = Gtot;
-        if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s) != hipSuccess) return ZECO_ERR_HIP;
+        if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 0, s) != hipSuccess) return ZECO_ERR_HIP;
         // chain of the two halves of every segment: the state and the log decay entering the second half,
         // the segment's end state and total
         zeco::ScanParams sp;
@@ -266,7 +271,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
         if (zeco::launch_apply_bf16(ap, d->d_k, d->d_v, s) != hipSuccess) return ZECO_ERR_HIP;
         return from_hip(zeco::launch_gate_offset_head(G_cum, Gpre, d->B, (long long)d->P * d->L, d->H, d->L / 2, s));
     }
-    if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 0, s));
+    if (S == 1) return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 0, s));
 
     // Few streams: P*S sub-segments of L/S tokens, Alg. 1's schedule applied inside each segment: the
     // sub-segments' end states and total decays from the zero state, their scan inside the segment,
@@ -277,7 +282,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     float *Ssub = ws + w.off_Ssub, *Sinit = ws + w.off_Sinit, *Gtot = ws + w.off_Gtot, *Gpre = ws + w.off_Gpre;
     p.P = d->P * S; set_length(p, d->L / S);
     p.S_loc = Ssub; p.G_tot = Gtot;
-    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s);
+    hipError_t e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 1, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::ScanParams sp;   // one chain of S sub-segments per segment; its end state is the segment's S_loc
@@ -288,7 +293,7 @@ zeco_status zeco_gla_local_fwd(const zeco_gla_desc *d, const void *q, const void
     if ((e = zeco::launch_scan(sp, s)) != hipSuccess) return ZECO_ERR_HIP;
 
     p.S_loc = nullptr; p.G_tot = nullptr; p.S_init = Sinit; p.G_off = Gpre;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 5, s));
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 5, s));
 }
 
 // ---- two-phase forward ------------------------------------------------------------------------------
@@ -432,7 +437,7 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *d, const void *q, const void
     if (correct) {
         p.q = q; p.o = o;
         if (d->g_per_head) p.G_cum = Gchunk; else p.G_chunk = Gchunk;
-        e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), d->g_per_head ? 0 : 6, s);
+        e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), d->g_per_head ? 0 : 6, s);
     } else {
         e = launch_phase(p, d, 1, s);
     }
@@ -509,7 +514,7 @@ static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const 
     c.P = P; set_length(c, L);
     c.seg_start = reinterpret_cast<const long long *>(seg_start); c.T = T;
     c.q = k; c.k = q; c.v = dO; c.g = g; c.o = dv; c.S_init = dS_in; c.scale = 1.f; c.kscale = d->scale;
-    hipError_t e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, gb, 4, s);
+    hipError_t e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, chunk_gate(d), 4, s);
     if (e != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::BwdQKParams b;
@@ -531,7 +536,7 @@ zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *d, const void *q, const voi
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.k = q; p.v = dO; p.g = g; p.S_loc = dS_loc; p.kscale = d->scale;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 3,
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 3,
                                             static_cast<hipStream_t>(stream)));
 }
 
@@ -644,7 +649,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     } else {
         // recomputed: phase 1 of the forward and its scan
         p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-        if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gb, 1, s)) != hipSuccess) return ZECO_ERR_HIP;
+        if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 1, s)) != hipSuccess) return ZECO_ERR_HIP;
         sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
         if ((e = launch_scan_chain(sp, ws + w.off_tree, s)) != hipSuccess) return ZECO_ERR_HIP;
     }
@@ -862,7 +867,7 @@ zeco_status zeco_gla_bwd_dstate_varlen(const zeco_gla_desc *d, const int64_t *se
     fill_chunk_params(p, d);
     p.k = q; p.v = dO; p.g = g; p.S_loc = dS_loc; p.kscale = d->scale;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 3, static_cast<hipStream_t>(stream)));
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 3, static_cast<hipStream_t>(stream)));
 }
 
 zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
@@ -973,7 +978,7 @@ zeco_status zeco_gla_fused_bwd_varlen(const zeco_gla_desc *d, const int64_t *seg
     fill_chunk_params(p, d);
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
     p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-    if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 1, s) != hipSuccess) return ZECO_ERR_HIP;
+    if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 1, s) != hipSuccess) return ZECO_ERR_HIP;
     zeco::ScanParams sp;
     sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
     sp.P = d->P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;
@@ -1001,7 +1006,7 @@ zeco_status zeco_gla_local_fwd_chunk_decay(const zeco_gla_desc *d, const void *q
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.q = q; p.k = k; p.v = v; p.g = g; p.o = o; p.S_loc = S_loc; p.G_tot = G_tot; p.G_chunk = G_chunk;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, gate_mode(d), 6,
+    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 6,
                                             static_cast<hipStream_t>(stream)));
 }
 

@@ -10,6 +10,9 @@ namespace zeco {
 // Gate layouts: kGateF32 / kGateBF16 = one log decay per (token, head, channel); kGateHead = one fp32
 // log decay per (token, head), shared by all channels (g, G_cum [B,T,H] contiguous; G_tot [P,B,H]).
 enum GateMode { kGateF32 = 0, kGateBF16 = 1, kGateHead = 2 };
+// added to the gate layout handed to launch_chunk_bf16: decay factors of the tiles counted from half the chunk's
+// total log decay (twice the range of gates, one more multiplication of the state per chunk)
+constexpr int kGateWide = 4;
 
 struct ChunkParams {
     const void *q, *k, *v, *g;

@@ -5,6 +5,7 @@ There is no CPU fallback: a missing library raises.  Tensor layouts: q, k, g [B,
 v, o [B,T,H,d_v] (any strides with a contiguous last dimension); S_loc, S_init [P,B,H,d_k,d_v]
 fp32; G_cum [B,T,H,d_k] fp32; G_tot [P,B,H,d_k] fp32.
 """
+import contextlib
 import ctypes
 import os
 
@@ -40,7 +41,8 @@ class GlaDesc(ctypes.Structure):
                 ("scale", ctypes.c_float),
                 ("stride_b", ctypes.c_int64), ("stride_t", ctypes.c_int64), ("stride_h", ctypes.c_int64),
                 ("vstride_b", ctypes.c_int64), ("vstride_t", ctypes.c_int64), ("vstride_h", ctypes.c_int64),
-                ("g_per_head", ctypes.c_int32)]
+                ("g_per_head", ctypes.c_int32),
+                ("wide_gates", ctypes.c_int32)]
 
 
 class ZecoError(RuntimeError):
@@ -157,6 +159,21 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+_WIDE_GATES = False
+
+
+@contextlib.contextmanager
+def wide_gates(on=True):
+    """Within the block every descriptor asks for the wide range of gates (zeco_gla_desc.wide_gates: the sum of
+    |g| over a chunk may reach 160 instead of 80 with bf16 q/k/v, at about 3 % more time in the chunk kernels)."""
+    global _WIDE_GATES
+    before, _WIDE_GATES = _WIDE_GATES, bool(on)
+    try:
+        yield
+    finally:
+        _WIDE_GATES = before
+
+
 def _desc(q, v, g_code, per_head, P, C, scale):
     B, T, H, dk = q.shape
     dv = v.shape[-1]
@@ -166,7 +183,7 @@ def _desc(q, v, g_code, per_head, P, C, scale):
         raise ValueError("innermost dimension must be contiguous")
     return GlaDesc(B, P, H, T // P, dk, dv, C, _dtype_code(q), g_code, float(scale),
                    q.stride(0), q.stride(1), q.stride(2), v.stride(0), v.stride(1), v.stride(2),
-                   int(per_head))
+                   int(per_head), int(_WIDE_GATES))
 
 
 def make_desc(q, v, g, P, C=64, scale=1.0):
@@ -323,7 +340,7 @@ def _varlen_desc(q, v, g_code, per_head, seg_start, max_len, scale, C=64):
     B, T, H, dk = q.shape
     return GlaDesc(B, seg_start.numel() - 1, H, int(max_len), dk, v.shape[-1], int(C), _dtype_code(q), g_code,
                    float(scale), q.stride(0), q.stride(1), q.stride(2), v.stride(0), v.stride(1), v.stride(2),
-                   int(per_head))
+                   int(per_head), int(_WIDE_GATES))
 
 
 def gla_local_fwd_varlen(q, k, v, g, seg_start, max_len, scale=1.0, C=64, out=None):

@@ -102,7 +102,7 @@ int main(void) {
     d.io_dtype = ZECO_BF16; d.g_dtype = ZECO_F32; d.scale = 0.5f;
     d.stride_b = (int64_t)T * H * DK; d.stride_t = H * DK; d.stride_h = DK;
     d.vstride_b = (int64_t)T * H * DV; d.vstride_t = H * DV; d.vstride_h = DV;
-    d.g_per_head = 0;
+    d.g_per_head = 0; d.wide_gates = 0;
 
     /* error paths answer before any HIP call */
     zeco_gla_desc bad = d;

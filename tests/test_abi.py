@@ -43,7 +43,7 @@ def test_version_and_strings(L):
 def good_desc(**kw):
     d = dict(B=1, P=2, H=2, L=128, d_k=128, d_v=128, C=64, io_dtype=zeco.ZECO_BF16,
              g_dtype=zeco.ZECO_F32, scale=1.0, stride_b=2 * 256 * 128 * 2, stride_t=256, stride_h=128,
-             vstride_b=2 * 256 * 128 * 2, vstride_t=256, vstride_h=128, g_per_head=0)
+             vstride_b=2 * 256 * 128 * 2, vstride_t=256, vstride_h=128, g_per_head=0, wide_gates=0)
     d.update(kw)
     return zeco.GlaDesc(*[d[f[0]] for f in zeco.GlaDesc._fields_])
 
@@ -58,6 +58,7 @@ def call_local(L, desc, q=FAKE, o=FAKE, ws_bytes=0):
 
 @pytest.mark.parametrize("kw,expect", [
     (dict(B=-1), zeco.ZECO_ERR_INVALID_ARG),
+    (dict(wide_gates=2), zeco.ZECO_ERR_INVALID_ARG),
     (dict(P=0), zeco.ZECO_ERR_INVALID_ARG),
     (dict(L=(1 << 30) + 64, P=1, stride_b=1 << 44), zeco.ZECO_ERR_INVALID_ARG),   # beyond the length limit
     (dict(L=40), zeco.ZECO_ERR_UNSUPPORTED),           # shorter than a chunk

@@ -347,6 +347,78 @@ def test_strong_gates_up_to_the_documented_range(per_head):
     assert rel_err_bh(host(grads[3]), dg_r, (0, 2)) <= (5e-2 if per_head else TOL["bf16"])
 
 
+@pytest.mark.parametrize("per_head", [False, True])
+def test_wide_range_of_gates(per_head):
+    """The wide range of gates (zeco_gla_desc.wide_gates): log decays of -1.2 to -2.4 per token, 77 to 154 per
+    chunk and channel, and one chunk with all of its 150 in its first 30 tokens.  The decay factors of the operand
+    tiles are then counted from half the chunk's total, so half a chunk's decay is what has to fit their range
+    (below 80) wherever in the chunk it falls; counted from the chunk's start these gates overflow.  Forward by
+    every route and backward against the oracle."""
+    B, H, P, L, dk, dv = 1, 3, 2, 320, 128, 128
+    print("gates beyond a whole-chunk reference", per_head, flush=True)
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=93, io="bf16", g="f32", device="cuda", per_head_gate=per_head)
+    gen = torch.Generator(device="cuda").manual_seed(94)
+    inp["g"] = -(1.2 + 1.2 * torch.rand(inp["g"].shape, generator=gen, device="cuda"))
+    inp["g"][:, 64:128] = -2.4                          # one chunk at the strongest decay in every channel
+    inp["g"][:, 192:222] = -5.0                         # one with all of its decay early ...
+    inp["g"][:, 222:256] = -1e-3                        # ... and next to none late
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda").to(torch.bfloat16)
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    h = {n: host(t) for n, t in inp.items()}
+    if per_head:
+        h["g"] = np.repeat(h["g"][..., None], dk, axis=-1)
+    o_r, S_r = oracle.gla_recurrent(h["q"], h["k"], h["v"], h["g"], 0.5)
+    ref = oracle.gla_recurrent_bwd(h["q"], h["k"], h["v"], h["g"], host(dO), 0.5, None, None)
+    with zeco.wide_gates():
+        o, S_last, _ = zeco.segmented_fwd(q, k, v, g, P, scale=0.5)
+        outs = [o] + [zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, schedule=sc)[0]
+                      for sc in (zeco.SCHEDULE_TWO_PHASE, zeco.SCHEDULE_CORRECT)]
+        grads = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5)
+    torch.cuda.synchronize()
+    for x in outs:
+        assert torch.isfinite(x.float()).all()
+        assert rel_err_bh(host(x), o_r, (0, 2)) <= TOL["bf16"]
+    assert rel_err_bh(host(S_last), S_r, (0, 1)) <= TOL["bf16"]
+    for name_, x, r in zip(("dq", "dk", "dv"), grads[:3], ref[:3]):
+        assert torch.isfinite(x.float()).all(), name_
+        assert rel_err_bh(host(x), r, (0, 2)) <= TOL["bf16"], name_
+    dg_r = ref[3].sum(axis=-1) if per_head else ref[3]
+    assert torch.isfinite(grads[3]).all()
+    print("  dg rel err %.4f" % rel_err_bh(host(grads[3]), dg_r, (0, 2)), flush=True)
+    # dG under gates this strong: the state lives a token or two, so the sum of nearly cancelling terms is small
+    # against its terms' bf16 rounding noise (the effect of the test above, here in both gate layouts)
+    assert rel_err_bh(host(grads[3]), dg_r, (0, 2)) <= 6e-2
+
+
+@pytest.mark.parametrize("per_head,L", [(False, 448), (True, 448), (False, 200)])
+def test_wide_range_on_ordinary_gates(per_head, L):
+    """wide_gates only moves the reference point of the tiles' decay factors: on the workloads' gates it gives the
+    results of the standard range up to rounding.  Forward by every route and backward against the oracle, whole
+    and ragged chunks."""
+    B, H, P, dk, dv = 2, 3, 3, 128, 128
+    print("wide range, ordinary gates", per_head, L, flush=True)
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=95 + L, io="bf16", g="f32", device="cuda", per_head_gate=per_head)
+    dO = randn_seeded(inp["v"].shape, 96).to(torch.bfloat16)
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    h = {n: host(t) for n, t in inp.items()}
+    if per_head:
+        h["g"] = np.repeat(h["g"][..., None], dk, axis=-1)
+    o_r, S_r = oracle.gla_recurrent(h["q"], h["k"], h["v"], h["g"], 0.5)
+    ref = oracle.gla_recurrent_bwd(h["q"], h["k"], h["v"], h["g"], host(dO), 0.5, None, None)
+    with zeco.wide_gates():
+        o, S_last, _ = zeco.segmented_fwd(q, k, v, g, P, scale=0.5)
+        outs = [o] + [zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, schedule=sc)[0]
+                      for sc in (zeco.SCHEDULE_TWO_PHASE, zeco.SCHEDULE_CORRECT)]
+        grads = zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5)
+    torch.cuda.synchronize()
+    for x in outs:
+        assert rel_err_bh(host(x), o_r, (0, 2)) <= TOL["bf16"]
+    assert rel_err_bh(host(S_last), S_r, (0, 1)) <= TOL["bf16"]
+    dg_r = ref[3].sum(axis=-1) if per_head else ref[3]
+    for name_, x, r in zip(("dq", "dk", "dv", "dg"), grads, (ref[0], ref[1], ref[2], dg_r)):
+        assert rel_err_bh(host(x), r, (0, 2)) <= TOL["bf16"], name_
+
+
 def test_empty_batch_is_a_no_op():
     """B = 0 through the binding: the calls succeed, return empty tensors and launch nothing."""
     q = torch.empty(0, 256, 2, 128, dtype=torch.bfloat16, device="cuda")

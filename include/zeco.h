@@ -229,8 +229,7 @@ zeco_status zeco_gla_fwd_from_state_varlen(const zeco_gla_desc *desc, const int6
 /* The backward's building blocks (zeco_gla_bwd_dstate, zeco_gla_bwd_from_state below) over the same table:
  * every segment's state gradient from dS = 0; then, after the reverse zeco_state_scan, dq, dk, dv, dg of
  * every segment.  Arguments as in the equal-length calls; the workspace is
- * zeco_gla_bwd_from_state_workspace(desc) bytes, sized for the bound desc->L on the lengths.
- * bf16 q/k/v only (fp32 returns ZECO_ERR_UNSUPPORTED). */
+ * zeco_gla_bwd_from_state_workspace(desc) bytes, sized for the bound desc->L on the lengths. */
 zeco_status zeco_gla_bwd_dstate_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
                                        const void *q, const void *g, const void *dO, float *dS_loc,
                                        void *stream);
@@ -246,8 +245,8 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *desc, const int6
  * the forward states and their scan again, the dQ pass, which also leaves every segment's state gradient, the
  * reverse scan from dS_T, and the dV and dK passes; dg is re-anchored every 512 tokens as in
  * zeco_gla_bwd_from_state.  Arguments as in zeco_gla_fused_fwd / zeco_gla_fused_bwd (no saved states, no
- * schedule); workspace sizes from the *_workspace queries, sized for the bound desc->L.  The forward takes
- * bf16 and fp32 q/k/v, the backward bf16 only. */
+ * schedule); workspace sizes from the *_workspace queries, sized for the bound desc->L.  Both take bf16 and
+ * fp32 q/k/v. */
 size_t zeco_gla_fused_fwd_varlen_workspace(const zeco_gla_desc *desc);
 zeco_status zeco_gla_fused_fwd_varlen(const zeco_gla_desc *desc, const int64_t *seg_start, int64_t T,
                                       const void *q, const void *k, const void *v, const void *g,
@@ -306,7 +305,9 @@ zeco_status zeco_gla_fused_fwd(const zeco_gla_desc *desc, const void *q, const v
                                int32_t schedule, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- Backward pass (App. A.4): gradients of  sum_t <o_t, dO_t> + <S_T, dS_T>  for the forward above.
- * bf16 q/k/v/dO and gradients only (fp32 returns ZECO_ERR_UNSUPPORTED).  dO, dv use the layout of v;
+ * q/k/v/dO and the gradients dq, dk, dv share one dtype, bf16 (bf16 MFMA operands, fp32 accumulation and
+ * states: the throughput path) or fp32 (fp32 MFMA throughout, chunk length desc->C: the accuracy path, about
+ * 7 times slower).  dO, dv use the layout of v;
  * dq, dk the layout of q; dg [B,T,H,d_k] fp32 contiguous; all state arrays fp32.  The state gradients
  * are true gradients (they include `scale`). --------------------------------------------------------- */
 

@@ -12,11 +12,23 @@
 // This is the accuracy path (relative error <= 1e-4 against the fp64 oracle); the bf16 kernel is
 // the throughput path.  The chunk length is a template parameter here (Sec. 2.1 leaves C free): a
 // shorter chunk does less masked work per token and, since K / Lambda spans the decay of one chunk,
-// takes proportionally stronger gates (the sum of |g| over a chunk must stay below 80).
+// takes proportionally stronger gates (the sum of |g| over a chunk must stay below 160: the factors
+// are counted from half the chunk's total log decay).
 //
 // MODE (the phases of Alg. 1, as in the bf16 kernel): kF32Local the local pass from the zero state
 // (o, S_loc, G_cum, G_tot); kF32States only the final state and total decay of each segment (S_loc,
 // G_tot; q is not read); kF32Output the output pass from given initial states S_init (o only).
+//
+// Two more modes run the same equations over the REVERSED sequence for the backward pass (App. A.4):
+//   kF32DState  dS <- (gamma^T 1) .* dS + (Q .* Lambda)^T dO from zero; S_loc receives the gradient the
+//               segment sends to the state entering it (called with k := q, v := dO)
+//   kF32DV      dV = (K / Lambda)((gamma^T 1) .* dS) + (intra-chunk scores)^T dO with dS started from
+//               S_init, the gradient entering the segment's final state (called with q := k, k := q,
+//               v := dO, o := dV)
+// With rho = L - 1 - t both are the forward recurrence in rho, except that the decay between two tokens
+// then covers the gate of the one in the key role and not of the one in the query role: the cumulative
+// sum of g over a chunk is taken EXCLUSIVE of a token's own gate.  The query scale rides on the operand in
+// the key role (p.kscale), so that the running dS is the true gradient.
 //
 // A segment length that is no multiple of C makes the FIRST chunk the short one: it covers the
 // tokens [0, r), r = L - C (N - 1), is loaded as the window [0, C) (inside the segment, L >= C)
@@ -27,7 +39,7 @@
 
 namespace zeco {
 
-enum F32Mode { kF32Local = 0, kF32States = 1, kF32Output = 2 };
+enum F32Mode { kF32Local = 0, kF32States = 1, kF32Output = 2, kF32DState = 3, kF32DV = 4 };
 
 template <int DK, int DV, int C> struct F32Cfg {
     static constexpr int kWaves = DV / 16;
@@ -56,8 +68,9 @@ template <int DK, int DV, int C> struct F32Cfg {
 template <int DK, int DV, int C, int MODE>
 __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
     typedef F32Cfg<DK, DV, C> Cfg;
-    constexpr bool NOQ = MODE == kF32States;         // only the state is computed
-    constexpr bool FROM_INIT = MODE == kF32Output;   // start from S_init, emit o only
+    constexpr bool REV = MODE == kF32DState || MODE == kF32DV;       // the sequence reversed
+    constexpr bool NOQ = MODE == kF32States || MODE == kF32DState;   // only the state is computed
+    constexpr bool FROM_INIT = MODE == kF32Output || MODE == kF32DV; // start from S_init, emit o only
     constexpr bool EMIT_G = MODE == kF32Local;
     extern __shared__ __align__(16) float lds[];
     float *Qs = lds + Cfg::kOffQ;    // Q .* Lambda * scale      [t][i]
@@ -78,12 +91,13 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
     const int seg = sidx % p.P, b = sidx / p.P;
     long long tok0 = (long long)seg * p.L, T = (long long)p.P * p.L;   // first token; tokens per batch entry
     int n_chunks = p.n_chunks, pad = p.pad;
+    long long len = p.L;
     if (p.seg_start) {
         // segments of unequal length: this one's bounds from the table; a segment that cannot be taken (under
         // 64 tokens, over the bound L, outside the tensor) is left alone
         tok0 = p.seg_start[seg];
         T = p.T;
-        const long long len = p.seg_start[seg + 1] - tok0;
+        len = p.seg_start[seg + 1] - tok0;
         if (tok0 < 0 || len < 64 || len > p.L || tok0 > T - len) return;   // (in this order: no sum can overflow)
         n_chunks = (int)((len + C - 1) / C);
         pad = C * n_chunks - (int)len;
@@ -110,6 +124,8 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
     }
 
     const int gc = tid % DK, tg = tid / DK;      // gate pass: channel and token group
+    // position in the segment of the token that sits at place x of the order the chunks are walked in
+    auto at = [&](long long x) { return REV ? len - 1 - x : x; };
     double seg_prefix = 0.0;                     // log decay accumulated over previous chunks
 
     for (int n = 0; n < n_chunks; ++n) {
@@ -122,14 +138,15 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
 #pragma unroll
             for (int u = 0; u < Cfg::kTPT; ++u) {
                 const int t = tg * Cfg::kTPT + u;
-                run += t < rows ? g[(t0 + t) * p.st + gc] : 0.f;
-                cs[u] = run;
+                if constexpr (REV) cs[u] = run;   // without the token's own gate
+                run += t < rows ? g[at(t0 + t) * p.st + gc] : 0.f;
+                if constexpr (!REV) cs[u] = run;
             }
             tot[tg * DK + gc] = run;
         }
         for (int e = tid; e < C * DV; e += Cfg::kThreads) {
             const int t = e / DV, j = e % DV;
-            Vs[t * Cfg::kVS + j] = t < rows ? v[(t0 + t) * p.vt + j] : 0.f;
+            Vs[t * Cfg::kVS + j] = t < rows ? v[at(t0 + t) * p.vt + j] : 0.f;
         }
         __syncthreads();
         // The factors of Qs and Ks are taken relative to half the chunk's total log decay (mid = total / 2): the
@@ -147,9 +164,10 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
         for (int u = 0; u < Cfg::kTPT; ++u) {
             const int t = tg * Cfg::kTPT + u;
             const float c = pre + cs[u];
-            const float kv = t < rows ? k[(t0 + t) * p.st + gc] : 0.f;
+            float kv = t < rows ? k[at(t0 + t) * p.st + gc] : 0.f;
+            if constexpr (REV) kv *= p.kscale;
             if constexpr (!NOQ) {
-                Qs[t * Cfg::kQS + gc] = q[(t0 + t) * p.st + gc] * fast_exp(c - mid) * p.scale;
+                Qs[t * Cfg::kQS + gc] = q[at(t0 + t) * p.st + gc] * fast_exp(c - mid) * p.scale;
                 Ks[t * Cfg::kQS + gc] = kv * fast_exp(mid - c);
             }
             Kt[t * Cfg::kKT + gc] = kv * fast_exp(total - c);
@@ -210,7 +228,7 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (16 * mt + 4 * kg + r < rows) o[(t0 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] = Oacc[mt][r];
+                    if (16 * mt + 4 * kg + r < rows) o[at(t0 + 16 * mt + 4 * kg + r) * p.vt + 16 * w + l16] = Oacc[mt][r];
             }
         }
 
@@ -237,7 +255,7 @@ __global__ __launch_bounds__(DV * 4) void gla_chunk_f32_kernel(ChunkParams p) {
         for (int it = 0; it < DK / 16; ++it)
 #pragma unroll
             for (int r = 0; r < 4; ++r) Sl[(16 * it + 4 * kg + r) * DV + 16 * w + l16] = Sacc[it][r];
-        if (tg == 0) p.G_tot[sbh * DK + gc] = (float)seg_prefix;
+        if (tg == 0 && (!REV || p.G_tot)) p.G_tot[sbh * DK + gc] = (float)seg_prefix;
     }
 }
 
@@ -254,6 +272,8 @@ template <int DK, int DV, int C, int MODE> static hipError_t launch_f32(const Ch
 template <int DK, int DV, int C> static hipError_t dispatch_f32_mode(const ChunkParams &p, int mode, hipStream_t s) {
     if (mode == kF32States) return launch_f32<DK, DV, C, kF32States>(p, s);
     if (mode == kF32Output) return launch_f32<DK, DV, C, kF32Output>(p, s);
+    if (mode == kF32DState) return launch_f32<DK, DV, C, kF32DState>(p, s);
+    if (mode == kF32DV) return launch_f32<DK, DV, C, kF32DV>(p, s);
     return launch_f32<DK, DV, C, kF32Local>(p, s);
 }
 
@@ -264,7 +284,8 @@ template <int DK, int DV> static hipError_t dispatch_f32_chunk(const ChunkParams
     return hipErrorInvalidValue;
 }
 
-// mode: 0 local pass, 1 states only, 2 output pass from S_init (the same numbering as the bf16 kernel's);
+// mode: 0 local pass, 1 states only, 2 output pass from S_init, 3 backward state pass, 4 dV pass (the same
+// numbering as the bf16 kernel's);
 // p.n_chunks and p.pad count chunks of C tokens
 hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, int C, int mode, hipStream_t s) {
     if (d_k == 64 && d_v == 64) return dispatch_f32_chunk<64, 64>(p, C, mode, s);

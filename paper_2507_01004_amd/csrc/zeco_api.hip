@@ -71,8 +71,8 @@ void set_length_c(zeco::ChunkParams &p, int L, int C) {
 
 int gate_mode(const zeco_gla_desc *d);
 int chunk_gate(const zeco_gla_desc *d);
-// One of the three phases both precisions have (0 local pass, 1 states only, 2 output pass from S_init), on the
-// segments p describes (p.L tokens each, or the table p.seg_start).
+// One of the phases both precisions have (0 local pass, 1 states only, 2 output pass from S_init, 3 backward
+// state pass, 4 dV pass), on the segments p describes (p.L tokens each, or the table p.seg_start).
 hipError_t launch_phase(zeco::ChunkParams &p, const zeco_gla_desc *d, int mode, hipStream_t s) {
     if (d->io_dtype == ZECO_F32) {
         set_length_c(p, p.L, d->C);
@@ -497,6 +497,17 @@ static zeco_status bwd_dq_pass(const zeco_gla_desc *d, int P, int L, const void 
     if (S_ck && bwd_checkpoints(L) > 0) { b.S_ck = S_ck; b.n_ck = bwd_checkpoints(L); b.short_last = 1; }
     b.seg_start = reinterpret_cast<const long long *>(seg_start); b.T = T;
     b.x = dO; b.y = v; b.z = k; b.z2 = q; b.out = dq; b.W_init = S_init; b.zscale = 1.f; b.oscale = d->scale;
+    if (d->io_dtype == ZECO_F32) {
+        // the fp32 kernels: dQ, and the segments' state gradients from dS = 0 as a pass of their own
+        if (zeco::launch_bwd_qk_f32(b, d->d_k, d->d_v, d->C, false, s) != hipSuccess) return ZECO_ERR_HIP;
+        if (!dS_loc) return ZECO_OK;
+        zeco::ChunkParams c;
+        fill_chunk_params(c, d);
+        c.P = P; set_length_c(c, L, d->C);
+        c.seg_start = reinterpret_cast<const long long *>(seg_start); c.T = T;
+        c.k = q; c.v = dO; c.g = g; c.S_loc = dS_loc; c.G_tot = G_tot_out; c.scale = 1.f; c.kscale = d->scale;
+        return from_hip(zeco::launch_chunk_f32(c, d->d_k, d->d_v, d->C, 3, s));
+    }
     b.dS_loc = dS_loc; b.G_tot_out = G_tot_out; b.qscale = d->scale;
     return from_hip(zeco::launch_bwd_qk(b, d->d_k, d->d_v, gate_mode(d), false, s));
 }
@@ -514,14 +525,14 @@ static zeco_status bwd_dv_dk_passes(const zeco_gla_desc *d, int P, int L, const 
     c.P = P; set_length(c, L);
     c.seg_start = reinterpret_cast<const long long *>(seg_start); c.T = T;
     c.q = k; c.k = q; c.v = dO; c.g = g; c.o = dv; c.S_init = dS_in; c.scale = 1.f; c.kscale = d->scale;
-    hipError_t e = zeco::launch_chunk_bf16(c, d->d_k, d->d_v, chunk_gate(d), 4, s);
-    if (e != hipSuccess) return ZECO_ERR_HIP;
+    if (launch_phase(c, d, 4, s) != hipSuccess) return ZECO_ERR_HIP;
 
     zeco::BwdQKParams b;
     fill_bwd_params(b, d, P, L, g, dg, S_init, S_last);
     b.seg_start = reinterpret_cast<const long long *>(seg_start); b.T = T;
     b.x = v; b.y = dO; b.z = q; b.z2 = k; b.out = dk; b.W_init = dS_in; b.zscale = d->scale; b.oscale = 1.f;
     if (S_ck && bwd_checkpoints(L) > 0) { b.S_ck = S_ck; b.n_ck = bwd_checkpoints(L); }
+    if (d->io_dtype == ZECO_F32) return from_hip(zeco::launch_bwd_qk_f32(b, d->d_k, d->d_v, d->C, true, s));
     return from_hip(zeco::launch_bwd_qk(b, d->d_k, d->d_v, gb, true, s));
 }
 
@@ -532,16 +543,14 @@ zeco_status zeco_gla_bwd_dstate(const zeco_gla_desc *d, const void *q, const voi
     if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !g || !dO || !dS_loc) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(g) || !aligned16(dO) || !aligned16(dS_loc)) return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.k = q; p.v = dO; p.g = g; p.S_loc = dS_loc; p.kscale = d->scale;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 3,
-                                            static_cast<hipStream_t>(stream)));
+    return from_hip(launch_phase(p, d, 3, static_cast<hipStream_t>(stream)));
 }
 
 size_t zeco_gla_bwd_from_state_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK) return 0;
     return bwd_checkpoint_floats(desc, desc->P, desc->L) * sizeof(float);
 }
 
@@ -561,7 +570,6 @@ zeco_status zeco_gla_bwd_from_state(const zeco_gla_desc *d, const void *q, const
         !aligned16(S_init) || !aligned16(S_last) || !aligned16(dS_in) || !aligned16(dq) || !aligned16(dk) ||
         !aligned16(dv) || !aligned16(dg))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *S_ck = need ? static_cast<float *>(workspace) : nullptr;
     const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, S_ck, s);
@@ -607,7 +615,7 @@ size_t zeco_gla_saved_states_bytes(const zeco_gla_desc *desc) {
 }
 
 size_t zeco_gla_fused_bwd_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK) return 0;
     return bwd_layout(desc, bwd_pieces(desc)).total * sizeof(float);
 }
 
@@ -623,7 +631,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
         !aligned16(S0) || !aligned16(dS_T) || !aligned16(S_saved) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) ||
         !aligned16(dg) || !aligned16(dS0) || !aligned16(workspace))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
+    if (d->io_dtype != ZECO_BF16 && S_saved) return ZECO_ERR_UNSUPPORTED;   // (the fp32 forward saves no states)
     if (workspace_bytes < zeco_gla_fused_bwd_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int S = bwd_pieces(d);
@@ -649,7 +657,7 @@ zeco_status zeco_gla_fused_bwd(const zeco_gla_desc *d, const void *q, const void
     } else {
         // recomputed: phase 1 of the forward and its scan
         p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-        if ((e = zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 1, s)) != hipSuccess) return ZECO_ERR_HIP;
+        if ((e = launch_phase(p, d, 1, s)) != hipSuccess) return ZECO_ERR_HIP;
         sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
         if ((e = launch_scan_chain(sp, ws + w.off_tree, s)) != hipSuccess) return ZECO_ERR_HIP;
     }
@@ -862,12 +870,11 @@ zeco_status zeco_gla_bwd_dstate_varlen(const zeco_gla_desc *d, const int64_t *se
     if (d->B == 0) return ZECO_OK;   // empty batch: nothing to do
     if (!q || !g || !dO || !dS_loc) return ZECO_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(g) || !aligned16(dO) || !aligned16(dS_loc)) return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     zeco::ChunkParams p;
     fill_chunk_params(p, d);
     p.k = q; p.v = dO; p.g = g; p.S_loc = dS_loc; p.kscale = d->scale;
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
-    return from_hip(zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 3, static_cast<hipStream_t>(stream)));
+    return from_hip(launch_phase(p, d, 3, static_cast<hipStream_t>(stream)));
 }
 
 zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *d, const int64_t *seg_start, int64_t T,
@@ -887,7 +894,6 @@ zeco_status zeco_gla_bwd_from_state_varlen(const zeco_gla_desc *d, const int64_t
         !aligned16(S_init) || !aligned16(S_last) || !aligned16(dS_in) || !aligned16(dq) || !aligned16(dk) ||
         !aligned16(dv) || !aligned16(dg))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *S_ck = need ? static_cast<float *>(workspace) : nullptr;
     const zeco_status sq = bwd_dq_pass(d, d->P, d->L, q, k, v, g, dO, S_init, S_last, dq, dg, nullptr, nullptr, S_ck, s,
@@ -921,7 +927,7 @@ size_t zeco_gla_fused_fwd_varlen_workspace(const zeco_gla_desc *desc) {
     return varlen_layout(desc, false).total * sizeof(float);
 }
 size_t zeco_gla_fused_bwd_varlen_workspace(const zeco_gla_desc *desc) {
-    if (check_desc(desc, true) != ZECO_OK || desc->io_dtype != ZECO_BF16) return 0;
+    if (check_desc(desc, true) != ZECO_OK) return 0;
     return varlen_layout(desc, true).total * sizeof(float);
 }
 
@@ -965,7 +971,6 @@ zeco_status zeco_gla_fused_bwd_varlen(const zeco_gla_desc *d, const int64_t *seg
         !aligned16(dS_T) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv) || !aligned16(dg) || !aligned16(dS0) ||
         !aligned16(workspace))
         return ZECO_ERR_INVALID_ARG;
-    if (d->io_dtype != ZECO_BF16) return ZECO_ERR_UNSUPPORTED;
     if (workspace_bytes < zeco_gla_fused_bwd_varlen_workspace(d)) return ZECO_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const VarlenLayout w = varlen_layout(d, true);
@@ -978,7 +983,7 @@ zeco_status zeco_gla_fused_bwd_varlen(const zeco_gla_desc *d, const int64_t *seg
     fill_chunk_params(p, d);
     p.seg_start = reinterpret_cast<const long long *>(seg_start); p.T = T;
     p.k = k; p.v = v; p.g = g; p.S_loc = Sloc; p.G_tot = Gtot;
-    if (zeco::launch_chunk_bf16(p, d->d_k, d->d_v, chunk_gate(d), 1, s) != hipSuccess) return ZECO_ERR_HIP;
+    if (launch_phase(p, d, 1, s) != hipSuccess) return ZECO_ERR_HIP;
     zeco::ScanParams sp;
     sp.S_loc = Sloc; sp.G_tot = Gtot; sp.S0 = S0; sp.S_init = Sinit; sp.S_last = Slast;
     sp.P = d->P; sp.groups = 1; sp.BH = d->B * d->H; sp.d_k = d->d_k; sp.d_v = d->d_v;

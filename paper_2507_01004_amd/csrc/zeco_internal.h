@@ -115,7 +115,7 @@ struct LdsLimit {
 
 // Each returns hipSuccess or the launch error.  d_k, d_v in {64,128}.
 // fp32 kernel: chunk length C in {16, 32, 64} (p.n_chunks, p.pad count chunks of C tokens); mode 0 local pass,
-// 1 states only, 2 output pass from S_init
+// 1 states only, 2 output pass from S_init, 3 backward state pass, 4 dV pass (as in the bf16 kernel below)
 hipError_t launch_chunk_f32(const ChunkParams &p, int d_k, int d_v, int C, int mode, hipStream_t s);
 // mode: 0 local pass (o, S_loc, G_cum, G_tot), 1 states only (S_loc, G_tot), 2 output pass from S_init (o),
 // 3 backward state pass (k := q, v := dO; S_loc := dS leaving the segment), 4 dV pass (q := k, k := q,
@@ -131,6 +131,8 @@ hipError_t launch_scan(const ScanParams &p, hipStream_t s);
 // reverse = false: dQ (x = dO, y = v, z = k, z2 = q, W_init = forward states); true: dK (x = v, y = dO,
 // z = q, z2 = k, W_init = state gradients; must run after the dQ pass, whose q .* dq it consumes)
 hipError_t launch_bwd_qk(const BwdQKParams &p, int d_k, int d_v, int gate_mode, bool reverse, hipStream_t s);
+// the same two passes on fp32 tensors (gla_bwd_f32.hip), chunk length C in {16, 32, 64}; no by-products
+hipError_t launch_bwd_qk_f32(const BwdQKParams &p, int d_k, int d_v, int C, bool reverse, hipStream_t s);
 // per-head log decays: G_cum [B,T,H] += G_pre [T/len, B, H] of the piece each token lies in
 hipError_t launch_gate_offset_head(float *G_cum, const float *G_pre, int B, long long T, int H, int len, hipStream_t s);
 hipError_t launch_copy(void *dst, const void *src, size_t bytes, hipStream_t s);

@@ -154,10 +154,9 @@ def test_unequal_segment_lengths_validate_before_any_launch(L):
         ref(d or good_desc(L=1000)), seg, T, q, *([FAKE] * 4), None, None, *([FAKE] * 4), None, FAKE, ws, None)
     need_f = L.zeco_gla_fused_fwd_varlen_workspace(ref(good_desc(L=1000)))
     need_b = L.zeco_gla_fused_bwd_varlen_workspace(ref(good_desc(L=1000)))
-    assert 0 < need_f < need_b and L.zeco_gla_fused_bwd_varlen_workspace(ref(good_desc(io_dtype=zeco.ZECO_F32))) == 0
+    assert 0 < need_f < need_b
+    assert L.zeco_gla_fused_bwd_varlen_workspace(ref(good_desc(L=1000, io_dtype=zeco.ZECO_F32))) == need_b   # fp32 too
     assert ffw(ws=need_f - 1) == zeco.ZECO_ERR_WORKSPACE and fbw(ws=need_b - 1) == zeco.ZECO_ERR_WORKSPACE
-    for call in (dst, bwd, fbw):     # the backward is bf16 only; the forward phases take fp32 too
-        assert call(d=good_desc(io_dtype=zeco.ZECO_F32)) == zeco.ZECO_ERR_UNSUPPORTED
     for call in (loc, app, sta, out, dst, bwd, ffw, fbw):
         assert call(seg=None) == zeco.ZECO_ERR_INVALID_ARG
         assert call(seg=ctypes.c_void_p(0x1004)) == zeco.ZECO_ERR_INVALID_ARG        # not 8-byte aligned
@@ -204,15 +203,16 @@ def test_backward_entry_points_reject_bad_arguments(L):
     f32 = good_desc(io_dtype=zeco.ZECO_F32)
     ref = ctypes.byref
     assert L.zeco_gla_bwd_dstate(ref(d), None, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG
-    assert L.zeco_gla_bwd_dstate(ref(f32), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED
+    assert L.zeco_gla_bwd_dstate(ref(f32), None, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_INVALID_ARG   # fp32 is taken
     assert L.zeco_gla_bwd_dstate(ref(good_desc(L=40)), FAKE, FAKE, FAKE, FAKE, None) == zeco.ZECO_ERR_UNSUPPORTED   # shorter than a chunk
     args = [FAKE] * 12
-    assert L.zeco_gla_bwd_from_state(ref(f32), *args, None, 0, None) == zeco.ZECO_ERR_UNSUPPORTED
     args[7] = None                                         # dS_in missing
     assert L.zeco_gla_bwd_from_state(ref(d), *args, None, 0, None) == zeco.ZECO_ERR_INVALID_ARG
+    assert L.zeco_gla_bwd_from_state(ref(f32), *args, None, 0, None) == zeco.ZECO_ERR_INVALID_ARG
     # checkpoints of the forward state that re-anchor dG: one per 512 tokens inside a segment, none up to 512
     wsz = L.zeco_gla_bwd_from_state_workspace
     assert wsz(ref(d)) == 0 and wsz(ref(good_desc(L=512))) == 0 and wsz(ref(f32)) == 0
+    assert wsz(ref(good_desc(L=513, io_dtype=zeco.ZECO_F32, C=16))) == 1 * 2 * 2 * 1 * 128 * 128 * 4   # whatever C
     long = good_desc(L=16384)
     assert wsz(ref(long)) == 1 * 2 * 2 * 31 * 128 * 128 * 4
     assert wsz(ref(good_desc(L=513))) == 1 * 2 * 2 * 1 * 128 * 128 * 4
@@ -220,9 +220,13 @@ def test_backward_entry_points_reject_bad_arguments(L):
     assert L.zeco_gla_bwd_from_state(ref(long), *args, FAKE, wsz(ref(long)) - 1, None) == zeco.ZECO_ERR_WORKSPACE
     assert L.zeco_gla_bwd_from_state(ref(long), *args, None, wsz(ref(long)), None) == zeco.ZECO_ERR_INVALID_ARG
     need = L.zeco_gla_fused_bwd_workspace(ref(d))
-    assert need > 0 and L.zeco_gla_fused_bwd_workspace(ref(f32)) == 0
+    assert need > 0 and L.zeco_gla_fused_bwd_workspace(ref(f32)) == need
     fused = [FAKE] * 5 + [None, None, None] + [FAKE] * 4 + [None, FAKE]
     assert L.zeco_gla_fused_bwd(ref(d), *fused, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
+    assert L.zeco_gla_fused_bwd(ref(f32), *fused, need - 1, None) == zeco.ZECO_ERR_WORKSPACE
+    saved = list(fused)
+    saved[7] = FAKE                                        # the fp32 forward saves no states to start from
+    assert L.zeco_gla_fused_bwd(ref(f32), *saved, need, None) == zeco.ZECO_ERR_UNSUPPORTED
     fused[0] = ctypes.c_void_p(0x1004)
     assert L.zeco_gla_fused_bwd(ref(d), *fused, need, None) == zeco.ZECO_ERR_INVALID_ARG
 

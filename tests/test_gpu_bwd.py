@@ -128,11 +128,8 @@ def test_bwd_zero_gate_and_strided_views():
         assert torch.equal(x, y), name_            # no atomics: bitwise reproducible
 
 
-def test_bwd_rejects_fp32_and_small_workspace():
+def test_bwd_rejects_a_small_workspace():
     q = torch.zeros(1, 64, 1, 64, device="cuda")
-    with pytest.raises(zeco.ZecoError) as e:
-        zeco.gla_fused_bwd(q, q, q, q, q, 1)
-    assert e.value.status == zeco.ZECO_ERR_UNSUPPORTED
     qb = q.to(torch.bfloat16)
     with pytest.raises(zeco.ZecoError) as e:
         zeco.gla_fused_bwd(qb, qb, qb, q, qb, 1, workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))

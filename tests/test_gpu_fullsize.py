@@ -281,16 +281,19 @@ def test_fullsize_unequal_segments_sampled_slices():
 @pytest.mark.parametrize("name", ["c2", "c3"])
 def test_fullsize_whole_forward_against_unsegmented_oracle(name):
     """Every token and head of configs 2 and 3 against Eq. (1) run over the whole sequence (the oracle
-    needs a few seconds for 131072 tokens x 16 heads)."""
+    needs a few seconds for 131072 tokens x 16 heads): the three calls, the fused call, and the three calls with
+    the wide range of gates."""
     inp, c = synth.config_inputs(name, device="cuda")
     P = c["P"]
     print("whole forward", name, c, flush=True)
     o, S_last, _ = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
     o_fused, S_last_fused = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
+    with zeco.wide_gates():      # the other reference point of the tiles' decay factors, in the same launch shapes
+        o_wide, S_last_wide, _ = zeco.segmented_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P)
     torch.cuda.synchronize()
     o_ref, S_ref = oracle.gla_recurrent(*(host(inp[n]) for n in ("q", "k", "v", "g")))
     print("  oracle done", flush=True)
-    for got, got_S in ((o, S_last), (o_fused, S_last_fused)):
+    for got, got_S in ((o, S_last), (o_fused, S_last_fused), (o_wide, S_last_wide)):
         assert rel_err_bh(host(got), o_ref, (0, 2)) <= TOL[c["io"]]
         assert rel_err_bh(host(got_S), S_ref, (0, 1)) <= TOL[c["io"]]
         # Frobenius norm of the error beside the max norm

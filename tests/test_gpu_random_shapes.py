@@ -61,6 +61,11 @@ CASES = draw_cases()
 
 @pytest.mark.parametrize("case", CASES, ids=["%d_B%d_H%d_P%d_L%d_%dx%d_%s" % c[:8] for c in CASES])
 def test_random_shape_all_routes(case):
+    with zeco.wide_gates(case[0] % 3 == 2):     # every third shape with the other range of gates
+        all_routes(case)
+
+
+def all_routes(case):
     ci, B, H, P, L, dk, dv, gate, start = case
     print("case", case, flush=True)
     tol = TOL["bf16"]
@@ -124,3 +129,49 @@ def test_random_shape_all_routes(case):
             assert rel_err_bh(host(x), r, (0, 2)) <= tol, nm + ", unequal segments"
         assert rel_err_bh(host(dS0), ref[4], (0, 1)) <= tol, "dS0, unequal segments"
         assert rel_err_bh(host(got[3]), ref_dg, (0, 2)) <= tol, "dg, unequal segments"
+
+
+F32_CASES = [c for c in CASES if c[7] != "head"][::3]
+
+
+@pytest.mark.parametrize("case", F32_CASES, ids=["%d_B%d_H%d_P%d_L%d_%dx%d_%s" % c[:8] for c in F32_CASES])
+def test_random_shape_fp32_routes(case):
+    """The same shapes on fp32 tensors, chunk length drawn from the three the fp32 kernels take: three calls,
+    two-phase forward, the backward in one call and, over the unequal cut, forward and backward in one call each."""
+    ci, B, H, P, L, dk, dv, gate, start = case
+    C = (16, 32, 64)[ci % 3]
+    print("fp32 case", case, "C", C, flush=True)
+    tol = TOL["f32"]
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=3000 * SEED + ci, io="f32", g="f32", device="cuda", gate_div=64.0)
+    gen = torch.Generator(device="cuda").manual_seed(7000 + 1000 * SEED + ci)
+    dO = torch.randn(inp["v"].shape, generator=gen, device="cuda")
+    S0 = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
+    dS_T = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
+    q, k, v, g = (inp[n] for n in "qkvg")
+    hq, hk, hv, hg = host(q), host(k), host(v), host(g)
+    o_f, S_f = oracle.gla_recurrent(hq, hk, hv, hg, 0.5, host(S0))
+    ref = oracle.gla_recurrent_bwd(hq, hk, hv, hg, host(dO), 0.5, host(S0), host(dS_T))
+
+    def check_forward(o, S_last, what):
+        torch.cuda.synchronize()
+        assert rel_err_bh(host(o), o_f, (0, 2)) <= tol, what
+        assert rel_err_bh(host(S_last), S_f, (0, 1)) <= tol, what
+
+    def check_backward(got, what):
+        torch.cuda.synchronize()
+        for nm, x, r in zip(("dq", "dk", "dv", "dg"), got[:4], ref[:4]):
+            assert rel_err_bh(host(x), r, (0, 2)) <= tol, nm + what
+        assert rel_err_bh(host(got[4]), ref[4], (0, 1)) <= tol, "dS0" + what
+
+    o, S_last, _ = zeco.segmented_fwd(q, k, v, g, P, scale=0.5, S0=S0, C=C)
+    check_forward(o, S_last, "three calls")
+    o, S_last = zeco.gla_fused_fwd(q, k, v, g, P, scale=0.5, S0=S0, C=C)
+    check_forward(o, S_last, "fused")
+    check_backward(zeco.gla_fused_bwd(q, k, v, g, dO, P, scale=0.5, S0=S0, dS_T=dS_T, C=C), "")
+    if start is not None:
+        seg = torch.tensor(start, dtype=torch.int64, device="cuda")
+        bound = int(max(np.diff(start)))
+        o, S_last = zeco.gla_fused_fwd_varlen(q, k, v, g, seg, bound, scale=0.5, S0=S0, C=C)
+        check_forward(o, S_last, "unequal segments %s" % (start,))
+        check_backward(zeco.gla_fused_bwd_varlen(q, k, v, g, dO, seg, bound, scale=0.5, C=C, S0=S0, dS_T=dS_T),
+                       ", unequal segments")

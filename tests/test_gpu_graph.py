@@ -74,3 +74,41 @@ def test_pipeline_forward_backward_replay_from_a_graph():
             assert torch.equal(a, b), (rep, i)
         if rep == 0:   # equal lengths: the same result as the ordinary three calls
             assert torch.equal(o5, o3) and torch.equal(S_last5, S_last3)
+
+
+def test_fp32_forward_backward_replay_from_a_graph():
+    """The fp32 kernels recorded the same way: the one-call forward and backward at a chunk length of 32, replayed
+    on new values, bitwise equal to the eager calls."""
+    B, H, P, L, dk, dv, C = 1, 2, 4, 200, 128, 64, 32
+    inp = synth.make_inputs(B, P * L, H, dk, dv, seed=33, io="f32", g="f32", device="cuda")
+    q, k, v, g = (inp[n] for n in ("q", "k", "v", "g"))
+    dO = randn_seeded(v.shape, 7302, v.dtype)
+    o, S_last = torch.empty_like(v), torch.empty(B, H, dk, dv, device="cuda")
+    ws_f = torch.empty(zeco.fused_workspace_bytes(q, v, g, P, C=C), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(zeco.fused_bwd_workspace_bytes(q, v, g, P, C=C), dtype=torch.uint8, device="cuda")
+    grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(v), torch.empty(B, P * L, H, dk, device="cuda"),
+             torch.empty(B, H, dk, dv, device="cuda"))
+
+    def run():
+        zeco.gla_fused_fwd(q, k, v, g, P, out=(o, S_last), workspace=ws_f, C=C)
+        zeco.gla_fused_bwd(q, k, v, g, dO, P, out=grads, workspace=ws_b, C=C)
+
+    outs = (o, S_last) + grads
+    run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        gen = torch.Generator(device="cuda").manual_seed(200 + rep)
+        q.copy_(torch.randn(q.shape, generator=gen, device="cuda"))
+        dO.copy_(torch.randn(v.shape, generator=gen, device="cuda"))
+        run()
+        torch.cuda.synchronize()
+        eager = [t.clone() for t in outs]
+        for t in outs:
+            t.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(outs, eager)):
+            assert torch.equal(a, b), (rep, i)

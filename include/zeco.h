@@ -292,7 +292,7 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *desc, const void *q, co
  *                              correction stops where the decay factor has vanished, so with decays whose
  *                              e-folding length is far below the piece length k, v, g are read once
  *                              instead of twice; with decays near 1 it moves about 10 % more than
- *                              two-phase.
+ *                              two-phase (measured 15 - 20 % more time: ask for TWO_PHASE with such data).
  *     ZECO_SCHEDULE_AUTO       CORRECT when it is available and the pieces are at least 4096 tokens long,
  *                              else TWO_PHASE.
  * workspace: zeco_gla_fused_fwd_workspace(desc) bytes of device memory, 16-byte aligned (enough for

@@ -365,8 +365,11 @@ zeco_status zeco_gla_fwd_from_state(const zeco_gla_desc *d, const void *q, const
 // Pieces each segment is cut into by zeco_gla_fused_fwd: up to 256 streams, at least 256 tokens each.
 static int fused_pieces(const zeco_gla_desc *d) {
     const long long streams = (long long)d->B * d->P * d->H;
-    int S = 1;   // as many workgroups as fit the 256 compute units in one round, not more
-    while (streams * S * 2 <= 256 && halves_evenly(d->L, S) && d->L / (2 * S) >= 256) S *= 2;
+    // as many workgroups as fit the 256 compute units in one round, not more; the fp32 kernels' tiles shrink
+    // with the chunk length, and 64 / C of their workgroups share a compute unit
+    const long long slots = 256 * (d->io_dtype == ZECO_F32 ? 64 / d->C : 1);
+    int S = 1;
+    while (streams * S * 2 <= slots && halves_evenly(d->L, S) && d->L / (2 * S) >= 256) S *= 2;
     return S;
 }
 

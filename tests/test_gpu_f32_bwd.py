@@ -25,6 +25,7 @@ CASES = [
     ("f32bwd_dk128_dv64", 1, 2, 1, 257, 128, 64, 64),
     ("f32bwd_anchor", 1, 2, 2, 1100, 128, 128, 64),        # two checkpoints of the forward state per segment
     ("f32bwd_anchor_c16", 1, 1, 1, 1601, 64, 64, 16),      # three, 32 chunks apart; the last chunk holds one token
+    ("f32bwd_pieces_c16", 2, 16, 4, 1024, 128, 128, 16),   # 128 streams cut into 4 pieces each (four workgroups share a compute unit at C = 16)
 ]
 GRADS = ("dq", "dk", "dv", "dg")
 AXES = (0, 2)
@@ -53,8 +54,12 @@ def test_fused_bwd_fp32_matches_unsegmented_oracle(case):
     dS_T = torch.randn(B, H, dk, dv, device="cuda", generator=gen) * 0.3
     for s0, dst in ((None, None), (S0, dS_T)):
         got = zeco.gla_fused_bwd(inp["q"], inp["k"], inp["v"], inp["g"], inp["dO"], P, scale=0.5, S0=s0, dS_T=dst, C=C)
+        o, S_last = zeco.gla_fused_fwd(inp["q"], inp["k"], inp["v"], inp["g"], P, scale=0.5, S0=s0, C=C)   # the same cut
         torch.cuda.synchronize()
         assert got[0].dtype == torch.float32
+        o_r, S_r = oracle.gla_recurrent(host(inp["q"]), host(inp["k"]), host(inp["v"]), host(inp["g"]), 0.5,
+                                        None if s0 is None else host(s0))
+        assert rel_err_bh(host(o), o_r, AXES) <= TOL["f32"] and rel_err_bh(host(S_last), S_r, (0, 1)) <= TOL["f32"]
         ref = oracle_bwd(inp, 0.5, None if s0 is None else host(s0), None if dst is None else host(dst))
         for name_, x, r in zip(GRADS, got[:4], ref[:4]):
             assert rel_err_bh(host(x), r, AXES) <= TOL["f32"], name_
